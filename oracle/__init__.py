@@ -1,0 +1,207 @@
+"""ctypes access to the CPU oracle (oracle.cpp).  TEST INFRASTRUCTURE ONLY.
+
+Only the tests, the smoke check and the benchmark's cpu_baseline leg import this package; the
+product package never does.  All arrays are numpy arrays on the host.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "oracle.cpp")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+F32, F16 = 0, 1
+SUM, MEAN = 0, 1
+EMPTY_TAG = np.uint64(0xFFFFFFFFFFFFFFFF)
+
+
+def build(force: bool = True) -> str:
+    """Compile oracle.cpp with g++ (no GPU toolchain involved)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-Wall", "-Wextra",
+                               _SRC, "-o", _LIB])
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = C.CDLL(_LIB)
+        p, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+        L.oracle_rows_direct.restype = i64
+        L.oracle_rows_direct.argtypes = [i32, p, p, i64, p, p, p]
+        L.oracle_emb_forward.restype = None
+        L.oracle_emb_forward.argtypes = [i32, i32, i32, p, i64, p, p, i64, p]
+        L.oracle_emb_backward_sgd.restype = i64
+        L.oracle_emb_backward_sgd.argtypes = [i32, i32, i32, p, i64, p, p, i64, p, f32, p, p]
+        L.oracle_hash_create.restype = p
+        L.oracle_hash_create.argtypes = [i64]
+        L.oracle_hash_destroy.restype = None
+        L.oracle_hash_destroy.argtypes = [p]
+        L.oracle_hash_size.restype = i64
+        L.oracle_hash_size.argtypes = [p]
+        L.oracle_hash_insert_or_find.restype = None
+        L.oracle_hash_insert_or_find.argtypes = [p, p, i64, i32, p]
+        L.oracle_cache_create.restype = p
+        L.oracle_cache_create.argtypes = [i64, i32, i32, p, i64]
+        L.oracle_cache_destroy.restype = None
+        L.oracle_cache_destroy.argtypes = [p]
+        L.oracle_cache_stats.restype = None
+        L.oracle_cache_stats.argtypes = [p, p]
+        L.oracle_cache_state.restype = None
+        L.oracle_cache_state.argtypes = [p, p, p, p]
+        L.oracle_cache_query.restype = None
+        L.oracle_cache_query.argtypes = [p, i64, p, p, i64, i64, i32, p, p]
+        _lib = L
+    return _lib
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _i64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+def _dtype_code(table: np.ndarray) -> int:
+    if table.dtype == np.float32:
+        return F32
+    if table.dtype == np.float16:
+        return F16
+    raise TypeError("table must be float32 or float16")
+
+
+def rows_direct(slot_base, slot_rows, keys, offsets=None, n_bags: Optional[int] = None) -> Tuple[np.ndarray, int]:
+    """Global row per key (direct-index mode) and the number of keys without a row.
+    Slot s owns rows [slot_base[s], slot_base[s] + slot_rows[s]) of the fused table."""
+    slot_base, slot_rows, keys = _i64(slot_base), _i64(slot_rows), _i64(keys)
+    S = len(slot_base)
+    assert len(slot_rows) == S
+    if offsets is not None:
+        offsets = _i64(offsets)
+        n_bags = len(offsets) - 1
+    elif n_bags is None:
+        n_bags = len(keys)
+    rows = np.empty(len(keys), dtype=np.int64)
+    bad = lib().oracle_rows_direct(S, _ptr(slot_base), _ptr(slot_rows), n_bags, _ptr(keys),
+                                   _ptr(offsets), _ptr(rows))
+    return rows, int(bad)
+
+
+def emb_forward(table: np.ndarray, rows, offsets=None, combiner: int = SUM,
+                n_bags: Optional[int] = None) -> np.ndarray:
+    """Pooled output [n_bags, D] float32."""
+    assert table.ndim == 2 and table.flags.c_contiguous
+    rows = _i64(rows)
+    if offsets is not None:
+        offsets = _i64(offsets)
+        n_bags = len(offsets) - 1
+    elif n_bags is None:
+        n_bags = len(rows)
+    out = np.empty((n_bags, table.shape[1]), dtype=np.float32)
+    lib().oracle_emb_forward(table.shape[1], _dtype_code(table), combiner, _ptr(table), table.shape[0],
+                             _ptr(rows), _ptr(offsets), n_bags, _ptr(out))
+    return out
+
+
+def emb_backward_sgd(table: np.ndarray, rows, dY: np.ndarray, lr: float, offsets=None,
+                     combiner: int = SUM, n_bags: Optional[int] = None):
+    """Updates `table` in place; returns (unique rows ascending, occurrence counts)."""
+    assert table.ndim == 2 and table.flags.c_contiguous and table.flags.writeable
+    rows = _i64(rows)
+    if offsets is not None:
+        offsets = _i64(offsets)
+        n_bags = len(offsets) - 1
+    elif n_bags is None:
+        n_bags = len(rows)
+    dY = np.ascontiguousarray(dY, dtype=np.float32).reshape(n_bags, table.shape[1])
+    uniq = np.empty(max(1, len(rows)), dtype=np.int64)
+    cnt = np.empty(max(1, len(rows)), dtype=np.int64)
+    u = lib().oracle_emb_backward_sgd(table.shape[1], _dtype_code(table), combiner, _ptr(table),
+                                      table.shape[0], _ptr(rows), _ptr(offsets), n_bags, _ptr(dY),
+                                      float(np.float32(lr)), _ptr(uniq), _ptr(cnt))
+    return uniq[:u].copy(), cnt[:u].copy()
+
+
+class Hash:
+    """Key -> dense row id in first-appearance order, capped at max_rows."""
+
+    def __init__(self, max_rows: int):
+        self._h = lib().oracle_hash_create(int(max_rows))
+        self.max_rows = int(max_rows)
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            lib().oracle_hash_destroy(self._h)
+            self._h = None
+
+    @property
+    def size(self) -> int:
+        return int(lib().oracle_hash_size(self._h))
+
+    def insert_or_find(self, keys, insert: bool = True) -> np.ndarray:
+        keys = _i64(keys)
+        rows = np.empty(len(keys), dtype=np.int64)
+        lib().oracle_hash_insert_or_find(self._h, _ptr(keys), len(keys), int(bool(insert)), _ptr(rows))
+        return rows
+
+
+class Cache:
+    """Set-associative cache of host_table rows with call-granular LRU."""
+
+    def __init__(self, num_sets: int, ways: int, host_table: np.ndarray):
+        assert host_table.dtype == np.float32 and host_table.ndim == 2 and host_table.flags.c_contiguous
+        self.host_table = host_table  # keep alive
+        self.num_sets, self.ways, self.dim = int(num_sets), int(ways), host_table.shape[1]
+        self._c = lib().oracle_cache_create(self.num_sets, self.ways, self.dim, _ptr(host_table),
+                                            host_table.shape[0])
+
+    def __del__(self):
+        if getattr(self, "_c", None):
+            lib().oracle_cache_destroy(self._c)
+            self._c = None
+
+    def query(self, keys, n_bags: int, offsets=None, insert_missing: bool = True):
+        """Returns (out [n_bags, D] float32, hit_mask [nnz] uint8)."""
+        keys = _i64(keys)
+        nnz = len(keys)
+        hot = 0
+        if offsets is not None:
+            offsets = _i64(offsets)
+            assert len(offsets) == n_bags + 1 and offsets[-1] == nnz
+        else:
+            assert n_bags > 0 and nnz % n_bags == 0
+            hot = nnz // n_bags
+        out = np.empty((n_bags, self.dim), dtype=np.float32)
+        hit = np.zeros(nnz, dtype=np.uint8)
+        lib().oracle_cache_query(self._c, n_bags, _ptr(keys), _ptr(offsets), hot, nnz,
+                                 int(bool(insert_missing)), _ptr(out), _ptr(hit))
+        return out, hit
+
+    @property
+    def stats(self) -> np.ndarray:
+        """[queries, hits, misses, inserts, evictions, skipped inserts]"""
+        s = np.zeros(6, dtype=np.int64)
+        lib().oracle_cache_stats(self._c, _ptr(s))
+        return s
+
+    def state(self, with_data: bool = False):
+        n = self.num_sets * self.ways
+        tags = np.empty(n, dtype=np.uint64)
+        stamps = np.empty(n, dtype=np.uint32)
+        data = np.empty((n, self.dim), dtype=np.float32) if with_data else None
+        lib().oracle_cache_state(self._c, _ptr(tags), _ptr(stamps), _ptr(data))
+        tags = tags.reshape(self.num_sets, self.ways)
+        stamps = stamps.reshape(self.num_sets, self.ways)
+        return (tags, stamps, data) if with_data else (tags, stamps)

@@ -1,0 +1,310 @@
+// CPU oracle for the hashed sparse embedding path.  TEST INFRASTRUCTURE ONLY.
+//
+// This file is the slow, plain definition of what the embedding layer computes, used by the tests,
+// by the smoke check and by the benchmark's CPU-baseline leg to judge the GPU library.  The
+// product path never calls it and shares no code with it.  Everything is a single-threaded loop
+// over std::unordered_map / std::vector, floating point accumulates in double and is rounded once.
+//
+// What each function follows in the paper (Merlin HugeCTR, RecSys'22 talk abstract):
+//   * key -> row lookup in an "embedding hash", one table per slot, and the intra-slot reduction
+//     of multi-hot features: section 1, "Localized slot embedding hash".
+//   * forward and backward propagation through the embedding: section 1, "Hybrid sparse
+//     embedding" (the paper names the passes; the SGD rule and the dedup of repeated keys are the
+//     benchmark definition's, the paper gives no optimizer).
+//   * FP16 parameter storage: section 1, "Mixed precision training".
+//   * the level-1 embedding inference cache with dynamic insertion, and the level-2 store in
+//     system memory that serves its misses: section 3, "embedding inference cache" and
+//     "Volatile database".
+//
+// Pins (tests/test_oracle_*.py): dense matrix-product brute force, torch's embedding_bag and
+// autograd, numpy.unique, hand-worked traces, textbook LRU / direct-mapped special cases and the
+// conservation invariants.  No function here is "parity unpinned".
+
+#include <cstdint>
+#include <cstring>
+#include <cmath>
+#include <unordered_map>
+#include <vector>
+#include <algorithm>
+
+namespace {
+
+enum { DT_F32 = 0, DT_F16 = 1 };
+enum { COMB_SUM = 0, COMB_MEAN = 1 };
+
+// IEEE binary16 bit pattern -> double, decoded field by field.
+double half_to_double(uint16_t h) {
+  int sign = (h >> 15) & 1;
+  int exp = (h >> 10) & 0x1F;
+  int man = h & 0x3FF;
+  double v;
+  if (exp == 0) v = std::ldexp((double)man, -24);                 // subnormal: man * 2^-24
+  else if (exp == 31) v = man ? NAN : INFINITY;
+  else v = std::ldexp((double)(man | 0x400), exp - 25);           // (1024+man) * 2^(exp-15-10)
+  return sign ? -v : v;
+}
+
+// double -> IEEE binary16 bit pattern, round to nearest, ties to even, overflow to infinity.
+uint16_t double_to_half(double x) {
+  uint16_t sign = std::signbit(x) ? 0x8000 : 0;
+  double a = std::fabs(x);
+  if (std::isnan(a)) return sign | 0x7E00;
+  if (a >= 65520.0) return sign | 0x7C00;                          // rounds to 2^16 => infinity
+  if (a == 0.0) return sign;
+  int e;
+  std::frexp(a, &e);                                               // a = f * 2^e, f in [0.5, 1)
+  int exp = e - 1;                                                 // a in [2^exp, 2^(exp+1))
+  if (exp < -14) exp = -14;                                        // subnormal range shares 2^-24 spacing
+  double q = std::ldexp(a, 10 - exp);                              // in units of the spacing
+  double r = std::nearbyint(q);                                    // default mode: ties to even
+  // q is in [1024, 2048) for normals, [0, 1024) for subnormals; r may reach 2048 (carry).
+  if (exp == -14 && r < 1024.0) return sign | (uint16_t)r;        // subnormal (or zero)
+  if (r >= 2048.0) { r = 1024.0; exp += 1; }
+  if (exp > 15) return sign | 0x7C00;
+  return sign | (uint16_t)(((exp + 15) << 10) | ((int)r - 1024));
+}
+
+inline double load_elem(const void* table, int dtype, int64_t idx) {
+  if (dtype == DT_F32) return (double)((const float*)table)[idx];
+  return half_to_double(((const uint16_t*)table)[idx]);
+}
+
+inline void store_elem(void* table, int dtype, int64_t idx, double v) {
+  if (dtype == DT_F32) ((float*)table)[idx] = (float)v;            // one rounding, nearest-even
+  else ((uint16_t*)table)[idx] = double_to_half(v);
+}
+
+inline int64_t bag_begin(const int64_t* offsets, int64_t bag) { return offsets ? offsets[bag] : bag; }
+inline int64_t bag_end(const int64_t* offsets, int64_t bag) { return offsets ? offsets[bag + 1] : bag + 1; }
+
+}  // namespace
+
+extern "C" {
+
+// Direct-index key -> global row of the fused table: the keys of bag (b, s) address the table of
+// slot s, which occupies rows [slot_base[s], slot_base[s] + slot_rows[s]) (slots may share a
+// table).  A key outside [0, slot_rows[s]) has no row (-1).  Returns the number of such keys.
+// offsets == NULL means one key per bag.
+int64_t oracle_rows_direct(int32_t num_slots, const int64_t* slot_base, const int64_t* slot_rows,
+                           int64_t n_bags, const int64_t* keys, const int64_t* offsets,
+                           int64_t* rows) {
+  int64_t bad = 0;
+  for (int64_t bag = 0; bag < n_bags; ++bag) {
+    int64_t s = bag % num_slots;
+    for (int64_t i = bag_begin(offsets, bag); i < bag_end(offsets, bag); ++i) {
+      if (keys[i] >= 0 && keys[i] < slot_rows[s]) rows[i] = slot_base[s] + keys[i];
+      else { rows[i] = -1; ++bad; }
+    }
+  }
+  return bad;
+}
+
+// Forward: out[bag, :] = w * sum_j T[row_j, :], w = 1 (sum) or 1/hotness (mean), hotness counting
+// every key of the bag (also repeated keys and keys without a row); an empty bag gives zeros.
+// Keys without a row (row < 0 or >= total_rows) add nothing.
+void oracle_emb_forward(int32_t dim, int32_t dtype, int32_t combiner, const void* table,
+                        int64_t total_rows, const int64_t* rows, const int64_t* offsets,
+                        int64_t n_bags, float* out) {
+  std::vector<double> acc(dim);
+  for (int64_t bag = 0; bag < n_bags; ++bag) {
+    std::fill(acc.begin(), acc.end(), 0.0);
+    int64_t b0 = bag_begin(offsets, bag), b1 = bag_end(offsets, bag);
+    for (int64_t i = b0; i < b1; ++i) {
+      int64_t r = rows[i];
+      if (r < 0 || r >= total_rows) continue;
+      for (int d = 0; d < dim; ++d) acc[d] += load_elem(table, dtype, r * dim + d);
+    }
+    double w = (combiner == COMB_MEAN && b1 > b0) ? 1.0 / (double)(b1 - b0) : 1.0;
+    for (int d = 0; d < dim; ++d) out[bag * dim + d] = (float)(acc[d] * w);
+  }
+}
+
+// Backward + SGD: for every distinct row r touched by the batch,
+//   g_r = sum over occurrences (bag, j) with row_j = r of w_bag * dY[bag, :],
+//   T[r, :] <- T[r, :] - lr * g_r   (evaluated in double, rounded once to the storage type).
+// A key repeated inside a bag counts once per occurrence.  Rows never touched keep their bits.
+// Also returns the dedup result: the distinct rows in ascending order with their occurrence
+// counts (uniq_rows / counts hold up to nnz entries), and their number.
+int64_t oracle_emb_backward_sgd(int32_t dim, int32_t dtype, int32_t combiner, void* table,
+                                int64_t total_rows, const int64_t* rows, const int64_t* offsets,
+                                int64_t n_bags, const float* dY, float lr,
+                                int64_t* uniq_rows, int64_t* counts) {
+  std::unordered_map<int64_t, std::vector<double>> grad;
+  std::unordered_map<int64_t, int64_t> occ;
+  for (int64_t bag = 0; bag < n_bags; ++bag) {
+    int64_t b0 = bag_begin(offsets, bag), b1 = bag_end(offsets, bag);
+    double w = (combiner == COMB_MEAN && b1 > b0) ? 1.0 / (double)(b1 - b0) : 1.0;
+    for (int64_t i = b0; i < b1; ++i) {
+      int64_t r = rows[i];
+      if (r < 0 || r >= total_rows) continue;
+      std::vector<double>& g = grad[r];
+      if (g.empty()) g.assign(dim, 0.0);
+      for (int d = 0; d < dim; ++d) g[d] += w * (double)dY[bag * dim + d];
+      occ[r] += 1;
+    }
+  }
+  std::vector<int64_t> order;
+  order.reserve(grad.size());
+  for (auto& kv : grad) order.push_back(kv.first);
+  std::sort(order.begin(), order.end());
+  int64_t u = 0;
+  for (int64_t r : order) {
+    const std::vector<double>& g = grad[r];
+    for (int d = 0; d < dim; ++d) {
+      double t = load_elem(table, dtype, r * dim + d);
+      store_elem(table, dtype, r * dim + d, t - (double)lr * g[d]);
+    }
+    if (uniq_rows) uniq_rows[u] = r;
+    if (counts) counts[u] = occ[r];
+    ++u;
+  }
+  return u;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Hash: key -> dense row id, rows handed out in order of first appearance.
+// ---------------------------------------------------------------------------------------------
+struct oracle_hash {
+  std::unordered_map<uint64_t, int64_t> map;
+  int64_t max_rows;
+};
+
+oracle_hash* oracle_hash_create(int64_t max_rows) {
+  oracle_hash* h = new oracle_hash();
+  h->max_rows = max_rows;
+  return h;
+}
+void oracle_hash_destroy(oracle_hash* h) { delete h; }
+int64_t oracle_hash_size(const oracle_hash* h) { return (int64_t)h->map.size(); }
+
+// Scan keys in array order.  Present -> its row.  Absent: if inserting and the table still has
+// room, the key gets row = current size; otherwise -1.  Negative keys are never stored (-1).
+void oracle_hash_insert_or_find(oracle_hash* h, const int64_t* keys, int64_t n, int32_t insert,
+                                int64_t* rows) {
+  for (int64_t i = 0; i < n; ++i) {
+    if (keys[i] < 0) { rows[i] = -1; continue; }
+    auto it = h->map.find((uint64_t)keys[i]);
+    if (it != h->map.end()) { rows[i] = it->second; continue; }
+    if (insert && (int64_t)h->map.size() < h->max_rows) {
+      int64_t r = (int64_t)h->map.size();
+      h->map.emplace((uint64_t)keys[i], r);
+      rows[i] = r;
+    } else {
+      rows[i] = -1;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Set-associative embedding cache over a host-resident table, LRU at the granularity of a call.
+// ---------------------------------------------------------------------------------------------
+struct oracle_cache {
+  int64_t num_sets;
+  int32_t ways, dim;
+  const float* host_table;
+  int64_t host_rows;
+  std::vector<uint64_t> tag;      // [num_sets * ways], EMPTY = all ones
+  std::vector<uint32_t> stamp;    // [num_sets * ways], epoch of last hit / insert
+  std::vector<float> data;        // [num_sets * ways * dim], copies of host rows
+  uint32_t epoch;
+  int64_t stats[6];               // queries, hits, misses, inserts, evictions, skipped inserts
+};
+
+static const uint64_t kEmptyTag = ~0ull;
+
+// Set index of a key: x = key * 0x9E3779B97F4A7C15 (mod 2^64); x ^= x >> 32; set = x mod num_sets.
+static int64_t cache_set_of(uint64_t key, int64_t num_sets) {
+  uint64_t x = key * 0x9E3779B97F4A7C15ull;
+  x ^= x >> 32;
+  return (int64_t)(x % (uint64_t)num_sets);
+}
+
+oracle_cache* oracle_cache_create(int64_t num_sets, int32_t ways, int32_t dim,
+                                  const float* host_table, int64_t host_rows) {
+  oracle_cache* c = new oracle_cache();
+  c->num_sets = num_sets; c->ways = ways; c->dim = dim;
+  c->host_table = host_table; c->host_rows = host_rows;
+  c->tag.assign((size_t)num_sets * ways, kEmptyTag);
+  c->stamp.assign((size_t)num_sets * ways, 0u);
+  c->data.assign((size_t)num_sets * ways * dim, 0.0f);
+  c->epoch = 0;
+  std::memset(c->stats, 0, sizeof(c->stats));
+  return c;
+}
+void oracle_cache_destroy(oracle_cache* c) { delete c; }
+void oracle_cache_stats(const oracle_cache* c, int64_t* out) { std::memcpy(out, c->stats, sizeof(c->stats)); }
+void oracle_cache_state(const oracle_cache* c, uint64_t* tags, uint32_t* stamps, float* data) {
+  if (tags) std::memcpy(tags, c->tag.data(), c->tag.size() * sizeof(uint64_t));
+  if (stamps) std::memcpy(stamps, c->stamp.data(), c->stamp.size() * sizeof(uint32_t));
+  if (data) std::memcpy(data, c->data.data(), c->data.size() * sizeof(float));
+}
+
+// One query call.  Every key is classified against the cache as it was when the call began (all
+// occurrences of a key get the same answer).  A hit reads the cached copy and refreshes its stamp;
+// a miss reads the host table (key = host row; out-of-range keys read as a zero row and are never
+// cached).  out[bag, :] is the plain sum of the bag's vectors.  With insert_missing, the distinct
+// missing keys are then placed in first-appearance order: lowest-index empty way, else the way
+// with the smallest stamp among those not touched in this call (ties: lowest way), else skipped.
+void oracle_cache_query(oracle_cache* c, int64_t n_bags, const int64_t* keys,
+                        const int64_t* offsets, int64_t hotness, int64_t nnz,
+                        int32_t insert_missing, float* out, uint8_t* hit_mask) {
+  c->epoch += 1;
+  const int W = c->ways, D = c->dim;
+  std::vector<int64_t> where(nnz, -1);            // cache line (set*ways+way) for hits
+  for (int64_t i = 0; i < nnz; ++i) {             // classify against the entry state: tags only
+    if (keys[i] < 0) continue;
+    int64_t set = cache_set_of((uint64_t)keys[i], c->num_sets);
+    for (int w = 0; w < W; ++w)
+      if (c->tag[set * W + w] == (uint64_t)keys[i]) { where[i] = set * W + w; break; }
+  }
+  std::vector<double> acc(D);
+  for (int64_t bag = 0; bag < n_bags; ++bag) {
+    std::fill(acc.begin(), acc.end(), 0.0);
+    int64_t b0 = offsets ? offsets[bag] : bag * hotness;
+    int64_t b1 = offsets ? offsets[bag + 1] : (bag + 1) * hotness;
+    for (int64_t i = b0; i < b1; ++i) {
+      c->stats[0] += 1;
+      if (where[i] >= 0) {
+        c->stats[1] += 1;
+        c->stamp[where[i]] = c->epoch;
+        if (hit_mask) hit_mask[i] = 1;
+        for (int d = 0; d < D; ++d) acc[d] += (double)c->data[where[i] * D + d];
+      } else {
+        c->stats[2] += 1;
+        if (hit_mask) hit_mask[i] = 0;
+        if (keys[i] >= 0 && keys[i] < c->host_rows)
+          for (int d = 0; d < D; ++d) acc[d] += (double)c->host_table[keys[i] * D + d];
+      }
+    }
+    for (int d = 0; d < D; ++d) out[bag * D + d] = (float)acc[d];
+  }
+  if (!insert_missing) return;
+  std::unordered_map<uint64_t, char> placed;      // missing keys already handled in this call
+  for (int64_t i = 0; i < nnz; ++i) {
+    if (where[i] >= 0 || keys[i] < 0 || keys[i] >= c->host_rows) continue;
+    uint64_t k = (uint64_t)keys[i];
+    if (!placed.emplace(k, 1).second) continue;
+    int64_t set = cache_set_of(k, c->num_sets);
+    int victim = -1;
+    for (int w = 0; w < W && victim < 0; ++w)
+      if (c->tag[set * W + w] == kEmptyTag) victim = w;
+    bool evict = false;
+    if (victim < 0) {
+      uint32_t best = 0;
+      for (int w = 0; w < W; ++w) {
+        uint32_t st = c->stamp[set * W + w];
+        if (st < c->epoch && (victim < 0 || st < best)) { victim = w; best = st; }
+      }
+      evict = victim >= 0;
+    }
+    if (victim < 0) { c->stats[5] += 1; continue; }
+    int64_t line = set * W + victim;
+    c->tag[line] = k;
+    c->stamp[line] = c->epoch;
+    std::memcpy(&c->data[line * D], &c->host_table[(int64_t)k * D], sizeof(float) * D);
+    c->stats[3] += 1;
+    if (evict) c->stats[4] += 1;
+  }
+}
+
+}  // extern "C"

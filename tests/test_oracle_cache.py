@@ -1,0 +1,133 @@
+"""Pins for the oracle's inference cache (section 3, "embedding inference cache", "Volatile
+database"): a hand-worked trace, the textbook structures it must reduce to (direct-mapped for
+one way, classical LRU for one set and one key per call), and state invariants."""
+import json
+import os
+from collections import OrderedDict
+
+import numpy as np
+
+import oracle
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "cache_batch_lru_trace.json")
+RNG = np.random.default_rng(77)
+M64 = (1 << 64) - 1
+
+
+def host_table(rows, dim):
+    return (np.arange(rows, dtype=np.float32)[:, None] + np.arange(dim, dtype=np.float32)[None, :] / 128).copy()
+
+
+def set_of(key, num_sets):
+    """The frozen set-index rule, in Python integers."""
+    x = (key * 0x9E3779B97F4A7C15) & M64
+    x ^= x >> 32
+    return x % num_sets
+
+
+def test_hand_worked_trace():
+    g = json.load(open(GOLD))
+    ht = host_table(g["host_rows"], g["dim"])
+    c = oracle.Cache(g["num_sets"], g["ways"], ht)
+    for call in g["calls"]:
+        keys = np.array(call["keys"], dtype=np.int64)
+        out, hit = c.query(keys, call["n_bags"], insert_missing=bool(call["insert"]))
+        assert hit.tolist() == call["hit"]
+        tags, stamps = c.state()
+        assert tags[0].tolist() == call["tags"] and stamps[0].tolist() == call["stamps"]
+        assert c.stats.tolist() == call["stats"]
+        hot = len(keys) // call["n_bags"]
+        ref = ht[keys].astype(np.float64).reshape(call["n_bags"], hot, -1).sum(1).astype(np.float32)
+        assert np.array_equal(out, ref)
+
+
+def test_one_way_is_a_direct_mapped_cache():
+    num_sets, ht = 13, host_table(500, 4)
+    c = oracle.Cache(num_sets, 1, ht)
+    slot = {}                                             # textbook direct-mapped: set -> resident key
+    for _ in range(300):
+        k = int(RNG.integers(0, 500))
+        _, hit = c.query(np.array([k]), 1)
+        s = set_of(k, num_sets)
+        assert bool(hit[0]) == (slot.get(s) == k)
+        slot[s] = k
+    tags, _ = c.state()
+    for s in range(num_sets):
+        assert tags[s, 0] == (slot[s] if s in slot else oracle.EMPTY_TAG)
+
+
+def test_one_set_one_key_per_call_is_classical_lru():
+    ways, ht = 5, host_table(40, 4)
+    c = oracle.Cache(1, ways, ht)
+    lru = OrderedDict()
+    for _ in range(500):
+        k = int(RNG.integers(0, 12))
+        _, hit = c.query(np.array([k]), 1)
+        assert bool(hit[0]) == (k in lru)
+        if k in lru:
+            lru.move_to_end(k)
+        else:
+            if len(lru) == ways:
+                lru.popitem(last=False)
+            lru[k] = True
+        tags, _ = c.state()
+        assert sorted(t for t in tags[0].tolist() if t != int(oracle.EMPTY_TAG)) == sorted(lru)
+
+
+def test_big_enough_cache_misses_each_key_exactly_once():
+    ht = host_table(300, 8)
+    keys_all = RNG.permutation(300)[:64]
+    num_sets, ways = 64, 8
+    load = np.bincount([set_of(int(k), num_sets) for k in keys_all], minlength=num_sets)
+    assert load.max() <= ways                             # no set overflows, so nothing is ever evicted
+    c = oracle.Cache(num_sets, ways, ht)
+    seen = set()
+    for _ in range(20):
+        keys = keys_all[RNG.integers(0, 64, 48)]
+        out, hit = c.query(keys, 12)
+        assert hit.tolist() == [int(k in seen) for k in keys.tolist()]
+        seen.update(keys.tolist())
+        ref = ht[keys].astype(np.float64).reshape(12, 4, -1).sum(1).astype(np.float32)
+        assert np.array_equal(out, ref)                   # output never depends on cache state
+    assert c.stats[4] == 0 and c.stats[5] == 0 and c.stats[3] == len(seen)
+
+
+def test_state_invariants_under_pressure():
+    ht = host_table(2000, 4)
+    c = oracle.Cache(16, 4, ht)
+    offsets = None
+    for it in range(30):
+        h = RNG.integers(0, 6, 40)
+        offsets = np.concatenate([[0], np.cumsum(h)])
+        keys = RNG.zipf(1.3, offsets[-1]) % 2000
+        keys[RNG.integers(0, len(keys), 2)] = [-5, 2000]  # keys outside the host table: zero rows, never cached
+        before_tags, _ = c.state()
+        s0 = c.stats
+        out, hit = c.query(keys, 40, offsets=offsets, insert_missing=(it % 3 != 2))
+        s1 = c.stats
+        tags, stamps = c.state()
+        assert s1[0] - s0[0] == len(keys) and (s1[1] - s0[1]) + (s1[2] - s0[2]) == len(keys)
+        assert s1[1] - s0[1] == hit.sum()
+        for s in range(16):
+            live = [t for t in tags[s].tolist() if t != int(oracle.EMPTY_TAG)]
+            assert len(live) == len(set(live))            # no duplicate tag in a set
+            assert all(set_of(t, 16) == s for t in live)  # every tag lives in its own set
+            assert all(0 <= t < 2000 for t in live)
+        valid = (keys >= 0) & (keys < 2000)
+        ref = np.zeros((40, 4))
+        np.add.at(ref, np.repeat(np.arange(40), h)[valid], ht[keys[valid]].astype(np.float64))
+        assert np.array_equal(out, ref.astype(np.float32))
+        if it % 3 == 2:
+            assert np.array_equal(tags, before_tags)      # no insertion requested: tags unchanged
+        # a key classified as hit was resident at entry; all occurrences of a key agree
+        resident = set(before_tags.ravel().tolist())
+        assert hit.tolist() == [int(int(k) in resident and k >= 0) for k in keys.tolist()]
+        assert s1[3] - s0[3] >= s1[4] - s0[4]
+
+
+def test_set_index_spreads_scrambled_keys_evenly():
+    num_sets = 257
+    keys = (np.arange(50000, dtype=np.uint64) * np.uint64(7919)) % np.uint64(10**9)
+    cnt = np.bincount([set_of(int(k), num_sets) for k in keys], minlength=num_sets)
+    chi2 = ((cnt - 50000 / num_sets) ** 2 / (50000 / num_sets)).sum()
+    assert chi2 < 2 * num_sets
