@@ -1,0 +1,206 @@
+/*
+ * hctr.h - C ABI of the MI355X (gfx950) hashed sparse embedding library.
+ *
+ * The operations are the hot path of the embedding layer and of the inference cache described in
+ * "Merlin HugeCTR: GPU-accelerated Recommender System Training and Inference" (RecSys'22):
+ *   - key -> row lookup per slot, row gather and intra-slot reduction (section 1, "Localized slot
+ *     embedding hash"), run forward and backward (section 1, "Hybrid sparse embedding"), with
+ *     FP16 parameter storage as an option (section 1, "Mixed precision training");
+ *   - the "embedding hash" itself: an open-addressing key -> row table with insert on miss
+ *     (section 1, "Localized / Distributed slot embedding hash");
+ *   - the level-1 GPU embedding cache with dynamic insertion, whose misses are served from system
+ *     memory across the host link (section 3, "embedding inference cache", "Volatile database").
+ *
+ * General conventions
+ *   Pointers   Every array argument says "device" or "host".  Device arrays are ordinary HIP device
+ *              allocations; "pinned host" means hipHostMalloc'ed, device-mapped host memory.
+ *   Ownership  The caller owns every buffer, including table, hash storage, cache storage and
+ *              workspaces.  The library never allocates or frees device memory; the opaque handles
+ *              are small host-side structs freed by the matching *_destroy.
+ *   Streams    `stream` is a hipStream_t passed as void* (NULL = the default stream).  Compute
+ *              calls enqueue work and return without waiting; only hctr_hash_size, hctr_cache_stats
+ *              and hctr_emb_invalid_keys wait for the stream.  A workspace must stay untouched by
+ *              the caller until the stream has passed the call that uses it.
+ *   Errors     Every call returns an hctr_status.  Argument errors are found on the host before
+ *              anything is launched.  A failing HIP call gives HCTR_E_DEVICE.  hctr_last_error()
+ *              returns a thread-local message for the last failing call on this thread.
+ *   Layout     Bags are numbered bag = sample * num_slots + slot.  Keys are int64, bag-major.
+ *              CSR offsets are int64 [n_bags + 1], offsets[0] = 0, offsets[n_bags] = nnz,
+ *              non-decreasing (not checked).  offsets == NULL means exactly one key per bag.
+ *              Pooled outputs and upstream gradients are fp32 [batch, num_slots, dim] row-major.
+ *              Tables are [total_rows, dim] row-major in fp32 or fp16, 16-byte aligned.
+ */
+#ifndef HCTR_H_
+#define HCTR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HCTR_OK = 0,
+  HCTR_E_INVALID_ARG = -1,
+  HCTR_E_NULL_PTR = -2,
+  HCTR_E_WORKSPACE = -3,   /* workspace missing, misaligned (256 B) or too small */
+  HCTR_E_UNSUPPORTED = -4,
+  HCTR_E_DEVICE = -5
+} hctr_status;
+
+typedef enum { HCTR_F32 = 0, HCTR_F16 = 1 } hctr_dtype;
+typedef enum { HCTR_SUM = 0, HCTR_MEAN = 1 } hctr_combiner;
+
+#define HCTR_MAX_SLOTS 128
+
+typedef struct hctr_hash hctr_hash;   /* opaque */
+typedef struct hctr_cache hctr_cache; /* opaque */
+
+/*
+ * Description of one fused embedding layer (section 1, "Localized slot embedding hash": every
+ * slot's table lives on this GPU).
+ *
+ * Direct mode (hash == NULL): slot s owns rows [slot_row_base[s], slot_row_base[s] + slot_num_rows[s])
+ * of `table`; key k of a bag of slot s addresses row slot_row_base[s] + k.  Slots may share a range.
+ * A key outside [0, slot_num_rows[s]) has no row.
+ * Hashed mode (hash != NULL): all slots share the key space of `hash`; the row of a key is the
+ * value the hash holds for it (with insert_on_miss, absent keys are inserted first, as by
+ * hctr_hash_insert_or_find); `table` must have at least the hash's max_rows rows and
+ * total_rows = max_rows.  slot_row_base / slot_num_rows are ignored.
+ * A key without a row contributes a zero vector in forward and nothing in backward (it still
+ * counts in a mean's denominator) and is counted (hctr_emb_invalid_keys).
+ */
+typedef struct {
+  int32_t num_slots;            /* S, 1..HCTR_MAX_SLOTS */
+  int32_t dim;                  /* D > 0, multiple of 4 (fp32 table) or 8 (fp16 table) */
+  int32_t table_dtype;          /* hctr_dtype of the table; out and dY are always fp32 */
+  int32_t combiner;             /* hctr_combiner */
+  void* table;                  /* device [total_rows, dim] */
+  int64_t total_rows;           /* 1 .. 2^32 - 2 */
+  const int64_t* slot_row_base; /* host [S] (direct mode) */
+  const int64_t* slot_num_rows; /* host [S] (direct mode) */
+  hctr_hash* hash;              /* NULL = direct mode */
+  int32_t insert_on_miss;       /* hashed mode, forward only: 1 = insert absent keys */
+} hctr_emb_desc;
+
+/* Bytes of workspace that forward and backward need for up to nnz_max keys (multiple of 256). */
+size_t hctr_emb_workspace_bytes(const hctr_emb_desc* desc, int64_t batch, int64_t nnz_max);
+
+/*
+ * Forward: out[b, s, :] = w * sum_j T[row(key_j), :] over the keys of bag (b, s); w = 1 for
+ * HCTR_SUM, 1/hotness for HCTR_MEAN (hotness = number of keys of the bag); an empty bag gives
+ * zeros.  fp16 tables are converted exactly to fp32; accumulation is fp32 in a fixed order, so two
+ * runs give the same bits.  (Section 1, "Localized slot embedding hash": lookup + intra-slot
+ * reduction.)
+ *   keys    device [nnz]           offsets device [batch*S + 1] or NULL (then nnz == batch*S)
+ *   out     device [batch, S, dim] fp32, 16-byte aligned, fully overwritten
+ *   ws      device, >= hctr_emb_workspace_bytes(desc, batch, nnz), 256-byte aligned
+ * batch == 0 is accepted and does nothing.
+ */
+hctr_status hctr_emb_forward(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
+                             const int64_t* offsets, int64_t nnz, float* out, void* ws,
+                             size_t ws_bytes, void* stream);
+
+/*
+ * Backward with fused SGD: for every distinct table row r addressed by the batch,
+ *   g_r = sum over the occurrences (bag, j) of r of w_bag * dY[bag, :]   (w as in forward),
+ *   T[r, :] <- T[r, :] - lr * g_r,
+ * computed in fp32 in a fixed order (deterministic); fp16 tables are widened, updated in fp32 and
+ * stored with round-to-nearest-even.  Rows not addressed keep their bits.  Internally: key -> row,
+ * stable radix sort of (row, bag) pairs, run boundaries (= dedup), segmented reduction of dY fused
+ * with the row update.  In hashed mode keys are looked up only (never inserted); unknown keys are
+ * skipped.  (Section 1, "Hybrid sparse embedding" names the backward pass; the paper gives no
+ * optimizer, plain SGD is the benchmark's.)
+ *   dY      device [batch, S, dim] fp32, 16-byte aligned
+ * The dedup result of the call stays in the workspace, see hctr_emb_dedup_view.
+ */
+hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
+                                  const int64_t* offsets, int64_t nnz, const float* dY, float lr,
+                                  void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Where the last backward call on `ws` left its dedup result (device pointers into ws, valid until
+ * ws is reused; `nnz` must be the nnz of that call, the workspace is laid out by it): *num_unique -> one int64 U; *uniq_rows -> uint32 [U] distinct global rows in
+ * ascending order; *seg_offsets -> uint32 [U + 1], seg_offsets[u+1] - seg_offsets[u] = number of
+ * occurrences of uniq_rows[u].  Pure pointer arithmetic, no device work.
+ */
+hctr_status hctr_emb_dedup_view(const hctr_emb_desc* desc, int64_t batch, int64_t nnz, void* ws,
+                                size_t ws_bytes, const int64_t** num_unique,
+                                const uint32_t** uniq_rows, const uint32_t** seg_offsets);
+
+/* Number of keys without a row seen by the last forward or backward call on `ws` (host int64;
+ * waits for the stream). */
+hctr_status hctr_emb_invalid_keys(const void* ws, size_t ws_bytes, void* stream, int64_t* count);
+
+/*
+ * Embedding hash (section 1, the "embedding hash" layers): open addressing, 16-byte slots
+ * {key, row} in 128-byte buckets, probed by groups of 8 lanes.  Valid keys are 0 <= key < 2^63.
+ * Rows are dense: the table holds keys with rows 0 .. size-1, a row never changes, and a call
+ * assigns new rows in the order in which new keys first appear in its key array.
+ *   capacity  number of slots (>= 64); max_rows = most keys it will ever hold, 1 <= max_rows <=
+ *             0.8 * capacity.  Once size == max_rows further new keys are rejected (row -1).
+ *   storage   device, >= hctr_hash_storage_bytes(capacity), 256-byte aligned; hctr_hash_create
+ *             enqueues its initialisation on `stream`.
+ */
+size_t hctr_hash_storage_bytes(int64_t capacity);
+hctr_status hctr_hash_create(void* storage, size_t storage_bytes, int64_t capacity, int64_t max_rows,
+                             void* stream, hctr_hash** out);
+size_t hctr_hash_workspace_bytes(int64_t n_max);
+/*
+ *   keys  device [n]; rows device [n] int64, row of each key or -1 (absent / rejected / negative key)
+ *   insert 0 = look up only, 1 = insert absent keys first
+ *   ws    device, >= hctr_hash_workspace_bytes(n), 256-byte aligned (may be NULL when n == 0)
+ */
+hctr_status hctr_hash_insert_or_find(hctr_hash* hash, const int64_t* keys, int64_t n, int32_t insert,
+                                     int64_t* rows, void* ws, size_t ws_bytes, void* stream);
+/* Number of keys held (host int64; waits for the stream). */
+hctr_status hctr_hash_size(hctr_hash* hash, void* stream, int64_t* size);
+void hctr_hash_destroy(hctr_hash* hash);
+
+/*
+ * Inference embedding cache (section 3, "embedding inference cache"): set-associative, num_sets
+ * sets of `ways` lines (ways a power of two, 1..64), each line one fp32 row of `dim` values
+ * (multiple of 4).  The backing store is a table in pinned host memory read by the GPU across the
+ * host link (section 3, "Volatile database"); key = row index in that table.
+ * Set of a key: x = key * 0x9E3779B97F4A7C15 mod 2^64; x ^= x >> 32; set = x mod num_sets.
+ * Replacement is LRU at the granularity of a query call, see hctr_cache_query.
+ *   storage     device, >= hctr_cache_storage_bytes(...), 256-byte aligned; initialised on `stream`
+ *   host_table  pinned host [host_rows, dim] fp32, must stay valid while the cache lives
+ */
+size_t hctr_cache_storage_bytes(int64_t num_sets, int32_t ways, int32_t dim);
+hctr_status hctr_cache_create(void* storage, size_t storage_bytes, int64_t num_sets, int32_t ways,
+                              int32_t dim, const float* host_table, int64_t host_rows, void* stream,
+                              hctr_cache** out);
+size_t hctr_cache_workspace_bytes(const hctr_cache* cache, int64_t nnz_max);
+/*
+ * One query: out[bag, :] = sum of the vectors of the bag's keys (fp32, fixed order).  Every key is
+ * classified against the cache contents at call entry: a hit reads the cached line and marks it
+ * used in this call; a miss reads host_table[key] (a key outside [0, host_rows) reads as zeros and
+ * is never cached).  With insert_missing != 0 the distinct missing keys are then inserted in order
+ * of first appearance: into the lowest-index empty way of their set, else over the least recently
+ * used way among those not used in this call (ties: lowest way), else the insert is skipped.
+ *   n_bags   batch * num_slots bags;  keys device [nnz]
+ *   offsets  device [n_bags + 1] or NULL = fixed hotness nnz / n_bags (nnz must divide evenly)
+ *   out      device [n_bags, dim] fp32;  hit_mask device [nnz] uint8 (1 = hit) or NULL
+ *   ws       device, >= hctr_cache_workspace_bytes(cache, nnz), 256-byte aligned
+ */
+hctr_status hctr_cache_query(hctr_cache* cache, int64_t batch, int32_t num_slots, const int64_t* keys,
+                             const int64_t* offsets, int64_t nnz, int32_t insert_missing, float* out,
+                             uint8_t* hit_mask, void* ws, size_t ws_bytes, void* stream);
+/* stats[6] (host) = cumulative {keys queried, hits, misses, inserts, evictions, skipped inserts};
+ * waits for the stream. */
+hctr_status hctr_cache_stats(hctr_cache* cache, void* stream, int64_t stats[6]);
+/* Device pointers to the cache state inside its storage (for inspection): tags uint64
+ * [num_sets, ways] (all ones = empty), stamps uint32 [num_sets, ways], data fp32 [num_sets*ways, dim]. */
+hctr_status hctr_cache_state_view(hctr_cache* cache, const uint64_t** tags, const uint32_t** stamps,
+                                  const float** data);
+void hctr_cache_destroy(hctr_cache* cache);
+
+/* Thread-local text of the last error on this thread; never NULL. */
+const char* hctr_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HCTR_H_ */

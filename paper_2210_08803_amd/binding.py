@@ -1,0 +1,290 @@
+"""ctypes binding of libhctr.so.  Names follow include/hctr.h; no arithmetic happens here."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libhctr.so")
+
+F32, F16 = 0, 1
+SUM, MEAN = 0, 1
+MAX_SLOTS = 128
+
+
+class HctrError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"hctr status {status}: {text}")
+        self.status = status
+
+
+class _EmbDesc(C.Structure):
+    _fields_ = [
+        ("num_slots", C.c_int32), ("dim", C.c_int32), ("table_dtype", C.c_int32), ("combiner", C.c_int32),
+        ("table", C.c_void_p), ("total_rows", C.c_int64),
+        ("slot_row_base", C.POINTER(C.c_int64)), ("slot_num_rows", C.POINTER(C.c_int64)),
+        ("hash", C.c_void_p), ("insert_on_miss", C.c_int32),
+    ]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> C.CDLL:
+    """Loads the built library; builds it first only when no library exists.  There is no other
+    implementation to fall back to: a missing toolchain or library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build()
+    L = C.CDLL(_LIB_PATH)
+    p, i32, i64, sz, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
+    dp = C.POINTER(_EmbDesc)
+    sig = {
+        "hctr_emb_workspace_bytes": (sz, [dp, i64, i64]),
+        "hctr_emb_forward": (i32, [dp, i64, p, p, i64, p, p, sz, p]),
+        "hctr_emb_backward_sgd": (i32, [dp, i64, p, p, i64, p, f32, p, sz, p]),
+        "hctr_emb_dedup_view": (i32, [dp, i64, i64, p, sz, C.POINTER(p), C.POINTER(p), C.POINTER(p)]),
+        "hctr_emb_invalid_keys": (i32, [p, sz, p, C.POINTER(i64)]),
+        "hctr_hash_storage_bytes": (sz, [i64]),
+        "hctr_hash_create": (i32, [p, sz, i64, i64, p, C.POINTER(p)]),
+        "hctr_hash_workspace_bytes": (sz, [i64]),
+        "hctr_hash_insert_or_find": (i32, [p, p, i64, i32, p, p, sz, p]),
+        "hctr_hash_size": (i32, [p, p, C.POINTER(i64)]),
+        "hctr_hash_destroy": (None, [p]),
+        "hctr_cache_storage_bytes": (sz, [i64, i32, i32]),
+        "hctr_cache_create": (i32, [p, sz, i64, i32, i32, p, i64, p, C.POINTER(p)]),
+        "hctr_cache_workspace_bytes": (sz, [p, i64]),
+        "hctr_cache_query": (i32, [p, i64, i32, p, p, i64, i32, p, p, p, sz, p]),
+        "hctr_cache_stats": (i32, [p, p, C.POINTER(i64)]),
+        "hctr_cache_state_view": (i32, [p, C.POINTER(p), C.POINTER(p), C.POINTER(p)]),
+        "hctr_cache_destroy": (None, [p]),
+        "hctr_last_error": (C.c_char_p, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = L
+    return L
+
+
+EXPORTS = [
+    "hctr_emb_workspace_bytes", "hctr_emb_forward", "hctr_emb_backward_sgd", "hctr_emb_dedup_view",
+    "hctr_emb_invalid_keys", "hctr_hash_storage_bytes", "hctr_hash_create", "hctr_hash_workspace_bytes",
+    "hctr_hash_insert_or_find", "hctr_hash_size", "hctr_hash_destroy", "hctr_cache_storage_bytes",
+    "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_query", "hctr_cache_stats",
+    "hctr_cache_state_view", "hctr_cache_destroy", "hctr_last_error",
+]
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise HctrError(status, lib().hctr_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(256, nbytes), dtype=torch.uint8, device=device)
+
+
+class HashTable:
+    """hctr_hash_*: key -> dense row id, rows assigned in first-appearance order."""
+
+    def __init__(self, capacity: int, max_rows: int, device="cuda"):
+        L = lib()
+        nbytes = L.hctr_hash_storage_bytes(capacity)
+        if nbytes == 0:
+            raise HctrError(-1, "capacity out of range")
+        self.storage = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.capacity, self.max_rows, self.device = capacity, max_rows, device
+        h = C.c_void_p()
+        _check(L.hctr_hash_create(self.storage.data_ptr(), nbytes, capacity, max_rows, _stream(None), C.byref(h)))
+        self.handle = h
+        self._wsbuf = None
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib().hctr_hash_destroy(self.handle)
+            self.handle = None
+
+    def workspace(self, n: int) -> torch.Tensor:
+        need = lib().hctr_hash_workspace_bytes(n)
+        if self._wsbuf is None or self._wsbuf.numel() < need:
+            self._wsbuf = _ws(need, self.device)
+        return self._wsbuf
+
+    def insert_or_find(self, keys: torch.Tensor, insert: bool = True, rows: Optional[torch.Tensor] = None,
+                       ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+        n = keys.numel()
+        if rows is None:
+            rows = torch.empty(n, dtype=torch.int64, device=keys.device)
+        if ws is None:
+            ws = self.workspace(n)
+        _check(lib().hctr_hash_insert_or_find(self.handle, _ptr(keys), n, int(insert), _ptr(rows), _ptr(ws),
+                                              ws.numel(), _stream(stream)))
+        return rows
+
+    @property
+    def size(self) -> int:
+        v = C.c_int64()
+        _check(lib().hctr_hash_size(self.handle, _stream(None), C.byref(v)))
+        return v.value
+
+
+class EmbeddingLayer:
+    """hctr_emb_*: fused multi-slot embedding over one table tensor [total_rows, dim]."""
+
+    def __init__(self, table: torch.Tensor, num_slots: int, combiner: int = SUM,
+                 slot_row_base: Optional[Sequence[int]] = None, slot_num_rows: Optional[Sequence[int]] = None,
+                 hash_table: Optional[HashTable] = None, insert_on_miss: bool = True):
+        assert table.is_cuda and table.is_contiguous() and table.dim() == 2
+        self.table, self.num_slots, self.combiner = table, num_slots, combiner
+        self.hash_table = hash_table
+        d = _EmbDesc()
+        d.num_slots, d.dim = num_slots, table.shape[1]
+        d.table_dtype = F32 if table.dtype == torch.float32 else F16
+        assert table.dtype in (torch.float32, torch.float16)
+        d.combiner = combiner
+        d.table, d.total_rows = table.data_ptr(), table.shape[0]
+        if hash_table is None:
+            self._base = (C.c_int64 * num_slots)(*[int(x) for x in slot_row_base])
+            self._num = (C.c_int64 * num_slots)(*[int(x) for x in slot_num_rows])
+            d.slot_row_base, d.slot_num_rows = self._base, self._num
+            d.hash = None
+        else:
+            d.hash = hash_table.handle
+        d.insert_on_miss = int(insert_on_miss)
+        self.desc = d
+        self._wsbuf = None
+
+    def workspace_bytes(self, batch: int, nnz: int) -> int:
+        return lib().hctr_emb_workspace_bytes(C.byref(self.desc), batch, nnz)
+
+    def workspace(self, batch: int, nnz: int) -> torch.Tensor:
+        need = self.workspace_bytes(batch, nnz)
+        if self._wsbuf is None or self._wsbuf.numel() < need:
+            self._wsbuf = _ws(need, self.table.device)
+        return self._wsbuf
+
+    def forward(self, batch: int, keys: torch.Tensor, offsets: Optional[torch.Tensor] = None,
+                out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+        nnz = keys.numel()
+        if out is None:
+            out = torch.empty((batch, self.num_slots, self.table.shape[1]), dtype=torch.float32,
+                              device=self.table.device)
+        if ws is None:
+            ws = self.workspace(batch, nnz)
+        _check(lib().hctr_emb_forward(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(out),
+                                      _ptr(ws), ws.numel(), _stream(stream)))
+        return out
+
+    def backward_sgd(self, batch: int, keys: torch.Tensor, dY: torch.Tensor, lr: float,
+                     offsets: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> None:
+        nnz = keys.numel()
+        if ws is None:
+            ws = self.workspace(batch, nnz)
+        _check(lib().hctr_emb_backward_sgd(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(dY),
+                                           float(lr), _ptr(ws), ws.numel(), _stream(stream)))
+
+    def dedup_result(self, batch: int, nnz: int, ws: Optional[torch.Tensor] = None):
+        """(unique rows uint32-as-int64 [U], occurrence counts [U]) of the last backward on ws."""
+        ws = ws if ws is not None else self._wsbuf
+        pu, pr, ps = C.c_void_p(), C.c_void_p(), C.c_void_p()
+        _check(lib().hctr_emb_dedup_view(C.byref(self.desc), batch, nnz, _ptr(ws), ws.numel(),
+                                         C.byref(pu), C.byref(pr), C.byref(ps)))
+        torch.cuda.synchronize()
+        base = ws.data_ptr()
+        u = int(ws[pu.value - base: pu.value - base + 8].view(torch.int64).item())
+        rows = ws[pr.value - base: pr.value - base + 4 * u].view(torch.int32).to(torch.int64) & 0xFFFFFFFF
+        seg = ws[ps.value - base: ps.value - base + 4 * (u + 1)].view(torch.int32).to(torch.int64) & 0xFFFFFFFF
+        return rows, seg[1:] - seg[:-1]
+
+    def invalid_keys(self, ws: Optional[torch.Tensor] = None) -> int:
+        ws = ws if ws is not None else self._wsbuf
+        v = C.c_int64()
+        _check(lib().hctr_emb_invalid_keys(_ptr(ws), ws.numel(), _stream(None), C.byref(v)))
+        return v.value
+
+
+class EmbeddingCache:
+    """hctr_cache_*: set-associative GPU cache over a pinned host table [host_rows, dim] fp32."""
+
+    def __init__(self, num_sets: int, ways: int, host_table: torch.Tensor, device="cuda"):
+        assert host_table.dtype == torch.float32 and host_table.dim() == 2 and host_table.is_contiguous()
+        assert host_table.is_pinned(), "host_table must be pinned (device-mapped) host memory"
+        L = lib()
+        self.host_table, self.device = host_table, device
+        self.num_sets, self.ways, self.dim = num_sets, ways, host_table.shape[1]
+        nbytes = L.hctr_cache_storage_bytes(num_sets, ways, self.dim)
+        if nbytes == 0:
+            raise HctrError(-1, "cache shape out of range")
+        self.storage = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        h = C.c_void_p()
+        _check(L.hctr_cache_create(self.storage.data_ptr(), nbytes, num_sets, ways, self.dim,
+                                   host_table.data_ptr(), host_table.shape[0], _stream(None), C.byref(h)))
+        self.handle = h
+        self._wsbuf = None
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib().hctr_cache_destroy(self.handle)
+            self.handle = None
+
+    def workspace(self, nnz: int) -> torch.Tensor:
+        need = lib().hctr_cache_workspace_bytes(self.handle, nnz)
+        if self._wsbuf is None or self._wsbuf.numel() < need:
+            self._wsbuf = _ws(need, self.device)
+        return self._wsbuf
+
+    def query(self, batch: int, num_slots: int, keys: torch.Tensor, offsets: Optional[torch.Tensor] = None,
+              insert_missing: bool = True, out: Optional[torch.Tensor] = None,
+              hit_mask: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None):
+        nnz = keys.numel()
+        if out is None:
+            out = torch.empty((batch, num_slots, self.dim), dtype=torch.float32, device=self.device)
+        if ws is None:
+            ws = self.workspace(nnz)
+        _check(lib().hctr_cache_query(self.handle, batch, num_slots, _ptr(keys), _ptr(offsets), nnz,
+                                      int(insert_missing), _ptr(out), _ptr(hit_mask), _ptr(ws), ws.numel(),
+                                      _stream(stream)))
+        return out
+
+    @property
+    def stats(self):
+        arr = (C.c_int64 * 6)()
+        _check(lib().hctr_cache_stats(self.handle, _stream(None), arr))
+        return list(arr)
+
+    def state(self):
+        """(tags [num_sets, ways] int64 bit patterns, stamps [num_sets, ways] int64) copied to host."""
+        pt, ps, pd = C.c_void_p(), C.c_void_p(), C.c_void_p()
+        _check(lib().hctr_cache_state_view(self.handle, C.byref(pt), C.byref(ps), C.byref(pd)))
+        torch.cuda.synchronize()
+        base, n = self.storage.data_ptr(), self.num_sets * self.ways
+        tags = self.storage[pt.value - base: pt.value - base + 8 * n].view(torch.int64).view(self.num_sets, self.ways)
+        stamps = self.storage[ps.value - base: ps.value - base + 4 * n].view(torch.int32).view(self.num_sets, self.ways)
+        return tags.cpu(), stamps.cpu().to(torch.int64) & 0xFFFFFFFF
+
+    def data(self) -> torch.Tensor:
+        pt, ps, pd = C.c_void_p(), C.c_void_p(), C.c_void_p()
+        _check(lib().hctr_cache_state_view(self.handle, C.byref(pt), C.byref(ps), C.byref(pd)))
+        base, n = self.storage.data_ptr(), self.num_sets * self.ways
+        off = pd.value - base
+        return self.storage[off: off + 4 * n * self.dim].view(torch.float32).view(n, self.dim)

@@ -1,0 +1,87 @@
+// Internal helpers shared by the HIP translation units of libhctr (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "hctr.h"
+
+#define HCTR_API extern "C" __attribute__((visibility("default")))
+
+namespace hctr {
+
+constexpr int kWave = 64;
+constexpr uint32_t kNoRow = 0xFFFFFFFFu;          // 32-bit global row id meaning "key has no row"
+constexpr uint64_t kEmptyKey = ~0ull;             // empty hash slot / empty cache tag
+
+// Error text of the last failing call on this thread.
+void set_error(const char* fmt, ...);
+hctr_status fail(hctr_status st, const char* fmt, ...);
+hctr_status check_hip(hipError_t e, const char* what);
+
+#define HCTR_TRY_HIP(expr)                                        \
+  do {                                                            \
+    hipError_t e_ = (expr);                                       \
+    if (e_ != hipSuccess) return ::hctr::check_hip(e_, #expr);    \
+  } while (0)
+
+#define HCTR_TRY(expr)                         \
+  do {                                         \
+    hctr_status s_ = (expr);                   \
+    if (s_ != HCTR_OK) return s_;              \
+  } while (0)
+
+inline hctr_status launch_status(const char* what) { return check_hip(hipGetLastError(), what); }
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int ceil_log2(uint64_t x) {  // smallest b with 2^b >= x
+  int b = 0;
+  while (b < 64 && (1ull << b) < x) ++b;
+  return b;
+}
+inline int pow2_ceil(int x) {
+  int p = 1;
+  while (p < x) p <<= 1;
+  return p;
+}
+
+// Carves a workspace into 256-byte aligned pieces; with base == nullptr it only measures.
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base(static_cast<char*>(b)) {}
+  template <typename T>
+  T* take(size_t count) {
+    size_t at = off;
+    off = align_up(off + count * sizeof(T));
+    return base ? reinterpret_cast<T*>(base + at) : nullptr;
+  }
+};
+
+// ---- device-side scan and sort primitives (primitives.hip) -------------------------------------
+
+// Exclusive prefix sum of uint32 in[0..n) into out (may alias in).  tmp holds scan_tmp_count(n)
+// uint32.  If total != nullptr the grand total is written there (uint32).
+size_t scan_tmp_count(uint32_t n);
+hctr_status exclusive_scan_u32(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* tmp,
+                               uint32_t* total, hipStream_t stream);
+
+// Stable LSD radix sort of (key, value) uint32 pairs on the low `bits` bits of the key.
+// The element count is *n_dev if n_dev != nullptr (must be <= n_max), else n_max.
+// Buffers 0 hold the input; the result lands in buffers (passes & 1), passes = ceil(bits / 8).
+struct SortPlan {
+  uint32_t n_max = 0;
+  uint32_t n_blocks = 0;   // tiles of kSortTile keys
+  uint32_t hist_count = 0; // 256 * n_blocks
+  int passes = 0;
+};
+constexpr uint32_t kSortTile = 4096;
+SortPlan sort_plan(uint32_t n_max, int bits);
+hctr_status radix_sort_pairs(const SortPlan& plan, int bits, const uint32_t* n_dev, uint32_t* keys0,
+                             uint32_t* vals0, uint32_t* keys1, uint32_t* vals1, uint32_t* hist,
+                             uint32_t* scan_tmp, hipStream_t stream);
+
+}  // namespace hctr

@@ -1,0 +1,664 @@
+// Embedding layer forward (key -> row, gather, pool) and backward (dedup, segmented reduce, SGD)
+// for gfx950.  Bandwidth-bound work: every lane moves 16 bytes per load, a table row is covered
+// by a group of LPR adjacent lanes (LPR * 16 bytes >= row bytes), and several independent row
+// loads are in flight per lane before the first use.
+#include "common.h"
+#include "rowvec.h"
+#include "hash_internal.h"
+
+namespace hctr {
+
+// Per-slot row ranges, passed by value in the kernel argument segment (2 KB).
+struct SlotTable {
+  int64_t base[HCTR_MAX_SLOTS];
+  int64_t num[HCTR_MAX_SLOTS];
+};
+
+// First 256 bytes of an embedding workspace.
+struct EmbHeader {
+  unsigned long long invalid;  // keys without a row in the last call
+  long long num_unique;        // U of the last backward
+  uint32_t n_valid;            // sorted positions holding a real row
+  uint32_t pad[59];
+};
+static_assert(sizeof(EmbHeader) == 256, "header is one 256-byte block");
+
+__global__ void emb_init_header(EmbHeader* hdr, uint32_t* seg_off) {
+  if (threadIdx.x == 0) {
+    hdr->invalid = 0;
+    hdr->num_unique = 0;
+    hdr->n_valid = 0;
+    if (seg_off) seg_off[0] = 0;
+  }
+}
+
+__device__ __forceinline__ void count_invalid(unsigned long long* counter, bool flag) {
+  const uint64_t m = __ballot(flag);
+  if (m != 0 && (threadIdx.x & 63) == (__ffsll((unsigned long long)m) - 1))
+    atomicAdd(counter, (unsigned long long)__popcll(m));
+}
+
+// ------------------------------------------------------------------------------------------------
+// Forward, one key per bag: a group of LPR lanes copies U rows (U independent 16-byte loads per
+// lane in flight), so a wave covers 64/LPR * U bags.
+// ------------------------------------------------------------------------------------------------
+template <typename T, int LPR, int U, bool HASHED>
+__global__ __launch_bounds__(256) void fwd_onehot(const T* __restrict__ table, int D,
+                                                  int64_t total_rows, const int64_t* __restrict__ keys,
+                                                  const int64_t* __restrict__ rows64, uint32_t n_bags,
+                                                  uint32_t S, const SlotTable slots,
+                                                  float* __restrict__ out, EmbHeader* hdr) {
+  constexpr int VEC = RowVec<T>::VEC;
+  const int sub = threadIdx.x % LPR;
+  const uint32_t group = (blockIdx.x * 256u + threadIdx.x) / LPR;
+  const int col = blockIdx.y * (LPR * VEC) + sub * VEC;
+  const bool active = col < D;
+  const uint32_t bag0 = group * U;
+
+  int64_t row[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t bag = bag0 + u;
+    row[u] = -1;
+    if (bag < n_bags) {
+      if (HASHED) {
+        const int64_t r = rows64[bag];
+        if (r >= 0 && r < total_rows) row[u] = r;
+      } else {
+        const int64_t k = keys[bag];
+        const uint32_t s = bag % S;
+        if (k >= 0 && k < slots.num[s]) row[u] = slots.base[s] + k;
+      }
+    }
+  }
+  float v[U][VEC];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) v[u][i] = 0.f;
+    if (row[u] >= 0 && active) RowVec<T>::load(table + row[u] * D + col, v[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t bag = bag0 + u;
+    if (bag < n_bags && active) store_stream<VEC>(out + (int64_t)bag * D + col, v[u]);
+  }
+  if (blockIdx.y == 0) {
+    uint32_t nbad = 0;  // counted by the first lane of each group
+#pragma unroll
+    for (int u = 0; u < U; ++u) nbad += ((sub == 0) && (bag0 + u < n_bags) && row[u] < 0) ? 1u : 0u;
+    if (__ballot(nbad != 0) != 0) {  // rare: add the groups' counts across the wave
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) nbad += __shfl_xor(nbad, d);
+      if ((threadIdx.x & 63) == 0) atomicAdd(&hdr->invalid, (unsigned long long)nbad);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Forward, CSR bags: one wave per bag.  The wave's 64/LPR lane groups take the bag's keys round
+// robin, U keys each per step; the groups' partial sums are staged in LDS and added in group order
+// by group 0, which scales (mean) and writes the pooled row.
+// ------------------------------------------------------------------------------------------------
+template <typename T, int LPR, int U, bool HASHED>
+__global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int D, int64_t total_rows,
+                                               const int64_t* __restrict__ keys,
+                                               const int64_t* __restrict__ rows64,
+                                               const int64_t* __restrict__ offsets, uint32_t n_bags,
+                                               uint32_t S, const SlotTable slots, int mean,
+                                               float* __restrict__ out, EmbHeader* hdr) {
+  constexpr int VEC = RowVec<T>::VEC;
+  constexpr int G = 64 / LPR;
+  __shared__ float part[4][(G > 1 ? (G - 1) : 1) * LPR * VEC];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane / LPR, sub = lane % LPR;
+  const int col = blockIdx.y * (LPR * VEC) + sub * VEC;
+  const bool active = col < D;
+  const uint32_t bag = blockIdx.x * 4u + wave;
+  const bool live = bag < n_bags;
+  int64_t b0 = 0, b1 = 0, base = 0, num = 0;
+  if (live) {
+    b0 = offsets[bag];
+    b1 = offsets[bag + 1];
+    if (!HASHED) {
+      const uint32_t s = bag % S;
+      base = slots.base[s];
+      num = slots.num[s];
+    }
+  }
+  float acc[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+  uint32_t nbad = 0;
+  for (int64_t j = b0 + g; j < b1; j += G * U) {
+    int64_t row[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t jj = j + u * G;
+      row[u] = -1;
+      if (jj < b1) {
+        if (HASHED) {
+          const int64_t r = rows64[jj];
+          if (r >= 0 && r < total_rows) row[u] = r;
+        } else {
+          const int64_t k = keys[jj];
+          if (k >= 0 && k < num) row[u] = base + k;
+        }
+        nbad += (row[u] < 0 && sub == 0) ? 1u : 0u;
+      }
+    }
+    float v[U][VEC];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) v[u][i] = 0.f;
+      if (row[u] >= 0 && active) RowVec<T>::load(table + row[u] * D + col, v[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] += v[u][i];
+  }
+  if (G > 1) {
+    if (g > 0) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) part[wave][((g - 1) * LPR + sub) * VEC + i] = acc[i];
+    }
+    __syncthreads();
+    if (g == 0) {
+#pragma unroll
+      for (int gg = 1; gg < G; ++gg)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] += part[wave][((gg - 1) * LPR + sub) * VEC + i];
+    }
+  }
+  if (live && g == 0 && active) {
+    if (mean && b1 > b0) {
+      const float w = 1.0f / (float)(b1 - b0);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] *= w;
+    }
+    store_stream<VEC>(out + (int64_t)bag * D + col, acc);
+  }
+  if (blockIdx.y == 0 && __ballot(nbad != 0) != 0) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) nbad += __shfl_xor(nbad, d);
+    if (lane == 0) atomicAdd(&hdr->invalid, (unsigned long long)nbad);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Backward step 1: per key, the 32-bit global row (or kNoRow) and the bag it belongs to.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void bwd_rows(const int64_t* __restrict__ keys,
+                                                const int64_t* __restrict__ rows64,
+                                                const int64_t* __restrict__ offsets, uint32_t nnz,
+                                                uint32_t n_bags, uint32_t S, const SlotTable slots,
+                                                int64_t total_rows, uint32_t* __restrict__ krow,
+                                                uint32_t* __restrict__ vbag, EmbHeader* hdr) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  bool bad = false;
+  if (i < nnz) {
+    uint32_t bag = i;
+    if (offsets != nullptr) {  // the bag with offsets[bag] <= i < offsets[bag + 1]
+      uint32_t lo = 0, hi = n_bags - 1;
+      while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (offsets[mid + 1] <= (int64_t)i) lo = mid + 1; else hi = mid;
+      }
+      bag = lo;
+    }
+    int64_t row = -1;
+    if (rows64 != nullptr) {
+      const int64_t r = rows64[i];
+      if (r >= 0 && r < total_rows) row = r;
+    } else {
+      const int64_t k = keys[i];
+      const uint32_t s = bag % S;
+      if (k >= 0 && k < slots.num[s]) row = slots.base[s] + k;
+    }
+    bad = row < 0;
+    krow[i] = bad ? kNoRow : (uint32_t)row;
+    vbag[i] = bag;
+  }
+  count_invalid(&hdr->invalid, bad);
+}
+
+// Backward step 3: run boundaries of the sorted rows = the distinct rows of the batch.
+__global__ __launch_bounds__(256) void seg_flags(const uint32_t* __restrict__ srow, uint32_t n,
+                                                 uint32_t* __restrict__ flags) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i < n) {
+    const uint32_t r = srow[i];
+    flags[i] = (r != kNoRow && (i == 0 || srow[i - 1] != r)) ? 1u : 0u;
+  }
+}
+
+__global__ __launch_bounds__(256) void seg_compact(const uint32_t* __restrict__ srow, uint32_t n,
+                                                   const uint32_t* __restrict__ idx,
+                                                   uint32_t* __restrict__ uniq,
+                                                   uint32_t* __restrict__ seg_off, EmbHeader* hdr) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i >= n) return;
+  const uint32_t r = srow[i];
+  if (r == kNoRow) return;
+  const bool start = (i == 0) || (srow[i - 1] != r);
+  const uint32_t u = idx[i];
+  if (start) {
+    uniq[u] = r;
+    seg_off[u] = i;
+  }
+  if (i == n - 1 || srow[i + 1] == kNoRow) {  // last real row: closes the last segment
+    const uint32_t U = u + (start ? 1u : 0u);
+    seg_off[U] = i + 1;
+    hdr->n_valid = i + 1;
+    hdr->num_unique = (long long)U;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Backward steps 4+5.  The sorted occurrence list is cut into windows of W positions; a group of
+// LPR lanes (4 dY columns per lane) walks one window.  A row whose occurrences all lie inside the
+// window is reduced and updated on the spot.  A row that crosses window borders leaves one partial
+// sum per window ("head" if the row began in an earlier window, else "tail"), and the second kernel
+// adds a row's partials in window order and applies the update.  Order of additions is fixed by
+// the sorted positions, so results do not vary from run to run.
+// ------------------------------------------------------------------------------------------------
+template <typename T, int LPR>
+__global__ __launch_bounds__(256) void bwd_reduce_windows(
+    T* __restrict__ table, int D, const uint32_t* __restrict__ srow, const uint32_t* __restrict__ sbag,
+    const EmbHeader* __restrict__ hdr, const int64_t* __restrict__ offsets, int mean,
+    const float* __restrict__ dY, float lr, float* __restrict__ head, float* __restrict__ tail,
+    uint8_t* __restrict__ tail_flag, uint32_t W) {
+  const int sub = threadIdx.x % LPR;
+  const uint32_t win = (blockIdx.x * 256u + threadIdx.x) / LPR;
+  const int col = blockIdx.y * (LPR * 4) + sub * 4;
+  const bool active = col < D;
+  const uint32_t n_valid = hdr->n_valid;
+  const uint64_t start64 = (uint64_t)win * W;
+  if (start64 >= n_valid) return;
+  const uint32_t start = (uint32_t)start64;
+  const uint32_t end = (n_valid - start < W) ? n_valid : start + W;
+
+  uint32_t cur = srow[start];
+  bool before = start > 0 && srow[start - 1] == cur;
+  bool wrote_tail = false;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+
+  auto flush = [&](bool ended) {
+    if (!before && ended) {
+      if (active) sgd_update4(table + (int64_t)cur * D + col, acc, lr);
+    } else if (before) {
+      if (active) store4(head + (int64_t)win * D + col, acc);
+    } else {
+      if (active) store4(tail + (int64_t)win * D + col, acc);
+      wrote_tail = true;
+    }
+  };
+
+  for (uint32_t p0 = start; p0 < end; p0 += LPR) {
+    const int cnt = (end - p0 < (uint32_t)LPR) ? (int)(end - p0) : LPR;
+    uint32_t myrow = kNoRow, mybag = 0;
+    float myw = 1.f;
+    if (sub < cnt) {
+      myrow = srow[p0 + sub];
+      mybag = sbag[p0 + sub];
+      if (mean) myw = 1.0f / (float)(offsets[mybag + 1] - offsets[mybag]);
+    }
+    for (int q0 = 0; q0 < cnt; q0 += 4) {
+      uint32_t r[4];
+      float w[4];
+      f32x4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int q = (q0 + u < cnt) ? q0 + u : q0;  // clamp: duplicates are ignored below
+        r[u] = __shfl(myrow, q, LPR);
+        const uint32_t b = __shfl(mybag, q, LPR);
+        w[u] = __shfl(myw, q, LPR);
+        v[u] = active ? load4(dY + (int64_t)b * D + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (q0 + u < cnt) {
+          if (r[u] != cur) {
+            flush(true);
+            cur = r[u];
+            acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            before = false;
+          }
+          acc.x += w[u] * v[u].x; acc.y += w[u] * v[u].y;
+          acc.z += w[u] * v[u].z; acc.w += w[u] * v[u].w;
+        }
+      }
+    }
+  }
+  const bool continues = end < n_valid && srow[end] == cur;
+  flush(!continues);
+  if (sub == 0 && blockIdx.y == 0) tail_flag[win] = wrote_tail ? 1 : 0;
+}
+
+template <typename T, int LPR>
+__global__ __launch_bounds__(256) void bwd_reduce_carry(
+    T* __restrict__ table, int D, const uint32_t* __restrict__ srow,
+    const EmbHeader* __restrict__ hdr, float lr, const float* __restrict__ head,
+    const float* __restrict__ tail, const uint8_t* __restrict__ tail_flag, uint32_t W) {
+  const int sub = threadIdx.x % LPR;
+  const uint32_t win = (blockIdx.x * 256u + threadIdx.x) / LPR;
+  const int col = blockIdx.y * (LPR * 4) + sub * 4;
+  const bool active = col < D;
+  const uint32_t n_valid = hdr->n_valid;
+  const uint64_t start64 = (uint64_t)win * W;
+  if (start64 >= n_valid) return;
+  if (!tail_flag[win]) return;
+  // a tail exists only when the window is full and its last row continues into the next window
+  const uint32_t r = srow[(uint32_t)start64 + W - 1];
+  f32x4 acc = active ? load4(tail + (int64_t)win * D + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+  for (uint64_t w2 = (uint64_t)win + 1; w2 * W < n_valid && srow[w2 * W] == r; ++w2) {
+    if (active) {
+      const f32x4 h = load4(head + (int64_t)w2 * D + col);
+      acc.x += h.x; acc.y += h.y; acc.z += h.z; acc.w += h.w;
+    }
+  }
+  if (active) sgd_update4(table + (int64_t)r * D + col, acc, lr);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Host side
+// ------------------------------------------------------------------------------------------------
+struct EmbLayout {
+  // byte offsets into the workspace (all multiples of 256)
+  size_t header, krow0, vbag0, krow1, vbag1, hist, scan_tmp, flags, uniq, seg_off, head, tail,
+      tail_flag, rows64, hash_ws, total;
+  uint32_t window, n_windows;
+  int sort_bits;
+  SortPlan sort;
+};
+
+static uint32_t pick_window(int64_t nnz) { return nnz <= (8ll << 20) ? 32u : 128u; }
+
+static EmbLayout emb_layout(const hctr_emb_desc* d, int64_t nnz_max) {
+  EmbLayout L{};
+  const size_t n = (size_t)(nnz_max > 0 ? nnz_max : 1);
+  Carver c(nullptr);
+  auto at = [&](size_t bytes) { size_t o = c.off; c.take<char>(bytes); return o; };
+  L.sort_bits = ceil_log2((uint64_t)d->total_rows + 1);
+  L.sort = sort_plan((uint32_t)n, L.sort_bits);
+  L.window = pick_window(nnz_max);
+  L.n_windows = (uint32_t)ceil_div((int64_t)n, L.window);
+  L.header = at(sizeof(EmbHeader));
+  L.krow0 = at(n * 4); L.vbag0 = at(n * 4); L.krow1 = at(n * 4); L.vbag1 = at(n * 4);
+  L.hist = at((size_t)L.sort.hist_count * 4);
+  size_t scan_n = L.sort.hist_count > n ? L.sort.hist_count : n;
+  L.scan_tmp = at(scan_tmp_count((uint32_t)scan_n) * 4);
+  L.flags = at(n * 4);
+  L.uniq = at(n * 4);
+  L.seg_off = at((n + 1) * 4);
+  L.head = at((size_t)L.n_windows * d->dim * 4);
+  L.tail = at((size_t)L.n_windows * d->dim * 4);
+  L.tail_flag = at(L.n_windows);
+  if (d->hash) {
+    L.rows64 = at(n * 8);
+    L.hash_ws = at(hash_ws_bytes((int64_t)n));
+  }
+  L.total = c.off;
+  return L;
+}
+
+static hctr_status validate_desc(const hctr_emb_desc* d) {
+  if (!d) return fail(HCTR_E_NULL_PTR, "desc is NULL");
+  if (d->num_slots < 1 || d->num_slots > HCTR_MAX_SLOTS)
+    return fail(HCTR_E_INVALID_ARG, "num_slots %d outside 1..%d", d->num_slots, HCTR_MAX_SLOTS);
+  if (d->table_dtype != HCTR_F32 && d->table_dtype != HCTR_F16)
+    return fail(HCTR_E_INVALID_ARG, "table_dtype %d unknown", d->table_dtype);
+  const int mult = d->table_dtype == HCTR_F32 ? 4 : 8;
+  if (d->dim <= 0 || d->dim % mult != 0)
+    return fail(HCTR_E_INVALID_ARG, "dim %d must be a positive multiple of %d", d->dim, mult);
+  if (d->combiner != HCTR_SUM && d->combiner != HCTR_MEAN)
+    return fail(HCTR_E_INVALID_ARG, "combiner %d unknown", d->combiner);
+  if (!d->table) return fail(HCTR_E_NULL_PTR, "table is NULL");
+  if ((uintptr_t)d->table % 16 != 0) return fail(HCTR_E_INVALID_ARG, "table must be 16-byte aligned");
+  if (d->total_rows < 1 || d->total_rows > 0xFFFFFFFEll)
+    return fail(HCTR_E_UNSUPPORTED, "total_rows %lld outside 1..2^32-2", (long long)d->total_rows);
+  if (d->hash) {
+    if (d->total_rows < d->hash->max_rows)
+      return fail(HCTR_E_INVALID_ARG, "table has %lld rows, the hash can hand out %lld",
+                  (long long)d->total_rows, (long long)d->hash->max_rows);
+  } else {
+    if (!d->slot_row_base || !d->slot_num_rows)
+      return fail(HCTR_E_NULL_PTR, "slot_row_base / slot_num_rows is NULL in direct mode");
+    for (int s = 0; s < d->num_slots; ++s) {
+      if (d->slot_row_base[s] < 0 || d->slot_num_rows[s] < 0 ||
+          d->slot_row_base[s] + d->slot_num_rows[s] > d->total_rows)
+        return fail(HCTR_E_INVALID_ARG, "slot %d rows [%lld, +%lld) leave the table of %lld rows", s,
+                    (long long)d->slot_row_base[s], (long long)d->slot_num_rows[s],
+                    (long long)d->total_rows);
+    }
+  }
+  return HCTR_OK;
+}
+
+static hctr_status validate_batch(const hctr_emb_desc* d, int64_t batch, const int64_t* keys,
+                                  const int64_t* offsets, int64_t nnz, const void* io, void* ws,
+                                  size_t ws_bytes, EmbLayout* L) {
+  HCTR_TRY(validate_desc(d));
+  if (batch < 0 || nnz < 0) return fail(HCTR_E_INVALID_ARG, "batch %lld / nnz %lld negative",
+                                        (long long)batch, (long long)nnz);
+  const int64_t n_bags = batch * d->num_slots;
+  if (n_bags >= (1ll << 31) || nnz >= (1ll << 31))
+    return fail(HCTR_E_UNSUPPORTED, "more than 2^31-1 bags or keys in one call");
+  if (!offsets && nnz != n_bags)
+    return fail(HCTR_E_INVALID_ARG, "offsets == NULL needs nnz == batch*num_slots (%lld != %lld)",
+                (long long)nnz, (long long)n_bags);
+  if (batch == 0 && nnz != 0) return fail(HCTR_E_INVALID_ARG, "nnz must be 0 when batch is 0");
+  if (nnz > 0 && !keys) return fail(HCTR_E_NULL_PTR, "keys is NULL");
+  if (n_bags > 0 && !io) return fail(HCTR_E_NULL_PTR, "out / dY is NULL");
+  if (io && (uintptr_t)io % 16 != 0) return fail(HCTR_E_INVALID_ARG, "out / dY must be 16-byte aligned");
+  *L = emb_layout(d, nnz);
+  if (!ws) return fail(HCTR_E_WORKSPACE, "workspace is NULL");
+  if ((uintptr_t)ws % 256 != 0) return fail(HCTR_E_WORKSPACE, "workspace must be 256-byte aligned");
+  if (ws_bytes < L->total)
+    return fail(HCTR_E_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, L->total);
+  return HCTR_OK;
+}
+
+static void fill_slots(const hctr_emb_desc* d, SlotTable* st) {
+  for (int s = 0; s < HCTR_MAX_SLOTS; ++s) {
+    st->base[s] = (!d->hash && s < d->num_slots) ? d->slot_row_base[s] : 0;
+    st->num[s] = (!d->hash && s < d->num_slots) ? d->slot_num_rows[s] : 0;
+  }
+}
+
+template <typename T>
+static int lanes_per_row(int dim) {
+  int l = pow2_ceil((int)ceil_div((int64_t)dim * (int64_t)sizeof(T), 16));
+  return l < 4 ? 4 : (l > 64 ? 64 : l);
+}
+
+template <typename T, int LPR>
+static void launch_forward(const hctr_emb_desc* d, const int64_t* keys, const int64_t* rows64,
+                           const int64_t* offsets, uint32_t n_bags, const SlotTable& st, float* out,
+                           EmbHeader* hdr, hipStream_t stream) {
+  constexpr int VEC = RowVec<T>::VEC;
+  const uint32_t ychunks = (uint32_t)ceil_div(d->dim, LPR * VEC);
+  const T* table = static_cast<const T*>(d->table);
+  if (!offsets) {
+    constexpr int U = 4;
+    const uint32_t bags_per_block = (256 / LPR) * U;
+    dim3 grid((uint32_t)ceil_div(n_bags, bags_per_block), ychunks);
+    if (rows64)
+      hipLaunchKernelGGL((fwd_onehot<T, LPR, U, true>), grid, dim3(256), 0, stream, table, d->dim,
+                         d->total_rows, keys, rows64, n_bags, (uint32_t)d->num_slots, st, out, hdr);
+    else
+      hipLaunchKernelGGL((fwd_onehot<T, LPR, U, false>), grid, dim3(256), 0, stream, table, d->dim,
+                         d->total_rows, keys, rows64, n_bags, (uint32_t)d->num_slots, st, out, hdr);
+  } else {
+    constexpr int U = 4;
+    dim3 grid((uint32_t)ceil_div(n_bags, 4), ychunks);
+    const int mean = d->combiner == HCTR_MEAN;
+    if (rows64)
+      hipLaunchKernelGGL((fwd_csr<T, LPR, U, true>), grid, dim3(256), 0, stream, table, d->dim,
+                         d->total_rows, keys, rows64, offsets, n_bags, (uint32_t)d->num_slots, st, mean,
+                         out, hdr);
+    else
+      hipLaunchKernelGGL((fwd_csr<T, LPR, U, false>), grid, dim3(256), 0, stream, table, d->dim,
+                         d->total_rows, keys, rows64, offsets, n_bags, (uint32_t)d->num_slots, st, mean,
+                         out, hdr);
+  }
+}
+
+template <typename T>
+static void dispatch_forward(int lpr, const hctr_emb_desc* d, const int64_t* keys,
+                             const int64_t* rows64, const int64_t* offsets, uint32_t n_bags,
+                             const SlotTable& st, float* out, EmbHeader* hdr, hipStream_t stream) {
+  switch (lpr) {
+    case 4: launch_forward<T, 4>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
+    case 8: launch_forward<T, 8>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
+    case 16: launch_forward<T, 16>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
+    case 32: launch_forward<T, 32>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
+    default: launch_forward<T, 64>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
+  }
+}
+
+template <typename T, int LPR>
+static void launch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, const uint32_t* srow,
+                          const uint32_t* sbag, const int64_t* offsets, const float* dY, float lr,
+                          hipStream_t stream) {
+  const uint32_t ychunks = (uint32_t)ceil_div(d->dim, LPR * 4);
+  dim3 grid((uint32_t)ceil_div(L.n_windows, 256 / LPR), ychunks);
+  T* table = static_cast<T*>(d->table);
+  EmbHeader* hdr = reinterpret_cast<EmbHeader*>(ws + L.header);
+  float* head = reinterpret_cast<float*>(ws + L.head);
+  float* tail = reinterpret_cast<float*>(ws + L.tail);
+  uint8_t* tflag = reinterpret_cast<uint8_t*>(ws + L.tail_flag);
+  const int mean = (d->combiner == HCTR_MEAN && offsets != nullptr) ? 1 : 0;
+  hipLaunchKernelGGL((bwd_reduce_windows<T, LPR>), grid, dim3(256), 0, stream, table, d->dim, srow,
+                     sbag, (const EmbHeader*)hdr, offsets, mean, dY, lr, head, tail, tflag, L.window);
+  hipLaunchKernelGGL((bwd_reduce_carry<T, LPR>), grid, dim3(256), 0, stream, table, d->dim, srow,
+                     (const EmbHeader*)hdr, lr, (const float*)head, (const float*)tail,
+                     (const uint8_t*)tflag, L.window);
+}
+
+template <typename T>
+static void dispatch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, const uint32_t* srow,
+                            const uint32_t* sbag, const int64_t* offsets, const float* dY, float lr,
+                            hipStream_t stream) {
+  int lpr = pow2_ceil((int)ceil_div(d->dim, 4));
+  lpr = lpr < 4 ? 4 : (lpr > 64 ? 64 : lpr);
+  switch (lpr) {
+    case 4: launch_reduce<T, 4>(d, L, ws, srow, sbag, offsets, dY, lr, stream); break;
+    case 8: launch_reduce<T, 8>(d, L, ws, srow, sbag, offsets, dY, lr, stream); break;
+    case 16: launch_reduce<T, 16>(d, L, ws, srow, sbag, offsets, dY, lr, stream); break;
+    case 32: launch_reduce<T, 32>(d, L, ws, srow, sbag, offsets, dY, lr, stream); break;
+    default: launch_reduce<T, 64>(d, L, ws, srow, sbag, offsets, dY, lr, stream); break;
+  }
+}
+
+}  // namespace hctr
+
+using namespace hctr;
+
+HCTR_API size_t hctr_emb_workspace_bytes(const hctr_emb_desc* desc, int64_t batch, int64_t nnz_max) {
+  (void)batch;
+  if (!desc || desc->dim <= 0 || desc->total_rows < 1 || nnz_max < 0 || nnz_max >= (1ll << 31)) return 0;
+  return emb_layout(desc, nnz_max).total;
+}
+
+HCTR_API hctr_status hctr_emb_forward(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
+                                      const int64_t* offsets, int64_t nnz, float* out, void* ws,
+                                      size_t ws_bytes, void* stream_) {
+  EmbLayout L;
+  HCTR_TRY(validate_batch(desc, batch, keys, offsets, nnz, out, ws, ws_bytes, &L));
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  char* w = static_cast<char*>(ws);
+  EmbHeader* hdr = reinterpret_cast<EmbHeader*>(w + L.header);
+  hipLaunchKernelGGL(emb_init_header, dim3(1), dim3(64), 0, stream, hdr, (uint32_t*)nullptr);
+  const int64_t n_bags = batch * desc->num_slots;
+  if (n_bags == 0) return launch_status("emb_init_header");
+  const int64_t* rows64 = nullptr;
+  if (desc->hash) {
+    int64_t* r = reinterpret_cast<int64_t*>(w + L.rows64);
+    HCTR_TRY(hash_lookup(desc->hash, keys, nnz, desc->insert_on_miss, r, w + L.hash_ws,
+                         L.total - L.hash_ws, stream));
+    rows64 = r;
+  }
+  SlotTable st;
+  fill_slots(desc, &st);
+  if (desc->table_dtype == HCTR_F32)
+    dispatch_forward<float>(lanes_per_row<float>(desc->dim), desc, keys, rows64, offsets,
+                            (uint32_t)n_bags, st, out, hdr, stream);
+  else
+    dispatch_forward<__half>(lanes_per_row<__half>(desc->dim), desc, keys, rows64, offsets,
+                             (uint32_t)n_bags, st, out, hdr, stream);
+  return launch_status("hctr_emb_forward");
+}
+
+HCTR_API hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
+                                           const int64_t* offsets, int64_t nnz, const float* dY, float lr,
+                                           void* ws, size_t ws_bytes, void* stream_) {
+  EmbLayout L;
+  HCTR_TRY(validate_batch(desc, batch, keys, offsets, nnz, dY, ws, ws_bytes, &L));
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  char* w = static_cast<char*>(ws);
+  EmbHeader* hdr = reinterpret_cast<EmbHeader*>(w + L.header);
+  uint32_t* seg_off = reinterpret_cast<uint32_t*>(w + L.seg_off);
+  hipLaunchKernelGGL(emb_init_header, dim3(1), dim3(64), 0, stream, hdr, seg_off);
+  if (nnz == 0) return launch_status("emb_init_header");
+  const uint32_t n = (uint32_t)nnz;
+  const uint32_t n_bags = (uint32_t)(batch * desc->num_slots);
+  const int64_t* rows64 = nullptr;
+  if (desc->hash) {
+    int64_t* r = reinterpret_cast<int64_t*>(w + L.rows64);
+    HCTR_TRY(hash_lookup(desc->hash, keys, nnz, 0, r, w + L.hash_ws, L.total - L.hash_ws, stream));
+    rows64 = r;
+  }
+  SlotTable st;
+  fill_slots(desc, &st);
+  uint32_t* k[2] = {reinterpret_cast<uint32_t*>(w + L.krow0), reinterpret_cast<uint32_t*>(w + L.krow1)};
+  uint32_t* v[2] = {reinterpret_cast<uint32_t*>(w + L.vbag0), reinterpret_cast<uint32_t*>(w + L.vbag1)};
+  uint32_t* hist = reinterpret_cast<uint32_t*>(w + L.hist);
+  uint32_t* scan_tmp = reinterpret_cast<uint32_t*>(w + L.scan_tmp);
+  uint32_t* flags = reinterpret_cast<uint32_t*>(w + L.flags);
+  uint32_t* uniq = reinterpret_cast<uint32_t*>(w + L.uniq);
+  const uint32_t nb = (uint32_t)ceil_div(n, 256);
+
+  hipLaunchKernelGGL(bwd_rows, dim3(nb), dim3(256), 0, stream, keys, rows64, offsets, n, n_bags,
+                     (uint32_t)desc->num_slots, st, desc->total_rows, k[0], v[0], hdr);
+  HCTR_TRY(radix_sort_pairs(L.sort, L.sort_bits, nullptr, k[0], v[0], k[1], v[1], hist, scan_tmp, stream));
+  const uint32_t* srow = k[L.sort.passes & 1];
+  const uint32_t* sbag = v[L.sort.passes & 1];
+  hipLaunchKernelGGL(seg_flags, dim3(nb), dim3(256), 0, stream, srow, n, flags);
+  HCTR_TRY(exclusive_scan_u32(flags, flags, n, scan_tmp, nullptr, stream));
+  hipLaunchKernelGGL(seg_compact, dim3(nb), dim3(256), 0, stream, srow, n, (const uint32_t*)flags, uniq,
+                     seg_off, hdr);
+  if (desc->table_dtype == HCTR_F32)
+    dispatch_reduce<float>(desc, L, w, srow, sbag, offsets, dY, lr, stream);
+  else
+    dispatch_reduce<__half>(desc, L, w, srow, sbag, offsets, dY, lr, stream);
+  return launch_status("hctr_emb_backward_sgd");
+}
+
+HCTR_API hctr_status hctr_emb_dedup_view(const hctr_emb_desc* desc, int64_t batch, int64_t nnz,
+                                         void* ws, size_t ws_bytes, const int64_t** num_unique,
+                                         const uint32_t** uniq_rows, const uint32_t** seg_offsets) {
+  (void)batch;
+  HCTR_TRY(validate_desc(desc));
+  if (!ws || !num_unique || !uniq_rows || !seg_offsets) return fail(HCTR_E_NULL_PTR, "NULL argument");
+  if (nnz < 0 || nnz >= (1ll << 31)) return fail(HCTR_E_INVALID_ARG, "nnz out of range");
+  const EmbLayout L = emb_layout(desc, nnz);
+  if (ws_bytes < L.total) return fail(HCTR_E_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, L.total);
+  char* w = static_cast<char*>(ws);
+  *num_unique = reinterpret_cast<const int64_t*>(w + L.header + offsetof(EmbHeader, num_unique));
+  *uniq_rows = reinterpret_cast<const uint32_t*>(w + L.uniq);
+  *seg_offsets = reinterpret_cast<const uint32_t*>(w + L.seg_off);
+  return HCTR_OK;
+}
+
+HCTR_API hctr_status hctr_emb_invalid_keys(const void* ws, size_t ws_bytes, void* stream, int64_t* count) {
+  if (!ws || !count) return fail(HCTR_E_NULL_PTR, "NULL argument");
+  if (ws_bytes < sizeof(EmbHeader)) return fail(HCTR_E_WORKSPACE, "workspace too small");
+  unsigned long long v = 0;
+  HCTR_TRY_HIP(hipMemcpyAsync(&v, ws, sizeof(v), hipMemcpyDeviceToHost, static_cast<hipStream_t>(stream)));
+  HCTR_TRY_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  *count = (int64_t)v;
+  return HCTR_OK;
+}

@@ -1,0 +1,358 @@
+// Embedding hash: open addressing over 128-byte buckets of eight {key, row} slots, probed by
+// groups of eight lanes (one 16-byte slot per lane, one bucket per group per step, eight keys per
+// wave in flight).  Linear probing over buckets; nothing is ever deleted, so an empty slot in a
+// bucket ends a search.
+//
+// Insert-or-find keeps the table's contract "rows are handed out in order of first appearance in
+// the call's key array" without any sequential step:
+//   1. find every key; flag the misses and compact their positions (scan);
+//   2. put the missed keys into a scratch table sized for this call, keeping per key the smallest
+//      position (atomicMin) = its first appearance;
+//   3. flag the first appearances, scan them: rank = how many new keys appear earlier;
+//   4. row = size + rank; keys whose row stays below max_rows claim a slot of the main table with a
+//      64-bit compare-and-swap and publish the row, the others are rejected;
+//   5. every missed position reads its key's verdict back from the scratch table.
+// The main table only ever holds published keys, so a later search never meets a half-made entry.
+#include "hash_internal.h"
+
+namespace hctr {
+
+typedef unsigned long long u64;
+typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+
+struct HashHeader {      // first 256 bytes of the hash storage
+  u64 size;
+  u64 pad[31];
+};
+
+__device__ __forceinline__ u64 mix_key(u64 x) {
+  x ^= x >> 33;
+  x *= 0xD6E8FEB86659FD93ull;
+  x ^= x >> 29;
+  x *= 0xA24BAED4963EE407ull;
+  x ^= x >> 32;
+  return x;
+}
+__device__ __forceinline__ uint32_t bucket_of(u64 key, uint32_t n_buckets) {
+  return (uint32_t)(((mix_key(key) >> 32) * (u64)n_buckets) >> 32);
+}
+__device__ __forceinline__ uint32_t scratch_capacity(uint32_t n_miss) {  // power of two >= 2 * n_miss
+  uint32_t want = n_miss < 32u ? 64u : 2u * n_miss;
+  return 1u << (32 - __clz(want - 1u));
+}
+__device__ __forceinline__ uint32_t group_bits(uint64_t ballot) {  // this 8-lane group's votes
+  return (uint32_t)(ballot >> (threadIdx.x & 56)) & 0xFFu;
+}
+
+__global__ __launch_bounds__(256) void hash_clear(u64x2* slots, uint64_t n_slots, HashHeader* hdr) {
+  const uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+  if (i < n_slots) slots[i] = u64x2{kEmptyKey, kEmptyKey};
+  if (i == 0) hdr->size = 0;
+}
+
+// One key per 8-lane group.
+__global__ __launch_bounds__(256) void hash_find(const u64x2* __restrict__ slots, uint32_t n_buckets,
+                                                 const int64_t* __restrict__ keys, uint32_t n,
+                                                 int64_t* __restrict__ rows,
+                                                 uint32_t* __restrict__ miss_flag) {
+  const uint32_t i = (blockIdx.x * 256u + threadIdx.x) >> 3;
+  const int sub = threadIdx.x & 7;
+  const int64_t key = i < n ? keys[i] : -1;
+  bool searching = key >= 0;
+  int64_t row = -1;
+  uint32_t b = searching ? bucket_of((u64)key, n_buckets) : 0u;
+  for (uint32_t step = 0; step < n_buckets; ++step) {
+    if (__ballot(searching) == 0) break;
+    u64x2 s = u64x2{kEmptyKey, kEmptyKey};
+    if (searching) s = slots[(uint64_t)b * 8u + sub];
+    const uint32_t hit = group_bits(__ballot(searching && s.x == (u64)key));
+    const uint32_t hole = group_bits(__ballot(searching && s.x == kEmptyKey));
+    if (searching) {
+      if (hit) {
+        const int src = (threadIdx.x & 56) + (__ffs(hit) - 1);
+        row = (int64_t)__shfl((long long)s.y, src);
+        searching = false;
+      } else if (hole) {
+        searching = false;
+      } else {
+        b = (b + 1 == n_buckets) ? 0u : b + 1;
+      }
+    }
+  }
+  if (i < n && sub == 0) {
+    rows[i] = row;
+    if (miss_flag) miss_flag[i] = (key >= 0 && row < 0) ? 1u : 0u;
+  }
+}
+
+__global__ __launch_bounds__(256) void hash_compact_misses(const uint32_t* __restrict__ flag,
+                                                           const uint32_t* __restrict__ idx, uint32_t n,
+                                                           uint32_t* __restrict__ miss_pos) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i < n && flag[i]) miss_pos[idx[i]] = i;
+}
+
+__global__ __launch_bounds__(256) void scratch_clear(u64x2* scratch, const HashWsHeader* hdr) {
+  const uint32_t cap = scratch_capacity(hdr->n_miss);
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (hdr->n_miss != 0 && i < cap) scratch[i] = u64x2{kEmptyKey, kEmptyKey};
+}
+
+// One missed key per lane: claim or join the key's scratch slot, keep the smallest position.
+__global__ __launch_bounds__(256) void scratch_insert(u64* scratch /* {key, val} pairs */,
+                                                      const HashWsHeader* hdr,
+                                                      const int64_t* __restrict__ keys,
+                                                      const uint32_t* __restrict__ miss_pos,
+                                                      uint32_t* __restrict__ scr_slot) {
+  const uint32_t m = blockIdx.x * 256u + threadIdx.x;
+  const uint32_t n_miss = hdr->n_miss;
+  if (m >= n_miss) return;
+  const uint32_t cap = scratch_capacity(n_miss);
+  const uint32_t pos = miss_pos[m];
+  const u64 key = (u64)keys[pos];
+  uint32_t s = (uint32_t)(mix_key(key ^ 0x5851F42D4C957F2Dull) >> 16) & (cap - 1);
+  for (uint32_t step = 0; step < cap; ++step) {
+    const u64 old = atomicCAS(&scratch[2ull * s], kEmptyKey, key);
+    if (old == kEmptyKey || old == key) {
+      atomicMin(&scratch[2ull * s + 1], (u64)pos);
+      scr_slot[m] = s;
+      return;
+    }
+    s = (s + 1) & (cap - 1);
+  }
+  scr_slot[m] = 0xFFFFFFFFu;  // cannot happen: at most cap/2 distinct keys
+}
+
+__global__ __launch_bounds__(256) void first_flags(const u64* __restrict__ scratch,
+                                                   const HashWsHeader* hdr,
+                                                   const uint32_t* __restrict__ miss_pos,
+                                                   const uint32_t* __restrict__ scr_slot, uint32_t n,
+                                                   uint32_t* __restrict__ first) {
+  const uint32_t m = blockIdx.x * 256u + threadIdx.x;
+  if (m >= n) return;
+  uint32_t f = 0;
+  if (m < hdr->n_miss) {
+    const uint32_t s = scr_slot[m];
+    f = (s != 0xFFFFFFFFu && scratch[2ull * s + 1] == (u64)miss_pos[m]) ? 1u : 0u;
+  }
+  first[m] = f;
+}
+
+// One new key per 8-lane group: assign the row, claim a slot in the main table, publish.
+__global__ __launch_bounds__(256) void hash_insert_new(u64* slots /* {key,row} pairs */,
+                                                       uint32_t n_buckets, const HashHeader* table_hdr,
+                                                       int64_t max_rows, u64* scratch,
+                                                       const HashWsHeader* hdr,
+                                                       const int64_t* __restrict__ keys,
+                                                       const uint32_t* __restrict__ miss_pos,
+                                                       const uint32_t* __restrict__ scr_slot,
+                                                       const uint32_t* __restrict__ first,
+                                                       const uint32_t* __restrict__ rank) {
+  const uint32_t m = (blockIdx.x * 256u + threadIdx.x) >> 3;
+  const int sub = threadIdx.x & 7;
+  const bool mine = m < hdr->n_miss && first[m] != 0;
+  u64 key = 0;
+  int64_t row = -1;
+  bool placing = false;
+  if (mine) {
+    key = (u64)keys[miss_pos[m]];
+    row = (int64_t)table_hdr->size + (int64_t)rank[m];
+    placing = row < max_rows;
+    if (!placing) row = -1;
+  }
+  uint32_t b = placing ? bucket_of(key, n_buckets) : 0u;
+  u64 seen = 0;        // this lane's view of its slot's key in the current bucket
+  bool fresh = true;   // view must be (re)loaded
+  for (uint64_t step = 0; step < 9ull * n_buckets; ++step) {
+    if (__ballot(placing) == 0) break;
+    if (placing && fresh) { seen = slots[2ull * ((uint64_t)b * 8u + sub)]; fresh = false; }
+    const uint32_t hole = group_bits(__ballot(placing && seen == kEmptyKey));
+    if (placing) {
+      if (hole) {
+        const int pick = __ffs(hole) - 1;
+        bool won = false;
+        if (sub == pick) {
+          u64* slot = &slots[2ull * ((uint64_t)b * 8u + sub)];
+          const u64 old = atomicCAS(slot, kEmptyKey, key);
+          if (old == kEmptyKey) { slot[1] = (u64)row; won = true; }
+          else seen = old;  // somebody else took it: remember, try the next hole
+        }
+        if (group_bits(__ballot(won))) placing = false;
+      } else {
+        b = (b + 1 == n_buckets) ? 0u : b + 1;
+        fresh = true;
+      }
+    }
+  }
+  if (mine && sub == 0) scratch[2ull * scr_slot[m] + 1] = (u64)row;  // verdict: row or -1 (all ones)
+}
+
+__global__ __launch_bounds__(256) void hash_resolve(const u64* __restrict__ scratch, HashWsHeader* hdr,
+                                                    HashHeader* table_hdr, int64_t max_rows,
+                                                    const uint32_t* __restrict__ miss_pos,
+                                                    const uint32_t* __restrict__ scr_slot,
+                                                    int64_t* __restrict__ rows) {
+  const uint32_t m = blockIdx.x * 256u + threadIdx.x;
+  if (m < hdr->n_miss) {
+    const uint32_t s = scr_slot[m];
+    rows[miss_pos[m]] = s != 0xFFFFFFFFu ? (int64_t)scratch[2ull * s + 1] : -1;
+  }
+  if (m == 0) {
+    const u64 grown = table_hdr->size + hdr->n_new;
+    table_hdr->size = grown < (u64)max_rows ? grown : (u64)max_rows;
+  }
+}
+
+
+// Steps 1b-3 above, shared with the cache's insertion path: from per-position miss flags to, per
+// missed position m (in position order), the scratch slot of its key, whether it is the key's first
+// appearance, and the rank of that first appearance among all first appearances.
+hctr_status dedup_first_appearance(const int64_t* keys, uint32_t n, const DedupBuffers& B,
+                                   hipStream_t stream) {
+  const uint32_t nb = (uint32_t)ceil_div(n, 256);
+  const HashWsHeader* hdr = reinterpret_cast<const HashWsHeader*>(B.n_miss);
+  HCTR_TRY(exclusive_scan_u32(B.flag, B.idx, n, B.scan_tmp, B.n_miss, stream));
+  hipLaunchKernelGGL(hash_compact_misses, dim3(nb), dim3(256), 0, stream, (const uint32_t*)B.flag,
+                     (const uint32_t*)B.idx, n, B.miss_pos);
+  hipLaunchKernelGGL(scratch_clear, dim3((uint32_t)ceil_div(B.scratch_cap_max, 256)), dim3(256), 0, stream,
+                     reinterpret_cast<u64x2*>(B.scratch), hdr);
+  hipLaunchKernelGGL(scratch_insert, dim3(nb), dim3(256), 0, stream, B.scratch, hdr, keys,
+                     (const uint32_t*)B.miss_pos, B.scr_slot);
+  hipLaunchKernelGGL(first_flags, dim3(nb), dim3(256), 0, stream, (const u64*)B.scratch, hdr,
+                     (const uint32_t*)B.miss_pos, (const uint32_t*)B.scr_slot, n, B.first);
+  HCTR_TRY(exclusive_scan_u32(B.first, B.rank, n, B.scan_tmp, B.n_new, stream));
+  return launch_status("dedup_first_appearance");
+}
+
+uint32_t dedup_scratch_capacity(uint32_t n_max) {
+  uint64_t cap = 64;
+  while (cap < 2ull * (n_max > 0 ? n_max : 1)) cap <<= 1;
+  return (uint32_t)cap;
+}
+
+struct HashWsLayout {
+  size_t header, flag, idx, miss_pos, scr_slot, first, rank, scan_tmp, scratch, total;
+  uint32_t scratch_cap_max;
+};
+
+static HashWsLayout hash_ws_layout(int64_t n_max) {
+  HashWsLayout L{};
+  const size_t n = (size_t)(n_max > 0 ? n_max : 1);
+  Carver c(nullptr);
+  auto at = [&](size_t bytes) { size_t o = c.off; c.take<char>(bytes); return o; };
+  L.header = at(sizeof(HashWsHeader));
+  L.flag = at(n * 4); L.idx = at(n * 4); L.miss_pos = at(n * 4); L.scr_slot = at(n * 4);
+  L.first = at(n * 4); L.rank = at(n * 4);
+  L.scan_tmp = at(scan_tmp_count((uint32_t)n) * 4);
+  L.scratch_cap_max = dedup_scratch_capacity((uint32_t)n);
+  L.scratch = at((size_t)L.scratch_cap_max * 16);
+  L.total = c.off;
+  return L;
+}
+
+size_t hash_ws_bytes(int64_t n_max) { return hash_ws_layout(n_max).total; }
+
+hctr_status hash_lookup(hctr_hash* h, const int64_t* keys, int64_t n64, int insert, int64_t* rows,
+                        void* ws, size_t ws_bytes, hipStream_t stream) {
+  if (n64 == 0) return HCTR_OK;
+  const uint32_t n = (uint32_t)n64;
+  const u64x2* slots = reinterpret_cast<const u64x2*>(h->slots);
+  const uint32_t find_blocks = (uint32_t)ceil_div((int64_t)n * 8, 256);
+  if (!insert) {
+    hipLaunchKernelGGL(hash_find, dim3(find_blocks), dim3(256), 0, stream, slots, h->n_buckets, keys, n,
+                       rows, (uint32_t*)nullptr);
+    return launch_status("hash_find");
+  }
+  const HashWsLayout L = hash_ws_layout(n64);
+  if (!ws) return fail(HCTR_E_WORKSPACE, "workspace is NULL");
+  if ((uintptr_t)ws % 256 != 0) return fail(HCTR_E_WORKSPACE, "workspace must be 256-byte aligned");
+  if (ws_bytes < L.total) return fail(HCTR_E_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, L.total);
+  char* w = static_cast<char*>(ws);
+  HashWsHeader* hdr = reinterpret_cast<HashWsHeader*>(w + L.header);
+  HashHeader* thdr = reinterpret_cast<HashHeader*>(reinterpret_cast<char*>(h->slots) - sizeof(HashHeader));
+  uint32_t* flag = reinterpret_cast<uint32_t*>(w + L.flag);
+  uint32_t* idx = reinterpret_cast<uint32_t*>(w + L.idx);
+  uint32_t* miss_pos = reinterpret_cast<uint32_t*>(w + L.miss_pos);
+  uint32_t* scr_slot = reinterpret_cast<uint32_t*>(w + L.scr_slot);
+  uint32_t* first = reinterpret_cast<uint32_t*>(w + L.first);
+  uint32_t* rank = reinterpret_cast<uint32_t*>(w + L.rank);
+  uint32_t* scan_tmp = reinterpret_cast<uint32_t*>(w + L.scan_tmp);
+  u64* scratch = reinterpret_cast<u64*>(w + L.scratch);
+  const uint32_t nb = (uint32_t)ceil_div(n, 256);
+
+  hipLaunchKernelGGL(hash_find, dim3(find_blocks), dim3(256), 0, stream, slots, h->n_buckets, keys, n, rows, flag);
+  DedupBuffers B{flag, idx, miss_pos, scr_slot, first, rank, scan_tmp, scratch, L.scratch_cap_max,
+                 &hdr->n_miss, &hdr->n_new};
+  HCTR_TRY(dedup_first_appearance(keys, n, B, stream));
+  hipLaunchKernelGGL(hash_insert_new, dim3(find_blocks), dim3(256), 0, stream, h->slots, h->n_buckets,
+                     (const HashHeader*)thdr, h->max_rows, scratch, (const HashWsHeader*)hdr, keys,
+                     (const uint32_t*)miss_pos, (const uint32_t*)scr_slot, (const uint32_t*)first,
+                     (const uint32_t*)rank);
+  hipLaunchKernelGGL(hash_resolve, dim3(nb), dim3(256), 0, stream, (const u64*)scratch, hdr, thdr,
+                     h->max_rows, (const uint32_t*)miss_pos, (const uint32_t*)scr_slot, rows);
+  return launch_status("hash_lookup");
+}
+
+}  // namespace hctr
+
+using namespace hctr;
+
+static uint32_t buckets_for(int64_t capacity) { return (uint32_t)ceil_div(capacity, 8); }
+
+HCTR_API size_t hctr_hash_storage_bytes(int64_t capacity) {
+  if (capacity < 64 || capacity > (1ll << 34)) return 0;
+  return sizeof(HashHeader) + (size_t)buckets_for(capacity) * 128;
+}
+
+HCTR_API hctr_status hctr_hash_create(void* storage, size_t storage_bytes, int64_t capacity,
+                                      int64_t max_rows, void* stream, hctr_hash** out) {
+  if (!out) return fail(HCTR_E_NULL_PTR, "out is NULL");
+  *out = nullptr;
+  if (!storage) return fail(HCTR_E_NULL_PTR, "storage is NULL");
+  if (capacity < 64 || capacity > (1ll << 34)) return fail(HCTR_E_INVALID_ARG, "capacity %lld outside 64..2^34", (long long)capacity);
+  if (max_rows < 1 || (double)max_rows > 0.8 * (double)capacity)
+    return fail(HCTR_E_INVALID_ARG, "max_rows %lld outside 1..0.8*capacity", (long long)max_rows);
+  if ((uintptr_t)storage % 256 != 0) return fail(HCTR_E_INVALID_ARG, "storage must be 256-byte aligned");
+  if (storage_bytes < hctr_hash_storage_bytes(capacity))
+    return fail(HCTR_E_INVALID_ARG, "storage has %zu bytes, %zu needed", storage_bytes, hctr_hash_storage_bytes(capacity));
+  hctr_hash* h = new hctr_hash();
+  h->n_buckets = buckets_for(capacity);
+  h->capacity = capacity;
+  h->max_rows = max_rows;
+  h->size = reinterpret_cast<unsigned long long*>(storage);
+  h->slots = reinterpret_cast<unsigned long long*>(static_cast<char*>(storage) + sizeof(HashHeader));
+  const uint64_t n_slots = (uint64_t)h->n_buckets * 8;
+  hipLaunchKernelGGL(hash_clear, dim3((uint32_t)ceil_div((int64_t)n_slots, 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), reinterpret_cast<u64x2*>(h->slots), n_slots,
+                     reinterpret_cast<HashHeader*>(storage));
+  hctr_status st = launch_status("hash_clear");
+  if (st != HCTR_OK) { delete h; return st; }
+  *out = h;
+  return HCTR_OK;
+}
+
+HCTR_API size_t hctr_hash_workspace_bytes(int64_t n_max) {
+  if (n_max < 0 || n_max >= (1ll << 31)) return 0;
+  return hash_ws_bytes(n_max);
+}
+
+HCTR_API hctr_status hctr_hash_insert_or_find(hctr_hash* hash, const int64_t* keys, int64_t n,
+                                              int32_t insert, int64_t* rows, void* ws, size_t ws_bytes,
+                                              void* stream) {
+  if (!hash) return fail(HCTR_E_NULL_PTR, "hash is NULL");
+  if (n < 0 || n >= (1ll << 31)) return fail(HCTR_E_INVALID_ARG, "n %lld outside 0..2^31-1", (long long)n);
+  if (n == 0) return HCTR_OK;
+  if (!keys || !rows) return fail(HCTR_E_NULL_PTR, "keys / rows is NULL");
+  return hash_lookup(hash, keys, n, insert, rows, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+HCTR_API hctr_status hctr_hash_size(hctr_hash* hash, void* stream, int64_t* size) {
+  if (!hash || !size) return fail(HCTR_E_NULL_PTR, "NULL argument");
+  unsigned long long v = 0;
+  HCTR_TRY_HIP(hipMemcpyAsync(&v, hash->size, sizeof(v), hipMemcpyDeviceToHost, static_cast<hipStream_t>(stream)));
+  HCTR_TRY_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  *size = (int64_t)v;
+  return HCTR_OK;
+}
+
+HCTR_API void hctr_hash_destroy(hctr_hash* hash) { delete hash; }

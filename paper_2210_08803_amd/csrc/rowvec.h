@@ -1,0 +1,75 @@
+// 16-byte row fragments: one lane moves 4 fp32 or 8 fp16 table elements per load.
+#pragma once
+
+#include "common.h"
+
+namespace hctr {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename T>
+struct RowVec;
+
+template <>
+struct RowVec<float> {
+  static constexpr int VEC = 4;
+  __device__ static __forceinline__ void load(const float* p, float (&v)[4]) {
+    f32x4 x = *reinterpret_cast<const f32x4*>(p);
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+  }
+};
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
+  return __half2float(__ushort_as_half((unsigned short)h16));
+}
+
+template <>
+struct RowVec<__half> {
+  static constexpr int VEC = 8;
+  __device__ static __forceinline__ void load(const __half* p, float (&v)[8]) {
+    u32x4 x = *reinterpret_cast<const u32x4*>(p);
+    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = half_bits_to_float(w[i] & 0xFFFFu);
+      v[2 * i + 1] = half_bits_to_float(w[i] >> 16);
+    }
+  }
+};
+
+// Streaming store of N consecutive floats (N = 4 or 8): the pooled output is written once and not
+// read again by this library, so it should not displace table rows from L2.
+template <int N>
+__device__ __forceinline__ void store_stream(float* p, const float (&v)[N]) {
+#pragma unroll
+  for (int i = 0; i < N; i += 4) {
+    f32x4 x = {v[i], v[i + 1], v[i + 2], v[i + 3]};
+    __builtin_nontemporal_store(x, reinterpret_cast<f32x4*>(p + i));
+  }
+}
+
+__device__ __forceinline__ f32x4 load4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
+__device__ __forceinline__ void store4(float* p, f32x4 x) { *reinterpret_cast<f32x4*>(p) = x; }
+
+// Read-modify-write of 4 table elements: t <- t - lr * g (fp16 storage: widen, update in fp32,
+// round to nearest even).
+__device__ __forceinline__ void sgd_update4(float* t, f32x4 g, float lr) {
+  f32x4 x = load4(t);
+  x.x -= lr * g.x; x.y -= lr * g.y; x.z -= lr * g.z; x.w -= lr * g.w;
+  store4(t, x);
+}
+__device__ __forceinline__ void sgd_update4(__half* t, f32x4 g, float lr) {
+  u32x2 raw = *reinterpret_cast<const u32x2*>(t);
+  float a = half_bits_to_float(raw.x & 0xFFFFu) - lr * g.x;
+  float b = half_bits_to_float(raw.x >> 16) - lr * g.y;
+  float c = half_bits_to_float(raw.y & 0xFFFFu) - lr * g.z;
+  float d = half_bits_to_float(raw.y >> 16) - lr * g.w;
+  u32x2 o;
+  o.x = (uint32_t)__half_as_ushort(__float2half_rn(a)) | ((uint32_t)__half_as_ushort(__float2half_rn(b)) << 16);
+  o.y = (uint32_t)__half_as_ushort(__float2half_rn(c)) | ((uint32_t)__half_as_ushort(__float2half_rn(d)) << 16);
+  *reinterpret_cast<u32x2*>(t) = o;
+}
+
+}  // namespace hctr

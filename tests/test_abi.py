@@ -1,0 +1,93 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments on the host before anything could be launched (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2210_08803_amd as H
+from paper_2210_08803_amd.binding import EXPORTS, _EmbDesc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "hctr.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hctr_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = H.lib()
+    names = header_functions()
+    assert len(names) >= 19
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(EXPORTS) == names
+
+
+def _desc(**kw):
+    base = (C.c_int64 * 2)(0, 10)
+    num = (C.c_int64 * 2)(10, 5)
+    d = _EmbDesc(num_slots=2, dim=8, table_dtype=H.F32, combiner=H.SUM, table=4096, total_rows=15,
+                 slot_row_base=base, slot_num_rows=num, hash=None, insert_on_miss=0)
+    d._keep = (base, num)
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def _fwd(d, batch=1, keys=4096, offsets=None, nnz=2, out=4096, ws=4096, ws_bytes=1 << 30):
+    return H.lib().hctr_emb_forward(C.byref(d), batch, keys, offsets, nnz, out, ws, ws_bytes, None)
+
+
+def test_forward_argument_errors_are_caught_on_the_host():
+    L = H.lib()
+    assert L.hctr_emb_forward(None, 1, 4096, None, 2, 4096, 4096, 1 << 30, None) == -2
+    assert _fwd(_desc(num_slots=0)) == -1
+    assert _fwd(_desc(num_slots=129)) == -1
+    assert _fwd(_desc(dim=6)) == -1                       # fp32 rows need a multiple of 4
+    assert _fwd(_desc(dim=12, table_dtype=H.F16)) == -1   # fp16 rows need a multiple of 8
+    assert _fwd(_desc(table_dtype=7)) == -1
+    assert _fwd(_desc(combiner=3)) == -1
+    assert _fwd(_desc(table=None)) == -2
+    assert _fwd(_desc(table=4100)) == -1                  # misaligned table
+    assert _fwd(_desc(total_rows=0)) == -4
+    assert _fwd(_desc(total_rows=14)) == -1               # slot 1 would leave the table
+    assert _fwd(_desc(), nnz=3) == -1                     # one-hot needs nnz == batch*S
+    assert _fwd(_desc(), batch=-1) == -1
+    assert _fwd(_desc(), keys=None) == -2
+    assert _fwd(_desc(), out=None) == -2
+    assert _fwd(_desc(), out=4100) == -1
+    assert _fwd(_desc(), ws=None) == -3
+    assert _fwd(_desc(), ws=4100) == -3
+    assert _fwd(_desc(), ws_bytes=16) == -3
+    assert b"workspace" in L.hctr_last_error()
+    d = _desc()
+    assert L.hctr_emb_backward_sgd(C.byref(d), 1, 4096, None, 2, None, 0.1, 4096, 1 << 30, None) == -2
+    need = L.hctr_emb_workspace_bytes(C.byref(d), 1, 2)
+    assert need > 0 and need % 256 == 0
+    assert L.hctr_emb_workspace_bytes(C.byref(d), 1, 1 << 20) > need
+
+
+def test_hash_and_cache_argument_errors():
+    L = H.lib()
+    h = C.c_void_p()
+    assert L.hctr_hash_storage_bytes(10) == 0
+    assert L.hctr_hash_storage_bytes(1024) == 256 + 128 * 128
+    assert L.hctr_hash_create(None, 1 << 20, 1024, 100, None, C.byref(h)) == -2
+    assert L.hctr_hash_create(4096, 1 << 20, 1024, 900, None, C.byref(h)) == -1   # above 0.8 * capacity
+    assert L.hctr_hash_create(4096, 100, 1024, 100, None, C.byref(h)) == -1       # storage too small
+    assert L.hctr_hash_create(4100, 1 << 20, 1024, 100, None, C.byref(h)) == -1   # misaligned
+    assert L.hctr_hash_insert_or_find(None, 4096, 1, 1, 4096, 4096, 1 << 20, None) == -2
+    assert L.hctr_hash_workspace_bytes(1000) % 256 == 0
+    assert L.hctr_cache_storage_bytes(8, 3, 16) == 0      # ways must be a power of two
+    assert L.hctr_cache_storage_bytes(8, 4, 6) == 0       # dim must be a multiple of 4
+    assert L.hctr_cache_storage_bytes(0, 4, 8) == 0
+    assert L.hctr_cache_storage_bytes(8, 4, 16) >= 8 * 4 * (8 + 4 + 64)
+    c = C.c_void_p()
+    assert L.hctr_cache_create(4096, 1 << 20, 8, 3, 16, 4096, 10, None, C.byref(c)) == -1
+    assert L.hctr_cache_create(4096, 16, 8, 4, 16, 4096, 10, None, C.byref(c)) == -1
+    assert L.hctr_cache_create(4096, 1 << 20, 8, 4, 16, None, 10, None, C.byref(c)) == -2
+    assert L.hctr_cache_query(None, 1, 1, 4096, None, 1, 1, 4096, None, 4096, 1 << 20, None) == -2

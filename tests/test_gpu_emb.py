@@ -1,0 +1,172 @@
+"""GPU parity: hctr_emb_forward / hctr_emb_backward_sgd (direct-index mode) against the oracle,
+element by element, on seeded synthetic inputs."""
+import numpy as np
+import pytest
+import torch
+
+import datagen
+import oracle
+from parity import assert_close, check_table_update, oracle_backward, oracle_forward, to_dev
+
+pytestmark = pytest.mark.gpu
+SEED = datagen.DEFAULT_SEED
+
+
+def H():
+    import paper_2210_08803_amd as h
+    return h
+
+
+def run_case(table_rows, dim, batch, *, dtype=torch.float32, combiner=0, alpha=1.05, hot=None, seed=SEED,
+             lr=0.01, share_table=False, poison=0, slot_base=None):
+    """One forward + backward comparison.  hot = None (one-hot) or (lo, hi) hotness range."""
+    h = H()
+    S = len(table_rows)
+    if share_table:
+        base = np.zeros(S, dtype=np.int64)
+        total = int(table_rows[0])
+    else:
+        ro = datagen.row_offsets(table_rows)
+        base, total = ro[:-1].copy(), int(ro[-1])
+    num = np.asarray(table_rows, dtype=np.int64)
+    table = datagen.table_rows_at(seed, torch.arange(total), dim, dtype)
+    n_bags = batch * S
+    if hot is None:
+        offsets = None
+        keys = datagen.onehot_keys(seed, 0, table_rows, batch, alpha)
+    else:
+        offsets = datagen.multihot_offsets(seed, 0, n_bags, hot[0], hot[1])
+        keys = datagen.multihot_keys(seed, 0, table_rows, batch, alpha, offsets)
+    if poison:
+        g = np.random.default_rng(seed)
+        idx = g.integers(0, len(keys), poison)
+        keys[idx] = torch.from_numpy(g.choice([-1, -2**62, 2**40, int(num.max())], poison))
+    dY = datagen.normal_grads(seed, 0, n_bags * dim).view(n_bags, dim)
+
+    tab_np, keys_np, dY_np = table.numpy(), keys.numpy(), dY.numpy()
+    off_np = None if offsets is None else offsets.numpy()
+    rows, bad = oracle.rows_direct(base, num, keys_np, off_np, n_bags=n_bags)
+    ref_out, mag_out = oracle_forward(tab_np, rows, off_np, combiner, n_bags)
+    ref_tab, mag_tab, uniq, cnt = oracle_backward(tab_np, rows, off_np, combiner, n_bags, dY_np, lr)
+
+    d_table = to_dev(table)
+    layer = h.EmbeddingLayer(d_table, S, combiner, base, num)
+    d_keys, d_off, d_dY = to_dev(keys), (None if offsets is None else to_dev(offsets)), to_dev(dY)
+    out = layer.forward(batch, d_keys, d_off)
+    torch.cuda.synchronize()
+    assert layer.invalid_keys() == bad
+    out_np = out.cpu().numpy().reshape(n_bags, dim)
+    if hot is None:
+        assert np.array_equal(out_np.view(np.uint32), ref_out.view(np.uint32)), "one-hot forward must be bit-exact"
+    assert_close(out_np, ref_out, mag_out, "forward")
+    out2 = layer.forward(batch, d_keys, d_off)
+    assert torch.equal(out, out2), "forward is not deterministic"
+
+    layer.backward_sgd(batch, d_keys, d_dY, lr, d_off)
+    torch.cuda.synchronize()
+    assert layer.invalid_keys() == bad
+    g_rows, g_cnt = layer.dedup_result(batch, len(keys_np))
+    assert np.array_equal(g_rows.cpu().numpy(), uniq), "unique rows differ"
+    assert np.array_equal(g_cnt.cpu().numpy(), cnt), "occurrence counts differ"
+    got = d_table.cpu().numpy()
+    check_table_update(got, tab_np, ref_tab, mag_tab, uniq, "backward")
+
+    d_table2 = to_dev(table)
+    layer2 = h.EmbeddingLayer(d_table2, S, combiner, base, num)
+    layer2.backward_sgd(batch, d_keys, d_dY, lr, d_off)
+    torch.cuda.synchronize()
+    assert torch.equal(d_table, d_table2), "backward is not deterministic"
+    return dict(nnz=len(keys_np), unique=len(uniq), max_count=int(cnt.max()) if len(cnt) else 0)
+
+
+def test_tiny_config():
+    """10,000 x 16 fp32, batch 256, 4 one-hot slots on the one table, uniform keys, lr 0.01."""
+    info = run_case([10000] * 4, 16, 256, alpha=0.0, share_table=True)
+    assert info["nnz"] == 1024
+
+
+def test_dlrm_shape_scaled_onehot():
+    """26 tables at 1/1000 of the full row counts, dim 128 fp32, Zipf 1.05; 2,051 samples give a
+    ragged last tile in every kernel and segments far longer than a reduction window."""
+    rows = datagen.scaled_table_rows(1e-3)
+    info = run_case(rows, 128, 2051)
+    assert info["max_count"] > 128 and info["unique"] < info["nnz"]
+
+
+def test_multihot_fp16_mean():
+    """fp16 storage, fp32 accumulate, mean combiner, hotness 1..100 per bag, Zipf 1.1."""
+    rows = datagen.scaled_table_rows(2e-4)
+    run_case(rows, 128, 96, dtype=torch.float16, combiner=1, alpha=1.1, hot=(1, 100))
+
+
+def test_multihot_with_empty_bags_sum_fp32():
+    run_case([50, 3000, 7], 64, 300, combiner=0, alpha=1.1, hot=(0, 9))
+
+
+def test_multihot_mean_fp32_with_empty_bags():
+    run_case([50, 3000, 7], 32, 300, combiner=1, alpha=1.1, hot=(0, 9))
+
+
+@pytest.mark.parametrize("dim", [4, 8, 20, 64, 100, 256, 384])
+def test_row_widths_fp32(dim):
+    run_case([37, 1000], dim, 130, hot=(0, 5))
+    run_case([37, 1000], dim, 130)
+
+
+@pytest.mark.parametrize("dim", [8, 24, 128, 520])
+def test_row_widths_fp16(dim):
+    run_case([37, 1000], dim, 130, dtype=torch.float16, hot=(0, 5))
+    run_case([37, 1000], dim, 130, dtype=torch.float16)
+
+
+def test_keys_without_a_row():
+    info = run_case([100, 2000, 30], 16, 500, poison=40)
+    run_case([100, 2000, 30], 16, 200, poison=60, hot=(0, 6), combiner=1)
+    assert info["nnz"] == 1500
+
+
+def test_every_key_equal_one_long_segment():
+    """All 9,000 keys hit one row: a segment spanning hundreds of windows and several sort tiles."""
+    info = run_case([1], 128, 9000)
+    assert info["unique"] == 1 and info["max_count"] == 9000
+
+
+@pytest.mark.parametrize("batch", [1, 31, 32, 33, 4095, 4096, 4097])
+def test_sizes_around_window_and_tile_edges(batch):
+    run_case([500], 32, batch)
+
+
+def test_all_keys_distinct():
+    h = H()
+    n = 5000
+    table = datagen.table_rows_at(SEED, torch.arange(n), 16, torch.float32)
+    keys = torch.randperm(n, generator=torch.Generator().manual_seed(3))
+    dY = datagen.normal_grads(SEED, 1, n * 16).view(n, 16)
+    d_table = to_dev(table)
+    layer = h.EmbeddingLayer(d_table, 1, 0, [0], [n])
+    layer.backward_sgd(n, to_dev(keys), to_dev(dY), 0.5)
+    torch.cuda.synchronize()
+    ref = table.clone()
+    ref[keys] -= 0.5 * dY
+    assert torch.equal(d_table.cpu(), ref)   # one term per row, lr a power of two: exact
+
+
+def test_empty_batch_and_lr_zero():
+    h = H()
+    table = datagen.table_rows_at(SEED, torch.arange(64), 8, torch.float32)
+    d_table = to_dev(table)
+    layer = h.EmbeddingLayer(d_table, 2, 0, [0, 32], [32, 32])
+    empty = torch.empty(0, dtype=torch.int64, device="cuda")
+    out = layer.forward(0, empty)
+    assert out.numel() == 0
+    layer.backward_sgd(0, empty, torch.empty(0, device="cuda"), 0.1)
+    keys = to_dev(torch.tensor([1, 2, 3, 4]))
+    layer.backward_sgd(2, keys, to_dev(torch.ones(4, 8)), 0.0)
+    torch.cuda.synchronize()
+    assert torch.equal(d_table.cpu(), table)
+
+
+def test_library_is_the_hip_build():
+    h = H()
+    import os
+    assert os.path.exists(h.lib_path()) and h.lib_path().endswith("libhctr.so")
