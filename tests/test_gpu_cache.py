@@ -1,0 +1,115 @@
+"""GPU parity: hctr_cache_query against the oracle's cache simulation.  Hit masks, tags, stamps
+and statistics must match exactly after every call; pooled outputs within the fp32 tolerance."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import datagen
+import oracle
+from parity import assert_close, to_dev
+
+pytestmark = pytest.mark.gpu
+SEED = datagen.DEFAULT_SEED
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "cache_batch_lru_trace.json")
+
+
+def H():
+    import paper_2210_08803_amd as h
+    return h
+
+
+def pinned_table(rows, dim, seed=SEED):
+    t = torch.empty((rows, dim), dtype=torch.float32, pin_memory=True)
+    t.copy_(datagen.table_rows_at(seed, torch.arange(rows), dim, torch.float32))
+    return t
+
+
+class Pair:
+    def __init__(self, num_sets, ways, host):
+        self.host = host
+        self.gpu = H().EmbeddingCache(num_sets, ways, host)
+        self.ref = oracle.Cache(num_sets, ways, host.numpy())
+        self.num_sets, self.ways = num_sets, ways
+
+    def query(self, keys, n_bags, offsets=None, insert=True, what=""):
+        keys = np.ascontiguousarray(keys, dtype=np.int64)
+        ref_out, ref_hit = self.ref.query(keys, n_bags, offsets=offsets, insert_missing=insert)
+        d_hit = torch.zeros(len(keys), dtype=torch.uint8, device="cuda")
+        d_off = None if offsets is None else to_dev(np.ascontiguousarray(offsets, dtype=np.int64))
+        out = self.gpu.query(n_bags, 1, to_dev(keys), d_off, insert, hit_mask=d_hit)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_hit.cpu().numpy(), ref_hit), f"{what}: hit mask differs"
+        assert self.gpu.stats == self.ref.stats.tolist(), f"{what}: stats {self.gpu.stats} vs {self.ref.stats.tolist()}"
+        tags, stamps = self.gpu.state()
+        rtags, rstamps, rdata = self.ref.state(with_data=True)
+        assert np.array_equal(tags.numpy().view(np.uint64), rtags), f"{what}: tags differ"
+        assert np.array_equal(stamps.numpy().astype(np.uint32), rstamps), f"{what}: stamps differ"
+        live = (rtags != oracle.EMPTY_TAG).ravel()
+        data = self.gpu.data().cpu().numpy()
+        assert np.array_equal(data[live], rdata[live]), f"{what}: cached rows differ"
+        # magnitude of the terms: gather-sum of |row| from the host table
+        valid = (keys >= 0) & (keys < self.host.shape[0])
+        bag = (np.repeat(np.arange(n_bags), np.diff(offsets)) if offsets is not None
+               else np.arange(len(keys)) // max(1, len(keys) // n_bags))
+        mag = np.zeros((n_bags, self.host.shape[1]))
+        np.add.at(mag, bag[valid], np.abs(self.host.numpy()[keys[valid]]).astype(np.float64))
+        assert_close(out.cpu().numpy().reshape(n_bags, -1), ref_out, mag, f"{what}: pooled output")
+        return ref_hit
+
+
+def test_hand_worked_trace():
+    g = json.load(open(GOLD))
+    host = torch.empty((g["host_rows"], g["dim"]), dtype=torch.float32, pin_memory=True)
+    host.copy_(torch.arange(g["host_rows"] * g["dim"], dtype=torch.float32).view(g["host_rows"], g["dim"]) / 8)
+    gpu = H().EmbeddingCache(g["num_sets"], g["ways"], host)
+    for call in g["calls"]:
+        keys = torch.tensor(call["keys"], dtype=torch.int64, device="cuda")
+        hit = torch.zeros(len(call["keys"]), dtype=torch.uint8, device="cuda")
+        gpu.query(call["n_bags"], 1, keys, None, bool(call["insert"]), hit_mask=hit)
+        torch.cuda.synchronize()
+        tags, stamps = gpu.state()
+        assert hit.cpu().tolist() == call["hit"]
+        assert tags[0].tolist() == call["tags"] and stamps[0].tolist() == call["stamps"]
+        assert gpu.stats == call["stats"]
+
+
+@pytest.mark.parametrize("num_sets,ways,dim", [(64, 8, 16), (1, 4, 8), (37, 1, 32), (16, 32, 128), (5, 64, 4), (300, 2, 260)])
+def test_zipf_traffic_matches_the_simulation(num_sets, ways, dim):
+    host_rows = 5000
+    p = Pair(num_sets, ways, pinned_table(host_rows, dim))
+    smp = datagen.ZipfSampler(host_rows, 1.2)
+    hits = 0
+    for it in range(12):
+        n_bags, hot = 26 * 9, 4
+        keys = datagen.cache_keys(SEED, it, host_rows, n_bags * hot, 1.2, sampler=smp).numpy()
+        if it == 5:
+            keys[::17] = -3
+            keys[1::29] = host_rows + 5                        # outside the host table
+        hits += p.query(keys, n_bags, insert=(it % 4 != 3), what=f"call {it}").sum()
+    assert hits > 0
+
+
+def test_csr_bags_and_batch_of_one_key():
+    host_rows, dim = 800, 64
+    p = Pair(32, 4, pinned_table(host_rows, dim))
+    rng = np.random.default_rng(8)
+    for it in range(10):
+        h = rng.integers(0, 7, 90)
+        offsets = np.concatenate([[0], np.cumsum(h)])
+        keys = rng.zipf(1.3, offsets[-1]) % host_rows
+        p.query(keys, 90, offsets=offsets, what=f"csr {it}")
+    for it in range(30):
+        p.query(rng.integers(0, 50, 1), 1, what=f"single {it}")   # classical per-access LRU traffic
+
+
+def test_set_overflow_in_one_call_skips_the_surplus():
+    host_rows, dim = 4096, 8
+    p = Pair(2, 4, pinned_table(host_rows, dim))
+    keys = np.arange(64)                                          # ~32 new keys per set, 4 ways each
+    p.query(keys, 64, what="flood")
+    assert p.ref.stats[5] > 0
+    p.query(keys[::-1].copy(), 64, what="flood again")
+    p.query(np.zeros(0, dtype=np.int64), 3, offsets=np.zeros(4, dtype=np.int64), what="empty bags")
