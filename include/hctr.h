@@ -87,6 +87,10 @@ typedef struct {
 /* Bytes of workspace that forward and backward need for up to nnz_max keys (multiple of 256). */
 size_t hctr_emb_workspace_bytes(const hctr_emb_desc* desc, int64_t batch, int64_t nnz_max);
 
+/* Must run once on a fresh workspace before its first use (it zeroes the counter of keys without
+ * a row, which forward and backward only ever add to); calling it again resets that counter. */
+hctr_status hctr_emb_workspace_init(void* ws, size_t ws_bytes, void* stream);
+
 /*
  * Forward: out[b, s, :] = w * sum_j T[row(key_j), :] over the keys of bag (b, s); w = 1 for
  * HCTR_SUM, 1/hotness for HCTR_MEAN (hotness = number of keys of the bag); an empty bag gives
@@ -129,8 +133,8 @@ hctr_status hctr_emb_dedup_view(const hctr_emb_desc* desc, int64_t batch, int64_
                                 size_t ws_bytes, const int64_t** num_unique,
                                 const uint32_t** uniq_rows, const uint32_t** seg_offsets);
 
-/* Number of keys without a row seen by the last forward or backward call on `ws` (host int64;
- * waits for the stream). */
+/* Number of keys without a row seen by all forward and backward calls on `ws` since
+ * hctr_emb_workspace_init (host int64; waits for the stream). */
 hctr_status hctr_emb_invalid_keys(const void* ws, size_t ws_bytes, void* stream, int64_t* count);
 
 /*

@@ -51,6 +51,7 @@ def lib() -> C.CDLL:
     dp = C.POINTER(_EmbDesc)
     sig = {
         "hctr_emb_workspace_bytes": (sz, [dp, i64, i64]),
+        "hctr_emb_workspace_init": (i32, [p, sz, p]),
         "hctr_emb_forward": (i32, [dp, i64, p, p, i64, p, p, sz, p]),
         "hctr_emb_backward_sgd": (i32, [dp, i64, p, p, i64, p, f32, p, sz, p]),
         "hctr_emb_dedup_view": (i32, [dp, i64, i64, p, sz, C.POINTER(p), C.POINTER(p), C.POINTER(p)]),
@@ -78,7 +79,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = [
-    "hctr_emb_workspace_bytes", "hctr_emb_forward", "hctr_emb_backward_sgd", "hctr_emb_dedup_view",
+    "hctr_emb_workspace_bytes", "hctr_emb_workspace_init", "hctr_emb_forward", "hctr_emb_backward_sgd", "hctr_emb_dedup_view",
     "hctr_emb_invalid_keys", "hctr_hash_storage_bytes", "hctr_hash_create", "hctr_hash_workspace_bytes",
     "hctr_hash_insert_or_find", "hctr_hash_size", "hctr_hash_destroy", "hctr_cache_storage_bytes",
     "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_query", "hctr_cache_stats",
@@ -180,8 +181,17 @@ class EmbeddingLayer:
     def workspace(self, batch: int, nnz: int) -> torch.Tensor:
         need = self.workspace_bytes(batch, nnz)
         if self._wsbuf is None or self._wsbuf.numel() < need:
-            self._wsbuf = _ws(need, self.table.device)
+            self._wsbuf = self.new_workspace(need)
         return self._wsbuf
+
+    def new_workspace(self, nbytes: int) -> torch.Tensor:
+        ws = _ws(nbytes, self.table.device)
+        _check(lib().hctr_emb_workspace_init(_ptr(ws), ws.numel(), _stream(None)))
+        return ws
+
+    def reset_invalid_keys(self, ws: Optional[torch.Tensor] = None) -> None:
+        ws = ws if ws is not None else self._wsbuf
+        _check(lib().hctr_emb_workspace_init(_ptr(ws), ws.numel(), _stream(None)))
 
     def forward(self, batch: int, keys: torch.Tensor, offsets: Optional[torch.Tensor] = None,
                 out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

@@ -16,16 +16,16 @@ struct SlotTable {
 
 // First 256 bytes of an embedding workspace.
 struct EmbHeader {
-  unsigned long long invalid;  // keys without a row in the last call
+  unsigned long long invalid;  // keys without a row, running total since hctr_emb_workspace_init
   long long num_unique;        // U of the last backward
   uint32_t n_valid;            // sorted positions holding a real row
   uint32_t pad[59];
 };
 static_assert(sizeof(EmbHeader) == 256, "header is one 256-byte block");
 
-__global__ void emb_init_header(EmbHeader* hdr, uint32_t* seg_off) {
+__global__ void emb_init_header(EmbHeader* hdr, uint32_t* seg_off, int reset_invalid) {
   if (threadIdx.x == 0) {
-    hdr->invalid = 0;
+    if (reset_invalid) hdr->invalid = 0;
     hdr->num_unique = 0;
     hdr->n_valid = 0;
     if (seg_off) seg_off[0] = 0;
@@ -571,9 +571,8 @@ HCTR_API hctr_status hctr_emb_forward(const hctr_emb_desc* desc, int64_t batch, 
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   char* w = static_cast<char*>(ws);
   EmbHeader* hdr = reinterpret_cast<EmbHeader*>(w + L.header);
-  hipLaunchKernelGGL(emb_init_header, dim3(1), dim3(64), 0, stream, hdr, (uint32_t*)nullptr);
   const int64_t n_bags = batch * desc->num_slots;
-  if (n_bags == 0) return launch_status("emb_init_header");
+  if (n_bags == 0) return HCTR_OK;
   const int64_t* rows64 = nullptr;
   if (desc->hash) {
     int64_t* r = reinterpret_cast<int64_t*>(w + L.rows64);
@@ -601,7 +600,7 @@ HCTR_API hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t ba
   char* w = static_cast<char*>(ws);
   EmbHeader* hdr = reinterpret_cast<EmbHeader*>(w + L.header);
   uint32_t* seg_off = reinterpret_cast<uint32_t*>(w + L.seg_off);
-  hipLaunchKernelGGL(emb_init_header, dim3(1), dim3(64), 0, stream, hdr, seg_off);
+  hipLaunchKernelGGL(emb_init_header, dim3(1), dim3(64), 0, stream, hdr, seg_off, 0);
   if (nnz == 0) return launch_status("emb_init_header");
   const uint32_t n = (uint32_t)nnz;
   const uint32_t n_bags = (uint32_t)(batch * desc->num_slots);
@@ -651,6 +650,15 @@ HCTR_API hctr_status hctr_emb_dedup_view(const hctr_emb_desc* desc, int64_t batc
   *uniq_rows = reinterpret_cast<const uint32_t*>(w + L.uniq);
   *seg_offsets = reinterpret_cast<const uint32_t*>(w + L.seg_off);
   return HCTR_OK;
+}
+
+HCTR_API hctr_status hctr_emb_workspace_init(void* ws, size_t ws_bytes, void* stream) {
+  if (!ws) return fail(HCTR_E_WORKSPACE, "workspace is NULL");
+  if ((uintptr_t)ws % 256 != 0) return fail(HCTR_E_WORKSPACE, "workspace must be 256-byte aligned");
+  if (ws_bytes < sizeof(EmbHeader)) return fail(HCTR_E_WORKSPACE, "workspace too small");
+  hipLaunchKernelGGL(emb_init_header, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream),
+                     static_cast<EmbHeader*>(ws), (uint32_t*)nullptr, 1);
+  return launch_status("emb_init_header");
 }
 
 HCTR_API hctr_status hctr_emb_invalid_keys(const void* ws, size_t ws_bytes, void* stream, int64_t* count) {

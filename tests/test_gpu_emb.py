@@ -62,6 +62,8 @@ def run_case(table_rows, dim, batch, *, dtype=torch.float32, combiner=0, alpha=1
     out2 = layer.forward(batch, d_keys, d_off)
     assert torch.equal(out, out2), "forward is not deterministic"
 
+    assert layer.invalid_keys() == 2 * bad            # the counter is a running total
+    layer.reset_invalid_keys()
     layer.backward_sgd(batch, d_keys, d_dY, lr, d_off)
     torch.cuda.synchronize()
     assert layer.invalid_keys() == bad

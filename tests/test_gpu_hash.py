@@ -111,10 +111,13 @@ def test_hashed_embedding_forward_backward():
         torch.cuda.synchronize()
         assert ht.size == ref_hash.size
         assert layer.invalid_keys() == int((rows < 0).sum())
+        layer.reset_invalid_keys()
         out_np = out.cpu().numpy().reshape(batch * S, dim)
         assert np.array_equal(out_np.view(np.uint32), ref_out.view(np.uint32))
         ref_tab, mag_tab, uniq, cnt = oracle_backward(tab_np, rows, None, 0, batch * S, dY.numpy(), 0.01)
         layer.backward_sgd(batch, to_dev(keys), to_dev(dY), 0.01)
+        assert layer.invalid_keys() == int((rows < 0).sum())
+        layer.reset_invalid_keys()
         g_rows, g_cnt = layer.dedup_result(batch, keys.numel())
         assert np.array_equal(g_rows.cpu().numpy(), uniq) and np.array_equal(g_cnt.cpu().numpy(), cnt)
         check_table_update(d_table.cpu().numpy(), tab_np, ref_tab, mag_tab, uniq, f"hashed backward {it}")
