@@ -88,7 +88,8 @@ typedef struct {
 size_t hctr_emb_workspace_bytes(const hctr_emb_desc* desc, int64_t batch, int64_t nnz_max);
 
 /* Must run once on a fresh workspace before its first use (it zeroes the counter of keys without
- * a row, which forward and backward only ever add to); calling it again resets that counter. */
+ * a row, which forward and backward only ever add to); calling it again resets that counter and
+ * forgets the last dedup result. */
 hctr_status hctr_emb_workspace_init(void* ws, size_t ws_bytes, void* stream);
 
 /*

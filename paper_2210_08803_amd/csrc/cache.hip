@@ -476,7 +476,7 @@ HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_
     hipLaunchKernelGGL(cache_list_new, dim3((uint32_t)ceil_div(n, 256)), dim3(256), 0, stream,
                        (const HashWsHeader*)ws_hdr, keys, (const uint32_t*)B.miss_pos,
                        (const uint32_t*)B.first, (const uint32_t*)B.rank, (u64)c->num_sets, new_key, k[0], v[0]);
-    HCTR_TRY(radix_sort_pairs(L.sort, L.sort_bits, &ws_hdr->n_new, k[0], v[0], k[1], v[1],
+    HCTR_TRY(radix_sort_pairs(L.sort, &ws_hdr->n_new, k[0], v[0], k[1], v[1],
                               reinterpret_cast<uint32_t*>(w + L.hist), B.scan_tmp, stream));
     const uint32_t* sset = k[L.sort.passes & 1];
     const uint32_t* sq = v[L.sort.passes & 1];

@@ -69,18 +69,21 @@ size_t scan_tmp_count(uint32_t n);
 hctr_status exclusive_scan_u32(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* tmp,
                                uint32_t* total, hipStream_t stream);
 
-// Stable LSD radix sort of (key, value) uint32 pairs on the low `bits` bits of the key.
-// The element count is *n_dev if n_dev != nullptr (must be <= n_max), else n_max.
-// Buffers 0 hold the input; the result lands in buffers (passes & 1), passes = ceil(bits / 8).
+// Stable LSD radix sort of (key, value) uint32 pairs on the low `bits` bits of the key, in
+// ceil(bits / 10) passes of evenly sized digits.  The element count is *n_dev if n_dev != nullptr
+// (must be <= n_max), else n_max.  Buffers 0 hold the input; the result lands in buffers
+// (passes & 1).  hist holds plan.hist_count words, scan_tmp scan_tmp_count(plan.hist_count).
+constexpr uint32_t kSortTile = 4096;
+constexpr int kSortMaxDigitBits = 10;
 struct SortPlan {
   uint32_t n_max = 0;
   uint32_t n_blocks = 0;   // tiles of kSortTile keys
-  uint32_t hist_count = 0; // 256 * n_blocks
+  uint32_t hist_count = 0; // largest bins * n_blocks over the passes
   int passes = 0;
+  int digit_bits[4] = {0, 0, 0, 0};
 };
-constexpr uint32_t kSortTile = 4096;
 SortPlan sort_plan(uint32_t n_max, int bits);
-hctr_status radix_sort_pairs(const SortPlan& plan, int bits, const uint32_t* n_dev, uint32_t* keys0,
+hctr_status radix_sort_pairs(const SortPlan& plan, const uint32_t* n_dev, uint32_t* keys0,
                              uint32_t* vals0, uint32_t* keys1, uint32_t* vals1, uint32_t* hist,
                              uint32_t* scan_tmp, hipStream_t stream);
 

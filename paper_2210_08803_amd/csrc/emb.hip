@@ -4,6 +4,7 @@
 // loads are in flight per lane before the first use.
 #include "common.h"
 #include "rowvec.h"
+#include "blockscan.h"
 #include "hash_internal.h"
 
 namespace hctr {
@@ -224,35 +225,68 @@ __global__ __launch_bounds__(256) void bwd_rows(const int64_t* __restrict__ keys
   count_invalid(&hdr->invalid, bad);
 }
 
-// Backward step 3: run boundaries of the sorted rows = the distinct rows of the batch.
-__global__ __launch_bounds__(256) void seg_flags(const uint32_t* __restrict__ srow, uint32_t n,
-                                                 uint32_t* __restrict__ flags) {
-  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-  if (i < n) {
-    const uint32_t r = srow[i];
-    flags[i] = (r != kNoRow && (i == 0 || srow[i - 1] != r)) ? 1u : 0u;
-  }
+// Backward step 3: run boundaries of the sorted rows = the distinct rows of the batch.  A position
+// starts a segment if it holds a real row that differs from its left neighbour.  Two tiled passes
+// around one small scan: count the starts per tile, then number them and write the unique rows,
+// the segment offsets and, per position, the number of starts before it.
+constexpr int kSegThreads = 256;
+constexpr int kSegItems = 16;
+constexpr uint32_t kSegTile = kSegThreads * kSegItems;
+
+__device__ __forceinline__ uint32_t seg_start(const uint32_t* __restrict__ srow, uint32_t i) {
+  const uint32_t r = srow[i];
+  return (r != kNoRow && (i == 0 || srow[i - 1] != r)) ? 1u : 0u;
 }
 
-__global__ __launch_bounds__(256) void seg_compact(const uint32_t* __restrict__ srow, uint32_t n,
-                                                   const uint32_t* __restrict__ idx,
-                                                   uint32_t* __restrict__ uniq,
-                                                   uint32_t* __restrict__ seg_off, EmbHeader* hdr) {
-  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-  if (i >= n) return;
-  const uint32_t r = srow[i];
-  if (r == kNoRow) return;
-  const bool start = (i == 0) || (srow[i - 1] != r);
-  const uint32_t u = idx[i];
-  if (start) {
-    uniq[u] = r;
-    seg_off[u] = i;
+__global__ __launch_bounds__(kSegThreads) void seg_tile_counts(const uint32_t* __restrict__ srow,
+                                                               uint32_t n, uint32_t* __restrict__ sums) {
+  __shared__ uint32_t lds[kSegThreads / 64 + 1];
+  const uint32_t base = blockIdx.x * kSegTile;
+  uint32_t s = 0;
+#pragma unroll
+  for (int i = 0; i < kSegItems; ++i) {
+    const uint32_t idx = base + i * kSegThreads + threadIdx.x;
+    if (idx < n) s += seg_start(srow, idx);
   }
-  if (i == n - 1 || srow[i + 1] == kNoRow) {  // last real row: closes the last segment
-    const uint32_t U = u + (start ? 1u : 0u);
-    seg_off[U] = i + 1;
-    hdr->n_valid = i + 1;
-    hdr->num_unique = (long long)U;
+  uint32_t total;
+  block_exclusive_scan<kSegThreads>(s, lds, &total);
+  if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kSegThreads) void seg_write(const uint32_t* __restrict__ srow, uint32_t n,
+                                                         const uint32_t* __restrict__ tile_base,
+                                                         uint32_t* __restrict__ starts_before,
+                                                         uint32_t* __restrict__ uniq,
+                                                         uint32_t* __restrict__ seg_off, EmbHeader* hdr) {
+  __shared__ uint32_t lds[kSegThreads / 64 + 1];
+  const uint32_t base = blockIdx.x * kSegTile + threadIdx.x * kSegItems;
+  uint32_t f[kSegItems];
+  uint32_t s = 0;
+#pragma unroll
+  for (int i = 0; i < kSegItems; ++i) {
+    f[i] = (base + i < n) ? seg_start(srow, base + i) : 0u;
+    s += f[i];
+  }
+  uint32_t total;
+  uint32_t run = block_exclusive_scan<kSegThreads>(s, lds, &total) + tile_base[blockIdx.x];
+#pragma unroll
+  for (int i = 0; i < kSegItems; ++i) {
+    const uint32_t p = base + i;
+    if (p < n) {
+      starts_before[p] = run;
+      const uint32_t r = srow[p];
+      if (f[i]) {
+        uniq[run] = r;
+        seg_off[run] = p;
+      }
+      if (r != kNoRow && (p == n - 1 || srow[p + 1] == kNoRow)) {  // last real row closes the last segment
+        const uint32_t U = run + f[i];
+        seg_off[U] = p + 1;
+        hdr->n_valid = p + 1;
+        hdr->num_unique = (long long)U;
+      }
+    }
+    run += f[i];
   }
 }
 
@@ -337,29 +371,54 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
   if (sub == 0 && blockIdx.y == 0) tail_flag[win] = wrote_tail ? 1 : 0;
 }
 
+// One block per window.  A window that holds the first piece of a border-crossing row gathers
+// that row: the block's 256/LPR lane groups each add a contiguous share of the following windows'
+// partials (4 loads in flight), the shares are staged in LDS and added in group order.
 template <typename T, int LPR>
 __global__ __launch_bounds__(256) void bwd_reduce_carry(
     T* __restrict__ table, int D, const uint32_t* __restrict__ srow,
+    const uint32_t* __restrict__ starts_before, const uint32_t* __restrict__ seg_off,
     const EmbHeader* __restrict__ hdr, float lr, const float* __restrict__ head,
     const float* __restrict__ tail, const uint8_t* __restrict__ tail_flag, uint32_t W) {
-  const int sub = threadIdx.x % LPR;
-  const uint32_t win = (blockIdx.x * 256u + threadIdx.x) / LPR;
+  constexpr int NG = 256 / LPR;
+  __shared__ f32x4 part[256];
+  const int sub = threadIdx.x % LPR, g = threadIdx.x / LPR;
+  const uint32_t win = blockIdx.x;
   const int col = blockIdx.y * (LPR * 4) + sub * 4;
   const bool active = col < D;
   const uint32_t n_valid = hdr->n_valid;
   const uint64_t start64 = (uint64_t)win * W;
-  if (start64 >= n_valid) return;
-  if (!tail_flag[win]) return;
+  if (start64 >= n_valid) return;   // block-uniform
+  if (!tail_flag[win]) return;      // block-uniform
   // a tail exists only when the window is full and its last row continues into the next window
-  const uint32_t r = srow[(uint32_t)start64 + W - 1];
-  f32x4 acc = active ? load4(tail + (int64_t)win * D + col) : f32x4{0.f, 0.f, 0.f, 0.f};
-  for (uint64_t w2 = (uint64_t)win + 1; w2 * W < n_valid && srow[w2 * W] == r; ++w2) {
-    if (active) {
-      const f32x4 h = load4(head + (int64_t)w2 * D + col);
-      acc.x += h.x; acc.y += h.y; acc.z += h.z; acc.w += h.w;
-    }
+  const uint32_t p = (uint32_t)start64 + W - 1;
+  const uint32_t r = srow[p];
+  const uint32_t u = starts_before[p] + ((p == 0 || srow[p - 1] != r) ? 1u : 0u) - 1u;  // segment of p
+  const uint32_t last = (seg_off[u + 1] - 1u) / W;  // last window holding a piece of the row
+  const uint32_t cnt = last - win;                   // following windows, each with a head partial
+  const uint32_t share = (cnt + NG - 1) / NG;
+  const uint32_t f0 = win + 1 + g * share;
+  const uint32_t f1 = (f0 + share < last + 1) ? f0 + share : last + 1;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (uint32_t w2 = f0; w2 < f1; w2 += 4) {
+    f32x4 h[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      h[k] = (active && w2 + k < f1) ? load4(head + (int64_t)(w2 + k) * D + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { acc.x += h[k].x; acc.y += h[k].y; acc.z += h[k].z; acc.w += h[k].w; }
   }
-  if (active) sgd_update4(table + (int64_t)r * D + col, acc, lr);
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  if (g == 0 && active) {
+    f32x4 tot = load4(tail + (int64_t)win * D + col);
+#pragma unroll
+    for (int gg = 0; gg < NG; ++gg) {
+      const f32x4 q = part[gg * LPR + sub];
+      tot.x += q.x; tot.y += q.y; tot.z += q.z; tot.w += q.w;
+    }
+    sgd_update4(table + (int64_t)r * D + col, tot, lr);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -389,7 +448,7 @@ static EmbLayout emb_layout(const hctr_emb_desc* d, int64_t nnz_max) {
   L.krow0 = at(n * 4); L.vbag0 = at(n * 4); L.krow1 = at(n * 4); L.vbag1 = at(n * 4);
   L.hist = at((size_t)L.sort.hist_count * 4);
   size_t scan_n = L.sort.hist_count > n ? L.sort.hist_count : n;
-  L.scan_tmp = at(scan_tmp_count((uint32_t)scan_n) * 4);
+  L.scan_tmp = at((scan_tmp_count((uint32_t)scan_n) + 2 * align_up(ceil_div((int64_t)n, 4096), 64) + 64) * 4);
   L.flags = at(n * 4);
   L.uniq = at(n * 4);
   L.seg_off = at((n + 1) * 4);
@@ -533,9 +592,11 @@ static void launch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, 
   const int mean = (d->combiner == HCTR_MEAN && offsets != nullptr) ? 1 : 0;
   hipLaunchKernelGGL((bwd_reduce_windows<T, LPR>), grid, dim3(256), 0, stream, table, d->dim, srow,
                      sbag, (const EmbHeader*)hdr, offsets, mean, dY, lr, head, tail, tflag, L.window);
-  hipLaunchKernelGGL((bwd_reduce_carry<T, LPR>), grid, dim3(256), 0, stream, table, d->dim, srow,
-                     (const EmbHeader*)hdr, lr, (const float*)head, (const float*)tail,
-                     (const uint8_t*)tflag, L.window);
+  dim3 cgrid(L.n_windows, ychunks);
+  hipLaunchKernelGGL((bwd_reduce_carry<T, LPR>), cgrid, dim3(256), 0, stream, table, d->dim, srow,
+                     reinterpret_cast<const uint32_t*>(ws + L.flags),
+                     reinterpret_cast<const uint32_t*>(ws + L.seg_off), (const EmbHeader*)hdr, lr,
+                     (const float*)head, (const float*)tail, (const uint8_t*)tflag, L.window);
 }
 
 template <typename T>
@@ -622,13 +683,14 @@ HCTR_API hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t ba
 
   hipLaunchKernelGGL(bwd_rows, dim3(nb), dim3(256), 0, stream, keys, rows64, offsets, n, n_bags,
                      (uint32_t)desc->num_slots, st, desc->total_rows, k[0], v[0], hdr);
-  HCTR_TRY(radix_sort_pairs(L.sort, L.sort_bits, nullptr, k[0], v[0], k[1], v[1], hist, scan_tmp, stream));
+  HCTR_TRY(radix_sort_pairs(L.sort, nullptr, k[0], v[0], k[1], v[1], hist, scan_tmp, stream));
   const uint32_t* srow = k[L.sort.passes & 1];
   const uint32_t* sbag = v[L.sort.passes & 1];
-  hipLaunchKernelGGL(seg_flags, dim3(nb), dim3(256), 0, stream, srow, n, flags);
-  HCTR_TRY(exclusive_scan_u32(flags, flags, n, scan_tmp, nullptr, stream));
-  hipLaunchKernelGGL(seg_compact, dim3(nb), dim3(256), 0, stream, srow, n, (const uint32_t*)flags, uniq,
-                     seg_off, hdr);
+  const uint32_t seg_tiles = (uint32_t)ceil_div(n, kSegTile);
+  hipLaunchKernelGGL(seg_tile_counts, dim3(seg_tiles), dim3(kSegThreads), 0, stream, srow, n, scan_tmp);
+  HCTR_TRY(exclusive_scan_u32(scan_tmp, scan_tmp, seg_tiles, scan_tmp + align_up(seg_tiles, 64), nullptr, stream));
+  hipLaunchKernelGGL(seg_write, dim3(seg_tiles), dim3(kSegThreads), 0, stream, srow, n,
+                     (const uint32_t*)scan_tmp, flags, uniq, seg_off, hdr);
   if (desc->table_dtype == HCTR_F32)
     dispatch_reduce<float>(desc, L, w, srow, sbag, offsets, dY, lr, stream);
   else

@@ -5,6 +5,7 @@
 // pass (sort (row, bag) pairs by row, then mark run boundaries) and the per-set ordering of cache
 // insertions.
 #include "common.h"
+#include "blockscan.h"
 
 namespace hctr {
 
@@ -14,41 +15,6 @@ namespace hctr {
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 16;
 constexpr uint32_t kScanTile = kScanThreads * kScanItems;  // 4096
-
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    uint32_t t = __shfl_up(v, d);
-    if (lane >= d) v += t;
-  }
-  return v;
-}
-
-// Exclusive scan of one value per thread over a block of NT threads; *block_total gets the sum.
-template <int NT>
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* lds /*[NT/64 + 1]*/,
-                                                         uint32_t* block_total) {
-  constexpr int NW = NT / 64;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t inc = wave_inclusive_scan(v);
-  if (lane == 63) lds[wave] = inc;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t run = 0;
-    for (int w = 0; w < NW; ++w) {
-      uint32_t t = lds[w];
-      lds[w] = run;
-      run += t;
-    }
-    lds[NW] = run;
-  }
-  __syncthreads();
-  uint32_t res = inc - v + lds[wave];
-  *block_total = lds[NW];
-  __syncthreads();  // lds may be reused by the caller right away
-  return res;
-}
 
 __global__ __launch_bounds__(kScanThreads) void scan_tile_sums(const uint32_t* __restrict__ in,
                                                                uint32_t n, uint32_t* __restrict__ sums) {
@@ -123,21 +89,23 @@ hctr_status exclusive_scan_u32(const uint32_t* in, uint32_t* out, uint32_t n, ui
 }
 
 // ------------------------------------------------------------------------------------------------
-// Radix sort: 8-bit digits, tiles of 4096 keys per 256-thread block.  Each of the block's four
-// waves owns 1024 consecutive keys and ranks them 64 at a time with ballot-based digit matching,
-// so equal digits keep their input order (stable).
+// Radix sort: digits of up to 10 bits (so 28-bit row ids take 3 passes), tiles of 4096 keys per
+// 256-thread block.  Each of the block's four waves owns 1024 consecutive keys and ranks them 64 at
+// a time with ballot-based digit matching, so equal digits keep their input order (stable).
 // ------------------------------------------------------------------------------------------------
 constexpr int kSortThreads = 256;
 constexpr int kSortRounds = kSortTile / kSortThreads;  // 16 rounds of 64 keys per wave
+constexpr int kMaxBins = 1 << kSortMaxDigitBits;
 
 __global__ __launch_bounds__(kSortThreads) void sort_hist(const uint32_t* __restrict__ keys,
                                                           uint32_t n_host,
                                                           const uint32_t* __restrict__ n_dev, int shift,
-                                                          uint32_t mask, uint32_t nblk,
+                                                          uint32_t bins, uint32_t nblk,
                                                           uint32_t* __restrict__ hist) {
-  __shared__ uint32_t h[256];
+  __shared__ uint32_t h[kMaxBins];
   const uint32_t n = n_dev ? *n_dev : n_host;
-  h[threadIdx.x] = 0;
+  const uint32_t mask = bins - 1;
+  for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads) h[d] = 0;
   __syncthreads();
   const uint32_t base = blockIdx.x * kSortTile;
   if (base < n) {
@@ -148,20 +116,26 @@ __global__ __launch_bounds__(kSortThreads) void sort_hist(const uint32_t* __rest
     }
   }
   __syncthreads();
-  hist[threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];  // digit-major for the scan
+  for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads)
+    hist[d * nblk + blockIdx.x] = h[d];  // digit-major for the scan
 }
 
+template <int DBITS>
 __global__ __launch_bounds__(kSortThreads) void sort_scatter(
     const uint32_t* __restrict__ kin, const uint32_t* __restrict__ vin, uint32_t* __restrict__ kout,
     uint32_t* __restrict__ vout, uint32_t n_host, const uint32_t* __restrict__ n_dev, int shift,
-    uint32_t mask, uint32_t nblk, const uint32_t* __restrict__ hist_scanned) {
-  __shared__ uint32_t cnt[kSortThreads / 64][256];
+    uint32_t bins, uint32_t nblk, const uint32_t* __restrict__ hist_scanned) {
+  constexpr int BINS_MAX = 1 << DBITS;
+  __shared__ uint32_t cnt[kSortThreads / 64][BINS_MAX];
   const uint32_t n = n_dev ? *n_dev : n_host;
+  const uint32_t mask = bins - 1;
   const uint32_t base = blockIdx.x * kSortTile;
   if (base >= n) return;  // whole block leaves together
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads) {
 #pragma unroll
-  for (int w = 0; w < kSortThreads / 64; ++w) cnt[w][threadIdx.x] = 0;
+    for (int w = 0; w < kSortThreads / 64; ++w) cnt[w][d] = 0;
+  }
   __syncthreads();
 
   const uint32_t wbase = base + wave * (kSortTile / 4);
@@ -170,13 +144,16 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(
 #pragma unroll
   for (int r = 0; r < kSortRounds; ++r) {
     const uint32_t idx = wbase + r * 64 + lane;
+    key[r] = idx < n ? kin[idx] : 0xFFFFFFFFu;
+  }
+#pragma unroll
+  for (int r = 0; r < kSortRounds; ++r) {
+    const uint32_t idx = wbase + r * 64 + lane;
     const bool valid = idx < n;
-    const uint32_t k = valid ? kin[idx] : 0xFFFFFFFFu;
-    key[r] = k;
-    const uint32_t d = (k >> shift) & mask;
+    const uint32_t d = (key[r] >> shift) & mask;
     uint64_t peers = __ballot(valid);
 #pragma unroll
-    for (int b = 0; b < 8; ++b) {
+    for (int b = 0; b < DBITS; ++b) {
       const bool bit = (d >> b) & 1u;
       const uint64_t vote = __ballot(bit);
       peers &= bit ? vote : ~vote;
@@ -189,8 +166,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(
     rank[r] = old + (uint32_t)__popcll(lower);
   }
   __syncthreads();
-  {
-    const uint32_t d = threadIdx.x;
+  for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads) {
     uint32_t run = hist_scanned[d * nblk + blockIdx.x];
 #pragma unroll
     for (int w = 0; w < kSortThreads / 64; ++w) {
@@ -214,29 +190,41 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(
 
 SortPlan sort_plan(uint32_t n_max, int bits) {
   SortPlan p;
+  if (bits < 1) bits = 1;
   p.n_max = n_max;
   p.n_blocks = (uint32_t)ceil_div(n_max > 0 ? n_max : 1, kSortTile);
-  p.hist_count = 256u * p.n_blocks;
-  p.passes = (bits + 7) / 8;
+  p.passes = (bits + kSortMaxDigitBits - 1) / kSortMaxDigitBits;
+  uint32_t max_bins = 0;
+  for (int i = 0; i < p.passes; ++i) {  // spread the bits evenly: 28 -> 10, 9, 9
+    p.digit_bits[i] = bits / p.passes + (i < bits % p.passes ? 1 : 0);
+    if ((1u << p.digit_bits[i]) > max_bins) max_bins = 1u << p.digit_bits[i];
+  }
+  p.hist_count = max_bins * p.n_blocks;
   return p;
 }
 
-hctr_status radix_sort_pairs(const SortPlan& plan, int bits, const uint32_t* n_dev, uint32_t* keys0,
+hctr_status radix_sort_pairs(const SortPlan& plan, const uint32_t* n_dev, uint32_t* keys0,
                              uint32_t* vals0, uint32_t* keys1, uint32_t* vals1, uint32_t* hist,
                              uint32_t* scan_tmp, hipStream_t stream) {
   uint32_t* k[2] = {keys0, keys1};
   uint32_t* v[2] = {vals0, vals1};
+  int shift = 0;
   for (int p = 0; p < plan.passes; ++p) {
-    const int shift = 8 * p;
-    const int nb = bits - shift < 8 ? bits - shift : 8;
-    const uint32_t mask = (1u << nb) - 1u;
+    const int db = plan.digit_bits[p];
+    const uint32_t bins = 1u << db;
     const int src = p & 1, dst = src ^ 1;
     hipLaunchKernelGGL(sort_hist, dim3(plan.n_blocks), dim3(kSortThreads), 0, stream,
-                       (const uint32_t*)k[src], plan.n_max, n_dev, shift, mask, plan.n_blocks, hist);
-    HCTR_TRY(exclusive_scan_u32(hist, hist, plan.hist_count, scan_tmp, nullptr, stream));
-    hipLaunchKernelGGL(sort_scatter, dim3(plan.n_blocks), dim3(kSortThreads), 0, stream,
-                       (const uint32_t*)k[src], (const uint32_t*)v[src], k[dst], v[dst], plan.n_max,
-                       n_dev, shift, mask, plan.n_blocks, (const uint32_t*)hist);
+                       (const uint32_t*)k[src], plan.n_max, n_dev, shift, bins, plan.n_blocks, hist);
+    HCTR_TRY(exclusive_scan_u32(hist, hist, bins * plan.n_blocks, scan_tmp, nullptr, stream));
+    if (db <= 8)
+      hipLaunchKernelGGL((sort_scatter<8>), dim3(plan.n_blocks), dim3(kSortThreads), 0, stream,
+                         (const uint32_t*)k[src], (const uint32_t*)v[src], k[dst], v[dst], plan.n_max,
+                         n_dev, shift, bins, plan.n_blocks, (const uint32_t*)hist);
+    else
+      hipLaunchKernelGGL((sort_scatter<kSortMaxDigitBits>), dim3(plan.n_blocks), dim3(kSortThreads), 0,
+                         stream, (const uint32_t*)k[src], (const uint32_t*)v[src], k[dst], v[dst],
+                         plan.n_max, n_dev, shift, bins, plan.n_blocks, (const uint32_t*)hist);
+    shift += db;
   }
   return launch_status("radix_sort_pairs");
 }

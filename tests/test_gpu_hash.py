@@ -116,9 +116,9 @@ def test_hashed_embedding_forward_backward():
         assert np.array_equal(out_np.view(np.uint32), ref_out.view(np.uint32))
         ref_tab, mag_tab, uniq, cnt = oracle_backward(tab_np, rows, None, 0, batch * S, dY.numpy(), 0.01)
         layer.backward_sgd(batch, to_dev(keys), to_dev(dY), 0.01)
+        g_rows, g_cnt = layer.dedup_result(batch, keys.numel())
         assert layer.invalid_keys() == int((rows < 0).sum())
         layer.reset_invalid_keys()
-        g_rows, g_cnt = layer.dedup_result(batch, keys.numel())
         assert np.array_equal(g_rows.cpu().numpy(), uniq) and np.array_equal(g_cnt.cpu().numpy(), cnt)
         check_table_update(d_table.cpu().numpy(), tab_np, ref_tab, mag_tab, uniq, f"hashed backward {it}")
         tab_np = d_table.cpu().numpy().copy()                            # continue from the GPU's table
