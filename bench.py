@@ -74,7 +74,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--seed", type=int, default=datagen.DEFAULT_SEED)
+    ap.add_argument("--alpha", type=float, default=ALPHA,
+                    help="Zipf exponent of the keys (0 = uniform); anything but the default is an experiment")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--serial", action="store_true",
+                    help="run forward and the whole backward on one stream (no overlap of the key-only half)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of the pooled-output size (for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only; --gpus must be 1 (no collectives, no sharding).")
@@ -99,8 +105,8 @@ def main():
     log(f"table {total} x {DIM} fp32 = {total * DIM * 4 / 1e9:.1f} GB filled in {time.time() - t0:.1f}s")
 
     t0 = time.time()
-    samplers = datagen.make_samplers(table_rows, ALPHA)
-    keys_cpu = [datagen.onehot_keys(args.seed, b, table_rows, BATCH, ALPHA, samplers=samplers)
+    samplers = datagen.make_samplers(table_rows, args.alpha) if args.alpha > 0 else None
+    keys_cpu = [datagen.onehot_keys(args.seed, b, table_rows, BATCH, args.alpha, samplers=samplers)
                 for b in range(N_KEY_BATCHES)]
     del samplers
     keys = [k.to(dev) for k in keys_cpu]
@@ -113,21 +119,45 @@ def main():
     ws = layer.workspace(BATCH, nnz)
     stream = torch.cuda.current_stream()
 
+    # One step = forward + backward of one batch.  The key-only half of backward (key -> row, sort,
+    # run boundaries) depends on nothing but the keys, so it is enqueued on a second stream and runs
+    # beside the forward gather; the dY half waits for both.  --serial keeps everything on one stream.
+    side = torch.cuda.Stream()
+
     def step(i, ev=None):
         k = keys[i % N_KEY_BATCHES]
+        if args.serial:
+            if ev:
+                ev[0].record(stream)
+            layer.forward(BATCH, k, out=out, ws=ws)
+            if ev:
+                ev[1].record(stream)
+            layer.backward_sgd(BATCH, k, dYs[i % 2], LR, ws=ws)
+            if ev:
+                ev[2].record(stream)
+            return
+        side.wait_stream(stream)            # the previous step's apply has finished with ws
         if ev:
+            ev[3].record(side)
+        layer.backward_dedup(BATCH, k, ws=ws, stream=side)
+        if ev:
+            ev[4].record(side)
             ev[0].record(stream)
         layer.forward(BATCH, k, out=out, ws=ws)
         if ev:
             ev[1].record(stream)
-        layer.backward_sgd(BATCH, k, dYs[i % 2], LR, ws=ws)
+        stream.wait_stream(side)
+        layer.backward_apply(BATCH, nnz, dYs[i % 2], LR, ws=ws)
         if ev:
             ev[2].record(stream)
 
+    if args.calibrate_copy:   # a plain copy of known size: reads and writes out.numel()*4 bytes
+        out.copy_(dYs[0])
+        torch.cuda.synchronize()
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i, evs[i])
@@ -135,6 +165,7 @@ def main():
     elapsed = time.perf_counter() - t0
     fwd_ms = np.array([e[0].elapsed_time(e[1]) for e in evs])
     bwd_ms = np.array([e[1].elapsed_time(e[2]) for e in evs])
+    dedup_ms = None if args.serial else np.array([e[3].elapsed_time(e[4]) for e in evs])
     assert layer.invalid_keys(ws) == 0
 
     ms_per_step = elapsed / args.steps * 1e3
@@ -162,16 +193,19 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "DLRM-shaped one-hot: 26 fp32 tables, dim 128, %d rows total, batch 55296, "
-                               "Zipf 1.05, sum, fwd + dedup/segmented-reduce bwd + SGD%s"
-                               % (total, "" if args.scale == 1.0 else f" (tables scaled x{args.scale})"),
+                               "Zipf %g, sum, fwd + dedup/segmented-reduce bwd + SGD%s"
+                               % (total, args.alpha, "" if args.scale == 1.0 else f" (tables scaled x{args.scale})"),
                    "batch": BATCH, "slots": S, "dim": DIM, "keys_per_step": nnz, "distinct_rows_per_step": int(U)},
         "roofline": {"bound": "hbm", "kernel": "fwd_onehot<float,32,4>", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": fwd_bytes, "avg_launch_ms": float(fwd_ms.mean())},
-        "phases": {"forward_ms": float(fwd_ms.mean()), "forward_ms_min": float(fwd_ms.min()),
-                   "backward_ms": float(bwd_ms.mean()), "backward_ms_min": float(bwd_ms.min()),
-                   "forward_keys_per_s": nnz / fwd_s, "backward_keys_per_s": nnz / (float(bwd_ms.mean()) * 1e-3),
-                   "backward_logical_GBs": bwd_bytes / (float(bwd_ms.mean()) * 1e-3) / 1e9,
+        "phases": {"schedule": "serial: forward, backward on one stream" if args.serial else
+                               "backward dedup (keys only) on a second stream beside forward; backward apply after both",
+                   "forward_ms": float(fwd_ms.mean()), "forward_ms_min": float(fwd_ms.min()),
+                   "backward_ms" if args.serial else "backward_apply_ms": float(bwd_ms.mean()),
+                   "backward_dedup_ms": None if args.serial else float(dedup_ms.mean()),
+                   "forward_keys_per_s": nnz / fwd_s,
+                   "backward_logical_bytes": bwd_bytes,
                    "fwd_bwd_logical_GBs": (fwd_bytes + bwd_bytes) / (elapsed / args.steps) / 1e9},
     }
     if not args.no_cpu_baseline:

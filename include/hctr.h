@@ -125,6 +125,22 @@ hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t batch, cons
                                   void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The two halves of hctr_emb_backward_sgd as separate calls, for callers that overlap them with
+ * other work.  hctr_emb_backward_dedup does the key-only part (key -> row, sort, run boundaries): it
+ * reads keys / offsets and writes `ws`, so in direct mode it may run on another stream at the same
+ * time as hctr_emb_forward of the same batch, even on the same workspace (in hashed mode it looks
+ * keys up in the hash and must be ordered after the forward that inserts them).
+ * hctr_emb_backward_apply then reduces dY over the sorted occurrences and updates the table; it
+ * must be ordered after the dedup call on the same `ws`, with the same batch, offsets and nnz.
+ */
+hctr_status hctr_emb_backward_dedup(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
+                                    const int64_t* offsets, int64_t nnz, void* ws, size_t ws_bytes,
+                                    void* stream);
+hctr_status hctr_emb_backward_apply(const hctr_emb_desc* desc, int64_t batch, const int64_t* offsets,
+                                    int64_t nnz, const float* dY, float lr, void* ws, size_t ws_bytes,
+                                    void* stream);
+
+/*
  * Where the last backward call on `ws` left its dedup result (device pointers into ws, valid until
  * ws is reused; `nnz` must be the nnz of that call, the workspace is laid out by it): *num_unique -> one int64 U; *uniq_rows -> uint32 [U] distinct global rows in
  * ascending order; *seg_offsets -> uint32 [U + 1], seg_offsets[u+1] - seg_offsets[u] = number of

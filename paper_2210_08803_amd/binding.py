@@ -54,6 +54,8 @@ def lib() -> C.CDLL:
         "hctr_emb_workspace_init": (i32, [p, sz, p]),
         "hctr_emb_forward": (i32, [dp, i64, p, p, i64, p, p, sz, p]),
         "hctr_emb_backward_sgd": (i32, [dp, i64, p, p, i64, p, f32, p, sz, p]),
+        "hctr_emb_backward_dedup": (i32, [dp, i64, p, p, i64, p, sz, p]),
+        "hctr_emb_backward_apply": (i32, [dp, i64, p, i64, p, f32, p, sz, p]),
         "hctr_emb_dedup_view": (i32, [dp, i64, i64, p, sz, C.POINTER(p), C.POINTER(p), C.POINTER(p)]),
         "hctr_emb_invalid_keys": (i32, [p, sz, p, C.POINTER(i64)]),
         "hctr_hash_storage_bytes": (sz, [i64]),
@@ -79,7 +81,8 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = [
-    "hctr_emb_workspace_bytes", "hctr_emb_workspace_init", "hctr_emb_forward", "hctr_emb_backward_sgd", "hctr_emb_dedup_view",
+    "hctr_emb_workspace_bytes", "hctr_emb_workspace_init", "hctr_emb_forward", "hctr_emb_backward_sgd", "hctr_emb_backward_dedup",
+    "hctr_emb_backward_apply", "hctr_emb_dedup_view",
     "hctr_emb_invalid_keys", "hctr_hash_storage_bytes", "hctr_hash_create", "hctr_hash_workspace_bytes",
     "hctr_hash_insert_or_find", "hctr_hash_size", "hctr_hash_destroy", "hctr_cache_storage_bytes",
     "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_query", "hctr_cache_stats",
@@ -212,6 +215,22 @@ class EmbeddingLayer:
             ws = self.workspace(batch, nnz)
         _check(lib().hctr_emb_backward_sgd(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(dY),
                                            float(lr), _ptr(ws), ws.numel(), _stream(stream)))
+
+    def backward_dedup(self, batch: int, keys: torch.Tensor, offsets: Optional[torch.Tensor] = None,
+                       ws: Optional[torch.Tensor] = None, stream=None) -> None:
+        nnz = keys.numel()
+        if ws is None:
+            ws = self.workspace(batch, nnz)
+        _check(lib().hctr_emb_backward_dedup(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz,
+                                             _ptr(ws), ws.numel(), _stream(stream)))
+
+    def backward_apply(self, batch: int, nnz: int, dY: torch.Tensor, lr: float,
+                       offsets: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                       stream=None) -> None:
+        if ws is None:
+            ws = self.workspace(batch, nnz)
+        _check(lib().hctr_emb_backward_apply(C.byref(self.desc), batch, _ptr(offsets), nnz, _ptr(dY),
+                                             float(lr), _ptr(ws), ws.numel(), _stream(stream)))
 
     def dedup_result(self, batch: int, nnz: int, ws: Optional[torch.Tensor] = None):
         """(unique rows uint32-as-int64 [U], occurrence counts [U]) of the last backward on ws."""

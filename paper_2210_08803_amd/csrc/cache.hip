@@ -82,7 +82,8 @@ __global__ __launch_bounds__(256) void cache_probe(const u64* __restrict__ tags,
     }
   }
   const uint64_t votes = __ballot(match);
-  const uint64_t gmask = WAYS == 64 ? ~0ull : (((1ull << WAYS) - 1ull) << (lane - way));
+  constexpr uint64_t kGroupOnes = WAYS == 64 ? ~0ull : ((1ull << (WAYS & 63)) - 1ull);
+  const uint64_t gmask = kGroupOnes << (lane - way);
   const uint64_t mine = votes & gmask;
   const bool hit = mine != 0;
   if (hit) line = __shfl(line, __ffsll((unsigned long long)mine) - 1);
@@ -173,15 +174,13 @@ __global__ __launch_bounds__(256) void cache_list_new(const HashWsHeader* hdr,
                                                       const uint32_t* __restrict__ first,
                                                       const uint32_t* __restrict__ rank, u64 num_sets,
                                                       u64* __restrict__ new_key,
-                                                      uint32_t* __restrict__ sort_set,
-                                                      uint32_t* __restrict__ sort_q) {
+                                                      u64* __restrict__ sort_kv) {
   const uint32_t m = blockIdx.x * 256u + threadIdx.x;
   if (m >= hdr->n_miss || !first[m]) return;
   const uint32_t q = rank[m];
   const u64 key = (u64)keys[miss_pos[m]];
   new_key[q] = key;
-  sort_set[q] = (uint32_t)set_of(key, num_sets);
-  sort_q[q] = q;
+  sort_kv[q] = (set_of(key, num_sets) << 32) | (u64)q;   // sorted by set, payload = first-appearance index
 }
 
 // One group of WAYS lanes per sorted position; the group at the start of a set's run places the
@@ -189,16 +188,15 @@ __global__ __launch_bounds__(256) void cache_list_new(const HashWsHeader* hdr,
 template <int WAYS>
 __global__ __launch_bounds__(256) void cache_place(u64* __restrict__ tags, uint32_t* __restrict__ stamps,
                                                    CacheHeader* hdr, const HashWsHeader* ws_hdr,
-                                                   const uint32_t* __restrict__ sset,
-                                                   const uint32_t* __restrict__ sq,
+                                                   const u64* __restrict__ skv,
                                                    const u64* __restrict__ new_key,
                                                    uint32_t* __restrict__ dst) {
   const uint32_t j = (blockIdx.x * 256u + threadIdx.x) / WAYS;
   const int way = threadIdx.x % WAYS;
   const uint32_t n_new = ws_hdr->n_new;
   if (j >= n_new) return;
-  const uint32_t set = sset[j];
-  if (j > 0 && sset[j - 1] == set) return;  // not the first of its set
+  const uint32_t set = (uint32_t)(skv[j] >> 32);
+  if (j > 0 && (uint32_t)(skv[j - 1] >> 32) == set) return;  // not the first of its set
   const uint32_t epoch = hdr->epoch;
   const uint64_t line = (uint64_t)set * WAYS + way;
   const u64 tag = tags[line];
@@ -215,8 +213,8 @@ __global__ __launch_bounds__(256) void cache_place(u64* __restrict__ tags, uint3
     n_elig += other != ~0ull ? 1u : 0u;
   }
   uint32_t inserted = 0, evicted = 0, skipped = 0;
-  for (uint32_t k = 0; j + k < n_new && sset[j + k] == set; ++k) {
-    const uint32_t q = sq[j + k];
+  for (uint32_t k = 0; j + k < n_new && (uint32_t)(skv[j + k] >> 32) == set; ++k) {
+    const uint32_t q = (uint32_t)skv[j + k];
     if (k < n_elig) {
       if (eligible && pos == k) {
         tags[line] = new_key[q];
@@ -258,8 +256,8 @@ __global__ __launch_bounds__(256) void cache_fill(float* __restrict__ data,
 }
 
 struct CacheWsLayout {
-  size_t header, line_of, flag, idx, miss_pos, scr_slot, first, rank, scan_tmp, scratch, new_key, k0, v0,
-      k1, v1, hist, dst, total;
+  size_t header, line_of, flag, idx, miss_pos, scr_slot, first, rank, scan_tmp, scratch, new_key, kv0, kv1,
+      hist, aux, dst, total;
   uint32_t scratch_cap_max;
   int sort_bits;
   SortPlan sort;
@@ -275,13 +273,13 @@ static CacheWsLayout cache_ws_layout(const hctr_cache* c, int64_t nnz_max) {
   L.header = at(sizeof(HashWsHeader));
   L.line_of = at(n * 4); L.flag = at(n * 4); L.idx = at(n * 4); L.miss_pos = at(n * 4);
   L.scr_slot = at(n * 4); L.first = at(n * 4); L.rank = at(n * 4);
-  size_t scan_n = L.sort.hist_count > n ? L.sort.hist_count : n;
-  L.scan_tmp = at(scan_tmp_count((uint32_t)scan_n) * 4);
+  L.scan_tmp = at(scan_tmp_count((uint32_t)n) * 4);
   L.scratch_cap_max = dedup_scratch_capacity((uint32_t)n);
   L.scratch = at((size_t)L.scratch_cap_max * 16);
   L.new_key = at(n * 8);
-  L.k0 = at(n * 4); L.v0 = at(n * 4); L.k1 = at(n * 4); L.v1 = at(n * 4);
-  L.hist = at((size_t)L.sort.hist_count * 4);
+  L.kv0 = at(n * 8); L.kv1 = at(n * 8);
+  L.hist = at(L.sort.hist_count * 4);
+  L.aux = at(L.sort.aux_count * 4);
   L.dst = at(n * 4);
   L.total = cv.off;
   return L;
@@ -299,12 +297,11 @@ static void launch_probe(const hctr_cache* c, const int64_t* keys, uint32_t nnz,
 
 template <int WAYS>
 static void launch_place(const hctr_cache* c, const HashWsHeader* ws_hdr, uint32_t n_max,
-                         const uint32_t* sset, const uint32_t* sq, const u64* new_key, uint32_t* dst,
-                         hipStream_t stream) {
+                         const u64* skv, const u64* new_key, uint32_t* dst, hipStream_t stream) {
   hipLaunchKernelGGL((cache_place<WAYS>), dim3((uint32_t)ceil_div((int64_t)n_max * WAYS, 256)), dim3(256),
                      0, stream, reinterpret_cast<u64*>(c->storage + c->off_tags),
                      reinterpret_cast<uint32_t*>(c->storage + c->off_stamps),
-                     reinterpret_cast<CacheHeader*>(c->storage), ws_hdr, sset, sq, new_key, dst);
+                     reinterpret_cast<CacheHeader*>(c->storage), ws_hdr, skv, new_key, dst);
 }
 
 template <int LPR>
@@ -470,17 +467,16 @@ HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_
                    &ws_hdr->n_new};
     HCTR_TRY(dedup_first_appearance(keys, n, B, stream));
     u64* new_key = reinterpret_cast<u64*>(w + L.new_key);
-    uint32_t* k[2] = {reinterpret_cast<uint32_t*>(w + L.k0), reinterpret_cast<uint32_t*>(w + L.k1)};
-    uint32_t* v[2] = {reinterpret_cast<uint32_t*>(w + L.v0), reinterpret_cast<uint32_t*>(w + L.v1)};
+    u64* kv[2] = {reinterpret_cast<u64*>(w + L.kv0), reinterpret_cast<u64*>(w + L.kv1)};
     uint32_t* dst = reinterpret_cast<uint32_t*>(w + L.dst);
     hipLaunchKernelGGL(cache_list_new, dim3((uint32_t)ceil_div(n, 256)), dim3(256), 0, stream,
                        (const HashWsHeader*)ws_hdr, keys, (const uint32_t*)B.miss_pos,
-                       (const uint32_t*)B.first, (const uint32_t*)B.rank, (u64)c->num_sets, new_key, k[0], v[0]);
-    HCTR_TRY(radix_sort_pairs(L.sort, &ws_hdr->n_new, k[0], v[0], k[1], v[1],
-                              reinterpret_cast<uint32_t*>(w + L.hist), B.scan_tmp, stream));
-    const uint32_t* sset = k[L.sort.passes & 1];
-    const uint32_t* sq = v[L.sort.passes & 1];
-#define CALL(W) launch_place<W>(c, ws_hdr, n, sset, sq, new_key, dst, stream)
+                       (const uint32_t*)B.first, (const uint32_t*)B.rank, (u64)c->num_sets, new_key, kv[0]);
+    HCTR_TRY(radix_sort_u64(L.sort, &ws_hdr->n_new, reinterpret_cast<uint64_t*>(kv[0]),
+                            reinterpret_cast<uint64_t*>(kv[1]), reinterpret_cast<uint32_t*>(w + L.hist),
+                            reinterpret_cast<uint32_t*>(w + L.aux), false, stream));
+    const u64* skv = kv[L.sort.passes & 1];
+#define CALL(W) launch_place<W>(c, ws_hdr, n, skv, new_key, dst, stream)
     HCTR_BY_WAYS(c->ways, CALL)
 #undef CALL
 #define CALL(LL) launch_fill<LL>(c, ws_hdr, n, new_key, dst, stream)

@@ -69,22 +69,37 @@ size_t scan_tmp_count(uint32_t n);
 hctr_status exclusive_scan_u32(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* tmp,
                                uint32_t* total, hipStream_t stream);
 
-// Stable LSD radix sort of (key, value) uint32 pairs on the low `bits` bits of the key, in
+// Stable LSD radix sort of packed words (key << 32 | value) on the low `bits` bits of the key, in
 // ceil(bits / 10) passes of evenly sized digits.  The element count is *n_dev if n_dev != nullptr
-// (must be <= n_max), else n_max.  Buffers 0 hold the input; the result lands in buffers
-// (passes & 1).  hist holds plan.hist_count words, scan_tmp scan_tmp_count(plan.hist_count).
+// (must be <= n_max), else n_max.  buf0 holds the input; the result lands in buf[passes & 1].
+// hist holds plan.hist_count words; aux holds plan.aux_count words that must be zero on entry
+// (aux_is_zero = false makes the sort clear them itself with one more launch).
 constexpr uint32_t kSortTile = 4096;
+constexpr uint32_t kSortSuper = 16;   // tiles per group with a shared running sum
 constexpr int kSortMaxDigitBits = 10;
 struct SortPlan {
   uint32_t n_max = 0;
-  uint32_t n_blocks = 0;   // tiles of kSortTile keys
-  uint32_t hist_count = 0; // largest bins * n_blocks over the passes
+  uint32_t n_blocks = 0;   // tiles of kSortTile words
+  uint32_t n_super = 0;    // groups of kSortSuper tiles
+  uint32_t max_bins = 0;
+  size_t hist_count = 0;   // max_bins * n_blocks
+  size_t aux_count = 0;    // passes * (1 + n_super) * max_bins
   int passes = 0;
   int digit_bits[4] = {0, 0, 0, 0};
 };
 SortPlan sort_plan(uint32_t n_max, int bits);
-hctr_status radix_sort_pairs(const SortPlan& plan, const uint32_t* n_dev, uint32_t* keys0,
-                             uint32_t* vals0, uint32_t* keys1, uint32_t* vals1, uint32_t* hist,
-                             uint32_t* scan_tmp, hipStream_t stream);
+// Per pass p the aux area holds tot[max_bins] followed by sup[n_super][max_bins].
+constexpr uint32_t kSortDirectSuperMax = 48;  // above this many groups the group sums get their own scan
+inline uint32_t* sort_aux_tot(const SortPlan& plan, uint32_t* aux, int p) {
+  return aux + (size_t)p * (1 + plan.n_super) * plan.max_bins;
+}
+inline uint32_t* sort_aux_sup(const SortPlan& plan, uint32_t* aux, int p) {
+  return sort_aux_tot(plan, aux, p) + plan.max_bins;
+}
+// first_hist_done: the caller has already filled hist[tile][digit] and sup for pass 0 (digit =
+// low digit_bits[0] bits of the key) while producing buf0.
+hctr_status radix_sort_u64(const SortPlan& plan, const uint32_t* n_dev, uint64_t* buf0, uint64_t* buf1,
+                           uint32_t* hist, uint32_t* aux, bool aux_is_zero, hipStream_t stream,
+                           bool first_hist_done = false);
 
 }  // namespace hctr

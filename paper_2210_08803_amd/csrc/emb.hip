@@ -24,13 +24,17 @@ struct EmbHeader {
 };
 static_assert(sizeof(EmbHeader) == 256, "header is one 256-byte block");
 
-__global__ void emb_init_header(EmbHeader* hdr, uint32_t* seg_off, int reset_invalid) {
-  if (threadIdx.x == 0) {
+// Resets the dedup part of the header and clears the counters that later kernels add to.
+__global__ __launch_bounds__(256) void emb_init_header(EmbHeader* hdr, uint32_t* seg_off, int reset_invalid,
+                                                       uint32_t* zero, uint32_t zero_count) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i == 0) {
     if (reset_invalid) hdr->invalid = 0;
     hdr->num_unique = 0;
     hdr->n_valid = 0;
     if (seg_off) seg_off[0] = 0;
   }
+  if (i < zero_count) zero[i] = 0u;
 }
 
 __device__ __forceinline__ void count_invalid(unsigned long long* counter, bool flag) {
@@ -43,7 +47,7 @@ __device__ __forceinline__ void count_invalid(unsigned long long* counter, bool 
 // Forward, one key per bag: a group of LPR lanes copies U rows (U independent 16-byte loads per
 // lane in flight), so a wave covers 64/LPR * U bags.
 // ------------------------------------------------------------------------------------------------
-template <typename T, int LPR, int U, bool HASHED>
+template <typename T, int LPR, int U, bool HASHED, bool NT = true>
 __global__ __launch_bounds__(256) void fwd_onehot(const T* __restrict__ table, int D,
                                                   int64_t total_rows, const int64_t* __restrict__ keys,
                                                   const int64_t* __restrict__ rows64, uint32_t n_bags,
@@ -51,48 +55,50 @@ __global__ __launch_bounds__(256) void fwd_onehot(const T* __restrict__ table, i
                                                   float* __restrict__ out, EmbHeader* hdr) {
   constexpr int VEC = RowVec<T>::VEC;
   const int sub = threadIdx.x % LPR;
-  const uint32_t group = (blockIdx.x * 256u + threadIdx.x) / LPR;
+  const uint32_t group0 = (blockIdx.x * 256u + threadIdx.x) / LPR;
+  const uint32_t n_groups = gridDim.x * (256u / LPR);
   const int col = blockIdx.y * (LPR * VEC) + sub * VEC;
   const bool active = col < D;
-  const uint32_t bag0 = group * U;
-
-  int64_t row[U];
+  uint32_t nbad = 0;  // counted by the first lane of each group
+  for (uint64_t bag0_64 = (uint64_t)group0 * U; bag0_64 < n_bags; bag0_64 += (uint64_t)n_groups * U) {
+    const uint32_t bag0 = (uint32_t)bag0_64;
+    int64_t row[U];
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const uint32_t bag = bag0 + u;
-    row[u] = -1;
-    if (bag < n_bags) {
-      if (HASHED) {
-        const int64_t r = rows64[bag];
-        if (r >= 0 && r < total_rows) row[u] = r;
-      } else {
-        const int64_t k = keys[bag];
-        const uint32_t s = bag % S;
-        if (k >= 0 && k < slots.num[s]) row[u] = slots.base[s] + k;
+    for (int u = 0; u < U; ++u) {
+      const uint32_t bag = bag0 + u;
+      row[u] = -1;
+      if (bag < n_bags) {
+        if (HASHED) {
+          const int64_t r = rows64[bag];
+          if (r >= 0 && r < total_rows) row[u] = r;
+        } else {
+          const int64_t k = keys[bag];
+          const uint32_t s = bag % S;
+          if (k >= 0 && k < slots.num[s]) row[u] = slots.base[s] + k;
+        }
+        nbad += (sub == 0 && row[u] < 0) ? 1u : 0u;
+      }
+    }
+    float v[U][VEC];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) v[u][i] = 0.f;
+      if (row[u] >= 0 && active) RowVec<T>::load(table + row[u] * D + col, v[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t bag = bag0 + u;
+      if (bag < n_bags && active) {
+        if (NT) store_stream<VEC>(out + (int64_t)bag * D + col, v[u]);
+        else store_plain<VEC>(out + (int64_t)bag * D + col, v[u]);
       }
     }
   }
-  float v[U][VEC];
+  if (blockIdx.y == 0 && __ballot(nbad != 0) != 0) {  // rare: add the groups' counts across the wave
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) v[u][i] = 0.f;
-    if (row[u] >= 0 && active) RowVec<T>::load(table + row[u] * D + col, v[u]);
-  }
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const uint32_t bag = bag0 + u;
-    if (bag < n_bags && active) store_stream<VEC>(out + (int64_t)bag * D + col, v[u]);
-  }
-  if (blockIdx.y == 0) {
-    uint32_t nbad = 0;  // counted by the first lane of each group
-#pragma unroll
-    for (int u = 0; u < U; ++u) nbad += ((sub == 0) && (bag0 + u < n_bags) && row[u] < 0) ? 1u : 0u;
-    if (__ballot(nbad != 0) != 0) {  // rare: add the groups' counts across the wave
-#pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) nbad += __shfl_xor(nbad, d);
-      if ((threadIdx.x & 63) == 0) atomicAdd(&hdr->invalid, (unsigned long long)nbad);
-    }
+    for (int d = 32; d >= 1; d >>= 1) nbad += __shfl_xor(nbad, d);
+    if ((threadIdx.x & 63) == 0) atomicAdd(&hdr->invalid, (unsigned long long)nbad);
   }
 }
 
@@ -195,98 +201,150 @@ __global__ __launch_bounds__(256) void bwd_rows(const int64_t* __restrict__ keys
                                                 const int64_t* __restrict__ rows64,
                                                 const int64_t* __restrict__ offsets, uint32_t nnz,
                                                 uint32_t n_bags, uint32_t S, const SlotTable slots,
-                                                int64_t total_rows, uint32_t* __restrict__ krow,
-                                                uint32_t* __restrict__ vbag, EmbHeader* hdr) {
-  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-  bool bad = false;
-  if (i < nnz) {
-    uint32_t bag = i;
-    if (offsets != nullptr) {  // the bag with offsets[bag] <= i < offsets[bag + 1]
-      uint32_t lo = 0, hi = n_bags - 1;
-      while (lo < hi) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (offsets[mid + 1] <= (int64_t)i) lo = mid + 1; else hi = mid;
+                                                int64_t total_rows, uint64_t* __restrict__ kv,
+                                                EmbHeader* hdr, uint32_t bins,
+                                                uint32_t* __restrict__ hist, uint32_t* __restrict__ sup) {
+  // One sort tile per block, so the block can also deliver the tile's histogram of the first sort
+  // digit (the low bits of the row) and spare the sort its first counting pass.
+  __shared__ uint32_t h[1 << kSortMaxDigitBits];
+  const uint32_t mask = bins - 1;
+  for (uint32_t d = threadIdx.x; d < bins; d += 256) h[d] = 0;
+  __syncthreads();
+  uint32_t nbad = 0;
+#pragma unroll 4
+  for (int it = 0; it < (int)(kSortTile / 256); ++it) {
+    const uint32_t i = blockIdx.x * kSortTile + it * 256u + threadIdx.x;
+    if (i < nnz) {
+      uint32_t bag = i;
+      if (offsets != nullptr) {  // the bag with offsets[bag] <= i < offsets[bag + 1]
+        uint32_t lo = 0, hi = n_bags - 1;
+        while (lo < hi) {
+          const uint32_t mid = (lo + hi) >> 1;
+          if (offsets[mid + 1] <= (int64_t)i) lo = mid + 1; else hi = mid;
+        }
+        bag = lo;
       }
-      bag = lo;
+      int64_t row = -1;
+      if (rows64 != nullptr) {
+        const int64_t r = rows64[i];
+        if (r >= 0 && r < total_rows) row = r;
+      } else {
+        const int64_t k = keys[i];
+        const uint32_t s = bag % S;
+        if (k >= 0 && k < slots.num[s]) row = slots.base[s] + k;
+      }
+      const uint32_t r32 = row < 0 ? kNoRow : (uint32_t)row;
+      nbad += row < 0 ? 1u : 0u;
+      kv[i] = ((uint64_t)r32 << 32) | bag;
+      atomicAdd(&h[r32 & mask], 1u);
     }
-    int64_t row = -1;
-    if (rows64 != nullptr) {
-      const int64_t r = rows64[i];
-      if (r >= 0 && r < total_rows) row = r;
-    } else {
-      const int64_t k = keys[i];
-      const uint32_t s = bag % S;
-      if (k >= 0 && k < slots.num[s]) row = slots.base[s] + k;
-    }
-    bad = row < 0;
-    krow[i] = bad ? kNoRow : (uint32_t)row;
-    vbag[i] = bag;
   }
-  count_invalid(&hdr->invalid, bad);
+  __syncthreads();
+  uint32_t* hrow = hist + (uint64_t)blockIdx.x * bins;
+  uint32_t* srow = sup + (uint64_t)(blockIdx.x / kSortSuper) * bins;
+  for (uint32_t d = threadIdx.x; d < bins; d += 256) {
+    const uint32_t c = h[d];
+    hrow[d] = c;
+    if (c) atomicAdd(&srow[d], c);
+  }
+  if (__ballot(nbad != 0) != 0) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) nbad += __shfl_xor(nbad, d);
+    if ((threadIdx.x & 63) == 0) atomicAdd(&hdr->invalid, (unsigned long long)nbad);
+  }
 }
 
 // Backward step 3: run boundaries of the sorted rows = the distinct rows of the batch.  A position
-// starts a segment if it holds a real row that differs from its left neighbour.  Two tiled passes
-// around one small scan: count the starts per tile, then number them and write the unique rows,
-// the segment offsets and, per position, the number of starts before it.
-constexpr int kSegThreads = 256;
-constexpr int kSegItems = 16;
-constexpr uint32_t kSegTile = kSegThreads * kSegItems;
+// starts a segment if it holds a real row that differs from its left neighbour.  Two kernels over
+// tiles of 4096 positions (a wave owns 1024 consecutive ones and finds starts 64 at a time with a
+// ballot): the first counts the starts per tile and adds them to a per-64-tiles sum; the second
+// derives its tile's first segment number from those, then numbers the starts and writes the
+// unique rows, the segment offsets and, per position, the number of starts before it.
+constexpr uint32_t kSegTile = 4096;
+constexpr uint32_t kSegSuper = 64;
 
-__device__ __forceinline__ uint32_t seg_start(const uint32_t* __restrict__ srow, uint32_t i) {
-  const uint32_t r = srow[i];
-  return (r != kNoRow && (i == 0 || srow[i - 1] != r)) ? 1u : 0u;
+__device__ __forceinline__ uint64_t seg_start_mask(const uint64_t* __restrict__ skv, uint32_t idx, uint32_t n,
+                                                   uint32_t* row_out) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t row = idx < n ? (uint32_t)(skv[idx] >> 32) : kNoRow;
+  uint32_t prev = __shfl_up(row, 1);
+  if (lane == 0) prev = (idx > 0 && idx < n) ? (uint32_t)(skv[idx - 1] >> 32) : kNoRow;
+  *row_out = row;
+  return __ballot(row != kNoRow && (idx == 0 || prev != row));
 }
 
-__global__ __launch_bounds__(kSegThreads) void seg_tile_counts(const uint32_t* __restrict__ srow,
-                                                               uint32_t n, uint32_t* __restrict__ sums) {
-  __shared__ uint32_t lds[kSegThreads / 64 + 1];
-  const uint32_t base = blockIdx.x * kSegTile;
-  uint32_t s = 0;
-#pragma unroll
-  for (int i = 0; i < kSegItems; ++i) {
-    const uint32_t idx = base + i * kSegThreads + threadIdx.x;
-    if (idx < n) s += seg_start(srow, idx);
+__global__ __launch_bounds__(256) void seg_count(const uint64_t* __restrict__ skv, uint32_t n,
+                                                 uint32_t* __restrict__ counts, uint32_t* __restrict__ segsup) {
+  __shared__ uint32_t wsum[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t wbase = blockIdx.x * kSegTile + wave * 1024u;
+  uint32_t c = 0;
+#pragma unroll 4
+  for (int r = 0; r < 16; ++r) {
+    uint32_t row;
+    c += (uint32_t)__popcll(seg_start_mask(skv, wbase + r * 64 + lane, n, &row));
   }
-  uint32_t total;
-  block_exclusive_scan<kSegThreads>(s, lds, &total);
-  if (threadIdx.x == 0) sums[blockIdx.x] = total;
+  if (lane == 0) wsum[wave] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t t = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    counts[blockIdx.x] = t;
+    if (t) atomicAdd(&segsup[blockIdx.x / kSegSuper], t);
+  }
 }
 
-__global__ __launch_bounds__(kSegThreads) void seg_write(const uint32_t* __restrict__ srow, uint32_t n,
-                                                         const uint32_t* __restrict__ tile_base,
-                                                         uint32_t* __restrict__ starts_before,
-                                                         uint32_t* __restrict__ uniq,
-                                                         uint32_t* __restrict__ seg_off, EmbHeader* hdr) {
-  __shared__ uint32_t lds[kSegThreads / 64 + 1];
-  const uint32_t base = blockIdx.x * kSegTile + threadIdx.x * kSegItems;
-  uint32_t f[kSegItems];
-  uint32_t s = 0;
+__global__ __launch_bounds__(256) void seg_write(const uint64_t* __restrict__ skv, uint32_t n,
+                                                 const uint32_t* __restrict__ counts,
+                                                 const uint32_t* __restrict__ segsup,
+                                                 uint32_t* __restrict__ starts_before,
+                                                 uint32_t* __restrict__ uniq,
+                                                 uint32_t* __restrict__ seg_off, EmbHeader* hdr) {
+  __shared__ uint32_t red[4];
+  __shared__ uint32_t wsum[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t tile = blockIdx.x;
+  const uint32_t g = tile / kSegSuper;
+  // number of starts in all earlier tiles
+  uint32_t part = 0;
+  for (uint32_t i = threadIdx.x; i < g; i += 256) part += segsup[i];
+  if (g * kSegSuper + threadIdx.x < tile) part += counts[g * kSegSuper + threadIdx.x];
 #pragma unroll
-  for (int i = 0; i < kSegItems; ++i) {
-    f[i] = (base + i < n) ? seg_start(srow, base + i) : 0u;
-    s += f[i];
+  for (int d = 32; d >= 1; d >>= 1) part += __shfl_xor(part, d);
+  if (lane == 0) red[wave] = part;
+
+  const uint32_t wbase = tile * kSegTile + wave * 1024u;
+  uint64_t m[16];
+  uint32_t row[16];
+  uint32_t c = 0;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    m[r] = seg_start_mask(skv, wbase + r * 64 + lane, n, &row[r]);
+    c += (uint32_t)__popcll(m[r]);
   }
-  uint32_t total;
-  uint32_t run = block_exclusive_scan<kSegThreads>(s, lds, &total) + tile_base[blockIdx.x];
+  if (lane == 0) wsum[wave] = c;
+  __syncthreads();
+  uint32_t run = red[0] + red[1] + red[2] + red[3];
+  for (int w = 0; w < wave; ++w) run += wsum[w];
+  const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
-  for (int i = 0; i < kSegItems; ++i) {
-    const uint32_t p = base + i;
+  for (int r = 0; r < 16; ++r) {
+    const uint32_t p = wbase + r * 64 + lane;
     if (p < n) {
-      starts_before[p] = run;
-      const uint32_t r = srow[p];
-      if (f[i]) {
-        uniq[run] = r;
-        seg_off[run] = p;
+      const uint32_t before = run + (uint32_t)__popcll(m[r] & below);
+      const bool start = (m[r] >> lane) & 1ull;
+      starts_before[p] = before;
+      if (start) {
+        uniq[before] = row[r];
+        seg_off[before] = p;
       }
-      if (r != kNoRow && (p == n - 1 || srow[p + 1] == kNoRow)) {  // last real row closes the last segment
-        const uint32_t U = run + f[i];
+      if (row[r] != kNoRow && (p == n - 1 || (uint32_t)(skv[p + 1] >> 32) == kNoRow)) {
+        const uint32_t U = before + (start ? 1u : 0u);  // last real row closes the last segment
         seg_off[U] = p + 1;
         hdr->n_valid = p + 1;
         hdr->num_unique = (long long)U;
       }
     }
-    run += f[i];
+    run += (uint32_t)__popcll(m[r]);
   }
 }
 
@@ -300,7 +358,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_write(const uint32_t* __restr
 // ------------------------------------------------------------------------------------------------
 template <typename T, int LPR>
 __global__ __launch_bounds__(256) void bwd_reduce_windows(
-    T* __restrict__ table, int D, const uint32_t* __restrict__ srow, const uint32_t* __restrict__ sbag,
+    T* __restrict__ table, int D, const uint64_t* __restrict__ skv,
     const EmbHeader* __restrict__ hdr, const int64_t* __restrict__ offsets, int mean,
     const float* __restrict__ dY, float lr, float* __restrict__ head, float* __restrict__ tail,
     uint8_t* __restrict__ tail_flag, uint32_t W) {
@@ -314,8 +372,8 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
   const uint32_t start = (uint32_t)start64;
   const uint32_t end = (n_valid - start < W) ? n_valid : start + W;
 
-  uint32_t cur = srow[start];
-  bool before = start > 0 && srow[start - 1] == cur;
+  uint32_t cur = (uint32_t)(skv[start] >> 32);
+  bool before = start > 0 && (uint32_t)(skv[start - 1] >> 32) == cur;
   bool wrote_tail = false;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 
@@ -335,8 +393,9 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
     uint32_t myrow = kNoRow, mybag = 0;
     float myw = 1.f;
     if (sub < cnt) {
-      myrow = srow[p0 + sub];
-      mybag = sbag[p0 + sub];
+      const uint64_t w64 = skv[p0 + sub];
+      myrow = (uint32_t)(w64 >> 32);
+      mybag = (uint32_t)w64;
       if (mean) myw = 1.0f / (float)(offsets[mybag + 1] - offsets[mybag]);
     }
     for (int q0 = 0; q0 < cnt; q0 += 4) {
@@ -366,7 +425,7 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
       }
     }
   }
-  const bool continues = end < n_valid && srow[end] == cur;
+  const bool continues = end < n_valid && (uint32_t)(skv[end] >> 32) == cur;
   flush(!continues);
   if (sub == 0 && blockIdx.y == 0) tail_flag[win] = wrote_tail ? 1 : 0;
 }
@@ -376,7 +435,7 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
 // partials (4 loads in flight), the shares are staged in LDS and added in group order.
 template <typename T, int LPR>
 __global__ __launch_bounds__(256) void bwd_reduce_carry(
-    T* __restrict__ table, int D, const uint32_t* __restrict__ srow,
+    T* __restrict__ table, int D, const uint64_t* __restrict__ skv,
     const uint32_t* __restrict__ starts_before, const uint32_t* __restrict__ seg_off,
     const EmbHeader* __restrict__ hdr, float lr, const float* __restrict__ head,
     const float* __restrict__ tail, const uint8_t* __restrict__ tail_flag, uint32_t W) {
@@ -392,8 +451,8 @@ __global__ __launch_bounds__(256) void bwd_reduce_carry(
   if (!tail_flag[win]) return;      // block-uniform
   // a tail exists only when the window is full and its last row continues into the next window
   const uint32_t p = (uint32_t)start64 + W - 1;
-  const uint32_t r = srow[p];
-  const uint32_t u = starts_before[p] + ((p == 0 || srow[p - 1] != r) ? 1u : 0u) - 1u;  // segment of p
+  const uint32_t r = (uint32_t)(skv[p] >> 32);
+  const uint32_t u = starts_before[p] + ((p == 0 || (uint32_t)(skv[p - 1] >> 32) != r) ? 1u : 0u) - 1u;  // segment of p
   const uint32_t last = (seg_off[u + 1] - 1u) / W;  // last window holding a piece of the row
   const uint32_t cnt = last - win;                   // following windows, each with a head partial
   const uint32_t share = (cnt + NG - 1) / NG;
@@ -426,9 +485,9 @@ __global__ __launch_bounds__(256) void bwd_reduce_carry(
 // ------------------------------------------------------------------------------------------------
 struct EmbLayout {
   // byte offsets into the workspace (all multiples of 256)
-  size_t header, krow0, vbag0, krow1, vbag1, hist, scan_tmp, flags, uniq, seg_off, head, tail,
+  size_t header, kv0, kv1, hist, aux, seg_counts, flags, uniq, seg_off, head, tail,
       tail_flag, rows64, hash_ws, total;
-  uint32_t window, n_windows;
+  uint32_t window, n_windows, seg_tiles, seg_super;
   int sort_bits;
   SortPlan sort;
 };
@@ -445,10 +504,12 @@ static EmbLayout emb_layout(const hctr_emb_desc* d, int64_t nnz_max) {
   L.window = pick_window(nnz_max);
   L.n_windows = (uint32_t)ceil_div((int64_t)n, L.window);
   L.header = at(sizeof(EmbHeader));
-  L.krow0 = at(n * 4); L.vbag0 = at(n * 4); L.krow1 = at(n * 4); L.vbag1 = at(n * 4);
-  L.hist = at((size_t)L.sort.hist_count * 4);
-  size_t scan_n = L.sort.hist_count > n ? L.sort.hist_count : n;
-  L.scan_tmp = at((scan_tmp_count((uint32_t)scan_n) + 2 * align_up(ceil_div((int64_t)n, 4096), 64) + 64) * 4);
+  L.kv0 = at(n * 8); L.kv1 = at(n * 8);
+  L.hist = at(L.sort.hist_count * 4);
+  L.seg_tiles = (uint32_t)ceil_div((int64_t)n, kSegTile);
+  L.seg_super = (uint32_t)ceil_div(L.seg_tiles, kSegSuper);
+  L.aux = at((L.sort.aux_count + L.seg_super) * 4);   // sort sums, then the per-64-tiles start counts
+  L.seg_counts = at((size_t)L.seg_tiles * 4);
   L.flags = at(n * 4);
   L.uniq = at(n * 4);
   L.seg_off = at((n + 1) * 4);
@@ -498,7 +559,8 @@ static hctr_status validate_desc(const hctr_emb_desc* d) {
 
 static hctr_status validate_batch(const hctr_emb_desc* d, int64_t batch, const int64_t* keys,
                                   const int64_t* offsets, int64_t nnz, const void* io, void* ws,
-                                  size_t ws_bytes, EmbLayout* L) {
+                                  size_t ws_bytes, EmbLayout* L, bool need_io = true,
+                                  bool need_keys = true) {
   HCTR_TRY(validate_desc(d));
   if (batch < 0 || nnz < 0) return fail(HCTR_E_INVALID_ARG, "batch %lld / nnz %lld negative",
                                         (long long)batch, (long long)nnz);
@@ -509,8 +571,8 @@ static hctr_status validate_batch(const hctr_emb_desc* d, int64_t batch, const i
     return fail(HCTR_E_INVALID_ARG, "offsets == NULL needs nnz == batch*num_slots (%lld != %lld)",
                 (long long)nnz, (long long)n_bags);
   if (batch == 0 && nnz != 0) return fail(HCTR_E_INVALID_ARG, "nnz must be 0 when batch is 0");
-  if (nnz > 0 && !keys) return fail(HCTR_E_NULL_PTR, "keys is NULL");
-  if (n_bags > 0 && !io) return fail(HCTR_E_NULL_PTR, "out / dY is NULL");
+  if (nnz > 0 && !keys && need_keys) return fail(HCTR_E_NULL_PTR, "keys is NULL");
+  if (n_bags > 0 && !io && need_io) return fail(HCTR_E_NULL_PTR, "out / dY is NULL");
   if (io && (uintptr_t)io % 16 != 0) return fail(HCTR_E_INVALID_ARG, "out / dY must be 16-byte aligned");
   *L = emb_layout(d, nnz);
   if (!ws) return fail(HCTR_E_WORKSPACE, "workspace is NULL");
@@ -579,9 +641,8 @@ static void dispatch_forward(int lpr, const hctr_emb_desc* d, const int64_t* key
 }
 
 template <typename T, int LPR>
-static void launch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, const uint32_t* srow,
-                          const uint32_t* sbag, const int64_t* offsets, const float* dY, float lr,
-                          hipStream_t stream) {
+static void launch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, const uint64_t* skv,
+                          const int64_t* offsets, const float* dY, float lr, hipStream_t stream) {
   const uint32_t ychunks = (uint32_t)ceil_div(d->dim, LPR * 4);
   dim3 grid((uint32_t)ceil_div(L.n_windows, 256 / LPR), ychunks);
   T* table = static_cast<T*>(d->table);
@@ -590,27 +651,26 @@ static void launch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, 
   float* tail = reinterpret_cast<float*>(ws + L.tail);
   uint8_t* tflag = reinterpret_cast<uint8_t*>(ws + L.tail_flag);
   const int mean = (d->combiner == HCTR_MEAN && offsets != nullptr) ? 1 : 0;
-  hipLaunchKernelGGL((bwd_reduce_windows<T, LPR>), grid, dim3(256), 0, stream, table, d->dim, srow,
-                     sbag, (const EmbHeader*)hdr, offsets, mean, dY, lr, head, tail, tflag, L.window);
+  hipLaunchKernelGGL((bwd_reduce_windows<T, LPR>), grid, dim3(256), 0, stream, table, d->dim, skv,
+                     (const EmbHeader*)hdr, offsets, mean, dY, lr, head, tail, tflag, L.window);
   dim3 cgrid(L.n_windows, ychunks);
-  hipLaunchKernelGGL((bwd_reduce_carry<T, LPR>), cgrid, dim3(256), 0, stream, table, d->dim, srow,
+  hipLaunchKernelGGL((bwd_reduce_carry<T, LPR>), cgrid, dim3(256), 0, stream, table, d->dim, skv,
                      reinterpret_cast<const uint32_t*>(ws + L.flags),
                      reinterpret_cast<const uint32_t*>(ws + L.seg_off), (const EmbHeader*)hdr, lr,
                      (const float*)head, (const float*)tail, (const uint8_t*)tflag, L.window);
 }
 
 template <typename T>
-static void dispatch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, const uint32_t* srow,
-                            const uint32_t* sbag, const int64_t* offsets, const float* dY, float lr,
-                            hipStream_t stream) {
+static void dispatch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, const uint64_t* skv,
+                            const int64_t* offsets, const float* dY, float lr, hipStream_t stream) {
   int lpr = pow2_ceil((int)ceil_div(d->dim, 4));
   lpr = lpr < 4 ? 4 : (lpr > 64 ? 64 : lpr);
   switch (lpr) {
-    case 4: launch_reduce<T, 4>(d, L, ws, srow, sbag, offsets, dY, lr, stream); break;
-    case 8: launch_reduce<T, 8>(d, L, ws, srow, sbag, offsets, dY, lr, stream); break;
-    case 16: launch_reduce<T, 16>(d, L, ws, srow, sbag, offsets, dY, lr, stream); break;
-    case 32: launch_reduce<T, 32>(d, L, ws, srow, sbag, offsets, dY, lr, stream); break;
-    default: launch_reduce<T, 64>(d, L, ws, srow, sbag, offsets, dY, lr, stream); break;
+    case 4: launch_reduce<T, 4>(d, L, ws, skv, offsets, dY, lr, stream); break;
+    case 8: launch_reduce<T, 8>(d, L, ws, skv, offsets, dY, lr, stream); break;
+    case 16: launch_reduce<T, 16>(d, L, ws, skv, offsets, dY, lr, stream); break;
+    case 32: launch_reduce<T, 32>(d, L, ws, skv, offsets, dY, lr, stream); break;
+    default: launch_reduce<T, 64>(d, L, ws, skv, offsets, dY, lr, stream); break;
   }
 }
 
@@ -652,16 +712,16 @@ HCTR_API hctr_status hctr_emb_forward(const hctr_emb_desc* desc, int64_t batch, 
   return launch_status("hctr_emb_forward");
 }
 
-HCTR_API hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
-                                           const int64_t* offsets, int64_t nnz, const float* dY, float lr,
-                                           void* ws, size_t ws_bytes, void* stream_) {
-  EmbLayout L;
-  HCTR_TRY(validate_batch(desc, batch, keys, offsets, nnz, dY, ws, ws_bytes, &L));
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
-  char* w = static_cast<char*>(ws);
+// B1-B3: key -> row, sort, run boundaries.  Reads keys / offsets only and writes the workspace.
+static hctr_status backward_dedup(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
+                                  const int64_t* offsets, int64_t nnz, const EmbLayout& L, char* w,
+                                  hipStream_t stream) {
   EmbHeader* hdr = reinterpret_cast<EmbHeader*>(w + L.header);
   uint32_t* seg_off = reinterpret_cast<uint32_t*>(w + L.seg_off);
-  hipLaunchKernelGGL(emb_init_header, dim3(1), dim3(64), 0, stream, hdr, seg_off, 0);
+  uint32_t* aux = reinterpret_cast<uint32_t*>(w + L.aux);
+  const uint32_t zero_count = (uint32_t)(L.sort.aux_count + L.seg_super);
+  hipLaunchKernelGGL(emb_init_header, dim3((uint32_t)ceil_div(zero_count, 256)), dim3(256), 0, stream, hdr,
+                     seg_off, 0, aux, zero_count);
   if (nnz == 0) return launch_status("emb_init_header");
   const uint32_t n = (uint32_t)nnz;
   const uint32_t n_bags = (uint32_t)(batch * desc->num_slots);
@@ -673,29 +733,62 @@ HCTR_API hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t ba
   }
   SlotTable st;
   fill_slots(desc, &st);
-  uint32_t* k[2] = {reinterpret_cast<uint32_t*>(w + L.krow0), reinterpret_cast<uint32_t*>(w + L.krow1)};
-  uint32_t* v[2] = {reinterpret_cast<uint32_t*>(w + L.vbag0), reinterpret_cast<uint32_t*>(w + L.vbag1)};
+  uint64_t* kv0 = reinterpret_cast<uint64_t*>(w + L.kv0);
+  uint64_t* kv1 = reinterpret_cast<uint64_t*>(w + L.kv1);
   uint32_t* hist = reinterpret_cast<uint32_t*>(w + L.hist);
-  uint32_t* scan_tmp = reinterpret_cast<uint32_t*>(w + L.scan_tmp);
+  uint32_t* segsup = aux + L.sort.aux_count;
+  uint32_t* seg_counts = reinterpret_cast<uint32_t*>(w + L.seg_counts);
   uint32_t* flags = reinterpret_cast<uint32_t*>(w + L.flags);
   uint32_t* uniq = reinterpret_cast<uint32_t*>(w + L.uniq);
-  const uint32_t nb = (uint32_t)ceil_div(n, 256);
 
-  hipLaunchKernelGGL(bwd_rows, dim3(nb), dim3(256), 0, stream, keys, rows64, offsets, n, n_bags,
-                     (uint32_t)desc->num_slots, st, desc->total_rows, k[0], v[0], hdr);
-  HCTR_TRY(radix_sort_pairs(L.sort, nullptr, k[0], v[0], k[1], v[1], hist, scan_tmp, stream));
-  const uint32_t* srow = k[L.sort.passes & 1];
-  const uint32_t* sbag = v[L.sort.passes & 1];
-  const uint32_t seg_tiles = (uint32_t)ceil_div(n, kSegTile);
-  hipLaunchKernelGGL(seg_tile_counts, dim3(seg_tiles), dim3(kSegThreads), 0, stream, srow, n, scan_tmp);
-  HCTR_TRY(exclusive_scan_u32(scan_tmp, scan_tmp, seg_tiles, scan_tmp + align_up(seg_tiles, 64), nullptr, stream));
-  hipLaunchKernelGGL(seg_write, dim3(seg_tiles), dim3(kSegThreads), 0, stream, srow, n,
-                     (const uint32_t*)scan_tmp, flags, uniq, seg_off, hdr);
+  hipLaunchKernelGGL(bwd_rows, dim3(L.sort.n_blocks), dim3(256), 0, stream, keys, rows64, offsets, n, n_bags,
+                     (uint32_t)desc->num_slots, st, desc->total_rows, kv0, hdr, 1u << L.sort.digit_bits[0],
+                     hist, sort_aux_sup(L.sort, aux, 0));
+  HCTR_TRY(radix_sort_u64(L.sort, nullptr, kv0, kv1, hist, aux, true, stream, true));
+  const uint64_t* skv = (L.sort.passes & 1) ? kv1 : kv0;
+  hipLaunchKernelGGL(seg_count, dim3(L.seg_tiles), dim3(256), 0, stream, skv, n, seg_counts, segsup);
+  hipLaunchKernelGGL(seg_write, dim3(L.seg_tiles), dim3(256), 0, stream, skv, n, (const uint32_t*)seg_counts,
+                     (const uint32_t*)segsup, flags, uniq, seg_off, hdr);
+  return launch_status("hctr_emb_backward_dedup");
+}
+
+// B4-B5: segmented reduction of dY over the sorted occurrences, fused with the SGD row update.
+static hctr_status backward_apply(const hctr_emb_desc* desc, const int64_t* offsets, int64_t nnz,
+                                  const float* dY, float lr, const EmbLayout& L, char* w,
+                                  hipStream_t stream) {
+  if (nnz == 0) return HCTR_OK;
+  const uint64_t* skv = reinterpret_cast<const uint64_t*>(w + ((L.sort.passes & 1) ? L.kv1 : L.kv0));
   if (desc->table_dtype == HCTR_F32)
-    dispatch_reduce<float>(desc, L, w, srow, sbag, offsets, dY, lr, stream);
+    dispatch_reduce<float>(desc, L, w, skv, offsets, dY, lr, stream);
   else
-    dispatch_reduce<__half>(desc, L, w, srow, sbag, offsets, dY, lr, stream);
-  return launch_status("hctr_emb_backward_sgd");
+    dispatch_reduce<__half>(desc, L, w, skv, offsets, dY, lr, stream);
+  return launch_status("hctr_emb_backward_apply");
+}
+
+HCTR_API hctr_status hctr_emb_backward_dedup(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
+                                             const int64_t* offsets, int64_t nnz, void* ws, size_t ws_bytes,
+                                             void* stream) {
+  EmbLayout L;
+  HCTR_TRY(validate_batch(desc, batch, keys, offsets, nnz, nullptr, ws, ws_bytes, &L, false));
+  return backward_dedup(desc, batch, keys, offsets, nnz, L, static_cast<char*>(ws), static_cast<hipStream_t>(stream));
+}
+
+HCTR_API hctr_status hctr_emb_backward_apply(const hctr_emb_desc* desc, int64_t batch, const int64_t* offsets,
+                                             int64_t nnz, const float* dY, float lr, void* ws,
+                                             size_t ws_bytes, void* stream) {
+  EmbLayout L;
+  HCTR_TRY(validate_batch(desc, batch, nullptr, offsets, nnz, dY, ws, ws_bytes, &L, true, false));
+  return backward_apply(desc, offsets, nnz, dY, lr, L, static_cast<char*>(ws), static_cast<hipStream_t>(stream));
+}
+
+HCTR_API hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
+                                           const int64_t* offsets, int64_t nnz, const float* dY, float lr,
+                                           void* ws, size_t ws_bytes, void* stream_) {
+  EmbLayout L;
+  HCTR_TRY(validate_batch(desc, batch, keys, offsets, nnz, dY, ws, ws_bytes, &L));
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  HCTR_TRY(backward_dedup(desc, batch, keys, offsets, nnz, L, static_cast<char*>(ws), stream));
+  return backward_apply(desc, offsets, nnz, dY, lr, L, static_cast<char*>(ws), stream);
 }
 
 HCTR_API hctr_status hctr_emb_dedup_view(const hctr_emb_desc* desc, int64_t batch, int64_t nnz,
@@ -718,8 +811,8 @@ HCTR_API hctr_status hctr_emb_workspace_init(void* ws, size_t ws_bytes, void* st
   if (!ws) return fail(HCTR_E_WORKSPACE, "workspace is NULL");
   if ((uintptr_t)ws % 256 != 0) return fail(HCTR_E_WORKSPACE, "workspace must be 256-byte aligned");
   if (ws_bytes < sizeof(EmbHeader)) return fail(HCTR_E_WORKSPACE, "workspace too small");
-  hipLaunchKernelGGL(emb_init_header, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream),
-                     static_cast<EmbHeader*>(ws), (uint32_t*)nullptr, 1);
+  hipLaunchKernelGGL(emb_init_header, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<EmbHeader*>(ws), (uint32_t*)nullptr, 1, (uint32_t*)nullptr, 0u);
   return launch_status("emb_init_header");
 }
 

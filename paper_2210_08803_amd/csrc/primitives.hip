@@ -89,68 +89,142 @@ hctr_status exclusive_scan_u32(const uint32_t* in, uint32_t* out, uint32_t n, ui
 }
 
 // ------------------------------------------------------------------------------------------------
-// Radix sort: digits of up to 10 bits (so 28-bit row ids take 3 passes), tiles of 4096 keys per
-// 256-thread block.  Each of the block's four waves owns 1024 consecutive keys and ranks them 64 at
-// a time with ballot-based digit matching, so equal digits keep their input order (stable).
+// Radix sort of packed (key << 32 | value) words by the key's low `bits` bits: LSD, digits of up
+// to 10 bits (28-bit row ids take 3 passes), tiles of 4096 words per 256-thread block, two kernels
+// per pass and no device-wide scan kernel in between:
+//   sort_hist     counts the tile's digits into hist[tile][digit] (block-major, coalesced) and adds
+//                 them to tot[digit] and to sup[tile / 16][digit] (sums over groups of 16 tiles);
+//   sort_scatter  derives the tile's global offsets on its own - exclusive scan of tot in LDS, plus
+//                 the sup rows of earlier groups, plus the hist rows of earlier tiles of its group
+//                 (at most n_tiles/16 + 15 coalesced row reads) - then ranks and scatters.
+// Each of a block's four waves owns 1024 consecutive words and ranks them 64 at a time with
+// ballot-based digit matching, so equal digits keep their input order (stable).
 // ------------------------------------------------------------------------------------------------
 constexpr int kSortThreads = 256;
-constexpr int kSortRounds = kSortTile / kSortThreads;  // 16 rounds of 64 keys per wave
+constexpr int kSortRounds = kSortTile / kSortThreads;  // 16 rounds of 64 words per wave
 constexpr int kMaxBins = 1 << kSortMaxDigitBits;
+typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(kSortThreads) void sort_hist(const uint32_t* __restrict__ keys,
-                                                          uint32_t n_host,
+__global__ __launch_bounds__(256) void sort_zero_aux(uint32_t* __restrict__ aux, uint32_t count) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i < count) aux[i] = 0u;
+}
+
+__global__ __launch_bounds__(kSortThreads) void sort_hist(const uint64_t* __restrict__ kv, uint32_t n_host,
                                                           const uint32_t* __restrict__ n_dev, int shift,
-                                                          uint32_t bins, uint32_t nblk,
-                                                          uint32_t* __restrict__ hist) {
+                                                          uint32_t bins, uint32_t* __restrict__ hist,
+                                                          uint32_t* __restrict__ sup) {
   __shared__ uint32_t h[kMaxBins];
   const uint32_t n = n_dev ? *n_dev : n_host;
+  const uint32_t base = blockIdx.x * kSortTile;
+  if (base >= n) return;  // nobody reads the rows of tiles past the end
   const uint32_t mask = bins - 1;
   for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads) h[d] = 0;
   __syncthreads();
-  const uint32_t base = blockIdx.x * kSortTile;
-  if (base < n) {
 #pragma unroll 4
-    for (int i = 0; i < kSortRounds; ++i) {
-      uint32_t idx = base + i * kSortThreads + threadIdx.x;
-      if (idx < n) atomicAdd(&h[(keys[idx] >> shift) & mask], 1u);
-    }
+  for (int i = 0; i < kSortRounds; ++i) {
+    const uint32_t idx = base + i * kSortThreads + threadIdx.x;
+    if (idx < n) atomicAdd(&h[(uint32_t)(kv[idx] >> (32 + shift)) & mask], 1u);
   }
   __syncthreads();
-  for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads)
-    hist[d * nblk + blockIdx.x] = h[d];  // digit-major for the scan
+  uint32_t* row = hist + (uint64_t)blockIdx.x * bins;
+  uint32_t* srow = sup + (uint64_t)(blockIdx.x / kSortSuper) * bins;
+  for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads) {
+    const uint32_t c = h[d];
+    row[d] = c;
+    if (c) atomicAdd(&srow[d], c);
+  }
+}
+
+// For many tiles the per-group sums are scanned once per pass (thread per digit, walking the
+// groups) so that a scatter block reads one row instead of one per earlier group.
+__global__ __launch_bounds__(256) void sort_scan_sup(uint32_t* __restrict__ sup, uint32_t* __restrict__ tot,
+                                                     uint32_t bins, uint32_t n_super) {
+  const uint32_t d = blockIdx.x * 256u + threadIdx.x;
+  if (d >= bins) return;
+  uint32_t run = 0;
+  uint32_t sb = 0;
+  for (; sb + 8 <= n_super; sb += 8) {
+    uint32_t v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = sup[(uint64_t)(sb + k) * bins + d];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { sup[(uint64_t)(sb + k) * bins + d] = run; run += v[k]; }
+  }
+  for (; sb < n_super; ++sb) {
+    const uint32_t v = sup[(uint64_t)sb * bins + d];
+    sup[(uint64_t)sb * bins + d] = run;
+    run += v;
+  }
+  tot[d] = run;
 }
 
 template <int DBITS>
 __global__ __launch_bounds__(kSortThreads) void sort_scatter(
-    const uint32_t* __restrict__ kin, const uint32_t* __restrict__ vin, uint32_t* __restrict__ kout,
-    uint32_t* __restrict__ vout, uint32_t n_host, const uint32_t* __restrict__ n_dev, int shift,
-    uint32_t bins, uint32_t nblk, const uint32_t* __restrict__ hist_scanned) {
+    const uint64_t* __restrict__ in, uint64_t* __restrict__ out, uint32_t n_host,
+    const uint32_t* __restrict__ n_dev, int shift, uint32_t bins, const uint32_t* __restrict__ hist,
+    const uint32_t* __restrict__ tot, const uint32_t* __restrict__ sup, uint32_t n_super,
+    int sup_is_scanned) {
   constexpr int BINS_MAX = 1 << DBITS;
   __shared__ uint32_t cnt[kSortThreads / 64][BINS_MAX];
+  __shared__ uint32_t gbase[BINS_MAX];
+  __shared__ uint32_t scan_lds[kSortThreads / 64 + 1];
   const uint32_t n = n_dev ? *n_dev : n_host;
   const uint32_t mask = bins - 1;
-  const uint32_t base = blockIdx.x * kSortTile;
+  const uint32_t blk = blockIdx.x;
+  const uint32_t base = blk * kSortTile;
   if (base >= n) return;  // whole block leaves together
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  // The tile's words first: their latency hides behind the offset computation below.
+  const uint32_t wbase = base + wave * (kSortTile / 4);
+  uint64_t word[kSortRounds];
+#pragma unroll
+  for (int r = 0; r < kSortRounds; ++r) {
+    const uint32_t idx = wbase + r * 64 + lane;
+    word[r] = idx < n ? in[idx] : ~0ull;
+  }
+
+  // Global offset of each digit for this tile: thread t owns digits 4t .. 4t+3.
+  {
+    const uint32_t d0 = threadIdx.x * 4;
+    u32x4v t4 = {0, 0, 0, 0}, pre = {0, 0, 0, 0};
+    if (d0 < bins) {
+      const uint32_t g = blk / kSortSuper;
+      if (sup_is_scanned) {
+        t4 = *reinterpret_cast<const u32x4v*>(tot + d0);
+        pre = *reinterpret_cast<const u32x4v*>(sup + (uint64_t)g * bins + d0);
+      } else {
+        for (uint32_t sb = 0; sb < n_super; ++sb) {
+          const u32x4v v = *reinterpret_cast<const u32x4v*>(sup + (uint64_t)sb * bins + d0);
+          t4 += v;
+          if (sb < g) pre += v;
+        }
+      }
+      for (uint32_t b = g * kSortSuper; b < blk; ++b) pre += *reinterpret_cast<const u32x4v*>(hist + (uint64_t)b * bins + d0);
+    }
+    uint32_t total;
+    uint32_t run = block_exclusive_scan<kSortThreads>(t4.x + t4.y + t4.z + t4.w, scan_lds, &total);
+    if (d0 < bins) {
+      gbase[d0] = run + pre.x; run += t4.x;
+      gbase[d0 + 1] = run + pre.y; run += t4.y;
+      gbase[d0 + 2] = run + pre.z; run += t4.z;
+      gbase[d0 + 3] = run + pre.w;
+    }
+  }
   for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads) {
 #pragma unroll
     for (int w = 0; w < kSortThreads / 64; ++w) cnt[w][d] = 0;
   }
   __syncthreads();
 
-  const uint32_t wbase = base + wave * (kSortTile / 4);
   const uint64_t below = (1ull << lane) - 1ull;
-  uint32_t key[kSortRounds], rank[kSortRounds];
-#pragma unroll
-  for (int r = 0; r < kSortRounds; ++r) {
-    const uint32_t idx = wbase + r * 64 + lane;
-    key[r] = idx < n ? kin[idx] : 0xFFFFFFFFu;
-  }
+  uint32_t rank[kSortRounds];
 #pragma unroll
   for (int r = 0; r < kSortRounds; ++r) {
     const uint32_t idx = wbase + r * 64 + lane;
     const bool valid = idx < n;
-    const uint32_t d = (key[r] >> shift) & mask;
+    const uint32_t d = (uint32_t)(word[r] >> (32 + shift)) & mask;
     uint64_t peers = __ballot(valid);
 #pragma unroll
     for (int b = 0; b < DBITS; ++b) {
@@ -167,10 +241,10 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(
   }
   __syncthreads();
   for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads) {
-    uint32_t run = hist_scanned[d * nblk + blockIdx.x];
+    uint32_t run = gbase[d];
 #pragma unroll
     for (int w = 0; w < kSortThreads / 64; ++w) {
-      uint32_t c = cnt[w][d];
+      const uint32_t c = cnt[w][d];
       cnt[w][d] = run;
       run += c;
     }
@@ -180,10 +254,8 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(
   for (int r = 0; r < kSortRounds; ++r) {
     const uint32_t idx = wbase + r * 64 + lane;
     if (idx < n) {
-      const uint32_t d = (key[r] >> shift) & mask;
-      const uint32_t pos = cnt[wave][d] + rank[r];
-      kout[pos] = key[r];
-      vout[pos] = vin[idx];
+      const uint32_t d = (uint32_t)(word[r] >> (32 + shift)) & mask;
+      out[cnt[wave][d] + rank[r]] = word[r];
     }
   }
 }
@@ -191,42 +263,56 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(
 SortPlan sort_plan(uint32_t n_max, int bits) {
   SortPlan p;
   if (bits < 1) bits = 1;
+  if (bits > 32) bits = 32;
   p.n_max = n_max;
   p.n_blocks = (uint32_t)ceil_div(n_max > 0 ? n_max : 1, kSortTile);
+  p.n_super = (uint32_t)ceil_div(p.n_blocks, kSortSuper);
   p.passes = (bits + kSortMaxDigitBits - 1) / kSortMaxDigitBits;
-  uint32_t max_bins = 0;
+  p.max_bins = 4;
   for (int i = 0; i < p.passes; ++i) {  // spread the bits evenly: 28 -> 10, 9, 9
     p.digit_bits[i] = bits / p.passes + (i < bits % p.passes ? 1 : 0);
-    if ((1u << p.digit_bits[i]) > max_bins) max_bins = 1u << p.digit_bits[i];
+    if (p.digit_bits[i] < 2) p.digit_bits[i] = 2;   // rows are read four digits at a time
+    if ((1u << p.digit_bits[i]) > p.max_bins) p.max_bins = 1u << p.digit_bits[i];
   }
-  p.hist_count = max_bins * p.n_blocks;
+  p.hist_count = (size_t)p.max_bins * p.n_blocks;
+  p.aux_count = (size_t)p.passes * (1 + p.n_super) * p.max_bins;
   return p;
 }
 
-hctr_status radix_sort_pairs(const SortPlan& plan, const uint32_t* n_dev, uint32_t* keys0,
-                             uint32_t* vals0, uint32_t* keys1, uint32_t* vals1, uint32_t* hist,
-                             uint32_t* scan_tmp, hipStream_t stream) {
-  uint32_t* k[2] = {keys0, keys1};
-  uint32_t* v[2] = {vals0, vals1};
+hctr_status radix_sort_u64(const SortPlan& plan, const uint32_t* n_dev, uint64_t* buf0, uint64_t* buf1,
+                           uint32_t* hist, uint32_t* aux, bool aux_is_zero, hipStream_t stream,
+                           bool first_hist_done) {
+  uint64_t* buf[2] = {buf0, buf1};
+  if (!aux_is_zero)
+    hipLaunchKernelGGL(sort_zero_aux, dim3((uint32_t)ceil_div((int64_t)plan.aux_count, 256)), dim3(256), 0,
+                       stream, aux, (uint32_t)plan.aux_count);
+  const int scan_sup = plan.n_super > kSortDirectSuperMax ? 1 : 0;
   int shift = 0;
   for (int p = 0; p < plan.passes; ++p) {
     const int db = plan.digit_bits[p];
     const uint32_t bins = 1u << db;
+    uint32_t* tot = sort_aux_tot(plan, aux, p);
+    uint32_t* sup = sort_aux_sup(plan, aux, p);
     const int src = p & 1, dst = src ^ 1;
-    hipLaunchKernelGGL(sort_hist, dim3(plan.n_blocks), dim3(kSortThreads), 0, stream,
-                       (const uint32_t*)k[src], plan.n_max, n_dev, shift, bins, plan.n_blocks, hist);
-    HCTR_TRY(exclusive_scan_u32(hist, hist, bins * plan.n_blocks, scan_tmp, nullptr, stream));
+    if (!(p == 0 && first_hist_done))
+      hipLaunchKernelGGL(sort_hist, dim3(plan.n_blocks), dim3(kSortThreads), 0, stream,
+                         (const uint64_t*)buf[src], plan.n_max, n_dev, shift, bins, hist, sup);
+    if (scan_sup)
+      hipLaunchKernelGGL(sort_scan_sup, dim3((uint32_t)ceil_div(bins, 256)), dim3(256), 0, stream, sup, tot,
+                         bins, plan.n_super);
     if (db <= 8)
       hipLaunchKernelGGL((sort_scatter<8>), dim3(plan.n_blocks), dim3(kSortThreads), 0, stream,
-                         (const uint32_t*)k[src], (const uint32_t*)v[src], k[dst], v[dst], plan.n_max,
-                         n_dev, shift, bins, plan.n_blocks, (const uint32_t*)hist);
+                         (const uint64_t*)buf[src], buf[dst], plan.n_max, n_dev, shift, bins,
+                         (const uint32_t*)hist, (const uint32_t*)tot, (const uint32_t*)sup, plan.n_super,
+                         scan_sup);
     else
       hipLaunchKernelGGL((sort_scatter<kSortMaxDigitBits>), dim3(plan.n_blocks), dim3(kSortThreads), 0,
-                         stream, (const uint32_t*)k[src], (const uint32_t*)v[src], k[dst], v[dst],
-                         plan.n_max, n_dev, shift, bins, plan.n_blocks, (const uint32_t*)hist);
+                         stream, (const uint64_t*)buf[src], buf[dst], plan.n_max, n_dev, shift, bins,
+                         (const uint32_t*)hist, (const uint32_t*)tot, (const uint32_t*)sup, plan.n_super,
+                         scan_sup);
     shift += db;
   }
-  return launch_status("radix_sort_pairs");
+  return launch_status("radix_sort_u64");
 }
 
 }  // namespace hctr

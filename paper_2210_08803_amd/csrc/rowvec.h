@@ -50,6 +50,12 @@ __device__ __forceinline__ void store_stream(float* p, const float (&v)[N]) {
   }
 }
 
+template <int N>
+__device__ __forceinline__ void store_plain(float* p, const float (&v)[N]) {
+#pragma unroll
+  for (int i = 0; i < N; i += 4) *reinterpret_cast<f32x4*>(p + i) = f32x4{v[i], v[i + 1], v[i + 2], v[i + 3]};
+}
+
 __device__ __forceinline__ f32x4 load4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
 __device__ __forceinline__ void store4(float* p, f32x4 x) { *reinterpret_cast<f32x4*>(p) = x; }
 

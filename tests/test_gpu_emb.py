@@ -172,3 +172,34 @@ def test_library_is_the_hip_build():
     h = H()
     import os
     assert os.path.exists(h.lib_path()) and h.lib_path().endswith("libhctr.so")
+
+
+def test_split_backward_beside_forward_on_two_streams():
+    """hctr_emb_backward_dedup on a second stream while hctr_emb_forward runs, then
+    hctr_emb_backward_apply: same bits as the single-call backward."""
+    h = H()
+    rows = datagen.scaled_table_rows(1e-3)
+    S, dim, batch = len(rows), 128, 1500
+    ro = datagen.row_offsets(rows)
+    table = datagen.table_rows_at(SEED, torch.arange(int(ro[-1])), dim, torch.float32)
+    keys = to_dev(datagen.onehot_keys(SEED, 3, rows, batch, 1.05))
+    dY = to_dev(datagen.normal_grads(SEED, 3, batch * S * dim).view(batch * S, dim))
+    t1, t2 = to_dev(table), to_dev(table)
+    a = h.EmbeddingLayer(t1, S, 0, ro[:-1], rows)
+    b = h.EmbeddingLayer(t2, S, 0, ro[:-1], rows)
+    out_a = a.forward(batch, keys)
+    a.backward_sgd(batch, keys, dY, 0.01)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    ws = b.workspace(batch, keys.numel())
+    for _ in range(3):                       # several rounds: the workspace is reused across steps
+        t2.copy_(to_dev(table))
+        side.wait_stream(main)
+        b.backward_dedup(batch, keys, ws=ws, stream=side)
+        out_b = b.forward(batch, keys, ws=ws)
+        main.wait_stream(side)
+        b.backward_apply(batch, keys.numel(), dY, 0.01, ws=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out_a, out_b) and torch.equal(t1, t2)
+    ra, ca = a.dedup_result(batch, keys.numel())
+    rb, cb = b.dedup_result(batch, keys.numel(), ws=ws)
+    assert torch.equal(ra, rb) and torch.equal(ca, cb)
