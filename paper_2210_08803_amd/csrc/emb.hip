@@ -432,7 +432,7 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
 
 // One block per window.  A window that holds the first piece of a border-crossing row gathers
 // that row: the block's 256/LPR lane groups each add a contiguous share of the following windows'
-// partials (4 loads in flight), the shares are staged in LDS and added in group order.
+// partials (8 loads in flight), the shares are staged in LDS and added in group order.
 template <typename T, int LPR>
 __global__ __launch_bounds__(256) void bwd_reduce_carry(
     T* __restrict__ table, int D, const uint64_t* __restrict__ skv,
@@ -459,13 +459,13 @@ __global__ __launch_bounds__(256) void bwd_reduce_carry(
   const uint32_t f0 = win + 1 + g * share;
   const uint32_t f1 = (f0 + share < last + 1) ? f0 + share : last + 1;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (uint32_t w2 = f0; w2 < f1; w2 += 4) {
-    f32x4 h[4];
+  for (uint32_t w2 = f0; w2 < f1; w2 += 8) {
+    f32x4 h[8];
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
+    for (int k = 0; k < 8; ++k)
       h[k] = (active && w2 + k < f1) ? load4(head + (int64_t)(w2 + k) * D + col) : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int k = 0; k < 4; ++k) { acc.x += h[k].x; acc.y += h[k].y; acc.z += h[k].z; acc.w += h[k].w; }
+    for (int k = 0; k < 8; ++k) { acc.x += h[k].x; acc.y += h[k].y; acc.z += h[k].z; acc.w += h[k].w; }
   }
   part[threadIdx.x] = acc;
   __syncthreads();

@@ -195,13 +195,28 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(
         t4 = *reinterpret_cast<const u32x4v*>(tot + d0);
         pre = *reinterpret_cast<const u32x4v*>(sup + (uint64_t)g * bins + d0);
       } else {
-        for (uint32_t sb = 0; sb < n_super; ++sb) {
-          const u32x4v v = *reinterpret_cast<const u32x4v*>(sup + (uint64_t)sb * bins + d0);
-          t4 += v;
-          if (sb < g) pre += v;
+        // rows are fetched eight at a time so the loads overlap instead of queueing behind each other
+        for (uint32_t sb0 = 0; sb0 < n_super; sb0 += 8) {
+          u32x4v v[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k)
+            v[k] = sb0 + k < n_super ? *reinterpret_cast<const u32x4v*>(sup + (uint64_t)(sb0 + k) * bins + d0)
+                                     : u32x4v{0, 0, 0, 0};
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            t4 += v[k];
+            if (sb0 + k < g) pre += v[k];
+          }
         }
       }
-      for (uint32_t b = g * kSortSuper; b < blk; ++b) pre += *reinterpret_cast<const u32x4v*>(hist + (uint64_t)b * bins + d0);
+      const uint32_t b_begin = g * kSortSuper;   // at most kSortSuper - 1 = 15 rows of this group
+      u32x4v hrow[kSortSuper - 1];
+#pragma unroll
+      for (uint32_t k = 0; k < kSortSuper - 1; ++k)
+        hrow[k] = b_begin + k < blk ? *reinterpret_cast<const u32x4v*>(hist + (uint64_t)(b_begin + k) * bins + d0)
+                                    : u32x4v{0, 0, 0, 0};
+#pragma unroll
+      for (uint32_t k = 0; k < kSortSuper - 1; ++k) pre += hrow[k];
     }
     uint32_t total;
     uint32_t run = block_exclusive_scan<kSortThreads>(t4.x + t4.y + t4.z + t4.w, scan_lds, &total);
