@@ -77,8 +77,10 @@ def main():
     ap.add_argument("--alpha", type=float, default=ALPHA,
                     help="Zipf exponent of the keys (0 = uniform); anything but the default is an experiment")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--serial", action="store_true",
-                    help="run forward and the whole backward on one stream (no overlap of the key-only half)")
+    ap.add_argument("--schedule", choices=["serial", "overlap", "pipeline"], default="pipeline",
+                    help="how the key-only half of backward is placed in time (see step())")
+    ap.add_argument("--calibrate-gather", action="store_true",
+                    help="also run the forward kernel once on all-distinct rows (known bytes, no cache reuse)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of the pooled-output size (for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -119,14 +121,21 @@ def main():
     ws = layer.workspace(BATCH, nnz)
     stream = torch.cuda.current_stream()
 
-    # One step = forward + backward of one batch.  The key-only half of backward (key -> row, sort,
-    # run boundaries) depends on nothing but the keys, so it is enqueued on a second stream and runs
-    # beside the forward gather; the dY half waits for both.  --serial keeps everything on one stream.
+    # One step = forward + backward (dedup + apply) of one batch.  The key-only half of backward
+    # (key -> row, sort, run boundaries) depends on nothing but the keys, so it can run on a second
+    # stream.  Schedules:
+    #   serial    everything on one stream, in order;
+    #   overlap   dedup(i) beside forward(i), apply(i) after both;
+    #   pipeline  forward(i) alone, then apply(i) beside dedup(i+1) (the next batch's keys are known
+    #             ahead of time, as from a prefetching data reader; two workspaces alternate).
+    # Every schedule runs exactly one forward, one dedup and one apply per step.
     side = torch.cuda.Stream()
+    ws2 = layer.new_workspace(layer.workspace_bytes(BATCH, nnz)) if args.schedule == "pipeline" else None
+    wss = [ws, ws2]
 
     def step(i, ev=None):
         k = keys[i % N_KEY_BATCHES]
-        if args.serial:
+        if args.schedule == "serial":
             if ev:
                 ev[0].record(stream)
             layer.forward(BATCH, k, out=out, ws=ws)
@@ -135,25 +144,52 @@ def main():
             layer.backward_sgd(BATCH, k, dYs[i % 2], LR, ws=ws)
             if ev:
                 ev[2].record(stream)
-            return
-        side.wait_stream(stream)            # the previous step's apply has finished with ws
-        if ev:
-            ev[3].record(side)
-        layer.backward_dedup(BATCH, k, ws=ws, stream=side)
-        if ev:
-            ev[4].record(side)
-            ev[0].record(stream)
-        layer.forward(BATCH, k, out=out, ws=ws)
-        if ev:
-            ev[1].record(stream)
-        stream.wait_stream(side)
-        layer.backward_apply(BATCH, nnz, dYs[i % 2], LR, ws=ws)
-        if ev:
-            ev[2].record(stream)
+        elif args.schedule == "overlap":
+            side.wait_stream(stream)            # the previous step's apply has finished with ws
+            if ev:
+                ev[3].record(side)
+            layer.backward_dedup(BATCH, k, ws=ws, stream=side)
+            if ev:
+                ev[4].record(side)
+                ev[0].record(stream)
+            layer.forward(BATCH, k, out=out, ws=ws)
+            if ev:
+                ev[1].record(stream)
+            stream.wait_stream(side)
+            layer.backward_apply(BATCH, nnz, dYs[i % 2], LR, ws=ws)
+            if ev:
+                ev[2].record(stream)
+        else:
+            w_cur, w_next = wss[i % 2], wss[(i + 1) % 2]
+            if ev:
+                ev[0].record(stream)
+            layer.forward(BATCH, k, out=out, ws=w_cur)
+            if ev:
+                ev[1].record(stream)
+            side.wait_stream(stream)            # apply(i-1), the last reader of w_next, is done
+            if ev:
+                ev[3].record(side)
+            layer.backward_dedup(BATCH, keys[(i + 1) % N_KEY_BATCHES], ws=w_next, stream=side)
+            if ev:
+                ev[4].record(side)
+            layer.backward_apply(BATCH, nnz, dYs[i % 2], LR, ws=w_cur)   # dedup(i) was ordered before forward(i)
+            stream.wait_stream(side)
+            if ev:
+                ev[2].record(stream)
+
+    if args.schedule == "pipeline":             # dedup of the first batch: the pipeline's prologue
+        layer.backward_dedup(BATCH, keys[0], ws=wss[0])
+        torch.cuda.synchronize()
 
     if args.calibrate_copy:   # a plain copy of known size: reads and writes out.numel()*4 bytes
         out.copy_(dYs[0])
         torch.cuda.synchronize()
+    if args.calibrate_gather:  # the forward kernel on nnz DISTINCT rows: no reuse, so it must fetch
+        cal = hctr.EmbeddingLayer(table, 1, hctr.SUM, [0], [total])   # nnz*(8+512) and write nnz*512 bytes
+        cal_keys = torch.randperm(total, device=dev)[:nnz].contiguous()
+        cal.forward(nnz, cal_keys, out=out.view(nnz, 1, DIM))
+        torch.cuda.synchronize()
+        del cal, cal_keys
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -165,7 +201,7 @@ def main():
     elapsed = time.perf_counter() - t0
     fwd_ms = np.array([e[0].elapsed_time(e[1]) for e in evs])
     bwd_ms = np.array([e[1].elapsed_time(e[2]) for e in evs])
-    dedup_ms = None if args.serial else np.array([e[3].elapsed_time(e[4]) for e in evs])
+    dedup_ms = None if args.schedule == "serial" else np.array([e[3].elapsed_time(e[4]) for e in evs])
     assert layer.invalid_keys(ws) == 0
 
     ms_per_step = elapsed / args.steps * 1e3
@@ -199,11 +235,10 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "fwd_onehot<float,32,4>", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": fwd_bytes, "avg_launch_ms": float(fwd_ms.mean())},
-        "phases": {"schedule": "serial: forward, backward on one stream" if args.serial else
-                               "backward dedup (keys only) on a second stream beside forward; backward apply after both",
+        "phases": {"schedule": args.schedule,
                    "forward_ms": float(fwd_ms.mean()), "forward_ms_min": float(fwd_ms.min()),
-                   "backward_ms" if args.serial else "backward_apply_ms": float(bwd_ms.mean()),
-                   "backward_dedup_ms": None if args.serial else float(dedup_ms.mean()),
+                   "backward_ms" if args.schedule == "serial" else "backward_apply_ms": float(bwd_ms.mean()),
+                   "backward_dedup_ms": None if dedup_ms is None else float(dedup_ms.mean()),
                    "forward_keys_per_s": nnz / fwd_s,
                    "backward_logical_bytes": bwd_bytes,
                    "fwd_bwd_logical_GBs": (fwd_bytes + bwd_bytes) / (elapsed / args.steps) / 1e9},
