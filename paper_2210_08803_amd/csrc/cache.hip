@@ -28,7 +28,7 @@ typedef unsigned long long u64;
 constexpr uint32_t kNoLine = 0xFFFFFFFFu;
 
 struct CacheHeader {  // first 256 bytes of the cache storage
-  u64 stats[6];       // queries, hits, misses, inserts, evictions, skipped inserts
+  u64 stats[6];       // queries, hits, (misses = queries - hits, filled in on the host), inserts, evictions, skipped inserts
   uint32_t epoch;
   uint32_t pad[51];
 };
@@ -48,16 +48,21 @@ __global__ __launch_bounds__(256) void cache_clear(u64* tags, uint32_t* stamps, 
   if (i == 0) hdr->epoch = 0;
 }
 
-__global__ void cache_begin(CacheHeader* hdr, HashWsHeader* ws_hdr) {
+__global__ void cache_begin(CacheHeader* hdr, HashWsHeader* ws_hdr, u64 nnz) {
   if (threadIdx.x == 0) {
     hdr->epoch += 1;
+    hdr->stats[0] += nnz;
     ws_hdr->n_miss = 0;
     ws_hdr->n_new = 0;
   }
 }
 
-// Classify every key against the tags as they stand (nothing writes tags in this kernel): one key
-// per group of WAYS lanes, each lane compares one tag.
+// Classify every key against the tags as they stand (nothing writes tags in this kernel).  A group
+// of WAYS lanes compares one tag per lane; each group takes kProbeKeys consecutive keys so that
+// their tag loads are in flight together, and a block reports its hits with a single atomic
+// (one atomic per wave on one address would serialise hundreds of thousands of them).
+constexpr int kProbeKeys = 8;
+
 template <int WAYS>
 __global__ __launch_bounds__(256) void cache_probe(const u64* __restrict__ tags,
                                                    uint32_t* __restrict__ stamps, u64 num_sets,
@@ -66,39 +71,46 @@ __global__ __launch_bounds__(256) void cache_probe(const u64* __restrict__ tags,
                                                    uint32_t* __restrict__ line_of,
                                                    uint8_t* __restrict__ hit_mask,
                                                    uint32_t* __restrict__ miss_flag) {
-  const uint32_t i = (blockIdx.x * 256u + threadIdx.x) / WAYS;
+  __shared__ uint32_t block_hits;
+  if (threadIdx.x == 0) block_hits = 0;
+  __syncthreads();
+  const uint32_t group = (blockIdx.x * 256u + threadIdx.x) / WAYS;
   const int way = threadIdx.x % WAYS;
   const int lane = threadIdx.x & 63;
-  const bool live = i < nnz;
-  const int64_t key = live ? keys[i] : -1;
-  uint32_t line = kNoLine;
-  bool match = false;
-  if (key >= 0) {
-    const u64 set = set_of((u64)key, num_sets);
-    match = tags[set * WAYS + way] == (u64)key;
-    if (match) {
-      line = (uint32_t)(set * WAYS + way);
-      stamps[line] = hdr->epoch;
-    }
-  }
-  const uint64_t votes = __ballot(match);
   constexpr uint64_t kGroupOnes = WAYS == 64 ? ~0ull : ((1ull << (WAYS & 63)) - 1ull);
   const uint64_t gmask = kGroupOnes << (lane - way);
-  const uint64_t mine = votes & gmask;
-  const bool hit = mine != 0;
-  if (hit) line = __shfl(line, __ffsll((unsigned long long)mine) - 1);
-  if (live && way == 0) {
-    line_of[i] = line;
-    if (hit_mask) hit_mask[i] = hit ? 1 : 0;
-    if (miss_flag) miss_flag[i] = (!hit && key >= 0 && key < host_rows) ? 1u : 0u;
+  const uint32_t epoch = hdr->epoch;
+  const uint32_t i0 = group * kProbeKeys;
+
+  int64_t key[kProbeKeys];
+  u64 tag[kProbeKeys];
+  u64 slot[kProbeKeys];
+#pragma unroll
+  for (int j = 0; j < kProbeKeys; ++j) key[j] = (i0 + j < nnz) ? keys[i0 + j] : -1;
+#pragma unroll
+  for (int j = 0; j < kProbeKeys; ++j) {
+    slot[j] = key[j] >= 0 ? set_of((u64)key[j], num_sets) * WAYS + way : 0;
+    tag[j] = key[j] >= 0 ? tags[slot[j]] : kEmptyKey;
   }
-  const uint64_t heads = __ballot(live && way == 0);
-  const uint64_t hits = __ballot(live && way == 0 && hit);
-  if (lane == 0 && heads) {
-    atomicAdd(&hdr->stats[0], (u64)__popcll(heads));
-    atomicAdd(&hdr->stats[1], (u64)__popcll(hits));
-    atomicAdd(&hdr->stats[2], (u64)(__popcll(heads) - __popcll(hits)));
+  uint32_t hits = 0;
+#pragma unroll
+  for (int j = 0; j < kProbeKeys; ++j) {
+    const bool match = key[j] >= 0 && tag[j] == (u64)key[j];
+    if (match) stamps[slot[j]] = epoch;
+    const uint64_t mine = __ballot(match) & gmask;
+    const bool hit = mine != 0;
+    uint32_t line = match ? (uint32_t)slot[j] : kNoLine;
+    if (hit) line = __shfl(line, __ffsll((unsigned long long)mine) - 1);
+    if (way == 0 && i0 + j < nnz) {
+      line_of[i0 + j] = hit ? line : kNoLine;
+      if (hit_mask) hit_mask[i0 + j] = hit ? 1 : 0;
+      if (miss_flag) miss_flag[i0 + j] = (!hit && key[j] >= 0 && key[j] < host_rows) ? 1u : 0u;
+      hits += hit ? 1u : 0u;
+    }
   }
+  if (hits) atomicAdd(&block_hits, hits);
+  __syncthreads();
+  if (threadIdx.x == 0 && block_hits) atomicAdd(&hdr->stats[1], (u64)block_hits);
 }
 
 // Pooled gather, one wave per bag: hits from the cache lines in HBM, misses from the host table.
@@ -191,51 +203,57 @@ __global__ __launch_bounds__(256) void cache_place(u64* __restrict__ tags, uint3
                                                    const u64* __restrict__ skv,
                                                    const u64* __restrict__ new_key,
                                                    uint32_t* __restrict__ dst) {
+  __shared__ uint32_t blk_stats[3];
+  if (threadIdx.x < 3) blk_stats[threadIdx.x] = 0;
+  __syncthreads();
   const uint32_t j = (blockIdx.x * 256u + threadIdx.x) / WAYS;
   const int way = threadIdx.x % WAYS;
   const uint32_t n_new = ws_hdr->n_new;
-  if (j >= n_new) return;
-  const uint32_t set = (uint32_t)(skv[j] >> 32);
-  if (j > 0 && (uint32_t)(skv[j - 1] >> 32) == set) return;  // not the first of its set
-  const uint32_t epoch = hdr->epoch;
-  const uint64_t line = (uint64_t)set * WAYS + way;
-  const u64 tag = tags[line];
-  const uint32_t stamp = stamps[line];
-  // order key of this way in the set's victim list; ways used in this call are not in the list
-  const bool empty = tag == kEmptyKey;
-  const bool eligible = empty || stamp < epoch;
-  const u64 okey = !eligible ? ~0ull : (empty ? (u64)way : (((u64)stamp + 1ull) << 8) | (u64)way);
-  uint32_t pos = 0, n_elig = 0;
-#pragma unroll
-  for (int w = 0; w < WAYS; ++w) {
-    const u64 other = (u64)__shfl((long long)okey, w, WAYS);
-    pos += other < okey ? 1u : 0u;
-    n_elig += other != ~0ull ? 1u : 0u;
-  }
-  uint32_t inserted = 0, evicted = 0, skipped = 0;
-  for (uint32_t k = 0; j + k < n_new && (uint32_t)(skv[j + k] >> 32) == set; ++k) {
-    const uint32_t q = (uint32_t)skv[j + k];
-    if (k < n_elig) {
-      if (eligible && pos == k) {
-        tags[line] = new_key[q];
-        stamps[line] = epoch;
-        dst[q] = (uint32_t)line;
-        evicted += empty ? 0u : 1u;
+  const uint32_t set = j < n_new ? (uint32_t)(skv[j] >> 32) : 0u;
+  const bool leader = j < n_new && !(j > 0 && (uint32_t)(skv[j - 1] >> 32) == set);  // first of its set
+  if (leader) {
+    const uint32_t epoch = hdr->epoch;
+    const uint64_t line = (uint64_t)set * WAYS + way;
+    const u64 tag = tags[line];
+    const uint32_t stamp = stamps[line];
+    // order key of this way in the set's victim list; ways used in this call are not in the list
+    const bool empty = tag == kEmptyKey;
+    const bool eligible = empty || stamp < epoch;
+    const u64 okey = !eligible ? ~0ull : (empty ? (u64)way : (((u64)stamp + 1ull) << 8) | (u64)way);
+    uint32_t pos = 0, n_elig = 0;
+  #pragma unroll
+    for (int w = 0; w < WAYS; ++w) {
+      const u64 other = (u64)__shfl((long long)okey, w, WAYS);
+      pos += other < okey ? 1u : 0u;
+      n_elig += other != ~0ull ? 1u : 0u;
+    }
+    uint32_t inserted = 0, evicted = 0, skipped = 0;
+    for (uint32_t k = 0; j + k < n_new && (uint32_t)(skv[j + k] >> 32) == set; ++k) {
+      const uint32_t q = (uint32_t)skv[j + k];
+      if (k < n_elig) {
+        if (eligible && pos == k) {
+          tags[line] = new_key[q];
+          stamps[line] = epoch;
+          dst[q] = (uint32_t)line;
+          evicted += empty ? 0u : 1u;
+        }
+        inserted += 1;
+      } else {
+        if (way == 0) dst[q] = kNoLine;
+        skipped += 1;
       }
-      inserted += 1;
-    } else {
-      if (way == 0) dst[q] = kNoLine;
-      skipped += 1;
+    }
+    // evicted is per lane; add it up over the group
+  #pragma unroll
+    for (int d = WAYS / 2; d >= 1; d >>= 1) evicted += __shfl_xor(evicted, d, WAYS);
+    if (way == 0) {
+      if (inserted) atomicAdd(&blk_stats[0], inserted);
+      if (evicted) atomicAdd(&blk_stats[1], evicted);
+      if (skipped) atomicAdd(&blk_stats[2], skipped);
     }
   }
-  // evicted is per lane; add it up over the group
-#pragma unroll
-  for (int d = WAYS / 2; d >= 1; d >>= 1) evicted += __shfl_xor(evicted, d, WAYS);
-  if (way == 0) {
-    if (inserted) atomicAdd(&hdr->stats[3], (u64)inserted);
-    if (evicted) atomicAdd(&hdr->stats[4], (u64)evicted);
-    if (skipped) atomicAdd(&hdr->stats[5], (u64)skipped);
-  }
+  __syncthreads();
+  if (threadIdx.x < 3 && blk_stats[threadIdx.x]) atomicAdd(&hdr->stats[3 + threadIdx.x], (u64)blk_stats[threadIdx.x]);
 }
 
 // Copy the rows of the placed keys from the host table into their cache lines.
@@ -288,7 +306,7 @@ static CacheWsLayout cache_ws_layout(const hctr_cache* c, int64_t nnz_max) {
 template <int WAYS>
 static void launch_probe(const hctr_cache* c, const int64_t* keys, uint32_t nnz, uint32_t* line_of,
                          uint8_t* hit_mask, uint32_t* miss_flag, hipStream_t stream) {
-  hipLaunchKernelGGL((cache_probe<WAYS>), dim3((uint32_t)ceil_div((int64_t)nnz * WAYS, 256)), dim3(256), 0,
+  hipLaunchKernelGGL((cache_probe<WAYS>), dim3((uint32_t)ceil_div(ceil_div((int64_t)nnz, kProbeKeys) * WAYS, 256)), dim3(256), 0,
                      stream, reinterpret_cast<const u64*>(c->storage + c->off_tags),
                      reinterpret_cast<uint32_t*>(c->storage + c->off_stamps), (u64)c->num_sets,
                      c->host_rows, reinterpret_cast<CacheHeader*>(c->storage), keys, nnz, line_of,
@@ -442,7 +460,7 @@ HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_
   uint32_t* flag = reinterpret_cast<uint32_t*>(w + L.flag);
   const uint32_t n = (uint32_t)nnz;
 
-  hipLaunchKernelGGL(cache_begin, dim3(1), dim3(64), 0, stream, reinterpret_cast<CacheHeader*>(c->storage), ws_hdr);
+  hipLaunchKernelGGL(cache_begin, dim3(1), dim3(64), 0, stream, reinterpret_cast<CacheHeader*>(c->storage), ws_hdr, (u64)nnz);
   if (n > 0) {
 #define CALL(W) launch_probe<W>(c, keys, n, line_of, hit_mask, insert_missing ? flag : nullptr, stream)
     HCTR_BY_WAYS(c->ways, CALL)
@@ -491,6 +509,7 @@ HCTR_API hctr_status hctr_cache_stats(hctr_cache* c, void* stream, int64_t stats
   HCTR_TRY_HIP(hipMemcpyAsync(stats, c->storage, 6 * sizeof(int64_t), hipMemcpyDeviceToHost,
                               static_cast<hipStream_t>(stream)));
   HCTR_TRY_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  stats[2] = stats[0] - stats[1];   // every queried key is a hit or a miss
   return HCTR_OK;
 }
 
