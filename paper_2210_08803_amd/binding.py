@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
         "hctr_cache_storage_bytes": (sz, [i64, i32, i32]),
         "hctr_cache_create": (i32, [p, sz, i64, i32, i32, p, i64, p, C.POINTER(p)]),
         "hctr_cache_workspace_bytes": (sz, [p, i64]),
+        "hctr_cache_set_small_call_limit": (i32, [p, i64]),
         "hctr_cache_query": (i32, [p, i64, i32, p, p, i64, i32, p, p, p, sz, p]),
         "hctr_cache_stats": (i32, [p, p, C.POINTER(i64)]),
         "hctr_cache_state_view": (i32, [p, C.POINTER(p), C.POINTER(p), C.POINTER(p)]),
@@ -85,7 +86,7 @@ EXPORTS = [
     "hctr_emb_backward_apply", "hctr_emb_dedup_view",
     "hctr_emb_invalid_keys", "hctr_hash_storage_bytes", "hctr_hash_create", "hctr_hash_workspace_bytes",
     "hctr_hash_insert_or_find", "hctr_hash_size", "hctr_hash_destroy", "hctr_cache_storage_bytes",
-    "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_query", "hctr_cache_stats",
+    "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_set_small_call_limit", "hctr_cache_query", "hctr_cache_stats",
     "hctr_cache_state_view", "hctr_cache_destroy", "hctr_last_error",
 ]
 
@@ -275,6 +276,9 @@ class EmbeddingCache:
         if getattr(self, "handle", None):
             lib().hctr_cache_destroy(self.handle)
             self.handle = None
+
+    def set_small_call_limit(self, max_keys: int) -> None:
+        _check(lib().hctr_cache_set_small_call_limit(self.handle, max_keys))
 
     def workspace(self, nnz: int) -> torch.Tensor:
         need = lib().hctr_cache_workspace_bytes(self.handle, nnz)

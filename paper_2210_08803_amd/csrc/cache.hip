@@ -1,16 +1,24 @@
-// Inference embedding cache: set-associative tags probed by groups of `ways` lanes, pooled gather
-// that reads hits from HBM and misses straight from the pinned host table, and a fully parallel
-// insertion that reproduces "insert distinct missing keys in first-appearance order, LRU victim per
-// set at call granularity".
+// Inference embedding cache: set-associative tags probed by groups of `ways` lanes, a pooled
+// gather that reads hits from HBM, and a fully parallel insertion that reproduces "insert the
+// distinct missing keys in first-appearance order, LRU victim per set at call granularity".
 //
 // Insertion without a sequential pass: the victims a set can give up in one call are a fixed list
 // once the call's hits are stamped (empty ways by index, then untouched ways by (stamp, way)),
 // because an inserted way is stamped with the current epoch and cannot be chosen again.  So the
 // k-th distinct missing key of a set (in first-appearance order) takes the k-th entry of that
-// list, or is skipped when the list is shorter.  The per-set order comes from a stable radix sort
-// of (set, first-appearance index) pairs.
+// list, or is skipped when the list is shorter.
+//
+// Two code paths compute exactly the same thing:
+//   * large calls: probe -> first-appearance dedup of the misses (shared with the embedding hash)
+//     -> each distinct missing row is fetched ONCE across the host link into a staging area in
+//     HBM -> gather (hits from cache lines, misses from staging) -> stable radix sort of
+//     (set, first-appearance index) -> per-set placement -> fill from staging;
+//   * small calls (<= kSmallMaxKeys keys): one fused probe+gather kernel (misses read straight
+//     from the pinned host table) and one single-block kernel for the whole insertion, because at
+//     a few hundred keys the cost is kernel launches, not bytes.
 #include "common.h"
 #include "rowvec.h"
+#include "blockscan.h"
 #include "hash_internal.h"
 
 struct hctr_cache {
@@ -20,15 +28,19 @@ struct hctr_cache {
   const float* host_table;
   int64_t host_rows;
   size_t off_tags, off_stamps, off_data;
+  uint32_t epoch;          // number of query calls so far (host copy; kernels get it as an argument)
+  int64_t small_max_keys;  // calls with at most this many keys take the fused small-call kernels
 };
 
 namespace hctr {
 
 typedef unsigned long long u64;
 constexpr uint32_t kNoLine = 0xFFFFFFFFu;
+constexpr uint32_t kStaged = 0x80000000u;  // line_of value: the row is in the staging area at (v & ~kStaged)
+constexpr int kSmallMaxKeys = 4096;
 
 struct CacheHeader {  // first 256 bytes of the cache storage
-  u64 stats[6];       // queries, hits, (misses = queries - hits, filled in on the host), inserts, evictions, skipped inserts
+  u64 stats[6];       // queries, hits, (misses = queries - hits, filled in on the host), inserts, evictions, skipped
   uint32_t epoch;
   uint32_t pad[51];
 };
@@ -48,14 +60,28 @@ __global__ __launch_bounds__(256) void cache_clear(u64* tags, uint32_t* stamps, 
   if (i == 0) hdr->epoch = 0;
 }
 
-__global__ void cache_begin(CacheHeader* hdr, HashWsHeader* ws_hdr, u64 nnz) {
-  if (threadIdx.x == 0) {
-    hdr->epoch += 1;
-    hdr->stats[0] += nnz;
-    ws_hdr->n_miss = 0;
-    ws_hdr->n_new = 0;
+// Position of this way in its set's victim list (ways used in this call are not in the list), and
+// the length of the list.  Called by all WAYS lanes of a group at once, one way per lane.
+template <int WAYS>
+__device__ __forceinline__ void victim_order(u64 tag, uint32_t stamp, uint32_t epoch, int way, bool* eligible,
+                                             bool* empty, uint32_t* pos, uint32_t* n_elig) {
+  *empty = tag == kEmptyKey;
+  *eligible = *empty || stamp < epoch;
+  const u64 okey = !*eligible ? ~0ull : (*empty ? (u64)way : (((u64)stamp + 1ull) << 8) | (u64)way);
+  uint32_t p = 0, ne = 0;
+#pragma unroll
+  for (int w = 0; w < WAYS; ++w) {
+    const u64 other = (u64)__shfl((long long)okey, w, WAYS);
+    p += other < okey ? 1u : 0u;
+    ne += other != ~0ull ? 1u : 0u;
   }
+  *pos = p;
+  *n_elig = ne;
 }
+
+// ------------------------------------------------------------------------------------------------
+// Large calls
+// ------------------------------------------------------------------------------------------------
 
 // Classify every key against the tags as they stand (nothing writes tags in this kernel).  A group
 // of WAYS lanes compares one tag per lane; each group takes kProbeKeys consecutive keys so that
@@ -66,7 +92,7 @@ constexpr int kProbeKeys = 8;
 template <int WAYS>
 __global__ __launch_bounds__(256) void cache_probe(const u64* __restrict__ tags,
                                                    uint32_t* __restrict__ stamps, u64 num_sets,
-                                                   int64_t host_rows, CacheHeader* hdr,
+                                                   int64_t host_rows, CacheHeader* hdr, uint32_t epoch,
                                                    const int64_t* __restrict__ keys, uint32_t nnz,
                                                    uint32_t* __restrict__ line_of,
                                                    uint8_t* __restrict__ hit_mask,
@@ -79,7 +105,6 @@ __global__ __launch_bounds__(256) void cache_probe(const u64* __restrict__ tags,
   const int lane = threadIdx.x & 63;
   constexpr uint64_t kGroupOnes = WAYS == 64 ? ~0ull : ((1ull << (WAYS & 63)) - 1ull);
   const uint64_t gmask = kGroupOnes << (lane - way);
-  const uint32_t epoch = hdr->epoch;
   const uint32_t i0 = group * kProbeKeys;
 
   int64_t key[kProbeKeys];
@@ -110,47 +135,44 @@ __global__ __launch_bounds__(256) void cache_probe(const u64* __restrict__ tags,
   }
   if (hits) atomicAdd(&block_hits, hits);
   __syncthreads();
-  if (threadIdx.x == 0 && block_hits) atomicAdd(&hdr->stats[1], (u64)block_hits);
+  if (threadIdx.x == 0) {
+    if (block_hits) atomicAdd(&hdr->stats[1], (u64)block_hits);
+    if (blockIdx.x == 0) {
+      hdr->epoch = epoch;
+      atomicAdd(&hdr->stats[0], (u64)nnz);
+    }
+  }
 }
 
-// Pooled gather, one wave per bag: hits from the cache lines in HBM, misses from the host table.
+// Where a key's vector lives: cache line, staging row, host row, or nowhere (zeros).
+__device__ __forceinline__ const float* row_source(uint32_t line, int64_t key, const float* data,
+                                                   const float* staging, const float* host_table,
+                                                   int64_t host_rows, int D) {
+  if (line == kNoLine) return (key >= 0 && key < host_rows) ? host_table + key * D : nullptr;
+  if (line & kStaged) return staging + (int64_t)(line & ~kStaged) * D;
+  return data + (int64_t)line * D;
+}
+
+// Pooled gather of one bag by one wave: 64/LPR lane groups take the bag's keys round robin, U row
+// loads each in flight; group partial sums are staged in LDS and added in group order.
 template <int LPR, int U>
-__global__ __launch_bounds__(256) void cache_gather(const float* __restrict__ data,
-                                                    const float* __restrict__ host_table,
-                                                    int64_t host_rows, int D,
-                                                    const int64_t* __restrict__ keys,
-                                                    const uint32_t* __restrict__ line_of,
-                                                    const int64_t* __restrict__ offsets, int64_t hotness,
-                                                    uint32_t n_bags, float* __restrict__ out) {
+__device__ __forceinline__ void gather_bag(const float* __restrict__ data, const float* __restrict__ staging,
+                                           const float* __restrict__ host_table, int64_t host_rows, int D,
+                                           const int64_t* __restrict__ keys,
+                                           const uint32_t* __restrict__ line_of, int64_t b0, int64_t b1,
+                                           bool live, uint32_t bag, float* __restrict__ out, float* part) {
   constexpr int G = 64 / LPR;
-  __shared__ float part[4][(G > 1 ? (G - 1) : 1) * LPR * 4];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
   const int g = lane / LPR, sub = lane % LPR;
   const int col = blockIdx.y * (LPR * 4) + sub * 4;
   const bool active = col < D;
-  const uint32_t bag = blockIdx.x * 4u + wave;
-  const bool live = bag < n_bags;
-  int64_t b0 = 0, b1 = 0;
-  if (live) {
-    b0 = offsets ? offsets[bag] : (int64_t)bag * hotness;
-    b1 = offsets ? offsets[bag + 1] : (int64_t)(bag + 1) * hotness;
-  }
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   for (int64_t j = b0 + g; j < b1; j += G * U) {
     const float* src[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t jj = j + u * G;
-      src[u] = nullptr;
-      if (jj < b1) {
-        const uint32_t line = line_of[jj];
-        if (line != kNoLine) {
-          src[u] = data + (int64_t)line * D;
-        } else {
-          const int64_t k = keys[jj];
-          if (k >= 0 && k < host_rows) src[u] = host_table + k * D;
-        }
-      }
+      src[u] = jj < b1 ? row_source(line_of[jj], keys[jj], data, staging, host_table, host_rows, D) : nullptr;
     }
     f32x4 v[U];
 #pragma unroll
@@ -161,14 +183,14 @@ __global__ __launch_bounds__(256) void cache_gather(const float* __restrict__ da
   }
   if (G > 1) {
     if (g > 0) {
-      float* p = &part[wave][((g - 1) * LPR + sub) * 4];
+      float* p = &part[((g - 1) * LPR + sub) * 4];
       p[0] = acc.x; p[1] = acc.y; p[2] = acc.z; p[3] = acc.w;
     }
     __syncthreads();
     if (g == 0) {
 #pragma unroll
       for (int gg = 1; gg < G; ++gg) {
-        const float* p = &part[wave][((gg - 1) * LPR + sub) * 4];
+        const float* p = &part[((gg - 1) * LPR + sub) * 4];
         acc.x += p[0]; acc.y += p[1]; acc.z += p[2]; acc.w += p[3];
       }
     }
@@ -179,13 +201,37 @@ __global__ __launch_bounds__(256) void cache_gather(const float* __restrict__ da
   }
 }
 
-// Distinct missing keys, in first-appearance order q = 0..n_new-1: key, and (set, q) sort pairs.
+template <int LPR, int U>
+__global__ __launch_bounds__(256) void cache_gather(const float* __restrict__ data,
+                                                    const float* __restrict__ staging,
+                                                    const float* __restrict__ host_table,
+                                                    int64_t host_rows, int D,
+                                                    const int64_t* __restrict__ keys,
+                                                    const uint32_t* __restrict__ line_of,
+                                                    const int64_t* __restrict__ offsets, int64_t hotness,
+                                                    uint32_t n_bags, float* __restrict__ out) {
+  constexpr int G = 64 / LPR;
+  __shared__ float part[4][(G > 1 ? (G - 1) : 1) * LPR * 4];
+  const int wave = threadIdx.x >> 6;
+  const uint32_t bag = blockIdx.x * 4u + wave;
+  const bool live = bag < n_bags;
+  int64_t b0 = 0, b1 = 0;
+  if (live) {
+    b0 = offsets ? offsets[bag] : (int64_t)bag * hotness;
+    b1 = offsets ? offsets[bag + 1] : (int64_t)(bag + 1) * hotness;
+  }
+  gather_bag<LPR, U>(data, staging, host_table, host_rows, D, keys, line_of, b0, b1, live, bag, out, part[wave]);
+}
+
+// First appearances of the missing keys, q = 0..n_new-1 in first-appearance order: remember the
+// key, emit the (set, q) sort word, and leave q in the key's scratch slot for the other positions.
 __global__ __launch_bounds__(256) void cache_list_new(const HashWsHeader* hdr,
                                                       const int64_t* __restrict__ keys,
                                                       const uint32_t* __restrict__ miss_pos,
+                                                      const uint32_t* __restrict__ scr_slot,
                                                       const uint32_t* __restrict__ first,
                                                       const uint32_t* __restrict__ rank, u64 num_sets,
-                                                      u64* __restrict__ new_key,
+                                                      u64* __restrict__ scratch, u64* __restrict__ new_key,
                                                       u64* __restrict__ sort_kv) {
   const uint32_t m = blockIdx.x * 256u + threadIdx.x;
   if (m >= hdr->n_miss || !first[m]) return;
@@ -193,14 +239,39 @@ __global__ __launch_bounds__(256) void cache_list_new(const HashWsHeader* hdr,
   const u64 key = (u64)keys[miss_pos[m]];
   new_key[q] = key;
   sort_kv[q] = (set_of(key, num_sets) << 32) | (u64)q;   // sorted by set, payload = first-appearance index
+  scratch[2ull * scr_slot[m] + 1] = (u64)q;
+}
+
+// Every missing position learns the staging row of its key.
+__global__ __launch_bounds__(256) void cache_mark_staged(const HashWsHeader* hdr,
+                                                         const uint32_t* __restrict__ miss_pos,
+                                                         const uint32_t* __restrict__ scr_slot,
+                                                         const u64* __restrict__ scratch,
+                                                         uint32_t* __restrict__ line_of) {
+  const uint32_t m = blockIdx.x * 256u + threadIdx.x;
+  if (m >= hdr->n_miss) return;
+  line_of[miss_pos[m]] = kStaged | (uint32_t)scratch[2ull * scr_slot[m] + 1];
+}
+
+// One row per group of LPR lanes: host table -> staging (the only trip across the host link).
+template <int LPR>
+__global__ __launch_bounds__(256) void cache_fetch(const float* __restrict__ host_table, int D,
+                                                   const HashWsHeader* hdr, const u64* __restrict__ new_key,
+                                                   float* __restrict__ staging) {
+  const uint32_t q = (blockIdx.x * 256u + threadIdx.x) / LPR;
+  const int sub = threadIdx.x % LPR;
+  if (q >= hdr->n_new) return;
+  const float* src = host_table + (int64_t)new_key[q] * D;
+  float* to = staging + (int64_t)q * D;
+  for (int col = sub * 4; col < D; col += LPR * 4) store4(to + col, load4(src + col));
 }
 
 // One group of WAYS lanes per sorted position; the group at the start of a set's run places the
 // whole run.  dst[q] = cache line that key q goes to, or kNoLine when its insert is skipped.
 template <int WAYS>
 __global__ __launch_bounds__(256) void cache_place(u64* __restrict__ tags, uint32_t* __restrict__ stamps,
-                                                   CacheHeader* hdr, const HashWsHeader* ws_hdr,
-                                                   const u64* __restrict__ skv,
+                                                   CacheHeader* hdr, uint32_t epoch,
+                                                   const HashWsHeader* ws_hdr, const u64* __restrict__ skv,
                                                    const u64* __restrict__ new_key,
                                                    uint32_t* __restrict__ dst) {
   __shared__ uint32_t blk_stats[3];
@@ -212,21 +283,10 @@ __global__ __launch_bounds__(256) void cache_place(u64* __restrict__ tags, uint3
   const uint32_t set = j < n_new ? (uint32_t)(skv[j] >> 32) : 0u;
   const bool leader = j < n_new && !(j > 0 && (uint32_t)(skv[j - 1] >> 32) == set);  // first of its set
   if (leader) {
-    const uint32_t epoch = hdr->epoch;
     const uint64_t line = (uint64_t)set * WAYS + way;
-    const u64 tag = tags[line];
-    const uint32_t stamp = stamps[line];
-    // order key of this way in the set's victim list; ways used in this call are not in the list
-    const bool empty = tag == kEmptyKey;
-    const bool eligible = empty || stamp < epoch;
-    const u64 okey = !eligible ? ~0ull : (empty ? (u64)way : (((u64)stamp + 1ull) << 8) | (u64)way);
-    uint32_t pos = 0, n_elig = 0;
-  #pragma unroll
-    for (int w = 0; w < WAYS; ++w) {
-      const u64 other = (u64)__shfl((long long)okey, w, WAYS);
-      pos += other < okey ? 1u : 0u;
-      n_elig += other != ~0ull ? 1u : 0u;
-    }
+    bool eligible, empty;
+    uint32_t pos, n_elig;
+    victim_order<WAYS>(tags[line], stamps[line], epoch, way, &eligible, &empty, &pos, &n_elig);
     uint32_t inserted = 0, evicted = 0, skipped = 0;
     for (uint32_t k = 0; j + k < n_new && (uint32_t)(skv[j + k] >> 32) == set; ++k) {
       const uint32_t q = (uint32_t)skv[j + k];
@@ -243,9 +303,8 @@ __global__ __launch_bounds__(256) void cache_place(u64* __restrict__ tags, uint3
         skipped += 1;
       }
     }
-    // evicted is per lane; add it up over the group
-  #pragma unroll
-    for (int d = WAYS / 2; d >= 1; d >>= 1) evicted += __shfl_xor(evicted, d, WAYS);
+#pragma unroll
+    for (int d = WAYS / 2; d >= 1; d >>= 1) evicted += __shfl_xor(evicted, d, WAYS);  // per lane -> per group
     if (way == 0) {
       if (inserted) atomicAdd(&blk_stats[0], inserted);
       if (evicted) atomicAdd(&blk_stats[1], evicted);
@@ -256,26 +315,234 @@ __global__ __launch_bounds__(256) void cache_place(u64* __restrict__ tags, uint3
   if (threadIdx.x < 3 && blk_stats[threadIdx.x]) atomicAdd(&hdr->stats[3 + threadIdx.x], (u64)blk_stats[threadIdx.x]);
 }
 
-// Copy the rows of the placed keys from the host table into their cache lines.
+// Copy the rows of the placed keys from staging into their cache lines.
 template <int LPR>
-__global__ __launch_bounds__(256) void cache_fill(float* __restrict__ data,
-                                                  const float* __restrict__ host_table, int D,
-                                                  const HashWsHeader* ws_hdr,
-                                                  const u64* __restrict__ new_key,
+__global__ __launch_bounds__(256) void cache_fill(float* __restrict__ data, const float* __restrict__ staging,
+                                                  int D, const HashWsHeader* ws_hdr,
                                                   const uint32_t* __restrict__ dst) {
   const uint32_t q = (blockIdx.x * 256u + threadIdx.x) / LPR;
   const int sub = threadIdx.x % LPR;
   if (q >= ws_hdr->n_new) return;
   const uint32_t line = dst[q];
   if (line == kNoLine) return;
-  const float* src = host_table + (int64_t)new_key[q] * D;
+  const float* src = staging + (int64_t)q * D;
   float* to = data + (int64_t)line * D;
   for (int col = sub * 4; col < D; col += LPR * 4) store4(to + col, load4(src + col));
 }
 
+// ------------------------------------------------------------------------------------------------
+// Small calls
+// ------------------------------------------------------------------------------------------------
+
+// Probe + gather in one launch, a block per four bags: the block first classifies the keys of its
+// bags (a group of WAYS lanes per key), then each wave pools one bag.  Misses are read straight
+// from the host table.  Rows must fit one column chunk (dim <= LPR * 4, i.e. dim <= 256).
+template <int WAYS, int LPR>
+__global__ __launch_bounds__(256) void cache_query_small(const u64* __restrict__ tags,
+                                                         uint32_t* __restrict__ stamps, u64 num_sets,
+                                                         const float* __restrict__ data,
+                                                         const float* __restrict__ host_table,
+                                                         int64_t host_rows, int D, CacheHeader* hdr,
+                                                         uint32_t epoch, const int64_t* __restrict__ keys,
+                                                         uint32_t nnz, const int64_t* __restrict__ offsets,
+                                                         int64_t hotness, uint32_t n_bags,
+                                                         uint32_t* line_of, uint8_t* __restrict__ hit_mask,
+                                                         uint32_t* __restrict__ miss_flag,
+                                                         float* __restrict__ out) {
+  constexpr int G = 64 / LPR;
+  __shared__ float part[4][(G > 1 ? (G - 1) : 1) * LPR * 4];
+  __shared__ uint32_t block_hits;
+  if (threadIdx.x == 0) block_hits = 0;
+  __syncthreads();
+  const uint32_t bag_lo = blockIdx.x * 4u;
+  const uint32_t bag_hi = bag_lo + 4u < n_bags ? bag_lo + 4u : n_bags;
+  const int64_t k_lo = offsets ? offsets[bag_lo] : (int64_t)bag_lo * hotness;
+  const int64_t k_hi = offsets ? offsets[bag_hi] : (int64_t)bag_hi * hotness;
+  {
+    const int way = threadIdx.x % WAYS;
+    const int lane = threadIdx.x & 63;
+    constexpr uint64_t kGroupOnes = WAYS == 64 ? ~0ull : ((1ull << (WAYS & 63)) - 1ull);
+    const uint64_t gmask = kGroupOnes << (lane - way);
+    constexpr int kPerRound = 256 / WAYS;
+    uint32_t hits = 0;
+    const int64_t n_rounds = (k_hi - k_lo + kPerRound - 1) / kPerRound;
+    for (int64_t r = 0; r < n_rounds; ++r) {
+      const int64_t i = k_lo + r * kPerRound + threadIdx.x / WAYS;
+      const int64_t key = i < k_hi ? keys[i] : -1;
+      u64 slot = 0;
+      bool match = false;
+      if (key >= 0) {
+        slot = set_of((u64)key, num_sets) * WAYS + way;
+        match = tags[slot] == (u64)key;
+        if (match) stamps[slot] = epoch;
+      }
+      const uint64_t mine = __ballot(match) & gmask;
+      const bool hit = mine != 0;
+      uint32_t line = match ? (uint32_t)slot : kNoLine;
+      if (hit) line = __shfl(line, __ffsll((unsigned long long)mine) - 1);
+      if (way == 0 && i < k_hi) {
+        line_of[i] = hit ? line : kNoLine;
+        if (hit_mask) hit_mask[i] = hit ? 1 : 0;
+        if (miss_flag) miss_flag[i] = (!hit && key >= 0 && key < host_rows) ? 1u : 0u;
+        hits += hit ? 1u : 0u;
+      }
+    }
+    if (hits) atomicAdd(&block_hits, hits);
+  }
+  __threadfence_block();
+  __syncthreads();   // line_of of this block's keys is complete and visible to the whole block
+  if (threadIdx.x == 0) {
+    if (block_hits) atomicAdd(&hdr->stats[1], (u64)block_hits);
+    if (blockIdx.x == 0) {
+      hdr->epoch = epoch;
+      atomicAdd(&hdr->stats[0], (u64)nnz);
+    }
+  }
+  const int wave = threadIdx.x >> 6;
+  const uint32_t bag = bag_lo + wave;
+  const bool live = bag < n_bags;
+  int64_t b0 = 0, b1 = 0;
+  if (live) {
+    b0 = offsets ? offsets[bag] : (int64_t)bag * hotness;
+    b1 = offsets ? offsets[bag + 1] : (int64_t)(bag + 1) * hotness;
+  }
+  // no line of a small call is staged; `data` only fills the staging argument
+  gather_bag<LPR, 4>(data, data, host_table, host_rows, D, keys, line_of, b0, b1, live, bag, out, part[wave]);
+}
+
+// The whole insertion of a small call in one block of 1024 threads (n <= kSmallMaxKeys keys).
+//   1. compact the missing positions (block scan), keys to LDS;  2. first appearances (pairwise
+//   compare);  3. number them (block scan) -> distinct keys q;    4. per key: rank among the earlier
+//   keys of its set, victim list of the set read from the state as the probe left it;
+//   5. after a barrier, write tags and stamps;                    6. copy the rows host -> cache lines.
+template <int WAYS>
+__global__ __launch_bounds__(1024) void cache_insert_small(u64* __restrict__ tags, uint32_t* __restrict__ stamps,
+                                                           float* __restrict__ data, CacheHeader* hdr,
+                                                           const float* __restrict__ host_table, int D,
+                                                           u64 num_sets, uint32_t epoch,
+                                                           const int64_t* __restrict__ keys,
+                                                           const uint32_t* __restrict__ miss_flag, uint32_t n) {
+  constexpr int T = 1024;
+  constexpr int PER = kSmallMaxKeys / T;            // positions per thread in the two scans
+  __shared__ uint32_t pos_or_dst[kSmallMaxKeys];    // missing positions (steps 1-3), then q -> line (4-6)
+  __shared__ u64 wide[kSmallMaxKeys];               // keys of the missing positions (1-2), then two u32 arrays
+  __shared__ uint8_t is_first[kSmallMaxKeys];
+  __shared__ uint32_t scan_lds[T / 64 + 1];
+  __shared__ uint32_t counters[3];                  // inserted, evicted, skipped
+  u64* mkey = wide;                                               // m -> key
+  uint32_t* ukey_pos = reinterpret_cast<uint32_t*>(wide);         // q -> position of the key's first appearance
+  uint32_t* uset = reinterpret_cast<uint32_t*>(wide) + kSmallMaxKeys;  // q -> set
+  const uint32_t tid = threadIdx.x;
+  if (tid < 3) counters[tid] = 0;
+
+  // 1. missing positions, ascending
+  uint32_t f[PER], cnt = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const uint32_t p = tid * PER + i;
+    f[i] = (p < n && miss_flag[p]) ? 1u : 0u;
+    cnt += f[i];
+  }
+  uint32_t M;
+  uint32_t run = block_exclusive_scan<T>(cnt, scan_lds, &M);
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    if (f[i]) {
+      pos_or_dst[run] = tid * PER + i;
+      mkey[run] = (u64)keys[tid * PER + i];
+      ++run;
+    }
+  }
+  __syncthreads();
+  if (M == 0) return;   // block-uniform
+
+  // 2. first appearance <=> no earlier missing position holds the same key
+  for (uint32_t m = tid; m < M; m += T) {
+    const u64 key = mkey[m];
+    bool first = true;
+    for (uint32_t j = 0; j < m; ++j) {
+      if (mkey[j] == key) { first = false; break; }
+    }
+    is_first[m] = first ? 1 : 0;
+  }
+  __syncthreads();
+
+  // 3. number the first appearances; from here on `wide` holds ukey_pos and uset
+  cnt = 0;
+  uint32_t my_pos[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const uint32_t m = tid * PER + i;
+    f[i] = (m < M && is_first[m]) ? 1u : 0u;
+    my_pos[i] = f[i] ? pos_or_dst[m] : 0u;
+    cnt += f[i];
+  }
+  uint32_t Uq;
+  run = block_exclusive_scan<T>(cnt, scan_lds, &Uq);   // ends with a barrier: all reads above are done
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    if (f[i]) {
+      ukey_pos[run] = my_pos[i];
+      uset[run] = (uint32_t)set_of((u64)keys[my_pos[i]], num_sets);
+      ++run;
+    }
+  }
+  __syncthreads();
+
+  // 4. placement decisions, one group of WAYS lanes per distinct key (cache state is only read here)
+  const int way = tid % WAYS;
+  constexpr uint32_t kGroups = T / WAYS;
+  for (uint32_t q0 = 0; q0 < Uq; q0 += kGroups) {
+    const uint32_t q = q0 + tid / WAYS;
+    if (q < Uq) {
+      const uint32_t set = uset[q];
+      uint32_t krank = 0;                               // earlier distinct keys of the same set
+      for (uint32_t j = way; j < q; j += WAYS) krank += uset[j] == set ? 1u : 0u;
+#pragma unroll
+      for (int d = WAYS / 2; d >= 1; d >>= 1) krank += __shfl_xor(krank, d, WAYS);
+      const uint64_t line = (uint64_t)set * WAYS + way;
+      bool eligible, empty;
+      uint32_t pos, n_elig;
+      victim_order<WAYS>(tags[line], stamps[line], epoch, way, &eligible, &empty, &pos, &n_elig);
+      if (krank < n_elig) {
+        if (eligible && pos == krank) {
+          pos_or_dst[q] = (uint32_t)line;
+          atomicAdd(&counters[0], 1u);
+          if (!empty) atomicAdd(&counters[1], 1u);
+        }
+      } else if (way == 0) {
+        pos_or_dst[q] = kNoLine;
+        atomicAdd(&counters[2], 1u);
+      }
+    }
+  }
+  __syncthreads();
+
+  // 5. + 6. publish tags and stamps, copy the rows
+  for (uint32_t q = tid; q < Uq; q += T) {
+    const uint32_t line = pos_or_dst[q];
+    if (line != kNoLine) {
+      tags[line] = (u64)keys[ukey_pos[q]];
+      stamps[line] = epoch;
+    }
+  }
+  constexpr int kCopyLanes = 32;   // lanes per row copy
+  for (uint32_t q = tid / kCopyLanes; q < Uq; q += T / kCopyLanes) {
+    const uint32_t line = pos_or_dst[q];
+    if (line == kNoLine) continue;
+    const float* src = host_table + keys[ukey_pos[q]] * D;
+    float* to = data + (int64_t)line * D;
+    for (int col = (tid % kCopyLanes) * 4; col < D; col += kCopyLanes * 4) store4(to + col, load4(src + col));
+  }
+  if (tid < 3 && counters[tid]) atomicAdd(&hdr->stats[3 + tid], (u64)counters[tid]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Host side
+// ------------------------------------------------------------------------------------------------
 struct CacheWsLayout {
   size_t header, line_of, flag, idx, miss_pos, scr_slot, first, rank, scan_tmp, scratch, new_key, kv0, kv1,
-      hist, aux, dst, total;
+      hist, aux, dst, staging, total;
   uint32_t scratch_cap_max;
   int sort_bits;
   SortPlan sort;
@@ -289,7 +556,12 @@ static CacheWsLayout cache_ws_layout(const hctr_cache* c, int64_t nnz_max) {
   L.sort_bits = ceil_log2((uint64_t)c->num_sets + 1);
   L.sort = sort_plan((uint32_t)n, L.sort_bits);
   L.header = at(sizeof(HashWsHeader));
-  L.line_of = at(n * 4); L.flag = at(n * 4); L.idx = at(n * 4); L.miss_pos = at(n * 4);
+  L.line_of = at(n * 4); L.flag = at(n * 4);
+  if ((int64_t)n <= c->small_max_keys && c->dim <= 256) {   // the small-call kernels need nothing else
+    L.total = cv.off;
+    return L;
+  }
+  L.idx = at(n * 4); L.miss_pos = at(n * 4);
   L.scr_slot = at(n * 4); L.first = at(n * 4); L.rank = at(n * 4);
   L.scan_tmp = at(scan_tmp_count((uint32_t)n) * 4);
   L.scratch_cap_max = dedup_scratch_capacity((uint32_t)n);
@@ -299,45 +571,9 @@ static CacheWsLayout cache_ws_layout(const hctr_cache* c, int64_t nnz_max) {
   L.hist = at(L.sort.hist_count * 4);
   L.aux = at(L.sort.aux_count * 4);
   L.dst = at(n * 4);
+  L.staging = at(n * (size_t)c->dim * 4);
   L.total = cv.off;
   return L;
-}
-
-template <int WAYS>
-static void launch_probe(const hctr_cache* c, const int64_t* keys, uint32_t nnz, uint32_t* line_of,
-                         uint8_t* hit_mask, uint32_t* miss_flag, hipStream_t stream) {
-  hipLaunchKernelGGL((cache_probe<WAYS>), dim3((uint32_t)ceil_div(ceil_div((int64_t)nnz, kProbeKeys) * WAYS, 256)), dim3(256), 0,
-                     stream, reinterpret_cast<const u64*>(c->storage + c->off_tags),
-                     reinterpret_cast<uint32_t*>(c->storage + c->off_stamps), (u64)c->num_sets,
-                     c->host_rows, reinterpret_cast<CacheHeader*>(c->storage), keys, nnz, line_of,
-                     hit_mask, miss_flag);
-}
-
-template <int WAYS>
-static void launch_place(const hctr_cache* c, const HashWsHeader* ws_hdr, uint32_t n_max,
-                         const u64* skv, const u64* new_key, uint32_t* dst, hipStream_t stream) {
-  hipLaunchKernelGGL((cache_place<WAYS>), dim3((uint32_t)ceil_div((int64_t)n_max * WAYS, 256)), dim3(256),
-                     0, stream, reinterpret_cast<u64*>(c->storage + c->off_tags),
-                     reinterpret_cast<uint32_t*>(c->storage + c->off_stamps),
-                     reinterpret_cast<CacheHeader*>(c->storage), ws_hdr, skv, new_key, dst);
-}
-
-template <int LPR>
-static void launch_gather(const hctr_cache* c, const int64_t* keys, const uint32_t* line_of,
-                          const int64_t* offsets, int64_t hotness, uint32_t n_bags, float* out,
-                          hipStream_t stream) {
-  dim3 grid((uint32_t)ceil_div(n_bags, 4), (uint32_t)ceil_div(c->dim, LPR * 4));
-  hipLaunchKernelGGL((cache_gather<LPR, 4>), grid, dim3(256), 0, stream,
-                     reinterpret_cast<const float*>(c->storage + c->off_data), c->host_table, c->host_rows,
-                     (int)c->dim, keys, line_of, offsets, hotness, n_bags, out);
-}
-
-template <int LPR>
-static void launch_fill(const hctr_cache* c, const HashWsHeader* ws_hdr, uint32_t n_max, const u64* new_key,
-                        const uint32_t* dst, hipStream_t stream) {
-  hipLaunchKernelGGL((cache_fill<LPR>), dim3((uint32_t)ceil_div((int64_t)n_max * LPR, 256)), dim3(256), 0,
-                     stream, reinterpret_cast<float*>(c->storage + c->off_data), c->host_table, (int)c->dim,
-                     ws_hdr, new_key, dst);
 }
 
 #define HCTR_BY_WAYS(W, CALL)                    \
@@ -359,6 +595,81 @@ static void launch_fill(const hctr_cache* c, const HashWsHeader* ws_hdr, uint32_
     default: CALL(64); break;                    \
   }
 
+struct QueryArgs {
+  const hctr_cache* c;
+  const int64_t* keys;
+  const int64_t* offsets;
+  int64_t hotness;
+  uint32_t n, n_bags, epoch;
+  float* out;
+  uint8_t* hit_mask;
+  uint32_t* line_of;
+  uint32_t* flag;   // nullptr when nothing will be inserted
+  hipStream_t stream;
+  u64* tags() const { return reinterpret_cast<u64*>(c->storage + c->off_tags); }
+  uint32_t* stamps() const { return reinterpret_cast<uint32_t*>(c->storage + c->off_stamps); }
+  float* data() const { return reinterpret_cast<float*>(c->storage + c->off_data); }
+  CacheHeader* hdr() const { return reinterpret_cast<CacheHeader*>(c->storage); }
+};
+
+template <int WAYS>
+static void launch_probe(const QueryArgs& a) {
+  const uint32_t blocks = (uint32_t)ceil_div(ceil_div((int64_t)a.n, kProbeKeys) * WAYS, 256);
+  hipLaunchKernelGGL((cache_probe<WAYS>), dim3(blocks), dim3(256), 0, a.stream, (const u64*)a.tags(), a.stamps(),
+                     (u64)a.c->num_sets, a.c->host_rows, a.hdr(), a.epoch, a.keys, a.n, a.line_of, a.hit_mask,
+                     a.flag);
+}
+
+template <int LPR>
+static void launch_gather(const QueryArgs& a, const float* staging) {
+  dim3 grid((uint32_t)ceil_div(a.n_bags, 4), (uint32_t)ceil_div(a.c->dim, LPR * 4));
+  hipLaunchKernelGGL((cache_gather<LPR, 4>), grid, dim3(256), 0, a.stream, (const float*)a.data(), staging,
+                     a.c->host_table, a.c->host_rows, (int)a.c->dim, a.keys, (const uint32_t*)a.line_of,
+                     a.offsets, a.hotness, a.n_bags, a.out);
+}
+
+template <int WAYS, int LPR>
+static void launch_query_small(const QueryArgs& a) {
+  dim3 grid((uint32_t)ceil_div(a.n_bags, 4), 1);
+  hipLaunchKernelGGL((cache_query_small<WAYS, LPR>), grid, dim3(256), 0, a.stream, (const u64*)a.tags(),
+                     a.stamps(), (u64)a.c->num_sets, (const float*)a.data(), a.c->host_table, a.c->host_rows,
+                     (int)a.c->dim, a.hdr(), a.epoch, a.keys, a.n, a.offsets, a.hotness, a.n_bags, a.line_of,
+                     a.hit_mask, a.flag, a.out);
+}
+
+template <int WAYS>
+static void dispatch_query_small(int lpr, const QueryArgs& a) {
+#define CALL(LL) launch_query_small<WAYS, LL>(a)
+  HCTR_BY_LPR(lpr, CALL)
+#undef CALL
+}
+
+template <int WAYS>
+static void launch_insert_small(const QueryArgs& a) {
+  hipLaunchKernelGGL((cache_insert_small<WAYS>), dim3(1), dim3(1024), 0, a.stream, a.tags(), a.stamps(), a.data(),
+                     a.hdr(), a.c->host_table, (int)a.c->dim, (u64)a.c->num_sets, a.epoch, a.keys,
+                     (const uint32_t*)a.flag, a.n);
+}
+
+template <int WAYS>
+static void launch_place(const QueryArgs& a, const HashWsHeader* ws_hdr, const u64* skv, const u64* new_key,
+                         uint32_t* dst) {
+  hipLaunchKernelGGL((cache_place<WAYS>), dim3((uint32_t)ceil_div((int64_t)a.n * WAYS, 256)), dim3(256), 0,
+                     a.stream, a.tags(), a.stamps(), a.hdr(), a.epoch, ws_hdr, skv, new_key, dst);
+}
+
+template <int LPR>
+static void launch_fetch_fill(const QueryArgs& a, const HashWsHeader* ws_hdr, const u64* new_key,
+                              float* staging, const uint32_t* dst, bool fill) {
+  const uint32_t blocks = (uint32_t)ceil_div((int64_t)a.n * LPR, 256);
+  if (!fill)
+    hipLaunchKernelGGL((cache_fetch<LPR>), dim3(blocks), dim3(256), 0, a.stream, a.c->host_table, (int)a.c->dim,
+                       ws_hdr, new_key, staging);
+  else
+    hipLaunchKernelGGL((cache_fill<LPR>), dim3(blocks), dim3(256), 0, a.stream, a.data(), (const float*)staging,
+                       (int)a.c->dim, ws_hdr, dst);
+}
+
 }  // namespace hctr
 
 using namespace hctr;
@@ -377,7 +688,7 @@ static bool cache_shape_ok(int64_t num_sets, int32_t ways, int32_t dim) {
   if (num_sets < 1 || num_sets > 0x7FFFFFFFll) return false;
   if (ways < 1 || ways > 64 || (ways & (ways - 1)) != 0) return false;
   if (dim < 4 || dim % 4 != 0) return false;
-  if ((uint64_t)num_sets * ways > 0xFFFFFFFEull) return false;
+  if ((uint64_t)num_sets * ways > 0x7FFFFFFFull) return false;   // line numbers keep their top bit free
   return true;
 }
 
@@ -410,6 +721,8 @@ HCTR_API hctr_status hctr_cache_create(void* storage, size_t storage_bytes, int6
   c->storage = static_cast<char*>(storage);
   c->num_sets = num_sets; c->ways = ways; c->dim = dim;
   c->host_table = host_table; c->host_rows = host_rows;
+  c->epoch = 0;
+  c->small_max_keys = kSmallMaxKeys;
   const uint64_t lines = (uint64_t)num_sets * ways;
   hipLaunchKernelGGL(cache_clear, dim3((uint32_t)ceil_div((int64_t)(lines > 6 ? lines : 6), 256)), dim3(256), 0,
                      static_cast<hipStream_t>(stream), reinterpret_cast<u64*>(c->storage + c->off_tags),
@@ -421,9 +734,21 @@ HCTR_API hctr_status hctr_cache_create(void* storage, size_t storage_bytes, int6
   return HCTR_OK;
 }
 
+HCTR_API hctr_status hctr_cache_set_small_call_limit(hctr_cache* c, int64_t max_keys) {
+  if (!c) return fail(HCTR_E_NULL_PTR, "cache is NULL");
+  if (max_keys < 0 || max_keys > kSmallMaxKeys)
+    return fail(HCTR_E_INVALID_ARG, "limit %lld outside 0..%d", (long long)max_keys, kSmallMaxKeys);
+  c->small_max_keys = max_keys;
+  return HCTR_OK;
+}
+
 HCTR_API size_t hctr_cache_workspace_bytes(const hctr_cache* cache, int64_t nnz_max) {
   if (!cache || nnz_max < 0 || nnz_max >= (1ll << 31)) return 0;
-  return cache_ws_layout(cache, nnz_max).total;
+  // sized for the general path, which needs the most; it then serves every call of up to nnz_max
+  // keys whichever path that call takes
+  hctr_cache general = *cache;
+  general.small_max_keys = 0;
+  return cache_ws_layout(&general, nnz_max).total;
 }
 
 HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_slots, const int64_t* keys,
@@ -453,54 +778,75 @@ HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_
   if ((uintptr_t)ws % 256 != 0) return fail(HCTR_E_WORKSPACE, "workspace must be 256-byte aligned");
   if (ws_bytes < L.total) return fail(HCTR_E_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, L.total);
 
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
   char* w = static_cast<char*>(ws);
   HashWsHeader* ws_hdr = reinterpret_cast<HashWsHeader*>(w + L.header);
-  uint32_t* line_of = reinterpret_cast<uint32_t*>(w + L.line_of);
-  uint32_t* flag = reinterpret_cast<uint32_t*>(w + L.flag);
-  const uint32_t n = (uint32_t)nnz;
-
-  hipLaunchKernelGGL(cache_begin, dim3(1), dim3(64), 0, stream, reinterpret_cast<CacheHeader*>(c->storage), ws_hdr, (u64)nnz);
-  if (n > 0) {
-#define CALL(W) launch_probe<W>(c, keys, n, line_of, hit_mask, insert_missing ? flag : nullptr, stream)
-    HCTR_BY_WAYS(c->ways, CALL)
-#undef CALL
-  }
+  c->epoch += 1;
+  QueryArgs a{c, keys, offsets, hotness, (uint32_t)nnz, (uint32_t)n_bags, c->epoch, out, hit_mask,
+              reinterpret_cast<uint32_t*>(w + L.line_of),
+              insert_missing ? reinterpret_cast<uint32_t*>(w + L.flag) : nullptr,
+              static_cast<hipStream_t>(stream_)};
   int lpr = pow2_ceil((int)ceil_div(c->dim, 4));
   lpr = lpr < 4 ? 4 : (lpr > 64 ? 64 : lpr);
-#define CALL(LL) launch_gather<LL>(c, keys, line_of, offsets, hotness, (uint32_t)n_bags, out, stream)
-  HCTR_BY_LPR(lpr, CALL)
-#undef CALL
-  if (insert_missing && n > 0) {
-    DedupBuffers B{flag,
-                   reinterpret_cast<uint32_t*>(w + L.idx),
-                   reinterpret_cast<uint32_t*>(w + L.miss_pos),
-                   reinterpret_cast<uint32_t*>(w + L.scr_slot),
-                   reinterpret_cast<uint32_t*>(w + L.first),
-                   reinterpret_cast<uint32_t*>(w + L.rank),
-                   reinterpret_cast<uint32_t*>(w + L.scan_tmp),
-                   reinterpret_cast<u64*>(w + L.scratch),
-                   L.scratch_cap_max,
-                   &ws_hdr->n_miss,
-                   &ws_hdr->n_new};
-    HCTR_TRY(dedup_first_appearance(keys, n, B, stream));
-    u64* new_key = reinterpret_cast<u64*>(w + L.new_key);
-    u64* kv[2] = {reinterpret_cast<u64*>(w + L.kv0), reinterpret_cast<u64*>(w + L.kv1)};
-    uint32_t* dst = reinterpret_cast<uint32_t*>(w + L.dst);
-    hipLaunchKernelGGL(cache_list_new, dim3((uint32_t)ceil_div(n, 256)), dim3(256), 0, stream,
-                       (const HashWsHeader*)ws_hdr, keys, (const uint32_t*)B.miss_pos,
-                       (const uint32_t*)B.first, (const uint32_t*)B.rank, (u64)c->num_sets, new_key, kv[0]);
-    HCTR_TRY(radix_sort_u64(L.sort, &ws_hdr->n_new, reinterpret_cast<uint64_t*>(kv[0]),
-                            reinterpret_cast<uint64_t*>(kv[1]), reinterpret_cast<uint32_t*>(w + L.hist),
-                            reinterpret_cast<uint32_t*>(w + L.aux), false, stream));
-    const u64* skv = kv[L.sort.passes & 1];
-#define CALL(W) launch_place<W>(c, ws_hdr, n, skv, new_key, dst, stream)
+
+  if (nnz <= c->small_max_keys && c->dim <= 256) {
+#define CALL(W) dispatch_query_small<W>(lpr, a)
     HCTR_BY_WAYS(c->ways, CALL)
 #undef CALL
-#define CALL(LL) launch_fill<LL>(c, ws_hdr, n, new_key, dst, stream)
+    if (insert_missing && nnz > 0) {
+#define CALL(W) launch_insert_small<W>(a)
+      HCTR_BY_WAYS(c->ways, CALL)
+#undef CALL
+    }
+    return launch_status("hctr_cache_query");
+  }
+
+#define CALL(W) launch_probe<W>(a)
+  HCTR_BY_WAYS(c->ways, CALL)
+#undef CALL
+  if (!insert_missing) {
+#define CALL(LL) launch_gather<LL>(a, nullptr)
     HCTR_BY_LPR(lpr, CALL)
 #undef CALL
+    return launch_status("hctr_cache_query");
   }
+  DedupBuffers B{a.flag,
+                 reinterpret_cast<uint32_t*>(w + L.idx),
+                 reinterpret_cast<uint32_t*>(w + L.miss_pos),
+                 reinterpret_cast<uint32_t*>(w + L.scr_slot),
+                 reinterpret_cast<uint32_t*>(w + L.first),
+                 reinterpret_cast<uint32_t*>(w + L.rank),
+                 reinterpret_cast<uint32_t*>(w + L.scan_tmp),
+                 reinterpret_cast<u64*>(w + L.scratch),
+                 L.scratch_cap_max,
+                 &ws_hdr->n_miss,
+                 &ws_hdr->n_new};
+  HCTR_TRY(dedup_first_appearance(keys, a.n, B, a.stream));
+  u64* new_key = reinterpret_cast<u64*>(w + L.new_key);
+  u64* kv[2] = {reinterpret_cast<u64*>(w + L.kv0), reinterpret_cast<u64*>(w + L.kv1)};
+  uint32_t* dst = reinterpret_cast<uint32_t*>(w + L.dst);
+  float* staging = reinterpret_cast<float*>(w + L.staging);
+  const uint32_t nb = (uint32_t)ceil_div(a.n, 256);
+  hipLaunchKernelGGL(cache_list_new, dim3(nb), dim3(256), 0, a.stream, (const HashWsHeader*)ws_hdr, keys,
+                     (const uint32_t*)B.miss_pos, (const uint32_t*)B.scr_slot, (const uint32_t*)B.first,
+                     (const uint32_t*)B.rank, (u64)c->num_sets, B.scratch, new_key, kv[0]);
+  hipLaunchKernelGGL(cache_mark_staged, dim3(nb), dim3(256), 0, a.stream, (const HashWsHeader*)ws_hdr,
+                     (const uint32_t*)B.miss_pos, (const uint32_t*)B.scr_slot, (const u64*)B.scratch, a.line_of);
+#define CALL(LL) launch_fetch_fill<LL>(a, ws_hdr, new_key, staging, dst, false)
+  HCTR_BY_LPR(lpr, CALL)
+#undef CALL
+#define CALL(LL) launch_gather<LL>(a, staging)
+  HCTR_BY_LPR(lpr, CALL)
+#undef CALL
+  HCTR_TRY(radix_sort_u64(L.sort, &ws_hdr->n_new, reinterpret_cast<uint64_t*>(kv[0]),
+                          reinterpret_cast<uint64_t*>(kv[1]), reinterpret_cast<uint32_t*>(w + L.hist),
+                          reinterpret_cast<uint32_t*>(w + L.aux), false, a.stream));
+  const u64* skv = kv[L.sort.passes & 1];
+#define CALL(W) launch_place<W>(a, ws_hdr, skv, new_key, dst)
+  HCTR_BY_WAYS(c->ways, CALL)
+#undef CALL
+#define CALL(LL) launch_fetch_fill<LL>(a, ws_hdr, new_key, staging, dst, true)
+  HCTR_BY_LPR(lpr, CALL)
+#undef CALL
   return launch_status("hctr_cache_query");
 }
 

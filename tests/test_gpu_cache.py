@@ -28,9 +28,11 @@ def pinned_table(rows, dim, seed=SEED):
 
 
 class Pair:
-    def __init__(self, num_sets, ways, host):
+    def __init__(self, num_sets, ways, host, small_limit=None):
         self.host = host
         self.gpu = H().EmbeddingCache(num_sets, ways, host)
+        if small_limit is not None:
+            self.gpu.set_small_call_limit(small_limit)
         self.ref = oracle.Cache(num_sets, ways, host.numpy())
         self.num_sets, self.ways = num_sets, ways
 
@@ -76,10 +78,11 @@ def test_hand_worked_trace():
         assert gpu.stats == call["stats"]
 
 
+@pytest.mark.parametrize("small_limit", [0, 4096], ids=["general", "fused-small"])
 @pytest.mark.parametrize("num_sets,ways,dim", [(64, 8, 16), (1, 4, 8), (37, 1, 32), (16, 32, 128), (5, 64, 4), (300, 2, 260)])
-def test_zipf_traffic_matches_the_simulation(num_sets, ways, dim):
+def test_zipf_traffic_matches_the_simulation(num_sets, ways, dim, small_limit):
     host_rows = 5000
-    p = Pair(num_sets, ways, pinned_table(host_rows, dim))
+    p = Pair(num_sets, ways, pinned_table(host_rows, dim), small_limit)
     smp = datagen.ZipfSampler(host_rows, 1.2)
     hits = 0
     for it in range(12):
@@ -92,9 +95,10 @@ def test_zipf_traffic_matches_the_simulation(num_sets, ways, dim):
     assert hits > 0
 
 
-def test_csr_bags_and_batch_of_one_key():
+@pytest.mark.parametrize("small_limit", [0, 4096], ids=["general", "fused-small"])
+def test_csr_bags_and_batch_of_one_key(small_limit):
     host_rows, dim = 800, 64
-    p = Pair(32, 4, pinned_table(host_rows, dim))
+    p = Pair(32, 4, pinned_table(host_rows, dim), small_limit)
     rng = np.random.default_rng(8)
     for it in range(10):
         h = rng.integers(0, 7, 90)
@@ -105,11 +109,23 @@ def test_csr_bags_and_batch_of_one_key():
         p.query(rng.integers(0, 50, 1), 1, what=f"single {it}")   # classical per-access LRU traffic
 
 
-def test_set_overflow_in_one_call_skips_the_surplus():
+@pytest.mark.parametrize("small_limit", [0, 4096], ids=["general", "fused-small"])
+def test_set_overflow_in_one_call_skips_the_surplus(small_limit):
     host_rows, dim = 4096, 8
-    p = Pair(2, 4, pinned_table(host_rows, dim))
+    p = Pair(2, 4, pinned_table(host_rows, dim), small_limit)
     keys = np.arange(64)                                          # ~32 new keys per set, 4 ways each
     p.query(keys, 64, what="flood")
     assert p.ref.stats[5] > 0
     p.query(keys[::-1].copy(), 64, what="flood again")
     p.query(np.zeros(0, dtype=np.int64), 3, offsets=np.zeros(4, dtype=np.int64), what="empty bags")
+
+
+def test_paths_switch_back_and_forth_on_one_cache():
+    """Calls above and below the small-call limit interleaved on one cache (one workspace)."""
+    host_rows, dim = 60000, 64
+    p = Pair(128, 16, pinned_table(host_rows, dim))
+    smp = datagen.ZipfSampler(host_rows, 1.2)
+    for it, batch in enumerate([300, 2, 40, 300, 1, 39, 40, 300]):     # 26*4*39 = 4056 <= 4096 < 26*4*40
+        n_bags = batch * 26
+        keys = datagen.cache_keys(SEED, 50 + it, host_rows, n_bags * 4, 1.2, sampler=smp).numpy()
+        p.query(keys, n_bags, what=f"mixed {it} (batch {batch})")
