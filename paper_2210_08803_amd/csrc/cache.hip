@@ -16,6 +16,8 @@
 //   * small calls (<= kSmallMaxKeys keys): one fused probe+gather kernel (misses read straight
 //     from the pinned host table) and one single-block kernel for the whole insertion, because at
 //     a few hundred keys the cost is kernel launches, not bytes.
+#include <algorithm>
+
 #include "common.h"
 #include "rowvec.h"
 #include "blockscan.h"
@@ -46,10 +48,23 @@ struct CacheHeader {  // first 256 bytes of the cache storage
 };
 static_assert(sizeof(CacheHeader) == 256, "header is one 256-byte block");
 
-__device__ __forceinline__ u64 set_of(u64 key, u64 num_sets) {
+// The divisor of the set index, with the reciprocal that turns the 64-bit remainder (a few hundred
+// instructions when left to the compiler) into a multiply-high and at most two subtractions.
+struct SetDiv {
+  u64 n;      // num_sets
+  u64 recip;  // floor((2^64 - 1) / n)
+};
+static inline SetDiv make_set_div(int64_t num_sets) { return SetDiv{(u64)num_sets, ~0ull / (u64)num_sets}; }
+
+// set = x mod num_sets with x = key * 0x9E3779B97F4A7C15 mod 2^64, x ^= x >> 32 (exact).
+__device__ __forceinline__ u64 set_of(u64 key, SetDiv d) {
   u64 x = key * 0x9E3779B97F4A7C15ull;
   x ^= x >> 32;
-  return x % num_sets;
+  const u64 q = __umul64hi(x, d.recip);   // floor(x / n) or one or two less
+  u64 r = x - q * d.n;
+  if (r >= d.n) r -= d.n;
+  if (r >= d.n) r -= d.n;
+  return r;
 }
 
 __global__ __launch_bounds__(256) void cache_clear(u64* tags, uint32_t* stamps, uint64_t n_lines,
@@ -84,53 +99,59 @@ __device__ __forceinline__ void victim_order(u64 tag, uint32_t stamp, uint32_t e
 // ------------------------------------------------------------------------------------------------
 
 // Classify every key against the tags as they stand (nothing writes tags in this kernel).  A group
-// of WAYS lanes compares one tag per lane; each group takes kProbeKeys consecutive keys so that
-// their tag loads are in flight together, and a block reports its hits with a single atomic
-// (one atomic per wave on one address would serialise hundreds of thousands of them).
-constexpr int kProbeKeys = 8;
-
+// of WAYS lanes compares one tag per lane and takes KP = min(8, WAYS) consecutive keys: lane j of
+// the group loads key j and works out its set (the 64-bit remainder is the expensive part, so it is
+// done once per key, not once per lane), the group then shares both by shuffle and has its KP tag
+// loads in flight together.  A block reports its hits with a single atomic (one atomic per wave
+// on one address would serialise hundreds of thousands of them).
 template <int WAYS>
 __global__ __launch_bounds__(256) void cache_probe(const u64* __restrict__ tags,
-                                                   uint32_t* __restrict__ stamps, u64 num_sets,
+                                                   uint32_t* __restrict__ stamps, SetDiv num_sets,
                                                    int64_t host_rows, CacheHeader* hdr, uint32_t epoch,
                                                    const int64_t* __restrict__ keys, uint32_t nnz,
                                                    uint32_t* __restrict__ line_of,
                                                    uint8_t* __restrict__ hit_mask,
                                                    uint32_t* __restrict__ miss_flag) {
+  constexpr int KP = WAYS >= 8 ? 8 : WAYS;
   __shared__ uint32_t block_hits;
   if (threadIdx.x == 0) block_hits = 0;
   __syncthreads();
-  const uint32_t group = (blockIdx.x * 256u + threadIdx.x) / WAYS;
   const int way = threadIdx.x % WAYS;
   const int lane = threadIdx.x & 63;
   constexpr uint64_t kGroupOnes = WAYS == 64 ? ~0ull : ((1ull << (WAYS & 63)) - 1ull);
   const uint64_t gmask = kGroupOnes << (lane - way);
-  const uint32_t i0 = group * kProbeKeys;
-
-  int64_t key[kProbeKeys];
-  u64 tag[kProbeKeys];
-  u64 slot[kProbeKeys];
-#pragma unroll
-  for (int j = 0; j < kProbeKeys; ++j) key[j] = (i0 + j < nnz) ? keys[i0 + j] : -1;
-#pragma unroll
-  for (int j = 0; j < kProbeKeys; ++j) {
-    slot[j] = key[j] >= 0 ? set_of((u64)key[j], num_sets) * WAYS + way : 0;
-    tag[j] = key[j] >= 0 ? tags[slot[j]] : kEmptyKey;
-  }
+  const uint32_t n_groups = gridDim.x * (256u / WAYS);
   uint32_t hits = 0;
+  // the grid is bounded (each block ends with an atomic on the one hit counter), groups stride over the keys
+  for (uint64_t i0_64 = (uint64_t)((blockIdx.x * 256u + threadIdx.x) / WAYS) * KP; i0_64 < nnz;
+       i0_64 += (uint64_t)n_groups * KP) {
+    const uint32_t i0 = (uint32_t)i0_64;
+    const int64_t own_key = (way < KP && i0 + way < nnz) ? keys[i0 + way] : -1;
+    const u64 own_set = own_key >= 0 ? set_of((u64)own_key, num_sets) : 0;
+    int64_t key[KP];
+    u64 tag[KP];
+    u64 slot[KP];
 #pragma unroll
-  for (int j = 0; j < kProbeKeys; ++j) {
-    const bool match = key[j] >= 0 && tag[j] == (u64)key[j];
-    if (match) stamps[slot[j]] = epoch;
-    const uint64_t mine = __ballot(match) & gmask;
-    const bool hit = mine != 0;
-    uint32_t line = match ? (uint32_t)slot[j] : kNoLine;
-    if (hit) line = __shfl(line, __ffsll((unsigned long long)mine) - 1);
-    if (way == 0 && i0 + j < nnz) {
-      line_of[i0 + j] = hit ? line : kNoLine;
-      if (hit_mask) hit_mask[i0 + j] = hit ? 1 : 0;
-      if (miss_flag) miss_flag[i0 + j] = (!hit && key[j] >= 0 && key[j] < host_rows) ? 1u : 0u;
-      hits += hit ? 1u : 0u;
+    for (int j = 0; j < KP; ++j) {
+      key[j] = (int64_t)__shfl((long long)own_key, j, WAYS);
+      slot[j] = (u64)__shfl((long long)own_set, j, WAYS) * WAYS + way;
+      tag[j] = key[j] >= 0 ? tags[slot[j]] : kEmptyKey;
+    }
+#pragma unroll
+    for (int j = 0; j < KP; ++j) {
+      const bool match = key[j] >= 0 && tag[j] == (u64)key[j];
+      // a popular key is hit by thousands of waves: only the first ones to see the old stamp write
+      if (match && stamps[slot[j]] != epoch) stamps[slot[j]] = epoch;
+      const uint64_t mine = __ballot(match) & gmask;
+      const bool hit = mine != 0;
+      uint32_t line = match ? (uint32_t)slot[j] : kNoLine;
+      if (hit) line = __shfl(line, __ffsll((unsigned long long)mine) - 1);
+      if (way == 0 && i0 + j < nnz) {
+        line_of[i0 + j] = hit ? line : kNoLine;
+        if (hit_mask) hit_mask[i0 + j] = hit ? 1 : 0;
+        if (miss_flag) miss_flag[i0 + j] = (!hit && key[j] >= 0 && key[j] < host_rows) ? 1u : 0u;
+        hits += hit ? 1u : 0u;
+      }
     }
   }
   if (hits) atomicAdd(&block_hits, hits);
@@ -230,7 +251,7 @@ __global__ __launch_bounds__(256) void cache_list_new(const HashWsHeader* hdr,
                                                       const uint32_t* __restrict__ miss_pos,
                                                       const uint32_t* __restrict__ scr_slot,
                                                       const uint32_t* __restrict__ first,
-                                                      const uint32_t* __restrict__ rank, u64 num_sets,
+                                                      const uint32_t* __restrict__ rank, SetDiv num_sets,
                                                       u64* __restrict__ scratch, u64* __restrict__ new_key,
                                                       u64* __restrict__ sort_kv) {
   const uint32_t m = blockIdx.x * 256u + threadIdx.x;
@@ -258,12 +279,13 @@ template <int LPR>
 __global__ __launch_bounds__(256) void cache_fetch(const float* __restrict__ host_table, int D,
                                                    const HashWsHeader* hdr, const u64* __restrict__ new_key,
                                                    float* __restrict__ staging) {
-  const uint32_t q = (blockIdx.x * 256u + threadIdx.x) / LPR;
   const int sub = threadIdx.x % LPR;
-  if (q >= hdr->n_new) return;
-  const float* src = host_table + (int64_t)new_key[q] * D;
-  float* to = staging + (int64_t)q * D;
-  for (int col = sub * 4; col < D; col += LPR * 4) store4(to + col, load4(src + col));
+  const uint32_t n_new = hdr->n_new;
+  for (uint32_t q = (blockIdx.x * 256u + threadIdx.x) / LPR; q < n_new; q += gridDim.x * (256u / LPR)) {
+    const float* src = host_table + (int64_t)new_key[q] * D;
+    float* to = staging + (int64_t)q * D;
+    for (int col = sub * 4; col < D; col += LPR * 4) store4(to + col, load4(src + col));
+  }
 }
 
 // One group of WAYS lanes per sorted position; the group at the start of a set's run places the
@@ -277,12 +299,11 @@ __global__ __launch_bounds__(256) void cache_place(u64* __restrict__ tags, uint3
   __shared__ uint32_t blk_stats[3];
   if (threadIdx.x < 3) blk_stats[threadIdx.x] = 0;
   __syncthreads();
-  const uint32_t j = (blockIdx.x * 256u + threadIdx.x) / WAYS;
   const int way = threadIdx.x % WAYS;
   const uint32_t n_new = ws_hdr->n_new;
-  const uint32_t set = j < n_new ? (uint32_t)(skv[j] >> 32) : 0u;
-  const bool leader = j < n_new && !(j > 0 && (uint32_t)(skv[j - 1] >> 32) == set);  // first of its set
-  if (leader) {
+  for (uint32_t j = (blockIdx.x * 256u + threadIdx.x) / WAYS; j < n_new; j += gridDim.x * (256u / WAYS)) {
+    const uint32_t set = (uint32_t)(skv[j] >> 32);
+    if (j > 0 && (uint32_t)(skv[j - 1] >> 32) == set) continue;  // not the first of its set
     const uint64_t line = (uint64_t)set * WAYS + way;
     bool eligible, empty;
     uint32_t pos, n_elig;
@@ -320,14 +341,15 @@ template <int LPR>
 __global__ __launch_bounds__(256) void cache_fill(float* __restrict__ data, const float* __restrict__ staging,
                                                   int D, const HashWsHeader* ws_hdr,
                                                   const uint32_t* __restrict__ dst) {
-  const uint32_t q = (blockIdx.x * 256u + threadIdx.x) / LPR;
   const int sub = threadIdx.x % LPR;
-  if (q >= ws_hdr->n_new) return;
-  const uint32_t line = dst[q];
-  if (line == kNoLine) return;
-  const float* src = staging + (int64_t)q * D;
-  float* to = data + (int64_t)line * D;
-  for (int col = sub * 4; col < D; col += LPR * 4) store4(to + col, load4(src + col));
+  const uint32_t n_new = ws_hdr->n_new;
+  for (uint32_t q = (blockIdx.x * 256u + threadIdx.x) / LPR; q < n_new; q += gridDim.x * (256u / LPR)) {
+    const uint32_t line = dst[q];
+    if (line == kNoLine) continue;
+    const float* src = staging + (int64_t)q * D;
+    float* to = data + (int64_t)line * D;
+    for (int col = sub * 4; col < D; col += LPR * 4) store4(to + col, load4(src + col));
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -339,7 +361,7 @@ __global__ __launch_bounds__(256) void cache_fill(float* __restrict__ data, cons
 // from the host table.  Rows must fit one column chunk (dim <= LPR * 4, i.e. dim <= 256).
 template <int WAYS, int LPR>
 __global__ __launch_bounds__(256) void cache_query_small(const u64* __restrict__ tags,
-                                                         uint32_t* __restrict__ stamps, u64 num_sets,
+                                                         uint32_t* __restrict__ stamps, SetDiv num_sets,
                                                          const float* __restrict__ data,
                                                          const float* __restrict__ host_table,
                                                          int64_t host_rows, int D, CacheHeader* hdr,
@@ -374,7 +396,7 @@ __global__ __launch_bounds__(256) void cache_query_small(const u64* __restrict__
       if (key >= 0) {
         slot = set_of((u64)key, num_sets) * WAYS + way;
         match = tags[slot] == (u64)key;
-        if (match) stamps[slot] = epoch;
+        if (match && stamps[slot] != epoch) stamps[slot] = epoch;
       }
       const uint64_t mine = __ballot(match) & gmask;
       const bool hit = mine != 0;
@@ -419,7 +441,7 @@ template <int WAYS>
 __global__ __launch_bounds__(1024) void cache_insert_small(u64* __restrict__ tags, uint32_t* __restrict__ stamps,
                                                            float* __restrict__ data, CacheHeader* hdr,
                                                            const float* __restrict__ host_table, int D,
-                                                           u64 num_sets, uint32_t epoch,
+                                                           SetDiv num_sets, uint32_t epoch,
                                                            const int64_t* __restrict__ keys,
                                                            const uint32_t* __restrict__ miss_flag, uint32_t n) {
   constexpr int T = 1024;
@@ -614,9 +636,10 @@ struct QueryArgs {
 
 template <int WAYS>
 static void launch_probe(const QueryArgs& a) {
-  const uint32_t blocks = (uint32_t)ceil_div(ceil_div((int64_t)a.n, kProbeKeys) * WAYS, 256);
+  constexpr int KP = WAYS >= 8 ? 8 : WAYS;
+  const uint32_t blocks = (uint32_t)std::min<int64_t>(ceil_div(ceil_div((int64_t)a.n, KP) * WAYS, 256), 2048);
   hipLaunchKernelGGL((cache_probe<WAYS>), dim3(blocks), dim3(256), 0, a.stream, (const u64*)a.tags(), a.stamps(),
-                     (u64)a.c->num_sets, a.c->host_rows, a.hdr(), a.epoch, a.keys, a.n, a.line_of, a.hit_mask,
+                     make_set_div(a.c->num_sets), a.c->host_rows, a.hdr(), a.epoch, a.keys, a.n, a.line_of, a.hit_mask,
                      a.flag);
 }
 
@@ -632,7 +655,7 @@ template <int WAYS, int LPR>
 static void launch_query_small(const QueryArgs& a) {
   dim3 grid((uint32_t)ceil_div(a.n_bags, 4), 1);
   hipLaunchKernelGGL((cache_query_small<WAYS, LPR>), grid, dim3(256), 0, a.stream, (const u64*)a.tags(),
-                     a.stamps(), (u64)a.c->num_sets, (const float*)a.data(), a.c->host_table, a.c->host_rows,
+                     a.stamps(), make_set_div(a.c->num_sets), (const float*)a.data(), a.c->host_table, a.c->host_rows,
                      (int)a.c->dim, a.hdr(), a.epoch, a.keys, a.n, a.offsets, a.hotness, a.n_bags, a.line_of,
                      a.hit_mask, a.flag, a.out);
 }
@@ -647,21 +670,23 @@ static void dispatch_query_small(int lpr, const QueryArgs& a) {
 template <int WAYS>
 static void launch_insert_small(const QueryArgs& a) {
   hipLaunchKernelGGL((cache_insert_small<WAYS>), dim3(1), dim3(1024), 0, a.stream, a.tags(), a.stamps(), a.data(),
-                     a.hdr(), a.c->host_table, (int)a.c->dim, (u64)a.c->num_sets, a.epoch, a.keys,
+                     a.hdr(), a.c->host_table, (int)a.c->dim, make_set_div(a.c->num_sets), a.epoch, a.keys,
                      (const uint32_t*)a.flag, a.n);
 }
 
 template <int WAYS>
 static void launch_place(const QueryArgs& a, const HashWsHeader* ws_hdr, const u64* skv, const u64* new_key,
                          uint32_t* dst) {
-  hipLaunchKernelGGL((cache_place<WAYS>), dim3((uint32_t)ceil_div((int64_t)a.n * WAYS, 256)), dim3(256), 0,
+  // few blocks: each ends with three atomics on the same statistics words
+  const uint32_t blocks = (uint32_t)std::min<int64_t>(ceil_div((int64_t)a.n * WAYS, 256), 512);
+  hipLaunchKernelGGL((cache_place<WAYS>), dim3(blocks), dim3(256), 0,
                      a.stream, a.tags(), a.stamps(), a.hdr(), a.epoch, ws_hdr, skv, new_key, dst);
 }
 
 template <int LPR>
 static void launch_fetch_fill(const QueryArgs& a, const HashWsHeader* ws_hdr, const u64* new_key,
                               float* staging, const uint32_t* dst, bool fill) {
-  const uint32_t blocks = (uint32_t)ceil_div((int64_t)a.n * LPR, 256);
+  const uint32_t blocks = (uint32_t)std::min<int64_t>(ceil_div((int64_t)a.n * LPR, 256), 4096);
   if (!fill)
     hipLaunchKernelGGL((cache_fetch<LPR>), dim3(blocks), dim3(256), 0, a.stream, a.c->host_table, (int)a.c->dim,
                        ws_hdr, new_key, staging);
@@ -828,7 +853,7 @@ HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_
   const uint32_t nb = (uint32_t)ceil_div(a.n, 256);
   hipLaunchKernelGGL(cache_list_new, dim3(nb), dim3(256), 0, a.stream, (const HashWsHeader*)ws_hdr, keys,
                      (const uint32_t*)B.miss_pos, (const uint32_t*)B.scr_slot, (const uint32_t*)B.first,
-                     (const uint32_t*)B.rank, (u64)c->num_sets, B.scratch, new_key, kv[0]);
+                     (const uint32_t*)B.rank, make_set_div(c->num_sets), B.scratch, new_key, kv[0]);
   hipLaunchKernelGGL(cache_mark_staged, dim3(nb), dim3(256), 0, a.stream, (const HashWsHeader*)ws_hdr,
                      (const uint32_t*)B.miss_pos, (const uint32_t*)B.scr_slot, (const u64*)B.scratch, a.line_of);
 #define CALL(LL) launch_fetch_fill<LL>(a, ws_hdr, new_key, staging, dst, false)
