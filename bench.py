@@ -77,7 +77,7 @@ def main():
     ap.add_argument("--alpha", type=float, default=ALPHA,
                     help="Zipf exponent of the keys (0 = uniform); anything but the default is an experiment")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--schedule", choices=["serial", "overlap", "pipeline"], default="pipeline",
+    ap.add_argument("--schedule", choices=["serial", "overlap", "pipeline"], default="serial",
                     help="how the key-only half of backward is placed in time (see step())")
     ap.add_argument("--calibrate-gather", action="store_true",
                     help="also run the forward kernel once on all-distinct rows (known bytes, no cache reuse)")

@@ -8,7 +8,8 @@ from typing import Optional, Sequence
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(HERE, "libhctr.so")
+# HCTR_LIB points at another build of the same library (e.g. to compare two builds in one run)
+_LIB_PATH = os.environ.get("HCTR_LIB") or os.path.join(HERE, "libhctr.so")
 
 F32, F16 = 0, 1
 SUM, MEAN = 0, 1

@@ -20,7 +20,8 @@ struct EmbHeader {
   unsigned long long invalid;  // keys without a row, running total since hctr_emb_workspace_init
   long long num_unique;        // U of the last backward
   uint32_t n_valid;            // sorted positions holding a real row
-  uint32_t pad[59];
+  uint32_t n_long;             // rows whose carry is left to the block-wide kernel
+  uint32_t pad[58];
 };
 static_assert(sizeof(EmbHeader) == 256, "header is one 256-byte block");
 
@@ -137,34 +138,41 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
 #pragma unroll
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
   uint32_t nbad = 0;
-  for (int64_t j = b0 + g; j < b1; j += G * U) {
-    int64_t row[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int64_t jj = j + u * G;
-      row[u] = -1;
-      if (jj < b1) {
-        if (HASHED) {
-          const int64_t r = rows64[jj];
-          if (r >= 0 && r < total_rows) row[u] = r;
-        } else {
-          const int64_t k = keys[jj];
-          if (k >= 0 && k < num) row[u] = base + k;
-        }
-        nbad += (row[u] < 0 && sub == 0) ? 1u : 0u;
+  // 64 keys at a time: one coalesced key load and one row computation per lane, then the groups
+  // pick their rows from the lanes by shuffle, U row loads each in flight.
+  for (int64_t c0 = b0; c0 < b1; c0 += 64) {
+    const int cnt = b1 - c0 < 64 ? (int)(b1 - c0) : 64;
+    uint32_t myrow = kNoRow;
+    if (lane < cnt) {
+      if (HASHED) {
+        const int64_t r = rows64[c0 + lane];
+        if (r >= 0 && r < total_rows) myrow = (uint32_t)r;
+      } else {
+        const int64_t k = keys[c0 + lane];
+        if (k >= 0 && k < num) myrow = (uint32_t)(base + k);
       }
+      nbad += myrow == kNoRow ? 1u : 0u;
     }
-    float v[U][VEC];
+    for (int j0 = 0; j0 < cnt; j0 += G * U) {   // same trip count for every lane: the shuffles need all lanes
+      uint32_t row[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+      for (int u = 0; u < U; ++u) {
+        const int jj = j0 + g + u * G;
+        row[u] = __shfl(myrow, jj < cnt ? jj : lane);
+        if (jj >= cnt) row[u] = kNoRow;
+      }
+      float v[U][VEC];
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) v[u][i] = 0.f;
-      if (row[u] >= 0 && active) RowVec<T>::load(table + row[u] * D + col, v[u]);
+      for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[u][i] = 0.f;
+        if (row[u] != kNoRow && active) RowVec<T>::load(table + (int64_t)row[u] * D + col, v[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] += v[u][i];
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) acc[i] += v[u][i];
   }
   if (G > 1) {
     if (g > 0) {
@@ -197,6 +205,56 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
 // ------------------------------------------------------------------------------------------------
 // Backward step 1: per key, the 32-bit global row (or kNoRow) and the bag it belongs to.
 // ------------------------------------------------------------------------------------------------
+// Bag of every key of one 4096-key tile of a CSR batch, into LDS (bag + 1; the tile starts at key
+// k0).  Two binary searches find the bags of the tile's first and last key; every bag in between
+// marks the position where it starts (atomicMax: of several bags starting at one position - empty
+// ones - the last owns the key); a running maximum over the positions fills in the rest.
+__device__ __forceinline__ void tile_bags(const int64_t* __restrict__ offsets, uint32_t n_bags, uint32_t k0,
+                                          uint32_t k1, uint32_t* bagof /*[kSortTile]*/, uint32_t* lds /*[6]*/) {
+  const uint32_t tid = threadIdx.x;
+  for (uint32_t i = tid; i < kSortTile; i += 256) bagof[i] = 0;
+  if (tid < 2) {  // the bag with offsets[bag] <= k < offsets[bag + 1] for k = k0 and k1 - 1
+    const int64_t k = tid == 0 ? k0 : k1 - 1;
+    uint32_t lo = 0, hi = n_bags - 1;
+    while (lo < hi) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (offsets[mid + 1] <= k) lo = mid + 1; else hi = mid;
+    }
+    lds[4 + tid] = lo;
+  }
+  __syncthreads();
+  const uint32_t b_lo = lds[4], b_hi = lds[5];
+  if (tid == 0) atomicMax(&bagof[0], b_lo + 1);
+  for (uint32_t bag = b_lo + 1 + tid; bag <= b_hi; bag += 256) {
+    const int64_t start = offsets[bag];
+    if (start >= (int64_t)k0 && start < (int64_t)k1) atomicMax(&bagof[(uint32_t)start - k0], bag + 1);
+  }
+  __syncthreads();
+  // inclusive running maximum, 16 consecutive positions per thread
+  uint32_t v[16], m = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    v[i] = bagof[tid * 16 + i];
+    m = v[i] > m ? v[i] : m;
+    v[i] = m;
+  }
+  uint32_t inc = m;  // wave-level inclusive max-scan of the thread maxima
+  const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t t = __shfl_up(inc, d);
+    if (lane >= d && t > inc) inc = t;
+  }
+  if (lane == 63) lds[wave] = inc;
+  __syncthreads();
+  uint32_t before = __shfl_up(inc, 1);
+  if (lane == 0) before = 0;
+  for (int w = 0; w < wave; ++w) before = lds[w] > before ? lds[w] : before;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) bagof[tid * 16 + i] = v[i] > before ? v[i] : before;
+  __syncthreads();
+}
+
 __global__ __launch_bounds__(256) void bwd_rows(const int64_t* __restrict__ keys,
                                                 const int64_t* __restrict__ rows64,
                                                 const int64_t* __restrict__ offsets, uint32_t nnz,
@@ -207,23 +265,20 @@ __global__ __launch_bounds__(256) void bwd_rows(const int64_t* __restrict__ keys
   // One sort tile per block, so the block can also deliver the tile's histogram of the first sort
   // digit (the low bits of the row) and spare the sort its first counting pass.
   __shared__ uint32_t h[1 << kSortMaxDigitBits];
+  __shared__ uint32_t bagof[kSortTile];
+  __shared__ uint32_t small[6];
   const uint32_t mask = bins - 1;
+  const uint32_t k0 = blockIdx.x * kSortTile;
+  const uint32_t k1 = nnz - k0 < kSortTile ? nnz : k0 + kSortTile;
   for (uint32_t d = threadIdx.x; d < bins; d += 256) h[d] = 0;
-  __syncthreads();
+  if (offsets != nullptr) tile_bags(offsets, n_bags, k0, k1, bagof, small);
+  else __syncthreads();
   uint32_t nbad = 0;
 #pragma unroll 4
   for (int it = 0; it < (int)(kSortTile / 256); ++it) {
-    const uint32_t i = blockIdx.x * kSortTile + it * 256u + threadIdx.x;
+    const uint32_t i = k0 + it * 256u + threadIdx.x;
     if (i < nnz) {
-      uint32_t bag = i;
-      if (offsets != nullptr) {  // the bag with offsets[bag] <= i < offsets[bag + 1]
-        uint32_t lo = 0, hi = n_bags - 1;
-        while (lo < hi) {
-          const uint32_t mid = (lo + hi) >> 1;
-          if (offsets[mid + 1] <= (int64_t)i) lo = mid + 1; else hi = mid;
-        }
-        bag = lo;
-      }
+      const uint32_t bag = offsets != nullptr ? bagof[i - k0] - 1u : i;
       int64_t row = -1;
       if (rows64 != nullptr) {
         const int64_t r = rows64[i];
@@ -361,12 +416,13 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
     T* __restrict__ table, int D, const uint64_t* __restrict__ skv,
     const EmbHeader* __restrict__ hdr, const int64_t* __restrict__ offsets, int mean,
     const float* __restrict__ dY, float lr, float* __restrict__ head, float* __restrict__ tail,
-    uint8_t* __restrict__ tail_flag, uint32_t W) {
+    uint8_t* __restrict__ tail_flag, uint32_t W, EmbHeader* hdr_rw) {
   const int sub = threadIdx.x % LPR;
   const uint32_t win = (blockIdx.x * 256u + threadIdx.x) / LPR;
   const int col = blockIdx.y * (LPR * 4) + sub * 4;
   const bool active = col < D;
   const uint32_t n_valid = hdr->n_valid;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) hdr_rw->n_long = 0;   // for the carry kernels
   const uint64_t start64 = (uint64_t)win * W;
   if (start64 >= n_valid) return;
   const uint32_t start = (uint32_t)start64;
@@ -430,53 +486,100 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
   if (sub == 0 && blockIdx.y == 0) tail_flag[win] = wrote_tail ? 1 : 0;
 }
 
-// One block per window.  A window that holds the first piece of a border-crossing row gathers
-// that row: the block's 256/LPR lane groups each add a contiguous share of the following windows'
-// partials (8 loads in flight), the shares are staged in LDS and added in group order.
+// Rows that cross window borders.  The window holding a row's first piece owns the row; its last
+// window follows from seg_off.  bwd_carry_short gives every window a lane group: an owner with at
+// most kCarryShort following windows adds their partials itself (all loads in flight at once) and
+// updates the row; longer rows are queued.  bwd_carry_long then gives each queued row a whole block
+// of 1024 threads: the lane groups each add a contiguous share of the partials, the shares are
+// staged in LDS and added in group order.  Which row lands where in the queue does not matter:
+// every row's additions happen in an order fixed by its length alone.
+constexpr uint32_t kCarryShort = 8;
+
+__device__ __forceinline__ bool carry_extent(const uint64_t* __restrict__ skv,
+                                             const uint32_t* __restrict__ starts_before,
+                                             const uint32_t* __restrict__ seg_off, uint32_t win, uint32_t W,
+                                             uint32_t* row, uint32_t* last) {
+  // a tail exists only when the window is full and its last row continues into the next window
+  const uint32_t p = win * W + W - 1;
+  const uint32_t r = (uint32_t)(skv[p] >> 32);
+  const uint32_t u = starts_before[p] + ((p == 0 || (uint32_t)(skv[p - 1] >> 32) != r) ? 1u : 0u) - 1u;
+  *row = r;
+  *last = (seg_off[u + 1] - 1u) / W;   // last window holding a piece of the row
+  return true;
+}
+
 template <typename T, int LPR>
-__global__ __launch_bounds__(256) void bwd_reduce_carry(
+__global__ __launch_bounds__(256) void bwd_carry_short(
+    T* __restrict__ table, int D, const uint64_t* __restrict__ skv,
+    const uint32_t* __restrict__ starts_before, const uint32_t* __restrict__ seg_off, EmbHeader* hdr,
+    float lr, const float* __restrict__ head, const float* __restrict__ tail,
+    const uint8_t* __restrict__ tail_flag, uint32_t W, uint32_t* __restrict__ long_list) {
+  const int sub = threadIdx.x % LPR;
+  const uint32_t win = (blockIdx.x * 256u + threadIdx.x) / LPR;
+  const int col = blockIdx.y * (LPR * 4) + sub * 4;
+  const bool active = col < D;
+  if ((uint64_t)win * W >= hdr->n_valid) return;
+  if (!tail_flag[win]) return;
+  uint32_t r, last;
+  carry_extent(skv, starts_before, seg_off, win, W, &r, &last);
+  const uint32_t cnt = last - win;   // following windows, each with a head partial
+  if (cnt > kCarryShort) {
+    if (sub == 0 && blockIdx.y == 0) long_list[atomicAdd(&hdr->n_long, 1u)] = win;
+    return;
+  }
+  f32x4 h[kCarryShort];
+#pragma unroll
+  for (uint32_t k = 0; k < kCarryShort; ++k)
+    h[k] = (active && k < cnt) ? load4(head + (int64_t)(win + 1 + k) * D + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+  if (active) {
+    f32x4 tot = load4(tail + (int64_t)win * D + col);
+#pragma unroll
+    for (uint32_t k = 0; k < kCarryShort; ++k) { tot.x += h[k].x; tot.y += h[k].y; tot.z += h[k].z; tot.w += h[k].w; }
+    sgd_update4(table + (int64_t)r * D + col, tot, lr);
+  }
+}
+
+template <typename T, int LPR>
+__global__ __launch_bounds__(1024) void bwd_carry_long(
     T* __restrict__ table, int D, const uint64_t* __restrict__ skv,
     const uint32_t* __restrict__ starts_before, const uint32_t* __restrict__ seg_off,
     const EmbHeader* __restrict__ hdr, float lr, const float* __restrict__ head,
-    const float* __restrict__ tail, const uint8_t* __restrict__ tail_flag, uint32_t W) {
-  constexpr int NG = 256 / LPR;
-  __shared__ f32x4 part[256];
+    const float* __restrict__ tail, uint32_t W, const uint32_t* __restrict__ long_list) {
+  constexpr int NG = 1024 / LPR;
+  __shared__ f32x4 part[1024];
   const int sub = threadIdx.x % LPR, g = threadIdx.x / LPR;
-  const uint32_t win = blockIdx.x;
   const int col = blockIdx.y * (LPR * 4) + sub * 4;
   const bool active = col < D;
-  const uint32_t n_valid = hdr->n_valid;
-  const uint64_t start64 = (uint64_t)win * W;
-  if (start64 >= n_valid) return;   // block-uniform
-  if (!tail_flag[win]) return;      // block-uniform
-  // a tail exists only when the window is full and its last row continues into the next window
-  const uint32_t p = (uint32_t)start64 + W - 1;
-  const uint32_t r = (uint32_t)(skv[p] >> 32);
-  const uint32_t u = starts_before[p] + ((p == 0 || (uint32_t)(skv[p - 1] >> 32) != r) ? 1u : 0u) - 1u;  // segment of p
-  const uint32_t last = (seg_off[u + 1] - 1u) / W;  // last window holding a piece of the row
-  const uint32_t cnt = last - win;                   // following windows, each with a head partial
-  const uint32_t share = (cnt + NG - 1) / NG;
-  const uint32_t f0 = win + 1 + g * share;
-  const uint32_t f1 = (f0 + share < last + 1) ? f0 + share : last + 1;
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (uint32_t w2 = f0; w2 < f1; w2 += 8) {
-    f32x4 h[8];
+  const uint32_t n_long = hdr->n_long;
+  for (uint32_t i = blockIdx.x; i < n_long; i += gridDim.x) {   // block-uniform loop
+    const uint32_t win = long_list[i];
+    uint32_t r, last;
+    carry_extent(skv, starts_before, seg_off, win, W, &r, &last);
+    const uint32_t cnt = last - win;
+    const uint32_t share = (cnt + NG - 1) / NG;
+    const uint32_t f0 = win + 1 + g * share;
+    const uint32_t f1 = (f0 + share < last + 1) ? f0 + share : last + 1;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (uint32_t w2 = f0; w2 < f1; w2 += 8) {
+      f32x4 h[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
-      h[k] = (active && w2 + k < f1) ? load4(head + (int64_t)(w2 + k) * D + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int k = 0; k < 8; ++k)
+        h[k] = (active && w2 + k < f1) ? load4(head + (int64_t)(w2 + k) * D + col) : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int k = 0; k < 8; ++k) { acc.x += h[k].x; acc.y += h[k].y; acc.z += h[k].z; acc.w += h[k].w; }
-  }
-  part[threadIdx.x] = acc;
-  __syncthreads();
-  if (g == 0 && active) {
-    f32x4 tot = load4(tail + (int64_t)win * D + col);
-#pragma unroll
-    for (int gg = 0; gg < NG; ++gg) {
-      const f32x4 q = part[gg * LPR + sub];
-      tot.x += q.x; tot.y += q.y; tot.z += q.z; tot.w += q.w;
+      for (int k = 0; k < 8; ++k) { acc.x += h[k].x; acc.y += h[k].y; acc.z += h[k].z; acc.w += h[k].w; }
     }
-    sgd_update4(table + (int64_t)r * D + col, tot, lr);
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    if (g == 0 && active) {
+      f32x4 tot = load4(tail + (int64_t)win * D + col);
+#pragma unroll 8
+      for (int gg = 0; gg < NG; ++gg) {
+        const f32x4 q = part[gg * LPR + sub];
+        tot.x += q.x; tot.y += q.y; tot.z += q.z; tot.w += q.w;
+      }
+      sgd_update4(table + (int64_t)r * D + col, tot, lr);
+    }
+    __syncthreads();   // part is reused by the next row
   }
 }
 
@@ -485,7 +588,7 @@ __global__ __launch_bounds__(256) void bwd_reduce_carry(
 // ------------------------------------------------------------------------------------------------
 struct EmbLayout {
   // byte offsets into the workspace (all multiples of 256)
-  size_t header, kv0, kv1, hist, aux, seg_counts, flags, uniq, seg_off, head, tail,
+  size_t header, kv0, kv1, hist, aux, seg_counts, flags, uniq, seg_off, long_list, head, tail,
       tail_flag, rows64, hash_ws, total;
   uint32_t window, n_windows, seg_tiles, seg_super;
   int sort_bits;
@@ -513,6 +616,7 @@ static EmbLayout emb_layout(const hctr_emb_desc* d, int64_t nnz_max) {
   L.flags = at(n * 4);
   L.uniq = at(n * 4);
   L.seg_off = at((n + 1) * 4);
+  L.long_list = at((size_t)L.n_windows * 4);
   L.head = at((size_t)L.n_windows * d->dim * 4);
   L.tail = at((size_t)L.n_windows * d->dim * 4);
   L.tail_flag = at(L.n_windows);
@@ -652,12 +756,17 @@ static void launch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, 
   uint8_t* tflag = reinterpret_cast<uint8_t*>(ws + L.tail_flag);
   const int mean = (d->combiner == HCTR_MEAN && offsets != nullptr) ? 1 : 0;
   hipLaunchKernelGGL((bwd_reduce_windows<T, LPR>), grid, dim3(256), 0, stream, table, d->dim, skv,
-                     (const EmbHeader*)hdr, offsets, mean, dY, lr, head, tail, tflag, L.window);
-  dim3 cgrid(L.n_windows, ychunks);
-  hipLaunchKernelGGL((bwd_reduce_carry<T, LPR>), cgrid, dim3(256), 0, stream, table, d->dim, skv,
-                     reinterpret_cast<const uint32_t*>(ws + L.flags),
-                     reinterpret_cast<const uint32_t*>(ws + L.seg_off), (const EmbHeader*)hdr, lr,
-                     (const float*)head, (const float*)tail, (const uint8_t*)tflag, L.window);
+                     (const EmbHeader*)hdr, offsets, mean, dY, lr, head, tail, tflag, L.window, hdr);
+  uint32_t* long_list = reinterpret_cast<uint32_t*>(ws + L.long_list);
+  const uint32_t* starts_before = reinterpret_cast<const uint32_t*>(ws + L.flags);
+  const uint32_t* seg_off = reinterpret_cast<const uint32_t*>(ws + L.seg_off);
+  hipLaunchKernelGGL((bwd_carry_short<T, LPR>), grid, dim3(256), 0, stream, table, d->dim, skv, starts_before,
+                     seg_off, hdr, lr, (const float*)head, (const float*)tail, (const uint8_t*)tflag, L.window,
+                     long_list);
+  dim3 lgrid(L.n_windows < 256u ? L.n_windows : 256u, ychunks);
+  hipLaunchKernelGGL((bwd_carry_long<T, LPR>), lgrid, dim3(1024), 0, stream, table, d->dim, skv, starts_before,
+                     seg_off, (const EmbHeader*)hdr, lr, (const float*)head, (const float*)tail, L.window,
+                     (const uint32_t*)long_list);
 }
 
 template <typename T>
