@@ -60,6 +60,12 @@ def lib() -> C.CDLL:
         L.oracle_cache_stats.argtypes = [p, p]
         L.oracle_cache_state.restype = None
         L.oracle_cache_state.argtypes = [p, p, p, p]
+        L.oracle_cache_insert.restype = None
+        L.oracle_cache_insert.argtypes = [p, p, i64]
+        L.oracle_cache_update.restype = i64
+        L.oracle_cache_update.argtypes = [p, p, p, i64]
+        L.oracle_cache_refresh.restype = None
+        L.oracle_cache_refresh.argtypes = [p]
         L.oracle_cache_query.restype = None
         L.oracle_cache_query.argtypes = [p, i64, p, p, i64, i64, i32, p, p]
         _lib = L
@@ -188,6 +194,20 @@ class Cache:
         lib().oracle_cache_query(self._c, n_bags, _ptr(keys), _ptr(offsets), hot, nnz,
                                  int(bool(insert_missing)), _ptr(out), _ptr(hit))
         return out, hit
+
+    def insert(self, keys) -> None:
+        keys = _i64(keys)
+        lib().oracle_cache_insert(self._c, _ptr(keys), len(keys))
+
+    def update(self, keys, rows: np.ndarray) -> int:
+        """Overwrite the cached rows of resident keys (last row of a repeated key wins)."""
+        keys = _i64(keys)
+        rows = np.ascontiguousarray(rows, dtype=np.float32).reshape(len(keys), self.dim)
+        return int(lib().oracle_cache_update(self._c, _ptr(keys), _ptr(rows), len(keys)))
+
+    def refresh(self) -> None:
+        """Every resident line re-reads its row from the host table (in place, as it is now)."""
+        lib().oracle_cache_refresh(self._c)
 
     @property
     def stats(self) -> np.ndarray:

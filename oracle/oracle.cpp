@@ -307,4 +307,44 @@ void oracle_cache_query(oracle_cache* c, int64_t n_bags, const int64_t* keys,
   }
 }
 
+// Manipulation operators of the cache (section 3, "embedding inference cache": query and
+// manipulation operators, refresh; "Online model updating": cached embeddings are replaced when
+// updates arrive).
+//
+// Insert: one call (epoch) that classifies and inserts like a query but pools nothing.
+void oracle_cache_insert(oracle_cache* c, const int64_t* keys, int64_t n) {
+  std::vector<float> sink((size_t)(n > 0 ? n : 1) * c->dim);
+  oracle_cache_query(c, n, keys, nullptr, 1, n, 1, sink.data(), nullptr);
+}
+
+// Update: for i = 0..n-1 in order, if keys[i] is resident its cached row becomes rows[i, :] (so the
+// last of several rows for one key wins).  Keys that are not resident are ignored; tags, stamps,
+// the epoch and the statistics do not change.  Returns the number of resident keys met (with
+// repetitions).
+int64_t oracle_cache_update(oracle_cache* c, const int64_t* keys, const float* rows, int64_t n) {
+  const int W = c->ways, D = c->dim;
+  int64_t met = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    if (keys[i] < 0) continue;
+    int64_t set = cache_set_of((uint64_t)keys[i], c->num_sets);
+    for (int w = 0; w < W; ++w) {
+      if (c->tag[set * W + w] == (uint64_t)keys[i]) {
+        std::memcpy(&c->data[(set * W + w) * D], &rows[i * D], sizeof(float) * D);
+        ++met;
+        break;
+      }
+    }
+  }
+  return met;
+}
+
+// Refresh: every resident line re-reads its row from the host table as it is now.
+void oracle_cache_refresh(oracle_cache* c) {
+  const int D = c->dim;
+  for (size_t line = 0; line < c->tag.size(); ++line) {
+    if (c->tag[line] == kEmptyTag) continue;
+    std::memcpy(&c->data[line * D], &c->host_table[(int64_t)c->tag[line] * D], sizeof(float) * D);
+  }
+}
+
 }  // extern "C"

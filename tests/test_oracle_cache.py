@@ -131,3 +131,53 @@ def test_set_index_spreads_scrambled_keys_evenly():
     cnt = np.bincount([set_of(int(k), num_sets) for k in keys], minlength=num_sets)
     chi2 = ((cnt - 50000 / num_sets) ** 2 / (50000 / num_sets)).sum()
     assert chi2 < 2 * num_sets
+
+
+# ---- manipulation operators (section 3: "query and manipulation operators", refresh; "Online model
+# ---- updating": cached embeddings are replaced when updates arrive)
+
+def test_insert_is_a_query_without_output():
+    ht = host_table(400, 4)
+    a, b = oracle.Cache(8, 2, ht), oracle.Cache(8, 2, ht)
+    for _ in range(12):
+        keys = RNG.integers(0, 60, 40)
+        a.query(keys, 40)
+        b.insert(keys)
+        ta, sa = a.state(); tb, sb = b.state()
+        assert np.array_equal(ta, tb) and np.array_equal(sa, sb) and np.array_equal(a.stats, b.stats)
+
+
+def test_update_replaces_resident_rows_only_and_last_row_wins():
+    ht = host_table(64, 4)
+    c = oracle.Cache(1, 4, ht)
+    c.query(np.array([3, 5, 7]), 3)                       # resident: 3, 5, 7 in ways 0, 1, 2
+    before_tags, before_stamps = c.state()
+    s0 = c.stats.copy()
+    rows = np.arange(5 * 4, dtype=np.float32).reshape(5, 4) + 1000
+    met = c.update(np.array([5, 9, 3, 5, -1]), rows)      # 9 and -1 are not resident; 5 comes twice
+    assert met == 3
+    tags, stamps, data = c.state(with_data=True)
+    assert np.array_equal(tags, before_tags) and np.array_equal(stamps, before_stamps) and np.array_equal(c.stats, s0)
+    assert np.array_equal(data[0], rows[2])               # key 3 <- its only row
+    assert np.array_equal(data[1], rows[3])               # key 5 <- the later of its two rows
+    assert np.array_equal(data[2], ht[7])                 # key 7 untouched
+    out, hit = c.query(np.array([5, 9, 3, 7]), 1, insert_missing=False)   # one bag of four keys
+    assert hit.tolist() == [1, 0, 1, 1]
+    want = (rows[3].astype(np.float64) + ht[9] + rows[2] + ht[7]).astype(np.float32)
+    assert np.array_equal(out[0], want)                   # hits read the cache, the miss reads the host table
+
+
+def test_refresh_rereads_every_resident_row_from_the_host_table():
+    ht = host_table(64, 4)
+    c = oracle.Cache(4, 2, ht)
+    c.query(np.arange(10), 10)
+    tags0, stamps0 = c.state()
+    ht[:] += 0.5                                          # the level-2 store changed underneath the cache
+    _, _, stale = c.state(with_data=True)
+    live = (tags0 != oracle.EMPTY_TAG).ravel()
+    assert not np.array_equal(stale[live], ht[tags0.ravel()[live].astype(np.int64)])
+    c.refresh()
+    tags, stamps, data = c.state(with_data=True)
+    assert np.array_equal(tags, tags0) and np.array_equal(stamps, stamps0)
+    assert np.array_equal(data[live], ht[tags.ravel()[live].astype(np.int64)])
+    assert np.all(data[~live] == 0)                       # empty lines are left alone
