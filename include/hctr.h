@@ -213,6 +213,33 @@ hctr_status hctr_cache_set_small_call_limit(hctr_cache* cache, int64_t max_keys)
 hctr_status hctr_cache_query(hctr_cache* cache, int64_t batch, int32_t num_slots, const int64_t* keys,
                              const int64_t* offsets, int64_t nnz, int32_t insert_missing, float* out,
                              uint8_t* hit_mask, void* ws, size_t ws_bytes, void* stream);
+/*
+ * Manipulation operators (section 3, "embedding inference cache": query and manipulation operators,
+ * dynamic insertion, asynchronous refresh; "Online model updating": cached embeddings are replaced
+ * when updates arrive and the cache periodically re-reads its contents).
+ *
+ * hctr_cache_query_async  as hctr_cache_query, and records `results_ready_event` (a hipEvent_t
+ *     created by the caller) on `stream` as soon as `out` and `hit_mask` are complete, i.e. before
+ *     the insertion work of the call is enqueued: a consumer on another stream can wait for the
+ *     event and overlap its own work with the insertion.
+ * hctr_cache_insert   one call (epoch) that classifies `keys` [n] and inserts the missing ones
+ *     exactly as hctr_cache_query(insert_missing = 1) does, but pools nothing.
+ * hctr_cache_update   for every key of `keys` [n] that is resident, the cached row is replaced by
+ *     its row of `rows` (device [n, dim] fp32, 16-byte aligned); of several rows given for one key
+ *     the last one wins.  Keys that are not resident are ignored; tags, stamps, statistics and the
+ *     call counter do not change.  ws >= hctr_cache_workspace_bytes(cache, n).
+ * hctr_cache_refresh  every resident line re-reads its row from the host table as it is now.
+ */
+hctr_status hctr_cache_query_async(hctr_cache* cache, int64_t batch, int32_t num_slots, const int64_t* keys,
+                                   const int64_t* offsets, int64_t nnz, int32_t insert_missing, float* out,
+                                   uint8_t* hit_mask, void* ws, size_t ws_bytes, void* stream,
+                                   void* results_ready_event);
+hctr_status hctr_cache_insert(hctr_cache* cache, const int64_t* keys, int64_t n, void* ws, size_t ws_bytes,
+                              void* stream);
+hctr_status hctr_cache_update(hctr_cache* cache, const int64_t* keys, const float* rows, int64_t n, void* ws,
+                              size_t ws_bytes, void* stream);
+hctr_status hctr_cache_refresh(hctr_cache* cache, void* stream);
+
 /* stats[6] (host) = cumulative {keys queried, hits, misses, inserts, evictions, skipped inserts};
  * waits for the stream. */
 hctr_status hctr_cache_stats(hctr_cache* cache, void* stream, int64_t stats[6]);

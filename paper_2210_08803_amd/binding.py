@@ -70,6 +70,10 @@ def lib() -> C.CDLL:
         "hctr_cache_workspace_bytes": (sz, [p, i64]),
         "hctr_cache_set_small_call_limit": (i32, [p, i64]),
         "hctr_cache_query": (i32, [p, i64, i32, p, p, i64, i32, p, p, p, sz, p]),
+        "hctr_cache_query_async": (i32, [p, i64, i32, p, p, i64, i32, p, p, p, sz, p, p]),
+        "hctr_cache_insert": (i32, [p, p, i64, p, sz, p]),
+        "hctr_cache_update": (i32, [p, p, p, i64, p, sz, p]),
+        "hctr_cache_refresh": (i32, [p, p]),
         "hctr_cache_stats": (i32, [p, p, C.POINTER(i64)]),
         "hctr_cache_state_view": (i32, [p, C.POINTER(p), C.POINTER(p), C.POINTER(p)]),
         "hctr_cache_destroy": (None, [p]),
@@ -87,7 +91,8 @@ EXPORTS = [
     "hctr_emb_backward_apply", "hctr_emb_dedup_view",
     "hctr_emb_invalid_keys", "hctr_hash_storage_bytes", "hctr_hash_create", "hctr_hash_workspace_bytes",
     "hctr_hash_insert_or_find", "hctr_hash_size", "hctr_hash_destroy", "hctr_cache_storage_bytes",
-    "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_set_small_call_limit", "hctr_cache_query", "hctr_cache_stats",
+    "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_set_small_call_limit", "hctr_cache_query",
+    "hctr_cache_query_async", "hctr_cache_insert", "hctr_cache_update", "hctr_cache_refresh", "hctr_cache_stats",
     "hctr_cache_state_view", "hctr_cache_destroy", "hctr_last_error",
 ]
 
@@ -299,6 +304,37 @@ class EmbeddingCache:
                                       int(insert_missing), _ptr(out), _ptr(hit_mask), _ptr(ws), ws.numel(),
                                       _stream(stream)))
         return out
+
+    def query_async(self, batch: int, num_slots: int, keys: torch.Tensor, ready: torch.cuda.Event,
+                    offsets: Optional[torch.Tensor] = None, insert_missing: bool = True,
+                    out: Optional[torch.Tensor] = None, hit_mask: Optional[torch.Tensor] = None,
+                    ws: Optional[torch.Tensor] = None, stream=None):
+        """As query(); `ready` (a torch.cuda.Event) fires when out / hit_mask are complete."""
+        nnz = keys.numel()
+        if out is None:
+            out = torch.empty((batch, num_slots, self.dim), dtype=torch.float32, device=self.device)
+        if ws is None:
+            ws = self.workspace(nnz)
+        ready.record(torch.cuda.current_stream() if stream is None else stream)   # makes torch create the event
+        _check(lib().hctr_cache_query_async(self.handle, batch, num_slots, _ptr(keys), _ptr(offsets), nnz,
+                                            int(insert_missing), _ptr(out), _ptr(hit_mask), _ptr(ws),
+                                            ws.numel(), _stream(stream), ready.cuda_event))
+        return out
+
+    def insert(self, keys: torch.Tensor, ws: Optional[torch.Tensor] = None, stream=None) -> None:
+        if ws is None:
+            ws = self.workspace(keys.numel())
+        _check(lib().hctr_cache_insert(self.handle, _ptr(keys), keys.numel(), _ptr(ws), ws.numel(), _stream(stream)))
+
+    def update(self, keys: torch.Tensor, rows: torch.Tensor, ws: Optional[torch.Tensor] = None, stream=None) -> None:
+        assert rows.dtype == torch.float32 and rows.is_contiguous() and rows.shape == (keys.numel(), self.dim)
+        if ws is None:
+            ws = self.workspace(keys.numel())
+        _check(lib().hctr_cache_update(self.handle, _ptr(keys), _ptr(rows), keys.numel(), _ptr(ws), ws.numel(),
+                                       _stream(stream)))
+
+    def refresh(self, stream=None) -> None:
+        _check(lib().hctr_cache_refresh(self.handle, _stream(stream)))
 
     @property
     def stats(self):

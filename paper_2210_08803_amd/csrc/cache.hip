@@ -429,7 +429,8 @@ __global__ __launch_bounds__(256) void cache_query_small(const u64* __restrict__
     b1 = offsets ? offsets[bag + 1] : (int64_t)(bag + 1) * hotness;
   }
   // no line of a small call is staged; `data` only fills the staging argument
-  gather_bag<LPR, 4>(data, data, host_table, host_rows, D, keys, line_of, b0, b1, live, bag, out, part[wave]);
+  if (out != nullptr)   // uniform: an insert-only call pools nothing
+    gather_bag<LPR, 4>(data, data, host_table, host_rows, D, keys, line_of, b0, b1, live, bag, out, part[wave]);
 }
 
 // The whole insertion of a small call in one block of 1024 threads (n <= kSmallMaxKeys keys).
@@ -557,6 +558,81 @@ __global__ __launch_bounds__(1024) void cache_insert_small(u64* __restrict__ tag
     for (int col = (tid % kCopyLanes) * 4; col < D; col += kCopyLanes * 4) store4(to + col, load4(src + col));
   }
   if (tid < 3 && counters[tid]) atomicAdd(&hdr->stats[3 + tid], (u64)counters[tid]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Manipulation operators
+// ------------------------------------------------------------------------------------------------
+
+// Update, step 1: position i' of the REVERSED key list (key = keys[n-1-i']) is probed; resident keys
+// are flagged and remembered with their line.  The first-appearance dedup over the reversed list
+// then marks, per key, its last occurrence in the caller's order - the row that must win.
+template <int WAYS>
+__global__ __launch_bounds__(256) void cache_update_probe(const u64* __restrict__ tags, SetDiv num_sets,
+                                                          const int64_t* __restrict__ keys, uint32_t n,
+                                                          int64_t* __restrict__ keys_rev,
+                                                          uint32_t* __restrict__ line_of,
+                                                          uint32_t* __restrict__ flag) {
+  const int way = threadIdx.x % WAYS;
+  const int lane = threadIdx.x & 63;
+  constexpr uint64_t kGroupOnes = WAYS == 64 ? ~0ull : ((1ull << (WAYS & 63)) - 1ull);
+  const uint64_t gmask = kGroupOnes << (lane - way);
+  const uint32_t n_groups = gridDim.x * (256u / WAYS);
+  const uint32_t rounds = (n + n_groups - 1) / n_groups;   // same trip count for every lane
+  for (uint32_t r = 0; r < rounds; ++r) {
+    const uint32_t ip = r * n_groups + (blockIdx.x * 256u + threadIdx.x) / WAYS;
+    const int64_t key = ip < n ? keys[n - 1 - ip] : -1;
+    u64 slot = 0;
+    bool match = false;
+    if (key >= 0) {
+      slot = set_of((u64)key, num_sets) * WAYS + way;
+      match = tags[slot] == (u64)key;
+    }
+    const uint64_t mine = __ballot(match) & gmask;
+    const bool hit = mine != 0;
+    uint32_t line = match ? (uint32_t)slot : kNoLine;
+    if (hit) line = __shfl(line, __ffsll((unsigned long long)mine) - 1);
+    if (way == 0 && ip < n) {
+      keys_rev[ip] = key;
+      line_of[ip] = hit ? line : kNoLine;
+      flag[ip] = hit ? 1u : 0u;
+    }
+  }
+}
+
+// Update, step 2: the winners copy their rows into the cache lines.
+template <int LPR>
+__global__ __launch_bounds__(256) void cache_update_copy(float* __restrict__ data, int D,
+                                                         const HashWsHeader* hdr,
+                                                         const uint32_t* __restrict__ miss_pos,
+                                                         const uint32_t* __restrict__ first,
+                                                         const uint32_t* __restrict__ line_of,
+                                                         const float* __restrict__ rows, uint32_t n) {
+  const int sub = threadIdx.x % LPR;
+  const uint32_t n_res = hdr->n_miss;   // here: number of resident positions
+  for (uint32_t m = (blockIdx.x * 256u + threadIdx.x) / LPR; m < n_res; m += gridDim.x * (256u / LPR)) {
+    if (!first[m]) continue;
+    const uint32_t ip = miss_pos[m];
+    const float* src = rows + (int64_t)(n - 1 - ip) * D;
+    float* to = data + (int64_t)line_of[ip] * D;
+    for (int col = sub * 4; col < D; col += LPR * 4) store4(to + col, load4(src + col));
+  }
+}
+
+// Refresh: every resident line re-reads its row from the host table.
+template <int LPR>
+__global__ __launch_bounds__(256) void cache_refresh_lines(const u64* __restrict__ tags, float* __restrict__ data,
+                                                           const float* __restrict__ host_table, int D,
+                                                           uint64_t n_lines) {
+  const int sub = threadIdx.x % LPR;
+  for (uint64_t line = (blockIdx.x * 256ull + threadIdx.x) / LPR; line < n_lines;
+       line += (uint64_t)gridDim.x * (256u / LPR)) {
+    const u64 tag = tags[line];
+    if (tag == kEmptyKey) continue;
+    const float* src = host_table + (int64_t)tag * D;
+    float* to = data + (int64_t)line * D;
+    for (int col = sub * 4; col < D; col += LPR * 4) store4(to + col, load4(src + col));
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -776,10 +852,12 @@ HCTR_API size_t hctr_cache_workspace_bytes(const hctr_cache* cache, int64_t nnz_
   return cache_ws_layout(&general, nnz_max).total;
 }
 
-HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_slots, const int64_t* keys,
-                                      const int64_t* offsets, int64_t nnz, int32_t insert_missing,
-                                      float* out, uint8_t* hit_mask, void* ws, size_t ws_bytes,
-                                      void* stream_) {
+// One query call.  out == nullptr pools nothing (insert-only); ready != nullptr is recorded on the
+// stream as soon as out and hit_mask are complete, before the insertion work is enqueued.
+static hctr_status cache_query_impl(hctr_cache* c, int64_t batch, int32_t num_slots, const int64_t* keys,
+                                    const int64_t* offsets, int64_t nnz, int32_t insert_missing, float* out,
+                                    bool need_out, uint8_t* hit_mask, void* ws, size_t ws_bytes, void* stream_,
+                                    hipEvent_t ready) {
   if (!c) return fail(HCTR_E_NULL_PTR, "cache is NULL");
   if (batch < 0 || num_slots < 1 || nnz < 0) return fail(HCTR_E_INVALID_ARG, "batch / num_slots / nnz invalid");
   const int64_t n_bags = batch * num_slots;
@@ -795,9 +873,9 @@ HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_
     if (nnz != 0) return fail(HCTR_E_INVALID_ARG, "nnz must be 0 when there are no bags");
     return HCTR_OK;
   }
-  if (!out) return fail(HCTR_E_NULL_PTR, "out is NULL");
+  if (!out && need_out) return fail(HCTR_E_NULL_PTR, "out is NULL");
   if (nnz > 0 && !keys) return fail(HCTR_E_NULL_PTR, "keys is NULL");
-  if ((uintptr_t)out % 16 != 0) return fail(HCTR_E_INVALID_ARG, "out must be 16-byte aligned");
+  if (out && (uintptr_t)out % 16 != 0) return fail(HCTR_E_INVALID_ARG, "out must be 16-byte aligned");
   const CacheWsLayout L = cache_ws_layout(c, nnz);
   if (!ws) return fail(HCTR_E_WORKSPACE, "workspace is NULL");
   if ((uintptr_t)ws % 256 != 0) return fail(HCTR_E_WORKSPACE, "workspace must be 256-byte aligned");
@@ -817,6 +895,7 @@ HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_
 #define CALL(W) dispatch_query_small<W>(lpr, a)
     HCTR_BY_WAYS(c->ways, CALL)
 #undef CALL
+    if (ready) HCTR_TRY_HIP(hipEventRecord(ready, a.stream));
     if (insert_missing && nnz > 0) {
 #define CALL(W) launch_insert_small<W>(a)
       HCTR_BY_WAYS(c->ways, CALL)
@@ -829,9 +908,12 @@ HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_
   HCTR_BY_WAYS(c->ways, CALL)
 #undef CALL
   if (!insert_missing) {
+    if (out) {
 #define CALL(LL) launch_gather<LL>(a, nullptr)
-    HCTR_BY_LPR(lpr, CALL)
+      HCTR_BY_LPR(lpr, CALL)
 #undef CALL
+    }
+    if (ready) HCTR_TRY_HIP(hipEventRecord(ready, a.stream));
     return launch_status("hctr_cache_query");
   }
   DedupBuffers B{a.flag,
@@ -859,9 +941,12 @@ HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_
 #define CALL(LL) launch_fetch_fill<LL>(a, ws_hdr, new_key, staging, dst, false)
   HCTR_BY_LPR(lpr, CALL)
 #undef CALL
+  if (out) {
 #define CALL(LL) launch_gather<LL>(a, staging)
-  HCTR_BY_LPR(lpr, CALL)
+    HCTR_BY_LPR(lpr, CALL)
 #undef CALL
+  }
+  if (ready) HCTR_TRY_HIP(hipEventRecord(ready, a.stream));
   HCTR_TRY(radix_sort_u64(L.sort, &ws_hdr->n_new, reinterpret_cast<uint64_t*>(kv[0]),
                           reinterpret_cast<uint64_t*>(kv[1]), reinterpret_cast<uint32_t*>(w + L.hist),
                           reinterpret_cast<uint32_t*>(w + L.aux), false, a.stream));
@@ -873,6 +958,95 @@ HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_
   HCTR_BY_LPR(lpr, CALL)
 #undef CALL
   return launch_status("hctr_cache_query");
+}
+
+HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_slots, const int64_t* keys,
+                                      const int64_t* offsets, int64_t nnz, int32_t insert_missing,
+                                      float* out, uint8_t* hit_mask, void* ws, size_t ws_bytes,
+                                      void* stream) {
+  return cache_query_impl(c, batch, num_slots, keys, offsets, nnz, insert_missing, out, true, hit_mask, ws,
+                          ws_bytes, stream, nullptr);
+}
+
+HCTR_API hctr_status hctr_cache_query_async(hctr_cache* c, int64_t batch, int32_t num_slots,
+                                            const int64_t* keys, const int64_t* offsets, int64_t nnz,
+                                            int32_t insert_missing, float* out, uint8_t* hit_mask, void* ws,
+                                            size_t ws_bytes, void* stream, void* results_ready_event) {
+  if (!results_ready_event) return fail(HCTR_E_NULL_PTR, "results_ready_event is NULL");
+  return cache_query_impl(c, batch, num_slots, keys, offsets, nnz, insert_missing, out, true, hit_mask, ws,
+                          ws_bytes, stream, static_cast<hipEvent_t>(results_ready_event));
+}
+
+HCTR_API hctr_status hctr_cache_insert(hctr_cache* c, const int64_t* keys, int64_t n, void* ws, size_t ws_bytes,
+                                       void* stream) {
+  if (n == 0) return c ? HCTR_OK : fail(HCTR_E_NULL_PTR, "cache is NULL");
+  return cache_query_impl(c, n, 1, keys, nullptr, n, 1, nullptr, false, nullptr, ws, ws_bytes, stream, nullptr);
+}
+
+HCTR_API hctr_status hctr_cache_update(hctr_cache* c, const int64_t* keys, const float* rows, int64_t n, void* ws,
+                                       size_t ws_bytes, void* stream_) {
+  if (!c) return fail(HCTR_E_NULL_PTR, "cache is NULL");
+  if (n < 0 || n >= (1ll << 31)) return fail(HCTR_E_INVALID_ARG, "n %lld outside 0..2^31-1", (long long)n);
+  if (n == 0) return HCTR_OK;
+  if (!keys || !rows) return fail(HCTR_E_NULL_PTR, "keys / rows is NULL");
+  if ((uintptr_t)rows % 16 != 0) return fail(HCTR_E_INVALID_ARG, "rows must be 16-byte aligned");
+  hctr_cache general = *c;
+  general.small_max_keys = 0;   // update always uses the general workspace layout
+  const CacheWsLayout L = cache_ws_layout(&general, n);
+  if (!ws) return fail(HCTR_E_WORKSPACE, "workspace is NULL");
+  if ((uintptr_t)ws % 256 != 0) return fail(HCTR_E_WORKSPACE, "workspace must be 256-byte aligned");
+  if (ws_bytes < L.total) return fail(HCTR_E_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, L.total);
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  char* w = static_cast<char*>(ws);
+  HashWsHeader* ws_hdr = reinterpret_cast<HashWsHeader*>(w + L.header);
+  uint32_t* line_of = reinterpret_cast<uint32_t*>(w + L.line_of);
+  int64_t* keys_rev = reinterpret_cast<int64_t*>(w + L.new_key);
+  DedupBuffers B{reinterpret_cast<uint32_t*>(w + L.flag),
+                 reinterpret_cast<uint32_t*>(w + L.idx),
+                 reinterpret_cast<uint32_t*>(w + L.miss_pos),
+                 reinterpret_cast<uint32_t*>(w + L.scr_slot),
+                 reinterpret_cast<uint32_t*>(w + L.first),
+                 reinterpret_cast<uint32_t*>(w + L.rank),
+                 reinterpret_cast<uint32_t*>(w + L.scan_tmp),
+                 reinterpret_cast<u64*>(w + L.scratch),
+                 L.scratch_cap_max,
+                 &ws_hdr->n_miss,
+                 &ws_hdr->n_new};
+  const uint32_t nn = (uint32_t)n;
+  const u64* tags = reinterpret_cast<const u64*>(c->storage + c->off_tags);
+  float* data = reinterpret_cast<float*>(c->storage + c->off_data);
+#define CALL(W)                                                                                               \
+  hipLaunchKernelGGL((cache_update_probe<W>),                                                                 \
+                     dim3((uint32_t)std::min<int64_t>(ceil_div((int64_t)nn * W, 256), 2048)), dim3(256), 0,   \
+                     stream, tags, make_set_div(c->num_sets), keys, nn, keys_rev, line_of, B.flag)
+  HCTR_BY_WAYS(c->ways, CALL)
+#undef CALL
+  HCTR_TRY(dedup_first_appearance(keys_rev, nn, B, stream));
+  int lpr = pow2_ceil((int)ceil_div(c->dim, 4));
+  lpr = lpr < 4 ? 4 : (lpr > 64 ? 64 : lpr);
+#define CALL(LL)                                                                                              \
+  hipLaunchKernelGGL((cache_update_copy<LL>),                                                                 \
+                     dim3((uint32_t)std::min<int64_t>(ceil_div((int64_t)nn * LL, 256), 4096)), dim3(256), 0,  \
+                     stream, data, (int)c->dim, (const HashWsHeader*)ws_hdr, (const uint32_t*)B.miss_pos,     \
+                     (const uint32_t*)B.first, (const uint32_t*)line_of, rows, nn)
+  HCTR_BY_LPR(lpr, CALL)
+#undef CALL
+  return launch_status("hctr_cache_update");
+}
+
+HCTR_API hctr_status hctr_cache_refresh(hctr_cache* c, void* stream) {
+  if (!c) return fail(HCTR_E_NULL_PTR, "cache is NULL");
+  const uint64_t lines = (uint64_t)c->num_sets * c->ways;
+  int lpr = pow2_ceil((int)ceil_div(c->dim, 4));
+  lpr = lpr < 4 ? 4 : (lpr > 64 ? 64 : lpr);
+#define CALL(LL)                                                                                              \
+  hipLaunchKernelGGL((cache_refresh_lines<LL>),                                                               \
+                     dim3((uint32_t)std::min<int64_t>(ceil_div((int64_t)lines * LL, 256), 8192)), dim3(256),  \
+                     0, static_cast<hipStream_t>(stream), reinterpret_cast<const u64*>(c->storage + c->off_tags), \
+                     reinterpret_cast<float*>(c->storage + c->off_data), c->host_table, (int)c->dim, lines)
+  HCTR_BY_LPR(lpr, CALL)
+#undef CALL
+  return launch_status("hctr_cache_refresh");
 }
 
 HCTR_API hctr_status hctr_cache_stats(hctr_cache* c, void* stream, int64_t stats[6]) {

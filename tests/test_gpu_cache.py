@@ -129,3 +129,93 @@ def test_paths_switch_back_and_forth_on_one_cache():
         n_bags = batch * 26
         keys = datagen.cache_keys(SEED, 50 + it, host_rows, n_bags * 4, 1.2, sampler=smp).numpy()
         p.query(keys, n_bags, what=f"mixed {it} (batch {batch})")
+
+
+# ---- manipulation operators ---------------------------------------------------------------------
+
+def _state_equal(p, what):
+    tags, stamps = p.gpu.state()
+    rtags, rstamps, rdata = p.ref.state(with_data=True)
+    assert np.array_equal(tags.numpy().view(np.uint64), rtags), f"{what}: tags differ"
+    assert np.array_equal(stamps.numpy().astype(np.uint32), rstamps), f"{what}: stamps differ"
+    live = (rtags != oracle.EMPTY_TAG).ravel()
+    assert np.array_equal(p.gpu.data().cpu().numpy()[live], rdata[live]), f"{what}: cached rows differ"
+    assert p.gpu.stats == p.ref.stats.tolist(), f"{what}: stats differ"
+
+
+@pytest.mark.parametrize("small_limit", [0, 4096], ids=["general", "fused-small"])
+def test_insert_only_calls(small_limit):
+    host_rows, dim = 3000, 32
+    p = Pair(16, 8, pinned_table(host_rows, dim), small_limit)
+    smp = datagen.ZipfSampler(host_rows, 1.2)
+    for it in range(6):
+        keys = datagen.cache_keys(SEED, 200 + it, host_rows, 700, 1.2, sampler=smp).numpy()
+        if it == 3:
+            keys[::9] = host_rows + 1
+        p.ref.insert(keys)
+        p.gpu.insert(to_dev(keys))
+        torch.cuda.synchronize()
+        _state_equal(p, f"insert {it}")
+    p.query(datagen.cache_keys(SEED, 300, host_rows, 400, 1.2, sampler=smp).numpy(), 100, what="query after inserts")
+
+
+def test_update_then_query_reads_the_new_rows():
+    host_rows, dim = 2000, 64
+    p = Pair(32, 4, pinned_table(host_rows, dim))
+    smp = datagen.ZipfSampler(host_rows, 1.2)
+    rng = np.random.default_rng(11)
+    for it in range(4):
+        p.query(datagen.cache_keys(SEED, 400 + it, host_rows, 600, 1.2, sampler=smp).numpy(), 150, what=f"warm {it}")
+    for it in range(3):
+        n = [5000, 37, 1][it]
+        keys = datagen.cache_keys(SEED, 500 + it, host_rows, n, 1.2, sampler=smp).numpy()   # many repeats
+        keys[rng.integers(0, n, max(1, n // 20))] = -7
+        rows = rng.standard_normal((n, dim)).astype(np.float32)
+        met = p.ref.update(keys, rows)
+        p.gpu.update(to_dev(keys), to_dev(rows))
+        torch.cuda.synchronize()
+        _state_equal(p, f"update {it}")
+        assert met > 0 or n == 1
+    # a query now mixes updated cached rows (hits) with host rows (misses)
+    keys = datagen.cache_keys(SEED, 600, host_rows, 800, 1.2, sampler=smp).numpy()
+    ref_out, ref_hit = p.ref.query(keys, 200, insert_missing=False)
+    d_hit = torch.zeros(len(keys), dtype=torch.uint8, device="cuda")
+    out = p.gpu.query(200, 1, to_dev(keys), None, False, hit_mask=d_hit)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_hit.cpu().numpy(), ref_hit)
+    mag = 4 * np.abs(ref_out) + 1.0
+    assert_close(out.cpu().numpy().reshape(200, dim), ref_out, mag, "query after update")
+
+
+def test_refresh_rereads_the_host_table():
+    host_rows, dim = 1500, 16
+    host = pinned_table(host_rows, dim)
+    p = Pair(20, 4, host)
+    smp = datagen.ZipfSampler(host_rows, 1.2)
+    for it in range(3):
+        p.query(datagen.cache_keys(SEED, 700 + it, host_rows, 500, 1.2, sampler=smp).numpy(), 125, what=f"warm {it}")
+    host += 0.25                                   # the level-2 store changes underneath (same memory for both sides)
+    p.ref.refresh()
+    p.gpu.refresh()
+    torch.cuda.synchronize()
+    _state_equal(p, "refresh")
+    p.query(datagen.cache_keys(SEED, 710, host_rows, 500, 1.2, sampler=smp).numpy(), 125, what="query after refresh")
+
+
+@pytest.mark.parametrize("small_limit", [0, 4096], ids=["general", "fused-small"])
+def test_async_query_signals_results_before_insertion(small_limit):
+    host_rows, dim = 4000, 32
+    p = Pair(64, 4, pinned_table(host_rows, dim), small_limit)
+    keys = datagen.cache_keys(SEED, 800, host_rows, 1040, 1.2).numpy()
+    ref_out, ref_hit = p.ref.query(keys, 260, insert_missing=True)
+    ready = torch.cuda.Event()
+    consumer = torch.cuda.Stream()
+    out = p.gpu.query_async(10, 26, to_dev(keys), ready)
+    with torch.cuda.stream(consumer):
+        consumer.wait_event(ready)
+        copy = out.clone()                          # a consumer that only waits for the results
+    consumer.synchronize()
+    mag = np.abs(p.host.numpy()[keys]).astype(np.float64).reshape(260, 4, dim).sum(1)
+    assert_close(copy.cpu().numpy().reshape(260, dim), ref_out, mag, "results seen by the waiting stream")
+    torch.cuda.synchronize()
+    _state_equal(p, "after async query")
