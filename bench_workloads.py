@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Timings of the configurations that are not the headline benchmark (bench.py covers that one):
+
+    python bench_workloads.py multihot   # 26 fp16 tables, batch 65,536, hotness 1..100, mean: fwd / dedup / apply
+    python bench_workloads.py hashed     # open 2^63 key space, capacity 1e8, dim 64: insert-or-find, fwd, bwd over load factor
+    python bench_workloads.py cache      # inference cache, Zipf 1.2, batch 1 / 64 / 1024 / 16384: hit rate, keys/s, p50 latency
+
+Each prints one JSON line.  Inputs are synthetic and seeded (datagen/), resident in HBM (the cache's
+backing table in pinned host memory) before anything is timed.  The inference-cache configuration
+asks for a 5e8-row host table (256 GB); --host-rows scales it (default 2e7 rows = 10 GB), the cache
+always holds 10 % of the rows in 32-way sets.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import datagen  # noqa: E402
+
+SEED = datagen.DEFAULT_SEED
+DEV = "cuda"
+
+
+def timeit(fn, iters=10, warm=2):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def multihot(h, args):
+    rows_t = datagen.DLRM_TABLE_ROWS
+    S, D, B = 26, 128, 65536
+    ro = datagen.row_offsets(rows_t)
+    base, total = ro[:-1].copy(), int(ro[-1])
+    table = torch.empty((total, D), dtype=torch.float16, device=DEV)
+    datagen.fill_table(SEED, table, 1 << 21)
+    smp = datagen.make_samplers(rows_t, 1.1, device=DEV)
+    offsets = datagen.multihot_offsets(SEED, 7, B * S, 1, 100, device=DEV)
+    keys = datagen.multihot_keys(SEED, 7, rows_t, B, 1.1, offsets, device=DEV, samplers=smp)
+    del smp
+    nnz = keys.numel()
+    dY = datagen.normal_grads(SEED, 7, B * S * D, device=DEV).view(B, S, D)
+    layer = h.EmbeddingLayer(table, S, h.MEAN, base, rows_t)
+    ws = layer.new_workspace(layer.workspace_bytes(B, nnz))
+    out = torch.empty((B, S, D), device=DEV)
+    f = timeit(lambda: layer.forward(B, keys, offsets, out=out, ws=ws), 5, 1)
+    d = timeit(lambda: layer.backward_dedup(B, keys, offsets, ws=ws), 5, 1)
+    a = timeit(lambda: layer.backward_apply(B, nnz, dY, 0.01, offsets, ws=ws), 5, 1)
+    uniq, _ = layer.dedup_result(B, nnz, ws=ws)
+    fwd_bytes = nnz * (8 + D * 2) + B * S * (D * 4 + 8)
+    apply_bytes = nnz * (8 + D * 4) + int(uniq.numel()) * 2 * D * 2
+    return dict(workload="multi-hot: 26 fp16 tables, dim 128, batch 65536, hotness 1..100, Zipf 1.1, mean", keys=nnz,
+                distinct_rows=int(uniq.numel()), forward_ms=f, forward_algorithmic_GBs=fwd_bytes / f / 1e6,
+                backward_dedup_ms=d, backward_apply_ms=a, backward_apply_logical_GBs=apply_bytes / a / 1e6,
+                fwd_bwd_keys_per_s=nnz / ((f + d + a) * 1e-3))
+
+
+def hashed(h, args):
+    S, D, B = 26, 64, 131072
+    cap, max_rows = 100_000_000, 80_000_000
+    ht = h.HashTable(cap, max_rows)
+    table = torch.empty((max_rows, D), dtype=torch.float32, device=DEV)
+    datagen.fill_table(SEED, table, 1 << 22)
+    layer = h.EmbeddingLayer(table, S, h.SUM, hash_table=ht, insert_on_miss=True)
+    nnz = B * S
+    ws = layer.new_workspace(layer.workspace_bytes(B, nnz))
+    out = torch.empty((B, S, D), device=DEV)
+    smp = datagen.ZipfSampler(1 << 63, 1.05, device=DEV)
+    dY = datagen.normal_grads(SEED, 1, nnz * D, device=DEV).view(B, S, D)
+    trace = []
+    keys = None
+    for it in range(args.hash_batches):
+        keys = datagen.open_space_keys(SEED, it, S, B, 1.05, device=DEV, sampler=smp)
+        torch.cuda.synchronize()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        layer.forward(B, keys, out=out, ws=ws)          # insert-or-find + gather
+        e[1].record()
+        layer.backward_sgd(B, keys, dY, 0.01, ws=ws)    # find + dedup + reduce + SGD
+        e[2].record()
+        torch.cuda.synchronize()
+        if it % 8 == 0 or it == args.hash_batches - 1:
+            size = ht.size
+            trace.append(dict(batch=it, size=size, load_factor=size / cap, forward_ms=e[0].elapsed_time(e[1]),
+                              backward_ms=e[1].elapsed_time(e[2]),
+                              keys_per_s=nnz / (e[0].elapsed_time(e[2]) * 1e-3)))
+    rows = torch.empty(nnz, dtype=torch.int64, device=DEV)
+    find_ms = timeit(lambda: ht.insert_or_find(keys, False, rows=rows), 10, 2)
+    return dict(workload="hashed open key space: capacity 1e8, max 8e7 rows, dim 64 fp32, 26 one-hot slots, "
+                         "batch 131072, Zipf 1.05 over 2^63 ids, insert on miss", keys=nnz, find_only_ms=find_ms,
+                find_only_keys_per_s=nnz / find_ms * 1e3, trace=trace)
+
+
+def cache(h, args):
+    host_rows, D, S, hot, ways = args.host_rows, 128, 26, 4, 32
+    num_sets = host_rows // 10 // ways
+    host = torch.empty((host_rows, D), dtype=torch.float32, pin_memory=True)
+    for r0 in range(0, host_rows, 1 << 20):
+        r1 = min(host_rows, r0 + (1 << 20))
+        host[r0:r1].copy_(datagen.table_rows_at(SEED, torch.arange(r0, r1, device=DEV), D, torch.float32))
+    c = h.EmbeddingCache(num_sets, ways, host)
+    smp = datagen.ZipfSampler(host_rows, 1.2)
+    call = 0
+    for _ in range(30):   # warm up until the hit rate is stationary
+        keys = datagen.cache_keys(SEED, call, host_rows, 16384 * S * hot, 1.2, sampler=smp).cuda()
+        call += 1
+        c.query(16384, S, keys)
+    torch.cuda.synchronize()
+    sweep = []
+    for batch in (1, 64, 1024, 16384):
+        n = batch * S * hot
+        ks_by_mode = {m: [datagen.cache_keys(SEED, 1000 + 1000 * j + call + i, host_rows, n, 1.2, sampler=smp).cuda()
+                          for i in range(100)] for j, m in enumerate(("insert", "lookup_only"))}
+        o = torch.empty((batch, S, D), device=DEV)
+        ws = c.workspace(n)
+        hm = torch.zeros(n, dtype=torch.uint8, device=DEV)
+        res = {}
+        for mode, insert in (("insert", True), ("lookup_only", False)):
+            s0 = c.stats
+            lat = []
+            for k in ks_by_mode[mode]:   # fresh keys for each mode, so lookup-only sees real misses too
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                c.query(batch, S, k, None, insert, out=o, hit_mask=hm, ws=ws)
+                torch.cuda.synchronize()
+                lat.append((time.perf_counter() - t0) * 1e6)
+            s1 = c.stats
+            res[mode] = dict(hit_rate=(s1[1] - s0[1]) / (s1[0] - s0[0]), p50_us=float(np.median(lat)),
+                             p99_us=float(np.percentile(lat, 99)), keys_per_s=n / np.median(lat) * 1e6)
+        sweep.append(dict(batch=batch, keys=n, **{f"{m}_{k}": v for m, r in res.items() for k, v in r.items()}))
+    return dict(workload=f"inference cache: {host_rows} x 128 fp32 host table (pinned), cache 10% in 32-way sets, "
+                         "26 slots x hotness 4, Zipf 1.2; latency = host call + stream sync", sweep=sweep)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("workload", choices=["multihot", "hashed", "cache"])
+    ap.add_argument("--host-rows", type=int, default=20_000_000)
+    ap.add_argument("--hash-batches", type=int, default=41)
+    args = ap.parse_args()
+    if not torch.cuda.is_available():
+        print("bench_workloads.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(2)
+    import paper_2210_08803_amd as h
+    res = {"multihot": multihot, "hashed": hashed, "cache": cache}[args.workload](h, args)
+    res["n_gpus"] = 1
+    res["data"] = "synthetic"
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()
