@@ -61,6 +61,14 @@ __global__ __launch_bounds__(256) void fwd_onehot(const T* __restrict__ table, i
   const int col = blockIdx.y * (LPR * VEC) + sub * VEC;
   const bool active = col < D;
   uint32_t nbad = 0;  // counted by the first lane of each group
+  __shared__ int64_t s_base[HCTR_MAX_SLOTS], s_num[HCTR_MAX_SLOTS];
+  if (!HASHED) {   // slot ranges by LDS: a per-lane index into the kernel arguments would be a global load
+    if (threadIdx.x < S) {
+      s_base[threadIdx.x] = slots.base[threadIdx.x];
+      s_num[threadIdx.x] = slots.num[threadIdx.x];
+    }
+    __syncthreads();
+  }
   for (uint64_t bag0_64 = (uint64_t)group0 * U; bag0_64 < n_bags; bag0_64 += (uint64_t)n_groups * U) {
     const uint32_t bag0 = (uint32_t)bag0_64;
     int64_t row[U];
@@ -75,7 +83,7 @@ __global__ __launch_bounds__(256) void fwd_onehot(const T* __restrict__ table, i
         } else {
           const int64_t k = keys[bag];
           const uint32_t s = bag % S;
-          if (k >= 0 && k < slots.num[s]) row[u] = slots.base[s] + k;
+          if (k >= 0 && k < s_num[s]) row[u] = s_base[s] + k;
         }
         nbad += (sub == 0 && row[u] < 0) ? 1u : 0u;
       }
@@ -271,6 +279,11 @@ __global__ __launch_bounds__(256) void bwd_rows(const int64_t* __restrict__ keys
   const uint32_t k0 = blockIdx.x * kSortTile;
   const uint32_t k1 = nnz - k0 < kSortTile ? nnz : k0 + kSortTile;
   for (uint32_t d = threadIdx.x; d < bins; d += 256) h[d] = 0;
+  __shared__ int64_t s_base[HCTR_MAX_SLOTS], s_num[HCTR_MAX_SLOTS];   // see fwd_onehot
+  if (rows64 == nullptr && threadIdx.x < S) {
+    s_base[threadIdx.x] = slots.base[threadIdx.x];
+    s_num[threadIdx.x] = slots.num[threadIdx.x];
+  }
   if (offsets != nullptr) tile_bags(offsets, n_bags, k0, k1, bagof, small);
   else __syncthreads();
   uint32_t nbad = 0;
@@ -286,7 +299,7 @@ __global__ __launch_bounds__(256) void bwd_rows(const int64_t* __restrict__ keys
       } else {
         const int64_t k = keys[i];
         const uint32_t s = bag % S;
-        if (k >= 0 && k < slots.num[s]) row = slots.base[s] + k;
+        if (k >= 0 && k < s_num[s]) row = s_base[s] + k;
       }
       const uint32_t r32 = row < 0 ? kNoRow : (uint32_t)row;
       nbad += row < 0 ? 1u : 0u;
@@ -428,61 +441,72 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
   const uint32_t start = (uint32_t)start64;
   const uint32_t end = (n_valid - start < W) ? n_valid : start + W;
 
-  uint32_t cur = (uint32_t)(skv[start] >> 32);
-  bool before = start > 0 && (uint32_t)(skv[start - 1] >> 32) == cur;
+  // `before`: the row being summed began in an earlier window (only the window's first row can).
+  bool before = start > 0 && (uint32_t)(skv[start - 1] >> 32) == (uint32_t)(skv[start] >> 32);
   bool wrote_tail = false;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-
-  auto flush = [&](bool ended) {
-    if (!before && ended) {
-      if (active) sgd_update4(table + (int64_t)cur * D + col, acc, lr);
-    } else if (before) {
-      if (active) store4(head + (int64_t)win * D + col, acc);
-    } else {
-      if (active) store4(tail + (int64_t)win * D + col, acc);
-      wrote_tail = true;
-    }
-  };
+  constexpr int UB = 4;   // occurrences per step: UB dY loads (+ the table rows that finish) in flight
 
   for (uint32_t p0 = start; p0 < end; p0 += LPR) {
     const int cnt = (end - p0 < (uint32_t)LPR) ? (int)(end - p0) : LPR;
-    uint32_t myrow = kNoRow, mybag = 0;
+    // one coalesced load of LPR (row, bag) words, and of each word's right neighbour: a row whose
+    // neighbour differs ends here, so its table row can be requested together with the dY rows
+    uint32_t myrow = kNoRow, mynext = kNoRow, mybag = 0;
     float myw = 1.f;
     if (sub < cnt) {
       const uint64_t w64 = skv[p0 + sub];
       myrow = (uint32_t)(w64 >> 32);
       mybag = (uint32_t)w64;
+      if (p0 + sub + 1 < n_valid) mynext = (uint32_t)(skv[p0 + sub + 1] >> 32);
       if (mean) myw = 1.0f / (float)(offsets[mybag + 1] - offsets[mybag]);
     }
-    for (int q0 = 0; q0 < cnt; q0 += 4) {
-      uint32_t r[4];
-      float w[4];
-      f32x4 v[4];
+    for (int q0 = 0; q0 < cnt; q0 += UB) {
+      uint32_t r[UB];
+      bool ends[UB];
+      float w[UB];
+      f32x4 v[UB], t[UB];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int q = (q0 + u < cnt) ? q0 + u : q0;  // clamp: duplicates are ignored below
+      for (int u = 0; u < UB; ++u) {
+        const bool live = q0 + u < cnt;
+        const int q = live ? q0 + u : q0;  // clamp: dead positions are ignored below
         r[u] = __shfl(myrow, q, LPR);
+        ends[u] = live && __shfl(mynext, q, LPR) != r[u];
         const uint32_t b = __shfl(mybag, q, LPR);
         w[u] = __shfl(myw, q, LPR);
         v[u] = active ? load4(dY + (int64_t)b * D + col) : f32x4{0.f, 0.f, 0.f, 0.f};
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < UB; ++u) {
+        t[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (ends[u] && active) t[u] = load_row4(table + (int64_t)r[u] * D + col);
+      }
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
         if (q0 + u < cnt) {
-          if (r[u] != cur) {
-            flush(true);
-            cur = r[u];
-            acc = f32x4{0.f, 0.f, 0.f, 0.f};
-            before = false;
-          }
           acc.x += w[u] * v[u].x; acc.y += w[u] * v[u].y;
           acc.z += w[u] * v[u].z; acc.w += w[u] * v[u].w;
+        }
+        if (ends[u]) {
+          if (active) {
+            if (before) {
+              store4(head + (int64_t)win * D + col, acc);
+            } else {
+              t[u].x -= lr * acc.x; t[u].y -= lr * acc.y; t[u].z -= lr * acc.z; t[u].w -= lr * acc.w;
+              store_row4(table + (int64_t)r[u] * D + col, t[u]);
+            }
+          }
+          acc = f32x4{0.f, 0.f, 0.f, 0.f};
+          before = false;
         }
       }
     }
   }
-  const bool continues = end < n_valid && (uint32_t)(skv[end] >> 32) == cur;
-  flush(!continues);
+  // the last row of the window continues in the next window
+  const bool continues = end < n_valid && (uint32_t)(skv[end] >> 32) == (uint32_t)(skv[end - 1] >> 32);
+  if (continues) {
+    if (active) store4((before ? head : tail) + (int64_t)win * D + col, acc);
+    wrote_tail = !before;
+  }
   if (sub == 0 && blockIdx.y == 0) tail_flag[win] = wrote_tail ? 1 : 0;
 }
 

@@ -59,6 +59,21 @@ __device__ __forceinline__ void store_plain(float* p, const float (&v)[N]) {
 __device__ __forceinline__ f32x4 load4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
 __device__ __forceinline__ void store4(float* p, f32x4 x) { *reinterpret_cast<f32x4*>(p) = x; }
 
+// 4 table elements widened to fp32 / narrowed from fp32 (round to nearest even).
+__device__ __forceinline__ f32x4 load_row4(const float* t) { return load4(t); }
+__device__ __forceinline__ void store_row4(float* t, f32x4 x) { store4(t, x); }
+__device__ __forceinline__ f32x4 load_row4(const __half* t) {
+  u32x2 raw = *reinterpret_cast<const u32x2*>(t);
+  return f32x4{half_bits_to_float(raw.x & 0xFFFFu), half_bits_to_float(raw.x >> 16),
+               half_bits_to_float(raw.y & 0xFFFFu), half_bits_to_float(raw.y >> 16)};
+}
+__device__ __forceinline__ void store_row4(__half* t, f32x4 x) {
+  u32x2 o;
+  o.x = (uint32_t)__half_as_ushort(__float2half_rn(x.x)) | ((uint32_t)__half_as_ushort(__float2half_rn(x.y)) << 16);
+  o.y = (uint32_t)__half_as_ushort(__float2half_rn(x.z)) | ((uint32_t)__half_as_ushort(__float2half_rn(x.w)) << 16);
+  *reinterpret_cast<u32x2*>(t) = o;
+}
+
 // Read-modify-write of 4 table elements: t <- t - lr * g (fp16 storage: widen, update in fp32,
 // round to nearest even).
 __device__ __forceinline__ void sgd_update4(float* t, f32x4 g, float lr) {
