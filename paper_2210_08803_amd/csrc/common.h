@@ -89,6 +89,7 @@ struct SortPlan {
 };
 SortPlan sort_plan(uint32_t n_max, int bits);
 // Per pass p the aux area holds tot[max_bins] followed by sup[n_super][max_bins].
+constexpr uint32_t kSortWideMaxTiles = 1024;  // up to this many tiles the sort uses 1024-thread blocks
 constexpr uint32_t kSortDirectSuperMax = 48;  // above this many groups the group sums get their own scan
 inline uint32_t* sort_aux_tot(const SortPlan& plan, uint32_t* aux, int p) {
   return aux + (size_t)p * (1 + plan.n_super) * plan.max_bins;

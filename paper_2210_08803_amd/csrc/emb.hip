@@ -263,35 +263,38 @@ __device__ __forceinline__ void tile_bags(const int64_t* __restrict__ offsets, u
   __syncthreads();
 }
 
-__global__ __launch_bounds__(256) void bwd_rows(const int64_t* __restrict__ keys,
-                                                const int64_t* __restrict__ rows64,
-                                                const int64_t* __restrict__ offsets, uint32_t nnz,
-                                                uint32_t n_bags, uint32_t S, const SlotTable slots,
-                                                int64_t total_rows, uint64_t* __restrict__ kv,
-                                                EmbHeader* hdr, uint32_t bins,
-                                                uint32_t* __restrict__ hist, uint32_t* __restrict__ sup) {
+// NT = 256, or 1024 for one-hot input when there is only about one tile per compute unit (tile_bags
+// is written for 256 threads).
+template <int NT>
+__global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
+                                               const int64_t* __restrict__ rows64,
+                                               const int64_t* __restrict__ offsets, uint32_t nnz,
+                                               uint32_t n_bags, uint32_t S, const SlotTable slots,
+                                               int64_t total_rows, uint64_t* __restrict__ kv,
+                                               EmbHeader* hdr, uint32_t bins,
+                                               uint32_t* __restrict__ hist, uint32_t* __restrict__ sup) {
   // One sort tile per block, so the block can also deliver the tile's histogram of the first sort
   // digit (the low bits of the row) and spare the sort its first counting pass.
   __shared__ uint32_t h[1 << kSortMaxDigitBits];
-  __shared__ uint32_t bagof[kSortTile];
+  __shared__ uint32_t bagof[NT == 256 ? kSortTile : 1];
   __shared__ uint32_t small[6];
   const uint32_t mask = bins - 1;
   const uint32_t k0 = blockIdx.x * kSortTile;
   const uint32_t k1 = nnz - k0 < kSortTile ? nnz : k0 + kSortTile;
-  for (uint32_t d = threadIdx.x; d < bins; d += 256) h[d] = 0;
+  for (uint32_t d = threadIdx.x; d < bins; d += NT) h[d] = 0;
   __shared__ int64_t s_base[HCTR_MAX_SLOTS], s_num[HCTR_MAX_SLOTS];   // see fwd_onehot
   if (rows64 == nullptr && threadIdx.x < S) {
     s_base[threadIdx.x] = slots.base[threadIdx.x];
     s_num[threadIdx.x] = slots.num[threadIdx.x];
   }
-  if (offsets != nullptr) tile_bags(offsets, n_bags, k0, k1, bagof, small);
+  if (NT == 256 && offsets != nullptr) tile_bags(offsets, n_bags, k0, k1, bagof, small);
   else __syncthreads();
   uint32_t nbad = 0;
 #pragma unroll 4
-  for (int it = 0; it < (int)(kSortTile / 256); ++it) {
-    const uint32_t i = k0 + it * 256u + threadIdx.x;
+  for (int it = 0; it < (int)(kSortTile / NT); ++it) {
+    const uint32_t i = k0 + it * (uint32_t)NT + threadIdx.x;
     if (i < nnz) {
-      const uint32_t bag = offsets != nullptr ? bagof[i - k0] - 1u : i;
+      const uint32_t bag = (NT == 256 && offsets != nullptr) ? bagof[i - k0] - 1u : i;
       int64_t row = -1;
       if (rows64 != nullptr) {
         const int64_t r = rows64[i];
@@ -310,7 +313,7 @@ __global__ __launch_bounds__(256) void bwd_rows(const int64_t* __restrict__ keys
   __syncthreads();
   uint32_t* hrow = hist + (uint64_t)blockIdx.x * bins;
   uint32_t* srow = sup + (uint64_t)(blockIdx.x / kSortSuper) * bins;
-  for (uint32_t d = threadIdx.x; d < bins; d += 256) {
+  for (uint32_t d = threadIdx.x; d < bins; d += NT) {
     const uint32_t c = h[d];
     hrow[d] = c;
     if (c) atomicAdd(&srow[d], c);
@@ -324,7 +327,7 @@ __global__ __launch_bounds__(256) void bwd_rows(const int64_t* __restrict__ keys
 
 // Backward step 3: run boundaries of the sorted rows = the distinct rows of the batch.  A position
 // starts a segment if it holds a real row that differs from its left neighbour.  Two kernels over
-// tiles of 4096 positions (a wave owns 1024 consecutive ones and finds starts 64 at a time with a
+// tiles of 4096 positions (a wave owns a run of consecutive ones and finds starts 64 at a time with a
 // ballot): the first counts the starts per tile and adds them to a per-64-tiles sum; the second
 // derives its tile's first segment number from those, then numbers the starts and writes the
 // unique rows, the segment offsets and, per position, the number of starts before it.
@@ -341,61 +344,69 @@ __device__ __forceinline__ uint64_t seg_start_mask(const uint64_t* __restrict__ 
   return __ballot(row != kNoRow && (idx == 0 || prev != row));
 }
 
-__global__ __launch_bounds__(256) void seg_count(const uint64_t* __restrict__ skv, uint32_t n,
-                                                 uint32_t* __restrict__ counts, uint32_t* __restrict__ segsup) {
-  __shared__ uint32_t wsum[4];
+template <int NT>
+__global__ __launch_bounds__(NT) void seg_count(const uint64_t* __restrict__ skv, uint32_t n,
+                                                uint32_t* __restrict__ counts, uint32_t* __restrict__ segsup) {
+  constexpr int NW = NT / 64, ROUNDS = kSegTile / NT;
+  __shared__ uint32_t wsum[NW];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t wbase = blockIdx.x * kSegTile + wave * 1024u;
+  const uint32_t wbase = blockIdx.x * kSegTile + wave * (ROUNDS * 64u);
   uint32_t c = 0;
 #pragma unroll 4
-  for (int r = 0; r < 16; ++r) {
+  for (int r = 0; r < ROUNDS; ++r) {
     uint32_t row;
     c += (uint32_t)__popcll(seg_start_mask(skv, wbase + r * 64 + lane, n, &row));
   }
   if (lane == 0) wsum[wave] = c;
   __syncthreads();
   if (threadIdx.x == 0) {
-    const uint32_t t = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    uint32_t t = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) t += wsum[w];
     counts[blockIdx.x] = t;
     if (t) atomicAdd(&segsup[blockIdx.x / kSegSuper], t);
   }
 }
 
-__global__ __launch_bounds__(256) void seg_write(const uint64_t* __restrict__ skv, uint32_t n,
-                                                 const uint32_t* __restrict__ counts,
-                                                 const uint32_t* __restrict__ segsup,
-                                                 uint32_t* __restrict__ starts_before,
-                                                 uint32_t* __restrict__ uniq,
-                                                 uint32_t* __restrict__ seg_off, EmbHeader* hdr) {
-  __shared__ uint32_t red[4];
-  __shared__ uint32_t wsum[4];
+template <int NT>
+__global__ __launch_bounds__(NT) void seg_write(const uint64_t* __restrict__ skv, uint32_t n,
+                                                const uint32_t* __restrict__ counts,
+                                                const uint32_t* __restrict__ segsup,
+                                                uint32_t* __restrict__ starts_before,
+                                                uint32_t* __restrict__ uniq,
+                                                uint32_t* __restrict__ seg_off, EmbHeader* hdr) {
+  constexpr int NW = NT / 64, ROUNDS = kSegTile / NT;
+  __shared__ uint32_t red[NW];
+  __shared__ uint32_t wsum[NW];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint32_t tile = blockIdx.x;
   const uint32_t g = tile / kSegSuper;
   // number of starts in all earlier tiles
   uint32_t part = 0;
-  for (uint32_t i = threadIdx.x; i < g; i += 256) part += segsup[i];
-  if (g * kSegSuper + threadIdx.x < tile) part += counts[g * kSegSuper + threadIdx.x];
+  for (uint32_t i = threadIdx.x; i < g; i += NT) part += segsup[i];
+  if (threadIdx.x < kSegSuper && g * kSegSuper + threadIdx.x < tile) part += counts[g * kSegSuper + threadIdx.x];
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) part += __shfl_xor(part, d);
   if (lane == 0) red[wave] = part;
 
-  const uint32_t wbase = tile * kSegTile + wave * 1024u;
-  uint64_t m[16];
-  uint32_t row[16];
+  const uint32_t wbase = tile * kSegTile + wave * (ROUNDS * 64u);
+  uint64_t m[ROUNDS];
+  uint32_t row[ROUNDS];
   uint32_t c = 0;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
+  for (int r = 0; r < ROUNDS; ++r) {
     m[r] = seg_start_mask(skv, wbase + r * 64 + lane, n, &row[r]);
     c += (uint32_t)__popcll(m[r]);
   }
   if (lane == 0) wsum[wave] = c;
   __syncthreads();
-  uint32_t run = red[0] + red[1] + red[2] + red[3];
+  uint32_t run = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) run += red[w];
   for (int w = 0; w < wave; ++w) run += wsum[w];
   const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
+  for (int r = 0; r < ROUNDS; ++r) {
     const uint32_t p = wbase + r * 64 + lane;
     if (p < n) {
       const uint32_t before = run + (uint32_t)__popcll(m[r] & below);
@@ -874,14 +885,28 @@ static hctr_status backward_dedup(const hctr_emb_desc* desc, int64_t batch, cons
   uint32_t* flags = reinterpret_cast<uint32_t*>(w + L.flags);
   uint32_t* uniq = reinterpret_cast<uint32_t*>(w + L.uniq);
 
-  hipLaunchKernelGGL(bwd_rows, dim3(L.sort.n_blocks), dim3(256), 0, stream, keys, rows64, offsets, n, n_bags,
-                     (uint32_t)desc->num_slots, st, desc->total_rows, kv0, hdr, 1u << L.sort.digit_bits[0],
-                     hist, sort_aux_sup(L.sort, aux, 0));
+  // About one tile per compute unit: 1024-thread blocks, so a wave's serial share is 4 rounds, not 16.
+  const bool wide = L.sort.n_blocks <= kSortWideMaxTiles;
+  const uint32_t bins0 = 1u << L.sort.digit_bits[0];
+  if (wide && offsets == nullptr)
+    hipLaunchKernelGGL((bwd_rows<1024>), dim3(L.sort.n_blocks), dim3(1024), 0, stream, keys, rows64, offsets, n,
+                       n_bags, (uint32_t)desc->num_slots, st, desc->total_rows, kv0, hdr, bins0, hist,
+                       sort_aux_sup(L.sort, aux, 0));
+  else
+    hipLaunchKernelGGL((bwd_rows<256>), dim3(L.sort.n_blocks), dim3(256), 0, stream, keys, rows64, offsets, n,
+                       n_bags, (uint32_t)desc->num_slots, st, desc->total_rows, kv0, hdr, bins0, hist,
+                       sort_aux_sup(L.sort, aux, 0));
   HCTR_TRY(radix_sort_u64(L.sort, nullptr, kv0, kv1, hist, aux, true, stream, true));
   const uint64_t* skv = (L.sort.passes & 1) ? kv1 : kv0;
-  hipLaunchKernelGGL(seg_count, dim3(L.seg_tiles), dim3(256), 0, stream, skv, n, seg_counts, segsup);
-  hipLaunchKernelGGL(seg_write, dim3(L.seg_tiles), dim3(256), 0, stream, skv, n, (const uint32_t*)seg_counts,
-                     (const uint32_t*)segsup, flags, uniq, seg_off, hdr);
+  if (wide) {
+    hipLaunchKernelGGL((seg_count<1024>), dim3(L.seg_tiles), dim3(1024), 0, stream, skv, n, seg_counts, segsup);
+    hipLaunchKernelGGL((seg_write<1024>), dim3(L.seg_tiles), dim3(1024), 0, stream, skv, n,
+                       (const uint32_t*)seg_counts, (const uint32_t*)segsup, flags, uniq, seg_off, hdr);
+  } else {
+    hipLaunchKernelGGL((seg_count<256>), dim3(L.seg_tiles), dim3(256), 0, stream, skv, n, seg_counts, segsup);
+    hipLaunchKernelGGL((seg_write<256>), dim3(L.seg_tiles), dim3(256), 0, stream, skv, n,
+                       (const uint32_t*)seg_counts, (const uint32_t*)segsup, flags, uniq, seg_off, hdr);
+  }
   return launch_status("hctr_emb_backward_dedup");
 }
 

@@ -97,11 +97,14 @@ hctr_status exclusive_scan_u32(const uint32_t* in, uint32_t* out, uint32_t n, ui
 //   sort_scatter  derives the tile's global offsets on its own - exclusive scan of tot in LDS, plus
 //                 the sup rows of earlier groups, plus the hist rows of earlier tiles of its group
 //                 (at most n_tiles/16 + 15 coalesced row reads) - then ranks and scatters.
-// Each of a block's four waves owns 1024 consecutive words and ranks them 64 at a time with
-// ballot-based digit matching, so equal digits keep their input order (stable).
+// Each wave of a block owns a run of consecutive words and ranks them 64 at a time with ballot-based
+// digit matching, so equal digits keep their input order (stable).  Blocks have 256 threads (waves
+// own 1024 words) when there are tiles enough to fill the chip several times over, else 1024
+// threads (waves own 256 words): with about one tile per compute unit the pass is bound by the
+// length of a wave's serial ranking, not by bandwidth.
 // ------------------------------------------------------------------------------------------------
 constexpr int kSortThreads = 256;
-constexpr int kSortRounds = kSortTile / kSortThreads;  // 16 rounds of 64 words per wave
+constexpr int kSortWideThreads = 1024;
 constexpr int kMaxBins = 1 << kSortMaxDigitBits;
 typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 
@@ -110,26 +113,27 @@ __global__ __launch_bounds__(256) void sort_zero_aux(uint32_t* __restrict__ aux,
   if (i < count) aux[i] = 0u;
 }
 
-__global__ __launch_bounds__(kSortThreads) void sort_hist(const uint64_t* __restrict__ kv, uint32_t n_host,
-                                                          const uint32_t* __restrict__ n_dev, int shift,
-                                                          uint32_t bins, uint32_t* __restrict__ hist,
-                                                          uint32_t* __restrict__ sup) {
+template <int NT>
+__global__ __launch_bounds__(NT) void sort_hist(const uint64_t* __restrict__ kv, uint32_t n_host,
+                                                const uint32_t* __restrict__ n_dev, int shift,
+                                                uint32_t bins, uint32_t* __restrict__ hist,
+                                                uint32_t* __restrict__ sup) {
   __shared__ uint32_t h[kMaxBins];
   const uint32_t n = n_dev ? *n_dev : n_host;
   const uint32_t base = blockIdx.x * kSortTile;
   if (base >= n) return;  // nobody reads the rows of tiles past the end
   const uint32_t mask = bins - 1;
-  for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads) h[d] = 0;
+  for (uint32_t d = threadIdx.x; d < bins; d += NT) h[d] = 0;
   __syncthreads();
 #pragma unroll 4
-  for (int i = 0; i < kSortRounds; ++i) {
-    const uint32_t idx = base + i * kSortThreads + threadIdx.x;
+  for (int i = 0; i < kSortTile / NT; ++i) {
+    const uint32_t idx = base + i * NT + threadIdx.x;
     if (idx < n) atomicAdd(&h[(uint32_t)(kv[idx] >> (32 + shift)) & mask], 1u);
   }
   __syncthreads();
   uint32_t* row = hist + (uint64_t)blockIdx.x * bins;
   uint32_t* srow = sup + (uint64_t)(blockIdx.x / kSortSuper) * bins;
-  for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads) {
+  for (uint32_t d = threadIdx.x; d < bins; d += NT) {
     const uint32_t c = h[d];
     row[d] = c;
     if (c) atomicAdd(&srow[d], c);
@@ -159,16 +163,16 @@ __global__ __launch_bounds__(256) void sort_scan_sup(uint32_t* __restrict__ sup,
   tot[d] = run;
 }
 
-template <int DBITS>
-__global__ __launch_bounds__(kSortThreads) void sort_scatter(
+template <int DBITS, int NT>
+__global__ __launch_bounds__(NT) void sort_scatter(
     const uint64_t* __restrict__ in, uint64_t* __restrict__ out, uint32_t n_host,
     const uint32_t* __restrict__ n_dev, int shift, uint32_t bins, const uint32_t* __restrict__ hist,
     const uint32_t* __restrict__ tot, const uint32_t* __restrict__ sup, uint32_t n_super,
     int sup_is_scanned) {
   constexpr int BINS_MAX = 1 << DBITS;
-  __shared__ uint32_t cnt[kSortThreads / 64][BINS_MAX];
+  __shared__ uint32_t cnt[NT / 64][BINS_MAX];
   __shared__ uint32_t gbase[BINS_MAX];
-  __shared__ uint32_t scan_lds[kSortThreads / 64 + 1];
+  __shared__ uint32_t scan_lds[NT / 64 + 1];
   const uint32_t n = n_dev ? *n_dev : n_host;
   const uint32_t mask = bins - 1;
   const uint32_t blk = blockIdx.x;
@@ -177,10 +181,11 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
   // The tile's words first: their latency hides behind the offset computation below.
-  const uint32_t wbase = base + wave * (kSortTile / 4);
-  uint64_t word[kSortRounds];
+  constexpr int ROUNDS = kSortTile / NT;   // rounds of 64 words per wave
+  const uint32_t wbase = base + wave * (ROUNDS * 64);
+  uint64_t word[ROUNDS];
 #pragma unroll
-  for (int r = 0; r < kSortRounds; ++r) {
+  for (int r = 0; r < ROUNDS; ++r) {
     const uint32_t idx = wbase + r * 64 + lane;
     word[r] = idx < n ? in[idx] : ~0ull;
   }
@@ -191,35 +196,36 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(
     u32x4v t4 = {0, 0, 0, 0}, pre = {0, 0, 0, 0};
     if (d0 < bins) {
       const uint32_t g = blk / kSortSuper;
+      const uint32_t b_begin = g * kSortSuper;   // at most kSortSuper - 1 = 15 rows of this group
+      u32x4v hrow[kSortSuper - 1];
+#pragma unroll
+      for (uint32_t k = 0; k < kSortSuper - 1; ++k)   // requested first: in flight while the group sums arrive
+        hrow[k] = b_begin + k < blk ? *reinterpret_cast<const u32x4v*>(hist + (uint64_t)(b_begin + k) * bins + d0)
+                                    : u32x4v{0, 0, 0, 0};
       if (sup_is_scanned) {
         t4 = *reinterpret_cast<const u32x4v*>(tot + d0);
         pre = *reinterpret_cast<const u32x4v*>(sup + (uint64_t)g * bins + d0);
       } else {
-        // rows are fetched eight at a time so the loads overlap instead of queueing behind each other
-        for (uint32_t sb0 = 0; sb0 < n_super; sb0 += 8) {
-          u32x4v v[8];
+        // rows are fetched twelve at a time so the loads overlap instead of queueing behind each other
+        constexpr uint32_t kBatch = 12;
+        for (uint32_t sb0 = 0; sb0 < n_super; sb0 += kBatch) {
+          u32x4v v[kBatch];
 #pragma unroll
-          for (int k = 0; k < 8; ++k)
+          for (uint32_t k = 0; k < kBatch; ++k)
             v[k] = sb0 + k < n_super ? *reinterpret_cast<const u32x4v*>(sup + (uint64_t)(sb0 + k) * bins + d0)
                                      : u32x4v{0, 0, 0, 0};
 #pragma unroll
-          for (int k = 0; k < 8; ++k) {
+          for (uint32_t k = 0; k < kBatch; ++k) {
             t4 += v[k];
             if (sb0 + k < g) pre += v[k];
           }
         }
       }
-      const uint32_t b_begin = g * kSortSuper;   // at most kSortSuper - 1 = 15 rows of this group
-      u32x4v hrow[kSortSuper - 1];
-#pragma unroll
-      for (uint32_t k = 0; k < kSortSuper - 1; ++k)
-        hrow[k] = b_begin + k < blk ? *reinterpret_cast<const u32x4v*>(hist + (uint64_t)(b_begin + k) * bins + d0)
-                                    : u32x4v{0, 0, 0, 0};
 #pragma unroll
       for (uint32_t k = 0; k < kSortSuper - 1; ++k) pre += hrow[k];
     }
     uint32_t total;
-    uint32_t run = block_exclusive_scan<kSortThreads>(t4.x + t4.y + t4.z + t4.w, scan_lds, &total);
+    uint32_t run = block_exclusive_scan<NT>(t4.x + t4.y + t4.z + t4.w, scan_lds, &total);
     if (d0 < bins) {
       gbase[d0] = run + pre.x; run += t4.x;
       gbase[d0 + 1] = run + pre.y; run += t4.y;
@@ -227,16 +233,16 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(
       gbase[d0 + 3] = run + pre.w;
     }
   }
-  for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads) {
+  for (uint32_t d = threadIdx.x; d < bins; d += NT) {
 #pragma unroll
-    for (int w = 0; w < kSortThreads / 64; ++w) cnt[w][d] = 0;
+    for (int w = 0; w < NT / 64; ++w) cnt[w][d] = 0;
   }
   __syncthreads();
 
   const uint64_t below = (1ull << lane) - 1ull;
-  uint32_t rank[kSortRounds];
+  uint32_t rank[ROUNDS];
 #pragma unroll
-  for (int r = 0; r < kSortRounds; ++r) {
+  for (int r = 0; r < ROUNDS; ++r) {
     const uint32_t idx = wbase + r * 64 + lane;
     const bool valid = idx < n;
     const uint32_t d = (uint32_t)(word[r] >> (32 + shift)) & mask;
@@ -255,10 +261,10 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(
     rank[r] = old + (uint32_t)__popcll(lower);
   }
   __syncthreads();
-  for (uint32_t d = threadIdx.x; d < bins; d += kSortThreads) {
+  for (uint32_t d = threadIdx.x; d < bins; d += NT) {
     uint32_t run = gbase[d];
 #pragma unroll
-    for (int w = 0; w < kSortThreads / 64; ++w) {
+    for (int w = 0; w < NT / 64; ++w) {
       const uint32_t c = cnt[w][d];
       cnt[w][d] = run;
       run += c;
@@ -266,7 +272,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_scatter(
   }
   __syncthreads();
 #pragma unroll
-  for (int r = 0; r < kSortRounds; ++r) {
+  for (int r = 0; r < ROUNDS; ++r) {
     const uint32_t idx = wbase + r * 64 + lane;
     if (idx < n) {
       const uint32_t d = (uint32_t)(word[r] >> (32 + shift)) & mask;
@@ -302,6 +308,7 @@ hctr_status radix_sort_u64(const SortPlan& plan, const uint32_t* n_dev, uint64_t
     hipLaunchKernelGGL(sort_zero_aux, dim3((uint32_t)ceil_div((int64_t)plan.aux_count, 256)), dim3(256), 0,
                        stream, aux, (uint32_t)plan.aux_count);
   const int scan_sup = plan.n_super > kSortDirectSuperMax ? 1 : 0;
+  const bool wide = plan.n_blocks <= kSortWideMaxTiles;
   int shift = 0;
   for (int p = 0; p < plan.passes; ++p) {
     const int db = plan.digit_bits[p];
@@ -309,22 +316,27 @@ hctr_status radix_sort_u64(const SortPlan& plan, const uint32_t* n_dev, uint64_t
     uint32_t* tot = sort_aux_tot(plan, aux, p);
     uint32_t* sup = sort_aux_sup(plan, aux, p);
     const int src = p & 1, dst = src ^ 1;
-    if (!(p == 0 && first_hist_done))
-      hipLaunchKernelGGL(sort_hist, dim3(plan.n_blocks), dim3(kSortThreads), 0, stream,
-                         (const uint64_t*)buf[src], plan.n_max, n_dev, shift, bins, hist, sup);
+    const uint64_t* in = buf[src];
+    const uint32_t* chist = hist;
+    const uint32_t* ctot = tot;
+    const uint32_t* csup = sup;
+    if (!(p == 0 && first_hist_done)) {
+      if (wide)
+        hipLaunchKernelGGL((sort_hist<kSortWideThreads>), dim3(plan.n_blocks), dim3(kSortWideThreads), 0, stream,
+                           in, plan.n_max, n_dev, shift, bins, hist, sup);
+      else
+        hipLaunchKernelGGL((sort_hist<kSortThreads>), dim3(plan.n_blocks), dim3(kSortThreads), 0, stream, in,
+                           plan.n_max, n_dev, shift, bins, hist, sup);
+    }
     if (scan_sup)
       hipLaunchKernelGGL(sort_scan_sup, dim3((uint32_t)ceil_div(bins, 256)), dim3(256), 0, stream, sup, tot,
                          bins, plan.n_super);
-    if (db <= 8)
-      hipLaunchKernelGGL((sort_scatter<8>), dim3(plan.n_blocks), dim3(kSortThreads), 0, stream,
-                         (const uint64_t*)buf[src], buf[dst], plan.n_max, n_dev, shift, bins,
-                         (const uint32_t*)hist, (const uint32_t*)tot, (const uint32_t*)sup, plan.n_super,
-                         scan_sup);
-    else
-      hipLaunchKernelGGL((sort_scatter<kSortMaxDigitBits>), dim3(plan.n_blocks), dim3(kSortThreads), 0,
-                         stream, (const uint64_t*)buf[src], buf[dst], plan.n_max, n_dev, shift, bins,
-                         (const uint32_t*)hist, (const uint32_t*)tot, (const uint32_t*)sup, plan.n_super,
-                         scan_sup);
+#define HCTR_SCATTER(DB, NT)                                                                             \
+  hipLaunchKernelGGL((sort_scatter<DB, NT>), dim3(plan.n_blocks), dim3(NT), 0, stream, in, buf[dst],     \
+                     plan.n_max, n_dev, shift, bins, chist, ctot, csup, plan.n_super, scan_sup)
+    if (db <= 8) HCTR_SCATTER(8, kSortThreads);          // the scatter measured faster with 256 threads
+    else HCTR_SCATTER(kSortMaxDigitBits, kSortThreads);  // at every size
+#undef HCTR_SCATTER
     shift += db;
   }
   return launch_status("radix_sort_u64");
