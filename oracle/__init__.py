@@ -44,6 +44,10 @@ def lib() -> C.CDLL:
         L.oracle_emb_forward.argtypes = [i32, i32, i32, p, i64, p, p, i64, p]
         L.oracle_emb_backward_sgd.restype = i64
         L.oracle_emb_backward_sgd.argtypes = [i32, i32, i32, p, i64, p, p, i64, p, f32, p, p]
+        L.oracle_group_forward.restype = None
+        L.oracle_group_forward.argtypes = [i32, p, p, p, i32, i32, p, p, i64, p, p, p]
+        L.oracle_group_backward_sgd.restype = i64
+        L.oracle_group_backward_sgd.argtypes = [i32, p, p, p, i32, i32, p, p, i64, p, p, p, f32]
         L.oracle_hash_create.restype = p
         L.oracle_hash_create.argtypes = [i64]
         L.oracle_hash_destroy.restype = None
@@ -138,6 +142,47 @@ def emb_backward_sgd(table: np.ndarray, rows, dY: np.ndarray, lr: float, offsets
                                       table.shape[0], _ptr(rows), _ptr(offsets), n_bags, _ptr(dY),
                                       float(np.float32(lr)), _ptr(uniq), _ptr(cnt))
     return uniq[:u].copy(), cnt[:u].copy()
+
+
+def _group_args(tables, lookup_table, lookup_comb):
+    assert len(tables) >= 1 and all(t.ndim == 2 and t.flags.c_contiguous and t.dtype == tables[0].dtype for t in tables)
+    ptrs = (C.c_void_p * len(tables))(*[t.ctypes.data for t in tables])
+    rows = np.array([t.shape[0] for t in tables], dtype=np.int64)
+    dims = np.array([t.shape[1] for t in tables], dtype=np.int32)
+    lt = np.ascontiguousarray(lookup_table, dtype=np.int32)
+    lc = np.ascontiguousarray(lookup_comb, dtype=np.int32)
+    assert len(lt) == len(lc) and lt.min() >= 0 and lt.max() < len(tables)
+    width = int(dims[lt].sum())
+    return ptrs, rows, dims, lt, lc, width
+
+
+def dense_offsets(batch: int, hotness) -> np.ndarray:
+    """CSR offsets of a dense input: every sample brings hotness[l] keys for lookup l."""
+    per_bag = np.tile(np.asarray(hotness, dtype=np.int64), batch)
+    return np.concatenate([[0], np.cumsum(per_bag)]).astype(np.int64)
+
+
+def group_forward(tables, lookup_table, lookup_comb, batch: int, keys, offsets) -> np.ndarray:
+    """Fused group of lookups: [batch, sum of the lookups' widths] float32."""
+    ptrs, rows, dims, lt, lc, width = _group_args(tables, lookup_table, lookup_comb)
+    keys, offsets = _i64(keys), _i64(offsets)
+    assert len(offsets) == batch * len(lt) + 1
+    out = np.empty((batch, width), dtype=np.float32)
+    lib().oracle_group_forward(len(tables), ptrs, _ptr(rows), _ptr(dims), _dtype_code(tables[0]), len(lt),
+                               _ptr(lt), _ptr(lc), batch, _ptr(keys), _ptr(offsets), _ptr(out))
+    return out
+
+
+def group_backward_sgd(tables, lookup_table, lookup_comb, batch: int, keys, offsets, dY, lr: float) -> int:
+    """Updates the tables in place; returns the number of distinct (table, row) pairs touched."""
+    ptrs, rows, dims, lt, lc, width = _group_args(tables, lookup_table, lookup_comb)
+    assert all(t.flags.writeable for t in tables)
+    keys, offsets = _i64(keys), _i64(offsets)
+    assert len(offsets) == batch * len(lt) + 1
+    dY = np.ascontiguousarray(dY, dtype=np.float32).reshape(batch, width)
+    return int(lib().oracle_group_backward_sgd(len(tables), ptrs, _ptr(rows), _ptr(dims), _dtype_code(tables[0]),
+                                               len(lt), _ptr(lt), _ptr(lc), batch, _ptr(keys), _ptr(offsets),
+                                               _ptr(dY), float(np.float32(lr))))
 
 
 class Hash:

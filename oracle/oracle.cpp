@@ -162,6 +162,85 @@ int64_t oracle_emb_backward_sgd(int32_t dim, int32_t dtype, int32_t combiner, vo
 }
 
 // ---------------------------------------------------------------------------------------------
+// Fused group of lookups (section 4, "Future Work": one embedding fusing tables of different
+// vector size and combiner, fed by dense or sparse inputs).  T tables, each [table_rows[t],
+// table_dim[t]]; L lookups, lookup l reads table lookup_table[l] with combiner lookup_comb[l];
+// bag = sample * L + l; the keys of a bag are direct row indices into the lookup's table (a key
+// outside the table adds nothing but counts in a mean's denominator).  The output row of a sample
+// is the concatenation of its L pooled vectors, lookup l at column col_l = sum of the widths of
+// the lookups before it.  Dense input is the CSR special case with constant bag lengths; the
+// caller passes offsets either way.
+// ---------------------------------------------------------------------------------------------
+void oracle_group_forward(int32_t num_tables, const void* const* tables, const int64_t* table_rows,
+                          const int32_t* table_dim, int32_t dtype, int32_t num_lookups,
+                          const int32_t* lookup_table, const int32_t* lookup_comb, int64_t batch,
+                          const int64_t* keys, const int64_t* offsets, float* out) {
+  (void)num_tables;
+  int64_t width = 0;
+  for (int l = 0; l < num_lookups; ++l) width += table_dim[lookup_table[l]];
+  for (int64_t b = 0; b < batch; ++b) {
+    int64_t col = 0;
+    for (int l = 0; l < num_lookups; ++l) {
+      const int t = lookup_table[l];
+      const int dim = table_dim[t];
+      const int64_t bag = b * num_lookups + l;
+      const int64_t b0 = offsets[bag], b1 = offsets[bag + 1];
+      std::vector<double> acc(dim, 0.0);
+      for (int64_t i = b0; i < b1; ++i) {
+        const int64_t k = keys[i];
+        if (k < 0 || k >= table_rows[t]) continue;
+        for (int d = 0; d < dim; ++d) acc[d] += load_elem(tables[t], dtype, k * dim + d);
+      }
+      const double w = (lookup_comb[l] == COMB_MEAN && b1 > b0) ? 1.0 / (double)(b1 - b0) : 1.0;
+      for (int d = 0; d < dim; ++d) out[b * width + col + d] = (float)(acc[d] * w);
+      col += dim;
+    }
+  }
+}
+
+// Backward + SGD over the group: every distinct (table, row) touched through any lookup gets
+//   T_t[r, :] <- T_t[r, :] - lr * sum over its occurrences of w_bag * dY[b, col_l : col_l + dim].
+// Returns the number of distinct (table, row) pairs.
+int64_t oracle_group_backward_sgd(int32_t num_tables, void* const* tables, const int64_t* table_rows,
+                                  const int32_t* table_dim, int32_t dtype, int32_t num_lookups,
+                                  const int32_t* lookup_table, const int32_t* lookup_comb, int64_t batch,
+                                  const int64_t* keys, const int64_t* offsets, const float* dY, float lr) {
+  int64_t width = 0;
+  for (int l = 0; l < num_lookups; ++l) width += table_dim[lookup_table[l]];
+  std::vector<std::unordered_map<int64_t, std::vector<double>>> grad(num_tables);
+  for (int64_t b = 0; b < batch; ++b) {
+    int64_t col = 0;
+    for (int l = 0; l < num_lookups; ++l) {
+      const int t = lookup_table[l];
+      const int dim = table_dim[t];
+      const int64_t bag = b * num_lookups + l;
+      const int64_t b0 = offsets[bag], b1 = offsets[bag + 1];
+      const double w = (lookup_comb[l] == COMB_MEAN && b1 > b0) ? 1.0 / (double)(b1 - b0) : 1.0;
+      for (int64_t i = b0; i < b1; ++i) {
+        const int64_t k = keys[i];
+        if (k < 0 || k >= table_rows[t]) continue;
+        std::vector<double>& g = grad[t][k];
+        if (g.empty()) g.assign(dim, 0.0);
+        for (int d = 0; d < dim; ++d) g[d] += w * (double)dY[b * width + col + d];
+      }
+      col += dim;
+    }
+  }
+  int64_t touched = 0;
+  for (int t = 0; t < num_tables; ++t) {
+    const int dim = table_dim[t];
+    for (auto& kv : grad[t]) {
+      for (int d = 0; d < dim; ++d) {
+        const double x = load_elem(tables[t], dtype, kv.first * dim + d);
+        store_elem(tables[t], dtype, kv.first * dim + d, x - (double)lr * kv.second[d]);
+      }
+      ++touched;
+    }
+  }
+  return touched;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Hash: key -> dense row id, rows handed out in order of first appearance.
 // ---------------------------------------------------------------------------------------------
 struct oracle_hash {
