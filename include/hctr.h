@@ -53,6 +53,7 @@ typedef enum { HCTR_F32 = 0, HCTR_F16 = 1 } hctr_dtype;
 typedef enum { HCTR_SUM = 0, HCTR_MEAN = 1 } hctr_combiner;
 
 #define HCTR_MAX_SLOTS 128
+#define HCTR_MAX_GROUP_LOOKUPS 64   /* lookups (and tables) of one fused group, see hctr_group_desc */
 
 typedef struct hctr_hash hctr_hash;   /* opaque */
 typedef struct hctr_cache hctr_cache; /* opaque */
@@ -153,6 +154,65 @@ hctr_status hctr_emb_dedup_view(const hctr_emb_desc* desc, int64_t batch, int64_
 /* Number of keys without a row seen by all forward and backward calls on `ws` since
  * hctr_emb_workspace_init (host int64; waits for the stream). */
 hctr_status hctr_emb_invalid_keys(const void* ws, size_t ws_bytes, void* stream, int64_t* count);
+
+/*
+ * Fused group of lookups (section 4, "Future Work": one embedding that fuses tables of different
+ * vector size and combiner and takes both dense and sparse inputs).  A group has T tables, each
+ * with its own allocation, row count and width, and L lookups; lookup l reads table
+ * lookups[l].table with its own combiner, and several lookups may read the same table (their
+ * gradients then meet in one update).  Keys are direct row indices into the lookup's table.
+ *   Bags      bag = sample * L + l; keys bag-major.
+ *   Input     sparse: CSR offsets [batch * L + 1] as for a layer.  Dense: offsets == NULL, every
+ *             sample brings exactly lookups[l].hotness keys for lookup l, so nnz = batch * sum of
+ *             hotness (the library writes the CSR offsets of that shape into the workspace).
+ *   Output    out / dY are fp32 [batch, width] row-major, width = sum of the lookups' table widths;
+ *             lookup l occupies columns [col_l, col_l + dim_l), col_l = sum of the widths before it.
+ *   Rows      for the dedup the tables' rows are numbered over their concatenation in tables[]
+ *             order; the total must stay below 2^32 - 1.
+ * A key outside [0, num_rows) contributes nothing and is counted, as for a layer.  The workspace
+ * starts with the same header as a layer's: hctr_emb_workspace_init and hctr_emb_invalid_keys apply.
+ * The host arrays are read during the call only.
+ */
+typedef struct {
+  void* data;        /* device [num_rows, dim], 16-byte aligned */
+  int64_t num_rows;  /* >= 1 */
+  int32_t dim;       /* > 0, multiple of 4 (fp32 tables) or 8 (fp16 tables) */
+  int32_t reserved;  /* 0 */
+} hctr_group_table;
+
+typedef struct {
+  int32_t table;     /* index into tables[] */
+  int32_t combiner;  /* hctr_combiner */
+  int32_t hotness;   /* dense input: keys per sample, >= 1; ignored for sparse input */
+  int32_t reserved;  /* 0 */
+} hctr_group_lookup;
+
+typedef struct {
+  int32_t num_tables;                /* T, 1..HCTR_MAX_GROUP_LOOKUPS */
+  int32_t num_lookups;               /* L, 1..HCTR_MAX_GROUP_LOOKUPS */
+  int32_t table_dtype;               /* hctr_dtype shared by all tables; out and dY are fp32 */
+  int32_t reserved;                  /* 0 */
+  const hctr_group_table* tables;    /* host [T] */
+  const hctr_group_lookup* lookups;  /* host [L] */
+} hctr_group_desc;
+
+/* Workspace bytes for calls with at most nnz_max keys and `batch` samples (0 on invalid arguments). */
+size_t hctr_group_workspace_bytes(const hctr_group_desc* desc, int64_t batch, int64_t nnz_max);
+
+/* out[b, col_l : col_l + dim_l] = w * sum of the rows named by bag (b, l); w = 1 (sum) or
+ * 1 / number of keys in the bag (mean); empty bag = zeros.  keys device [nnz]; offsets device or
+ * NULL (dense); out device [batch, width]; ws device, 256-byte aligned. */
+hctr_status hctr_group_forward(const hctr_group_desc* desc, int64_t batch, const int64_t* keys,
+                               const int64_t* offsets, int64_t nnz, float* out, void* ws, size_t ws_bytes,
+                               void* stream);
+
+/* Backward with plain SGD for every table of the group: row r of table t gets
+ * r -= lr * sum over the occurrences of (t, r) in the call, whatever lookup they came through,
+ * of w * dY[b, col_l : col_l + dim_l].  Same dedup / segmented reduction as hctr_emb_backward_sgd;
+ * additions in an order fixed by the sorted (row, bag) list. */
+hctr_status hctr_group_backward_sgd(const hctr_group_desc* desc, int64_t batch, const int64_t* keys,
+                                    const int64_t* offsets, int64_t nnz, const float* dY, float lr,
+                                    void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Embedding hash (section 1, the "embedding hash" layers): open addressing, 16-byte slots

@@ -31,6 +31,19 @@ class _EmbDesc(C.Structure):
     ]
 
 
+class _GroupTable(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("num_rows", C.c_int64), ("dim", C.c_int32), ("reserved", C.c_int32)]
+
+
+class _GroupLookup(C.Structure):
+    _fields_ = [("table", C.c_int32), ("combiner", C.c_int32), ("hotness", C.c_int32), ("reserved", C.c_int32)]
+
+
+class _GroupDesc(C.Structure):
+    _fields_ = [("num_tables", C.c_int32), ("num_lookups", C.c_int32), ("table_dtype", C.c_int32),
+                ("reserved", C.c_int32), ("tables", C.POINTER(_GroupTable)), ("lookups", C.POINTER(_GroupLookup))]
+
+
 _lib = None
 
 
@@ -50,7 +63,11 @@ def lib() -> C.CDLL:
     L = C.CDLL(_LIB_PATH)
     p, i32, i64, sz, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
     dp = C.POINTER(_EmbDesc)
+    gp = C.POINTER(_GroupDesc)
     sig = {
+        "hctr_group_workspace_bytes": (sz, [gp, i64, i64]),
+        "hctr_group_forward": (i32, [gp, i64, p, p, i64, p, p, sz, p]),
+        "hctr_group_backward_sgd": (i32, [gp, i64, p, p, i64, p, f32, p, sz, p]),
         "hctr_emb_workspace_bytes": (sz, [dp, i64, i64]),
         "hctr_emb_workspace_init": (i32, [p, sz, p]),
         "hctr_emb_forward": (i32, [dp, i64, p, p, i64, p, p, sz, p]),
@@ -89,7 +106,8 @@ def lib() -> C.CDLL:
 EXPORTS = [
     "hctr_emb_workspace_bytes", "hctr_emb_workspace_init", "hctr_emb_forward", "hctr_emb_backward_sgd", "hctr_emb_backward_dedup",
     "hctr_emb_backward_apply", "hctr_emb_dedup_view",
-    "hctr_emb_invalid_keys", "hctr_hash_storage_bytes", "hctr_hash_create", "hctr_hash_workspace_bytes",
+    "hctr_emb_invalid_keys", "hctr_group_workspace_bytes", "hctr_group_forward", "hctr_group_backward_sgd",
+    "hctr_hash_storage_bytes", "hctr_hash_create", "hctr_hash_workspace_bytes",
     "hctr_hash_insert_or_find", "hctr_hash_size", "hctr_hash_destroy", "hctr_cache_storage_bytes",
     "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_set_small_call_limit", "hctr_cache_query",
     "hctr_cache_query_async", "hctr_cache_insert", "hctr_cache_update", "hctr_cache_refresh", "hctr_cache_stats",
@@ -251,6 +269,70 @@ class EmbeddingLayer:
         rows = ws[pr.value - base: pr.value - base + 4 * u].view(torch.int32).to(torch.int64) & 0xFFFFFFFF
         seg = ws[ps.value - base: ps.value - base + 4 * (u + 1)].view(torch.int32).to(torch.int64) & 0xFFFFFFFF
         return rows, seg[1:] - seg[:-1]
+
+    def invalid_keys(self, ws: Optional[torch.Tensor] = None) -> int:
+        ws = ws if ws is not None else self._wsbuf
+        v = C.c_int64()
+        _check(lib().hctr_emb_invalid_keys(_ptr(ws), ws.numel(), _stream(None), C.byref(v)))
+        return v.value
+
+
+class EmbeddingGroup:
+    """hctr_group_*: fused lookups over tables of different widths.  `tables`: 2-D device tensors of one
+    dtype; `lookups`: (table index, combiner[, hotness]) per lookup.  Dense input = offsets None."""
+
+    def __init__(self, tables: Sequence[torch.Tensor], lookups: Sequence[Sequence[int]]):
+        assert len(tables) >= 1 and all(t.is_cuda and t.is_contiguous() and t.dim() == 2 for t in tables)
+        assert all(t.dtype == tables[0].dtype for t in tables) and tables[0].dtype in (torch.float32, torch.float16)
+        self.tables = list(tables)
+        self.lookups = [tuple(l) + (1,) * (3 - len(l)) for l in lookups]
+        self._t = (_GroupTable * len(tables))()
+        for i, t in enumerate(tables):
+            self._t[i].data, self._t[i].num_rows, self._t[i].dim = t.data_ptr(), t.shape[0], t.shape[1]
+        self._l = (_GroupLookup * len(self.lookups))()
+        for i, (t, c, h) in enumerate(self.lookups):
+            self._l[i].table, self._l[i].combiner, self._l[i].hotness = int(t), int(c), int(h)
+        d = _GroupDesc()
+        d.num_tables, d.num_lookups = len(tables), len(self.lookups)
+        d.table_dtype = F32 if tables[0].dtype == torch.float32 else F16
+        d.tables, d.lookups = self._t, self._l
+        self.desc = d
+        self.width = sum(tables[t].shape[1] for t, _, _ in self.lookups)
+        self.device = tables[0].device
+        self._wsbuf = None
+
+    def workspace_bytes(self, batch: int, nnz: int) -> int:
+        return lib().hctr_group_workspace_bytes(C.byref(self.desc), batch, nnz)
+
+    def new_workspace(self, nbytes: int) -> torch.Tensor:
+        ws = _ws(nbytes, self.device)
+        _check(lib().hctr_emb_workspace_init(_ptr(ws), ws.numel(), _stream(None)))
+        return ws
+
+    def workspace(self, batch: int, nnz: int) -> torch.Tensor:
+        need = self.workspace_bytes(batch, nnz)
+        if self._wsbuf is None or self._wsbuf.numel() < need:
+            self._wsbuf = self.new_workspace(need)
+        return self._wsbuf
+
+    def forward(self, batch: int, keys: torch.Tensor, offsets: Optional[torch.Tensor] = None,
+                out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+        nnz = keys.numel()
+        if out is None:
+            out = torch.empty((batch, self.width), dtype=torch.float32, device=self.device)
+        if ws is None:
+            ws = self.workspace(batch, nnz)
+        _check(lib().hctr_group_forward(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(out),
+                                        _ptr(ws), ws.numel(), _stream(stream)))
+        return out
+
+    def backward_sgd(self, batch: int, keys: torch.Tensor, dY: torch.Tensor, lr: float,
+                     offsets: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> None:
+        nnz = keys.numel()
+        if ws is None:
+            ws = self.workspace(batch, nnz)
+        _check(lib().hctr_group_backward_sgd(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(dY),
+                                             float(lr), _ptr(ws), ws.numel(), _stream(stream)))
 
     def invalid_keys(self, ws: Optional[torch.Tensor] = None) -> int:
         ws = ws if ws is not None else self._wsbuf

@@ -428,6 +428,69 @@ __global__ __launch_bounds__(NT) void seg_write(const uint64_t* __restrict__ skv
 }
 
 // ------------------------------------------------------------------------------------------------
+// Where the backward kernels find an occurrence's gradient row and a row's storage.  UniformView:
+// one fused table, every bag D wide, dY is [n_bags, D].  GroupView: a fused group of lookups of
+// different widths over separate tables; dY is [batch, width_total] with lookup l at column
+// col[l]; bag = sample * L + l; rows are numbered over the concatenation of the tables.
+// ------------------------------------------------------------------------------------------------
+struct GroupLookup {
+  void* table;        // the lookup's table (several lookups may name the same one)
+  uint32_t row_base;  // first row number of that table
+  uint32_t col;       // first output column
+  uint32_t dim;       // row width
+  uint32_t mean;      // 1: mean combiner
+};
+static_assert(sizeof(GroupLookup) == 24, "kernel-argument layout");
+
+template <typename T>
+struct UniformView {
+  static constexpr int kLds = 1;
+  T* table;
+  const float* dY;
+  int D;
+  int mean;
+  __device__ __forceinline__ const GroupLookup* stage(GroupLookup*) const { return nullptr; }
+  __device__ __forceinline__ int dmax() const { return D; }
+  __device__ __forceinline__ bool is_mean(uint32_t, const GroupLookup*) const { return mean != 0; }
+  __device__ __forceinline__ const float* grad(uint32_t bag, const GroupLookup*, int* width) const {
+    *width = D;
+    return dY + (int64_t)bag * D;
+  }
+  __device__ __forceinline__ T* row(uint32_t r, uint32_t, const GroupLookup*, int* width) const {
+    *width = D;
+    return table + (int64_t)r * D;
+  }
+};
+
+template <typename T>
+struct GroupView {
+  static constexpr int kLds = HCTR_MAX_GROUP_LOOKUPS;
+  const float* dY;
+  uint32_t L;
+  uint32_t width_total;
+  int dmax_;
+  GroupLookup lk[HCTR_MAX_GROUP_LOOKUPS];
+  // The lookups go to LDS first: indexing the kernel arguments per lane would be a global load.
+  __device__ __forceinline__ const GroupLookup* stage(GroupLookup* lds) const {
+    if (threadIdx.x < L) lds[threadIdx.x] = lk[threadIdx.x];
+    __syncthreads();
+    return lds;
+  }
+  __device__ __forceinline__ int dmax() const { return dmax_; }
+  __device__ __forceinline__ bool is_mean(uint32_t bag, const GroupLookup* l) const { return l[bag % L].mean != 0; }
+  __device__ __forceinline__ const float* grad(uint32_t bag, const GroupLookup* l, int* width) const {
+    const GroupLookup& k = l[bag % L];
+    *width = (int)k.dim;
+    return dY + (int64_t)(bag / L) * width_total + k.col;
+  }
+  __device__ __forceinline__ T* row(uint32_t r, uint32_t bag, const GroupLookup* l, int* width) const {
+    const GroupLookup& k = l[bag % L];
+    *width = (int)k.dim;
+    return static_cast<T*>(k.table) + (int64_t)(r - k.row_base) * k.dim;
+  }
+};
+
+// ------------------------------------------------------------------------------------------------
 // Backward steps 4+5.  The sorted occurrence list is cut into windows of W positions; a group of
 // LPR lanes (4 dY columns per lane) walks one window.  A row whose occurrences all lie inside the
 // window is reduced and updated on the spot.  A row that crosses window borders leaves one partial
@@ -435,16 +498,17 @@ __global__ __launch_bounds__(NT) void seg_write(const uint64_t* __restrict__ skv
 // adds a row's partials in window order and applies the update.  Order of additions is fixed by
 // the sorted positions, so results do not vary from run to run.
 // ------------------------------------------------------------------------------------------------
-template <typename T, int LPR>
+template <typename T, int LPR, typename View>
 __global__ __launch_bounds__(256) void bwd_reduce_windows(
-    T* __restrict__ table, int D, const uint64_t* __restrict__ skv,
-    const EmbHeader* __restrict__ hdr, const int64_t* __restrict__ offsets, int mean,
-    const float* __restrict__ dY, float lr, float* __restrict__ head, float* __restrict__ tail,
+    const View view, const uint64_t* __restrict__ skv, const EmbHeader* __restrict__ hdr,
+    const int64_t* __restrict__ offsets, float lr, float* __restrict__ head, float* __restrict__ tail,
     uint8_t* __restrict__ tail_flag, uint32_t W, EmbHeader* hdr_rw) {
+  __shared__ GroupLookup lds_lk[View::kLds];
+  const GroupLookup* lk = view.stage(lds_lk);
   const int sub = threadIdx.x % LPR;
   const uint32_t win = (blockIdx.x * 256u + threadIdx.x) / LPR;
   const int col = blockIdx.y * (LPR * 4) + sub * 4;
-  const bool active = col < D;
+  const int DM = view.dmax();
   const uint32_t n_valid = hdr->n_valid;
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) hdr_rw->n_long = 0;   // for the carry kernels
   const uint64_t start64 = (uint64_t)win * W;
@@ -469,10 +533,10 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
       myrow = (uint32_t)(w64 >> 32);
       mybag = (uint32_t)w64;
       if (p0 + sub + 1 < n_valid) mynext = (uint32_t)(skv[p0 + sub + 1] >> 32);
-      if (mean) myw = 1.0f / (float)(offsets[mybag + 1] - offsets[mybag]);
+      if (view.is_mean(mybag, lk)) myw = 1.0f / (float)(offsets[mybag + 1] - offsets[mybag]);
     }
     for (int q0 = 0; q0 < cnt; q0 += UB) {
-      uint32_t r[UB];
+      uint32_t r[UB], b[UB];
       bool ends[UB];
       float w[UB];
       f32x4 v[UB], t[UB];
@@ -482,14 +546,20 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
         const int q = live ? q0 + u : q0;  // clamp: dead positions are ignored below
         r[u] = __shfl(myrow, q, LPR);
         ends[u] = live && __shfl(mynext, q, LPR) != r[u];
-        const uint32_t b = __shfl(mybag, q, LPR);
+        b[u] = __shfl(mybag, q, LPR);
         w[u] = __shfl(myw, q, LPR);
-        v[u] = active ? load4(dY + (int64_t)b * D + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+        int width;
+        const float* g = view.grad(b[u], lk, &width);
+        v[u] = col < width ? load4(g + col) : f32x4{0.f, 0.f, 0.f, 0.f};
       }
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
         t[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (ends[u] && active) t[u] = load_row4(table + (int64_t)r[u] * D + col);
+        if (ends[u]) {
+          int width;
+          const T* rp = view.row(r[u], b[u], lk, &width);
+          if (col < width) t[u] = load_row4(rp + col);
+        }
       }
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
@@ -498,12 +568,14 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
           acc.z += w[u] * v[u].z; acc.w += w[u] * v[u].w;
         }
         if (ends[u]) {
-          if (active) {
+          int width;
+          T* rp = view.row(r[u], b[u], lk, &width);
+          if (col < width) {
             if (before) {
-              store4(head + (int64_t)win * D + col, acc);
+              store4(head + (int64_t)win * DM + col, acc);
             } else {
               t[u].x -= lr * acc.x; t[u].y -= lr * acc.y; t[u].z -= lr * acc.z; t[u].w -= lr * acc.w;
-              store_row4(table + (int64_t)r[u] * D + col, t[u]);
+              store_row4(rp + col, t[u]);
             }
           }
           acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -515,7 +587,7 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
   // the last row of the window continues in the next window
   const bool continues = end < n_valid && (uint32_t)(skv[end] >> 32) == (uint32_t)(skv[end - 1] >> 32);
   if (continues) {
-    if (active) store4((before ? head : tail) + (int64_t)win * D + col, acc);
+    if (col < DM) store4((before ? head : tail) + (int64_t)win * DM + col, acc);
     wrote_tail = !before;
   }
   if (sub == 0 && blockIdx.y == 0) tail_flag[win] = wrote_tail ? 1 : 0;
@@ -530,66 +602,77 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
 // every row's additions happen in an order fixed by its length alone.
 constexpr uint32_t kCarryShort = 8;
 
-__device__ __forceinline__ bool carry_extent(const uint64_t* __restrict__ skv,
+__device__ __forceinline__ void carry_extent(const uint64_t* __restrict__ skv,
                                              const uint32_t* __restrict__ starts_before,
                                              const uint32_t* __restrict__ seg_off, uint32_t win, uint32_t W,
-                                             uint32_t* row, uint32_t* last) {
+                                             uint32_t* row, uint32_t* bag, uint32_t* last) {
   // a tail exists only when the window is full and its last row continues into the next window
   const uint32_t p = win * W + W - 1;
-  const uint32_t r = (uint32_t)(skv[p] >> 32);
+  const uint64_t w64 = skv[p];
+  const uint32_t r = (uint32_t)(w64 >> 32);
   const uint32_t u = starts_before[p] + ((p == 0 || (uint32_t)(skv[p - 1] >> 32) != r) ? 1u : 0u) - 1u;
   *row = r;
+  *bag = (uint32_t)w64;   // any occurrence of the row names its table
   *last = (seg_off[u + 1] - 1u) / W;   // last window holding a piece of the row
-  return true;
 }
 
-template <typename T, int LPR>
+template <typename T, int LPR, typename View>
 __global__ __launch_bounds__(256) void bwd_carry_short(
-    T* __restrict__ table, int D, const uint64_t* __restrict__ skv,
-    const uint32_t* __restrict__ starts_before, const uint32_t* __restrict__ seg_off, EmbHeader* hdr,
-    float lr, const float* __restrict__ head, const float* __restrict__ tail,
-    const uint8_t* __restrict__ tail_flag, uint32_t W, uint32_t* __restrict__ long_list) {
+    const View view, const uint64_t* __restrict__ skv, const uint32_t* __restrict__ starts_before,
+    const uint32_t* __restrict__ seg_off, EmbHeader* hdr, float lr, const float* __restrict__ head,
+    const float* __restrict__ tail, const uint8_t* __restrict__ tail_flag, uint32_t W,
+    uint32_t* __restrict__ long_list) {
+  __shared__ GroupLookup lds_lk[View::kLds];
+  const GroupLookup* lk = view.stage(lds_lk);
   const int sub = threadIdx.x % LPR;
   const uint32_t win = (blockIdx.x * 256u + threadIdx.x) / LPR;
   const int col = blockIdx.y * (LPR * 4) + sub * 4;
-  const bool active = col < D;
+  const int DM = view.dmax();
   if ((uint64_t)win * W >= hdr->n_valid) return;
   if (!tail_flag[win]) return;
-  uint32_t r, last;
-  carry_extent(skv, starts_before, seg_off, win, W, &r, &last);
+  uint32_t r, bag, last;
+  carry_extent(skv, starts_before, seg_off, win, W, &r, &bag, &last);
   const uint32_t cnt = last - win;   // following windows, each with a head partial
   if (cnt > kCarryShort) {
     if (sub == 0 && blockIdx.y == 0) long_list[atomicAdd(&hdr->n_long, 1u)] = win;
     return;
   }
+  int width;
+  T* rp = view.row(r, bag, lk, &width);
+  const bool active = col < width;
   f32x4 h[kCarryShort];
 #pragma unroll
   for (uint32_t k = 0; k < kCarryShort; ++k)
-    h[k] = (active && k < cnt) ? load4(head + (int64_t)(win + 1 + k) * D + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+    h[k] = (active && k < cnt) ? load4(head + (int64_t)(win + 1 + k) * DM + col) : f32x4{0.f, 0.f, 0.f, 0.f};
   if (active) {
-    f32x4 tot = load4(tail + (int64_t)win * D + col);
+    f32x4 tot = load4(tail + (int64_t)win * DM + col);
 #pragma unroll
     for (uint32_t k = 0; k < kCarryShort; ++k) { tot.x += h[k].x; tot.y += h[k].y; tot.z += h[k].z; tot.w += h[k].w; }
-    sgd_update4(table + (int64_t)r * D + col, tot, lr);
+    sgd_update4(rp + col, tot, lr);
   }
 }
 
-template <typename T, int LPR>
+template <typename T, int LPR, typename View>
 __global__ __launch_bounds__(1024) void bwd_carry_long(
-    T* __restrict__ table, int D, const uint64_t* __restrict__ skv,
-    const uint32_t* __restrict__ starts_before, const uint32_t* __restrict__ seg_off,
-    const EmbHeader* __restrict__ hdr, float lr, const float* __restrict__ head,
-    const float* __restrict__ tail, uint32_t W, const uint32_t* __restrict__ long_list) {
+    const View view, const uint64_t* __restrict__ skv, const uint32_t* __restrict__ starts_before,
+    const uint32_t* __restrict__ seg_off, const EmbHeader* __restrict__ hdr, float lr,
+    const float* __restrict__ head, const float* __restrict__ tail, uint32_t W,
+    const uint32_t* __restrict__ long_list) {
   constexpr int NG = 1024 / LPR;
   __shared__ f32x4 part[1024];
+  __shared__ GroupLookup lds_lk[View::kLds];
+  const GroupLookup* lk = view.stage(lds_lk);
   const int sub = threadIdx.x % LPR, g = threadIdx.x / LPR;
   const int col = blockIdx.y * (LPR * 4) + sub * 4;
-  const bool active = col < D;
+  const int DM = view.dmax();
   const uint32_t n_long = hdr->n_long;
   for (uint32_t i = blockIdx.x; i < n_long; i += gridDim.x) {   // block-uniform loop
     const uint32_t win = long_list[i];
-    uint32_t r, last;
-    carry_extent(skv, starts_before, seg_off, win, W, &r, &last);
+    uint32_t r, bag, last;
+    carry_extent(skv, starts_before, seg_off, win, W, &r, &bag, &last);
+    int width;
+    T* rp = view.row(r, bag, lk, &width);
+    const bool active = col < width;
     const uint32_t cnt = last - win;
     const uint32_t share = (cnt + NG - 1) / NG;
     const uint32_t f0 = win + 1 + g * share;
@@ -599,23 +682,108 @@ __global__ __launch_bounds__(1024) void bwd_carry_long(
       f32x4 h[8];
 #pragma unroll
       for (int k = 0; k < 8; ++k)
-        h[k] = (active && w2 + k < f1) ? load4(head + (int64_t)(w2 + k) * D + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+        h[k] = (active && w2 + k < f1) ? load4(head + (int64_t)(w2 + k) * DM + col) : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int k = 0; k < 8; ++k) { acc.x += h[k].x; acc.y += h[k].y; acc.z += h[k].z; acc.w += h[k].w; }
     }
     part[threadIdx.x] = acc;
     __syncthreads();
     if (g == 0 && active) {
-      f32x4 tot = load4(tail + (int64_t)win * D + col);
+      f32x4 tot = load4(tail + (int64_t)win * DM + col);
 #pragma unroll 8
       for (int gg = 0; gg < NG; ++gg) {
         const f32x4 q = part[gg * LPR + sub];
         tot.x += q.x; tot.y += q.y; tot.z += q.z; tot.w += q.w;
       }
-      sgd_update4(table + (int64_t)r * D + col, tot, lr);
+      sgd_update4(rp + col, tot, lr);
     }
     __syncthreads();   // part is reused by the next row
   }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Fused group of lookups over tables of different widths.  Forward: a thread owns four adjacent
+// output columns of one sample (one lookup's quad), walks that bag's keys with four row loads in
+// flight and writes its quad once; the lanes of a lookup read the same keys (one request per
+// wave) and adjacent 16-byte pieces of the same rows, and a wave's stores are contiguous whatever
+// the widths are.
+// ------------------------------------------------------------------------------------------------
+struct GroupFwdArgs {
+  uint32_t L;
+  uint32_t width_total;
+  GroupLookup lk[HCTR_MAX_GROUP_LOOKUPS];
+  uint32_t num_rows[HCTR_MAX_GROUP_LOOKUPS];   // rows of the lookup's table
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void fwd_group(const GroupFwdArgs a, const int64_t* __restrict__ keys,
+                                                 const int64_t* __restrict__ offsets, uint64_t n_quads,
+                                                 float* __restrict__ out, EmbHeader* hdr) {
+  __shared__ GroupLookup lk[HCTR_MAX_GROUP_LOOKUPS];
+  __shared__ uint32_t nrows[HCTR_MAX_GROUP_LOOKUPS];
+  if (threadIdx.x < a.L) {
+    lk[threadIdx.x] = a.lk[threadIdx.x];
+    nrows[threadIdx.x] = a.num_rows[threadIdx.x];
+  }
+  __syncthreads();
+  const uint32_t W4 = a.width_total / 4;
+  uint32_t nbad = 0;   // counted by the lane that owns a lookup's first quad
+  for (uint64_t q = (uint64_t)blockIdx.x * 256u + threadIdx.x; q < n_quads; q += (uint64_t)gridDim.x * 256u) {
+    const uint32_t b = (uint32_t)(q / W4);
+    const uint32_t c = (uint32_t)(q % W4) * 4u;
+    int lo = 0, hi = (int)a.L - 1;   // the lookup that owns column c: the last one starting at or before it
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (lk[mid].col <= c) lo = mid; else hi = mid - 1;
+    }
+    const GroupLookup k = lk[lo];
+    const uint32_t cl = c - k.col;
+    const int64_t nr = nrows[lo];
+    const T* __restrict__ tbl = static_cast<const T*>(k.table);
+    const uint64_t bag = (uint64_t)b * a.L + (uint32_t)lo;
+    const int64_t k0 = offsets[bag], k1 = offsets[bag + 1];
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t p = k0; p < k1; p += 4) {
+      int64_t key[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) key[u] = p + u < k1 ? keys[p + u] : (int64_t)-1;
+      f32x4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool ok = key[u] >= 0 && key[u] < nr;
+        v[u] = ok ? load_row4(tbl + key[u] * k.dim + cl) : f32x4{0.f, 0.f, 0.f, 0.f};
+        nbad += (cl == 0 && p + u < k1 && !ok) ? 1u : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+    }
+    if (k.mean && k1 > k0) {
+      const float w = 1.0f / (float)(k1 - k0);
+      acc.x *= w; acc.y *= w; acc.z *= w; acc.w *= w;
+    }
+    __builtin_nontemporal_store(acc, reinterpret_cast<f32x4*>(out + (uint64_t)b * a.width_total + c));
+  }
+  if (__ballot(nbad != 0) != 0) {   // every lane of the wave is here: the loop above has no early exit
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) nbad += __shfl_xor(nbad, d);
+    if ((threadIdx.x & 63) == 0) atomicAdd(&hdr->invalid, (unsigned long long)nbad);
+  }
+}
+
+// Dense input: the CSR offsets of `batch` samples that each bring hot[l] keys for lookup l.
+struct GroupHotness {
+  uint32_t L;
+  uint32_t per_sample;                            // sum of the hotness values
+  uint32_t before[HCTR_MAX_GROUP_LOOKUPS];        // keys of a sample before lookup l
+};
+__global__ __launch_bounds__(256) void group_dense_offsets(const GroupHotness h, uint64_t n_bags,
+                                                           int64_t* __restrict__ offsets) {
+  __shared__ uint32_t before[HCTR_MAX_GROUP_LOOKUPS];
+  if (threadIdx.x < h.L) before[threadIdx.x] = h.before[threadIdx.x];
+  __syncthreads();
+  const uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+  if (i < n_bags) offsets[i] = (int64_t)(i / h.L) * h.per_sample + before[i % h.L];
+  if (i == n_bags) offsets[i] = (int64_t)(n_bags / h.L) * h.per_sample;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -624,7 +792,7 @@ __global__ __launch_bounds__(1024) void bwd_carry_long(
 struct EmbLayout {
   // byte offsets into the workspace (all multiples of 256)
   size_t header, kv0, kv1, hist, aux, seg_counts, flags, uniq, seg_off, long_list, head, tail,
-      tail_flag, rows64, hash_ws, total;
+      tail_flag, rows64, hash_ws, extra, total;
   uint32_t window, n_windows, seg_tiles, seg_super;
   int sort_bits;
   SortPlan sort;
@@ -632,12 +800,14 @@ struct EmbLayout {
 
 static uint32_t pick_window(int64_t nnz) { return nnz <= (8ll << 20) ? 32u : 128u; }
 
-static EmbLayout emb_layout(const hctr_emb_desc* d, int64_t nnz_max) {
+// Workspace of a layer or a group: total_rows rows in all, widest row dmax, hashed = with the
+// key -> row scratch of the hashed mode, extra = bytes appended for the caller (group: CSR offsets).
+static EmbLayout emb_layout_raw(int64_t total_rows, int dmax, int64_t nnz_max, bool hashed, size_t extra) {
   EmbLayout L{};
   const size_t n = (size_t)(nnz_max > 0 ? nnz_max : 1);
   Carver c(nullptr);
   auto at = [&](size_t bytes) { size_t o = c.off; c.take<char>(bytes); return o; };
-  L.sort_bits = ceil_log2((uint64_t)d->total_rows + 1);
+  L.sort_bits = ceil_log2((uint64_t)total_rows + 1);
   L.sort = sort_plan((uint32_t)n, L.sort_bits);
   L.window = pick_window(nnz_max);
   L.n_windows = (uint32_t)ceil_div((int64_t)n, L.window);
@@ -652,15 +822,20 @@ static EmbLayout emb_layout(const hctr_emb_desc* d, int64_t nnz_max) {
   L.uniq = at(n * 4);
   L.seg_off = at((n + 1) * 4);
   L.long_list = at((size_t)L.n_windows * 4);
-  L.head = at((size_t)L.n_windows * d->dim * 4);
-  L.tail = at((size_t)L.n_windows * d->dim * 4);
+  L.head = at((size_t)L.n_windows * dmax * 4);
+  L.tail = at((size_t)L.n_windows * dmax * 4);
   L.tail_flag = at(L.n_windows);
-  if (d->hash) {
+  if (hashed) {
     L.rows64 = at(n * 8);
     L.hash_ws = at(hash_ws_bytes((int64_t)n));
   }
+  if (extra) L.extra = at(extra);
   L.total = c.off;
   return L;
+}
+
+static EmbLayout emb_layout(const hctr_emb_desc* d, int64_t nnz_max) {
+  return emb_layout_raw(d->total_rows, d->dim, nnz_max, d->hash != nullptr, 0);
 }
 
 static hctr_status validate_desc(const hctr_emb_desc* d) {
@@ -779,43 +954,53 @@ static void dispatch_forward(int lpr, const hctr_emb_desc* d, const int64_t* key
   }
 }
 
-template <typename T, int LPR>
-static void launch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, const uint64_t* skv,
-                          const int64_t* offsets, const float* dY, float lr, hipStream_t stream) {
-  const uint32_t ychunks = (uint32_t)ceil_div(d->dim, LPR * 4);
+// Launches the three reduction kernels for one view; dmax = widest row of the view.
+template <typename T, int LPR, typename View>
+static void launch_reduce(const View& view, int dmax, const EmbLayout& L, char* ws, const uint64_t* skv,
+                          const int64_t* offsets, float lr, hipStream_t stream) {
+  const uint32_t ychunks = (uint32_t)ceil_div(dmax, LPR * 4);
   dim3 grid((uint32_t)ceil_div(L.n_windows, 256 / LPR), ychunks);
-  T* table = static_cast<T*>(d->table);
   EmbHeader* hdr = reinterpret_cast<EmbHeader*>(ws + L.header);
   float* head = reinterpret_cast<float*>(ws + L.head);
   float* tail = reinterpret_cast<float*>(ws + L.tail);
   uint8_t* tflag = reinterpret_cast<uint8_t*>(ws + L.tail_flag);
-  const int mean = (d->combiner == HCTR_MEAN && offsets != nullptr) ? 1 : 0;
-  hipLaunchKernelGGL((bwd_reduce_windows<T, LPR>), grid, dim3(256), 0, stream, table, d->dim, skv,
-                     (const EmbHeader*)hdr, offsets, mean, dY, lr, head, tail, tflag, L.window, hdr);
+  hipLaunchKernelGGL((bwd_reduce_windows<T, LPR, View>), grid, dim3(256), 0, stream, view, skv,
+                     (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr);
   uint32_t* long_list = reinterpret_cast<uint32_t*>(ws + L.long_list);
   const uint32_t* starts_before = reinterpret_cast<const uint32_t*>(ws + L.flags);
   const uint32_t* seg_off = reinterpret_cast<const uint32_t*>(ws + L.seg_off);
-  hipLaunchKernelGGL((bwd_carry_short<T, LPR>), grid, dim3(256), 0, stream, table, d->dim, skv, starts_before,
+  hipLaunchKernelGGL((bwd_carry_short<T, LPR, View>), grid, dim3(256), 0, stream, view, skv, starts_before,
                      seg_off, hdr, lr, (const float*)head, (const float*)tail, (const uint8_t*)tflag, L.window,
                      long_list);
   dim3 lgrid(L.n_windows < 256u ? L.n_windows : 256u, ychunks);
-  hipLaunchKernelGGL((bwd_carry_long<T, LPR>), lgrid, dim3(1024), 0, stream, table, d->dim, skv, starts_before,
+  hipLaunchKernelGGL((bwd_carry_long<T, LPR, View>), lgrid, dim3(1024), 0, stream, view, skv, starts_before,
                      seg_off, (const EmbHeader*)hdr, lr, (const float*)head, (const float*)tail, L.window,
                      (const uint32_t*)long_list);
+}
+
+template <typename T, typename View>
+static void dispatch_reduce_view(const View& view, int dmax, const EmbLayout& L, char* ws, const uint64_t* skv,
+                                 const int64_t* offsets, float lr, hipStream_t stream) {
+  int lpr = pow2_ceil((int)ceil_div(dmax, 4));
+  lpr = lpr < 4 ? 4 : (lpr > 64 ? 64 : lpr);
+  switch (lpr) {
+    case 4: launch_reduce<T, 4>(view, dmax, L, ws, skv, offsets, lr, stream); break;
+    case 8: launch_reduce<T, 8>(view, dmax, L, ws, skv, offsets, lr, stream); break;
+    case 16: launch_reduce<T, 16>(view, dmax, L, ws, skv, offsets, lr, stream); break;
+    case 32: launch_reduce<T, 32>(view, dmax, L, ws, skv, offsets, lr, stream); break;
+    default: launch_reduce<T, 64>(view, dmax, L, ws, skv, offsets, lr, stream); break;
+  }
 }
 
 template <typename T>
 static void dispatch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, const uint64_t* skv,
                             const int64_t* offsets, const float* dY, float lr, hipStream_t stream) {
-  int lpr = pow2_ceil((int)ceil_div(d->dim, 4));
-  lpr = lpr < 4 ? 4 : (lpr > 64 ? 64 : lpr);
-  switch (lpr) {
-    case 4: launch_reduce<T, 4>(d, L, ws, skv, offsets, dY, lr, stream); break;
-    case 8: launch_reduce<T, 8>(d, L, ws, skv, offsets, dY, lr, stream); break;
-    case 16: launch_reduce<T, 16>(d, L, ws, skv, offsets, dY, lr, stream); break;
-    case 32: launch_reduce<T, 32>(d, L, ws, skv, offsets, dY, lr, stream); break;
-    default: launch_reduce<T, 64>(d, L, ws, skv, offsets, dY, lr, stream); break;
-  }
+  UniformView<T> view;
+  view.table = static_cast<T*>(d->table);
+  view.dY = dY;
+  view.D = d->dim;
+  view.mean = (d->combiner == HCTR_MEAN && offsets != nullptr) ? 1 : 0;
+  dispatch_reduce_view<T>(view, d->dim, L, ws, skv, offsets, lr, stream);
 }
 
 }  // namespace hctr
@@ -856,10 +1041,11 @@ HCTR_API hctr_status hctr_emb_forward(const hctr_emb_desc* desc, int64_t batch, 
   return launch_status("hctr_emb_forward");
 }
 
-// B1-B3: key -> row, sort, run boundaries.  Reads keys / offsets only and writes the workspace.
-static hctr_status backward_dedup(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
-                                  const int64_t* offsets, int64_t nnz, const EmbLayout& L, char* w,
-                                  hipStream_t stream) {
+// B1-B3 (reads keys / offsets only and writes the workspace) for keys whose bags cycle through n_slots slots with the row ranges in st (or whose rows
+// are given in rows64): packed (row, bag) words, sorted by row, run boundaries.
+static hctr_status dedup_core(const int64_t* keys, const int64_t* rows64, const int64_t* offsets, int64_t nnz,
+                              uint32_t n_bags, uint32_t n_slots, const SlotTable& st, int64_t total_rows,
+                              const EmbLayout& L, char* w, hipStream_t stream) {
   EmbHeader* hdr = reinterpret_cast<EmbHeader*>(w + L.header);
   uint32_t* seg_off = reinterpret_cast<uint32_t*>(w + L.seg_off);
   uint32_t* aux = reinterpret_cast<uint32_t*>(w + L.aux);
@@ -868,15 +1054,6 @@ static hctr_status backward_dedup(const hctr_emb_desc* desc, int64_t batch, cons
                      seg_off, 0, aux, zero_count);
   if (nnz == 0) return launch_status("emb_init_header");
   const uint32_t n = (uint32_t)nnz;
-  const uint32_t n_bags = (uint32_t)(batch * desc->num_slots);
-  const int64_t* rows64 = nullptr;
-  if (desc->hash) {
-    int64_t* r = reinterpret_cast<int64_t*>(w + L.rows64);
-    HCTR_TRY(hash_lookup(desc->hash, keys, nnz, 0, r, w + L.hash_ws, L.total - L.hash_ws, stream));
-    rows64 = r;
-  }
-  SlotTable st;
-  fill_slots(desc, &st);
   uint64_t* kv0 = reinterpret_cast<uint64_t*>(w + L.kv0);
   uint64_t* kv1 = reinterpret_cast<uint64_t*>(w + L.kv1);
   uint32_t* hist = reinterpret_cast<uint32_t*>(w + L.hist);
@@ -890,12 +1067,10 @@ static hctr_status backward_dedup(const hctr_emb_desc* desc, int64_t batch, cons
   const uint32_t bins0 = 1u << L.sort.digit_bits[0];
   if (wide && offsets == nullptr)
     hipLaunchKernelGGL((bwd_rows<1024>), dim3(L.sort.n_blocks), dim3(1024), 0, stream, keys, rows64, offsets, n,
-                       n_bags, (uint32_t)desc->num_slots, st, desc->total_rows, kv0, hdr, bins0, hist,
-                       sort_aux_sup(L.sort, aux, 0));
+                       n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sort_aux_sup(L.sort, aux, 0));
   else
     hipLaunchKernelGGL((bwd_rows<256>), dim3(L.sort.n_blocks), dim3(256), 0, stream, keys, rows64, offsets, n,
-                       n_bags, (uint32_t)desc->num_slots, st, desc->total_rows, kv0, hdr, bins0, hist,
-                       sort_aux_sup(L.sort, aux, 0));
+                       n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sort_aux_sup(L.sort, aux, 0));
   HCTR_TRY(radix_sort_u64(L.sort, nullptr, kv0, kv1, hist, aux, true, stream, true));
   const uint64_t* skv = (L.sort.passes & 1) ? kv1 : kv0;
   if (wide) {
@@ -907,7 +1082,22 @@ static hctr_status backward_dedup(const hctr_emb_desc* desc, int64_t batch, cons
     hipLaunchKernelGGL((seg_write<256>), dim3(L.seg_tiles), dim3(256), 0, stream, skv, n,
                        (const uint32_t*)seg_counts, (const uint32_t*)segsup, flags, uniq, seg_off, hdr);
   }
-  return launch_status("hctr_emb_backward_dedup");
+  return launch_status("dedup");
+}
+
+static hctr_status backward_dedup(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
+                                  const int64_t* offsets, int64_t nnz, const EmbLayout& L, char* w,
+                                  hipStream_t stream) {
+  const int64_t* rows64 = nullptr;
+  if (desc->hash && nnz > 0) {
+    int64_t* r = reinterpret_cast<int64_t*>(w + L.rows64);
+    HCTR_TRY(hash_lookup(desc->hash, keys, nnz, 0, r, w + L.hash_ws, L.total - L.hash_ws, stream));
+    rows64 = r;
+  }
+  SlotTable st;
+  fill_slots(desc, &st);
+  return dedup_core(keys, rows64, offsets, nnz, (uint32_t)(batch * desc->num_slots), (uint32_t)desc->num_slots,
+                    st, desc->total_rows, L, w, stream);
 }
 
 // B4-B5: segmented reduction of dY over the sorted occurrences, fused with the SGD row update.
@@ -982,4 +1172,188 @@ HCTR_API hctr_status hctr_emb_invalid_keys(const void* ws, size_t ws_bytes, void
   HCTR_TRY_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
   *count = (int64_t)v;
   return HCTR_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Fused group: host side
+// ------------------------------------------------------------------------------------------------
+namespace hctr {
+
+struct GroupPlan {
+  uint32_t L, width_total, per_sample;
+  int dmax;
+  int64_t total_rows;
+  uint32_t row_base[HCTR_MAX_GROUP_LOOKUPS];   // per table
+  GroupLookup lk[HCTR_MAX_GROUP_LOOKUPS];      // per lookup
+  uint32_t num_rows[HCTR_MAX_GROUP_LOOKUPS];   // per lookup
+  GroupHotness hot;
+};
+
+static hctr_status group_plan(const hctr_group_desc* d, GroupPlan* P) {
+  if (!d) return fail(HCTR_E_NULL_PTR, "desc is NULL");
+  if (d->num_tables < 1 || d->num_tables > HCTR_MAX_GROUP_LOOKUPS || d->num_lookups < 1 ||
+      d->num_lookups > HCTR_MAX_GROUP_LOOKUPS)
+    return fail(HCTR_E_INVALID_ARG, "num_tables %d / num_lookups %d outside 1..%d", d->num_tables,
+                d->num_lookups, HCTR_MAX_GROUP_LOOKUPS);
+  if (d->table_dtype != HCTR_F32 && d->table_dtype != HCTR_F16)
+    return fail(HCTR_E_INVALID_ARG, "table_dtype %d unknown", d->table_dtype);
+  if (!d->tables || !d->lookups) return fail(HCTR_E_NULL_PTR, "tables / lookups is NULL");
+  const int mult = d->table_dtype == HCTR_F32 ? 4 : 8;
+  int64_t rows = 0;
+  for (int t = 0; t < d->num_tables; ++t) {
+    const hctr_group_table& tb = d->tables[t];
+    if (!tb.data) return fail(HCTR_E_NULL_PTR, "table %d: data is NULL", t);
+    if ((uintptr_t)tb.data % 16 != 0) return fail(HCTR_E_INVALID_ARG, "table %d must be 16-byte aligned", t);
+    if (tb.dim <= 0 || tb.dim % mult != 0)
+      return fail(HCTR_E_INVALID_ARG, "table %d: dim %d must be a positive multiple of %d", t, tb.dim, mult);
+    if (tb.num_rows < 1) return fail(HCTR_E_INVALID_ARG, "table %d: num_rows %lld < 1", t, (long long)tb.num_rows);
+    P->row_base[t] = (uint32_t)rows;
+    rows += tb.num_rows;
+    if (rows > 0xFFFFFFFEll) return fail(HCTR_E_UNSUPPORTED, "the group's tables have more than 2^32-2 rows");
+  }
+  P->total_rows = rows;
+  P->L = (uint32_t)d->num_lookups;
+  P->dmax = 0;
+  uint32_t col = 0, hot = 0;
+  for (int l = 0; l < d->num_lookups; ++l) {
+    const hctr_group_lookup& lu = d->lookups[l];
+    if (lu.table < 0 || lu.table >= d->num_tables)
+      return fail(HCTR_E_INVALID_ARG, "lookup %d: table %d outside 0..%d", l, lu.table, d->num_tables - 1);
+    if (lu.combiner != HCTR_SUM && lu.combiner != HCTR_MEAN)
+      return fail(HCTR_E_INVALID_ARG, "lookup %d: combiner %d unknown", l, lu.combiner);
+    const hctr_group_table& tb = d->tables[lu.table];
+    P->lk[l].table = tb.data;
+    P->lk[l].row_base = P->row_base[lu.table];
+    P->lk[l].col = col;
+    P->lk[l].dim = (uint32_t)tb.dim;
+    P->lk[l].mean = lu.combiner == HCTR_MEAN ? 1u : 0u;
+    P->num_rows[l] = (uint32_t)tb.num_rows;
+    P->hot.before[l] = hot;
+    col += (uint32_t)tb.dim;
+    hot += lu.hotness > 0 ? (uint32_t)lu.hotness : 0u;
+    if (tb.dim > P->dmax) P->dmax = tb.dim;
+  }
+  P->width_total = col;
+  P->per_sample = hot;
+  P->hot.L = P->L;
+  P->hot.per_sample = hot;
+  return HCTR_OK;
+}
+
+static EmbLayout group_layout(const GroupPlan& P, int64_t batch, int64_t nnz_max) {
+  return emb_layout_raw(P.total_rows, P.dmax, nnz_max, false, (size_t)(batch * P.L + 1) * 8);
+}
+
+// Argument checks shared by forward and backward; *csr gets the offsets to use (the caller's, or
+// the ones written into the workspace for dense input).
+static hctr_status group_prepare(const hctr_group_desc* d, int64_t batch, const int64_t* keys,
+                                 const int64_t* offsets, int64_t nnz, const void* io, void* ws, size_t ws_bytes,
+                                 GroupPlan* P, EmbLayout* L, const int64_t** csr, hipStream_t stream) {
+  HCTR_TRY(group_plan(d, P));
+  if (batch < 0 || nnz < 0)
+    return fail(HCTR_E_INVALID_ARG, "batch %lld / nnz %lld negative", (long long)batch, (long long)nnz);
+  const int64_t n_bags = batch * P->L;
+  if (n_bags >= (1ll << 31) || nnz >= (1ll << 31))
+    return fail(HCTR_E_UNSUPPORTED, "more than 2^31-1 bags or keys in one call");
+  if (!offsets) {
+    for (int l = 0; l < d->num_lookups; ++l)
+      if (d->lookups[l].hotness < 1)
+        return fail(HCTR_E_INVALID_ARG, "dense input (offsets == NULL): lookup %d has hotness %d < 1", l,
+                    d->lookups[l].hotness);
+    if (nnz != batch * (int64_t)P->per_sample)
+      return fail(HCTR_E_INVALID_ARG, "dense input needs nnz == batch * sum of hotness (%lld != %lld)",
+                  (long long)nnz, (long long)(batch * (int64_t)P->per_sample));
+  }
+  if (batch == 0 && nnz != 0) return fail(HCTR_E_INVALID_ARG, "nnz must be 0 when batch is 0");
+  if (nnz > 0 && !keys) return fail(HCTR_E_NULL_PTR, "keys is NULL");
+  if (n_bags > 0 && !io) return fail(HCTR_E_NULL_PTR, "out / dY is NULL");
+  if (io && (uintptr_t)io % 16 != 0) return fail(HCTR_E_INVALID_ARG, "out / dY must be 16-byte aligned");
+  *L = group_layout(*P, batch, nnz);
+  if (!ws) return fail(HCTR_E_WORKSPACE, "workspace is NULL");
+  if ((uintptr_t)ws % 256 != 0) return fail(HCTR_E_WORKSPACE, "workspace must be 256-byte aligned");
+  if (ws_bytes < L->total)
+    return fail(HCTR_E_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, L->total);
+  *csr = offsets;
+  if (!offsets && n_bags > 0) {
+    int64_t* gen = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + L->extra);
+    hipLaunchKernelGGL(group_dense_offsets, dim3((uint32_t)ceil_div(n_bags + 1, 256)), dim3(256), 0, stream, P->hot,
+                       (uint64_t)n_bags, gen);
+    *csr = gen;
+  }
+  return HCTR_OK;
+}
+
+template <typename T>
+static void group_launch_forward(const GroupPlan& P, int64_t batch, const int64_t* keys, const int64_t* csr,
+                                 float* out, EmbHeader* hdr, hipStream_t stream) {
+  GroupFwdArgs a;
+  a.L = P.L;
+  a.width_total = P.width_total;
+  for (int l = 0; l < HCTR_MAX_GROUP_LOOKUPS; ++l) {
+    a.lk[l] = l < (int)P.L ? P.lk[l] : GroupLookup{nullptr, 0, 0, 0, 0};
+    a.num_rows[l] = l < (int)P.L ? P.num_rows[l] : 0;
+  }
+  const uint64_t n_quads = (uint64_t)batch * (P.width_total / 4);
+  uint64_t blocks = ceil_div((int64_t)n_quads, 256);
+  if (blocks > (1u << 20)) blocks = 1u << 20;   // grid-stride beyond a million blocks
+  hipLaunchKernelGGL((fwd_group<T>), dim3((uint32_t)blocks), dim3(256), 0, stream, a, keys, csr, n_quads, out, hdr);
+}
+
+template <typename T>
+static void group_launch_reduce(const GroupPlan& P, const EmbLayout& L, char* w, const uint64_t* skv,
+                                const int64_t* csr, const float* dY, float lr, hipStream_t stream) {
+  GroupView<T> view;
+  view.dY = dY;
+  view.L = P.L;
+  view.width_total = P.width_total;
+  view.dmax_ = P.dmax;
+  for (int l = 0; l < HCTR_MAX_GROUP_LOOKUPS; ++l)
+    view.lk[l] = l < (int)P.L ? P.lk[l] : GroupLookup{nullptr, 0, 0, 0, 0};
+  dispatch_reduce_view<T>(view, P.dmax, L, w, skv, csr, lr, stream);
+}
+
+}  // namespace hctr
+
+HCTR_API size_t hctr_group_workspace_bytes(const hctr_group_desc* desc, int64_t batch, int64_t nnz_max) {
+  GroupPlan P;
+  if (batch < 0 || nnz_max < 0 || nnz_max >= (1ll << 31) || group_plan(desc, &P) != HCTR_OK) return 0;
+  if (batch * P.L >= (1ll << 31)) return 0;
+  return group_layout(P, batch, nnz_max).total;
+}
+
+HCTR_API hctr_status hctr_group_forward(const hctr_group_desc* desc, int64_t batch, const int64_t* keys,
+                                        const int64_t* offsets, int64_t nnz, float* out, void* ws,
+                                        size_t ws_bytes, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  GroupPlan P;
+  EmbLayout L;
+  const int64_t* csr = nullptr;
+  HCTR_TRY(group_prepare(desc, batch, keys, offsets, nnz, out, ws, ws_bytes, &P, &L, &csr, stream));
+  if (batch == 0) return HCTR_OK;
+  EmbHeader* hdr = reinterpret_cast<EmbHeader*>(static_cast<char*>(ws) + L.header);
+  if (desc->table_dtype == HCTR_F32) group_launch_forward<float>(P, batch, keys, csr, out, hdr, stream);
+  else group_launch_forward<__half>(P, batch, keys, csr, out, hdr, stream);
+  return launch_status("hctr_group_forward");
+}
+
+HCTR_API hctr_status hctr_group_backward_sgd(const hctr_group_desc* desc, int64_t batch, const int64_t* keys,
+                                             const int64_t* offsets, int64_t nnz, const float* dY, float lr,
+                                             void* ws, size_t ws_bytes, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  GroupPlan P;
+  EmbLayout L;
+  const int64_t* csr = nullptr;
+  HCTR_TRY(group_prepare(desc, batch, keys, offsets, nnz, dY, ws, ws_bytes, &P, &L, &csr, stream));
+  char* w = static_cast<char*>(ws);
+  SlotTable st;   // the key -> row kernel sees the lookups as slots whose ranges are their tables' rows
+  for (int s = 0; s < HCTR_MAX_SLOTS; ++s) {
+    st.base[s] = s < (int)P.L ? (int64_t)P.lk[s].row_base : 0;
+    st.num[s] = s < (int)P.L ? (int64_t)P.num_rows[s] : 0;
+  }
+  HCTR_TRY(dedup_core(keys, nullptr, csr, nnz, (uint32_t)(batch * P.L), P.L, st, P.total_rows, L, w, stream));
+  if (nnz == 0) return HCTR_OK;
+  const uint64_t* skv = reinterpret_cast<const uint64_t*>(w + ((L.sort.passes & 1) ? L.kv1 : L.kv0));
+  if (desc->table_dtype == HCTR_F32) group_launch_reduce<float>(P, L, w, skv, csr, dY, lr, stream);
+  else group_launch_reduce<__half>(P, L, w, skv, csr, dY, lr, stream);
+  return launch_status("hctr_group_backward_sgd");
 }

@@ -7,7 +7,7 @@ import re
 import pytest
 
 import paper_2210_08803_amd as H
-from paper_2210_08803_amd.binding import EXPORTS, _EmbDesc
+from paper_2210_08803_amd.binding import EXPORTS, _EmbDesc, _GroupDesc, _GroupLookup, _GroupTable
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -69,6 +69,47 @@ def test_forward_argument_errors_are_caught_on_the_host():
     need = L.hctr_emb_workspace_bytes(C.byref(d), 1, 2)
     assert need > 0 and need % 256 == 0
     assert L.hctr_emb_workspace_bytes(C.byref(d), 1, 1 << 20) > need
+
+
+def _group(tables=((4096, 10, 8), (8192, 5, 16)), lookups=((0, 0, 1), (1, 1, 2), (0, 1, 1)), dtype=0):
+    t = (_GroupTable * len(tables))()
+    for i, (ptr, rows, dim) in enumerate(tables):
+        t[i].data, t[i].num_rows, t[i].dim = ptr, rows, dim
+    l = (_GroupLookup * len(lookups))()
+    for i, (tb, comb, hot) in enumerate(lookups):
+        l[i].table, l[i].combiner, l[i].hotness = tb, comb, hot
+    d = _GroupDesc(num_tables=len(tables), num_lookups=len(lookups), table_dtype=dtype, tables=t, lookups=l)
+    d._keep = (t, l)
+    return d
+
+
+def test_group_argument_errors_are_caught_on_the_host():
+    L = H.lib()
+
+    def fwd(d, batch=2, keys=4096, offsets=None, nnz=8, out=4096, ws=4096, ws_bytes=1 << 30):
+        return L.hctr_group_forward(C.byref(d), batch, keys, offsets, nnz, out, ws, ws_bytes, None)
+
+    assert L.hctr_group_forward(None, 1, 4096, None, 4, 4096, 4096, 1 << 30, None) == -2
+    assert fwd(_group(tables=((4096, 10, 6),), lookups=((0, 0, 1),)), nnz=2) == -1       # width not a multiple of 4
+    assert fwd(_group(tables=((4096, 10, 12),), lookups=((0, 0, 1),), dtype=1), nnz=2) == -1   # fp16: multiple of 8
+    assert fwd(_group(tables=((None, 10, 8),), lookups=((0, 0, 1),)), nnz=2) == -2
+    assert fwd(_group(tables=((4100, 10, 8),), lookups=((0, 0, 1),)), nnz=2) == -1       # misaligned table
+    assert fwd(_group(tables=((4096, 0, 8),), lookups=((0, 0, 1),)), nnz=2) == -1
+    assert fwd(_group(lookups=((2, 0, 1),)), nnz=2) == -1                                # table index out of range
+    assert fwd(_group(lookups=((0, 5, 1),)), nnz=2) == -1                                # unknown combiner
+    assert fwd(_group(lookups=((0, 0, 0),)), nnz=0) == -1                                # dense input needs hotness >= 1
+    assert fwd(_group(), nnz=7) == -1                                                    # dense: nnz = batch * sum(hotness)
+    assert fwd(_group(tables=((4096, 1 << 32, 8),), lookups=((0, 0, 1),)), nnz=2) == -4  # too many rows for the dedup
+    assert fwd(_group(), keys=None) == -2
+    assert fwd(_group(), out=None) == -2
+    assert fwd(_group(), ws=None) == -3
+    assert fwd(_group(), ws_bytes=64) == -3
+    d = _group()
+    assert L.hctr_group_backward_sgd(C.byref(d), 2, 4096, None, 8, None, 0.1, 4096, 1 << 30, None) == -2
+    need = L.hctr_group_workspace_bytes(C.byref(d), 2, 8)
+    assert need > 0 and need % 256 == 0
+    assert L.hctr_group_workspace_bytes(C.byref(d), 1000, 8) > need       # room for the dense input's offsets
+    assert L.hctr_group_workspace_bytes(None, 2, 8) == 0
 
 
 def test_hash_and_cache_argument_errors():
