@@ -4,6 +4,7 @@
     python bench_workloads.py multihot   # 26 fp16 tables, batch 65,536, hotness 1..100, mean: fwd / dedup / apply
     python bench_workloads.py hashed     # open 2^63 key space, capacity 1e8, dim 64: insert-or-find, fwd, bwd over load factor
     python bench_workloads.py cache      # inference cache, Zipf 1.2, batch 1 / 64 / 1024 / 16384: hit rate, keys/s, p50 latency
+    python bench_workloads.py group      # fused group: the 26 DLRM-sized tables with widths 128/64/32/16, dense one-hot input
 
 Each prints one JSON line.  Inputs are synthetic and seeded (datagen/), resident in HBM (the cache's
 backing table in pinned host memory) before anything is timed.  The inference-cache configuration
@@ -148,9 +149,47 @@ def cache(h, args):
                          "26 slots x hotness 4, Zipf 1.2; latency = host call + stream sync", sweep=sweep)
 
 
+def group(h, args):
+    rows_t = datagen.DLRM_TABLE_ROWS
+    B, L = 55296, len(rows_t)
+    dims = [(128, 64, 32, 16)[t % 4] for t in range(L)]
+    tables = []
+    for t in range(L):
+        tab = torch.empty((int(rows_t[t]), dims[t]), dtype=torch.float32, device=DEV)
+        datagen.fill_table(SEED + t, tab, 1 << 21)
+        tables.append(tab)
+    smp = datagen.make_samplers(rows_t, 1.05, device=DEV)
+    keys = [datagen.onehot_keys(SEED, b, rows_t, B, 1.05, device=DEV, samplers=smp) for b in range(4)]
+    del smp
+    g = h.EmbeddingGroup(tables, [(t, h.SUM, 1) for t in range(L)])
+    nnz = B * L
+    ws = g.new_workspace(g.workspace_bytes(B, nnz))
+    out = torch.empty((B, g.width), device=DEV)
+    dY = datagen.normal_grads(SEED, 3, B * g.width, device=DEV).view(B, g.width)
+    it = [0]
+
+    def fwd():
+        g.forward(B, keys[it[0] % 4], out=out, ws=ws)
+        it[0] += 1
+
+    def bwd():
+        g.backward_sgd(B, keys[it[0] % 4], dY, 0.01, ws=ws)
+        it[0] += 1
+
+    f = timeit(fwd, 20, 4)
+    b = timeit(bwd, 20, 4)
+    row_bytes = sum(4 * d for d in dims)                       # one sample: every lookup's row once
+    fwd_bytes = B * (L * 8 + row_bytes + g.width * 4)          # keys + rows read + output written
+    bwd_bytes = B * (L * (8 + 8) + g.width * 4)                # keys + generated offsets + dY read; row updates come on top
+    return dict(workload="fused group: 26 fp32 tables of the DLRM sizes with widths 128/64/32/16 (cycling), one lookup "
+                         "per table, sum, dense one-hot input, batch 55296, Zipf 1.05", keys=nnz, width=g.width,
+                forward_ms=f, forward_algorithmic_GBs=fwd_bytes / f / 1e6, backward_ms=b,
+                backward_read_GBs=bwd_bytes / b / 1e6, fwd_bwd_keys_per_s=nnz / ((f + b) * 1e-3))
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("workload", choices=["multihot", "hashed", "cache"])
+    ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group"])
     ap.add_argument("--host-rows", type=int, default=20_000_000)
     ap.add_argument("--hash-batches", type=int, default=41)
     args = ap.parse_args()
@@ -158,7 +197,7 @@ def main():
         print("bench_workloads.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(2)
     import paper_2210_08803_amd as h
-    res = {"multihot": multihot, "hashed": hashed, "cache": cache}[args.workload](h, args)
+    res = {"multihot": multihot, "hashed": hashed, "cache": cache, "group": group}[args.workload](h, args)
     res["n_gpus"] = 1
     res["data"] = "synthetic"
     print(json.dumps(res), flush=True)

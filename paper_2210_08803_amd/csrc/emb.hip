@@ -711,57 +711,94 @@ __global__ __launch_bounds__(1024) void bwd_carry_long(
 struct GroupFwdArgs {
   uint32_t L;
   uint32_t width_total;
+  uint32_t per_sample;                          // dense input: keys per sample; 0 = CSR offsets are given
   GroupLookup lk[HCTR_MAX_GROUP_LOOKUPS];
-  uint32_t num_rows[HCTR_MAX_GROUP_LOOKUPS];   // rows of the lookup's table
+  uint32_t num_rows[HCTR_MAX_GROUP_LOOKUPS];    // rows of the lookup's table
+  uint32_t before[HCTR_MAX_GROUP_LOOKUPS];      // dense input: keys of a sample before lookup l
+  uint32_t hot[HCTR_MAX_GROUP_LOOKUPS];         // dense input: keys of lookup l per sample
 };
 
-template <typename T>
+// A thread works on NQ quads at a time (the same columns of NQ samples a grid stride apart) and
+// keeps one key and one row load per quad in flight; with dense input the bag bounds are computed,
+// not loaded, so a one-hot lookup costs two dependent loads (key, row), NQ-fold overlapped.
+template <typename T, int NQ>
 __global__ __launch_bounds__(256) void fwd_group(const GroupFwdArgs a, const int64_t* __restrict__ keys,
                                                  const int64_t* __restrict__ offsets, uint64_t n_quads,
                                                  float* __restrict__ out, EmbHeader* hdr) {
   __shared__ GroupLookup lk[HCTR_MAX_GROUP_LOOKUPS];
-  __shared__ uint32_t nrows[HCTR_MAX_GROUP_LOOKUPS];
+  __shared__ uint32_t nrows[HCTR_MAX_GROUP_LOOKUPS], before[HCTR_MAX_GROUP_LOOKUPS], hot[HCTR_MAX_GROUP_LOOKUPS];
   if (threadIdx.x < a.L) {
     lk[threadIdx.x] = a.lk[threadIdx.x];
     nrows[threadIdx.x] = a.num_rows[threadIdx.x];
+    before[threadIdx.x] = a.before[threadIdx.x];
+    hot[threadIdx.x] = a.hot[threadIdx.x];
   }
   __syncthreads();
   const uint32_t W4 = a.width_total / 4;
+  const uint64_t n_threads = (uint64_t)gridDim.x * 256u;
+  const bool dense = a.per_sample != 0;
   uint32_t nbad = 0;   // counted by the lane that owns a lookup's first quad
-  for (uint64_t q = (uint64_t)blockIdx.x * 256u + threadIdx.x; q < n_quads; q += (uint64_t)gridDim.x * 256u) {
-    const uint32_t b = (uint32_t)(q / W4);
-    const uint32_t c = (uint32_t)(q % W4) * 4u;
-    int lo = 0, hi = (int)a.L - 1;   // the lookup that owns column c: the last one starting at or before it
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if (lk[mid].col <= c) lo = mid; else hi = mid - 1;
-    }
-    const GroupLookup k = lk[lo];
-    const uint32_t cl = c - k.col;
-    const int64_t nr = nrows[lo];
-    const T* __restrict__ tbl = static_cast<const T*>(k.table);
-    const uint64_t bag = (uint64_t)b * a.L + (uint32_t)lo;
-    const int64_t k0 = offsets[bag], k1 = offsets[bag + 1];
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t p = k0; p < k1; p += 4) {
-      int64_t key[4];
+  for (uint64_t q0 = (uint64_t)blockIdx.x * 256u + threadIdx.x; q0 < n_quads; q0 += n_threads * NQ) {
+    const T* tbl[NQ];
+    uint32_t cl[NQ], dim[NQ], mean[NQ];
+    int64_t nr[NQ], k0[NQ], k1[NQ];
+    uint64_t dst[NQ];
+    int64_t longest = 0;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) key[u] = p + u < k1 ? keys[p + u] : (int64_t)-1;
-      f32x4 v[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const bool ok = key[u] >= 0 && key[u] < nr;
-        v[u] = ok ? load_row4(tbl + key[u] * k.dim + cl) : f32x4{0.f, 0.f, 0.f, 0.f};
-        nbad += (cl == 0 && p + u < k1 && !ok) ? 1u : 0u;
+    for (int u = 0; u < NQ; ++u) {
+      const uint64_t q = q0 + (uint64_t)u * n_threads;
+      const bool live = q < n_quads;
+      const uint64_t qq = live ? q : q0;
+      const uint32_t b = (uint32_t)(qq / W4);
+      const uint32_t c = (uint32_t)(qq % W4) * 4u;
+      int lo = 0, hi = (int)a.L - 1;   // the lookup that owns column c: the last one starting at or before it
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (lk[mid].col <= c) lo = mid; else hi = mid - 1;
       }
+      const GroupLookup k = lk[lo];
+      tbl[u] = static_cast<const T*>(k.table);
+      cl[u] = c - k.col;
+      dim[u] = k.dim;
+      mean[u] = k.mean;
+      nr[u] = nrows[lo];
+      dst[u] = (uint64_t)b * a.width_total + c;
+      if (dense) {
+        k0[u] = (int64_t)b * a.per_sample + before[lo];
+        k1[u] = k0[u] + hot[lo];
+      } else {
+        const uint64_t bag = (uint64_t)b * a.L + (uint32_t)lo;
+        k0[u] = offsets[bag];
+        k1[u] = offsets[bag + 1];
+      }
+      if (!live) k1[u] = k0[u];   // nothing to read, nothing to write
+      if (k1[u] - k0[u] > longest) longest = k1[u] - k0[u];
+    }
+    f32x4 acc[NQ];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+    for (int u = 0; u < NQ; ++u) acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int64_t j = 0; j < longest; ++j) {
+      int64_t key[NQ];
+#pragma unroll
+      for (int u = 0; u < NQ; ++u) key[u] = k0[u] + j < k1[u] ? keys[k0[u] + j] : (int64_t)-1;
+#pragma unroll
+      for (int u = 0; u < NQ; ++u) {
+        const bool ok = key[u] >= 0 && key[u] < nr[u];
+        const f32x4 v = ok ? load_row4(tbl[u] + key[u] * dim[u] + cl[u]) : f32x4{0.f, 0.f, 0.f, 0.f};
+        nbad += (cl[u] == 0 && k0[u] + j < k1[u] && !ok) ? 1u : 0u;
+        acc[u].x += v.x; acc[u].y += v.y; acc[u].z += v.z; acc[u].w += v.w;
+      }
     }
-    if (k.mean && k1 > k0) {
-      const float w = 1.0f / (float)(k1 - k0);
-      acc.x *= w; acc.y *= w; acc.z *= w; acc.w *= w;
+#pragma unroll
+    for (int u = 0; u < NQ; ++u) {
+      if (q0 + (uint64_t)u * n_threads < n_quads) {
+        if (mean[u] && k1[u] > k0[u]) {
+          const float w = 1.0f / (float)(k1[u] - k0[u]);
+          acc[u].x *= w; acc[u].y *= w; acc[u].z *= w; acc[u].w *= w;
+        }
+        __builtin_nontemporal_store(acc[u], reinterpret_cast<f32x4*>(out + dst[u]));
+      }
     }
-    __builtin_nontemporal_store(acc, reinterpret_cast<f32x4*>(out + (uint64_t)b * a.width_total + c));
   }
   if (__ballot(nbad != 0) != 0) {   // every lane of the wave is here: the loop above has no early exit
 #pragma unroll
@@ -1186,6 +1223,7 @@ struct GroupPlan {
   uint32_t row_base[HCTR_MAX_GROUP_LOOKUPS];   // per table
   GroupLookup lk[HCTR_MAX_GROUP_LOOKUPS];      // per lookup
   uint32_t num_rows[HCTR_MAX_GROUP_LOOKUPS];   // per lookup
+  uint32_t hot_of[HCTR_MAX_GROUP_LOOKUPS];     // per lookup: declared hotness (dense input)
   GroupHotness hot;
 };
 
@@ -1229,6 +1267,7 @@ static hctr_status group_plan(const hctr_group_desc* d, GroupPlan* P) {
     P->lk[l].mean = lu.combiner == HCTR_MEAN ? 1u : 0u;
     P->num_rows[l] = (uint32_t)tb.num_rows;
     P->hot.before[l] = hot;
+    P->hot_of[l] = lu.hotness > 0 ? (uint32_t)lu.hotness : 0u;
     col += (uint32_t)tb.dim;
     hot += lu.hotness > 0 ? (uint32_t)lu.hotness : 0u;
     if (tb.dim > P->dmax) P->dmax = tb.dim;
@@ -1248,7 +1287,8 @@ static EmbLayout group_layout(const GroupPlan& P, int64_t batch, int64_t nnz_max
 // the ones written into the workspace for dense input).
 static hctr_status group_prepare(const hctr_group_desc* d, int64_t batch, const int64_t* keys,
                                  const int64_t* offsets, int64_t nnz, const void* io, void* ws, size_t ws_bytes,
-                                 GroupPlan* P, EmbLayout* L, const int64_t** csr, hipStream_t stream) {
+                                 GroupPlan* P, EmbLayout* L, const int64_t** csr, bool need_csr,
+                                 hipStream_t stream) {
   HCTR_TRY(group_plan(d, P));
   if (batch < 0 || nnz < 0)
     return fail(HCTR_E_INVALID_ARG, "batch %lld / nnz %lld negative", (long long)batch, (long long)nnz);
@@ -1274,7 +1314,7 @@ static hctr_status group_prepare(const hctr_group_desc* d, int64_t batch, const 
   if (ws_bytes < L->total)
     return fail(HCTR_E_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, L->total);
   *csr = offsets;
-  if (!offsets && n_bags > 0) {
+  if (!offsets && n_bags > 0 && need_csr) {
     int64_t* gen = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + L->extra);
     hipLaunchKernelGGL(group_dense_offsets, dim3((uint32_t)ceil_div(n_bags + 1, 256)), dim3(256), 0, stream, P->hot,
                        (uint64_t)n_bags, gen);
@@ -1284,19 +1324,25 @@ static hctr_status group_prepare(const hctr_group_desc* d, int64_t batch, const 
 }
 
 template <typename T>
-static void group_launch_forward(const GroupPlan& P, int64_t batch, const int64_t* keys, const int64_t* csr,
-                                 float* out, EmbHeader* hdr, hipStream_t stream) {
+static void group_launch_forward(const GroupPlan& P, bool dense, int64_t batch, const int64_t* keys,
+                                 const int64_t* csr, float* out, EmbHeader* hdr, hipStream_t stream) {
   GroupFwdArgs a;
   a.L = P.L;
   a.width_total = P.width_total;
+  a.per_sample = dense ? P.per_sample : 0;
   for (int l = 0; l < HCTR_MAX_GROUP_LOOKUPS; ++l) {
-    a.lk[l] = l < (int)P.L ? P.lk[l] : GroupLookup{nullptr, 0, 0, 0, 0};
-    a.num_rows[l] = l < (int)P.L ? P.num_rows[l] : 0;
+    const bool used = l < (int)P.L;
+    a.lk[l] = used ? P.lk[l] : GroupLookup{nullptr, 0, 0, 0, 0};
+    a.num_rows[l] = used ? P.num_rows[l] : 0;
+    a.before[l] = used ? P.hot.before[l] : 0;
+    a.hot[l] = used ? P.hot_of[l] : 0;
   }
+  constexpr int NQ = 4;
   const uint64_t n_quads = (uint64_t)batch * (P.width_total / 4);
-  uint64_t blocks = ceil_div((int64_t)n_quads, 256);
+  uint64_t blocks = ceil_div((int64_t)n_quads, 256 * NQ);
   if (blocks > (1u << 20)) blocks = 1u << 20;   // grid-stride beyond a million blocks
-  hipLaunchKernelGGL((fwd_group<T>), dim3((uint32_t)blocks), dim3(256), 0, stream, a, keys, csr, n_quads, out, hdr);
+  hipLaunchKernelGGL((fwd_group<T, NQ>), dim3((uint32_t)blocks), dim3(256), 0, stream, a, keys, csr, n_quads, out,
+                     hdr);
 }
 
 template <typename T>
@@ -1328,11 +1374,12 @@ HCTR_API hctr_status hctr_group_forward(const hctr_group_desc* desc, int64_t bat
   GroupPlan P;
   EmbLayout L;
   const int64_t* csr = nullptr;
-  HCTR_TRY(group_prepare(desc, batch, keys, offsets, nnz, out, ws, ws_bytes, &P, &L, &csr, stream));
+  HCTR_TRY(group_prepare(desc, batch, keys, offsets, nnz, out, ws, ws_bytes, &P, &L, &csr, false, stream));
   if (batch == 0) return HCTR_OK;
   EmbHeader* hdr = reinterpret_cast<EmbHeader*>(static_cast<char*>(ws) + L.header);
-  if (desc->table_dtype == HCTR_F32) group_launch_forward<float>(P, batch, keys, csr, out, hdr, stream);
-  else group_launch_forward<__half>(P, batch, keys, csr, out, hdr, stream);
+  const bool dense = offsets == nullptr;   // bag bounds follow from the declared hotness
+  if (desc->table_dtype == HCTR_F32) group_launch_forward<float>(P, dense, batch, keys, csr, out, hdr, stream);
+  else group_launch_forward<__half>(P, dense, batch, keys, csr, out, hdr, stream);
   return launch_status("hctr_group_forward");
 }
 
@@ -1343,7 +1390,7 @@ HCTR_API hctr_status hctr_group_backward_sgd(const hctr_group_desc* desc, int64_
   GroupPlan P;
   EmbLayout L;
   const int64_t* csr = nullptr;
-  HCTR_TRY(group_prepare(desc, batch, keys, offsets, nnz, dY, ws, ws_bytes, &P, &L, &csr, stream));
+  HCTR_TRY(group_prepare(desc, batch, keys, offsets, nnz, dY, ws, ws_bytes, &P, &L, &csr, true, stream));
   char* w = static_cast<char*>(ws);
   SlotTable st;   // the key -> row kernel sees the lookups as slots whose ranges are their tables' rows
   for (int s = 0; s < HCTR_MAX_SLOTS; ++s) {
