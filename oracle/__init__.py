@@ -44,6 +44,10 @@ def lib() -> C.CDLL:
         L.oracle_emb_forward.argtypes = [i32, i32, i32, p, i64, p, p, i64, p]
         L.oracle_emb_backward_sgd.restype = i64
         L.oracle_emb_backward_sgd.argtypes = [i32, i32, i32, p, i64, p, p, i64, p, f32, p, p]
+        L.oracle_emb_forward_mixed.restype = None
+        L.oracle_emb_forward_mixed.argtypes = [i32, i32, i32, p, i64, p, p, i64, i32, p]
+        L.oracle_emb_backward_sgd_mixed.restype = i64
+        L.oracle_emb_backward_sgd_mixed.argtypes = [i32, i32, i32, p, p, i64, p, p, i64, i32, p, f32]
         L.oracle_group_forward.restype = None
         L.oracle_group_forward.argtypes = [i32, p, p, p, i32, i32, p, p, i64, p, p, p]
         L.oracle_group_backward_sgd.restype = i64
@@ -142,6 +146,42 @@ def emb_backward_sgd(table: np.ndarray, rows, dY: np.ndarray, lr: float, offsets
                                       table.shape[0], _ptr(rows), _ptr(offsets), n_bags, _ptr(dY),
                                       float(np.float32(lr)), _ptr(uniq), _ptr(cnt))
     return uniq[:u].copy(), cnt[:u].copy()
+
+
+def emb_forward_mixed(table: np.ndarray, rows, offsets=None, combiner: int = SUM, n_bags: Optional[int] = None,
+                      out_dtype=np.float16) -> np.ndarray:
+    """Pooled output [n_bags, D] in out_dtype (float16: one rounding from the double sum)."""
+    assert table.ndim == 2 and table.flags.c_contiguous
+    rows = _i64(rows)
+    if offsets is not None:
+        offsets = _i64(offsets)
+        n_bags = len(offsets) - 1
+    elif n_bags is None:
+        n_bags = len(rows)
+    out = np.empty((n_bags, table.shape[1]), dtype=out_dtype)
+    lib().oracle_emb_forward_mixed(table.shape[1], _dtype_code(table), combiner, _ptr(table), table.shape[0],
+                                   _ptr(rows), _ptr(offsets), n_bags, _dtype_code(out), _ptr(out))
+    return out
+
+
+def emb_backward_sgd_mixed(table: np.ndarray, rows, dY: np.ndarray, lr: float, offsets=None, combiner: int = SUM,
+                           n_bags: Optional[int] = None, master: Optional[np.ndarray] = None) -> int:
+    """Backward + SGD with dY in its own dtype (float16 or float32) and an optional fp32 master copy
+    of an fp16 table; updates table (and master) in place, returns the number of distinct rows."""
+    assert table.ndim == 2 and table.flags.c_contiguous and table.flags.writeable
+    rows = _i64(rows)
+    if offsets is not None:
+        offsets = _i64(offsets)
+        n_bags = len(offsets) - 1
+    elif n_bags is None:
+        n_bags = len(rows)
+    dY = np.ascontiguousarray(dY).reshape(n_bags, table.shape[1])
+    if master is not None:
+        assert master.dtype == np.float32 and master.shape == table.shape and master.flags.c_contiguous
+        assert table.dtype == np.float16
+    return int(lib().oracle_emb_backward_sgd_mixed(table.shape[1], _dtype_code(table), combiner, _ptr(table),
+                                                   _ptr(master), table.shape[0], _ptr(rows), _ptr(offsets), n_bags,
+                                                   _dtype_code(dY), _ptr(dY), float(np.float32(lr))))
 
 
 def _group_args(tables, lookup_table, lookup_comb):

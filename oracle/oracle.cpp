@@ -162,6 +162,64 @@ int64_t oracle_emb_backward_sgd(int32_t dim, int32_t dtype, int32_t combiner, vo
 }
 
 // ---------------------------------------------------------------------------------------------
+// Mixed precision (section 1, "Mixed precision training": parameters kept in FP16, the layers
+// downstream computing in reduced precision).  Same definitions as above with
+//   * io_dtype = FP16: the pooled output is rounded once, from the double sum, to binary16; the
+//     upstream gradient arrives as binary16 and is widened exactly;
+//   * master != NULL (FP16 table only): master is an fp32 copy [total_rows, dim] of the
+//     parameters.  The update is applied to the master row, m <- m - lr * g rounded once to fp32,
+//     and the table row becomes that fp32 value rounded to binary16, so the FP16 table never
+//     accumulates its own rounding errors.
+// ---------------------------------------------------------------------------------------------
+void oracle_emb_forward_mixed(int32_t dim, int32_t dtype, int32_t combiner, const void* table,
+                              int64_t total_rows, const int64_t* rows, const int64_t* offsets,
+                              int64_t n_bags, int32_t io_dtype, void* out) {
+  std::vector<double> acc(dim);
+  for (int64_t bag = 0; bag < n_bags; ++bag) {
+    std::fill(acc.begin(), acc.end(), 0.0);
+    int64_t b0 = bag_begin(offsets, bag), b1 = bag_end(offsets, bag);
+    for (int64_t i = b0; i < b1; ++i) {
+      int64_t r = rows[i];
+      if (r < 0 || r >= total_rows) continue;
+      for (int d = 0; d < dim; ++d) acc[d] += load_elem(table, dtype, r * dim + d);
+    }
+    double w = (combiner == COMB_MEAN && b1 > b0) ? 1.0 / (double)(b1 - b0) : 1.0;
+    for (int d = 0; d < dim; ++d) store_elem(out, io_dtype, bag * dim + d, acc[d] * w);
+  }
+}
+
+int64_t oracle_emb_backward_sgd_mixed(int32_t dim, int32_t dtype, int32_t combiner, void* table,
+                                      float* master, int64_t total_rows, const int64_t* rows,
+                                      const int64_t* offsets, int64_t n_bags, int32_t io_dtype,
+                                      const void* dY, float lr) {
+  std::unordered_map<int64_t, std::vector<double>> grad;
+  for (int64_t bag = 0; bag < n_bags; ++bag) {
+    int64_t b0 = bag_begin(offsets, bag), b1 = bag_end(offsets, bag);
+    double w = (combiner == COMB_MEAN && b1 > b0) ? 1.0 / (double)(b1 - b0) : 1.0;
+    for (int64_t i = b0; i < b1; ++i) {
+      int64_t r = rows[i];
+      if (r < 0 || r >= total_rows) continue;
+      std::vector<double>& g = grad[r];
+      if (g.empty()) g.assign(dim, 0.0);
+      for (int d = 0; d < dim; ++d) g[d] += w * load_elem(dY, io_dtype, bag * dim + d);
+    }
+  }
+  for (auto& kv : grad) {
+    const int64_t r = kv.first;
+    for (int d = 0; d < dim; ++d) {
+      if (master) {
+        master[r * dim + d] = (float)((double)master[r * dim + d] - (double)lr * kv.second[d]);
+        store_elem(table, dtype, r * dim + d, (double)master[r * dim + d]);
+      } else {
+        double t = load_elem(table, dtype, r * dim + d);
+        store_elem(table, dtype, r * dim + d, t - (double)lr * kv.second[d]);
+      }
+    }
+  }
+  return (int64_t)grad.size();
+}
+
+// ---------------------------------------------------------------------------------------------
 // Fused group of lookups (section 4, "Future Work": one embedding fusing tables of different
 // vector size and combiner, fed by dense or sparse inputs).  T tables, each [table_rows[t],
 // table_dim[t]]; L lookups, lookup l reads table lookup_table[l] with combiner lookup_comb[l];
