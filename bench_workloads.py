@@ -4,6 +4,7 @@
     python bench_workloads.py multihot   # 26 fp16 tables, batch 65,536, hotness 1..100, mean: fwd / dedup / apply
     python bench_workloads.py hashed     # open 2^63 key space, capacity 1e8, dim 64: insert-or-find, fwd, bwd over load factor
     python bench_workloads.py cache      # inference cache, Zipf 1.2, batch 1 / 64 / 1024 / 16384: hit rate, keys/s, p50 latency
+    python bench_workloads.py mixed      # headline shape in mixed precision: fp16 table + fp32 master rows, fp16 out / dY
     python bench_workloads.py group      # fused group: the 26 DLRM-sized tables with widths 128/64/32/16, dense one-hot input
 
 Each prints one JSON line.  Inputs are synthetic and seeded (datagen/), resident in HBM (the cache's
@@ -149,6 +150,43 @@ def cache(h, args):
                          "26 slots x hotness 4, Zipf 1.2; latency = host call + stream sync", sweep=sweep)
 
 
+def mixed(h, args):
+    rows_t = datagen.DLRM_TABLE_ROWS
+    S, D, B = 26, 128, 55296
+    ro = datagen.row_offsets(rows_t)
+    base, total = ro[:-1].copy(), int(ro[-1])
+    master = torch.empty((total, D), dtype=torch.float32, device=DEV)
+    datagen.fill_table(SEED, master, 1 << 21)
+    table = torch.empty((total, D), dtype=torch.float16, device=DEV)
+    for r0 in range(0, total, 1 << 22):
+        table[r0:r0 + (1 << 22)].copy_(master[r0:r0 + (1 << 22)])
+    smp = datagen.make_samplers(rows_t, 1.05, device=DEV)
+    keys = [datagen.onehot_keys(SEED, b, rows_t, B, 1.05, device=DEV, samplers=smp) for b in range(4)]
+    del smp
+    nnz = B * S
+    dY = datagen.normal_grads(SEED, 5, nnz * D, device=DEV).view(B, S, D).to(torch.float16)
+    out = torch.empty((B, S, D), dtype=torch.float16, device=DEV)
+    res = {}
+    for name, m in (("fp16_table", None), ("fp16_table_fp32_master", master)):
+        layer = h.EmbeddingLayer(table, S, h.SUM, base, rows_t, io_dtype=torch.float16, master=m)
+        ws = layer.new_workspace(layer.workspace_bytes(B, nnz))
+        it = [0]
+
+        def fwd():
+            layer.forward(B, keys[it[0] % 4], out=out, ws=ws)
+            it[0] += 1
+
+        def bwd():
+            layer.backward_sgd(B, keys[it[0] % 4], dY, 0.01, ws=ws)
+            it[0] += 1
+
+        f, b = timeit(fwd, 20, 4), timeit(bwd, 20, 4)
+        res[name] = dict(forward_ms=f, forward_algorithmic_GBs=nnz * (8 + 2 * D + 2 * D) / f / 1e6, backward_ms=b,
+                         fwd_bwd_keys_per_s=nnz / ((f + b) * 1e-3))
+    return dict(workload="headline shape in mixed precision: 26 fp16 tables (165,158,233 x 128), fp16 out and dY, "
+                         "batch 55296, one-hot, Zipf 1.05, sum", keys=nnz, **res)
+
+
 def group(h, args):
     rows_t = datagen.DLRM_TABLE_ROWS
     B, L = 55296, len(rows_t)
@@ -189,7 +227,7 @@ def group(h, args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group"])
+    ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group", "mixed"])
     ap.add_argument("--host-rows", type=int, default=20_000_000)
     ap.add_argument("--hash-batches", type=int, default=41)
     args = ap.parse_args()
@@ -197,7 +235,7 @@ def main():
         print("bench_workloads.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(2)
     import paper_2210_08803_amd as h
-    res = {"multihot": multihot, "hashed": hashed, "cache": cache, "group": group}[args.workload](h, args)
+    res = {"multihot": multihot, "hashed": hashed, "cache": cache, "group": group, "mixed": mixed}[args.workload](h, args)
     res["n_gpus"] = 1
     res["data"] = "synthetic"
     print(json.dumps(res), flush=True)

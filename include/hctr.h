@@ -27,7 +27,8 @@
  *   Layout     Bags are numbered bag = sample * num_slots + slot.  Keys are int64, bag-major.
  *              CSR offsets are int64 [n_bags + 1], offsets[0] = 0, offsets[n_bags] = nnz,
  *              non-decreasing (not checked).  offsets == NULL means exactly one key per bag.
- *              Pooled outputs and upstream gradients are fp32 [batch, num_slots, dim] row-major.
+ *              Pooled outputs and upstream gradients are [batch, num_slots, dim] row-major, fp32
+ *              (or fp16 when the layer's io_dtype says so).
  *              Tables are [total_rows, dim] row-major in fp32 or fp16, 16-byte aligned.
  */
 #ifndef HCTR_H_
@@ -75,7 +76,7 @@ typedef struct hctr_cache hctr_cache; /* opaque */
 typedef struct {
   int32_t num_slots;            /* S, 1..HCTR_MAX_SLOTS */
   int32_t dim;                  /* D > 0, multiple of 4 (fp32 table) or 8 (fp16 table) */
-  int32_t table_dtype;          /* hctr_dtype of the table; out and dY are always fp32 */
+  int32_t table_dtype;          /* hctr_dtype of the table */
   int32_t combiner;             /* hctr_combiner */
   void* table;                  /* device [total_rows, dim] */
   int64_t total_rows;           /* 1 .. 2^32 - 2 */
@@ -83,6 +84,13 @@ typedef struct {
   const int64_t* slot_num_rows; /* host [S] (direct mode) */
   hctr_hash* hash;              /* NULL = direct mode */
   int32_t insert_on_miss;       /* hashed mode, forward only: 1 = insert absent keys */
+  int32_t io_dtype;             /* hctr_dtype of out and dY: HCTR_F32 (0), or HCTR_F16 for layers
+                                   downstream that compute in half precision (section 1, "Mixed
+                                   precision training"); sums are always formed in fp32 */
+  float* master;                /* device [total_rows, dim] fp32 copy of an fp16 table, or NULL.
+                                   With it backward updates the master row in fp32 and stores its
+                                   rounding (nearest even) as the table row; forward reads only
+                                   the fp16 table.  The caller keeps the two consistent at start. */
 } hctr_emb_desc;
 
 /* Bytes of workspace that forward and backward need for up to nnz_max keys (multiple of 256). */
@@ -100,12 +108,13 @@ hctr_status hctr_emb_workspace_init(void* ws, size_t ws_bytes, void* stream);
  * runs give the same bits.  (Section 1, "Localized slot embedding hash": lookup + intra-slot
  * reduction.)
  *   keys    device [nnz]           offsets device [batch*S + 1] or NULL (then nnz == batch*S)
- *   out     device [batch, S, dim] fp32, 16-byte aligned, fully overwritten
+ *   out     device [batch, S, dim] in desc->io_dtype (fp16: the fp32 sum rounded to nearest even),
+ *           16-byte aligned, fully overwritten
  *   ws      device, >= hctr_emb_workspace_bytes(desc, batch, nnz), 256-byte aligned
  * batch == 0 is accepted and does nothing.
  */
 hctr_status hctr_emb_forward(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
-                             const int64_t* offsets, int64_t nnz, float* out, void* ws,
+                             const int64_t* offsets, int64_t nnz, void* out, void* ws,
                              size_t ws_bytes, void* stream);
 
 /*
@@ -118,11 +127,13 @@ hctr_status hctr_emb_forward(const hctr_emb_desc* desc, int64_t batch, const int
  * with the row update.  In hashed mode keys are looked up only (never inserted); unknown keys are
  * skipped.  (Section 1, "Hybrid sparse embedding" names the backward pass; the paper gives no
  * optimizer, plain SGD is the benchmark's.)
- *   dY      device [batch, S, dim] fp32, 16-byte aligned
+ *   dY      device [batch, S, dim] in desc->io_dtype (fp16 is widened exactly), 16-byte aligned
+ * With desc->master the update goes to the fp32 master row and the fp16 table row becomes its
+ * rounding (see hctr_emb_desc).
  * The dedup result of the call stays in the workspace, see hctr_emb_dedup_view.
  */
 hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
-                                  const int64_t* offsets, int64_t nnz, const float* dY, float lr,
+                                  const int64_t* offsets, int64_t nnz, const void* dY, float lr,
                                   void* ws, size_t ws_bytes, void* stream);
 
 /*
@@ -138,7 +149,7 @@ hctr_status hctr_emb_backward_dedup(const hctr_emb_desc* desc, int64_t batch, co
                                     const int64_t* offsets, int64_t nnz, void* ws, size_t ws_bytes,
                                     void* stream);
 hctr_status hctr_emb_backward_apply(const hctr_emb_desc* desc, int64_t batch, const int64_t* offsets,
-                                    int64_t nnz, const float* dY, float lr, void* ws, size_t ws_bytes,
+                                    int64_t nnz, const void* dY, float lr, void* ws, size_t ws_bytes,
                                     void* stream);
 
 /*

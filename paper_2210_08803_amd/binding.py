@@ -27,7 +27,8 @@ class _EmbDesc(C.Structure):
         ("num_slots", C.c_int32), ("dim", C.c_int32), ("table_dtype", C.c_int32), ("combiner", C.c_int32),
         ("table", C.c_void_p), ("total_rows", C.c_int64),
         ("slot_row_base", C.POINTER(C.c_int64)), ("slot_num_rows", C.POINTER(C.c_int64)),
-        ("hash", C.c_void_p), ("insert_on_miss", C.c_int32),
+        ("hash", C.c_void_p), ("insert_on_miss", C.c_int32), ("io_dtype", C.c_int32),
+        ("master", C.c_void_p),
     ]
 
 
@@ -182,8 +183,14 @@ class EmbeddingLayer:
 
     def __init__(self, table: torch.Tensor, num_slots: int, combiner: int = SUM,
                  slot_row_base: Optional[Sequence[int]] = None, slot_num_rows: Optional[Sequence[int]] = None,
-                 hash_table: Optional[HashTable] = None, insert_on_miss: bool = True):
+                 hash_table: Optional[HashTable] = None, insert_on_miss: bool = True,
+                 io_dtype: torch.dtype = torch.float32, master: Optional[torch.Tensor] = None):
         assert table.is_cuda and table.is_contiguous() and table.dim() == 2
+        assert io_dtype in (torch.float32, torch.float16)
+        if master is not None:
+            assert master.is_cuda and master.is_contiguous() and master.dtype == torch.float32
+            assert master.shape == table.shape
+        self.io_dtype, self.master = io_dtype, master
         self.table, self.num_slots, self.combiner = table, num_slots, combiner
         self.hash_table = hash_table
         d = _EmbDesc()
@@ -200,6 +207,8 @@ class EmbeddingLayer:
         else:
             d.hash = hash_table.handle
         d.insert_on_miss = int(insert_on_miss)
+        d.io_dtype = F32 if io_dtype == torch.float32 else F16
+        d.master = None if master is None else master.data_ptr()
         self.desc = d
         self._wsbuf = None
 
@@ -225,8 +234,9 @@ class EmbeddingLayer:
                 out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
         nnz = keys.numel()
         if out is None:
-            out = torch.empty((batch, self.num_slots, self.table.shape[1]), dtype=torch.float32,
+            out = torch.empty((batch, self.num_slots, self.table.shape[1]), dtype=self.io_dtype,
                               device=self.table.device)
+        assert out.dtype == self.io_dtype
         if ws is None:
             ws = self.workspace(batch, nnz)
         _check(lib().hctr_emb_forward(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(out),
@@ -236,6 +246,7 @@ class EmbeddingLayer:
     def backward_sgd(self, batch: int, keys: torch.Tensor, dY: torch.Tensor, lr: float,
                      offsets: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> None:
         nnz = keys.numel()
+        assert dY.dtype == self.io_dtype and dY.is_contiguous()
         if ws is None:
             ws = self.workspace(batch, nnz)
         _check(lib().hctr_emb_backward_sgd(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(dY),
@@ -252,6 +263,7 @@ class EmbeddingLayer:
     def backward_apply(self, batch: int, nnz: int, dY: torch.Tensor, lr: float,
                        offsets: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
                        stream=None) -> None:
+        assert dY.dtype == self.io_dtype and dY.is_contiguous()
         if ws is None:
             ws = self.workspace(batch, nnz)
         _check(lib().hctr_emb_backward_apply(C.byref(self.desc), batch, _ptr(offsets), nnz, _ptr(dY),

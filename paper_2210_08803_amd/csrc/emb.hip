@@ -48,12 +48,12 @@ __device__ __forceinline__ void count_invalid(unsigned long long* counter, bool 
 // Forward, one key per bag: a group of LPR lanes copies U rows (U independent 16-byte loads per
 // lane in flight), so a wave covers 64/LPR * U bags.
 // ------------------------------------------------------------------------------------------------
-template <typename T, int LPR, int U, bool HASHED, bool NT = true>
+template <typename T, typename OutT, int LPR, int U, bool HASHED>
 __global__ __launch_bounds__(256) void fwd_onehot(const T* __restrict__ table, int D,
                                                   int64_t total_rows, const int64_t* __restrict__ keys,
                                                   const int64_t* __restrict__ rows64, uint32_t n_bags,
                                                   uint32_t S, const SlotTable slots,
-                                                  float* __restrict__ out, EmbHeader* hdr) {
+                                                  OutT* __restrict__ out, EmbHeader* hdr) {
   constexpr int VEC = RowVec<T>::VEC;
   const int sub = threadIdx.x % LPR;
   const uint32_t group0 = (blockIdx.x * 256u + threadIdx.x) / LPR;
@@ -99,8 +99,7 @@ __global__ __launch_bounds__(256) void fwd_onehot(const T* __restrict__ table, i
     for (int u = 0; u < U; ++u) {
       const uint32_t bag = bag0 + u;
       if (bag < n_bags && active) {
-        if (NT) store_stream<VEC>(out + (int64_t)bag * D + col, v[u]);
-        else store_plain<VEC>(out + (int64_t)bag * D + col, v[u]);
+        store_stream<VEC>(out + (int64_t)bag * D + col, v[u]);
       }
     }
   }
@@ -116,13 +115,13 @@ __global__ __launch_bounds__(256) void fwd_onehot(const T* __restrict__ table, i
 // robin, U keys each per step; the groups' partial sums are staged in LDS and added in group order
 // by group 0, which scales (mean) and writes the pooled row.
 // ------------------------------------------------------------------------------------------------
-template <typename T, int LPR, int U, bool HASHED>
+template <typename T, typename OutT, int LPR, int U, bool HASHED>
 __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int D, int64_t total_rows,
                                                const int64_t* __restrict__ keys,
                                                const int64_t* __restrict__ rows64,
                                                const int64_t* __restrict__ offsets, uint32_t n_bags,
                                                uint32_t S, const SlotTable slots, int mean,
-                                               float* __restrict__ out, EmbHeader* hdr) {
+                                               OutT* __restrict__ out, EmbHeader* hdr) {
   constexpr int VEC = RowVec<T>::VEC;
   constexpr int G = 64 / LPR;
   __shared__ float part[4][(G > 1 ? (G - 1) : 1) * LPR * VEC];
@@ -442,23 +441,30 @@ struct GroupLookup {
 };
 static_assert(sizeof(GroupLookup) == 24, "kernel-argument layout");
 
-template <typename T>
+template <typename T, typename DyT>
 struct UniformView {
   static constexpr int kLds = 1;
   T* table;
-  const float* dY;
+  float* master;   // fp32 copy of an fp16 table that takes the update (the table row is its rounding), or NULL
+  const DyT* dY;
   int D;
   int mean;
   __device__ __forceinline__ const GroupLookup* stage(GroupLookup*) const { return nullptr; }
   __device__ __forceinline__ int dmax() const { return D; }
   __device__ __forceinline__ bool is_mean(uint32_t, const GroupLookup*) const { return mean != 0; }
-  __device__ __forceinline__ const float* grad(uint32_t bag, const GroupLookup*, int* width) const {
+  __device__ __forceinline__ const DyT* grad(uint32_t bag, const GroupLookup*, int* width) const {
     *width = D;
     return dY + (int64_t)bag * D;
   }
-  __device__ __forceinline__ T* row(uint32_t r, uint32_t, const GroupLookup*, int* width) const {
-    *width = D;
-    return table + (int64_t)r * D;
+  __device__ __forceinline__ int row_width(uint32_t, const GroupLookup*) const { return D; }
+  // four weights of row r at column col, widened to fp32 / written back
+  __device__ __forceinline__ f32x4 load_weights(uint32_t r, uint32_t, const GroupLookup*, int col) const {
+    if (master) return load4(master + (int64_t)r * D + col);
+    return load_row4(table + (int64_t)r * D + col);
+  }
+  __device__ __forceinline__ void store_weights(uint32_t r, uint32_t, const GroupLookup*, int col, f32x4 x) const {
+    if (master) store4(master + (int64_t)r * D + col, x);
+    store_row4(table + (int64_t)r * D + col, x);
   }
 };
 
@@ -483,10 +489,15 @@ struct GroupView {
     *width = (int)k.dim;
     return dY + (int64_t)(bag / L) * width_total + k.col;
   }
-  __device__ __forceinline__ T* row(uint32_t r, uint32_t bag, const GroupLookup* l, int* width) const {
+  __device__ __forceinline__ int row_width(uint32_t bag, const GroupLookup* l) const { return (int)l[bag % L].dim; }
+  __device__ __forceinline__ f32x4 load_weights(uint32_t r, uint32_t bag, const GroupLookup* l, int col) const {
     const GroupLookup& k = l[bag % L];
-    *width = (int)k.dim;
-    return static_cast<T*>(k.table) + (int64_t)(r - k.row_base) * k.dim;
+    return load_row4(static_cast<const T*>(k.table) + (int64_t)(r - k.row_base) * k.dim + col);
+  }
+  __device__ __forceinline__ void store_weights(uint32_t r, uint32_t bag, const GroupLookup* l, int col,
+                                                f32x4 x) const {
+    const GroupLookup& k = l[bag % L];
+    store_row4(static_cast<T*>(k.table) + (int64_t)(r - k.row_base) * k.dim + col, x);
   }
 };
 
@@ -549,17 +560,13 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
         b[u] = __shfl(mybag, q, LPR);
         w[u] = __shfl(myw, q, LPR);
         int width;
-        const float* g = view.grad(b[u], lk, &width);
-        v[u] = col < width ? load4(g + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+        const auto* g = view.grad(b[u], lk, &width);
+        v[u] = col < width ? load_row4(g + col) : f32x4{0.f, 0.f, 0.f, 0.f};
       }
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
         t[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (ends[u]) {
-          int width;
-          const T* rp = view.row(r[u], b[u], lk, &width);
-          if (col < width) t[u] = load_row4(rp + col);
-        }
+        if (ends[u] && col < view.row_width(b[u], lk)) t[u] = view.load_weights(r[u], b[u], lk, col);
       }
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
@@ -568,14 +575,12 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
           acc.z += w[u] * v[u].z; acc.w += w[u] * v[u].w;
         }
         if (ends[u]) {
-          int width;
-          T* rp = view.row(r[u], b[u], lk, &width);
-          if (col < width) {
+          if (col < view.row_width(b[u], lk)) {
             if (before) {
               store4(head + (int64_t)win * DM + col, acc);
             } else {
               t[u].x -= lr * acc.x; t[u].y -= lr * acc.y; t[u].z -= lr * acc.z; t[u].w -= lr * acc.w;
-              store_row4(rp + col, t[u]);
+              view.store_weights(r[u], b[u], lk, col, t[u]);
             }
           }
           acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -637,9 +642,7 @@ __global__ __launch_bounds__(256) void bwd_carry_short(
     if (sub == 0 && blockIdx.y == 0) long_list[atomicAdd(&hdr->n_long, 1u)] = win;
     return;
   }
-  int width;
-  T* rp = view.row(r, bag, lk, &width);
-  const bool active = col < width;
+  const bool active = col < view.row_width(bag, lk);
   f32x4 h[kCarryShort];
 #pragma unroll
   for (uint32_t k = 0; k < kCarryShort; ++k)
@@ -648,7 +651,9 @@ __global__ __launch_bounds__(256) void bwd_carry_short(
     f32x4 tot = load4(tail + (int64_t)win * DM + col);
 #pragma unroll
     for (uint32_t k = 0; k < kCarryShort; ++k) { tot.x += h[k].x; tot.y += h[k].y; tot.z += h[k].z; tot.w += h[k].w; }
-    sgd_update4(rp + col, tot, lr);
+    f32x4 x = view.load_weights(r, bag, lk, col);
+    x.x -= lr * tot.x; x.y -= lr * tot.y; x.z -= lr * tot.z; x.w -= lr * tot.w;
+    view.store_weights(r, bag, lk, col, x);
   }
 }
 
@@ -670,9 +675,7 @@ __global__ __launch_bounds__(1024) void bwd_carry_long(
     const uint32_t win = long_list[i];
     uint32_t r, bag, last;
     carry_extent(skv, starts_before, seg_off, win, W, &r, &bag, &last);
-    int width;
-    T* rp = view.row(r, bag, lk, &width);
-    const bool active = col < width;
+    const bool active = col < view.row_width(bag, lk);
     const uint32_t cnt = last - win;
     const uint32_t share = (cnt + NG - 1) / NG;
     const uint32_t f0 = win + 1 + g * share;
@@ -695,7 +698,9 @@ __global__ __launch_bounds__(1024) void bwd_carry_long(
         const f32x4 q = part[gg * LPR + sub];
         tot.x += q.x; tot.y += q.y; tot.z += q.z; tot.w += q.w;
       }
-      sgd_update4(rp + col, tot, lr);
+      f32x4 x = view.load_weights(r, bag, lk, col);
+      x.x -= lr * tot.x; x.y -= lr * tot.y; x.z -= lr * tot.z; x.w -= lr * tot.w;
+      view.store_weights(r, bag, lk, col, x);
     }
     __syncthreads();   // part is reused by the next row
   }
@@ -886,6 +891,12 @@ static hctr_status validate_desc(const hctr_emb_desc* d) {
     return fail(HCTR_E_INVALID_ARG, "dim %d must be a positive multiple of %d", d->dim, mult);
   if (d->combiner != HCTR_SUM && d->combiner != HCTR_MEAN)
     return fail(HCTR_E_INVALID_ARG, "combiner %d unknown", d->combiner);
+  if (d->io_dtype != HCTR_F32 && d->io_dtype != HCTR_F16)
+    return fail(HCTR_E_INVALID_ARG, "io_dtype %d unknown", d->io_dtype);
+  if (d->master) {
+    if (d->table_dtype != HCTR_F16) return fail(HCTR_E_INVALID_ARG, "master rows go with an fp16 table only");
+    if ((uintptr_t)d->master % 16 != 0) return fail(HCTR_E_INVALID_ARG, "master must be 16-byte aligned");
+  }
   if (!d->table) return fail(HCTR_E_NULL_PTR, "table is NULL");
   if ((uintptr_t)d->table % 16 != 0) return fail(HCTR_E_INVALID_ARG, "table must be 16-byte aligned");
   if (d->total_rows < 1 || d->total_rows > 0xFFFFFFFEll)
@@ -946,9 +957,9 @@ static int lanes_per_row(int dim) {
   return l < 4 ? 4 : (l > 64 ? 64 : l);
 }
 
-template <typename T, int LPR>
+template <typename T, typename OutT, int LPR>
 static void launch_forward(const hctr_emb_desc* d, const int64_t* keys, const int64_t* rows64,
-                           const int64_t* offsets, uint32_t n_bags, const SlotTable& st, float* out,
+                           const int64_t* offsets, uint32_t n_bags, const SlotTable& st, OutT* out,
                            EmbHeader* hdr, hipStream_t stream) {
   constexpr int VEC = RowVec<T>::VEC;
   const uint32_t ychunks = (uint32_t)ceil_div(d->dim, LPR * VEC);
@@ -958,36 +969,36 @@ static void launch_forward(const hctr_emb_desc* d, const int64_t* keys, const in
     const uint32_t bags_per_block = (256 / LPR) * U;
     dim3 grid((uint32_t)ceil_div(n_bags, bags_per_block), ychunks);
     if (rows64)
-      hipLaunchKernelGGL((fwd_onehot<T, LPR, U, true>), grid, dim3(256), 0, stream, table, d->dim,
+      hipLaunchKernelGGL((fwd_onehot<T, OutT, LPR, U, true>), grid, dim3(256), 0, stream, table, d->dim,
                          d->total_rows, keys, rows64, n_bags, (uint32_t)d->num_slots, st, out, hdr);
     else
-      hipLaunchKernelGGL((fwd_onehot<T, LPR, U, false>), grid, dim3(256), 0, stream, table, d->dim,
+      hipLaunchKernelGGL((fwd_onehot<T, OutT, LPR, U, false>), grid, dim3(256), 0, stream, table, d->dim,
                          d->total_rows, keys, rows64, n_bags, (uint32_t)d->num_slots, st, out, hdr);
   } else {
     constexpr int U = 4;
     dim3 grid((uint32_t)ceil_div(n_bags, 4), ychunks);
     const int mean = d->combiner == HCTR_MEAN;
     if (rows64)
-      hipLaunchKernelGGL((fwd_csr<T, LPR, U, true>), grid, dim3(256), 0, stream, table, d->dim,
+      hipLaunchKernelGGL((fwd_csr<T, OutT, LPR, U, true>), grid, dim3(256), 0, stream, table, d->dim,
                          d->total_rows, keys, rows64, offsets, n_bags, (uint32_t)d->num_slots, st, mean,
                          out, hdr);
     else
-      hipLaunchKernelGGL((fwd_csr<T, LPR, U, false>), grid, dim3(256), 0, stream, table, d->dim,
+      hipLaunchKernelGGL((fwd_csr<T, OutT, LPR, U, false>), grid, dim3(256), 0, stream, table, d->dim,
                          d->total_rows, keys, rows64, offsets, n_bags, (uint32_t)d->num_slots, st, mean,
                          out, hdr);
   }
 }
 
-template <typename T>
+template <typename T, typename OutT>
 static void dispatch_forward(int lpr, const hctr_emb_desc* d, const int64_t* keys,
                              const int64_t* rows64, const int64_t* offsets, uint32_t n_bags,
-                             const SlotTable& st, float* out, EmbHeader* hdr, hipStream_t stream) {
+                             const SlotTable& st, OutT* out, EmbHeader* hdr, hipStream_t stream) {
   switch (lpr) {
-    case 4: launch_forward<T, 4>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
-    case 8: launch_forward<T, 8>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
-    case 16: launch_forward<T, 16>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
-    case 32: launch_forward<T, 32>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
-    default: launch_forward<T, 64>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
+    case 4: launch_forward<T, OutT, 4>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
+    case 8: launch_forward<T, OutT, 8>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
+    case 16: launch_forward<T, OutT, 16>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
+    case 32: launch_forward<T, OutT, 32>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
+    default: launch_forward<T, OutT, 64>(d, keys, rows64, offsets, n_bags, st, out, hdr, stream); break;
   }
 }
 
@@ -1029,12 +1040,13 @@ static void dispatch_reduce_view(const View& view, int dmax, const EmbLayout& L,
   }
 }
 
-template <typename T>
+template <typename T, typename DyT>
 static void dispatch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, const uint64_t* skv,
-                            const int64_t* offsets, const float* dY, float lr, hipStream_t stream) {
-  UniformView<T> view;
+                            const int64_t* offsets, const void* dY, float lr, hipStream_t stream) {
+  UniformView<T, DyT> view;
   view.table = static_cast<T*>(d->table);
-  view.dY = dY;
+  view.master = d->master;
+  view.dY = static_cast<const DyT*>(dY);
   view.D = d->dim;
   view.mean = (d->combiner == HCTR_MEAN && offsets != nullptr) ? 1 : 0;
   dispatch_reduce_view<T>(view, d->dim, L, ws, skv, offsets, lr, stream);
@@ -1051,7 +1063,7 @@ HCTR_API size_t hctr_emb_workspace_bytes(const hctr_emb_desc* desc, int64_t batc
 }
 
 HCTR_API hctr_status hctr_emb_forward(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
-                                      const int64_t* offsets, int64_t nnz, float* out, void* ws,
+                                      const int64_t* offsets, int64_t nnz, void* out, void* ws,
                                       size_t ws_bytes, void* stream_) {
   EmbLayout L;
   HCTR_TRY(validate_batch(desc, batch, keys, offsets, nnz, out, ws, ws_bytes, &L));
@@ -1069,12 +1081,19 @@ HCTR_API hctr_status hctr_emb_forward(const hctr_emb_desc* desc, int64_t batch, 
   }
   SlotTable st;
   fill_slots(desc, &st);
-  if (desc->table_dtype == HCTR_F32)
-    dispatch_forward<float>(lanes_per_row<float>(desc->dim), desc, keys, rows64, offsets,
-                            (uint32_t)n_bags, st, out, hdr, stream);
+  const bool t32 = desc->table_dtype == HCTR_F32, o32 = desc->io_dtype == HCTR_F32;
+  if (t32 && o32)
+    dispatch_forward<float, float>(lanes_per_row<float>(desc->dim), desc, keys, rows64, offsets, (uint32_t)n_bags,
+                                   st, static_cast<float*>(out), hdr, stream);
+  else if (t32)
+    dispatch_forward<float, __half>(lanes_per_row<float>(desc->dim), desc, keys, rows64, offsets, (uint32_t)n_bags,
+                                    st, static_cast<__half*>(out), hdr, stream);
+  else if (o32)
+    dispatch_forward<__half, float>(lanes_per_row<__half>(desc->dim), desc, keys, rows64, offsets, (uint32_t)n_bags,
+                                    st, static_cast<float*>(out), hdr, stream);
   else
-    dispatch_forward<__half>(lanes_per_row<__half>(desc->dim), desc, keys, rows64, offsets,
-                             (uint32_t)n_bags, st, out, hdr, stream);
+    dispatch_forward<__half, __half>(lanes_per_row<__half>(desc->dim), desc, keys, rows64, offsets,
+                                     (uint32_t)n_bags, st, static_cast<__half*>(out), hdr, stream);
   return launch_status("hctr_emb_forward");
 }
 
@@ -1139,14 +1158,15 @@ static hctr_status backward_dedup(const hctr_emb_desc* desc, int64_t batch, cons
 
 // B4-B5: segmented reduction of dY over the sorted occurrences, fused with the SGD row update.
 static hctr_status backward_apply(const hctr_emb_desc* desc, const int64_t* offsets, int64_t nnz,
-                                  const float* dY, float lr, const EmbLayout& L, char* w,
+                                  const void* dY, float lr, const EmbLayout& L, char* w,
                                   hipStream_t stream) {
   if (nnz == 0) return HCTR_OK;
   const uint64_t* skv = reinterpret_cast<const uint64_t*>(w + ((L.sort.passes & 1) ? L.kv1 : L.kv0));
-  if (desc->table_dtype == HCTR_F32)
-    dispatch_reduce<float>(desc, L, w, skv, offsets, dY, lr, stream);
-  else
-    dispatch_reduce<__half>(desc, L, w, skv, offsets, dY, lr, stream);
+  const bool t32 = desc->table_dtype == HCTR_F32, g32 = desc->io_dtype == HCTR_F32;
+  if (t32 && g32) dispatch_reduce<float, float>(desc, L, w, skv, offsets, dY, lr, stream);
+  else if (t32) dispatch_reduce<float, __half>(desc, L, w, skv, offsets, dY, lr, stream);
+  else if (g32) dispatch_reduce<__half, float>(desc, L, w, skv, offsets, dY, lr, stream);
+  else dispatch_reduce<__half, __half>(desc, L, w, skv, offsets, dY, lr, stream);
   return launch_status("hctr_emb_backward_apply");
 }
 
@@ -1159,7 +1179,7 @@ HCTR_API hctr_status hctr_emb_backward_dedup(const hctr_emb_desc* desc, int64_t 
 }
 
 HCTR_API hctr_status hctr_emb_backward_apply(const hctr_emb_desc* desc, int64_t batch, const int64_t* offsets,
-                                             int64_t nnz, const float* dY, float lr, void* ws,
+                                             int64_t nnz, const void* dY, float lr, void* ws,
                                              size_t ws_bytes, void* stream) {
   EmbLayout L;
   HCTR_TRY(validate_batch(desc, batch, nullptr, offsets, nnz, dY, ws, ws_bytes, &L, true, false));
@@ -1167,7 +1187,7 @@ HCTR_API hctr_status hctr_emb_backward_apply(const hctr_emb_desc* desc, int64_t 
 }
 
 HCTR_API hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
-                                           const int64_t* offsets, int64_t nnz, const float* dY, float lr,
+                                           const int64_t* offsets, int64_t nnz, const void* dY, float lr,
                                            void* ws, size_t ws_bytes, void* stream_) {
   EmbLayout L;
   HCTR_TRY(validate_batch(desc, batch, keys, offsets, nnz, dY, ws, ws_bytes, &L));

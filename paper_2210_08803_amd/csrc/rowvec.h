@@ -50,6 +50,26 @@ __device__ __forceinline__ void store_stream(float* p, const float (&v)[N]) {
   }
 }
 
+// The same into an fp16 output: N floats rounded to nearest even, 2 * N bytes.
+template <int N>
+__device__ __forceinline__ void store_stream(__half* p, const float (&v)[N]) {
+  uint32_t w[N / 2];
+#pragma unroll
+  for (int i = 0; i < N / 2; ++i)
+    w[i] = (uint32_t)__half_as_ushort(__float2half_rn(v[2 * i])) |
+           ((uint32_t)__half_as_ushort(__float2half_rn(v[2 * i + 1])) << 16);
+  if constexpr (N == 4) {
+    u32x2 x = {w[0], w[1]};
+    __builtin_nontemporal_store(x, reinterpret_cast<u32x2*>(p));
+  } else {
+#pragma unroll
+    for (int i = 0; i < N / 2; i += 4) {
+      u32x4 x = {w[i], w[i + 1], w[i + 2], w[i + 3]};
+      __builtin_nontemporal_store(x, reinterpret_cast<u32x4*>(p + 2 * i));
+    }
+  }
+}
+
 template <int N>
 __device__ __forceinline__ void store_plain(float* p, const float (&v)[N]) {
 #pragma unroll

@@ -51,6 +51,9 @@ def test_forward_argument_errors_are_caught_on_the_host():
     assert _fwd(_desc(dim=12, table_dtype=H.F16)) == -1   # fp16 rows need a multiple of 8
     assert _fwd(_desc(table_dtype=7)) == -1
     assert _fwd(_desc(combiner=3)) == -1
+    assert _fwd(_desc(io_dtype=2)) == -1
+    assert _fwd(_desc(master=8192)) == -1                 # master rows go with an fp16 table only
+    assert _fwd(_desc(dim=8, table_dtype=H.F16, master=8196)) == -1   # misaligned master
     assert _fwd(_desc(table=None)) == -2
     assert _fwd(_desc(table=4100)) == -1                  # misaligned table
     assert _fwd(_desc(total_rows=0)) == -4
