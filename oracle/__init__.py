@@ -74,6 +74,16 @@ def lib() -> C.CDLL:
         L.oracle_cache_update.argtypes = [p, p, p, i64]
         L.oracle_cache_refresh.restype = None
         L.oracle_cache_refresh.argtypes = [p]
+        L.oracle_etc_create.restype = p
+        L.oracle_etc_create.argtypes = [i64, i32, p, i64, p]
+        L.oracle_etc_destroy.restype = None
+        L.oracle_etc_destroy.argtypes = [p]
+        L.oracle_etc_load.restype = None
+        L.oracle_etc_load.argtypes = [p, p, i64, p]
+        L.oracle_etc_dump.restype = None
+        L.oracle_etc_dump.argtypes = [p, i32]
+        L.oracle_etc_stats.restype = None
+        L.oracle_etc_stats.argtypes = [p, p]
         L.oracle_cache_query.restype = None
         L.oracle_cache_query.argtypes = [p, i64, p, p, i64, i64, i32, p, p]
         _lib = L
@@ -310,3 +320,35 @@ class Cache:
         tags = tags.reshape(self.num_sets, self.ways)
         stamps = stamps.reshape(self.num_sets, self.ways)
         return (tags, stamps, data) if with_data else (tags, stamps)
+
+
+class Etc:
+    """Embedding training cache staged in host memory: `host` [host_rows, D] float32 is the model (written
+    by dump), `work` [max_rows, D] float32 is the working table training addresses through load's rows."""
+
+    def __init__(self, host: np.ndarray, max_rows: int):
+        assert host.dtype == np.float32 and host.ndim == 2 and host.flags.c_contiguous and host.flags.writeable
+        self.host = host
+        self.work = np.zeros((max_rows, host.shape[1]), dtype=np.float32)
+        self._e = lib().oracle_etc_create(int(max_rows), host.shape[1], _ptr(host), host.shape[0], _ptr(self.work))
+
+    def __del__(self):
+        if getattr(self, "_e", None):
+            lib().oracle_etc_destroy(self._e)
+            self._e = None
+
+    def load(self, keys) -> np.ndarray:
+        keys = _i64(keys)
+        rows = np.empty(len(keys), dtype=np.int64)
+        lib().oracle_etc_load(self._e, _ptr(keys), len(keys), _ptr(rows))
+        return rows
+
+    def dump(self, evict: bool = True) -> None:
+        lib().oracle_etc_dump(self._e, int(evict))
+
+    @property
+    def stats(self) -> Tuple[int, int, int, int]:
+        """(resident keys, rows loaded, rejected key occurrences, occurrences outside the host table)."""
+        out = np.zeros(4, dtype=np.int64)
+        lib().oracle_etc_stats(self._e, _ptr(out))
+        return tuple(int(x) for x in out)

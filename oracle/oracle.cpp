@@ -484,4 +484,64 @@ void oracle_cache_refresh(oracle_cache* c) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Embedding training cache, staged in host memory (section 1, "Online training": subsets of the
+// embedding tables are loaded on demand into the GPU, the whole table lives in host memory).
+// State: the host table [host_rows, dim] (the model), a working table [max_rows, dim] (what the
+// GPU holds), a key -> row map with rows handed out in first-appearance order as by the hash above,
+// and the key of every row.
+//   load(keys): keys in array order; a key already resident keeps its row; a new key with
+//     0 <= key < host_rows gets row = number of resident keys (if below max_rows, else it is
+//     rejected, row -1) and the working row becomes a copy of host row `key`; a key outside the
+//     host table is never loaded (row -1).
+//   dump(evict): every resident row is written back to its host row; with evict the cache then
+//     forgets all keys.
+// Training between load and dump addresses the working table through the rows load returned.
+// ---------------------------------------------------------------------------------------------
+struct oracle_etc {
+  int64_t max_rows, host_rows;
+  int32_t dim;
+  float* host;
+  float* work;
+  std::unordered_map<int64_t, int64_t> row_of;
+  std::vector<int64_t> key_of;
+  int64_t stats[3];   // loaded rows, rejected key occurrences, occurrences outside the host table (totals)
+};
+
+oracle_etc* oracle_etc_create(int64_t max_rows, int32_t dim, float* host, int64_t host_rows, float* work) {
+  oracle_etc* e = new oracle_etc();
+  e->max_rows = max_rows; e->host_rows = host_rows; e->dim = dim; e->host = host; e->work = work;
+  e->stats[0] = e->stats[1] = e->stats[2] = 0;
+  return e;
+}
+void oracle_etc_destroy(oracle_etc* e) { delete e; }
+
+void oracle_etc_load(oracle_etc* e, const int64_t* keys, int64_t n, int64_t* rows) {
+  for (int64_t i = 0; i < n; ++i) {
+    const int64_t k = keys[i];
+    if (k < 0 || k >= e->host_rows) { rows[i] = -1; e->stats[2] += 1; continue; }
+    auto it = e->row_of.find(k);
+    if (it != e->row_of.end()) { rows[i] = it->second; continue; }
+    if ((int64_t)e->key_of.size() >= e->max_rows) { rows[i] = -1; e->stats[1] += 1; continue; }
+    const int64_t r = (int64_t)e->key_of.size();
+    e->row_of[k] = r;
+    e->key_of.push_back(k);
+    std::memcpy(e->work + r * e->dim, e->host + k * e->dim, sizeof(float) * e->dim);
+    e->stats[0] += 1;
+    rows[i] = r;
+  }
+}
+
+void oracle_etc_dump(oracle_etc* e, int32_t evict) {
+  for (size_t r = 0; r < e->key_of.size(); ++r)
+    std::memcpy(e->host + e->key_of[r] * e->dim, e->work + (int64_t)r * e->dim, sizeof(float) * e->dim);
+  if (evict) { e->row_of.clear(); e->key_of.clear(); }
+}
+
+// out[0] = resident keys, out[1..3] = the three running totals above
+void oracle_etc_stats(const oracle_etc* e, int64_t* out) {
+  out[0] = (int64_t)e->key_of.size();
+  out[1] = e->stats[0]; out[2] = e->stats[1]; out[3] = e->stats[2];
+}
+
 }  // extern "C"
