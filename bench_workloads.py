@@ -5,6 +5,7 @@
     python bench_workloads.py hashed     # open 2^63 key space, capacity 1e8, dim 64: insert-or-find, fwd, bwd over load factor
     python bench_workloads.py cache      # inference cache, Zipf 1.2, batch 1 / 64 / 1024 / 16384: hit rate, keys/s, p50 latency
     python bench_workloads.py mixed      # headline shape in mixed precision: fp16 table + fp32 master rows, fp16 out / dY
+    python bench_workloads.py etc        # training cache staged in host memory: load / train / dump passes of 8 batches
     python bench_workloads.py group      # fused group: the 26 DLRM-sized tables with widths 128/64/32/16, dense one-hot input
 
 Each prints one JSON line.  Inputs are synthetic and seeded (datagen/), resident in HBM (the cache's
@@ -187,6 +188,50 @@ def mixed(h, args):
                          "batch 55296, one-hot, Zipf 1.05, sum", keys=nnz, **res)
 
 
+def etc(h, args):
+    host_rows, D, S, B, per_pass = args.host_rows, 128, 26, 55296, 8
+    host = torch.empty((host_rows, D), dtype=torch.float32, pin_memory=True)
+    for r0 in range(0, host_rows, 1 << 20):
+        r1 = min(host_rows, r0 + (1 << 20))
+        host[r0:r1].copy_(datagen.table_rows_at(SEED, torch.arange(r0, r1, device=DEV), D, torch.float32))
+    nnz = B * S
+    max_rows = 6_000_000
+    cache = h.EmbeddingTrainingCache(host, max_rows, capacity=8_000_000)
+    layer = cache.layer(S, h.SUM)
+    smp = datagen.ZipfSampler(host_rows, 1.05)
+    dY = datagen.normal_grads(SEED, 9, nnz * D, device=DEV).view(B, S, D)
+    out = torch.empty((B, S, D), device=DEV)
+    ws = layer.new_workspace(layer.workspace_bytes(B, nnz))
+    passes = []
+    for p in range(args.etc_passes):
+        batches = [datagen.cache_keys(SEED, 100 * p + i, host_rows, nnz, 1.05, sampler=smp).cuda() for i in range(per_pass)]
+        pass_keys = torch.cat(batches)
+        cache.workspace(pass_keys.numel())
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        ev[0].record()
+        cache.load(pass_keys)
+        ev[1].record()
+        for k in batches:
+            layer.forward(B, k, out=out, ws=ws)
+            layer.backward_sgd(B, k, dY, 0.01, ws=ws)
+        ev[2].record()
+        cache.dump(evict=True)
+        ev[3].record()
+        torch.cuda.synchronize()
+        st = cache.stats
+        rows = st[1] - sum(x["rows"] for x in passes)
+        load_ms, train_ms, dump_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), ev[2].elapsed_time(ev[3])
+        passes.append(dict(rows=rows, load_ms=load_ms, load_host_link_GBs=rows * D * 4 / load_ms / 1e6,
+                           train_ms_per_batch=train_ms / per_pass, dump_ms=dump_ms,
+                           dump_host_link_GBs=rows * D * 4 / dump_ms / 1e6,
+                           keys_per_s=per_pass * nnz / ((load_ms + train_ms + dump_ms) * 1e-3)))
+    assert cache.stats[2] == 0 and layer.invalid_keys(ws) == 0
+    return dict(workload=f"training cache staged in host memory: {host_rows} x 128 fp32 host table (pinned), working "
+                         f"table {max_rows} rows, passes of {per_pass} batches of 55296 x 26 one-hot keys, Zipf 1.05, "
+                         "load + forward/backward + dump with eviction", keys_per_pass=per_pass * nnz, passes=passes)
+
+
 def group(h, args):
     rows_t = datagen.DLRM_TABLE_ROWS
     B, L = 55296, len(rows_t)
@@ -227,7 +272,8 @@ def group(h, args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group", "mixed"])
+    ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group", "mixed", "etc"])
+    ap.add_argument("--etc-passes", type=int, default=4)
     ap.add_argument("--host-rows", type=int, default=20_000_000)
     ap.add_argument("--hash-batches", type=int, default=41)
     args = ap.parse_args()
@@ -235,7 +281,7 @@ def main():
         print("bench_workloads.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(2)
     import paper_2210_08803_amd as h
-    res = {"multihot": multihot, "hashed": hashed, "cache": cache, "group": group, "mixed": mixed}[args.workload](h, args)
+    res = {"multihot": multihot, "hashed": hashed, "cache": cache, "group": group, "mixed": mixed, "etc": etc}[args.workload](h, args)
     res["n_gpus"] = 1
     res["data"] = "synthetic"
     print(json.dumps(res), flush=True)

@@ -18,8 +18,8 @@
  *              workspaces.  The library never allocates or frees device memory; the opaque handles
  *              are small host-side structs freed by the matching *_destroy.
  *   Streams    `stream` is a hipStream_t passed as void* (NULL = the default stream).  Compute
- *              calls enqueue work and return without waiting; only hctr_hash_size, hctr_cache_stats
- *              and hctr_emb_invalid_keys wait for the stream.  A workspace must stay untouched by
+ *              calls enqueue work and return without waiting; only hctr_hash_size, hctr_cache_stats,
+ *              hctr_etc_stats and hctr_emb_invalid_keys wait for the stream.  A workspace must stay untouched by
  *              the caller until the stream has passed the call that uses it.
  *   Errors     Every call returns an hctr_status.  Argument errors are found on the host before
  *              anything is launched.  A failing HIP call gives HCTR_E_DEVICE.  hctr_last_error()
@@ -58,6 +58,7 @@ typedef enum { HCTR_SUM = 0, HCTR_MEAN = 1 } hctr_combiner;
 
 typedef struct hctr_hash hctr_hash;   /* opaque */
 typedef struct hctr_cache hctr_cache; /* opaque */
+typedef struct hctr_etc hctr_etc;     /* opaque */
 
 /*
  * Description of one fused embedding layer (section 1, "Localized slot embedding hash": every
@@ -248,7 +249,45 @@ hctr_status hctr_hash_insert_or_find(hctr_hash* hash, const int64_t* keys, int64
                                      int64_t* rows, void* ws, size_t ws_bytes, void* stream);
 /* Number of keys held (host int64; waits for the stream). */
 hctr_status hctr_hash_size(hctr_hash* hash, void* stream, int64_t* size);
+/* Forgets every key (size 0, all slots empty); enqueued on `stream`. */
+hctr_status hctr_hash_clear(hctr_hash* hash, void* stream);
 void hctr_hash_destroy(hctr_hash* hash);
+
+/*
+ * Embedding training cache staged in host memory (section 1, "Online training": the Embedding
+ * Training Cache loads subsets of the embedding tables on demand into the GPU; its "Staged-PS"
+ * keeps the whole table in host memory).  The model is host_table, pinned host [host_rows, dim]
+ * fp32, a key being its row index.  The GPU holds a working table, device [max_rows, dim] fp32,
+ * addressed through `hash` (max_rows = the hash's): train on it with a hashed-mode layer
+ * (hctr_emb_desc.hash = hash, insert_on_miss = 0, table = the working table).  One pass:
+ *   hctr_etc_load   keys device [n], the keys the coming batches will use (repeats allowed).  Keys
+ *                   already resident keep their rows.  New keys with 0 <= key < host_rows get rows
+ *                   in first-appearance order, as by hctr_hash_insert_or_find, and their host rows
+ *                   are copied into the working table (one read of the row across the host link).
+ *                   New keys that find no room (size == max_rows) and keys outside the host table
+ *                   are not loaded (row -1, counted); a layer treats them as keys without a row.
+ *                   rows: device [n] or NULL, receives the row of every key.
+ *   (training calls on the working table)
+ *   hctr_etc_dump   writes every resident row back to its host row (one write of the row across the
+ *                   host link); with evict != 0 the hash is then cleared, so the next load starts
+ *                   from an empty working table.  The host must not read host_table before the
+ *                   stream has passed the call.
+ *   storage   device, >= hctr_etc_storage_bytes(max_rows), 256-byte aligned (counters and the key of
+ *             every row); ws device, >= hctr_etc_workspace_bytes(n), 256-byte aligned.
+ *   hctr_etc_stats  host int64 [4] = resident keys, rows loaded, rejected key occurrences,
+ *                   occurrences outside the host table (the last three running totals); waits for
+ *                   the stream.
+ * The handle does not own hash, tables or storage.
+ */
+size_t hctr_etc_storage_bytes(int64_t max_rows);
+size_t hctr_etc_workspace_bytes(int64_t n_max);
+hctr_status hctr_etc_create(hctr_hash* hash, void* table, int32_t dim, float* host_table, int64_t host_rows,
+                            void* storage, size_t storage_bytes, void* stream, hctr_etc** out);
+hctr_status hctr_etc_load(hctr_etc* etc, const int64_t* keys, int64_t n, int64_t* rows, void* ws,
+                          size_t ws_bytes, void* stream);
+hctr_status hctr_etc_dump(hctr_etc* etc, int32_t evict, void* stream);
+hctr_status hctr_etc_stats(hctr_etc* etc, void* stream, int64_t* stats);
+void hctr_etc_destroy(hctr_etc* etc);
 
 /*
  * Inference embedding cache (section 3, "embedding inference cache"): set-associative, num_sets

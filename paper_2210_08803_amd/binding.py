@@ -83,6 +83,14 @@ def lib() -> C.CDLL:
         "hctr_hash_insert_or_find": (i32, [p, p, i64, i32, p, p, sz, p]),
         "hctr_hash_size": (i32, [p, p, C.POINTER(i64)]),
         "hctr_hash_destroy": (None, [p]),
+        "hctr_hash_clear": (i32, [p, p]),
+        "hctr_etc_storage_bytes": (sz, [i64]),
+        "hctr_etc_workspace_bytes": (sz, [i64]),
+        "hctr_etc_create": (i32, [p, p, i32, p, i64, p, sz, p, C.POINTER(p)]),
+        "hctr_etc_load": (i32, [p, p, i64, p, p, sz, p]),
+        "hctr_etc_dump": (i32, [p, i32, p]),
+        "hctr_etc_stats": (i32, [p, p, C.POINTER(i64)]),
+        "hctr_etc_destroy": (None, [p]),
         "hctr_cache_storage_bytes": (sz, [i64, i32, i32]),
         "hctr_cache_create": (i32, [p, sz, i64, i32, i32, p, i64, p, C.POINTER(p)]),
         "hctr_cache_workspace_bytes": (sz, [p, i64]),
@@ -109,7 +117,9 @@ EXPORTS = [
     "hctr_emb_backward_apply", "hctr_emb_dedup_view",
     "hctr_emb_invalid_keys", "hctr_group_workspace_bytes", "hctr_group_forward", "hctr_group_backward_sgd",
     "hctr_hash_storage_bytes", "hctr_hash_create", "hctr_hash_workspace_bytes",
-    "hctr_hash_insert_or_find", "hctr_hash_size", "hctr_hash_destroy", "hctr_cache_storage_bytes",
+    "hctr_hash_insert_or_find", "hctr_hash_size", "hctr_hash_destroy", "hctr_hash_clear", "hctr_etc_storage_bytes",
+    "hctr_etc_workspace_bytes", "hctr_etc_create", "hctr_etc_load", "hctr_etc_dump", "hctr_etc_stats",
+    "hctr_etc_destroy", "hctr_cache_storage_bytes",
     "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_set_small_call_limit", "hctr_cache_query",
     "hctr_cache_query_async", "hctr_cache_insert", "hctr_cache_update", "hctr_cache_refresh", "hctr_cache_stats",
     "hctr_cache_state_view", "hctr_cache_destroy", "hctr_last_error",
@@ -176,6 +186,9 @@ class HashTable:
         v = C.c_int64()
         _check(lib().hctr_hash_size(self.handle, _stream(None), C.byref(v)))
         return v.value
+
+    def clear(self, stream=None) -> None:
+        _check(lib().hctr_hash_clear(self.handle, _stream(stream)))
 
 
 class EmbeddingLayer:
@@ -351,6 +364,58 @@ class EmbeddingGroup:
         v = C.c_int64()
         _check(lib().hctr_emb_invalid_keys(_ptr(ws), ws.numel(), _stream(None), C.byref(v)))
         return v.value
+
+
+class EmbeddingTrainingCache:
+    """hctr_etc_*: the model in pinned host memory, the rows of a pass in a working table on the GPU.
+    `layer(...)` gives the hashed-mode layer that trains on the working table."""
+
+    def __init__(self, host_table: torch.Tensor, max_rows: int, capacity: Optional[int] = None, device="cuda"):
+        assert host_table.is_pinned() and host_table.dtype == torch.float32 and host_table.is_contiguous()
+        L = lib()
+        self.host_table, self.max_rows, self.device = host_table, max_rows, device
+        self.hash_table = HashTable(capacity if capacity is not None else max(64, int(max_rows / 0.75) + 8), max_rows,
+                                    device)
+        self.table = torch.zeros((max_rows, host_table.shape[1]), dtype=torch.float32, device=device)
+        nbytes = L.hctr_etc_storage_bytes(max_rows)
+        self.storage = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        h = C.c_void_p()
+        _check(L.hctr_etc_create(self.hash_table.handle, self.table.data_ptr(), host_table.shape[1],
+                                 host_table.data_ptr(), host_table.shape[0], self.storage.data_ptr(), nbytes,
+                                 _stream(None), C.byref(h)))
+        self.handle = h
+        self._wsbuf = None
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib().hctr_etc_destroy(self.handle)
+            self.handle = None
+
+    def workspace(self, n: int) -> torch.Tensor:
+        need = lib().hctr_etc_workspace_bytes(n)
+        if self._wsbuf is None or self._wsbuf.numel() < need:
+            self._wsbuf = _ws(need, self.device)
+        return self._wsbuf
+
+    def load(self, keys: torch.Tensor, rows: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+             stream=None) -> Optional[torch.Tensor]:
+        n = keys.numel()
+        if ws is None:
+            ws = self.workspace(n)
+        _check(lib().hctr_etc_load(self.handle, _ptr(keys), n, _ptr(rows), _ptr(ws), ws.numel(), _stream(stream)))
+        return rows
+
+    def dump(self, evict: bool = True, stream=None) -> None:
+        _check(lib().hctr_etc_dump(self.handle, int(evict), _stream(stream)))
+
+    def layer(self, num_slots: int, combiner: int = SUM) -> "EmbeddingLayer":
+        return EmbeddingLayer(self.table, num_slots, combiner, hash_table=self.hash_table, insert_on_miss=False)
+
+    @property
+    def stats(self):
+        out = (C.c_int64 * 4)()
+        _check(lib().hctr_etc_stats(self.handle, _stream(None), out))
+        return tuple(out)
 
 
 class EmbeddingCache:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhctr.so")
-SOURCES = ["runtime.cpp", "primitives.hip", "emb.hip", "hash.hip", "cache.hip"]
+SOURCES = ["runtime.cpp", "primitives.hip", "emb.hip", "hash.hip", "cache.hip", "etc.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",

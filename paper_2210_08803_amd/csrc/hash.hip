@@ -331,6 +331,15 @@ HCTR_API hctr_status hctr_hash_create(void* storage, size_t storage_bytes, int64
   return HCTR_OK;
 }
 
+HCTR_API hctr_status hctr_hash_clear(hctr_hash* hash, void* stream) {
+  if (!hash) return fail(HCTR_E_NULL_PTR, "hash is NULL");
+  const uint64_t n_slots = (uint64_t)hash->n_buckets * 8;
+  hipLaunchKernelGGL(hash_clear, dim3((uint32_t)ceil_div((int64_t)n_slots, 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), reinterpret_cast<u64x2*>(hash->slots), n_slots,
+                     reinterpret_cast<HashHeader*>(hash->size));
+  return launch_status("hash_clear");
+}
+
 HCTR_API size_t hctr_hash_workspace_bytes(int64_t n_max) {
   if (n_max < 0 || n_max >= (1ll << 31)) return 0;
   return hash_ws_bytes(n_max);

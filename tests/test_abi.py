@@ -135,3 +135,17 @@ def test_hash_and_cache_argument_errors():
     assert L.hctr_cache_create(4096, 16, 8, 4, 16, 4096, 10, None, C.byref(c)) == -1
     assert L.hctr_cache_create(4096, 1 << 20, 8, 4, 16, None, 10, None, C.byref(c)) == -2
     assert L.hctr_cache_query(None, 1, 1, 4096, None, 1, 1, 4096, None, 4096, 1 << 20, None) == -2
+
+
+def test_etc_argument_errors():
+    L = H.lib()
+    e = C.c_void_p()
+    assert L.hctr_etc_storage_bytes(0) == 0
+    assert L.hctr_etc_storage_bytes(1000) == 256 + 8192          # header + one key per row, rounded to 256
+    assert L.hctr_etc_workspace_bytes(-1) == 0
+    assert L.hctr_etc_workspace_bytes(1000) > 16000
+    assert L.hctr_etc_create(None, 4096, 8, 4096, 10, 4096, 1 << 20, None, C.byref(e)) == -2
+    assert L.hctr_etc_load(None, 4096, 4, None, 4096, 1 << 20, None) == -2
+    assert L.hctr_etc_dump(None, 1, None) == -2
+    assert L.hctr_etc_stats(None, None, None) == -2
+    assert L.hctr_hash_clear(None, None) == -2
