@@ -86,7 +86,7 @@ def hashed(h, args):
     out = torch.empty((B, S, D), device=DEV)
     smp = datagen.ZipfSampler(1 << 63, 1.05, device=DEV)
     dY = datagen.normal_grads(SEED, 1, nnz * D, device=DEV).view(B, S, D)
-    trace = []
+    per_batch = []
     keys = None
     for it in range(args.hash_batches):
         keys = datagen.open_space_keys(SEED, it, S, B, 1.05, device=DEV, sampler=smp)
@@ -98,11 +98,18 @@ def hashed(h, args):
         layer.backward_sgd(B, keys, dY, 0.01, ws=ws)    # find + dedup + reduce + SGD
         e[2].record()
         torch.cuda.synchronize()
-        if it % 8 == 0 or it == args.hash_batches - 1:
-            size = ht.size
-            trace.append(dict(batch=it, size=size, load_factor=size / cap, forward_ms=e[0].elapsed_time(e[1]),
-                              backward_ms=e[1].elapsed_time(e[2]),
-                              keys_per_s=nnz / (e[0].elapsed_time(e[2]) * 1e-3)))
+        per_batch.append((ht.size / cap, e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2])))
+    # windows of the load factor reached after the batch; the last window is the saturated regime:
+    # the table is at max_rows, new keys are rejected (find + refused inserts)
+    trace = []
+    edges = [0.0, 0.2, 0.4, 0.6, 0.8 - 1e-9, 1.0]
+    names = ["0-0.2", "0.2-0.4", "0.4-0.6", "0.6-0.8", "saturated (0.8)"]
+    for lo, hi, name in zip(edges[:-1], edges[1:], names):
+        sel = [(f, b) for lf, f, b in per_batch if lo < lf <= hi]
+        if sel:
+            f, b = float(np.median([x[0] for x in sel])), float(np.median([x[1] for x in sel]))
+            trace.append(dict(load_factor=name, batches=len(sel), forward_ms=f, backward_ms=b,
+                              keys_per_s=nnz / ((f + b) * 1e-3)))
     rows = torch.empty(nnz, dtype=torch.int64, device=DEV)
     find_ms = timeit(lambda: ht.insert_or_find(keys, False, rows=rows), 10, 2)
     return dict(workload="hashed open key space: capacity 1e8, max 8e7 rows, dim 64 fp32, 26 one-hot slots, "
@@ -128,27 +135,34 @@ def cache(h, args):
     sweep = []
     for batch in (1, 64, 1024, 16384):
         n = batch * S * hot
-        ks_by_mode = {m: [datagen.cache_keys(SEED, 1000 + 1000 * j + call + i, host_rows, n, 1.2, sampler=smp).cuda()
-                          for i in range(100)] for j, m in enumerate(("insert", "lookup_only"))}
+        reps = 1000 if batch <= 1024 else 200
+        ks_by_mode = {m: [datagen.cache_keys(SEED, 1000 + 2000 * j + call + i, host_rows, n, 1.2, sampler=smp).cuda()
+                          for i in range(reps)] for j, m in enumerate(("insert", "lookup_only"))}
         o = torch.empty((batch, S, D), device=DEV)
         ws = c.workspace(n)
         hm = torch.zeros(n, dtype=torch.uint8, device=DEV)
         res = {}
         for mode, insert in (("insert", True), ("lookup_only", False)):
             s0 = c.stats
-            lat = []
+            lat, gpu = [], []
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             for k in ks_by_mode[mode]:   # fresh keys for each mode, so lookup-only sees real misses too
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
+                e0.record()
                 c.query(batch, S, k, None, insert, out=o, hit_mask=hm, ws=ws)
+                e1.record()
                 torch.cuda.synchronize()
                 lat.append((time.perf_counter() - t0) * 1e6)
+                gpu.append(e0.elapsed_time(e1) * 1e3)
             s1 = c.stats
             res[mode] = dict(hit_rate=(s1[1] - s0[1]) / (s1[0] - s0[0]), p50_us=float(np.median(lat)),
-                             p99_us=float(np.percentile(lat, 99)), keys_per_s=n / np.median(lat) * 1e6)
-        sweep.append(dict(batch=batch, keys=n, **{f"{m}_{k}": v for m, r in res.items() for k, v in r.items()}))
+                             p99_us=float(np.percentile(lat, 99)), gpu_p50_us=float(np.median(gpu)),
+                             keys_per_s=n / np.median(lat) * 1e6)
+        sweep.append(dict(batch=batch, keys=n, queries=reps,
+                          **{f"{m}_{k}": v for m, r in res.items() for k, v in r.items()}))
     return dict(workload=f"inference cache: {host_rows} x 128 fp32 host table (pinned), cache 10% in 32-way sets, "
-                         "26 slots x hotness 4, Zipf 1.2; latency = host call + stream sync", sweep=sweep)
+                         "26 slots x hotness 4, Zipf 1.2; latency = host call + stream sync, gpu = event pair around the call", sweep=sweep)
 
 
 def mixed(h, args):
@@ -275,7 +289,7 @@ def main():
     ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group", "mixed", "etc"])
     ap.add_argument("--etc-passes", type=int, default=4)
     ap.add_argument("--host-rows", type=int, default=20_000_000)
-    ap.add_argument("--hash-batches", type=int, default=41)
+    ap.add_argument("--hash-batches", type=int, default=100)
     args = ap.parse_args()
     if not torch.cuda.is_available():
         print("bench_workloads.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)

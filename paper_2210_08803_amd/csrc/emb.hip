@@ -15,33 +15,41 @@ struct SlotTable {
   int64_t num[HCTR_MAX_SLOTS];
 };
 
-// First 256 bytes of an embedding workspace.
+// The count of keys without a row is kept in kInvalidParts partial counters behind the header (a
+// wave adds to the counter picked by its block index): thousands of waves adding to ONE address
+// queue up behind each other (about 10 ns each), which cost milliseconds when a third of a batch's
+// keys had no row.  The reader sums the parts.
+constexpr uint32_t kInvalidParts = 1024;
+
+// First 256 bytes of an embedding workspace; kInvalidParts 8-byte counters follow.
 struct EmbHeader {
-  unsigned long long invalid;  // keys without a row, running total since hctr_emb_workspace_init
+  unsigned long long reserved;
   long long num_unique;        // U of the last backward
   uint32_t n_valid;            // sorted positions holding a real row
   uint32_t n_long;             // rows whose carry is left to the block-wide kernel
   uint32_t pad[58];
 };
 static_assert(sizeof(EmbHeader) == 256, "header is one 256-byte block");
+constexpr size_t kEmbHeadBytes = sizeof(EmbHeader) + kInvalidParts * 8;
+
+// Adds a wave's count of keys without a row (call with the wave's total in every lane).
+__device__ __forceinline__ void add_invalid(EmbHeader* hdr, uint32_t wave_total) {
+  if ((threadIdx.x & 63) == 0 && wave_total != 0)
+    atomicAdd(reinterpret_cast<unsigned long long*>(hdr + 1) + (blockIdx.x & (kInvalidParts - 1)),
+              (unsigned long long)wave_total);
+}
 
 // Resets the dedup part of the header and clears the counters that later kernels add to.
 __global__ __launch_bounds__(256) void emb_init_header(EmbHeader* hdr, uint32_t* seg_off, int reset_invalid,
                                                        uint32_t* zero, uint32_t zero_count) {
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (reset_invalid && i < kInvalidParts) reinterpret_cast<unsigned long long*>(hdr + 1)[i] = 0;
   if (i == 0) {
-    if (reset_invalid) hdr->invalid = 0;
     hdr->num_unique = 0;
     hdr->n_valid = 0;
     if (seg_off) seg_off[0] = 0;
   }
   if (i < zero_count) zero[i] = 0u;
-}
-
-__device__ __forceinline__ void count_invalid(unsigned long long* counter, bool flag) {
-  const uint64_t m = __ballot(flag);
-  if (m != 0 && (threadIdx.x & 63) == (__ffsll((unsigned long long)m) - 1))
-    atomicAdd(counter, (unsigned long long)__popcll(m));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -106,7 +114,7 @@ __global__ __launch_bounds__(256) void fwd_onehot(const T* __restrict__ table, i
   if (blockIdx.y == 0 && __ballot(nbad != 0) != 0) {  // rare: add the groups' counts across the wave
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) nbad += __shfl_xor(nbad, d);
-    if ((threadIdx.x & 63) == 0) atomicAdd(&hdr->invalid, (unsigned long long)nbad);
+    add_invalid(hdr, nbad);
   }
 }
 
@@ -205,7 +213,7 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
   if (blockIdx.y == 0 && __ballot(nbad != 0) != 0) {
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) nbad += __shfl_xor(nbad, d);
-    if (lane == 0) atomicAdd(&hdr->invalid, (unsigned long long)nbad);
+    add_invalid(hdr, nbad);
   }
 }
 
@@ -320,7 +328,7 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
   if (__ballot(nbad != 0) != 0) {
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) nbad += __shfl_xor(nbad, d);
-    if ((threadIdx.x & 63) == 0) atomicAdd(&hdr->invalid, (unsigned long long)nbad);
+    add_invalid(hdr, nbad);
   }
 }
 
@@ -808,7 +816,7 @@ __global__ __launch_bounds__(256) void fwd_group(const GroupFwdArgs a, const int
   if (__ballot(nbad != 0) != 0) {   // every lane of the wave is here: the loop above has no early exit
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) nbad += __shfl_xor(nbad, d);
-    if ((threadIdx.x & 63) == 0) atomicAdd(&hdr->invalid, (unsigned long long)nbad);
+    add_invalid(hdr, nbad);
   }
 }
 
@@ -853,7 +861,7 @@ static EmbLayout emb_layout_raw(int64_t total_rows, int dmax, int64_t nnz_max, b
   L.sort = sort_plan((uint32_t)n, L.sort_bits);
   L.window = pick_window(nnz_max);
   L.n_windows = (uint32_t)ceil_div((int64_t)n, L.window);
-  L.header = at(sizeof(EmbHeader));
+  L.header = at(kEmbHeadBytes);
   L.kv0 = at(n * 8); L.kv1 = at(n * 8);
   L.hist = at(L.sort.hist_count * 4);
   L.seg_tiles = (uint32_t)ceil_div((int64_t)n, kSegTile);
@@ -1215,18 +1223,21 @@ HCTR_API hctr_status hctr_emb_dedup_view(const hctr_emb_desc* desc, int64_t batc
 HCTR_API hctr_status hctr_emb_workspace_init(void* ws, size_t ws_bytes, void* stream) {
   if (!ws) return fail(HCTR_E_WORKSPACE, "workspace is NULL");
   if ((uintptr_t)ws % 256 != 0) return fail(HCTR_E_WORKSPACE, "workspace must be 256-byte aligned");
-  if (ws_bytes < sizeof(EmbHeader)) return fail(HCTR_E_WORKSPACE, "workspace too small");
-  hipLaunchKernelGGL(emb_init_header, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream),
+  if (ws_bytes < kEmbHeadBytes) return fail(HCTR_E_WORKSPACE, "workspace too small");
+  hipLaunchKernelGGL(emb_init_header, dim3(kInvalidParts / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<EmbHeader*>(ws), (uint32_t*)nullptr, 1, (uint32_t*)nullptr, 0u);
   return launch_status("emb_init_header");
 }
 
 HCTR_API hctr_status hctr_emb_invalid_keys(const void* ws, size_t ws_bytes, void* stream, int64_t* count) {
   if (!ws || !count) return fail(HCTR_E_NULL_PTR, "NULL argument");
-  if (ws_bytes < sizeof(EmbHeader)) return fail(HCTR_E_WORKSPACE, "workspace too small");
-  unsigned long long v = 0;
-  HCTR_TRY_HIP(hipMemcpyAsync(&v, ws, sizeof(v), hipMemcpyDeviceToHost, static_cast<hipStream_t>(stream)));
+  if (ws_bytes < kEmbHeadBytes) return fail(HCTR_E_WORKSPACE, "workspace too small");
+  unsigned long long parts[kInvalidParts];
+  HCTR_TRY_HIP(hipMemcpyAsync(parts, static_cast<const char*>(ws) + sizeof(EmbHeader), sizeof(parts),
+                              hipMemcpyDeviceToHost, static_cast<hipStream_t>(stream)));
   HCTR_TRY_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  unsigned long long v = 0;
+  for (uint32_t i = 0; i < kInvalidParts; ++i) v += parts[i];
   *count = (int64_t)v;
   return HCTR_OK;
 }
