@@ -6,6 +6,7 @@
     python bench_workloads.py cache      # inference cache, Zipf 1.2, batch 1 / 64 / 1024 / 16384: hit rate, keys/s, p50 latency
     python bench_workloads.py mixed      # headline shape in mixed precision: fp16 table + fp32 master rows, fp16 out / dY
     python bench_workloads.py etc        # training cache staged in host memory: load / train / dump passes of 8 batches
+    python bench_workloads.py fwd_probe  # the forward kernel on key patterns of known locality (what bounds it)
     python bench_workloads.py group      # fused group: the 26 DLRM-sized tables with widths 128/64/32/16, dense one-hot input
 
 Each prints one JSON line.  Inputs are synthetic and seeded (datagen/), resident in HBM (the cache's
@@ -246,6 +247,34 @@ def etc(h, args):
                          "load + forward/backward + dump with eviction", keys_per_pass=per_pass * nnz, passes=passes)
 
 
+def fwd_probe(h, args):
+    D, total, nnz = 128, 40_000_000, 55296 * 26
+    table = torch.empty((total, D), dtype=torch.float32, device=DEV)
+    datagen.fill_table(SEED, table, 1 << 21)
+    out = torch.empty((nnz, 1, D), device=DEV)
+    layer = h.EmbeddingLayer(table, 1, h.SUM, [0], [total])
+    ws = layer.new_workspace(layer.workspace_bytes(nnz, nnz))
+    res = []
+
+    def run(name, keys):
+        keys = keys.contiguous()
+        ms = timeit(lambda: layer.forward(nnz, keys, out=out, ws=ws), 20, 3)
+        res.append(dict(pattern=name, us=ms * 1e3, algorithmic_GBs=nnz * (8 + 2 * D * 4) / ms / 1e6))
+
+    run("all keys name one row", torch.zeros(nnz, dtype=torch.int64, device=DEV))
+    for hot in (1 << 10, 1 << 14, 1 << 18, 1 << 22):
+        run(f"uniform over {hot} rows spread over the table", torch.randint(0, hot, (nnz,), device=DEV) * (total // hot))
+    run("distinct random rows", torch.randperm(total, device=DEV)[:nnz])
+    run("consecutive rows", torch.arange(nnz, device=DEV))
+    flat, src = out.view(-1), torch.empty(nnz * D, device=DEV)
+    ms = timeit(lambda: flat.copy_(src), 20, 3)
+    res.append(dict(pattern="torch device copy of the output size", us=ms * 1e3, read_write_GBs=nnz * D * 8 / ms / 1e6))
+    ms = timeit(lambda: flat.fill_(1.5), 20, 3)
+    res.append(dict(pattern="torch fill of the output", us=ms * 1e3, write_GBs=nnz * D * 4 / ms / 1e6))
+    return dict(workload="forward kernel (one slot, 40,000,000 x 128 fp32 rows, 1,437,696 one-hot keys) on key patterns "
+                         "of known locality", patterns=res)
+
+
 def group(h, args):
     rows_t = datagen.DLRM_TABLE_ROWS
     B, L = 55296, len(rows_t)
@@ -286,7 +315,7 @@ def group(h, args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group", "mixed", "etc"])
+    ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group", "mixed", "etc", "fwd_probe"])
     ap.add_argument("--etc-passes", type=int, default=4)
     ap.add_argument("--host-rows", type=int, default=20_000_000)
     ap.add_argument("--hash-batches", type=int, default=100)
@@ -295,7 +324,7 @@ def main():
         print("bench_workloads.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(2)
     import paper_2210_08803_amd as h
-    res = {"multihot": multihot, "hashed": hashed, "cache": cache, "group": group, "mixed": mixed, "etc": etc}[args.workload](h, args)
+    res = {"multihot": multihot, "hashed": hashed, "cache": cache, "group": group, "mixed": mixed, "etc": etc, "fwd_probe": fwd_probe}[args.workload](h, args)
     res["n_gpus"] = 1
     res["data"] = "synthetic"
     print(json.dumps(res), flush=True)
