@@ -143,7 +143,11 @@ __global__ __launch_bounds__(256) void first_flags(const u64* __restrict__ scrat
   first[m] = f;
 }
 
-// One new key per 8-lane group: assign the row, claim a slot in the main table, publish.
+// One new key per lane: assign the row, claim a slot in the main table, publish.  The key is known to
+// be absent, so the lane only needs an empty slot: it reads the 8 keys of the bucket, tries the
+// holes in slot order (a CAS that fails means another new key took the hole: next hole) and moves
+// on to the next bucket when none is left.  (A group of 8 lanes per key, as in the search, made
+// this kernel latency-bound: eight times the waves for the same dependent load -> CAS -> store.)
 __global__ __launch_bounds__(256) void hash_insert_new(u64* slots /* {key,row} pairs */,
                                                        uint32_t n_buckets, const HashHeader* table_hdr,
                                                        int64_t max_rows, u64* scratch,
@@ -153,43 +157,32 @@ __global__ __launch_bounds__(256) void hash_insert_new(u64* slots /* {key,row} p
                                                        const uint32_t* __restrict__ scr_slot,
                                                        const uint32_t* __restrict__ first,
                                                        const uint32_t* __restrict__ rank) {
-  const uint32_t m = (blockIdx.x * 256u + threadIdx.x) >> 3;
-  const int sub = threadIdx.x & 7;
-  const bool mine = m < hdr->n_miss && first[m] != 0;
-  u64 key = 0;
-  int64_t row = -1;
-  bool placing = false;
-  if (mine) {
-    key = (u64)keys[miss_pos[m]];
-    row = (int64_t)table_hdr->size + (int64_t)rank[m];
-    placing = row < max_rows;
-    if (!placing) row = -1;
-  }
-  uint32_t b = placing ? bucket_of(key, n_buckets) : 0u;
-  u64 seen = 0;        // this lane's view of its slot's key in the current bucket
-  bool fresh = true;   // view must be (re)loaded
-  for (uint64_t step = 0; step < 9ull * n_buckets; ++step) {
-    if (__ballot(placing) == 0) break;
-    if (placing && fresh) { seen = slots[2ull * ((uint64_t)b * 8u + sub)]; fresh = false; }
-    const uint32_t hole = group_bits(__ballot(placing && seen == kEmptyKey));
-    if (placing) {
-      if (hole) {
-        const int pick = __ffs(hole) - 1;
-        bool won = false;
-        if (sub == pick) {
-          u64* slot = &slots[2ull * ((uint64_t)b * 8u + sub)];
-          const u64 old = atomicCAS(slot, kEmptyKey, key);
-          if (old == kEmptyKey) { slot[1] = (u64)row; won = true; }
-          else seen = old;  // somebody else took it: remember, try the next hole
+  const uint32_t m = blockIdx.x * 256u + threadIdx.x;
+  if (m >= hdr->n_miss || first[m] == 0) return;
+  const u64 key = (u64)keys[miss_pos[m]];
+  int64_t row = (int64_t)table_hdr->size + (int64_t)rank[m];
+  bool placed = false;
+  if (row < max_rows) {
+    uint32_t b = bucket_of(key, n_buckets);
+    for (uint32_t step = 0; step < n_buckets && !placed; ++step) {   // ends: the table keeps 20 % of its slots empty
+      const u64x2* line = reinterpret_cast<const u64x2*>(slots) + (uint64_t)b * 8u;
+      u64 seen[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) seen[j] = line[j].x;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (!placed && seen[j] == kEmptyKey) {
+          u64* slot = &slots[2ull * ((uint64_t)b * 8u + j)];
+          if (atomicCAS(slot, kEmptyKey, key) == kEmptyKey) {
+            slot[1] = (u64)row;
+            placed = true;
+          }
         }
-        if (group_bits(__ballot(won))) placing = false;
-      } else {
-        b = (b + 1 == n_buckets) ? 0u : b + 1;
-        fresh = true;
       }
+      b = (b + 1 == n_buckets) ? 0u : b + 1;
     }
   }
-  if (mine && sub == 0) scratch[2ull * scr_slot[m] + 1] = (u64)row;  // verdict: row or -1 (all ones)
+  scratch[2ull * scr_slot[m] + 1] = placed ? (u64)row : ~0ull;  // verdict: row or -1 (all ones)
 }
 
 __global__ __launch_bounds__(256) void hash_resolve(const u64* __restrict__ scratch, HashWsHeader* hdr,
@@ -289,7 +282,7 @@ hctr_status hash_lookup(hctr_hash* h, const int64_t* keys, int64_t n64, int inse
   DedupBuffers B{flag, idx, miss_pos, scr_slot, first, rank, scan_tmp, scratch, L.scratch_cap_max,
                  &hdr->n_miss, &hdr->n_new};
   HCTR_TRY(dedup_first_appearance(keys, n, B, stream));
-  hipLaunchKernelGGL(hash_insert_new, dim3(find_blocks), dim3(256), 0, stream, h->slots, h->n_buckets,
+  hipLaunchKernelGGL(hash_insert_new, dim3(nb), dim3(256), 0, stream, h->slots, h->n_buckets,
                      (const HashHeader*)thdr, h->max_rows, scratch, (const HashWsHeader*)hdr, keys,
                      (const uint32_t*)miss_pos, (const uint32_t*)scr_slot, (const uint32_t*)first,
                      (const uint32_t*)rank);
