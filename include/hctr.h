@@ -304,7 +304,7 @@ hctr_status hctr_cache_create(void* storage, size_t storage_bytes, int64_t num_s
                               int32_t dim, const float* host_table, int64_t host_rows, void* stream,
                               hctr_cache** out);
 size_t hctr_cache_workspace_bytes(const hctr_cache* cache, int64_t nnz_max);
-/* Calls with at most max_keys keys (0..4096, default 4096; rows of at most 256 values) run as two
+/* Calls with at most max_keys keys (0..8192, default 8192; rows of at most 256 values) run as two
  * fused kernels instead of the general pipeline, because at that size launches cost more than
  * bytes.  Both paths give identical results; 0 switches the fused path off. */
 hctr_status hctr_cache_set_small_call_limit(hctr_cache* cache, int64_t max_keys);

@@ -39,7 +39,7 @@ namespace hctr {
 typedef unsigned long long u64;
 constexpr uint32_t kNoLine = 0xFFFFFFFFu;
 constexpr uint32_t kStaged = 0x80000000u;  // line_of value: the row is in the staging area at (v & ~kStaged)
-constexpr int kSmallMaxKeys = 4096;
+constexpr int kSmallMaxKeys = 8192;   // 104 KB of LDS in cache_insert_small
 
 struct CacheHeader {  // first 256 bytes of the cache storage
   u64 stats[6];       // queries, hits, (misses = queries - hits, filled in on the host), inserts, evictions, skipped
@@ -549,13 +549,23 @@ __global__ __launch_bounds__(1024) void cache_insert_small(u64* __restrict__ tag
       stamps[line] = epoch;
     }
   }
+  // rows cross the host link: each group of lanes keeps four row pieces in flight (latency-bound)
   constexpr int kCopyLanes = 32;   // lanes per row copy
-  for (uint32_t q = tid / kCopyLanes; q < Uq; q += T / kCopyLanes) {
-    const uint32_t line = pos_or_dst[q];
-    if (line == kNoLine) continue;
-    const float* src = host_table + keys[ukey_pos[q]] * D;
-    float* to = data + (int64_t)line * D;
-    for (int col = (tid % kCopyLanes) * 4; col < D; col += kCopyLanes * 4) store4(to + col, load4(src + col));
+  constexpr uint32_t kRowsAtOnce = T / kCopyLanes;
+  for (uint32_t q0 = tid / kCopyLanes; q0 < Uq; q0 += 4 * kRowsAtOnce) {
+    for (int col = (tid % kCopyLanes) * 4; col < D; col += kCopyLanes * 4) {
+      f32x4 v[4];
+      uint32_t line[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t q = q0 + u * kRowsAtOnce;
+        line[u] = q < Uq ? pos_or_dst[q] : kNoLine;
+        if (line[u] != kNoLine) v[u] = load4(host_table + keys[ukey_pos[q]] * D + col);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (line[u] != kNoLine) store4(data + (int64_t)line[u] * D + col, v[u]);
+    }
   }
   if (tid < 3 && counters[tid]) atomicAdd(&hdr->stats[3 + tid], (u64)counters[tid]);
 }

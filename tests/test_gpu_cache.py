@@ -78,7 +78,7 @@ def test_hand_worked_trace():
         assert gpu.stats == call["stats"]
 
 
-@pytest.mark.parametrize("small_limit", [0, 4096], ids=["general", "fused-small"])
+@pytest.mark.parametrize("small_limit", [0, 8192], ids=["general", "fused-small"])
 @pytest.mark.parametrize("num_sets,ways,dim", [(64, 8, 16), (1, 4, 8), (37, 1, 32), (16, 32, 128), (5, 64, 4), (300, 2, 260)])
 def test_zipf_traffic_matches_the_simulation(num_sets, ways, dim, small_limit):
     host_rows = 5000
@@ -95,7 +95,7 @@ def test_zipf_traffic_matches_the_simulation(num_sets, ways, dim, small_limit):
     assert hits > 0
 
 
-@pytest.mark.parametrize("small_limit", [0, 4096], ids=["general", "fused-small"])
+@pytest.mark.parametrize("small_limit", [0, 8192], ids=["general", "fused-small"])
 def test_csr_bags_and_batch_of_one_key(small_limit):
     host_rows, dim = 800, 64
     p = Pair(32, 4, pinned_table(host_rows, dim), small_limit)
@@ -109,7 +109,7 @@ def test_csr_bags_and_batch_of_one_key(small_limit):
         p.query(rng.integers(0, 50, 1), 1, what=f"single {it}")   # classical per-access LRU traffic
 
 
-@pytest.mark.parametrize("small_limit", [0, 4096], ids=["general", "fused-small"])
+@pytest.mark.parametrize("small_limit", [0, 8192], ids=["general", "fused-small"])
 def test_set_overflow_in_one_call_skips_the_surplus(small_limit):
     host_rows, dim = 4096, 8
     p = Pair(2, 4, pinned_table(host_rows, dim), small_limit)
@@ -125,7 +125,7 @@ def test_paths_switch_back_and_forth_on_one_cache():
     host_rows, dim = 60000, 64
     p = Pair(128, 16, pinned_table(host_rows, dim))
     smp = datagen.ZipfSampler(host_rows, 1.2)
-    for it, batch in enumerate([300, 2, 40, 300, 1, 39, 40, 300]):     # 26*4*39 = 4056 <= 4096 < 26*4*40
+    for it, batch in enumerate([300, 2, 79, 300, 1, 78, 79, 300]):     # 26*4*78 = 8112 <= 8192 < 26*4*79
         n_bags = batch * 26
         keys = datagen.cache_keys(SEED, 50 + it, host_rows, n_bags * 4, 1.2, sampler=smp).numpy()
         p.query(keys, n_bags, what=f"mixed {it} (batch {batch})")
@@ -143,7 +143,7 @@ def _state_equal(p, what):
     assert p.gpu.stats == p.ref.stats.tolist(), f"{what}: stats differ"
 
 
-@pytest.mark.parametrize("small_limit", [0, 4096], ids=["general", "fused-small"])
+@pytest.mark.parametrize("small_limit", [0, 8192], ids=["general", "fused-small"])
 def test_insert_only_calls(small_limit):
     host_rows, dim = 3000, 32
     p = Pair(16, 8, pinned_table(host_rows, dim), small_limit)
@@ -202,7 +202,7 @@ def test_refresh_rereads_the_host_table():
     p.query(datagen.cache_keys(SEED, 710, host_rows, 500, 1.2, sampler=smp).numpy(), 125, what="query after refresh")
 
 
-@pytest.mark.parametrize("small_limit", [0, 4096], ids=["general", "fused-small"])
+@pytest.mark.parametrize("small_limit", [0, 8192], ids=["general", "fused-small"])
 def test_async_query_signals_results_before_insertion(small_limit):
     host_rows, dim = 4000, 32
     p = Pair(64, 4, pinned_table(host_rows, dim), small_limit)
