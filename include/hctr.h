@@ -26,7 +26,7 @@
  *              returns a thread-local message for the last failing call on this thread.
  *   Layout     Bags are numbered bag = sample * num_slots + slot.  Keys are int64, bag-major.
  *              CSR offsets are int64 [n_bags + 1], offsets[0] = 0, offsets[n_bags] = nnz,
- *              non-decreasing (not checked).  offsets == NULL means exactly one key per bag.
+ *              non-decreasing (not checked by the compute calls, see hctr_check_offsets).  offsets == NULL means exactly one key per bag.
  *              Pooled outputs and upstream gradients are [batch, num_slots, dim] row-major, fp32
  *              (or fp16 when the layer's io_dtype says so).
  *              Tables are [total_rows, dim] row-major in fp32 or fp16, 16-byte aligned.
@@ -162,6 +162,15 @@ hctr_status hctr_emb_backward_apply(const hctr_emb_desc* desc, int64_t batch, co
 hctr_status hctr_emb_dedup_view(const hctr_emb_desc* desc, int64_t batch, int64_t nnz, void* ws,
                                 size_t ws_bytes, const int64_t** num_unique,
                                 const uint32_t** uniq_rows, const uint32_t** seg_offsets);
+
+/*
+ * The compute calls do not check CSR offsets (a kernel that trusts broken offsets reads outside its
+ * buffers).  This call does, for callers that cannot vouch for their input: offsets device
+ * [n_bags + 1] must start at 0, end at nnz and never decrease; otherwise HCTR_E_INVALID_ARG.  ws:
+ * device, 8 bytes, 8-byte aligned.  Waits for the stream.
+ */
+hctr_status hctr_check_offsets(const int64_t* offsets, int64_t n_bags, int64_t nnz, void* ws, size_t ws_bytes,
+                               void* stream);
 
 /* Number of keys without a row seen by all forward and backward calls on `ws` since
  * hctr_emb_workspace_init (host int64; waits for the stream). */

@@ -77,6 +77,7 @@ def lib() -> C.CDLL:
         "hctr_emb_backward_apply": (i32, [dp, i64, p, i64, p, f32, p, sz, p]),
         "hctr_emb_dedup_view": (i32, [dp, i64, i64, p, sz, C.POINTER(p), C.POINTER(p), C.POINTER(p)]),
         "hctr_emb_invalid_keys": (i32, [p, sz, p, C.POINTER(i64)]),
+        "hctr_check_offsets": (i32, [p, i64, i64, p, sz, p]),
         "hctr_hash_storage_bytes": (sz, [i64]),
         "hctr_hash_create": (i32, [p, sz, i64, i64, p, C.POINTER(p)]),
         "hctr_hash_workspace_bytes": (sz, [i64]),
@@ -115,7 +116,7 @@ def lib() -> C.CDLL:
 EXPORTS = [
     "hctr_emb_workspace_bytes", "hctr_emb_workspace_init", "hctr_emb_forward", "hctr_emb_backward_sgd", "hctr_emb_backward_dedup",
     "hctr_emb_backward_apply", "hctr_emb_dedup_view",
-    "hctr_emb_invalid_keys", "hctr_group_workspace_bytes", "hctr_group_forward", "hctr_group_backward_sgd",
+    "hctr_emb_invalid_keys", "hctr_check_offsets", "hctr_group_workspace_bytes", "hctr_group_forward", "hctr_group_backward_sgd",
     "hctr_hash_storage_bytes", "hctr_hash_create", "hctr_hash_workspace_bytes",
     "hctr_hash_insert_or_find", "hctr_hash_size", "hctr_hash_destroy", "hctr_hash_clear", "hctr_etc_storage_bytes",
     "hctr_etc_workspace_bytes", "hctr_etc_create", "hctr_etc_load", "hctr_etc_dump", "hctr_etc_stats",
@@ -142,6 +143,12 @@ def _stream(stream: Optional[torch.cuda.Stream]) -> int:
 
 def _ws(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(256, nbytes), dtype=torch.uint8, device=device)
+
+
+def check_offsets(offsets: torch.Tensor, nnz: int, stream=None) -> None:
+    """hctr_check_offsets: raises HctrError unless offsets is a valid CSR offset array for nnz keys."""
+    ws = torch.empty(1, dtype=torch.int64, device=offsets.device)
+    _check(lib().hctr_check_offsets(_ptr(offsets), offsets.numel() - 1, int(nnz), _ptr(ws), 8, _stream(stream)))
 
 
 class HashTable:

@@ -836,6 +836,24 @@ __global__ __launch_bounds__(256) void group_dense_offsets(const GroupHotness h,
   if (i == n_bags) offsets[i] = (int64_t)(n_bags / h.L) * h.per_sample;
 }
 
+// Counts the violations of the CSR contract: offsets[0] = 0, offsets[n_bags] = nnz, non-decreasing.
+__global__ __launch_bounds__(256) void check_offsets(const int64_t* __restrict__ offsets, uint64_t n_bags,
+                                                     int64_t nnz, unsigned long long* bad) {
+  __shared__ uint32_t blk;
+  if (threadIdx.x == 0) blk = 0;
+  __syncthreads();
+  uint32_t mine = 0;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i <= n_bags; i += (uint64_t)gridDim.x * 256u) {
+    const int64_t o = offsets[i];
+    if (i == 0 && o != 0) ++mine;
+    if (i == n_bags && o != nnz) ++mine;
+    if (i < n_bags && offsets[i + 1] < o) ++mine;
+  }
+  if (mine) atomicAdd(&blk, mine);
+  __syncthreads();
+  if (threadIdx.x == 0 && blk) atomicAdd(bad, (unsigned long long)blk);
+}
+
 // ------------------------------------------------------------------------------------------------
 // Host side
 // ------------------------------------------------------------------------------------------------
@@ -1434,4 +1452,24 @@ HCTR_API hctr_status hctr_group_backward_sgd(const hctr_group_desc* desc, int64_
   if (desc->table_dtype == HCTR_F32) group_launch_reduce<float>(P, L, w, skv, csr, dY, lr, stream);
   else group_launch_reduce<__half>(P, L, w, skv, csr, dY, lr, stream);
   return launch_status("hctr_group_backward_sgd");
+}
+
+HCTR_API hctr_status hctr_check_offsets(const int64_t* offsets, int64_t n_bags, int64_t nnz, void* ws,
+                                        size_t ws_bytes, void* stream_) {
+  if (!offsets) return fail(HCTR_E_NULL_PTR, "offsets is NULL");
+  if (n_bags < 0 || nnz < 0) return fail(HCTR_E_INVALID_ARG, "n_bags %lld / nnz %lld negative", (long long)n_bags,
+                                         (long long)nnz);
+  if (!ws || ws_bytes < 8 || (uintptr_t)ws % 8 != 0) return fail(HCTR_E_WORKSPACE, "ws must hold 8 aligned bytes");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  unsigned long long* bad = static_cast<unsigned long long*>(ws);
+  unsigned long long v = 0;
+  HCTR_TRY_HIP(hipMemcpyAsync(bad, &v, sizeof(v), hipMemcpyHostToDevice, stream));
+  const uint32_t blocks = (uint32_t)std::min<int64_t>(ceil_div(n_bags + 1, 256), 2048);
+  hipLaunchKernelGGL(check_offsets, dim3(blocks), dim3(256), 0, stream, offsets, (uint64_t)n_bags, nnz, bad);
+  HCTR_TRY(launch_status("check_offsets"));
+  HCTR_TRY_HIP(hipMemcpyAsync(&v, bad, sizeof(v), hipMemcpyDeviceToHost, stream));
+  HCTR_TRY_HIP(hipStreamSynchronize(stream));
+  if (v != 0)
+    return fail(HCTR_E_INVALID_ARG, "offsets break the CSR contract at %llu place(s) (first 0, last nnz, non-decreasing)", v);
+  return HCTR_OK;
 }

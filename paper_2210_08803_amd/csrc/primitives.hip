@@ -126,7 +126,7 @@ __global__ __launch_bounds__(NT) void sort_hist(const uint64_t* __restrict__ kv,
   for (uint32_t d = threadIdx.x; d < bins; d += NT) h[d] = 0;
   __syncthreads();
 #pragma unroll 4
-  for (int i = 0; i < kSortTile / NT; ++i) {
+  for (int i = 0; i < (int)(kSortTile / NT); ++i) {
     const uint32_t idx = base + i * NT + threadIdx.x;
     if (idx < n) atomicAdd(&h[(uint32_t)(kv[idx] >> (32 + shift)) & mask], 1u);
   }

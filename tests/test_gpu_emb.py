@@ -203,3 +203,18 @@ def test_split_backward_beside_forward_on_two_streams():
     ra, ca = a.dedup_result(batch, keys.numel())
     rb, cb = b.dedup_result(batch, keys.numel(), ws=ws)
     assert torch.equal(ra, rb) and torch.equal(ca, cb)
+
+
+def test_check_offsets_accepts_valid_and_names_broken_input():
+    h = H()
+    good = torch.tensor([0, 2, 2, 5, 9], dtype=torch.int64, device="cuda")
+    h.check_offsets(good, 9)
+    big = torch.arange(0, 3_000_001, dtype=torch.int64, device="cuda") * 3
+    h.check_offsets(big, 9_000_000)
+    for bad, nnz in [([1, 2, 2, 5, 9], 9), ([0, 2, 2, 5, 9], 10), ([0, 3, 2, 5, 9], 9), ([0, 2, 2, 5, -1], -1 + 10)]:
+        with pytest.raises(h.HctrError) as e:
+            h.check_offsets(torch.tensor(bad, dtype=torch.int64, device="cuda"), nnz)
+        assert e.value.status == -1 and "CSR" in str(e.value)
+    big[1_500_000] = 0
+    with pytest.raises(h.HctrError):
+        h.check_offsets(big, 9_000_000)
