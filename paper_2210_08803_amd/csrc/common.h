@@ -97,8 +97,12 @@ inline uint32_t* sort_aux_tot(const SortPlan& plan, uint32_t* aux, int p) {
 inline uint32_t* sort_aux_sup(const SortPlan& plan, uint32_t* aux, int p) {
   return sort_aux_tot(plan, aux, p) + plan.max_bins;
 }
-// first_hist_done: the caller has already filled hist[tile][digit] and sup for pass 0 (digit =
-// low digit_bits[0] bits of the key) while producing buf0.
+// Above kSortDirectSuperMax groups the group sums are built from the tile histograms and scanned by
+// kernels of their own; the histogram kernels then add nothing to sup (pass NULL).
+inline bool sort_scans_groups(const SortPlan& plan) { return plan.n_super > kSortDirectSuperMax; }
+// first_hist_done: the caller has already filled hist[tile][digit] (and, unless
+// sort_scans_groups(plan), added it to sup) for pass 0 (digit = low digit_bits[0] bits of the key)
+// while producing buf0.
 hctr_status radix_sort_u64(const SortPlan& plan, const uint32_t* n_dev, uint64_t* buf0, uint64_t* buf1,
                            uint32_t* hist, uint32_t* aux, bool aux_is_zero, hipStream_t stream,
                            bool first_hist_done = false);

@@ -323,7 +323,7 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
   for (uint32_t d = threadIdx.x; d < bins; d += NT) {
     const uint32_t c = h[d];
     hrow[d] = c;
-    if (c) atomicAdd(&srow[d], c);
+    if (c && sup) atomicAdd(&srow[d], c);
   }
   if (__ballot(nbad != 0) != 0) {
 #pragma unroll
@@ -1147,12 +1147,13 @@ static hctr_status dedup_core(const int64_t* keys, const int64_t* rows64, const 
   // About one tile per compute unit: 1024-thread blocks, so a wave's serial share is 4 rounds, not 16.
   const bool wide = L.sort.n_blocks <= kSortWideMaxTiles;
   const uint32_t bins0 = 1u << L.sort.digit_bits[0];
+  uint32_t* sup0 = sort_scans_groups(L.sort) ? nullptr : sort_aux_sup(L.sort, aux, 0);
   if (wide && offsets == nullptr)
     hipLaunchKernelGGL((bwd_rows<1024>), dim3(L.sort.n_blocks), dim3(1024), 0, stream, keys, rows64, offsets, n,
-                       n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sort_aux_sup(L.sort, aux, 0));
+                       n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sup0);
   else
     hipLaunchKernelGGL((bwd_rows<256>), dim3(L.sort.n_blocks), dim3(256), 0, stream, keys, rows64, offsets, n,
-                       n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sort_aux_sup(L.sort, aux, 0));
+                       n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sup0);
   HCTR_TRY(radix_sort_u64(L.sort, nullptr, kv0, kv1, hist, aux, true, stream, true));
   const uint64_t* skv = (L.sort.passes & 1) ? kv1 : kv0;
   if (wide) {

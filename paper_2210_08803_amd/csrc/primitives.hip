@@ -90,18 +90,20 @@ hctr_status exclusive_scan_u32(const uint32_t* in, uint32_t* out, uint32_t n, ui
 
 // ------------------------------------------------------------------------------------------------
 // Radix sort of packed (key << 32 | value) words by the key's low `bits` bits: LSD, digits of up
-// to 10 bits (28-bit row ids take 3 passes), tiles of 4096 words per 256-thread block, two kernels
-// per pass and no device-wide scan kernel in between:
+// to 10 bits (28-bit row ids take 3 passes), tiles of 4096 words per block, two kernels per pass
+// up to 48 groups of 16 tiles (about 3 M words) and no device-wide scan kernel in between:
 //   sort_hist     counts the tile's digits into hist[tile][digit] (block-major, coalesced) and adds
-//                 them to tot[digit] and to sup[tile / 16][digit] (sums over groups of 16 tiles);
-//   sort_scatter  derives the tile's global offsets on its own - exclusive scan of tot in LDS, plus
-//                 the sup rows of earlier groups, plus the hist rows of earlier tiles of its group
-//                 (at most n_tiles/16 + 15 coalesced row reads) - then ranks and scatters.
+//                 them to sup[tile / 16][digit] (sums over groups of 16 tiles);
+//   sort_scatter  derives the tile's global offsets on its own - digit totals = sum of all sup
+//                 rows, scanned in LDS, plus the sup rows of earlier groups, plus the hist rows of
+//                 earlier tiles of its group (at most n_tiles/16 + 15 coalesced row reads) - then
+//                 ranks and scatters.
+// Beyond that, sort_sum_groups / sort_scan_groups build and scan the group sums between the two.
 // Each wave of a block owns a run of consecutive words and ranks them 64 at a time with ballot-based
 // digit matching, so equal digits keep their input order (stable).  Blocks have 256 threads (waves
 // own 1024 words) when there are tiles enough to fill the chip several times over, else 1024
-// threads (waves own 256 words): with about one tile per compute unit the pass is bound by the
-// length of a wave's serial ranking, not by bandwidth.
+// threads for the counting kernel: with about one tile per compute unit it is bound by the length
+// of a thread's serial loop, not by bandwidth (the scatter measured faster with 256 threads).
 // ------------------------------------------------------------------------------------------------
 constexpr int kSortThreads = 256;
 constexpr int kSortWideThreads = 1024;
@@ -136,31 +138,74 @@ __global__ __launch_bounds__(NT) void sort_hist(const uint64_t* __restrict__ kv,
   for (uint32_t d = threadIdx.x; d < bins; d += NT) {
     const uint32_t c = h[d];
     row[d] = c;
-    if (c) atomicAdd(&srow[d], c);
+    if (c && sup) atomicAdd(&srow[d], c);
   }
 }
 
-// For many tiles the per-group sums are scanned once per pass (thread per digit, walking the
-// groups) so that a scatter block reads one row instead of one per earlier group.
-__global__ __launch_bounds__(256) void sort_scan_sup(uint32_t* __restrict__ sup, uint32_t* __restrict__ tot,
-                                                     uint32_t bins, uint32_t n_super) {
-  const uint32_t d = blockIdx.x * 256u + threadIdx.x;
-  if (d >= bins) return;
-  uint32_t run = 0;
-  uint32_t sb = 0;
-  for (; sb + 8 <= n_super; sb += 8) {
-    uint32_t v[8];
+// For many tiles the group sums get kernels of their own, so that a scatter block reads one row
+// instead of one per earlier group.  sort_sum_groups: one block per group adds the histograms of
+// its (at most 16) tiles.  sort_scan_groups: a block of 1024 threads owns 32 digits; its threads
+// form 32 chunks of consecutive groups x 32 digits, sum their chunk, combine the chunk sums through
+// LDS and then turn their chunk into running sums (sup[g][d] = count of digit d in all earlier
+// groups) - every load of a chunk is independent of the others, where one thread per digit walking
+// all groups took 88 us per pass for 1,300 groups.
+__global__ __launch_bounds__(256) void sort_sum_groups(const uint32_t* __restrict__ hist, uint32_t n_host,
+                                                       const uint32_t* __restrict__ n_dev, uint32_t bins,
+                                                       uint32_t* __restrict__ sup) {
+  const uint32_t n = n_dev ? *n_dev : n_host;
+  const uint32_t n_tiles = (uint32_t)(((uint64_t)n + kSortTile - 1) / kSortTile);
+  const uint32_t g = blockIdx.x;
+  const uint32_t d0 = threadIdx.x * 4;
+  if (d0 >= bins) return;
+  u32x4v acc = {0, 0, 0, 0}, v[kSortSuper];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) v[k] = sup[(uint64_t)(sb + k) * bins + d];
+  for (uint32_t k = 0; k < kSortSuper; ++k) {
+    const uint32_t t = g * kSortSuper + k;
+    v[k] = t < n_tiles ? *reinterpret_cast<const u32x4v*>(hist + (uint64_t)t * bins + d0) : u32x4v{0, 0, 0, 0};
+  }
 #pragma unroll
-    for (int k = 0; k < 8; ++k) { sup[(uint64_t)(sb + k) * bins + d] = run; run += v[k]; }
+  for (uint32_t k = 0; k < kSortSuper; ++k) acc += v[k];
+  *reinterpret_cast<u32x4v*>(sup + (uint64_t)g * bins + d0) = acc;
+}
+
+__global__ __launch_bounds__(1024) void sort_scan_groups(uint32_t* __restrict__ sup, uint32_t* __restrict__ tot,
+                                                         uint32_t bins, uint32_t n_super) {
+  __shared__ uint32_t part[32][33];
+  const uint32_t dd = threadIdx.x & 31, c = threadIdx.x >> 5;
+  const uint32_t d = blockIdx.x * 32 + dd;   // bins is a multiple of 4 and may be below 32: guard below
+  const uint32_t per = (n_super + 31) / 32;
+  const uint32_t g0 = c * per, g1 = (g0 + per < n_super) ? g0 + per : n_super;
+  uint32_t sum = 0;
+  if (d < bins) {
+    for (uint32_t g = g0; g < g1; g += 8) {
+      uint32_t v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = g + k < g1 ? sup[(uint64_t)(g + k) * bins + d] : 0u;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) sum += v[k];
+    }
   }
-  for (; sb < n_super; ++sb) {
-    const uint32_t v = sup[(uint64_t)sb * bins + d];
-    sup[(uint64_t)sb * bins + d] = run;
-    run += v;
+  part[c][dd] = sum;
+  __syncthreads();
+  uint32_t run = 0, all = 0;
+  for (uint32_t cc = 0; cc < 32; ++cc) {
+    const uint32_t p = part[cc][dd];
+    if (cc < c) run += p;
+    all += p;
   }
-  tot[d] = run;
+  if (d < bins) {
+    if (c == 0) tot[d] = all;
+    for (uint32_t g = g0; g < g1; g += 8) {
+      uint32_t v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = g + k < g1 ? sup[(uint64_t)(g + k) * bins + d] : 0u;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        if (g + k < g1) sup[(uint64_t)(g + k) * bins + d] = run;
+        run += v[k];
+      }
+    }
+  }
 }
 
 template <int DBITS, int NT>
@@ -307,7 +352,7 @@ hctr_status radix_sort_u64(const SortPlan& plan, const uint32_t* n_dev, uint64_t
   if (!aux_is_zero)
     hipLaunchKernelGGL(sort_zero_aux, dim3((uint32_t)ceil_div((int64_t)plan.aux_count, 256)), dim3(256), 0,
                        stream, aux, (uint32_t)plan.aux_count);
-  const int scan_sup = plan.n_super > kSortDirectSuperMax ? 1 : 0;
+  const int scan_sup = sort_scans_groups(plan) ? 1 : 0;
   const bool wide = plan.n_blocks <= kSortWideMaxTiles;
   int shift = 0;
   for (int p = 0; p < plan.passes; ++p) {
@@ -320,17 +365,21 @@ hctr_status radix_sort_u64(const SortPlan& plan, const uint32_t* n_dev, uint64_t
     const uint32_t* chist = hist;
     const uint32_t* ctot = tot;
     const uint32_t* csup = sup;
+    uint32_t* hist_sup = scan_sup ? nullptr : sup;   // the scanned path builds sup from the histograms
     if (!(p == 0 && first_hist_done)) {
       if (wide)
         hipLaunchKernelGGL((sort_hist<kSortWideThreads>), dim3(plan.n_blocks), dim3(kSortWideThreads), 0, stream,
-                           in, plan.n_max, n_dev, shift, bins, hist, sup);
+                           in, plan.n_max, n_dev, shift, bins, hist, hist_sup);
       else
         hipLaunchKernelGGL((sort_hist<kSortThreads>), dim3(plan.n_blocks), dim3(kSortThreads), 0, stream, in,
-                           plan.n_max, n_dev, shift, bins, hist, sup);
+                           plan.n_max, n_dev, shift, bins, hist, hist_sup);
     }
-    if (scan_sup)
-      hipLaunchKernelGGL(sort_scan_sup, dim3((uint32_t)ceil_div(bins, 256)), dim3(256), 0, stream, sup, tot,
+    if (scan_sup) {
+      hipLaunchKernelGGL(sort_sum_groups, dim3(plan.n_super), dim3(256), 0, stream, chist, plan.n_max, n_dev, bins,
+                         sup);
+      hipLaunchKernelGGL(sort_scan_groups, dim3((uint32_t)ceil_div(bins, 32)), dim3(1024), 0, stream, sup, tot,
                          bins, plan.n_super);
+    }
 #define HCTR_SCATTER(DB, NT)                                                                             \
   hipLaunchKernelGGL((sort_scatter<DB, NT>), dim3(plan.n_blocks), dim3(NT), 0, stream, in, buf[dst],     \
                      plan.n_max, n_dev, shift, bins, chist, ctot, csup, plan.n_super, scan_sup)
