@@ -232,9 +232,12 @@ def main():
                                "Zipf %g, sum, fwd + dedup/segmented-reduce bwd + SGD%s"
                                % (total, args.alpha, "" if args.scale == 1.0 else f" (tables scaled x{args.scale})"),
                    "batch": BATCH, "slots": S, "dim": DIM, "keys_per_step": nnz, "distinct_rows_per_step": int(U)},
-        "roofline": {"bound": "hbm", "kernel": "fwd_onehot<float,32,4>", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": fwd_bytes, "avg_launch_ms": float(fwd_ms.mean())},
+        "roofline": {"bound": "hbm", "kernel": "fwd_onehot<float,float,32,4>", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": fwd_bytes,
+                     # the same with every distinct row read once only (what no cache could go below)
+                     "compulsory_bytes_per_launch": nnz * (8 + DIM * 4) + int(U) * DIM * 4,
+                     "avg_launch_ms": float(fwd_ms.mean())},
         "phases": {"schedule": args.schedule,
                    "forward_ms": float(fwd_ms.mean()), "forward_ms_min": float(fwd_ms.min()),
                    "backward_ms" if args.schedule == "serial" else "backward_apply_ms": float(bwd_ms.mean()),
