@@ -218,3 +218,31 @@ def test_check_offsets_accepts_valid_and_names_broken_input():
     big[1_500_000] = 0
     with pytest.raises(h.HctrError):
         h.check_offsets(big, 9_000_000)
+
+
+@pytest.mark.parametrize("hot", [None, (0, 5)])
+def test_no_key_has_a_row(hot):
+    """Every key outside its table: zeros out, table untouched, an empty dedup result, all keys counted."""
+    h = H()
+    rows, dim, batch, S = [50, 7, 300], 32, 700, 3
+    ro = datagen.row_offsets(rows)
+    table = datagen.table_rows_at(SEED, torch.arange(int(ro[-1])), dim, torch.float32)
+    n_bags = batch * S
+    if hot is None:
+        offsets, nnz = None, n_bags
+    else:
+        offsets = datagen.multihot_offsets(SEED, 3, n_bags, hot[0], hot[1])
+        nnz = int(offsets[-1])
+    g = np.random.default_rng(4)
+    keys = torch.from_numpy(g.choice([-1, -7, 300, 10 ** 12], nnz).astype(np.int64))
+    d_table = to_dev(table)
+    layer = h.EmbeddingLayer(d_table, S, h.MEAN, ro[:-1].copy(), rows)
+    d_off = None if offsets is None else to_dev(offsets)
+    out = layer.forward(batch, to_dev(keys), d_off)
+    assert torch.count_nonzero(out) == 0
+    dY = datagen.normal_grads(SEED, 3, n_bags * dim).view(n_bags, dim)
+    layer.backward_sgd(batch, to_dev(keys), to_dev(dY), 0.5, d_off)
+    assert torch.equal(d_table.cpu(), table)
+    assert layer.invalid_keys() == 2 * nnz
+    uniq, cnt = layer.dedup_result(batch, nnz)
+    assert uniq.numel() == 0 and cnt.numel() == 0
