@@ -81,7 +81,7 @@ def hashed(h, args):
     ht = h.HashTable(cap, max_rows)
     table = torch.empty((max_rows, D), dtype=torch.float32, device=DEV)
     datagen.fill_table(SEED, table, 1 << 22)
-    layer = h.EmbeddingLayer(table, S, h.SUM, hash_table=ht, insert_on_miss=True)
+    layer = h.EmbeddingLayer(table, S, h.SUM, hash_table=ht, insert_on_miss=True, reuse_forward_rows=True)
     nnz = B * S
     ws = layer.new_workspace(layer.workspace_bytes(B, nnz))
     out = torch.empty((B, S, D), device=DEV)
@@ -96,7 +96,7 @@ def hashed(h, args):
         e[0].record()
         layer.forward(B, keys, out=out, ws=ws)          # insert-or-find + gather
         e[1].record()
-        layer.backward_sgd(B, keys, dY, 0.01, ws=ws)    # find + dedup + reduce + SGD
+        layer.backward_sgd(B, keys, dY, 0.01, ws=ws)    # (rows of the forward) dedup + reduce + SGD
         e[2].record()
         torch.cuda.synchronize()
         per_batch.append((ht.size / cap, e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2])))
@@ -212,7 +212,7 @@ def etc(h, args):
     nnz = B * S
     max_rows = 6_000_000
     cache = h.EmbeddingTrainingCache(host, max_rows, capacity=8_000_000)
-    layer = cache.layer(S, h.SUM)
+    layer = cache.layer(S, h.SUM, reuse_forward_rows=True)
     smp = datagen.ZipfSampler(host_rows, 1.05)
     dY = datagen.normal_grads(SEED, 9, nnz * D, device=DEV).view(B, S, D)
     out = torch.empty((B, S, D), device=DEV)

@@ -88,6 +88,10 @@ typedef struct {
   int32_t io_dtype;             /* hctr_dtype of out and dY: HCTR_F32 (0), or HCTR_F16 for layers
                                    downstream that compute in half precision (section 1, "Mixed
                                    precision training"); sums are always formed in fp32 */
+  int32_t reuse_forward_rows;   /* hashed mode: 1 = backward takes the rows that the last
+                                   hctr_emb_forward on the same workspace found, instead of looking
+                                   the keys up again.  The caller vouches that it was given the same
+                                   keys (same nnz) and that no call has used the workspace since */
   float* master;                /* device [total_rows, dim] fp32 copy of an fp16 table, or NULL.
                                    With it backward updates the master row in fp32 and stores its
                                    rounding (nearest even) as the table row; forward reads only

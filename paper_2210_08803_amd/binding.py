@@ -28,7 +28,7 @@ class _EmbDesc(C.Structure):
         ("table", C.c_void_p), ("total_rows", C.c_int64),
         ("slot_row_base", C.POINTER(C.c_int64)), ("slot_num_rows", C.POINTER(C.c_int64)),
         ("hash", C.c_void_p), ("insert_on_miss", C.c_int32), ("io_dtype", C.c_int32),
-        ("master", C.c_void_p),
+        ("reuse_forward_rows", C.c_int32), ("master", C.c_void_p),
     ]
 
 
@@ -204,7 +204,8 @@ class EmbeddingLayer:
     def __init__(self, table: torch.Tensor, num_slots: int, combiner: int = SUM,
                  slot_row_base: Optional[Sequence[int]] = None, slot_num_rows: Optional[Sequence[int]] = None,
                  hash_table: Optional[HashTable] = None, insert_on_miss: bool = True,
-                 io_dtype: torch.dtype = torch.float32, master: Optional[torch.Tensor] = None):
+                 io_dtype: torch.dtype = torch.float32, master: Optional[torch.Tensor] = None,
+                 reuse_forward_rows: bool = False):
         assert table.is_cuda and table.is_contiguous() and table.dim() == 2
         assert io_dtype in (torch.float32, torch.float16)
         if master is not None:
@@ -229,6 +230,7 @@ class EmbeddingLayer:
         d.insert_on_miss = int(insert_on_miss)
         d.io_dtype = F32 if io_dtype == torch.float32 else F16
         d.master = None if master is None else master.data_ptr()
+        d.reuse_forward_rows = int(reuse_forward_rows)
         self.desc = d
         self._wsbuf = None
 
@@ -415,8 +417,9 @@ class EmbeddingTrainingCache:
     def dump(self, evict: bool = True, stream=None) -> None:
         _check(lib().hctr_etc_dump(self.handle, int(evict), _stream(stream)))
 
-    def layer(self, num_slots: int, combiner: int = SUM) -> "EmbeddingLayer":
-        return EmbeddingLayer(self.table, num_slots, combiner, hash_table=self.hash_table, insert_on_miss=False)
+    def layer(self, num_slots: int, combiner: int = SUM, reuse_forward_rows: bool = False) -> "EmbeddingLayer":
+        return EmbeddingLayer(self.table, num_slots, combiner, hash_table=self.hash_table, insert_on_miss=False,
+                              reuse_forward_rows=reuse_forward_rows)
 
     @property
     def stats(self):

@@ -1174,7 +1174,8 @@ static hctr_status backward_dedup(const hctr_emb_desc* desc, int64_t batch, cons
   const int64_t* rows64 = nullptr;
   if (desc->hash && nnz > 0) {
     int64_t* r = reinterpret_cast<int64_t*>(w + L.rows64);
-    HCTR_TRY(hash_lookup(desc->hash, keys, nnz, 0, r, w + L.hash_ws, L.total - L.hash_ws, stream));
+    if (!desc->reuse_forward_rows)   // else: the forward on this workspace left them there
+      HCTR_TRY(hash_lookup(desc->hash, keys, nnz, 0, r, w + L.hash_ws, L.total - L.hash_ws, stream));
     rows64 = r;
   }
   SlotTable st;

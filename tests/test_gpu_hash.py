@@ -90,14 +90,15 @@ def test_split_calls_give_the_same_mapping():
     assert np.array_equal(ra, rb) and a.size == b.size
 
 
-def test_hashed_embedding_forward_backward():
+@pytest.mark.parametrize("reuse", [False, True], ids=["lookup-twice", "reuse-forward-rows"])
+def test_hashed_embedding_forward_backward(reuse):
     """26 one-hot slots over an open key space, dim 64 fp32, insert on miss in forward."""
     h = H()
     S, dim, batch, max_rows = 26, 64, 513, 12000
     ht, ref_hash = both(16384, max_rows)
     table = datagen.table_rows_at(SEED, torch.arange(max_rows), dim, torch.float32)
     d_table = to_dev(table)
-    layer = h.EmbeddingLayer(d_table, S, h.SUM, hash_table=ht, insert_on_miss=True)
+    layer = h.EmbeddingLayer(d_table, S, h.SUM, hash_table=ht, insert_on_miss=True, reuse_forward_rows=reuse)
     tab_np = table.numpy().copy()
     smp = datagen.ZipfSampler(1 << 63, 1.05)
     for it in range(3):
