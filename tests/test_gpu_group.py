@@ -141,3 +141,24 @@ def test_group_empty_calls():
     g.backward_sgd(5, empty, torch.ones((5, g.width), device="cuda"), 0.1, off)
     for t, dtab in zip(tables, g.tables):
         assert np.array_equal(dtab.cpu().numpy(), t)
+
+
+def test_group_is_deterministic():
+    rng = np.random.default_rng(18)
+    shapes = [(50, 32), (2000, 128), (9, 8)]
+    lookups = [(0, H.SUM, 1), (1, H.MEAN, 1), (2, H.SUM, 1), (1, H.SUM, 1)]
+    tables = [(rng.standard_normal(s) * 0.25).astype(np.float32) for s in shapes]
+    batch, L = 3000, len(lookups)
+    offsets = np.concatenate([[0], np.cumsum(rng.integers(0, 7, batch * L))]).astype(np.int64)
+    keys = make_keys(rng, shapes, np.array([l[0] for l in lookups]), batch, offsets, zipf=True)
+    dY = rng.standard_normal((batch, 32 + 128 + 8 + 128)).astype(np.float32)
+    results = []
+    for _ in range(2):
+        dev = [to_dev(t) for t in tables]
+        g = H.EmbeddingGroup(dev, lookups)
+        out = g.forward(batch, to_dev(keys), to_dev(offsets))
+        g.backward_sgd(batch, to_dev(keys), to_dev(dY), 0.05, to_dev(offsets))
+        results.append((out, dev))
+    assert torch.equal(results[0][0], results[1][0])
+    for a, b in zip(results[0][1], results[1][1]):
+        assert torch.equal(a, b)
