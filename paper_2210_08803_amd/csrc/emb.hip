@@ -52,9 +52,7 @@ __global__ __launch_bounds__(256) void emb_init_header(EmbHeader* hdr, uint32_t*
   if (i < zero_count) zero[i] = 0u;
 }
 
-#ifndef HCTR_SLOT_MAJOR_MIN
-#define HCTR_SLOT_MAJOR_MIN 512
-#endif
+constexpr size_t kSlotMajorMinRowBytes = 512;
 // Order in which the forward kernels walk the bags.  n_samples == 0: in memory order (bag = sample *
 // S + slot).  n_samples == batch: slot by slot (all samples of slot 0, then slot 1, ...): the chip
 // then works on one table at a time and that table's hot rows stay in the 4 MB L2 of every XCD
@@ -1007,7 +1005,7 @@ static void launch_forward(const hctr_emb_desc* d, const int64_t* keys, const in
   const T* table = static_cast<const T*>(d->table);
   // slot by slot when every slot has a table of its own and an output row fills four cache lines
   const uint32_t S = (uint32_t)d->num_slots;
-  const uint32_t n_samples = (!rows64 && S > 1 && (size_t)d->dim * sizeof(OutT) >= HCTR_SLOT_MAJOR_MIN) ? n_bags / S : 0u;
+  const uint32_t n_samples = (!rows64 && S > 1 && (size_t)d->dim * sizeof(OutT) >= kSlotMajorMinRowBytes) ? n_bags / S : 0u;
   if (!offsets) {
     constexpr int U = 4;
     const uint32_t bags_per_block = (256 / LPR) * U;
