@@ -477,6 +477,7 @@ struct UniformView {
     *width = D;
     return dY + (int64_t)bag * D;
   }
+
   __device__ __forceinline__ int row_width(uint32_t, const GroupLookup*) const { return D; }
   // four weights of row r at column col, widened to fp32 / written back
   __device__ __forceinline__ f32x4 load_weights(uint32_t r, uint32_t, const GroupLookup*, int col) const {
@@ -530,7 +531,10 @@ struct GroupView {
 // adds a row's partials in window order and applies the update.  Order of additions is fixed by
 // the sorted positions, so results do not vary from run to run.
 // ------------------------------------------------------------------------------------------------
-template <typename T, int LPR, typename View>
+// ONCE: one key per bag, so every gradient row is read exactly once and is loaded with a streaming
+// load that keeps the caches for what is reused.  With several keys per bag the rows ARE reused (a
+// multi-hot backward ran 45 % slower with streaming loads), so they are read the ordinary way.
+template <typename T, int LPR, typename View, bool ONCE>
 __global__ __launch_bounds__(256) void bwd_reduce_windows(
     const View view, const uint64_t* __restrict__ skv, const EmbHeader* __restrict__ hdr,
     const int64_t* __restrict__ offsets, float lr, float* __restrict__ head, float* __restrict__ tail,
@@ -582,7 +586,8 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
         w[u] = __shfl(myw, q, LPR);
         int width;
         const auto* g = view.grad(b[u], lk, &width);
-        v[u] = col < width ? load_row4(g + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (ONCE) v[u] = col < width ? load_stream4(g + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+        else v[u] = col < width ? load_row4(g + col) : f32x4{0.f, 0.f, 0.f, 0.f};
       }
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
@@ -1046,16 +1051,20 @@ static void dispatch_forward(int lpr, const hctr_emb_desc* d, const int64_t* key
 
 // Launches the three reduction kernels for one view; dmax = widest row of the view.
 template <typename T, int LPR, typename View>
-static void launch_reduce(const View& view, int dmax, const EmbLayout& L, char* ws, const uint64_t* skv,
-                          const int64_t* offsets, float lr, hipStream_t stream) {
+static void launch_reduce(const View& view, int dmax, bool once, const EmbLayout& L, char* ws,
+                          const uint64_t* skv, const int64_t* offsets, float lr, hipStream_t stream) {
   const uint32_t ychunks = (uint32_t)ceil_div(dmax, LPR * 4);
   dim3 grid((uint32_t)ceil_div(L.n_windows, 256 / LPR), ychunks);
   EmbHeader* hdr = reinterpret_cast<EmbHeader*>(ws + L.header);
   float* head = reinterpret_cast<float*>(ws + L.head);
   float* tail = reinterpret_cast<float*>(ws + L.tail);
   uint8_t* tflag = reinterpret_cast<uint8_t*>(ws + L.tail_flag);
-  hipLaunchKernelGGL((bwd_reduce_windows<T, LPR, View>), grid, dim3(256), 0, stream, view, skv,
-                     (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr);
+  if (once)
+    hipLaunchKernelGGL((bwd_reduce_windows<T, LPR, View, true>), grid, dim3(256), 0, stream, view, skv,
+                       (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr);
+  else
+    hipLaunchKernelGGL((bwd_reduce_windows<T, LPR, View, false>), grid, dim3(256), 0, stream, view, skv,
+                       (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr);
   uint32_t* long_list = reinterpret_cast<uint32_t*>(ws + L.long_list);
   const uint32_t* starts_before = reinterpret_cast<const uint32_t*>(ws + L.flags);
   const uint32_t* seg_off = reinterpret_cast<const uint32_t*>(ws + L.seg_off);
@@ -1069,16 +1078,16 @@ static void launch_reduce(const View& view, int dmax, const EmbLayout& L, char* 
 }
 
 template <typename T, typename View>
-static void dispatch_reduce_view(const View& view, int dmax, const EmbLayout& L, char* ws, const uint64_t* skv,
-                                 const int64_t* offsets, float lr, hipStream_t stream) {
+static void dispatch_reduce_view(const View& view, int dmax, bool once, const EmbLayout& L, char* ws,
+                                 const uint64_t* skv, const int64_t* offsets, float lr, hipStream_t stream) {
   int lpr = pow2_ceil((int)ceil_div(dmax, 4));
   lpr = lpr < 4 ? 4 : (lpr > 64 ? 64 : lpr);
   switch (lpr) {
-    case 4: launch_reduce<T, 4>(view, dmax, L, ws, skv, offsets, lr, stream); break;
-    case 8: launch_reduce<T, 8>(view, dmax, L, ws, skv, offsets, lr, stream); break;
-    case 16: launch_reduce<T, 16>(view, dmax, L, ws, skv, offsets, lr, stream); break;
-    case 32: launch_reduce<T, 32>(view, dmax, L, ws, skv, offsets, lr, stream); break;
-    default: launch_reduce<T, 64>(view, dmax, L, ws, skv, offsets, lr, stream); break;
+    case 4: launch_reduce<T, 4>(view, dmax, once, L, ws, skv, offsets, lr, stream); break;
+    case 8: launch_reduce<T, 8>(view, dmax, once, L, ws, skv, offsets, lr, stream); break;
+    case 16: launch_reduce<T, 16>(view, dmax, once, L, ws, skv, offsets, lr, stream); break;
+    case 32: launch_reduce<T, 32>(view, dmax, once, L, ws, skv, offsets, lr, stream); break;
+    default: launch_reduce<T, 64>(view, dmax, once, L, ws, skv, offsets, lr, stream); break;
   }
 }
 
@@ -1091,7 +1100,7 @@ static void dispatch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws
   view.dY = static_cast<const DyT*>(dY);
   view.D = d->dim;
   view.mean = (d->combiner == HCTR_MEAN && offsets != nullptr) ? 1 : 0;
-  dispatch_reduce_view<T>(view, d->dim, L, ws, skv, offsets, lr, stream);
+  dispatch_reduce_view<T>(view, d->dim, offsets == nullptr, L, ws, skv, offsets, lr, stream);
 }
 
 }  // namespace hctr
@@ -1422,7 +1431,7 @@ static void group_launch_reduce(const GroupPlan& P, const EmbLayout& L, char* w,
   view.dmax_ = P.dmax;
   for (int l = 0; l < HCTR_MAX_GROUP_LOOKUPS; ++l)
     view.lk[l] = l < (int)P.L ? P.lk[l] : GroupLookup{nullptr, 0, 0, 0, 0};
-  dispatch_reduce_view<T>(view, P.dmax, L, w, skv, csr, lr, stream);
+  dispatch_reduce_view<T>(view, P.dmax, false, L, w, skv, csr, lr, stream);
 }
 
 }  // namespace hctr
