@@ -239,6 +239,10 @@ def main():
                      "compulsory_bytes_per_launch": nnz * (8 + DIM * 4) + int(U) * DIM * 4,
                      "avg_launch_ms": float(fwd_ms.mean())},
         "phases": {"schedule": args.schedule,
+                   # per-step GPU time between the step's first and last event (steps overlap under
+                   # the pipelined schedules, so these are meaningful for `serial` only)
+                   "step_ms_median": float(np.median(fwd_ms + bwd_ms)) if args.schedule == "serial" else None,
+                   "step_ms_min": float((fwd_ms + bwd_ms).min()) if args.schedule == "serial" else None,
                    "forward_ms": float(fwd_ms.mean()), "forward_ms_min": float(fwd_ms.min()),
                    "backward_ms" if args.schedule == "serial" else "backward_apply_ms": float(bwd_ms.mean()),
                    "backward_dedup_ms": None if dedup_ms is None else float(dedup_ms.mean()),
