@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--schedule", choices=["serial", "overlap", "pipeline"], default="serial",
                     help="how the key-only half of backward is placed in time (see step())")
+    ap.add_argument("--graph", action="store_true",
+                    help="serial schedule only: capture each key batch's step in a HIP graph and replay it "
+                         "(one launch per step; the per-phase event times are then not available)")
     ap.add_argument("--calibrate-gather", action="store_true",
                     help="also run the forward kernel once on all-distinct rows (known bytes, no cache reuse)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -133,9 +136,17 @@ def main():
     ws2 = layer.new_workspace(layer.workspace_bytes(BATCH, nnz)) if args.schedule == "pipeline" else None
     wss = [ws, ws2]
 
+    graphs = None
+
     def step(i, ev=None):
         k = keys[i % N_KEY_BATCHES]
-        if args.schedule == "serial":
+        if graphs is not None:
+            if ev:
+                ev[0].record(stream)
+            graphs[i % N_KEY_BATCHES].replay()
+            if ev:
+                ev[2].record(stream)
+        elif args.schedule == "serial":
             if ev:
                 ev[0].record(stream)
             layer.forward(BATCH, k, out=out, ws=ws)
@@ -177,6 +188,26 @@ def main():
             if ev:
                 ev[2].record(stream)
 
+    if args.graph:
+        if args.schedule != "serial":
+            log("bench.py: --graph goes with --schedule serial only.")
+            sys.exit(2)
+        for i in range(2):                       # once eagerly, so that nothing is initialised during capture
+            step(i)
+        torch.cuda.synchronize()
+        captured = []
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            for b in range(N_KEY_BATCHES):       # N_KEY_BATCHES is even: batch b always meets dY buffer b % 2
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    layer.forward(BATCH, keys[b], out=out, ws=ws)
+                    layer.backward_sgd(BATCH, keys[b], dYs[b % 2], LR, ws=ws)
+                captured.append(g)
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        graphs = captured
+
     if args.schedule == "pipeline":             # dedup of the first batch: the pipeline's prologue
         layer.backward_dedup(BATCH, keys[0], ws=wss[0])
         torch.cuda.synchronize()
@@ -199,6 +230,16 @@ def main():
         step(args.warmup + i, evs[i])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    if graphs is not None:   # only the whole step is timed; the roofline figure then needs an eager run
+        step_ms = np.array([e[0].elapsed_time(e[2]) for e in evs])
+        log("bench.py --graph: %.4f ms per step by wall clock, %.4f median / %.4f min by events; run without "
+            "--graph for the JSON line with the roofline figure" % (elapsed / args.steps * 1e3,
+                                                                     float(np.median(step_ms)), float(step_ms.min())))
+        print(json.dumps({"metric": "embedding keys/sec fwd+bwd, 26-slot DLRM shape, step replayed as a HIP graph",
+                          "value": nnz / (elapsed / args.steps), "unit": "keys/s", "n_gpus": 1, "steps": args.steps,
+                          "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+                          "step_ms_median": float(np.median(step_ms)), "data": "synthetic"}), flush=True)
+        return
     fwd_ms = np.array([e[0].elapsed_time(e[1]) for e in evs])
     bwd_ms = np.array([e[1].elapsed_time(e[2]) for e in evs])
     dedup_ms = None if args.schedule == "serial" else np.array([e[3].elapsed_time(e[4]) for e in evs])

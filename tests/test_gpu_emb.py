@@ -246,3 +246,48 @@ def test_no_key_has_a_row(hot):
     assert layer.invalid_keys() == 2 * nnz
     uniq, cnt = layer.dedup_result(batch, nnz)
     assert uniq.numel() == 0 and cnt.numel() == 0
+
+
+def test_forward_and_backward_can_be_captured_in_a_graph():
+    """The compute calls only enqueue kernels (no allocation, no synchronisation, no memset), so a
+    step can be captured once and replayed; every replay must give the eager result."""
+    h = H()
+    rows, dim, batch = [5000, 60, 900], 64, 2048
+    S = len(rows)
+    ro = datagen.row_offsets(rows)
+    table0 = datagen.table_rows_at(SEED, torch.arange(int(ro[-1])), dim, torch.float32)
+    keys = to_dev(datagen.onehot_keys(SEED, 0, rows, batch, 1.05))
+    dY = to_dev(datagen.normal_grads(SEED, 0, batch * S * dim).view(batch, S, dim))
+
+    def make():
+        t = to_dev(table0)
+        layer = h.EmbeddingLayer(t, S, h.SUM, ro[:-1].copy(), rows)
+        ws = layer.new_workspace(layer.workspace_bytes(batch, batch * S))
+        out = torch.empty((batch, S, dim), device="cuda")
+        return t, layer, ws, out
+
+    t_e, layer_e, ws_e, out_e = make()     # eager reference: three steps
+    eager = []
+    for _ in range(3):
+        layer_e.forward(batch, keys, out=out_e, ws=ws_e)
+        layer_e.backward_sgd(batch, keys, dY, 0.05, ws=ws_e)
+        eager.append((out_e.clone(), t_e.clone()))
+
+    t_g, layer_g, ws_g, out_g = make()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            layer_g.forward(batch, keys, out=out_g, ws=ws_g)
+            layer_g.backward_sgd(batch, keys, dY, 0.05, ws=ws_g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    assert torch.equal(t_g, to_dev(table0))          # capturing runs nothing
+    for i in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        scratch = torch.randn(1 << 20, device="cuda").sum().item()   # eager work between the replays
+        assert scratch == scratch
+        assert torch.equal(out_g, eager[i][0]), f"replay {i}: forward differs from the eager step"
+        assert torch.equal(t_g, eager[i][1]), f"replay {i}: table differs from the eager step"
