@@ -149,7 +149,7 @@ __global__ __launch_bounds__(NT) void sort_hist(const uint64_t* __restrict__ kv,
 // LDS and then turn their chunk into running sums (sup[g][d] = count of digit d in all earlier
 // groups) - every load of a chunk is independent of the others, where one thread per digit walking
 // all groups took 88 us per pass for 1,300 groups.
-__global__ __launch_bounds__(256) void sort_sum_groups(const uint32_t* __restrict__ hist, uint32_t n_host,
+__global__ __launch_bounds__(256) void sort_sum_groups(uint32_t* __restrict__ hist, uint32_t n_host,
                                                        const uint32_t* __restrict__ n_dev, uint32_t bins,
                                                        uint32_t* __restrict__ sup) {
   const uint32_t n = n_dev ? *n_dev : n_host;
@@ -164,7 +164,11 @@ __global__ __launch_bounds__(256) void sort_sum_groups(const uint32_t* __restric
     v[k] = t < n_tiles ? *reinterpret_cast<const u32x4v*>(hist + (uint64_t)t * bins + d0) : u32x4v{0, 0, 0, 0};
   }
 #pragma unroll
-  for (uint32_t k = 0; k < kSortSuper; ++k) acc += v[k];
+  for (uint32_t k = 0; k < kSortSuper; ++k) {
+    const uint32_t t = g * kSortSuper + k;
+    if (t < n_tiles) *reinterpret_cast<u32x4v*>(hist + (uint64_t)t * bins + d0) = acc;
+    acc += v[k];
+  }
   *reinterpret_cast<u32x4v*>(sup + (uint64_t)g * bins + d0) = acc;
 }
 
@@ -220,7 +224,11 @@ __global__ __launch_bounds__(NT) void sort_scatter(
   __shared__ uint32_t scan_lds[NT / 64 + 1];
   const uint32_t n = n_dev ? *n_dev : n_host;
   const uint32_t mask = bins - 1;
-  const uint32_t blk = blockIdx.x;
+  // Workgroups go to the chip's 8 dies in turn, each with an L2 of its own.  Die x takes the x-th
+  // eighth of the input, so that the blocks resident on a die hold neighbouring tiles: their runs of
+  // one digit are adjacent in the output and leave that L2 as whole lines instead of pieces.
+  const uint32_t gq = gridDim.x >> 3, gr = gridDim.x & 7u, die = blockIdx.x & 7u;
+  const uint32_t blk = die * gq + (die < gr ? die : gr) + (blockIdx.x >> 3);   // tile of this block
   const uint32_t base = blk * kSortTile;
   if (base >= n) return;  // whole block leaves together
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -241,16 +249,17 @@ __global__ __launch_bounds__(NT) void sort_scatter(
     u32x4v t4 = {0, 0, 0, 0}, pre = {0, 0, 0, 0};
     if (d0 < bins) {
       const uint32_t g = blk / kSortSuper;
-      const uint32_t b_begin = g * kSortSuper;   // at most kSortSuper - 1 = 15 rows of this group
-      u32x4v hrow[kSortSuper - 1];
-#pragma unroll
-      for (uint32_t k = 0; k < kSortSuper - 1; ++k)   // requested first: in flight while the group sums arrive
-        hrow[k] = b_begin + k < blk ? *reinterpret_cast<const u32x4v*>(hist + (uint64_t)(b_begin + k) * bins + d0)
-                                    : u32x4v{0, 0, 0, 0};
-      if (sup_is_scanned) {
+      if (sup_is_scanned) {   // sort_sum_groups left the running sums within the group in hist
         t4 = *reinterpret_cast<const u32x4v*>(tot + d0);
         pre = *reinterpret_cast<const u32x4v*>(sup + (uint64_t)g * bins + d0);
+        pre += *reinterpret_cast<const u32x4v*>(hist + (uint64_t)blk * bins + d0);
       } else {
+        const uint32_t b_begin = g * kSortSuper;   // at most kSortSuper - 1 = 15 rows of this group
+        u32x4v hrow[kSortSuper - 1];
+#pragma unroll
+        for (uint32_t k = 0; k < kSortSuper - 1; ++k)   // requested first: in flight while the group sums arrive
+          hrow[k] = b_begin + k < blk ? *reinterpret_cast<const u32x4v*>(hist + (uint64_t)(b_begin + k) * bins + d0)
+                                        : u32x4v{0, 0, 0, 0};
         // rows are fetched twelve at a time so the loads overlap instead of queueing behind each other
         constexpr uint32_t kBatch = 12;
         for (uint32_t sb0 = 0; sb0 < n_super; sb0 += kBatch) {
@@ -265,9 +274,9 @@ __global__ __launch_bounds__(NT) void sort_scatter(
             if (sb0 + k < g) pre += v[k];
           }
         }
-      }
 #pragma unroll
-      for (uint32_t k = 0; k < kSortSuper - 1; ++k) pre += hrow[k];
+        for (uint32_t k = 0; k < kSortSuper - 1; ++k) pre += hrow[k];
+      }
     }
     uint32_t total;
     uint32_t run = block_exclusive_scan<NT>(t4.x + t4.y + t4.z + t4.w, scan_lds, &total);
@@ -375,7 +384,7 @@ hctr_status radix_sort_u64(const SortPlan& plan, const uint32_t* n_dev, uint64_t
                            plan.n_max, n_dev, shift, bins, hist, hist_sup);
     }
     if (scan_sup) {
-      hipLaunchKernelGGL(sort_sum_groups, dim3(plan.n_super), dim3(256), 0, stream, chist, plan.n_max, n_dev, bins,
+      hipLaunchKernelGGL(sort_sum_groups, dim3(plan.n_super), dim3(256), 0, stream, hist, plan.n_max, n_dev, bins,
                          sup);
       hipLaunchKernelGGL(sort_scan_groups, dim3((uint32_t)ceil_div(bins, 32)), dim3(1024), 0, stream, sup, tot,
                          bins, plan.n_super);
