@@ -50,38 +50,62 @@ __global__ __launch_bounds__(256) void hash_clear(u64x2* slots, uint64_t n_slots
   if (i == 0) hdr->size = 0;
 }
 
-// One key per 8-lane group.
+// An 8-lane group reads one bucket (8 slots of 16 bytes = one 128-byte line) per probe and works on
+// kFindKeys keys at once, so that many independent bucket loads are in flight per wave: the search
+// is bound by the latency of random lines, not by bandwidth.
+constexpr int kFindKeys = 4;   // find-only call on 3.4 M keys, load 0.8: 0.277 / 0.236 / 0.227 ms with 1 / 2 / 4
 __global__ __launch_bounds__(256) void hash_find(const u64x2* __restrict__ slots, uint32_t n_buckets,
                                                  const int64_t* __restrict__ keys, uint32_t n,
                                                  int64_t* __restrict__ rows,
                                                  uint32_t* __restrict__ miss_flag) {
-  const uint32_t i = (blockIdx.x * 256u + threadIdx.x) >> 3;
+  const uint64_t i0 = (uint64_t)((blockIdx.x * 256u + threadIdx.x) >> 3) * kFindKeys;
   const int sub = threadIdx.x & 7;
-  const int64_t key = i < n ? keys[i] : -1;
-  bool searching = key >= 0;
-  int64_t row = -1;
-  uint32_t b = searching ? bucket_of((u64)key, n_buckets) : 0u;
+  int64_t key[kFindKeys], row[kFindKeys];
+  bool searching[kFindKeys];
+  uint32_t b[kFindKeys];
+#pragma unroll
+  for (int u = 0; u < kFindKeys; ++u) {
+    key[u] = i0 + u < n ? keys[i0 + u] : -1;
+    searching[u] = key[u] >= 0;
+    row[u] = -1;
+    b[u] = searching[u] ? bucket_of((u64)key[u], n_buckets) : 0u;
+  }
   for (uint32_t step = 0; step < n_buckets; ++step) {
-    if (__ballot(searching) == 0) break;
-    u64x2 s = u64x2{kEmptyKey, kEmptyKey};
-    if (searching) s = slots[(uint64_t)b * 8u + sub];
-    const uint32_t hit = group_bits(__ballot(searching && s.x == (u64)key));
-    const uint32_t hole = group_bits(__ballot(searching && s.x == kEmptyKey));
-    if (searching) {
-      if (hit) {
-        const int src = (threadIdx.x & 56) + (__ffs(hit) - 1);
-        row = (int64_t)__shfl((long long)s.y, src);
-        searching = false;
-      } else if (hole) {
-        searching = false;
-      } else {
-        b = (b + 1 == n_buckets) ? 0u : b + 1;
+    bool any = false;
+#pragma unroll
+    for (int u = 0; u < kFindKeys; ++u) any |= searching[u];
+    if (__ballot(any) == 0) break;
+    u64x2 s[kFindKeys];
+#pragma unroll
+    for (int u = 0; u < kFindKeys; ++u) {
+      s[u] = u64x2{kEmptyKey, kEmptyKey};
+      if (searching[u]) s[u] = slots[(uint64_t)b[u] * 8u + sub];
+    }
+#pragma unroll
+    for (int u = 0; u < kFindKeys; ++u) {
+      const uint32_t hit = group_bits(__ballot(searching[u] && s[u].x == (u64)key[u]));
+      const uint32_t hole = group_bits(__ballot(searching[u] && s[u].x == kEmptyKey));
+      if (searching[u]) {
+        if (hit) {
+          const int src = (threadIdx.x & 56) + (__ffs(hit) - 1);
+          row[u] = (int64_t)__shfl((long long)s[u].y, src);
+          searching[u] = false;
+        } else if (hole) {
+          searching[u] = false;
+        } else {
+          b[u] = (b[u] + 1 == n_buckets) ? 0u : b[u] + 1;
+        }
       }
     }
   }
-  if (i < n && sub == 0) {
-    rows[i] = row;
-    if (miss_flag) miss_flag[i] = (key >= 0 && row < 0) ? 1u : 0u;
+  if (sub == 0) {
+#pragma unroll
+    for (int u = 0; u < kFindKeys; ++u) {
+      if (i0 + u < n) {
+        rows[i0 + u] = row[u];
+        if (miss_flag) miss_flag[i0 + u] = (key[u] >= 0 && row[u] < 0) ? 1u : 0u;
+      }
+    }
   }
 }
 
@@ -255,7 +279,7 @@ hctr_status hash_lookup(hctr_hash* h, const int64_t* keys, int64_t n64, int inse
   if (n64 == 0) return HCTR_OK;
   const uint32_t n = (uint32_t)n64;
   const u64x2* slots = reinterpret_cast<const u64x2*>(h->slots);
-  const uint32_t find_blocks = (uint32_t)ceil_div((int64_t)n * 8, 256);
+  const uint32_t find_blocks = (uint32_t)ceil_div(ceil_div((int64_t)n, kFindKeys) * 8, 256);
   if (!insert) {
     hipLaunchKernelGGL(hash_find, dim3(find_blocks), dim3(256), 0, stream, slots, h->n_buckets, keys, n,
                        rows, (uint32_t*)nullptr);
