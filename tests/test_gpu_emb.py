@@ -138,6 +138,38 @@ def test_sizes_around_window_and_tile_edges(batch):
     run_case([500], 32, batch)
 
 
+@pytest.mark.parametrize("tiles", [768, 769, 770, 771, 773, 776, 1024, 1025])
+def test_dedup_around_the_switches_of_the_sort(tiles):
+    """The sort derives its offsets differently above 48 groups of 16 tiles (768 tiles of 4,096 keys),
+    uses narrower blocks above 1,024 tiles, and its scatter hands tiles to blocks die by die, with a
+    remainder when the tile count is no multiple of 8.  Distinct rows and their counts against numpy
+    on 3.1 to 4.2 M keys with 28-bit row ids (three passes)."""
+    h = H()
+    S, D = 2, 4
+    rows_t = [3_000_000, 130_000_000]
+    base = [0, rows_t[0]]
+    nnz = tiles * 4096 - 6
+    B = nnz // S
+    g = torch.Generator(device="cuda").manual_seed(tiles)
+    k0 = torch.randint(0, rows_t[0], (B,), generator=g, device="cuda")
+    hot = torch.randint(0, 1000, (B,), generator=g, device="cuda")
+    cold = torch.randint(0, rows_t[1], (B,), generator=g, device="cuda")
+    k1 = torch.where(torch.rand(B, generator=g, device="cuda") < 0.5, hot, cold)
+    keys = torch.stack([k0, k1], dim=1).contiguous()
+    table = torch.empty((sum(rows_t), D), dtype=torch.float32, device="cuda")   # the key-only half never reads it
+    layer = h.EmbeddingLayer(table, S, 0, base, rows_t)
+    ws = layer.new_workspace(layer.workspace_bytes(B, nnz))
+    layer.backward_dedup(B, keys, ws=ws)
+    d_rows, d_cnt = layer.dedup_result(B, nnz, ws=ws)
+    torch.cuda.synchronize()
+    g_rows = (keys.cpu().numpy() + np.asarray(base)[None, :]).reshape(-1)
+    uniq, cnt = np.unique(g_rows, return_counts=True)
+    assert np.array_equal(d_rows.cpu().numpy(), uniq)
+    assert np.array_equal(d_cnt.cpu().numpy(), cnt)
+    assert layer.invalid_keys(ws) == 0
+    del table, ws
+
+
 def test_all_keys_distinct():
     h = H()
     n = 5000
