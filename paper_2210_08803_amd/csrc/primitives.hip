@@ -217,12 +217,11 @@ __global__ __launch_bounds__(1024) void sort_scan_groups(uint32_t* __restrict__ 
   }
 }
 
-template <int DBITS, int NT>
+template <int DBITS, int NT, bool SCANNED>
 __global__ __launch_bounds__(NT) void sort_scatter(
     const uint64_t* __restrict__ in, uint64_t* __restrict__ out, uint32_t n_host,
     const uint32_t* __restrict__ n_dev, int shift, uint32_t bins, const uint32_t* __restrict__ hist,
-    const uint32_t* __restrict__ tot, const uint32_t* __restrict__ sup, uint32_t n_super,
-    int sup_is_scanned) {
+    const uint32_t* __restrict__ tot, const uint32_t* __restrict__ sup, uint32_t n_super) {
   constexpr int BINS_MAX = 1 << DBITS;
   __shared__ uint32_t cnt[NT / 64][BINS_MAX];
   __shared__ uint32_t gbase[BINS_MAX];
@@ -254,7 +253,7 @@ __global__ __launch_bounds__(NT) void sort_scatter(
     u32x4v t4 = {0, 0, 0, 0}, pre = {0, 0, 0, 0};
     if (d0 < bins) {
       const uint32_t g = blk / kSortSuper;
-      if (sup_is_scanned) {   // sort_sum_groups left the running sums within the group in hist
+      if (SCANNED) {   // sort_sum_groups left the running sums within the group in hist
         t4 = *reinterpret_cast<const u32x4v*>(tot + d0);
         pre = *reinterpret_cast<const u32x4v*>(sup + (uint64_t)g * bins + d0);
         pre += *reinterpret_cast<const u32x4v*>(hist + (uint64_t)blk * bins + d0);
@@ -394,11 +393,14 @@ hctr_status radix_sort_u64(const SortPlan& plan, const uint32_t* n_dev, uint64_t
       hipLaunchKernelGGL(sort_scan_groups, dim3((uint32_t)ceil_div(bins, 32)), dim3(1024), 0, stream, sup, tot,
                          bins, plan.n_super);
     }
-#define HCTR_SCATTER(DB, NT)                                                                             \
-  hipLaunchKernelGGL((sort_scatter<DB, NT>), dim3(plan.n_blocks), dim3(NT), 0, stream, in, buf[dst],     \
-                     plan.n_max, n_dev, shift, bins, chist, ctot, csup, plan.n_super, scan_sup)
-    if (db <= 8) HCTR_SCATTER(8, kSortThreads);          // the scatter measured faster with 256 threads
-    else HCTR_SCATTER(kSortMaxDigitBits, kSortThreads);  // at every size
+#define HCTR_SCATTER(DB, NT, SC)                                                                         \
+  hipLaunchKernelGGL((sort_scatter<DB, NT, SC>), dim3(plan.n_blocks), dim3(NT), 0, stream, in, buf[dst], \
+                     plan.n_max, n_dev, shift, bins, chist, ctot, csup, plan.n_super)
+    if (scan_sup) {   // an instantiation of its own: without the rows of the other scheme it needs fewer registers
+      if (db <= 8) HCTR_SCATTER(8, kSortThreads, true);
+      else HCTR_SCATTER(kSortMaxDigitBits, kSortThreads, true);
+    } else if (db <= 8) HCTR_SCATTER(8, kSortThreads, false);   // the scatter measured faster with 256 threads
+    else HCTR_SCATTER(kSortMaxDigitBits, kSortThreads, false);  // at every size
 #undef HCTR_SCATTER
     shift += db;
   }
