@@ -126,18 +126,18 @@ def cache(h, args):
         r1 = min(host_rows, r0 + (1 << 20))
         host[r0:r1].copy_(datagen.table_rows_at(SEED, torch.arange(r0, r1, device=DEV), D, torch.float32))
     c = h.EmbeddingCache(num_sets, ways, host)
-    smp = datagen.ZipfSampler(host_rows, 1.2)
+    smp = datagen.ZipfSampler(host_rows, 1.2, DEV)
     call = 0
     for _ in range(30):   # warm up until the hit rate is stationary
-        keys = datagen.cache_keys(SEED, call, host_rows, 16384 * S * hot, 1.2, sampler=smp).cuda()
+        keys = datagen.cache_keys(SEED, call, host_rows, 16384 * S * hot, 1.2, device=DEV, sampler=smp)
         call += 1
         c.query(16384, S, keys)
     torch.cuda.synchronize()
     sweep = []
     for batch in (1, 64, 1024, 16384):
         n = batch * S * hot
-        reps = 1000 if batch <= 1024 else 200
-        ks_by_mode = {m: [datagen.cache_keys(SEED, 1000 + 2000 * j + call + i, host_rows, n, 1.2, sampler=smp).cuda()
+        reps = 1000
+        ks_by_mode = {m: [datagen.cache_keys(SEED, 1000 + 2000 * j + call + i, host_rows, n, 1.2, device=DEV, sampler=smp)
                           for i in range(reps)] for j, m in enumerate(("insert", "lookup_only"))}
         o = torch.empty((batch, S, D), device=DEV)
         ws = c.workspace(n)
