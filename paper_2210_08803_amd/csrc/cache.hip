@@ -94,6 +94,46 @@ __device__ __forceinline__ void victim_order(u64 tag, uint32_t stamp, uint32_t e
   *n_elig = ne;
 }
 
+// The same through LDS, for a block whose waves all rank at once: 64 cross-lane reads per call (the
+// shuffles above, two per 64-bit word) keep the LDS pipe of the compute unit busy for longer than
+// everything else in the placement step; here a lane stores one 32-bit code and reads the group's
+// codes four at a time.  code = 0 (empty way), last use + 1, or all ones (used in this call); ties go
+// to the lower way, as above.  `codes` = the group's WAYS words; the group's lanes are in one wave,
+// whose LDS instructions are served in order.
+template <int WAYS>
+__device__ __forceinline__ void victim_order_lds(uint32_t* codes, u64 tag, uint32_t stamp, uint32_t epoch,
+                                                 int way, bool* eligible, bool* empty, uint32_t* pos,
+                                                 uint32_t* n_elig) {
+  *empty = tag == kEmptyKey;
+  *eligible = *empty || stamp < epoch;
+  const uint32_t code = !*eligible ? 0xFFFFFFFFu : (*empty ? 0u : stamp + 1u);
+  codes[way] = code;
+  __builtin_amdgcn_wave_barrier();
+  uint32_t p = 0, ne = 0;
+  if constexpr (WAYS >= 4) {
+#pragma unroll
+    for (int w0 = 0; w0 < WAYS; w0 += 4) {
+      const uint4 o = *reinterpret_cast<const uint4*>(codes + w0);
+      const uint32_t other[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        p += (other[k] < code || (other[k] == code && w0 + k < way)) ? 1u : 0u;
+        ne += other[k] != 0xFFFFFFFFu ? 1u : 0u;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int w = 0; w < WAYS; ++w) {
+      const uint32_t other = codes[w];
+      p += (other < code || (other == code && w < way)) ? 1u : 0u;
+      ne += other != 0xFFFFFFFFu ? 1u : 0u;
+    }
+  }
+  __builtin_amdgcn_wave_barrier();   // the next call's stores come after these loads
+  *pos = p;
+  *n_elig = ne;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Large calls
 // ------------------------------------------------------------------------------------------------
@@ -452,18 +492,28 @@ __global__ __launch_bounds__(1024) void cache_insert_small(u64* __restrict__ tag
   __shared__ uint8_t is_first[kSmallMaxKeys];
   __shared__ uint32_t scan_lds[T / 64 + 1];
   __shared__ uint32_t counters[3];                  // inserted, evicted, skipped
+  __shared__ __attribute__((aligned(16))) uint32_t way_code[T];   // victim ranking, one word per lane
   u64* mkey = wide;                                               // m -> key
   uint32_t* ukey_pos = reinterpret_cast<uint32_t*>(wide);         // q -> position of the key's first appearance
   uint32_t* uset = reinterpret_cast<uint32_t*>(wide) + kSmallMaxKeys;  // q -> set
   const uint32_t tid = threadIdx.x;
   if (tid < 3) counters[tid] = 0;
 
-  // 1. missing positions, ascending
+  // 1. missing positions, ascending (flags and keys of all the thread's positions requested at once,
+  //    index clamped instead of a branch: a load under a branch is waited for before the next one)
+  if (n == 0) return;   // block-uniform
   uint32_t f[PER], cnt = 0;
+  u64 kk[PER];
 #pragma unroll
   for (int i = 0; i < PER; ++i) {
     const uint32_t p = tid * PER + i;
-    f[i] = (p < n && miss_flag[p]) ? 1u : 0u;
+    const uint32_t pc = p < n ? p : n - 1;
+    f[i] = miss_flag[pc];
+    kk[i] = (u64)keys[pc];
+  }
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    f[i] = (tid * PER + i < n && f[i]) ? 1u : 0u;
     cnt += f[i];
   }
   uint32_t M;
@@ -472,7 +522,7 @@ __global__ __launch_bounds__(1024) void cache_insert_small(u64* __restrict__ tag
   for (int i = 0; i < PER; ++i) {
     if (f[i]) {
       pos_or_dst[run] = tid * PER + i;
-      mkey[run] = (u64)keys[tid * PER + i];
+      mkey[run] = kk[i];
       ++run;
     }
   }
@@ -480,13 +530,27 @@ __global__ __launch_bounds__(1024) void cache_insert_small(u64* __restrict__ tag
   if (M == 0) return;   // block-uniform
 
   // 2. first appearance <=> no earlier missing position holds the same key
-  for (uint32_t m = tid; m < M; m += T) {
-    const u64 key = mkey[m];
-    bool first = true;
-    for (uint32_t j = 0; j < m; ++j) {
-      if (mkey[j] == key) { first = false; break; }
+  //    With fewer missing positions than threads, C = T / M threads share the earlier keys of one
+  //    position (183 positions: 5 threads each), eight keys per step read independently of each other.
+  for (uint32_t m = tid; m < M; m += T) is_first[m] = 1;
+  __syncthreads();
+  {
+    const uint32_t C = M < T ? T / M : 1u;
+    for (uint32_t w = tid; w < M * C; w += T) {
+      const uint32_t m = w / C, c = w % C;
+      const uint32_t len = (m + C - 1) / C;
+      const uint32_t j_lo = c * len, j_hi = j_lo + len < m ? j_lo + len : m;
+      const u64 key = mkey[m];
+      bool first = true;
+      for (uint32_t j0 = j_lo; j0 < j_hi && first; j0 += 8) {
+        u64 k[8];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) k[u] = mkey[j0 + u < j_hi ? j0 + u : m];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) first = first && !(j0 + u < j_hi && k[u] == key);
+      }
+      if (!first) is_first[m] = 0;   // several threads may store the same 0
     }
-    is_first[m] = first ? 1 : 0;
   }
   __syncthreads();
 
@@ -515,27 +579,45 @@ __global__ __launch_bounds__(1024) void cache_insert_small(u64* __restrict__ tag
   // 4. placement decisions, one group of WAYS lanes per distinct key (cache state is only read here)
   const int way = tid % WAYS;
   constexpr uint32_t kGroups = T / WAYS;
-  for (uint32_t q0 = 0; q0 < Uq; q0 += kGroups) {
-    const uint32_t q = q0 + tid / WAYS;
-    if (q < Uq) {
-      const uint32_t set = uset[q];
-      uint32_t krank = 0;                               // earlier distinct keys of the same set
-      for (uint32_t j = way; j < q; j += WAYS) krank += uset[j] == set ? 1u : 0u;
+  const uint64_t gmask = ((WAYS == 64 ? 0ull : (1ull << (WAYS & 63))) - 1ull) << ((tid & 63) - way);   // this group's lanes
+  //    The sets' tags and stamps of four keys per group are requested together: one memory round
+  //    trip per four keys instead of one per key.
+  constexpr uint32_t kKeysAtOnce = 4;
+  for (uint32_t q0 = 0; q0 < Uq; q0 += kKeysAtOnce * kGroups) {
+    uint32_t setv[kKeysAtOnce], stv[kKeysAtOnce];
+    u64 tagv[kKeysAtOnce];
 #pragma unroll
-      for (int d = WAYS / 2; d >= 1; d >>= 1) krank += __shfl_xor(krank, d, WAYS);
-      const uint64_t line = (uint64_t)set * WAYS + way;
-      bool eligible, empty;
-      uint32_t pos, n_elig;
-      victim_order<WAYS>(tags[line], stamps[line], epoch, way, &eligible, &empty, &pos, &n_elig);
-      if (krank < n_elig) {
-        if (eligible && pos == krank) {
-          pos_or_dst[q] = (uint32_t)line;
-          atomicAdd(&counters[0], 1u);
-          if (!empty) atomicAdd(&counters[1], 1u);
+    for (uint32_t b = 0; b < kKeysAtOnce; ++b) {
+      const uint32_t q = q0 + b * kGroups + tid / WAYS;
+      setv[b] = uset[q < Uq ? q : Uq - 1];            // clamped: loads without a branch
+      const uint64_t line = (uint64_t)setv[b] * WAYS + way;
+      tagv[b] = tags[line];
+      stv[b] = stamps[line];
+    }
+#pragma unroll
+    for (uint32_t b = 0; b < kKeysAtOnce; ++b) {
+      const uint32_t q = q0 + b * kGroups + tid / WAYS;
+      if (q < Uq) {                                     // uniform within the group of WAYS lanes
+        const uint32_t set = setv[b];
+        uint32_t krank = 0;                             // earlier distinct keys of the same set
+        for (uint32_t j0 = 0; j0 < q; j0 += WAYS) {     // counted by ballot: no cross-lane adds
+          const uint32_t j = j0 + way;
+          krank += (uint32_t)__popcll(__ballot(j < q && uset[j] == set) & gmask);
         }
-      } else if (way == 0) {
-        pos_or_dst[q] = kNoLine;
-        atomicAdd(&counters[2], 1u);
+        const uint64_t line = (uint64_t)set * WAYS + way;
+        bool eligible, empty;
+        uint32_t pos, n_elig;
+        victim_order_lds<WAYS>(way_code + (tid - way), tagv[b], stv[b], epoch, way, &eligible, &empty, &pos, &n_elig);
+        if (krank < n_elig) {
+          if (eligible && pos == krank) {
+            pos_or_dst[q] = (uint32_t)line;
+            atomicAdd(&counters[0], 1u);
+            if (!empty) atomicAdd(&counters[1], 1u);
+          }
+        } else if (way == 0) {
+          pos_or_dst[q] = kNoLine;
+          atomicAdd(&counters[2], 1u);
+        }
       }
     }
   }
@@ -549,21 +631,27 @@ __global__ __launch_bounds__(1024) void cache_insert_small(u64* __restrict__ tag
       stamps[line] = epoch;
     }
   }
-  // rows cross the host link: each group of lanes keeps four row pieces in flight (latency-bound)
+  // rows cross the host link: each group of lanes keeps eight row pieces in flight (latency-bound;
+  // 256 rows per sweep).  The keys come first, all together, then the rows they name.
   constexpr int kCopyLanes = 32;   // lanes per row copy
   constexpr uint32_t kRowsAtOnce = T / kCopyLanes;
-  for (uint32_t q0 = tid / kCopyLanes; q0 < Uq; q0 += 4 * kRowsAtOnce) {
+  constexpr int kInFlight = 8;
+  for (uint32_t q0 = tid / kCopyLanes; q0 < Uq; q0 += kInFlight * kRowsAtOnce) {
+    uint32_t line[kInFlight];
+    int64_t src[kInFlight];
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) {
+      const uint32_t q = q0 + u * kRowsAtOnce;
+      line[u] = q < Uq ? pos_or_dst[q] : kNoLine;
+      src[u] = keys[ukey_pos[q < Uq ? q : Uq - 1]];
+    }
     for (int col = (tid % kCopyLanes) * 4; col < D; col += kCopyLanes * 4) {
-      f32x4 v[4];
-      uint32_t line[4];
+      f32x4 v[kInFlight];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const uint32_t q = q0 + u * kRowsAtOnce;
-        line[u] = q < Uq ? pos_or_dst[q] : kNoLine;
-        if (line[u] != kNoLine) v[u] = load4(host_table + keys[ukey_pos[q]] * D + col);
-      }
+      for (int u = 0; u < kInFlight; ++u)   // unconditional (src always names a real row): no branch between the loads
+        v[u] = load4(host_table + src[u] * D + col);
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < kInFlight; ++u)
         if (line[u] != kNoLine) store4(data + (int64_t)line[u] * D + col, v[u]);
     }
   }
