@@ -68,6 +68,10 @@ def lib() -> C.CDLL:
         L.oracle_cache_stats.argtypes = [p, p]
         L.oracle_cache_state.restype = None
         L.oracle_cache_state.argtypes = [p, p, p, p]
+        L.oracle_cache_set_epoch_limit.restype = None
+        L.oracle_cache_set_epoch_limit.argtypes = [p, C.c_uint32]
+        L.oracle_cache_epoch.restype = C.c_uint32
+        L.oracle_cache_epoch.argtypes = [p]
         L.oracle_cache_insert.restype = None
         L.oracle_cache_insert.argtypes = [p, p, i64]
         L.oracle_cache_update.restype = i64
@@ -272,6 +276,15 @@ class Cache:
         if getattr(self, "_c", None):
             lib().oracle_cache_destroy(self._c)
             self._c = None
+
+    def set_epoch_limit(self, limit: int) -> None:
+        """Call count at which stamps and count are lowered by limit / 2 (default 2^32 - 256)."""
+        assert 2 <= limit <= 0xFFFFFF00
+        lib().oracle_cache_set_epoch_limit(self._c, limit)
+
+    @property
+    def epoch(self) -> int:
+        return int(lib().oracle_cache_epoch(self._c))
 
     def query(self, keys, n_bags: int, offsets=None, insert_missing: bool = True):
         """Returns (out [n_bags, D] float32, hit_mask [nnz] uint8)."""

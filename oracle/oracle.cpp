@@ -344,6 +344,7 @@ struct oracle_cache {
   std::vector<uint32_t> stamp;    // [num_sets * ways], epoch of last hit / insert
   std::vector<float> data;        // [num_sets * ways * dim], copies of host rows
   uint32_t epoch;
+  uint32_t epoch_limit;           // see oracle_cache_set_epoch_limit
   int64_t stats[6];               // queries, hits, misses, inserts, evictions, skipped inserts
 };
 
@@ -365,9 +366,18 @@ oracle_cache* oracle_cache_create(int64_t num_sets, int32_t ways, int32_t dim,
   c->stamp.assign((size_t)num_sets * ways, 0u);
   c->data.assign((size_t)num_sets * ways * dim, 0.0f);
   c->epoch = 0;
+  c->epoch_limit = 0xFFFFFF00u;
   std::memset(c->stats, 0, sizeof(c->stats));
   return c;
 }
+// Stamps are 32-bit call counts, so the count must not run out.  A call that finds the count at or
+// above the limit first lowers every stamp and the count by half the limit; stamps at or below
+// that half become 0, i.e. "never used" (among those the lowest way goes first, as after a clear).
+// The order of all stamps above the half, and so the victim among ways used in the last limit/2
+// calls, is unchanged.  (The paper gives no replacement policy; this keeps the least-recently-used
+// choice meaningful for a server that never restarts.)  limit: 2 .. 2^32 - 256.
+void oracle_cache_set_epoch_limit(oracle_cache* c, uint32_t limit) { c->epoch_limit = limit; }
+uint32_t oracle_cache_epoch(const oracle_cache* c) { return c->epoch; }
 void oracle_cache_destroy(oracle_cache* c) { delete c; }
 void oracle_cache_stats(const oracle_cache* c, int64_t* out) { std::memcpy(out, c->stats, sizeof(c->stats)); }
 void oracle_cache_state(const oracle_cache* c, uint64_t* tags, uint32_t* stamps, float* data) {
@@ -385,6 +395,11 @@ void oracle_cache_state(const oracle_cache* c, uint64_t* tags, uint32_t* stamps,
 void oracle_cache_query(oracle_cache* c, int64_t n_bags, const int64_t* keys,
                         const int64_t* offsets, int64_t hotness, int64_t nnz,
                         int32_t insert_missing, float* out, uint8_t* hit_mask) {
+  if (c->epoch >= c->epoch_limit) {
+    const uint32_t by = c->epoch_limit / 2;
+    for (uint32_t& st : c->stamp) st = st > by ? st - by : 0u;
+    c->epoch -= by;
+  }
   c->epoch += 1;
   const int W = c->ways, D = c->dim;
   std::vector<int64_t> where(nnz, -1);            // cache line (set*ways+way) for hits

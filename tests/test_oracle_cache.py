@@ -181,3 +181,52 @@ def test_refresh_rereads_every_resident_row_from_the_host_table():
     assert np.array_equal(tags, tags0) and np.array_equal(stamps, stamps0)
     assert np.array_equal(data[live], ht[tags.ravel()[live].astype(np.int64)])
     assert np.all(data[~live] == 0)                       # empty lines are left alone
+
+
+def test_epoch_limit_hand_worked():
+    """One set of three ways, limit 4: a call that finds the count at 4 first lowers stamps and count
+    by 2 (stamps <= 2 become 0).  Expected states worked out by hand; E = empty."""
+    E = int(oracle.EMPTY_TAG)
+    c = oracle.Cache(1, 3, host_table(10, 4))
+    c.set_epoch_limit(4)
+    steps = [  # key, hit, tags, stamps, count after the call
+        (1, 0, [1, E, E], [1, 0, 0], 1),
+        (2, 0, [1, 2, E], [1, 2, 0], 2),
+        (2, 1, [1, 2, E], [1, 3, 0], 3),
+        (2, 1, [1, 2, E], [1, 4, 0], 4),
+        (3, 0, [1, 2, 3], [0, 2, 3], 3),   # lowered first: [0, 2, 0], count 2 -> 3; key 3 takes the empty way
+        (4, 0, [4, 2, 3], [4, 2, 3], 4),   # no empty way: the smallest stamp (way 0) goes
+        (5, 0, [4, 5, 3], [2, 3, 1], 3),   # lowered first: [2, 0, 1], count 2 -> 3; way 1 goes
+        (1, 0, [4, 5, 1], [2, 3, 4], 4),   # way 2 (stamp 1) was the oldest: the order survived the lowering
+    ]
+    for key, hit, tags, stamps, count in steps:
+        _, h = c.query(np.array([key]), 1)
+        t, s = c.state()
+        assert (int(h[0]), t[0].tolist(), s[0].tolist(), c.epoch) == (hit, tags, stamps, count)
+
+
+def test_epoch_limit_leaves_classical_lru_intact():
+    """The count passes a limit of 64 many times in 600 calls; every resident key was used within the
+    last 32 calls (5 ways, 12 keys), so no stamp ever collapses and the cache must still be the
+    textbook LRU - it would not be if the lowering lost the order or froze the replacement."""
+    ways, ht = 5, host_table(40, 4)
+    c = oracle.Cache(1, ways, ht)
+    c.set_epoch_limit(64)
+    rng = np.random.default_rng(5)
+    lru = OrderedDict()
+    top = 0
+    for _ in range(600):
+        k = int(rng.integers(0, 12))
+        _, hit = c.query(np.array([k]), 1)
+        assert bool(hit[0]) == (k in lru)
+        if k in lru:
+            lru.move_to_end(k)
+        else:
+            if len(lru) == ways:
+                lru.popitem(last=False)
+            lru[k] = True
+        tags, stamps = c.state()
+        assert sorted(t for t in tags[0].tolist() if t != int(oracle.EMPTY_TAG)) == sorted(lru)
+        assert c.epoch <= 64 and stamps.max() <= c.epoch
+        top = max(top, c.epoch)
+    assert top == 64
