@@ -321,6 +321,13 @@ size_t hctr_cache_workspace_bytes(const hctr_cache* cache, int64_t nnz_max);
  * fused kernels instead of the general pipeline, because at that size launches cost more than
  * bytes.  Both paths give identical results; 0 switches the fused path off. */
 hctr_status hctr_cache_set_small_call_limit(hctr_cache* cache, int64_t max_keys);
+/* The recency stamps are 32-bit counts of the query / insert calls made so far.  A call that finds
+ * the count at or above `limit` (2 .. 2^32 - 256, the default) first lowers every stamp and the
+ * count by limit / 2, stamps at or below that becoming 0 = never used (among those the lowest way
+ * is replaced first).  The order of the ways used within the last limit / 2 calls is unchanged, so
+ * a cache serves any number of calls.  Lower limits exist for tests.  (The paper gives no
+ * replacement policy; section 3, "embedding inference cache", only names dynamic insertion.) */
+hctr_status hctr_cache_set_epoch_limit(hctr_cache* cache, int64_t limit);
 /*
  * One query: out[bag, :] = sum of the vectors of the bag's keys (fp32, fixed order).  Every key is
  * classified against the cache contents at call entry: a hit reads the cached line and marks it

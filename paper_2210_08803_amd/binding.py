@@ -96,6 +96,7 @@ def lib() -> C.CDLL:
         "hctr_cache_create": (i32, [p, sz, i64, i32, i32, p, i64, p, C.POINTER(p)]),
         "hctr_cache_workspace_bytes": (sz, [p, i64]),
         "hctr_cache_set_small_call_limit": (i32, [p, i64]),
+        "hctr_cache_set_epoch_limit": (i32, [p, i64]),
         "hctr_cache_query": (i32, [p, i64, i32, p, p, i64, i32, p, p, p, sz, p]),
         "hctr_cache_query_async": (i32, [p, i64, i32, p, p, i64, i32, p, p, p, sz, p, p]),
         "hctr_cache_insert": (i32, [p, p, i64, p, sz, p]),
@@ -121,7 +122,7 @@ EXPORTS = [
     "hctr_hash_insert_or_find", "hctr_hash_size", "hctr_hash_destroy", "hctr_hash_clear", "hctr_etc_storage_bytes",
     "hctr_etc_workspace_bytes", "hctr_etc_create", "hctr_etc_load", "hctr_etc_dump", "hctr_etc_stats",
     "hctr_etc_destroy", "hctr_cache_storage_bytes",
-    "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_set_small_call_limit", "hctr_cache_query",
+    "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_set_small_call_limit", "hctr_cache_set_epoch_limit", "hctr_cache_query",
     "hctr_cache_query_async", "hctr_cache_insert", "hctr_cache_update", "hctr_cache_refresh", "hctr_cache_stats",
     "hctr_cache_state_view", "hctr_cache_destroy", "hctr_last_error",
 ]
@@ -454,6 +455,9 @@ class EmbeddingCache:
 
     def set_small_call_limit(self, max_keys: int) -> None:
         _check(lib().hctr_cache_set_small_call_limit(self.handle, max_keys))
+
+    def set_epoch_limit(self, limit: int) -> None:
+        _check(lib().hctr_cache_set_epoch_limit(self.handle, limit))
 
     def workspace(self, nnz: int) -> torch.Tensor:
         need = lib().hctr_cache_workspace_bytes(self.handle, nnz)

@@ -31,6 +31,7 @@ struct hctr_cache {
   int64_t host_rows;
   size_t off_tags, off_stamps, off_data;
   uint32_t epoch;          // number of query calls so far (host copy; kernels get it as an argument)
+  uint32_t epoch_limit;    // a call that finds epoch >= this first lowers stamps and epoch by half of it
   int64_t small_max_keys;  // calls with at most this many keys take the fused small-call kernels
 };
 
@@ -73,6 +74,17 @@ __global__ __launch_bounds__(256) void cache_clear(u64* tags, uint32_t* stamps, 
   if (i < n_lines) { tags[i] = kEmptyKey; stamps[i] = 0u; }
   if (i < 6) hdr->stats[i] = 0;
   if (i == 0) hdr->epoch = 0;
+}
+
+// Stamps are 32-bit call counts; before the count runs out every stamp is lowered by `by` (and the
+// host's count with them).  Stamps at or below `by` become 0, "never used".
+__global__ __launch_bounds__(256) void cache_lower_stamps(uint32_t* __restrict__ stamps, uint64_t n_lines,
+                                                          uint32_t by) {
+  const uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+  if (i < n_lines) {
+    const uint32_t s = stamps[i];
+    stamps[i] = s > by ? s - by : 0u;
+  }
 }
 
 // Position of this way in its set's victim list (ways used in this call are not in the list), and
@@ -922,6 +934,7 @@ HCTR_API hctr_status hctr_cache_create(void* storage, size_t storage_bytes, int6
   c->host_table = host_table; c->host_rows = host_rows;
   c->epoch = 0;
   c->small_max_keys = kSmallMaxKeys;
+  c->epoch_limit = 0xFFFFFF00u;
   const uint64_t lines = (uint64_t)num_sets * ways;
   hipLaunchKernelGGL(cache_clear, dim3((uint32_t)ceil_div((int64_t)(lines > 6 ? lines : 6), 256)), dim3(256), 0,
                      static_cast<hipStream_t>(stream), reinterpret_cast<u64*>(c->storage + c->off_tags),
@@ -930,6 +943,14 @@ HCTR_API hctr_status hctr_cache_create(void* storage, size_t storage_bytes, int6
   hctr_status st = launch_status("cache_clear");
   if (st != HCTR_OK) { delete c; return st; }
   *out = c;
+  return HCTR_OK;
+}
+
+HCTR_API hctr_status hctr_cache_set_epoch_limit(hctr_cache* c, int64_t limit) {
+  if (!c) return fail(HCTR_E_NULL_PTR, "cache is NULL");
+  if (limit < 2 || limit > 0xFFFFFF00ll)
+    return fail(HCTR_E_INVALID_ARG, "limit %lld outside 2..2^32-256", (long long)limit);
+  c->epoch_limit = (uint32_t)limit;
   return HCTR_OK;
 }
 
@@ -981,6 +1002,15 @@ static hctr_status cache_query_impl(hctr_cache* c, int64_t batch, int32_t num_sl
 
   char* w = static_cast<char*>(ws);
   HashWsHeader* ws_hdr = reinterpret_cast<HashWsHeader*>(w + L.header);
+  if (c->epoch >= c->epoch_limit) {   // the count is about to run out: lower it and every stamp
+    const uint32_t by = c->epoch_limit / 2;
+    const uint64_t lines = (uint64_t)c->num_sets * c->ways;
+    hipLaunchKernelGGL(cache_lower_stamps, dim3((uint32_t)ceil_div((int64_t)lines, 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream_), reinterpret_cast<uint32_t*>(c->storage + c->off_stamps),
+                       lines, by);
+    HCTR_TRY(launch_status("cache_lower_stamps"));
+    c->epoch -= by;
+  }
   c->epoch += 1;
   QueryArgs a{c, keys, offsets, hotness, (uint32_t)nnz, (uint32_t)n_bags, c->epoch, out, hit_mask,
               reinterpret_cast<uint32_t*>(w + L.line_of),

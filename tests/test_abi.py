@@ -135,6 +135,8 @@ def test_hash_and_cache_argument_errors():
     assert L.hctr_cache_create(4096, 16, 8, 4, 16, 4096, 10, None, C.byref(c)) == -1
     assert L.hctr_cache_create(4096, 1 << 20, 8, 4, 16, None, 10, None, C.byref(c)) == -2
     assert L.hctr_cache_query(None, 1, 1, 4096, None, 1, 1, 4096, None, 4096, 1 << 20, None) == -2
+    assert L.hctr_cache_set_epoch_limit(None, 100) == -2
+    assert L.hctr_cache_set_small_call_limit(None, 100) == -2
 
 
 def test_etc_argument_errors():

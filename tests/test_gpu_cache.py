@@ -96,6 +96,32 @@ def test_zipf_traffic_matches_the_simulation(num_sets, ways, dim, small_limit):
 
 
 @pytest.mark.parametrize("small_limit", [0, 8192], ids=["general", "fused-small"])
+def test_call_count_limit_lowers_stamps_like_the_simulation(small_limit):
+    """With a limit of 6 the call count and every stamp are lowered by 3 every few calls; ways not
+    used for 3 calls collapse to stamp 0.  Tags, stamps, rows and statistics must stay equal to the
+    oracle's after each of 40 calls, insert-only calls included."""
+    host_rows, dim = 3000, 32
+    p = Pair(24, 4, pinned_table(host_rows, dim), small_limit)
+    p.gpu.set_epoch_limit(6)
+    p.ref.set_epoch_limit(6)
+    smp = datagen.ZipfSampler(host_rows, 1.1)
+    lowered = 0
+    for it in range(40):
+        before = p.ref.epoch
+        keys = datagen.cache_keys(SEED, 300 + it, host_rows, 60, 1.1, sampler=smp).numpy()
+        if it % 7 == 3:
+            p.ref.insert(keys)
+            p.gpu.insert(to_dev(keys))
+            torch.cuda.synchronize()
+            _state_equal(p, f"insert {it}")
+        else:
+            p.query(keys, 20, insert=(it % 5 != 4), what=f"call {it}")
+        lowered += p.ref.epoch <= before
+        assert p.ref.epoch <= 6
+    assert lowered >= 10
+
+
+@pytest.mark.parametrize("small_limit", [0, 8192], ids=["general", "fused-small"])
 def test_csr_bags_and_batch_of_one_key(small_limit):
     host_rows, dim = 800, 64
     p = Pair(32, 4, pinned_table(host_rows, dim), small_limit)
