@@ -1054,7 +1054,8 @@ static hctr_status cache_query_impl(hctr_cache* c, int64_t batch, int32_t num_sl
                  reinterpret_cast<u64*>(w + L.scratch),
                  L.scratch_cap_max,
                  &ws_hdr->n_miss,
-                 &ws_hdr->n_new};
+                 &ws_hdr->n_new,
+                 nullptr};
   HCTR_TRY(dedup_first_appearance(keys, a.n, B, a.stream));
   u64* new_key = reinterpret_cast<u64*>(w + L.new_key);
   u64* kv[2] = {reinterpret_cast<u64*>(w + L.kv0), reinterpret_cast<u64*>(w + L.kv1)};
@@ -1139,7 +1140,8 @@ HCTR_API hctr_status hctr_cache_update(hctr_cache* c, const int64_t* keys, const
                  reinterpret_cast<u64*>(w + L.scratch),
                  L.scratch_cap_max,
                  &ws_hdr->n_miss,
-                 &ws_hdr->n_new};
+                 &ws_hdr->n_new,
+                 nullptr};
   const uint32_t nn = (uint32_t)n;
   const u64* tags = reinterpret_cast<const u64*>(c->storage + c->off_tags);
   float* data = reinterpret_cast<float*>(c->storage + c->off_data);

@@ -64,10 +64,12 @@ struct Carver {
 // ---- device-side scan and sort primitives (primitives.hip) -------------------------------------
 
 // Exclusive prefix sum of uint32 in[0..n) into out (may alias in).  tmp holds scan_tmp_count(n)
-// uint32.  If total != nullptr the grand total is written there (uint32).
+// uint32.  If total != nullptr the grand total is written there (uint32).  With n_dev != nullptr
+// only the first min(*n_dev, n) items are scanned (a count known on the device only, read when the
+// kernels run); items past it are neither read nor written, and total covers the scanned ones.
 size_t scan_tmp_count(uint32_t n);
 hctr_status exclusive_scan_u32(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* tmp,
-                               uint32_t* total, hipStream_t stream);
+                               uint32_t* total, hipStream_t stream, const uint32_t* n_dev = nullptr);
 
 // Stable LSD radix sort of packed words (key << 32 | value) on the low `bits` bits of the key, in
 // ceil(bits / 10) passes of evenly sized digits.  The element count is *n_dev if n_dev != nullptr

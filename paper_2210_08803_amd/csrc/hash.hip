@@ -57,7 +57,14 @@ constexpr int kFindKeys = 4;   // find-only call on 3.4 M keys, load 0.8: 0.277 
 __global__ __launch_bounds__(256) void hash_find(const u64x2* __restrict__ slots, uint32_t n_buckets,
                                                  const int64_t* __restrict__ keys, uint32_t n,
                                                  int64_t* __restrict__ rows,
-                                                 uint32_t* __restrict__ miss_flag) {
+                                                 uint32_t* __restrict__ miss_flag,
+                                                 const HashHeader* __restrict__ table_hdr, int64_t max_rows,
+                                                 HashWsHeader* ws_hdr) {
+  // A table that already holds max_rows rows rejects every new key: nothing is flagged as missing
+  // then, the scans are told to look at no position, and the insertion kernels that follow find an
+  // empty list (row -1 is already the answer).
+  const bool full = table_hdr != nullptr && table_hdr->size >= (u64)max_rows;
+  if (ws_hdr != nullptr && blockIdx.x == 0 && threadIdx.x == 0) ws_hdr->n_scan = full ? 0u : n;
   const uint64_t i0 = (uint64_t)((blockIdx.x * 256u + threadIdx.x) >> 3) * kFindKeys;
   const int sub = threadIdx.x & 7;
   int64_t key[kFindKeys], row[kFindKeys];
@@ -103,7 +110,7 @@ __global__ __launch_bounds__(256) void hash_find(const u64x2* __restrict__ slots
     for (int u = 0; u < kFindKeys; ++u) {
       if (i0 + u < n) {
         rows[i0 + u] = row[u];
-        if (miss_flag) miss_flag[i0 + u] = (key[u] >= 0 && row[u] < 0) ? 1u : 0u;
+        if (miss_flag) miss_flag[i0 + u] = (key[u] >= 0 && row[u] < 0 && !full) ? 1u : 0u;
       }
     }
   }
@@ -233,7 +240,7 @@ hctr_status dedup_first_appearance(const int64_t* keys, uint32_t n, const DedupB
                                    hipStream_t stream) {
   const uint32_t nb = (uint32_t)ceil_div(n, 256);
   const HashWsHeader* hdr = reinterpret_cast<const HashWsHeader*>(B.n_miss);
-  HCTR_TRY(exclusive_scan_u32(B.flag, B.idx, n, B.scan_tmp, B.n_miss, stream));
+  HCTR_TRY(exclusive_scan_u32(B.flag, B.idx, n, B.scan_tmp, B.n_miss, stream, B.n_scan));
   hipLaunchKernelGGL(hash_compact_misses, dim3(nb), dim3(256), 0, stream, (const uint32_t*)B.flag,
                      (const uint32_t*)B.idx, n, B.miss_pos);
   hipLaunchKernelGGL(scratch_clear, dim3((uint32_t)ceil_div(B.scratch_cap_max, 256)), dim3(256), 0, stream,
@@ -242,7 +249,7 @@ hctr_status dedup_first_appearance(const int64_t* keys, uint32_t n, const DedupB
                      (const uint32_t*)B.miss_pos, B.scr_slot);
   hipLaunchKernelGGL(first_flags, dim3(nb), dim3(256), 0, stream, (const u64*)B.scratch, hdr,
                      (const uint32_t*)B.miss_pos, (const uint32_t*)B.scr_slot, n, B.first);
-  HCTR_TRY(exclusive_scan_u32(B.first, B.rank, n, B.scan_tmp, B.n_new, stream));
+  HCTR_TRY(exclusive_scan_u32(B.first, B.rank, n, B.scan_tmp, B.n_new, stream, B.n_miss));   // first[m] is used for m < n_miss only
   return launch_status("dedup_first_appearance");
 }
 
@@ -282,7 +289,7 @@ hctr_status hash_lookup(hctr_hash* h, const int64_t* keys, int64_t n64, int inse
   const uint32_t find_blocks = (uint32_t)ceil_div(ceil_div((int64_t)n, kFindKeys) * 8, 256);
   if (!insert) {
     hipLaunchKernelGGL(hash_find, dim3(find_blocks), dim3(256), 0, stream, slots, h->n_buckets, keys, n,
-                       rows, (uint32_t*)nullptr);
+                       rows, (uint32_t*)nullptr, (const HashHeader*)nullptr, (int64_t)0, (HashWsHeader*)nullptr);
     return launch_status("hash_find");
   }
   const HashWsLayout L = hash_ws_layout(n64);
@@ -302,9 +309,10 @@ hctr_status hash_lookup(hctr_hash* h, const int64_t* keys, int64_t n64, int inse
   u64* scratch = reinterpret_cast<u64*>(w + L.scratch);
   const uint32_t nb = (uint32_t)ceil_div(n, 256);
 
-  hipLaunchKernelGGL(hash_find, dim3(find_blocks), dim3(256), 0, stream, slots, h->n_buckets, keys, n, rows, flag);
+  hipLaunchKernelGGL(hash_find, dim3(find_blocks), dim3(256), 0, stream, slots, h->n_buckets, keys, n, rows, flag,
+                     (const HashHeader*)thdr, h->max_rows, hdr);
   DedupBuffers B{flag, idx, miss_pos, scr_slot, first, rank, scan_tmp, scratch, L.scratch_cap_max,
-                 &hdr->n_miss, &hdr->n_new};
+                 &hdr->n_miss, &hdr->n_new, &hdr->n_scan};
   HCTR_TRY(dedup_first_appearance(keys, n, B, stream));
   hipLaunchKernelGGL(hash_insert_new, dim3(nb), dim3(256), 0, stream, h->slots, h->n_buckets,
                      (const HashHeader*)thdr, h->max_rows, scratch, (const HashWsHeader*)hdr, keys,

@@ -17,7 +17,8 @@ namespace hctr {
 struct HashWsHeader {
   uint32_t n_miss;   // positions whose key was not found
   uint32_t n_new;    // distinct keys among them
-  uint32_t pad[62];
+  uint32_t n_scan;   // insert-or-find: how many positions can hold a missing key (0 once the table is full)
+  uint32_t pad[61];
 };
 
 // Work arrays of the first-appearance dedup, each [n] unless noted.
@@ -33,6 +34,7 @@ struct DedupBuffers {
   uint32_t scratch_cap_max;     // dedup_scratch_capacity(n)
   uint32_t* n_miss;     // device: &HashWsHeader::n_miss
   uint32_t* n_new;      // device: &HashWsHeader::n_new
+  const uint32_t* n_scan;  // device, or nullptr: only flag[0 .. *n_scan) can be set (nullptr: all n)
 };
 uint32_t dedup_scratch_capacity(uint32_t n_max);
 hctr_status dedup_first_appearance(const int64_t* keys, uint32_t n, const DedupBuffers& B,

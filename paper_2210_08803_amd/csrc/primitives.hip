@@ -16,9 +16,21 @@ constexpr int kScanThreads = 256;
 constexpr int kScanItems = 16;
 constexpr uint32_t kScanTile = kScanThreads * kScanItems;  // 4096
 
+// Length actually scanned: the first *n_dev items when a device-side count is given (never more
+// than the host's n); items past it are neither read nor written.
+__device__ __forceinline__ uint32_t scan_length(uint32_t n_host, const uint32_t* n_dev) {
+  if (n_dev == nullptr) return n_host;
+  const uint32_t nd = *n_dev;
+  return nd < n_host ? nd : n_host;
+}
+
+
 __global__ __launch_bounds__(kScanThreads) void scan_tile_sums(const uint32_t* __restrict__ in,
-                                                               uint32_t n, uint32_t* __restrict__ sums) {
+                                                               uint32_t n_host,
+                                                               const uint32_t* __restrict__ n_dev,
+                                                               uint32_t* __restrict__ sums) {
   __shared__ uint32_t lds[kScanThreads / 64 + 1];
+  const uint32_t n = scan_length(n_host, n_dev);
   const uint32_t base = blockIdx.x * kScanTile;
   uint32_t s = 0;
 #pragma unroll
@@ -48,10 +60,12 @@ __global__ __launch_bounds__(1024) void scan_sums_inplace(uint32_t* __restrict__
 }
 
 // in and out may be the same array: a thread reads all of its items before it writes any.
-__global__ __launch_bounds__(kScanThreads) void scan_apply(const uint32_t* in, uint32_t* out, uint32_t n,
+__global__ __launch_bounds__(kScanThreads) void scan_apply(const uint32_t* in, uint32_t* out, uint32_t n_host,
+                                                           const uint32_t* __restrict__ n_dev,
                                                            const uint32_t* __restrict__ sums,
                                                            uint32_t* __restrict__ total_out) {
   __shared__ uint32_t lds[kScanThreads / 64 + 1];
+  const uint32_t n = scan_length(n_host, n_dev);
   const uint32_t base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
   uint32_t v[kScanItems];
   uint32_t s = 0;
@@ -74,16 +88,16 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply(const uint32_t* in, u
 size_t scan_tmp_count(uint32_t n) { return (size_t)ceil_div(n > 0 ? n : 1, kScanTile); }
 
 hctr_status exclusive_scan_u32(const uint32_t* in, uint32_t* out, uint32_t n, uint32_t* tmp,
-                               uint32_t* total, hipStream_t stream) {
+                               uint32_t* total, hipStream_t stream, const uint32_t* n_dev) {
   const uint32_t nb = (uint32_t)ceil_div(n > 0 ? n : 1, kScanTile);
   if (nb == 1) {
-    hipLaunchKernelGGL(scan_apply, dim3(1), dim3(kScanThreads), 0, stream, in, out, n,
+    hipLaunchKernelGGL(scan_apply, dim3(1), dim3(kScanThreads), 0, stream, in, out, n, n_dev,
                        (const uint32_t*)nullptr, total);
     return launch_status("scan_apply");
   }
-  hipLaunchKernelGGL(scan_tile_sums, dim3(nb), dim3(kScanThreads), 0, stream, in, n, tmp);
+  hipLaunchKernelGGL(scan_tile_sums, dim3(nb), dim3(kScanThreads), 0, stream, in, n, n_dev, tmp);
   hipLaunchKernelGGL(scan_sums_inplace, dim3(1), dim3(1024), 0, stream, tmp, nb, total);
-  hipLaunchKernelGGL(scan_apply, dim3(nb), dim3(kScanThreads), 0, stream, in, out, n,
+  hipLaunchKernelGGL(scan_apply, dim3(nb), dim3(kScanThreads), 0, stream, in, out, n, n_dev,
                      (const uint32_t*)tmp, (uint32_t*)nullptr);
   return launch_status("exclusive_scan_u32");
 }
