@@ -1390,7 +1390,8 @@ static hctr_status group_prepare(const hctr_group_desc* d, int64_t batch, const 
   if (ws_bytes < L->total)
     return fail(HCTR_E_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, L->total);
   *csr = offsets;
-  if (!offsets && n_bags > 0 && need_csr) {
+  // Dense input with one key per lookup is the one-hot case (bag i holds key i): no offsets needed.
+  if (!offsets && n_bags > 0 && need_csr && P->per_sample != P->L) {
     int64_t* gen = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + L->extra);
     hipLaunchKernelGGL(group_dense_offsets, dim3((uint32_t)ceil_div(n_bags + 1, 256)), dim3(256), 0, stream, P->hot,
                        (uint64_t)n_bags, gen);
@@ -1429,8 +1430,10 @@ static void group_launch_reduce(const GroupPlan& P, const EmbLayout& L, char* w,
   view.L = P.L;
   view.width_total = P.width_total;
   view.dmax_ = P.dmax;
-  for (int l = 0; l < HCTR_MAX_GROUP_LOOKUPS; ++l)
+  for (int l = 0; l < HCTR_MAX_GROUP_LOOKUPS; ++l) {
     view.lk[l] = l < (int)P.L ? P.lk[l] : GroupLookup{nullptr, 0, 0, 0, 0};
+    if (csr == nullptr) view.lk[l].mean = 0;   // one key per bag: the mean is the sum, and no offsets exist to read
+  }
   dispatch_reduce_view<T>(view, P.dmax, false, L, w, skv, csr, lr, stream);
 }
 
