@@ -304,7 +304,7 @@ __global__ __launch_bounds__(256) void cache_list_new(const HashWsHeader* hdr,
                                                       const uint32_t* __restrict__ scr_slot,
                                                       const uint32_t* __restrict__ first,
                                                       const uint32_t* __restrict__ rank, SetDiv num_sets,
-                                                      u64* __restrict__ scratch, u64* __restrict__ new_key,
+                                                      uint32_t* __restrict__ scratch, u64* __restrict__ new_key,
                                                       u64* __restrict__ sort_kv) {
   const uint32_t m = blockIdx.x * 256u + threadIdx.x;
   if (m >= hdr->n_miss || !first[m]) return;
@@ -312,18 +312,18 @@ __global__ __launch_bounds__(256) void cache_list_new(const HashWsHeader* hdr,
   const u64 key = (u64)keys[miss_pos[m]];
   new_key[q] = key;
   sort_kv[q] = (set_of(key, num_sets) << 32) | (u64)q;   // sorted by set, payload = first-appearance index
-  scratch[2ull * scr_slot[m] + 1] = (u64)q;
+  scratch[scr_slot[m]] = q;   // the slot's position has served its purpose (first[] is final)
 }
 
 // Every missing position learns the staging row of its key.
 __global__ __launch_bounds__(256) void cache_mark_staged(const HashWsHeader* hdr,
                                                          const uint32_t* __restrict__ miss_pos,
                                                          const uint32_t* __restrict__ scr_slot,
-                                                         const u64* __restrict__ scratch,
+                                                         const uint32_t* __restrict__ scratch,
                                                          uint32_t* __restrict__ line_of) {
   const uint32_t m = blockIdx.x * 256u + threadIdx.x;
   if (m >= hdr->n_miss) return;
-  line_of[miss_pos[m]] = kStaged | (uint32_t)scratch[2ull * scr_slot[m] + 1];
+  line_of[miss_pos[m]] = kStaged | scratch[scr_slot[m]];
 }
 
 // One row per group of LPR lanes: host table -> staging (the only trip across the host link).
@@ -773,7 +773,7 @@ static CacheWsLayout cache_ws_layout(const hctr_cache* c, int64_t nnz_max) {
   L.scr_slot = at(n * 4); L.first = at(n * 4); L.rank = at(n * 4);
   L.scan_tmp = at(scan_tmp_count((uint32_t)n) * 4);
   L.scratch_cap_max = dedup_scratch_capacity((uint32_t)n);
-  L.scratch = at((size_t)L.scratch_cap_max * 16);
+  L.scratch = at((size_t)L.scratch_cap_max * 4);
   L.new_key = at(n * 8);
   L.kv0 = at(n * 8); L.kv1 = at(n * 8);
   L.hist = at(L.sort.hist_count * 4);
@@ -1051,7 +1051,7 @@ static hctr_status cache_query_impl(hctr_cache* c, int64_t batch, int32_t num_sl
                  reinterpret_cast<uint32_t*>(w + L.first),
                  reinterpret_cast<uint32_t*>(w + L.rank),
                  reinterpret_cast<uint32_t*>(w + L.scan_tmp),
-                 reinterpret_cast<u64*>(w + L.scratch),
+                 reinterpret_cast<uint32_t*>(w + L.scratch),
                  L.scratch_cap_max,
                  &ws_hdr->n_miss,
                  &ws_hdr->n_new,
@@ -1066,7 +1066,7 @@ static hctr_status cache_query_impl(hctr_cache* c, int64_t batch, int32_t num_sl
                      (const uint32_t*)B.miss_pos, (const uint32_t*)B.scr_slot, (const uint32_t*)B.first,
                      (const uint32_t*)B.rank, make_set_div(c->num_sets), B.scratch, new_key, kv[0]);
   hipLaunchKernelGGL(cache_mark_staged, dim3(nb), dim3(256), 0, a.stream, (const HashWsHeader*)ws_hdr,
-                     (const uint32_t*)B.miss_pos, (const uint32_t*)B.scr_slot, (const u64*)B.scratch, a.line_of);
+                     (const uint32_t*)B.miss_pos, (const uint32_t*)B.scr_slot, (const uint32_t*)B.scratch, a.line_of);
 #define CALL(LL) launch_fetch_fill<LL>(a, ws_hdr, new_key, staging, dst, false)
   HCTR_BY_LPR(lpr, CALL)
 #undef CALL
@@ -1137,7 +1137,7 @@ HCTR_API hctr_status hctr_cache_update(hctr_cache* c, const int64_t* keys, const
                  reinterpret_cast<uint32_t*>(w + L.first),
                  reinterpret_cast<uint32_t*>(w + L.rank),
                  reinterpret_cast<uint32_t*>(w + L.scan_tmp),
-                 reinterpret_cast<u64*>(w + L.scratch),
+                 reinterpret_cast<uint32_t*>(w + L.scratch),
                  L.scratch_cap_max,
                  &ws_hdr->n_miss,
                  &ws_hdr->n_new,

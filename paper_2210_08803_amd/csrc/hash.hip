@@ -6,12 +6,13 @@
 // Insert-or-find keeps the table's contract "rows are handed out in order of first appearance in
 // the call's key array" without any sequential step:
 //   1. find every key; flag the misses and compact their positions (scan);
-//   2. put the missed keys into a scratch table sized for this call, keeping per key the smallest
-//      position (atomicMin) = its first appearance;
+//   2. put the missed keys into a scratch table sized for this call: a slot holds only a position
+//      of the call's key array (4 bytes; the key it stands for is keys[position]) and keeps the
+//      smallest position of its key (atomicMin) = the key's first appearance;
 //   3. flag the first appearances, scan them: rank = how many new keys appear earlier;
 //   4. row = size + rank; keys whose row stays below max_rows claim a slot of the main table with a
 //      64-bit compare-and-swap and publish the row, the others are rejected;
-//   5. every missed position reads its key's verdict back from the scratch table.
+//   5. every other missed position copies the answer of its key's first appearance.
 // The main table only ever holds published keys, so a later search never meets a half-made entry.
 #include "hash_internal.h"
 
@@ -123,15 +124,18 @@ __global__ __launch_bounds__(256) void hash_compact_misses(const uint32_t* __res
   if (i < n && flag[i]) miss_pos[idx[i]] = i;
 }
 
-__global__ __launch_bounds__(256) void scratch_clear(u64x2* scratch, const HashWsHeader* hdr) {
+constexpr uint32_t kNoPos = 0xFFFFFFFFu;   // empty scratch slot (positions stay below 2^31)
+
+__global__ __launch_bounds__(256) void scratch_clear(uint32_t* scratch, const HashWsHeader* hdr) {
   const uint32_t cap = scratch_capacity(hdr->n_miss);
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-  if (hdr->n_miss != 0 && i < cap) scratch[i] = u64x2{kEmptyKey, kEmptyKey};
+  if (hdr->n_miss != 0 && i < cap) scratch[i] = kNoPos;
 }
 
-// One missed key per lane: claim or join the key's scratch slot, keep the smallest position.
-__global__ __launch_bounds__(256) void scratch_insert(u64* scratch /* {key, val} pairs */,
-                                                      const HashWsHeader* hdr,
+// One missed key per lane: claim or join the key's scratch slot, keep the smallest position.  A slot
+// holds a position p and stands for the key keys[p]; once claimed it only ever moves to smaller
+// positions of the same key, so "keys[slot] == my key" stays true or stays false.
+__global__ __launch_bounds__(256) void scratch_insert(uint32_t* scratch, const HashWsHeader* hdr,
                                                       const int64_t* __restrict__ keys,
                                                       const uint32_t* __restrict__ miss_pos,
                                                       uint32_t* __restrict__ scr_slot) {
@@ -143,14 +147,17 @@ __global__ __launch_bounds__(256) void scratch_insert(u64* scratch /* {key, val}
   const u64 key = (u64)keys[pos];
   uint32_t s = (uint32_t)(mix_key(key ^ 0x5851F42D4C957F2Dull) >> 16) & (cap - 1);
   for (uint32_t step = 0; step < cap; ++step) {
-    // A plain look first: a slot's key never changes once set and its position only shrinks, so a
-    // (possibly stale) view that already shows this key with a position <= pos settles the matter
-    // without an atomic.  A hot key repeated a million times would otherwise queue a million
-    // atomics on one address (measured: 22 ms for 11.5 M keys of a Zipf pass, now under 1 ms).
-    u64 seen = scratch[2ull * s];
-    if (seen == kEmptyKey) seen = atomicCAS(&scratch[2ull * s], kEmptyKey, key);
-    if (seen == kEmptyKey || seen == key) {
-      if (scratch[2ull * s + 1] > (u64)pos) atomicMin(&scratch[2ull * s + 1], (u64)pos);
+    // A plain look first: a view (possibly stale) that already shows this key with a position
+    // <= pos settles the matter without an atomic.  A hot key repeated a million times would
+    // otherwise queue a million atomics on one address (measured: 22 ms for 11.5 M keys of a Zipf
+    // pass, under 1 ms with the look).  A new key costs one load and one compare-and-swap.
+    uint32_t seen = scratch[s];
+    if (seen == kNoPos) {
+      seen = atomicCAS(&scratch[s], kNoPos, pos);
+      if (seen == kNoPos) { scr_slot[m] = s; return; }   // claimed
+    }
+    if ((u64)keys[seen] == key) {
+      if (seen > pos) atomicMin(&scratch[s], pos);
       scr_slot[m] = s;
       return;
     }
@@ -159,7 +166,7 @@ __global__ __launch_bounds__(256) void scratch_insert(u64* scratch /* {key, val}
   scr_slot[m] = 0xFFFFFFFFu;  // cannot happen: at most cap/2 distinct keys
 }
 
-__global__ __launch_bounds__(256) void first_flags(const u64* __restrict__ scratch,
+__global__ __launch_bounds__(256) void first_flags(const uint32_t* __restrict__ scratch,
                                                    const HashWsHeader* hdr,
                                                    const uint32_t* __restrict__ miss_pos,
                                                    const uint32_t* __restrict__ scr_slot, uint32_t n,
@@ -169,7 +176,7 @@ __global__ __launch_bounds__(256) void first_flags(const u64* __restrict__ scrat
   uint32_t f = 0;
   if (m < hdr->n_miss) {
     const uint32_t s = scr_slot[m];
-    f = (s != 0xFFFFFFFFu && scratch[2ull * s + 1] == (u64)miss_pos[m]) ? 1u : 0u;
+    f = (s != 0xFFFFFFFFu && scratch[s] == miss_pos[m]) ? 1u : 0u;
   }
   first[m] = f;
 }
@@ -181,7 +188,7 @@ __global__ __launch_bounds__(256) void first_flags(const u64* __restrict__ scrat
 // this kernel latency-bound: eight times the waves for the same dependent load -> CAS -> store.)
 __global__ __launch_bounds__(256) void hash_insert_new(u64* slots /* {key,row} pairs */,
                                                        uint32_t n_buckets, const HashHeader* table_hdr,
-                                                       int64_t max_rows, u64* scratch,
+                                                       int64_t max_rows, int64_t* __restrict__ rows,
                                                        const HashWsHeader* hdr,
                                                        const int64_t* __restrict__ keys,
                                                        const uint32_t* __restrict__ miss_pos,
@@ -213,18 +220,22 @@ __global__ __launch_bounds__(256) void hash_insert_new(u64* slots /* {key,row} p
       b = (b + 1 == n_buckets) ? 0u : b + 1;
     }
   }
-  scratch[2ull * scr_slot[m] + 1] = placed ? (u64)row : ~0ull;  // verdict: row or -1 (all ones)
+  rows[miss_pos[m]] = placed ? row : -1;   // the answer, read by the key's other positions afterwards
 }
 
-__global__ __launch_bounds__(256) void hash_resolve(const u64* __restrict__ scratch, HashWsHeader* hdr,
+// Every missed position that is not its key's first appearance copies the answer of the first one
+// (the scratch slot still holds that position; first appearances were answered by hash_insert_new
+// and are not written here, so the reads and writes of this kernel never meet).
+__global__ __launch_bounds__(256) void hash_resolve(const uint32_t* __restrict__ scratch, HashWsHeader* hdr,
                                                     HashHeader* table_hdr, int64_t max_rows,
                                                     const uint32_t* __restrict__ miss_pos,
                                                     const uint32_t* __restrict__ scr_slot,
-                                                    int64_t* __restrict__ rows) {
+                                                    const uint32_t* __restrict__ first,
+                                                    int64_t* rows) {
   const uint32_t m = blockIdx.x * 256u + threadIdx.x;
-  if (m < hdr->n_miss) {
+  if (m < hdr->n_miss && !first[m]) {
     const uint32_t s = scr_slot[m];
-    rows[miss_pos[m]] = s != 0xFFFFFFFFu ? (int64_t)scratch[2ull * s + 1] : -1;
+    rows[miss_pos[m]] = s != 0xFFFFFFFFu ? rows[scratch[s]] : -1;
   }
   if (m == 0) {
     const u64 grown = table_hdr->size + hdr->n_new;
@@ -244,10 +255,10 @@ hctr_status dedup_first_appearance(const int64_t* keys, uint32_t n, const DedupB
   hipLaunchKernelGGL(hash_compact_misses, dim3(nb), dim3(256), 0, stream, (const uint32_t*)B.flag,
                      (const uint32_t*)B.idx, n, B.miss_pos);
   hipLaunchKernelGGL(scratch_clear, dim3((uint32_t)ceil_div(B.scratch_cap_max, 256)), dim3(256), 0, stream,
-                     reinterpret_cast<u64x2*>(B.scratch), hdr);
+                     B.scratch, hdr);
   hipLaunchKernelGGL(scratch_insert, dim3(nb), dim3(256), 0, stream, B.scratch, hdr, keys,
                      (const uint32_t*)B.miss_pos, B.scr_slot);
-  hipLaunchKernelGGL(first_flags, dim3(nb), dim3(256), 0, stream, (const u64*)B.scratch, hdr,
+  hipLaunchKernelGGL(first_flags, dim3(nb), dim3(256), 0, stream, (const uint32_t*)B.scratch, hdr,
                      (const uint32_t*)B.miss_pos, (const uint32_t*)B.scr_slot, n, B.first);
   HCTR_TRY(exclusive_scan_u32(B.first, B.rank, n, B.scan_tmp, B.n_new, stream, B.n_miss));   // first[m] is used for m < n_miss only
   return launch_status("dedup_first_appearance");
@@ -274,7 +285,7 @@ static HashWsLayout hash_ws_layout(int64_t n_max) {
   L.first = at(n * 4); L.rank = at(n * 4);
   L.scan_tmp = at(scan_tmp_count((uint32_t)n) * 4);
   L.scratch_cap_max = dedup_scratch_capacity((uint32_t)n);
-  L.scratch = at((size_t)L.scratch_cap_max * 16);
+  L.scratch = at((size_t)L.scratch_cap_max * 4);
   L.total = c.off;
   return L;
 }
@@ -306,7 +317,7 @@ hctr_status hash_lookup(hctr_hash* h, const int64_t* keys, int64_t n64, int inse
   uint32_t* first = reinterpret_cast<uint32_t*>(w + L.first);
   uint32_t* rank = reinterpret_cast<uint32_t*>(w + L.rank);
   uint32_t* scan_tmp = reinterpret_cast<uint32_t*>(w + L.scan_tmp);
-  u64* scratch = reinterpret_cast<u64*>(w + L.scratch);
+  uint32_t* scratch = reinterpret_cast<uint32_t*>(w + L.scratch);
   const uint32_t nb = (uint32_t)ceil_div(n, 256);
 
   hipLaunchKernelGGL(hash_find, dim3(find_blocks), dim3(256), 0, stream, slots, h->n_buckets, keys, n, rows, flag,
@@ -315,11 +326,11 @@ hctr_status hash_lookup(hctr_hash* h, const int64_t* keys, int64_t n64, int inse
                  &hdr->n_miss, &hdr->n_new, &hdr->n_scan};
   HCTR_TRY(dedup_first_appearance(keys, n, B, stream));
   hipLaunchKernelGGL(hash_insert_new, dim3(nb), dim3(256), 0, stream, h->slots, h->n_buckets,
-                     (const HashHeader*)thdr, h->max_rows, scratch, (const HashWsHeader*)hdr, keys,
+                     (const HashHeader*)thdr, h->max_rows, rows, (const HashWsHeader*)hdr, keys,
                      (const uint32_t*)miss_pos, (const uint32_t*)scr_slot, (const uint32_t*)first,
                      (const uint32_t*)rank);
-  hipLaunchKernelGGL(hash_resolve, dim3(nb), dim3(256), 0, stream, (const u64*)scratch, hdr, thdr,
-                     h->max_rows, (const uint32_t*)miss_pos, (const uint32_t*)scr_slot, rows);
+  hipLaunchKernelGGL(hash_resolve, dim3(nb), dim3(256), 0, stream, (const uint32_t*)scratch, hdr, thdr,
+                     h->max_rows, (const uint32_t*)miss_pos, (const uint32_t*)scr_slot, (const uint32_t*)first, rows);
   return launch_status("hash_lookup");
 }
 

@@ -30,7 +30,7 @@ struct DedupBuffers {
   uint32_t* first;      // out: 1 where the missing position is its key's first appearance
   uint32_t* rank;       // out: exclusive scan of first
   uint32_t* scan_tmp;   // [scan_tmp_count(n)]
-  unsigned long long* scratch;  // [2 * scratch_cap_max] {key, smallest position | verdict}
+  uint32_t* scratch;    // [scratch_cap_max] per key met: the smallest missing position holding it
   uint32_t scratch_cap_max;     // dedup_scratch_capacity(n)
   uint32_t* n_miss;     // device: &HashWsHeader::n_miss
   uint32_t* n_new;      // device: &HashWsHeader::n_new
