@@ -237,32 +237,45 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
 // k0).  Two binary searches find the bags of the tile's first and last key; every bag in between
 // marks the position where it starts (atomicMax: of several bags starting at one position - empty
 // ones - the last owns the key); a running maximum over the positions fills in the rest.
+template <int NT>
 __device__ __forceinline__ void tile_bags(const int64_t* __restrict__ offsets, uint32_t n_bags, uint32_t k0,
-                                          uint32_t k1, uint32_t* bagof /*[kSortTile]*/, uint32_t* lds /*[6]*/) {
+                                          uint32_t k1, uint32_t* bagof /*[kSortTile]*/,
+                                          uint32_t* lds /*[NT / 64 + 2]*/) {
+  constexpr int PER = kSortTile / NT;    // consecutive positions per thread in the running maximum
+  constexpr int NW = NT / 64;
   const uint32_t tid = threadIdx.x;
-  for (uint32_t i = tid; i < kSortTile; i += 256) bagof[i] = 0;
-  if (tid < 2) {  // the bag with offsets[bag] <= k < offsets[bag + 1] for k = k0 and k1 - 1
-    const int64_t k = tid == 0 ? k0 : k1 - 1;
-    uint32_t lo = 0, hi = n_bags - 1;
+  for (uint32_t i = tid; i < kSortTile; i += NT) bagof[i] = 0;
+  if (tid < 128) {
+    // The bag with offsets[bag] <= k < offsets[bag + 1] - the last bag that starts at or before k -
+    // for k = k0 (wave 0) and k = k1 - 1 (wave 1).  A wave narrows the range 64-fold per step (each
+    // lane tests one pivot): 4 dependent loads for a million bags where a binary search needs 20.
+    const int64_t k = tid < 64 ? k0 : k1 - 1;
+    const uint32_t ln = tid & 63;
+    uint32_t lo = 0, hi = n_bags - 1;   // the answer lies in [lo, hi]; offsets[lo] <= k throughout
     while (lo < hi) {
-      const uint32_t mid = (lo + hi) >> 1;
-      if (offsets[mid + 1] <= k) lo = mid + 1; else hi = mid;
+      const uint32_t step = (hi - lo) / 64 + 1;
+      const uint64_t p = (uint64_t)lo + (uint64_t)ln * step;
+      const bool at_or_before = p <= hi && offsets[p] <= k;
+      const uint32_t j = (uint32_t)__popcll(__ballot(at_or_before)) - 1u;   // lane 0 always votes yes
+      const uint64_t top = (uint64_t)lo + (uint64_t)(j + 1) * step - 1;
+      lo += j * step;
+      hi = top < hi ? (uint32_t)top : hi;
     }
-    lds[4 + tid] = lo;
+    if (ln == 0) lds[NW + (tid >> 6)] = lo;
   }
   __syncthreads();
-  const uint32_t b_lo = lds[4], b_hi = lds[5];
+  const uint32_t b_lo = lds[NW], b_hi = lds[NW + 1];
   if (tid == 0) atomicMax(&bagof[0], b_lo + 1);
-  for (uint32_t bag = b_lo + 1 + tid; bag <= b_hi; bag += 256) {
+  for (uint32_t bag = b_lo + 1 + tid; bag <= b_hi; bag += NT) {
     const int64_t start = offsets[bag];
     if (start >= (int64_t)k0 && start < (int64_t)k1) atomicMax(&bagof[(uint32_t)start - k0], bag + 1);
   }
   __syncthreads();
-  // inclusive running maximum, 16 consecutive positions per thread
-  uint32_t v[16], m = 0;
+  // inclusive running maximum, PER consecutive positions per thread
+  uint32_t v[PER], m = 0;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    v[i] = bagof[tid * 16 + i];
+  for (int i = 0; i < PER; ++i) {
+    v[i] = bagof[tid * PER + i];
     m = v[i] > m ? v[i] : m;
     v[i] = m;
   }
@@ -279,12 +292,11 @@ __device__ __forceinline__ void tile_bags(const int64_t* __restrict__ offsets, u
   if (lane == 0) before = 0;
   for (int w = 0; w < wave; ++w) before = lds[w] > before ? lds[w] : before;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) bagof[tid * 16 + i] = v[i] > before ? v[i] : before;
+  for (int i = 0; i < PER; ++i) bagof[tid * PER + i] = v[i] > before ? v[i] : before;
   __syncthreads();
 }
 
-// NT = 256, or 1024 for one-hot input when there is only about one tile per compute unit (tile_bags
-// is written for 256 threads).
+// NT = 256, or 1024 when there is only about one tile per compute unit.
 template <int NT>
 __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
                                                const int64_t* __restrict__ rows64,
@@ -296,8 +308,8 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
   // One sort tile per block, so the block can also deliver the tile's histogram of the first sort
   // digit (the low bits of the row) and spare the sort its first counting pass.
   __shared__ uint32_t h[1 << kSortMaxDigitBits];
-  __shared__ uint32_t bagof[NT == 256 ? kSortTile : 1];
-  __shared__ uint32_t small[6];
+  __shared__ uint32_t bagof[kSortTile];
+  __shared__ uint32_t small[NT / 64 + 2];
   const uint32_t mask = bins - 1;
   const uint32_t k0 = blockIdx.x * kSortTile;
   const uint32_t k1 = nnz - k0 < kSortTile ? nnz : k0 + kSortTile;
@@ -307,14 +319,14 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
     s_base[threadIdx.x] = slots.base[threadIdx.x];
     s_num[threadIdx.x] = slots.num[threadIdx.x];
   }
-  if (NT == 256 && offsets != nullptr) tile_bags(offsets, n_bags, k0, k1, bagof, small);
+  if (offsets != nullptr) tile_bags<NT>(offsets, n_bags, k0, k1, bagof, small);
   else __syncthreads();
   uint32_t nbad = 0;
 #pragma unroll 4
   for (int it = 0; it < (int)(kSortTile / NT); ++it) {
     const uint32_t i = k0 + it * (uint32_t)NT + threadIdx.x;
     if (i < nnz) {
-      const uint32_t bag = (NT == 256 && offsets != nullptr) ? bagof[i - k0] - 1u : i;
+      const uint32_t bag = offsets != nullptr ? bagof[i - k0] - 1u : i;
       int64_t row = -1;
       if (rows64 != nullptr) {
         const int64_t r = rows64[i];
@@ -1173,7 +1185,7 @@ static hctr_status dedup_core(const int64_t* keys, const int64_t* rows64, const 
   const bool wide = L.sort.n_blocks <= kSortWideMaxTiles;
   const uint32_t bins0 = 1u << L.sort.digit_bits[0];
   uint32_t* sup0 = sort_scans_groups(L.sort) ? nullptr : sort_aux_sup(L.sort, aux, 0);
-  if (wide && offsets == nullptr)
+  if (wide)
     hipLaunchKernelGGL((bwd_rows<1024>), dim3(L.sort.n_blocks), dim3(1024), 0, stream, keys, rows64, offsets, n,
                        n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sup0);
   else
