@@ -307,7 +307,7 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
                                                uint32_t* __restrict__ hist, uint32_t* __restrict__ sup) {
   // One sort tile per block, so the block can also deliver the tile's histogram of the first sort
   // digit (the low bits of the row) and spare the sort its first counting pass.
-  __shared__ uint32_t h[1 << kSortMaxDigitBits];
+  __shared__ uint32_t h[1 << kSortMaxDigitBits];   // (four copies as in sort_hist cost occupancy here: slower)
   __shared__ uint32_t bagof[kSortTile];
   __shared__ uint32_t small[NT / 64 + 2];
   const uint32_t mask = bins - 1;
@@ -322,17 +322,26 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
   if (offsets != nullptr) tile_bags<NT>(offsets, n_bags, k0, k1, bagof, small);
   else __syncthreads();
   uint32_t nbad = 0;
-#pragma unroll 4
-  for (int it = 0; it < (int)(kSortTile / NT); ++it) {
+  // the thread's keys (or rows) first, index clamped instead of a branch: all loads leave together
+  constexpr int PER = (int)(kSortTile / NT);
+  const int64_t* src = rows64 != nullptr ? rows64 : keys;
+  int64_t in[PER];
+#pragma unroll
+  for (int it = 0; it < PER; ++it) {
+    const uint32_t i = k0 + it * (uint32_t)NT + threadIdx.x;
+    in[it] = src[i < nnz ? i : nnz - 1];
+  }
+#pragma unroll
+  for (int it = 0; it < PER; ++it) {
     const uint32_t i = k0 + it * (uint32_t)NT + threadIdx.x;
     if (i < nnz) {
       const uint32_t bag = offsets != nullptr ? bagof[i - k0] - 1u : i;
       int64_t row = -1;
       if (rows64 != nullptr) {
-        const int64_t r = rows64[i];
+        const int64_t r = in[it];
         if (r >= 0 && r < total_rows) row = r;
       } else {
-        const int64_t k = keys[i];
+        const int64_t k = in[it];
         const uint32_t s = bag % S;
         if (k >= 0 && k < s_num[s]) row = s_base[s] + k;
       }
@@ -366,13 +375,37 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
 constexpr uint32_t kSegTile = 4096;
 constexpr uint32_t kSegSuper = 64;
 
-__device__ __forceinline__ uint64_t seg_start_mask(const uint64_t* __restrict__ skv, uint32_t idx, uint32_t n,
-                                                   uint32_t* row_out) {
+// The rows of a wave's ROUNDS * 64 consecutive sorted words plus the row before the first and after
+// the last of them, all requested at once and without a branch (indices clamped; a load under a
+// branch is waited for before the next one is issued, which made these kernels latency-bound).
+// Words past the end count as kNoRow.  rows[0] = the row before, rows[1 + r] = round r's.
+template <int ROUNDS>
+__device__ __forceinline__ void seg_load_rows(const uint64_t* __restrict__ skv, uint32_t wbase, uint32_t n,
+                                              uint32_t* rows /*[ROUNDS + 2]*/) {
   const int lane = threadIdx.x & 63;
-  const uint32_t row = idx < n ? (uint32_t)(skv[idx] >> 32) : kNoRow;
+  const uint32_t last = n - 1;   // n >= 1
+  uint64_t w[ROUNDS + 2];
+  const uint32_t before = wbase > 0 ? wbase - 1 : 0;
+  w[0] = skv[before < last ? before : last];
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    const uint32_t idx = wbase + r * 64 + lane;
+    w[1 + r] = skv[idx < last ? idx : last];
+  }
+  const uint32_t after = wbase + ROUNDS * 64;
+  w[ROUNDS + 1] = skv[after < last ? after : last];
+  rows[0] = (wbase > 0 && wbase - 1 < n) ? (uint32_t)(w[0] >> 32) : kNoRow;
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) rows[1 + r] = wbase + r * 64 + lane < n ? (uint32_t)(w[1 + r] >> 32) : kNoRow;
+  rows[ROUNDS + 1] = after < n ? (uint32_t)(w[ROUNDS + 1] >> 32) : kNoRow;
+}
+
+// Lanes of round r whose word starts a run of equal rows; prev63 = the row of the word just before
+// the round's first (the previous round's last lane, or the row before the wave's range).
+__device__ __forceinline__ uint64_t seg_start_mask(uint32_t row, uint32_t prev63, uint32_t idx) {
+  const int lane = threadIdx.x & 63;
   uint32_t prev = __shfl_up(row, 1);
-  if (lane == 0) prev = (idx > 0 && idx < n) ? (uint32_t)(skv[idx - 1] >> 32) : kNoRow;
-  *row_out = row;
+  if (lane == 0) prev = prev63;
   return __ballot(row != kNoRow && (idx == 0 || prev != row));
 }
 
@@ -383,11 +416,13 @@ __global__ __launch_bounds__(NT) void seg_count(const uint64_t* __restrict__ skv
   __shared__ uint32_t wsum[NW];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint32_t wbase = blockIdx.x * kSegTile + wave * (ROUNDS * 64u);
-  uint32_t c = 0;
-#pragma unroll 4
+  uint32_t rows[ROUNDS + 2];
+  seg_load_rows<ROUNDS>(skv, wbase, n, rows);
+  uint32_t c = 0, prev63 = rows[0];
+#pragma unroll
   for (int r = 0; r < ROUNDS; ++r) {
-    uint32_t row;
-    c += (uint32_t)__popcll(seg_start_mask(skv, wbase + r * 64 + lane, n, &row));
+    c += (uint32_t)__popcll(seg_start_mask(rows[1 + r], prev63, wbase + r * 64 + lane));
+    prev63 = __shfl(rows[1 + r], 63);
   }
   if (lane == 0) wsum[wave] = c;
   __syncthreads();
@@ -404,7 +439,7 @@ template <int NT>
 __global__ __launch_bounds__(NT) void seg_write(const uint64_t* __restrict__ skv, uint32_t n,
                                                 const uint32_t* __restrict__ counts,
                                                 const uint32_t* __restrict__ segsup,
-                                                uint32_t* __restrict__ starts_before,
+                                                uint32_t* __restrict__ starts_before, uint32_t W,
                                                 uint32_t* __restrict__ uniq,
                                                 uint32_t* __restrict__ seg_off, EmbHeader* hdr) {
   constexpr int NW = NT / 64, ROUNDS = kSegTile / NT;
@@ -413,6 +448,9 @@ __global__ __launch_bounds__(NT) void seg_write(const uint64_t* __restrict__ skv
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint32_t tile = blockIdx.x;
   const uint32_t g = tile / kSegSuper;
+  const uint32_t wbase = tile * kSegTile + wave * (ROUNDS * 64u);
+  uint32_t rows[ROUNDS + 2];
+  seg_load_rows<ROUNDS>(skv, wbase, n, rows);   // requested before the sums below: both in flight together
   // number of starts in all earlier tiles
   uint32_t part = 0;
   for (uint32_t i = threadIdx.x; i < g; i += NT) part += segsup[i];
@@ -421,13 +459,12 @@ __global__ __launch_bounds__(NT) void seg_write(const uint64_t* __restrict__ skv
   for (int d = 32; d >= 1; d >>= 1) part += __shfl_xor(part, d);
   if (lane == 0) red[wave] = part;
 
-  const uint32_t wbase = tile * kSegTile + wave * (ROUNDS * 64u);
   uint64_t m[ROUNDS];
-  uint32_t row[ROUNDS];
-  uint32_t c = 0;
+  uint32_t c = 0, prev63 = rows[0];
 #pragma unroll
   for (int r = 0; r < ROUNDS; ++r) {
-    m[r] = seg_start_mask(skv, wbase + r * 64 + lane, n, &row[r]);
+    m[r] = seg_start_mask(rows[1 + r], prev63, wbase + r * 64 + lane);
+    prev63 = __shfl(rows[1 + r], 63);
     c += (uint32_t)__popcll(m[r]);
   }
   if (lane == 0) wsum[wave] = c;
@@ -440,15 +477,21 @@ __global__ __launch_bounds__(NT) void seg_write(const uint64_t* __restrict__ skv
 #pragma unroll
   for (int r = 0; r < ROUNDS; ++r) {
     const uint32_t p = wbase + r * 64 + lane;
+    const uint32_t row = rows[1 + r];
+    // the row to the right: the neighbouring lane's, or the next round's first / the row after the range
+    uint32_t next = __shfl_down(row, 1);
+    const uint32_t next0 = __shfl(rows[2 + r], 0);   // rows[ROUNDS + 1] is the same in every lane
+    if (lane == 63) next = next0;
     if (p < n) {
       const uint32_t before = run + (uint32_t)__popcll(m[r] & below);
       const bool start = (m[r] >> lane) & 1ull;
-      starts_before[p] = before;
+      // the reduction asks for this count only at the last position of a window (W is a power of two)
+      if (((p + 1) & (W - 1)) == 0) starts_before[p / W] = before;
       if (start) {
-        uniq[before] = row[r];
+        uniq[before] = row;
         seg_off[before] = p;
       }
-      if (row[r] != kNoRow && (p == n - 1 || (uint32_t)(skv[p + 1] >> 32) == kNoRow)) {
+      if (row != kNoRow && (p == n - 1 || next == kNoRow)) {
         const uint32_t U = before + (start ? 1u : 0u);  // last real row closes the last segment
         seg_off[U] = p + 1;
         hdr->n_valid = p + 1;
@@ -653,7 +696,7 @@ __device__ __forceinline__ void carry_extent(const uint64_t* __restrict__ skv,
   const uint32_t p = win * W + W - 1;
   const uint64_t w64 = skv[p];
   const uint32_t r = (uint32_t)(w64 >> 32);
-  const uint32_t u = starts_before[p] + ((p == 0 || (uint32_t)(skv[p - 1] >> 32) != r) ? 1u : 0u) - 1u;
+  const uint32_t u = starts_before[win] + ((p == 0 || (uint32_t)(skv[p - 1] >> 32) != r) ? 1u : 0u) - 1u;
   *row = r;
   *bag = (uint32_t)w64;   // any occurrence of the row names its table
   *last = (seg_off[u + 1] - 1u) / W;   // last window holding a piece of the row
@@ -896,7 +939,7 @@ struct EmbLayout {
   SortPlan sort;
 };
 
-static uint32_t pick_window(int64_t nnz) { return nnz <= (8ll << 20) ? 32u : 128u; }
+static uint32_t pick_window(int64_t nnz) { return nnz <= (8ll << 20) ? 32u : 128u; }   // powers of two (seg_write)
 
 // Workspace of a layer or a group: total_rows rows in all, widest row dmax, hashed = with the
 // key -> row scratch of the hashed mode, extra = bytes appended for the caller (group: CSR offsets).
@@ -916,7 +959,7 @@ static EmbLayout emb_layout_raw(int64_t total_rows, int dmax, int64_t nnz_max, b
   L.seg_super = (uint32_t)ceil_div(L.seg_tiles, kSegSuper);
   L.aux = at((L.sort.aux_count + L.seg_super) * 4);   // sort sums, then the per-64-tiles start counts
   L.seg_counts = at((size_t)L.seg_tiles * 4);
-  L.flags = at(n * 4);
+  L.flags = at((size_t)L.n_windows * 4);   // per window: distinct rows that begin before its last position
   L.uniq = at(n * 4);
   L.seg_off = at((n + 1) * 4);
   L.long_list = at((size_t)L.n_windows * 4);
@@ -1196,11 +1239,11 @@ static hctr_status dedup_core(const int64_t* keys, const int64_t* rows64, const 
   if (wide) {
     hipLaunchKernelGGL((seg_count<1024>), dim3(L.seg_tiles), dim3(1024), 0, stream, skv, n, seg_counts, segsup);
     hipLaunchKernelGGL((seg_write<1024>), dim3(L.seg_tiles), dim3(1024), 0, stream, skv, n,
-                       (const uint32_t*)seg_counts, (const uint32_t*)segsup, flags, uniq, seg_off, hdr);
+                       (const uint32_t*)seg_counts, (const uint32_t*)segsup, flags, L.window, uniq, seg_off, hdr);
   } else {
     hipLaunchKernelGGL((seg_count<256>), dim3(L.seg_tiles), dim3(256), 0, stream, skv, n, seg_counts, segsup);
     hipLaunchKernelGGL((seg_write<256>), dim3(L.seg_tiles), dim3(256), 0, stream, skv, n,
-                       (const uint32_t*)seg_counts, (const uint32_t*)segsup, flags, uniq, seg_off, hdr);
+                       (const uint32_t*)seg_counts, (const uint32_t*)segsup, flags, L.window, uniq, seg_off, hdr);
   }
   return launch_status("dedup");
 }
