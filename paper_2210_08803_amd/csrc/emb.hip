@@ -91,23 +91,26 @@ __global__ __launch_bounds__(256) void fwd_onehot(const T* __restrict__ table, i
   }
   for (uint64_t bag0_64 = (uint64_t)group0 * U; bag0_64 < n_bags; bag0_64 += (uint64_t)n_groups * U) {
     const uint32_t bag0 = (uint32_t)bag0_64;
-    int64_t row[U];
+    int64_t row[U], in[U];
     uint32_t bags[U];
+    // The U keys (hashed mode: rows) first, index clamped instead of a branch: a load whose value is
+    // used under the same branch is waited for before the next one is issued, which put four key
+    // latencies in a row ahead of the row loads.
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t bag = bags[u] = walk_to_bag(bag0 + u, n_bags, S, n_samples);
-      row[u] = -1;
-      if (bag < n_bags) {
-        if (HASHED) {
-          const int64_t r = rows64[bag];
-          if (r >= 0 && r < total_rows) row[u] = r;
-        } else {
-          const int64_t k = keys[bag];
-          const uint32_t s = bag % S;
-          if (k >= 0 && k < s_num[s]) row[u] = s_base[s] + k;
-        }
-        nbad += (sub == 0 && row[u] < 0) ? 1u : 0u;
-      }
+      const uint32_t bc = bag < n_bags ? bag : n_bags - 1;
+      in[u] = HASHED ? rows64[bc] : keys[bc];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t bag = bags[u];
+      const uint32_t s = (bag < n_bags ? bag : n_bags - 1) % S;
+      const int64_t lim = HASHED ? total_rows : s_num[s];
+      const int64_t add = HASHED ? 0 : s_base[s];
+      const bool ok = bag < n_bags && in[u] >= 0 && in[u] < lim;
+      row[u] = ok ? add + in[u] : -1;
+      nbad += (sub == 0 && bag < n_bags && !ok) ? 1u : 0u;
     }
     float v[U][VEC];
 #pragma unroll
