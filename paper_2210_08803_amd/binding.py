@@ -168,8 +168,8 @@ class HashTable:
         self._wsbuf = None
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().hctr_hash_destroy(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:   # at interpreter exit the module may be gone
+            _lib.hctr_hash_destroy(self.handle)
             self.handle = None
 
     def workspace(self, n: int) -> torch.Tensor:
@@ -397,8 +397,8 @@ class EmbeddingTrainingCache:
         self._wsbuf = None
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().hctr_etc_destroy(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:   # at interpreter exit the module may be gone
+            _lib.hctr_etc_destroy(self.handle)
             self.handle = None
 
     def workspace(self, n: int) -> torch.Tensor:
@@ -449,8 +449,8 @@ class EmbeddingCache:
         self._wsbuf = None
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().hctr_cache_destroy(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:   # at interpreter exit the module may be gone
+            _lib.hctr_cache_destroy(self.handle)
             self.handle = None
 
     def set_small_call_limit(self, max_keys: int) -> None:
