@@ -172,13 +172,9 @@ __global__ __launch_bounds__(256) void first_flags(const uint32_t* __restrict__ 
                                                    const uint32_t* __restrict__ scr_slot, uint32_t n,
                                                    uint32_t* __restrict__ first) {
   const uint32_t m = blockIdx.x * 256u + threadIdx.x;
-  if (m >= n) return;
-  uint32_t f = 0;
-  if (m < hdr->n_miss) {
-    const uint32_t s = scr_slot[m];
-    f = (s != 0xFFFFFFFFu && scratch[s] == miss_pos[m]) ? 1u : 0u;
-  }
-  first[m] = f;
+  if (m >= n || m >= hdr->n_miss) return;   // first[] is read (and scanned) for m < n_miss only
+  const uint32_t s = scr_slot[m];
+  first[m] = (s != 0xFFFFFFFFu && scratch[s] == miss_pos[m]) ? 1u : 0u;
 }
 
 // One new key per lane: assign the row, claim a slot in the main table, publish.  The key is known to

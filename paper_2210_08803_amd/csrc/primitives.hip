@@ -12,6 +12,7 @@ namespace hctr {
 // ------------------------------------------------------------------------------------------------
 // Exclusive scan
 // ------------------------------------------------------------------------------------------------
+typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 16;
 constexpr uint32_t kScanTile = kScanThreads * kScanItems;  // 4096
@@ -33,10 +34,15 @@ __global__ __launch_bounds__(kScanThreads) void scan_tile_sums(const uint32_t* _
   const uint32_t n = scan_length(n_host, n_dev);
   const uint32_t base = blockIdx.x * kScanTile;
   uint32_t s = 0;
+  if (base < n) {   // block-uniform; the items themselves without a branch (index clamped), all in flight
+    uint32_t v[kScanItems];
 #pragma unroll
-  for (int i = 0; i < kScanItems; ++i) {
-    uint32_t idx = base + i * kScanThreads + threadIdx.x;
-    if (idx < n) s += in[idx];
+    for (int i = 0; i < kScanItems; ++i) {
+      const uint32_t idx = base + i * kScanThreads + threadIdx.x;
+      v[i] = in[idx < n ? idx : n - 1];
+    }
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) s += base + i * kScanThreads + threadIdx.x < n ? v[i] : 0u;
   }
   uint32_t total;
   block_exclusive_scan<kScanThreads>(s, lds, &total);
@@ -69,18 +75,41 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply(const uint32_t* in, u
   const uint32_t base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
   uint32_t v[kScanItems];
   uint32_t s = 0;
+  // a thread's 16 consecutive items as four 16-byte accesses when they all exist and the arrays
+  // allow it (word by word, a wave's load touches 64 separate 64-byte pieces)
+  const bool whole = (uint64_t)base + kScanItems <= n &&
+                     ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15u) == 0;
+  if (whole) {
 #pragma unroll
-  for (int i = 0; i < kScanItems; ++i) {
-    v[i] = (base + i < n) ? in[base + i] : 0u;
-    s += v[i];
+    for (int i = 0; i < kScanItems; i += 4) {
+      const u32x4v q = *reinterpret_cast<const u32x4v*>(in + base + i);
+      v[i] = q.x; v[i + 1] = q.y; v[i + 2] = q.z; v[i + 3] = q.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) v[i] = (base + i < n) ? in[base + i] : 0u;
   }
+#pragma unroll
+  for (int i = 0; i < kScanItems; ++i) s += v[i];
   uint32_t total;
   uint32_t run = block_exclusive_scan<kScanThreads>(s, lds, &total);
   run += sums ? sums[blockIdx.x] : 0u;
+  if (whole) {
 #pragma unroll
-  for (int i = 0; i < kScanItems; ++i) {
-    if (base + i < n) out[base + i] = run;
-    run += v[i];
+    for (int i = 0; i < kScanItems; i += 4) {
+      u32x4v q;
+      q.x = run; run += v[i];
+      q.y = run; run += v[i + 1];
+      q.z = run; run += v[i + 2];
+      q.w = run; run += v[i + 3];
+      *reinterpret_cast<u32x4v*>(out + base + i) = q;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+      if (base + i < n) out[base + i] = run;
+      run += v[i];
+    }
   }
   if (sums == nullptr && total_out != nullptr && threadIdx.x == 0) *total_out = total;
 }
@@ -124,7 +153,6 @@ hctr_status exclusive_scan_u32(const uint32_t* in, uint32_t* out, uint32_t n, ui
 constexpr int kSortThreads = 256;
 constexpr int kSortWideThreads = 1024;
 constexpr int kMaxBins = 1 << kSortMaxDigitBits;
-typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 
 __global__ __launch_bounds__(256) void sort_zero_aux(uint32_t* __restrict__ aux, uint32_t count) {
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
