@@ -112,12 +112,20 @@ __global__ __launch_bounds__(256) void fwd_onehot(const T* __restrict__ table, i
       row[u] = ok ? add + in[u] : -1;
       nbad += (sub == 0 && bag < n_bags && !ok) ? 1u : 0u;
     }
+    // the U row pieces without a branch (a bag without a row, or a lane past the row's end, reads
+    // the start of row 0 and is zeroed below), widened only after all of them are under way
+    typename RowVec<T>::Raw raw[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      raw[u] = RowVec<T>::load_raw(table + ((row[u] >= 0 && active) ? row[u] * D + col : (int64_t)0));
     float v[U][VEC];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+      RowVec<T>::widen(raw[u], v[u]);
+      if (!(row[u] >= 0 && active)) {
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) v[u][i] = 0.f;
-      if (row[u] >= 0 && active) RowVec<T>::load(table + row[u] * D + col, v[u]);
+        for (int i = 0; i < VEC; ++i) v[u][i] = 0.f;
+      }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -192,17 +200,21 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
         row[u] = __shfl(myrow, jj < cnt ? jj : lane);
         if (jj >= cnt) row[u] = kNoRow;
       }
-      float v[U][VEC];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) v[u][i] = 0.f;
-        if (row[u] != kNoRow && active) RowVec<T>::load(table + (int64_t)row[u] * D + col, v[u]);
-      }
+      // the U row pieces without a branch (no row, or a lane past the row's end: the start of row 0,
+      // left out of the sum below), widened only after all of them are under way
+      typename RowVec<T>::Raw raw[U];
 #pragma unroll
       for (int u = 0; u < U; ++u)
+        raw[u] = RowVec<T>::load_raw(table + ((row[u] != kNoRow && active) ? (int64_t)row[u] * D + col : (int64_t)0));
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[i] += v[u][i];
+      for (int u = 0; u < U; ++u) {
+        float v[VEC];
+        RowVec<T>::widen(raw[u], v);
+        if (row[u] != kNoRow && active) {
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) acc[i] += v[i];
+        }
+      }
     }
   }
   if (G > 1) {

@@ -12,13 +12,18 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 template <typename T>
 struct RowVec;
 
+// load = load_raw + widen.  Kernels that keep several row loads in flight call load_raw for all of
+// them first and widen afterwards: a conversion (or any use) right behind a load that sits under a
+// branch makes the compiler wait for that load before it issues the next one.
 template <>
 struct RowVec<float> {
   static constexpr int VEC = 4;
-  __device__ static __forceinline__ void load(const float* p, float (&v)[4]) {
-    f32x4 x = *reinterpret_cast<const f32x4*>(p);
+  typedef f32x4 Raw;
+  __device__ static __forceinline__ Raw load_raw(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
+  __device__ static __forceinline__ void widen(const Raw& x, float (&v)[4]) {
     v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
   }
+  __device__ static __forceinline__ void load(const float* p, float (&v)[4]) { widen(load_raw(p), v); }
 };
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
@@ -28,8 +33,9 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
 template <>
 struct RowVec<__half> {
   static constexpr int VEC = 8;
-  __device__ static __forceinline__ void load(const __half* p, float (&v)[8]) {
-    u32x4 x = *reinterpret_cast<const u32x4*>(p);
+  typedef u32x4 Raw;
+  __device__ static __forceinline__ Raw load_raw(const __half* p) { return *reinterpret_cast<const u32x4*>(p); }
+  __device__ static __forceinline__ void widen(const Raw& x, float (&v)[8]) {
     const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -37,6 +43,7 @@ struct RowVec<__half> {
       v[2 * i + 1] = half_bits_to_float(w[i] >> 16);
     }
   }
+  __device__ static __forceinline__ void load(const __half* p, float (&v)[8]) { widen(load_raw(p), v); }
 };
 
 // Streaming store of N consecutive floats (N = 4 or 8): the pooled output is written once and not
