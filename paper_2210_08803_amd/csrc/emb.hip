@@ -554,6 +554,15 @@ struct UniformView {
     if (master) return load4(master + (int64_t)r * D + col);
     return load_row4(table + (int64_t)r * D + col);
   }
+  // the same in two steps, so that the caller can have several rows under way before it widens any
+  __device__ __forceinline__ Raw4 load_weights_raw(uint32_t r, uint32_t, const GroupLookup*, int col) const {
+    if (master) return load_raw4(master + (int64_t)r * D + col);
+    return load_raw4(table + (int64_t)r * D + col);
+  }
+  __device__ __forceinline__ f32x4 widen_weights(const Raw4& x) const {
+    if (master) return widen4(x, static_cast<const float*>(nullptr));
+    return widen4(x, static_cast<const T*>(nullptr));
+  }
   __device__ __forceinline__ void store_weights(uint32_t r, uint32_t, const GroupLookup*, int col, f32x4 x) const {
     if (master) store4(master + (int64_t)r * D + col, x);
     store_row4(table + (int64_t)r * D + col, x);
@@ -585,6 +594,13 @@ struct GroupView {
   __device__ __forceinline__ f32x4 load_weights(uint32_t r, uint32_t bag, const GroupLookup* l, int col) const {
     const GroupLookup& k = l[bag % L];
     return load_row4(static_cast<const T*>(k.table) + (int64_t)(r - k.row_base) * k.dim + col);
+  }
+  __device__ __forceinline__ Raw4 load_weights_raw(uint32_t r, uint32_t bag, const GroupLookup* l, int col) const {
+    const GroupLookup& k = l[bag % L];
+    return load_raw4(static_cast<const T*>(k.table) + (int64_t)(r - k.row_base) * k.dim + col);
+  }
+  __device__ __forceinline__ f32x4 widen_weights(const Raw4& x) const {
+    return widen4(x, static_cast<const T*>(nullptr));
   }
   __device__ __forceinline__ void store_weights(uint32_t r, uint32_t bag, const GroupLookup* l, int col,
                                                 f32x4 x) const {
@@ -642,10 +658,13 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
       if (view.is_mean(mybag, lk)) myw = 1.0f / (float)(offsets[mybag + 1] - offsets[mybag]);
     }
     for (int q0 = 0; q0 < cnt; q0 += UB) {
+      // All loads of the step raw and first - the UB gradient pieces without a branch (a lane past
+      // the row's width reads the row's first piece and leaves it out), the table rows that end
+      // here under their branch but with nothing else in it - and widened only afterwards.
       uint32_t r[UB], b[UB];
-      bool ends[UB];
+      bool ends[UB], in_row[UB];
       float w[UB];
-      f32x4 v[UB], t[UB];
+      Raw4 vr[UB], tr[UB];
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
         const bool live = q0 + u < cnt;
@@ -656,27 +675,31 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
         w[u] = __shfl(myw, q, LPR);
         int width;
         const auto* g = view.grad(b[u], lk, &width);
-        if constexpr (ONCE) v[u] = col < width ? load_stream4(g + col) : f32x4{0.f, 0.f, 0.f, 0.f};
-        else v[u] = col < width ? load_row4(g + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+        in_row[u] = col < width;
+        if constexpr (ONCE) vr[u] = load_stream_raw4(g + (in_row[u] ? col : 0));
+        else vr[u] = load_raw4(g + (in_row[u] ? col : 0));
       }
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
-        t[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (ends[u] && col < view.row_width(b[u], lk)) t[u] = view.load_weights(r[u], b[u], lk, col);
+        tr[u] = Raw4{u32x4{0u, 0u, 0u, 0u}};
+        if (ends[u] && in_row[u]) tr[u] = view.load_weights_raw(r[u], b[u], lk, col);
       }
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
-        if (q0 + u < cnt) {
-          acc.x += w[u] * v[u].x; acc.y += w[u] * v[u].y;
-          acc.z += w[u] * v[u].z; acc.w += w[u] * v[u].w;
+        int width;
+        const f32x4 v = widen4(vr[u], view.grad(b[u], lk, &width));   // the pointer only names the type
+        if (q0 + u < cnt && in_row[u]) {
+          acc.x += w[u] * v.x; acc.y += w[u] * v.y;
+          acc.z += w[u] * v.z; acc.w += w[u] * v.w;
         }
         if (ends[u]) {
-          if (col < view.row_width(b[u], lk)) {
+          if (in_row[u]) {
             if (before) {
               store4(head + (int64_t)win * DM + col, acc);
             } else {
-              t[u].x -= lr * acc.x; t[u].y -= lr * acc.y; t[u].z -= lr * acc.z; t[u].w -= lr * acc.w;
-              view.store_weights(r[u], b[u], lk, col, t[u]);
+              f32x4 t = view.widen_weights(tr[u]);
+              t.x -= lr * acc.x; t.y -= lr * acc.y; t.z -= lr * acc.z; t.w -= lr * acc.w;
+              view.store_weights(r[u], b[u], lk, col, t);
             }
           }
           acc = f32x4{0.f, 0.f, 0.f, 0.f};

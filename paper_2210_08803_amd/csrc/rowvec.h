@@ -112,6 +112,32 @@ __device__ __forceinline__ f32x4 load_stream4(const __half* p) {
                half_bits_to_float(raw.y & 0xFFFFu), half_bits_to_float(raw.y >> 16)};
 }
 
+// Four elements as a load brings them, before they are widened to fp32 (fp32: four words; fp16: the
+// first two words hold four halves).  The backward kernels request all pieces of a step raw and
+// widen them afterwards, for the reason given at RowVec.  The pointer argument of widen4 only
+// selects the element type.
+struct Raw4 { u32x4 bits; };
+__device__ __forceinline__ Raw4 load_raw4(const float* p) { return Raw4{*reinterpret_cast<const u32x4*>(p)}; }
+__device__ __forceinline__ Raw4 load_raw4(const __half* p) {
+  const u32x2 x = *reinterpret_cast<const u32x2*>(p);
+  return Raw4{u32x4{x.x, x.y, 0u, 0u}};
+}
+__device__ __forceinline__ Raw4 load_stream_raw4(const float* p) {
+  return Raw4{__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p))};
+}
+__device__ __forceinline__ Raw4 load_stream_raw4(const __half* p) {
+  const u32x2 x = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+  return Raw4{u32x4{x.x, x.y, 0u, 0u}};
+}
+__device__ __forceinline__ f32x4 widen4(const Raw4& r, const float*) {
+  return f32x4{__uint_as_float(r.bits.x), __uint_as_float(r.bits.y), __uint_as_float(r.bits.z),
+               __uint_as_float(r.bits.w)};
+}
+__device__ __forceinline__ f32x4 widen4(const Raw4& r, const __half*) {
+  return f32x4{half_bits_to_float(r.bits.x & 0xFFFFu), half_bits_to_float(r.bits.x >> 16),
+               half_bits_to_float(r.bits.y & 0xFFFFu), half_bits_to_float(r.bits.y >> 16)};
+}
+
 // Read-modify-write of 4 table elements: t <- t - lr * g (fp16 storage: widen, update in fp32,
 // round to nearest even).
 __device__ __forceinline__ void sgd_update4(float* t, f32x4 g, float lr) {
