@@ -905,12 +905,20 @@ __global__ __launch_bounds__(256) void fwd_group(const GroupFwdArgs a, const int
       int64_t key[NQ];
 #pragma unroll
       for (int u = 0; u < NQ; ++u) key[u] = k0[u] + j < k1[u] ? keys[k0[u] + j] : (int64_t)-1;
+      // the NQ row pieces raw and without a branch (a key with no row reads row 0 and is left out),
+      // widened once all are under way: see RowVec
+      Raw4 raw[NQ];
+      bool ok[NQ];
 #pragma unroll
       for (int u = 0; u < NQ; ++u) {
-        const bool ok = key[u] >= 0 && key[u] < nr[u];
-        const f32x4 v = ok ? load_row4(tbl[u] + key[u] * dim[u] + cl[u]) : f32x4{0.f, 0.f, 0.f, 0.f};
-        nbad += (cl[u] == 0 && k0[u] + j < k1[u] && !ok) ? 1u : 0u;
-        acc[u].x += v.x; acc[u].y += v.y; acc[u].z += v.z; acc[u].w += v.w;
+        ok[u] = key[u] >= 0 && key[u] < nr[u];
+        raw[u] = load_raw4(tbl[u] + (ok[u] ? key[u] : 0) * dim[u] + cl[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < NQ; ++u) {
+        const f32x4 v = widen4(raw[u], tbl[u]);
+        nbad += (cl[u] == 0 && k0[u] + j < k1[u] && !ok[u]) ? 1u : 0u;
+        if (ok[u]) { acc[u].x += v.x; acc[u].y += v.y; acc[u].z += v.z; acc[u].w += v.w; }
       }
     }
 #pragma unroll
