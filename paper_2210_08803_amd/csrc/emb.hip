@@ -346,6 +346,7 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
     const uint32_t i = k0 + it * (uint32_t)NT + threadIdx.x;
     in[it] = src[i < nnz ? i : nnz - 1];
   }
+  __builtin_amdgcn_sched_barrier(0);   // every load above is issued before the first use below
 #pragma unroll
   for (int it = 0; it < PER; ++it) {
     const uint32_t i = k0 + it * (uint32_t)NT + threadIdx.x;
@@ -409,6 +410,7 @@ __device__ __forceinline__ void seg_load_rows(const uint64_t* __restrict__ skv, 
   }
   const uint32_t after = wbase + ROUNDS * 64;
   w[ROUNDS + 1] = skv[after < last ? after : last];
+  __builtin_amdgcn_sched_barrier(0);   // every load above is issued before the first use below
   rows[0] = (wbase > 0 && wbase - 1 < n) ? (uint32_t)(w[0] >> 32) : kNoRow;
 #pragma unroll
   for (int r = 0; r < ROUNDS; ++r) rows[1 + r] = wbase + r * 64 + lane < n ? (uint32_t)(w[1 + r] >> 32) : kNoRow;

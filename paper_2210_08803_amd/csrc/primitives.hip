@@ -188,6 +188,7 @@ __global__ __launch_bounds__(NT) void sort_hist(const uint64_t* __restrict__ kv,
     const uint32_t idx = base + i * NT + threadIdx.x;
     w[i] = kv[idx < n ? idx : n - 1];
   }
+  __builtin_amdgcn_sched_barrier(0);   // every load above is issued before the first use below
 #pragma unroll
   for (int i = 0; i < PER; ++i) {
     const uint32_t idx = base + i * NT + threadIdx.x;
