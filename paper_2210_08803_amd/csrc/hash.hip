@@ -188,7 +188,6 @@ __global__ __launch_bounds__(256) void hash_insert_new(u64* slots /* {key,row} p
                                                        const HashWsHeader* hdr,
                                                        const int64_t* __restrict__ keys,
                                                        const uint32_t* __restrict__ miss_pos,
-                                                       const uint32_t* __restrict__ scr_slot,
                                                        const uint32_t* __restrict__ first,
                                                        const uint32_t* __restrict__ rank) {
   const uint32_t m = blockIdx.x * 256u + threadIdx.x;
@@ -323,8 +322,7 @@ hctr_status hash_lookup(hctr_hash* h, const int64_t* keys, int64_t n64, int inse
   HCTR_TRY(dedup_first_appearance(keys, n, B, stream));
   hipLaunchKernelGGL(hash_insert_new, dim3(nb), dim3(256), 0, stream, h->slots, h->n_buckets,
                      (const HashHeader*)thdr, h->max_rows, rows, (const HashWsHeader*)hdr, keys,
-                     (const uint32_t*)miss_pos, (const uint32_t*)scr_slot, (const uint32_t*)first,
-                     (const uint32_t*)rank);
+                     (const uint32_t*)miss_pos, (const uint32_t*)first, (const uint32_t*)rank);
   hipLaunchKernelGGL(hash_resolve, dim3(nb), dim3(256), 0, stream, (const uint32_t*)scratch, hdr, thdr,
                      h->max_rows, (const uint32_t*)miss_pos, (const uint32_t*)scr_slot, (const uint32_t*)first, rows);
   return launch_status("hash_lookup");
