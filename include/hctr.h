@@ -189,7 +189,8 @@ hctr_status hctr_emb_invalid_keys(const void* ws, size_t ws_bytes, void* stream,
  *   Bags      bag = sample * L + l; keys bag-major.
  *   Input     sparse: CSR offsets [batch * L + 1] as for a layer.  Dense: offsets == NULL, every
  *             sample brings exactly lookups[l].hotness keys for lookup l, so nnz = batch * sum of
- *             hotness (the library writes the CSR offsets of that shape into the workspace).
+ *             hotness (for backward the library writes the CSR offsets of that shape into the workspace,
+ *             unless every lookup has hotness 1).
  *   Output    out / dY are fp32 [batch, width] row-major, width = sum of the lookups' table widths;
  *             lookup l occupies columns [col_l, col_l + dim_l), col_l = sum of the widths before it.
  *   Rows      for the dedup the tables' rows are numbered over their concatenation in tables[]
