@@ -326,7 +326,8 @@ hctr_status hctr_cache_set_small_call_limit(hctr_cache* cache, int64_t max_keys)
  * the count at or above `limit` (2 .. 2^32 - 256, the default) first lowers every stamp and the
  * count by limit / 2, stamps at or below that becoming 0 = never used (among those the lowest way
  * is replaced first).  The order of the ways used within the last limit / 2 calls is unchanged, so
- * a cache serves any number of calls.  Lower limits exist for tests.  (The paper gives no
+ * a cache serves any number of calls.  Lower limits exist for tests; set one before the count
+ * has passed it (a count far above the limit comes down by only limit / 2 per call).  (The paper gives no
  * replacement policy; section 3, "embedding inference cache", only names dynamic insertion.) */
 hctr_status hctr_cache_set_epoch_limit(hctr_cache* cache, int64_t limit);
 /*
