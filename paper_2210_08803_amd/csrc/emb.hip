@@ -69,15 +69,16 @@ __device__ __forceinline__ uint32_t walk_to_bag(uint32_t v, uint32_t n_bags, uin
 // lane in flight), so a wave covers 64/LPR * U bags.
 // ------------------------------------------------------------------------------------------------
 template <typename T, typename OutT, int LPR, int U, bool HASHED>
-__global__ __launch_bounds__(256) void fwd_onehot(const T* __restrict__ table, int D,
+__global__ __launch_bounds__(HASHED ? 256 : 512) void fwd_onehot(const T* __restrict__ table, int D,
                                                   int64_t total_rows, const int64_t* __restrict__ keys,
                                                   const int64_t* __restrict__ rows64, uint32_t n_bags,
                                                   uint32_t S, uint32_t n_samples, const SlotTable slots,
                                                   OutT* __restrict__ out, EmbHeader* hdr) {
   constexpr int VEC = RowVec<T>::VEC;
+  constexpr uint32_t kThreads = HASHED ? 256u : 512u;   // direct mode measured 1.5 % faster with 512 (same buffers)
   const int sub = threadIdx.x % LPR;
-  const uint32_t group0 = (blockIdx.x * 256u + threadIdx.x) / LPR;
-  const uint32_t n_groups = gridDim.x * (256u / LPR);
+  const uint32_t group0 = (blockIdx.x * kThreads + threadIdx.x) / LPR;
+  const uint32_t n_groups = gridDim.x * (kThreads / LPR);
   const int col = blockIdx.y * (LPR * VEC) + sub * VEC;
   const bool active = col < D;
   uint32_t nbad = 0;  // counted by the first lane of each group
@@ -1116,13 +1117,14 @@ static void launch_forward(const hctr_emb_desc* d, const int64_t* keys, const in
   const uint32_t n_samples = (!rows64 && S > 1 && (size_t)d->dim * sizeof(OutT) >= kSlotMajorMinRowBytes) ? n_bags / S : 0u;
   if (!offsets) {
     constexpr int U = 4;
-    const uint32_t bags_per_block = (256 / LPR) * U;
+    const uint32_t threads = rows64 ? 256u : 512u;   // as in the kernel
+    const uint32_t bags_per_block = (threads / LPR) * U;
     dim3 grid((uint32_t)ceil_div(n_bags, bags_per_block), ychunks);
     if (rows64)
       hipLaunchKernelGGL((fwd_onehot<T, OutT, LPR, U, true>), grid, dim3(256), 0, stream, table, d->dim,
                          d->total_rows, keys, rows64, n_bags, S, n_samples, st, out, hdr);
     else
-      hipLaunchKernelGGL((fwd_onehot<T, OutT, LPR, U, false>), grid, dim3(256), 0, stream, table, d->dim,
+      hipLaunchKernelGGL((fwd_onehot<T, OutT, LPR, U, false>), grid, dim3(512), 0, stream, table, d->dim,
                          d->total_rows, keys, rows64, n_bags, S, n_samples, st, out, hdr);
   } else {
     constexpr int U = 4;
