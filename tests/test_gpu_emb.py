@@ -133,6 +133,15 @@ def test_every_key_equal_one_long_segment():
     assert info["unique"] == 1 and info["max_count"] == 9000
 
 
+def test_more_long_rows_than_blocks_in_the_long_row_kernel():
+    """The largest slot count (128), three rows per slot, uniform keys: all 384 rows collect about 830
+    occurrences each, i.e. 13 reduction windows, so every row goes to the list of long rows and that
+    list is longer than the grid of the kernel that walks it (256 blocks)."""
+    info = run_case([3] * 128, 8, 2500, alpha=0.0)
+    assert info["unique"] == 384 and info["nnz"] == 320000
+    assert info["nnz"] // info["unique"] > 9 * 64
+
+
 @pytest.mark.parametrize("batch", [1, 31, 32, 33, 4095, 4096, 4097])
 def test_sizes_around_window_and_tile_edges(batch):
     run_case([500], 32, batch)
