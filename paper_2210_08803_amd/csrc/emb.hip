@@ -246,6 +246,25 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
   }
 }
 
+// Low half of a sorted (row, bag) word.  A mean needs 1 / (keys of the bag) for every occurrence,
+// and fetching the bag's two bounds from the offsets at that point is a random read per occurrence
+// (it cost a fifth of the multi-hot reduction).  The key -> row kernel walks the keys in bag order
+// and has the bounds at hand, so when bag numbers leave bag_bits < 32 the count goes into the bits
+// above the bag number; a count too large for them is stored as 0 = "look it up".  bag_bits == 32:
+// the low half is the bag number alone.
+struct BagWord {
+  static __device__ __forceinline__ uint32_t pack(uint32_t bag, uint64_t count, uint32_t bag_bits) {
+    const uint32_t room = 32u - bag_bits;   // 4..31
+    return bag | ((count >> room) == 0 ? (uint32_t)count << bag_bits : 0u);
+  }
+  static __device__ __forceinline__ uint32_t bag(uint32_t low, uint32_t bag_bits) {
+    return bag_bits < 32u ? low & ((1u << bag_bits) - 1u) : low;
+  }
+  static __device__ __forceinline__ uint32_t count(uint32_t low, uint32_t bag_bits) {   // 0: not stored
+    return bag_bits < 32u ? low >> bag_bits : 0u;
+  }
+};
+
 // ------------------------------------------------------------------------------------------------
 // Backward step 1: per key, the 32-bit global row (or kNoRow) and the bag it belongs to.
 // ------------------------------------------------------------------------------------------------
@@ -320,7 +339,8 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
                                                uint32_t n_bags, uint32_t S, const SlotTable slots,
                                                int64_t total_rows, uint64_t* __restrict__ kv,
                                                EmbHeader* hdr, uint32_t bins,
-                                               uint32_t* __restrict__ hist, uint32_t* __restrict__ sup) {
+                                               uint32_t* __restrict__ hist, uint32_t* __restrict__ sup,
+                                               uint32_t bag_bits) {
   // One sort tile per block, so the block can also deliver the tile's histogram of the first sort
   // digit (the low bits of the row) and spare the sort its first counting pass.
   __shared__ uint32_t h[1 << kSortMaxDigitBits];   // (four copies as in sort_hist cost occupancy here: slower)
@@ -347,6 +367,18 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
     const uint32_t i = k0 + it * (uint32_t)NT + threadIdx.x;
     in[it] = src[i < nnz ? i : nnz - 1];
   }
+  // bag_bits < 32: the number of keys of the bag rides in the word's spare bits (see BagWord)
+  const bool pack = offsets != nullptr && bag_bits < 32u;
+  int64_t first[PER], past[PER];
+  if (pack) {
+#pragma unroll
+    for (int it = 0; it < PER; ++it) {
+      const uint32_t i = k0 + it * (uint32_t)NT + threadIdx.x;
+      const uint32_t bag = bagof[(i < nnz ? i : nnz - 1) - k0] - 1u;
+      first[it] = offsets[bag];
+      past[it] = offsets[bag + 1];
+    }
+  }
   __builtin_amdgcn_sched_barrier(0);   // every load above is issued before the first use below
 #pragma unroll
   for (int it = 0; it < PER; ++it) {
@@ -364,7 +396,8 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
       }
       const uint32_t r32 = row < 0 ? kNoRow : (uint32_t)row;
       nbad += row < 0 ? 1u : 0u;
-      kv[i] = ((uint64_t)r32 << 32) | bag;
+      const uint32_t low = pack ? BagWord::pack(bag, (uint64_t)(past[it] - first[it]), bag_bits) : bag;
+      kv[i] = ((uint64_t)r32 << 32) | low;
       atomicAdd(&h[r32 & mask], 1u);
     }
   }
@@ -627,7 +660,7 @@ template <typename T, int LPR, typename View, bool ONCE>
 __global__ __launch_bounds__(256) void bwd_reduce_windows(
     const View view, const uint64_t* __restrict__ skv, const EmbHeader* __restrict__ hdr,
     const int64_t* __restrict__ offsets, float lr, float* __restrict__ head, float* __restrict__ tail,
-    uint8_t* __restrict__ tail_flag, uint32_t W, EmbHeader* hdr_rw) {
+    uint8_t* __restrict__ tail_flag, uint32_t W, EmbHeader* hdr_rw, uint32_t bag_bits) {
   __shared__ GroupLookup lds_lk[View::kLds];
   const GroupLookup* lk = view.stage(lds_lk);
   const int sub = threadIdx.x % LPR;
@@ -656,9 +689,12 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
     if (sub < cnt) {
       const uint64_t w64 = skv[p0 + sub];
       myrow = (uint32_t)(w64 >> 32);
-      mybag = (uint32_t)w64;
+      mybag = BagWord::bag((uint32_t)w64, bag_bits);
       if (p0 + sub + 1 < n_valid) mynext = (uint32_t)(skv[p0 + sub + 1] >> 32);
-      if (view.is_mean(mybag, lk)) myw = 1.0f / (float)(offsets[mybag + 1] - offsets[mybag]);
+      if (view.is_mean(mybag, lk)) {
+        const uint32_t stored = BagWord::count((uint32_t)w64, bag_bits);
+        myw = 1.0f / (stored ? (float)stored : (float)(offsets[mybag + 1] - offsets[mybag]));
+      }
     }
     for (int q0 = 0; q0 < cnt; q0 += UB) {
       // All loads of the step raw and first - the UB gradient pieces without a branch (a lane past
@@ -732,14 +768,14 @@ constexpr uint32_t kCarryShort = 8;
 __device__ __forceinline__ void carry_extent(const uint64_t* __restrict__ skv,
                                              const uint32_t* __restrict__ starts_before,
                                              const uint32_t* __restrict__ seg_off, uint32_t win, uint32_t W,
-                                             uint32_t* row, uint32_t* bag, uint32_t* last) {
+                                             uint32_t bag_bits, uint32_t* row, uint32_t* bag, uint32_t* last) {
   // a tail exists only when the window is full and its last row continues into the next window
   const uint32_t p = win * W + W - 1;
   const uint64_t w64 = skv[p];
   const uint32_t r = (uint32_t)(w64 >> 32);
   const uint32_t u = starts_before[win] + ((p == 0 || (uint32_t)(skv[p - 1] >> 32) != r) ? 1u : 0u) - 1u;
   *row = r;
-  *bag = (uint32_t)w64;   // any occurrence of the row names its table
+  *bag = BagWord::bag((uint32_t)w64, bag_bits);   // any occurrence of the row names its table
   *last = (seg_off[u + 1] - 1u) / W;   // last window holding a piece of the row
 }
 
@@ -748,7 +784,7 @@ __global__ __launch_bounds__(256) void bwd_carry_short(
     const View view, const uint64_t* __restrict__ skv, const uint32_t* __restrict__ starts_before,
     const uint32_t* __restrict__ seg_off, EmbHeader* hdr, float lr, const float* __restrict__ head,
     const float* __restrict__ tail, const uint8_t* __restrict__ tail_flag, uint32_t W,
-    uint32_t* __restrict__ long_list) {
+    uint32_t* __restrict__ long_list, uint32_t bag_bits) {
   __shared__ GroupLookup lds_lk[View::kLds];
   const GroupLookup* lk = view.stage(lds_lk);
   const int sub = threadIdx.x % LPR;
@@ -758,7 +794,7 @@ __global__ __launch_bounds__(256) void bwd_carry_short(
   if ((uint64_t)win * W >= hdr->n_valid) return;
   if (!tail_flag[win]) return;
   uint32_t r, bag, last;
-  carry_extent(skv, starts_before, seg_off, win, W, &r, &bag, &last);
+  carry_extent(skv, starts_before, seg_off, win, W, bag_bits, &r, &bag, &last);
   const uint32_t cnt = last - win;   // following windows, each with a head partial
   if (cnt > kCarryShort) {
     if (sub == 0 && blockIdx.y == 0) long_list[atomicAdd(&hdr->n_long, 1u)] = win;
@@ -784,7 +820,7 @@ __global__ __launch_bounds__(1024) void bwd_carry_long(
     const View view, const uint64_t* __restrict__ skv, const uint32_t* __restrict__ starts_before,
     const uint32_t* __restrict__ seg_off, const EmbHeader* __restrict__ hdr, float lr,
     const float* __restrict__ head, const float* __restrict__ tail, uint32_t W,
-    const uint32_t* __restrict__ long_list) {
+    const uint32_t* __restrict__ long_list, uint32_t bag_bits) {
   constexpr int NG = 1024 / LPR;
   __shared__ f32x4 part[1024];
   __shared__ GroupLookup lds_lk[View::kLds];
@@ -796,7 +832,7 @@ __global__ __launch_bounds__(1024) void bwd_carry_long(
   for (uint32_t i = blockIdx.x; i < n_long; i += gridDim.x) {   // block-uniform loop
     const uint32_t win = long_list[i];
     uint32_t r, bag, last;
-    carry_extent(skv, starts_before, seg_off, win, W, &r, &bag, &last);
+    carry_extent(skv, starts_before, seg_off, win, W, bag_bits, &r, &bag, &last);
     const bool active = col < view.row_width(bag, lk);
     const uint32_t cnt = last - win;
     const uint32_t share = (cnt + NG - 1) / NG;
@@ -1154,9 +1190,17 @@ static void dispatch_forward(int lpr, const hctr_emb_desc* d, const int64_t* key
   }
 }
 
+// Bits of a sorted word's low half that hold the bag number (see BagWord): all 32 unless a mean is
+// taken over bags given by offsets and the bag numbers leave at least four bits for the count.
+static uint32_t bag_bits_for(bool mean_over_offsets, int64_t n_bags) {
+  if (!mean_over_offsets) return 32u;
+  const int bits = std::max(1, ceil_log2((uint64_t)n_bags));
+  return bits <= 28 ? (uint32_t)bits : 32u;
+}
+
 // Launches the three reduction kernels for one view; dmax = widest row of the view.
 template <typename T, int LPR, typename View>
-static void launch_reduce(const View& view, int dmax, bool once, const EmbLayout& L, char* ws,
+static void launch_reduce(const View& view, int dmax, bool once, uint32_t bag_bits, const EmbLayout& L, char* ws,
                           const uint64_t* skv, const int64_t* offsets, float lr, hipStream_t stream) {
   const uint32_t ychunks = (uint32_t)ceil_div(dmax, LPR * 4);
   dim3 grid((uint32_t)ceil_div(L.n_windows, 256 / LPR), ychunks);
@@ -1166,46 +1210,49 @@ static void launch_reduce(const View& view, int dmax, bool once, const EmbLayout
   uint8_t* tflag = reinterpret_cast<uint8_t*>(ws + L.tail_flag);
   if (once)
     hipLaunchKernelGGL((bwd_reduce_windows<T, LPR, View, true>), grid, dim3(256), 0, stream, view, skv,
-                       (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr);
+                       (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr, bag_bits);
   else
     hipLaunchKernelGGL((bwd_reduce_windows<T, LPR, View, false>), grid, dim3(256), 0, stream, view, skv,
-                       (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr);
+                       (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr, bag_bits);
   uint32_t* long_list = reinterpret_cast<uint32_t*>(ws + L.long_list);
   const uint32_t* starts_before = reinterpret_cast<const uint32_t*>(ws + L.flags);
   const uint32_t* seg_off = reinterpret_cast<const uint32_t*>(ws + L.seg_off);
   hipLaunchKernelGGL((bwd_carry_short<T, LPR, View>), grid, dim3(256), 0, stream, view, skv, starts_before,
                      seg_off, hdr, lr, (const float*)head, (const float*)tail, (const uint8_t*)tflag, L.window,
-                     long_list);
+                     long_list, bag_bits);
   dim3 lgrid(L.n_windows < 256u ? L.n_windows : 256u, ychunks);
   hipLaunchKernelGGL((bwd_carry_long<T, LPR, View>), lgrid, dim3(1024), 0, stream, view, skv, starts_before,
                      seg_off, (const EmbHeader*)hdr, lr, (const float*)head, (const float*)tail, L.window,
-                     (const uint32_t*)long_list);
+                     (const uint32_t*)long_list, bag_bits);
 }
 
 template <typename T, typename View>
-static void dispatch_reduce_view(const View& view, int dmax, bool once, const EmbLayout& L, char* ws,
-                                 const uint64_t* skv, const int64_t* offsets, float lr, hipStream_t stream) {
+static void dispatch_reduce_view(const View& view, int dmax, bool once, uint32_t bag_bits, const EmbLayout& L,
+                                 char* ws, const uint64_t* skv, const int64_t* offsets, float lr,
+                                 hipStream_t stream) {
   int lpr = pow2_ceil((int)ceil_div(dmax, 4));
   lpr = lpr < 4 ? 4 : (lpr > 64 ? 64 : lpr);
   switch (lpr) {
-    case 4: launch_reduce<T, 4>(view, dmax, once, L, ws, skv, offsets, lr, stream); break;
-    case 8: launch_reduce<T, 8>(view, dmax, once, L, ws, skv, offsets, lr, stream); break;
-    case 16: launch_reduce<T, 16>(view, dmax, once, L, ws, skv, offsets, lr, stream); break;
-    case 32: launch_reduce<T, 32>(view, dmax, once, L, ws, skv, offsets, lr, stream); break;
-    default: launch_reduce<T, 64>(view, dmax, once, L, ws, skv, offsets, lr, stream); break;
+    case 4: launch_reduce<T, 4>(view, dmax, once, bag_bits, L, ws, skv, offsets, lr, stream); break;
+    case 8: launch_reduce<T, 8>(view, dmax, once, bag_bits, L, ws, skv, offsets, lr, stream); break;
+    case 16: launch_reduce<T, 16>(view, dmax, once, bag_bits, L, ws, skv, offsets, lr, stream); break;
+    case 32: launch_reduce<T, 32>(view, dmax, once, bag_bits, L, ws, skv, offsets, lr, stream); break;
+    default: launch_reduce<T, 64>(view, dmax, once, bag_bits, L, ws, skv, offsets, lr, stream); break;
   }
 }
 
 template <typename T, typename DyT>
-static void dispatch_reduce(const hctr_emb_desc* d, const EmbLayout& L, char* ws, const uint64_t* skv,
-                            const int64_t* offsets, const void* dY, float lr, hipStream_t stream) {
+static void dispatch_reduce(const hctr_emb_desc* d, int64_t batch, const EmbLayout& L, char* ws,
+                            const uint64_t* skv, const int64_t* offsets, const void* dY, float lr,
+                            hipStream_t stream) {
   UniformView<T, DyT> view;
   view.table = static_cast<T*>(d->table);
   view.master = d->master;
   view.dY = static_cast<const DyT*>(dY);
   view.D = d->dim;
   view.mean = (d->combiner == HCTR_MEAN && offsets != nullptr) ? 1 : 0;
-  dispatch_reduce_view<T>(view, d->dim, offsets == nullptr, L, ws, skv, offsets, lr, stream);
+  const uint32_t bag_bits = bag_bits_for(view.mean != 0, batch * d->num_slots);
+  dispatch_reduce_view<T>(view, d->dim, offsets == nullptr, bag_bits, L, ws, skv, offsets, lr, stream);
 }
 
 }  // namespace hctr
@@ -1257,7 +1304,7 @@ HCTR_API hctr_status hctr_emb_forward(const hctr_emb_desc* desc, int64_t batch, 
 // are given in rows64): packed (row, bag) words, sorted by row, run boundaries.
 static hctr_status dedup_core(const int64_t* keys, const int64_t* rows64, const int64_t* offsets, int64_t nnz,
                               uint32_t n_bags, uint32_t n_slots, const SlotTable& st, int64_t total_rows,
-                              const EmbLayout& L, char* w, hipStream_t stream) {
+                              uint32_t bag_bits, const EmbLayout& L, char* w, hipStream_t stream) {
   EmbHeader* hdr = reinterpret_cast<EmbHeader*>(w + L.header);
   uint32_t* seg_off = reinterpret_cast<uint32_t*>(w + L.seg_off);
   uint32_t* aux = reinterpret_cast<uint32_t*>(w + L.aux);
@@ -1280,10 +1327,10 @@ static hctr_status dedup_core(const int64_t* keys, const int64_t* rows64, const 
   uint32_t* sup0 = sort_scans_groups(L.sort) ? nullptr : sort_aux_sup(L.sort, aux, 0);
   if (wide)
     hipLaunchKernelGGL((bwd_rows<1024>), dim3(L.sort.n_blocks), dim3(1024), 0, stream, keys, rows64, offsets, n,
-                       n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sup0);
+                       n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sup0, bag_bits);
   else
     hipLaunchKernelGGL((bwd_rows<256>), dim3(L.sort.n_blocks), dim3(256), 0, stream, keys, rows64, offsets, n,
-                       n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sup0);
+                       n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sup0, bag_bits);
   HCTR_TRY(radix_sort_u64(L.sort, nullptr, kv0, kv1, hist, aux, true, stream, true));
   const uint64_t* skv = (L.sort.passes & 1) ? kv1 : kv0;
   if (wide) {
@@ -1310,21 +1357,23 @@ static hctr_status backward_dedup(const hctr_emb_desc* desc, int64_t batch, cons
   }
   SlotTable st;
   fill_slots(desc, &st);
-  return dedup_core(keys, rows64, offsets, nnz, (uint32_t)(batch * desc->num_slots), (uint32_t)desc->num_slots,
-                    st, desc->total_rows, L, w, stream);
+  const int64_t n_bags = batch * desc->num_slots;
+  const uint32_t bag_bits = bag_bits_for(desc->combiner == HCTR_MEAN && offsets != nullptr, n_bags);
+  return dedup_core(keys, rows64, offsets, nnz, (uint32_t)n_bags, (uint32_t)desc->num_slots, st, desc->total_rows,
+                    bag_bits, L, w, stream);
 }
 
 // B4-B5: segmented reduction of dY over the sorted occurrences, fused with the SGD row update.
-static hctr_status backward_apply(const hctr_emb_desc* desc, const int64_t* offsets, int64_t nnz,
+static hctr_status backward_apply(const hctr_emb_desc* desc, int64_t batch, const int64_t* offsets, int64_t nnz,
                                   const void* dY, float lr, const EmbLayout& L, char* w,
                                   hipStream_t stream) {
   if (nnz == 0) return HCTR_OK;
   const uint64_t* skv = reinterpret_cast<const uint64_t*>(w + ((L.sort.passes & 1) ? L.kv1 : L.kv0));
   const bool t32 = desc->table_dtype == HCTR_F32, g32 = desc->io_dtype == HCTR_F32;
-  if (t32 && g32) dispatch_reduce<float, float>(desc, L, w, skv, offsets, dY, lr, stream);
-  else if (t32) dispatch_reduce<float, __half>(desc, L, w, skv, offsets, dY, lr, stream);
-  else if (g32) dispatch_reduce<__half, float>(desc, L, w, skv, offsets, dY, lr, stream);
-  else dispatch_reduce<__half, __half>(desc, L, w, skv, offsets, dY, lr, stream);
+  if (t32 && g32) dispatch_reduce<float, float>(desc, batch, L, w, skv, offsets, dY, lr, stream);
+  else if (t32) dispatch_reduce<float, __half>(desc, batch, L, w, skv, offsets, dY, lr, stream);
+  else if (g32) dispatch_reduce<__half, float>(desc, batch, L, w, skv, offsets, dY, lr, stream);
+  else dispatch_reduce<__half, __half>(desc, batch, L, w, skv, offsets, dY, lr, stream);
   return launch_status("hctr_emb_backward_apply");
 }
 
@@ -1341,7 +1390,7 @@ HCTR_API hctr_status hctr_emb_backward_apply(const hctr_emb_desc* desc, int64_t 
                                              size_t ws_bytes, void* stream) {
   EmbLayout L;
   HCTR_TRY(validate_batch(desc, batch, nullptr, offsets, nnz, dY, ws, ws_bytes, &L, true, false));
-  return backward_apply(desc, offsets, nnz, dY, lr, L, static_cast<char*>(ws), static_cast<hipStream_t>(stream));
+  return backward_apply(desc, batch, offsets, nnz, dY, lr, L, static_cast<char*>(ws), static_cast<hipStream_t>(stream));
 }
 
 HCTR_API hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
@@ -1351,7 +1400,7 @@ HCTR_API hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t ba
   HCTR_TRY(validate_batch(desc, batch, keys, offsets, nnz, dY, ws, ws_bytes, &L));
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   HCTR_TRY(backward_dedup(desc, batch, keys, offsets, nnz, L, static_cast<char*>(ws), stream));
-  return backward_apply(desc, offsets, nnz, dY, lr, L, static_cast<char*>(ws), stream);
+  return backward_apply(desc, batch, offsets, nnz, dY, lr, L, static_cast<char*>(ws), stream);
 }
 
 HCTR_API hctr_status hctr_emb_dedup_view(const hctr_emb_desc* desc, int64_t batch, int64_t nnz,
@@ -1528,8 +1577,9 @@ static void group_launch_forward(const GroupPlan& P, bool dense, int64_t batch, 
 }
 
 template <typename T>
-static void group_launch_reduce(const GroupPlan& P, const EmbLayout& L, char* w, const uint64_t* skv,
-                                const int64_t* csr, const float* dY, float lr, hipStream_t stream) {
+static void group_launch_reduce(const GroupPlan& P, uint32_t bag_bits, const EmbLayout& L, char* w,
+                                const uint64_t* skv, const int64_t* csr, const float* dY, float lr,
+                                hipStream_t stream) {
   GroupView<T> view;
   view.dY = dY;
   view.L = P.L;
@@ -1539,7 +1589,7 @@ static void group_launch_reduce(const GroupPlan& P, const EmbLayout& L, char* w,
     view.lk[l] = l < (int)P.L ? P.lk[l] : GroupLookup{nullptr, 0, 0, 0, 0};
     if (csr == nullptr) view.lk[l].mean = 0;   // one key per bag: the mean is the sum, and no offsets exist to read
   }
-  dispatch_reduce_view<T>(view, P.dmax, false, L, w, skv, csr, lr, stream);
+  dispatch_reduce_view<T>(view, P.dmax, false, bag_bits, L, w, skv, csr, lr, stream);
 }
 
 }  // namespace hctr
@@ -1581,11 +1631,14 @@ HCTR_API hctr_status hctr_group_backward_sgd(const hctr_group_desc* desc, int64_
     st.base[s] = s < (int)P.L ? (int64_t)P.lk[s].row_base : 0;
     st.num[s] = s < (int)P.L ? (int64_t)P.num_rows[s] : 0;
   }
-  HCTR_TRY(dedup_core(keys, nullptr, csr, nnz, (uint32_t)(batch * P.L), P.L, st, P.total_rows, L, w, stream));
+  bool any_mean = false;
+  for (uint32_t l = 0; l < P.L; ++l) any_mean |= P.lk[l].mean != 0;
+  const uint32_t bag_bits = bag_bits_for(any_mean && csr != nullptr, batch * P.L);
+  HCTR_TRY(dedup_core(keys, nullptr, csr, nnz, (uint32_t)(batch * P.L), P.L, st, P.total_rows, bag_bits, L, w, stream));
   if (nnz == 0) return HCTR_OK;
   const uint64_t* skv = reinterpret_cast<const uint64_t*>(w + ((L.sort.passes & 1) ? L.kv1 : L.kv0));
-  if (desc->table_dtype == HCTR_F32) group_launch_reduce<float>(P, L, w, skv, csr, dY, lr, stream);
-  else group_launch_reduce<__half>(P, L, w, skv, csr, dY, lr, stream);
+  if (desc->table_dtype == HCTR_F32) group_launch_reduce<float>(P, bag_bits, L, w, skv, csr, dY, lr, stream);
+  else group_launch_reduce<__half>(P, bag_bits, L, w, skv, csr, dY, lr, stream);
   return launch_status("hctr_group_backward_sgd");
 }
 

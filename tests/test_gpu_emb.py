@@ -19,7 +19,8 @@ def H():
 
 def run_case(table_rows, dim, batch, *, dtype=torch.float32, combiner=0, alpha=1.05, hot=None, seed=SEED,
              lr=0.01, share_table=False, poison=0, slot_base=None):
-    """One forward + backward comparison.  hot = None (one-hot) or (lo, hi) hotness range."""
+    """One forward + backward comparison.  hot = None (one-hot), (lo, hi) hotness range, or an array
+    with the number of keys of every bag."""
     h = H()
     S = len(table_rows)
     if share_table:
@@ -35,7 +36,11 @@ def run_case(table_rows, dim, batch, *, dtype=torch.float32, combiner=0, alpha=1
         offsets = None
         keys = datagen.onehot_keys(seed, 0, table_rows, batch, alpha)
     else:
-        offsets = datagen.multihot_offsets(seed, 0, n_bags, hot[0], hot[1])
+        if isinstance(hot, np.ndarray):
+            offsets = torch.zeros(n_bags + 1, dtype=torch.int64)
+            offsets[1:] = torch.from_numpy(np.cumsum(hot.astype(np.int64)))
+        else:
+            offsets = datagen.multihot_offsets(seed, 0, n_bags, hot[0], hot[1])
         keys = datagen.multihot_keys(seed, 0, table_rows, batch, alpha, offsets)
     if poison:
         g = np.random.default_rng(seed)
@@ -140,6 +145,23 @@ def test_more_long_rows_than_blocks_in_the_long_row_kernel():
     info = run_case([3] * 128, 8, 2500, alpha=0.0)
     assert info["unique"] == 384 and info["nnz"] == 320000
     assert info["nnz"] // info["unique"] > 9 * 64
+
+
+@pytest.mark.parametrize("combiner", [0, 1], ids=["sum", "mean"])
+def test_bag_sizes_around_what_the_sorted_word_can_carry(combiner):
+    """For a mean over bags given by offsets the backward keeps each bag's key count in the bits its
+    sorted (row, bag) words do not need for the bag number, and reads the offsets again where the
+    count does not fit.  600,000 bags need 20 bits and leave 12: counts up to 4,095 ride along,
+    4,096 and more do not.  Most bags are empty; a few sit on either side of that edge."""
+    n_bags = 600_000
+    hot = np.zeros(n_bags, dtype=np.int64)
+    g = np.random.default_rng(SEED)
+    where = g.choice(n_bags, 40, replace=False)
+    hot[where] = g.integers(1, 60, 40)
+    hot[where[:8]] = [4095, 4096, 4097, 5000, 4094, 1, 8191, 8192]
+    hot[n_bags - 1] = 4100                      # the last bag: its bound is the last offset
+    info = run_case([3000], 8, n_bags, combiner=combiner, alpha=0.8, hot=hot)
+    assert info["nnz"] == int(hot.sum())
 
 
 @pytest.mark.parametrize("batch", [1, 31, 32, 33, 4095, 4096, 4097])
