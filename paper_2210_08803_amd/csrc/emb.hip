@@ -253,9 +253,9 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
 // above the bag number; a count too large for them is stored as 0 = "look it up".  bag_bits == 32:
 // the low half is the bag number alone.
 struct BagWord {
-  static __device__ __forceinline__ uint32_t pack(uint32_t bag, uint64_t count, uint32_t bag_bits) {
+  static __device__ __forceinline__ uint32_t pack(uint32_t bag, uint32_t count, uint32_t bag_bits) {
     const uint32_t room = 32u - bag_bits;   // 4..31
-    return bag | ((count >> room) == 0 ? (uint32_t)count << bag_bits : 0u);
+    return bag | ((count >> room) == 0 ? count << bag_bits : 0u);
   }
   static __device__ __forceinline__ uint32_t bag(uint32_t low, uint32_t bag_bits) {
     return bag_bits < 32u ? low & ((1u << bag_bits) - 1u) : low;
@@ -331,8 +331,10 @@ __device__ __forceinline__ void tile_bags(const int64_t* __restrict__ offsets, u
   __syncthreads();
 }
 
-// NT = 256, or 1024 when there is only about one tile per compute unit.
-template <int NT>
+// NT = 256, or 1024 when there is only about one tile per compute unit.  PACK: the number of keys of
+// the bag rides in the word's spare bits (see BagWord; needs offsets and bag_bits < 32).  A template
+// choice because the extra loads cost registers that the plain kernel should not pay for.
+template <int NT, bool PACK>
 __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
                                                const int64_t* __restrict__ rows64,
                                                const int64_t* __restrict__ offsets, uint32_t nnz,
@@ -367,16 +369,16 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
     const uint32_t i = k0 + it * (uint32_t)NT + threadIdx.x;
     in[it] = src[i < nnz ? i : nnz - 1];
   }
-  // bag_bits < 32: the number of keys of the bag rides in the word's spare bits (see BagWord)
-  const bool pack = offsets != nullptr && bag_bits < 32u;
-  int64_t first[PER], past[PER];
-  if (pack) {
+  // the bounds of each key's bag; their low halves are enough, a call has fewer than 2^31 keys
+  uint32_t first[PACK ? PER : 1], past[PACK ? PER : 1];
+  if constexpr (PACK) {
+    const uint32_t* low = reinterpret_cast<const uint32_t*>(offsets);
 #pragma unroll
     for (int it = 0; it < PER; ++it) {
       const uint32_t i = k0 + it * (uint32_t)NT + threadIdx.x;
       const uint32_t bag = bagof[(i < nnz ? i : nnz - 1) - k0] - 1u;
-      first[it] = offsets[bag];
-      past[it] = offsets[bag + 1];
+      first[it] = low[2 * (uint64_t)bag];
+      past[it] = low[2 * (uint64_t)bag + 2];
     }
   }
   __builtin_amdgcn_sched_barrier(0);   // every load above is issued before the first use below
@@ -396,7 +398,8 @@ __global__ __launch_bounds__(NT) void bwd_rows(const int64_t* __restrict__ keys,
       }
       const uint32_t r32 = row < 0 ? kNoRow : (uint32_t)row;
       nbad += row < 0 ? 1u : 0u;
-      const uint32_t low = pack ? BagWord::pack(bag, (uint64_t)(past[it] - first[it]), bag_bits) : bag;
+      uint32_t low = bag;
+      if constexpr (PACK) low = BagWord::pack(bag, past[it] - first[it], bag_bits);
       kv[i] = ((uint64_t)r32 << 32) | low;
       atomicAdd(&h[r32 & mask], 1u);
     }
@@ -1325,12 +1328,15 @@ static hctr_status dedup_core(const int64_t* keys, const int64_t* rows64, const 
   const bool wide = L.sort.n_blocks <= kSortWideMaxTiles;
   const uint32_t bins0 = 1u << L.sort.digit_bits[0];
   uint32_t* sup0 = sort_scans_groups(L.sort) ? nullptr : sort_aux_sup(L.sort, aux, 0);
-  if (wide)
-    hipLaunchKernelGGL((bwd_rows<1024>), dim3(L.sort.n_blocks), dim3(1024), 0, stream, keys, rows64, offsets, n,
-                       n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sup0, bag_bits);
-  else
-    hipLaunchKernelGGL((bwd_rows<256>), dim3(L.sort.n_blocks), dim3(256), 0, stream, keys, rows64, offsets, n,
-                       n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sup0, bag_bits);
+  const bool pack = offsets != nullptr && bag_bits < 32u;
+#define HCTR_BWD_ROWS(NT, PACK)                                                                                 \
+  hipLaunchKernelGGL((bwd_rows<NT, PACK>), dim3(L.sort.n_blocks), dim3(NT), 0, stream, keys, rows64, offsets, n, \
+                     n_bags, n_slots, st, total_rows, kv0, hdr, bins0, hist, sup0, bag_bits)
+  if (wide && pack) HCTR_BWD_ROWS(1024, true);
+  else if (wide) HCTR_BWD_ROWS(1024, false);
+  else if (pack) HCTR_BWD_ROWS(256, true);
+  else HCTR_BWD_ROWS(256, false);
+#undef HCTR_BWD_ROWS
   HCTR_TRY(radix_sort_u64(L.sort, nullptr, kv0, kv1, hist, aux, true, stream, true));
   const uint64_t* skv = (L.sort.passes & 1) ? kv1 : kv0;
   if (wide) {
