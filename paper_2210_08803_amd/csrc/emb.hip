@@ -26,8 +26,9 @@ struct EmbHeader {
   unsigned long long reserved;
   long long num_unique;        // U of the last backward
   uint32_t n_valid;            // sorted positions holding a real row
-  uint32_t n_long;             // rows whose carry is left to the block-wide kernel
-  uint32_t pad[58];
+  uint32_t n_long;             // rows whose carry is left to whole blocks (0 between backward calls)
+  uint32_t carry_done;         // blocks of the carry kernel that have finished (0 between calls)
+  uint32_t pad[57];
 };
 static_assert(sizeof(EmbHeader) == 256, "header is one 256-byte block");
 constexpr size_t kEmbHeadBytes = sizeof(EmbHeader) + kInvalidParts * 8;
@@ -47,6 +48,8 @@ __global__ __launch_bounds__(256) void emb_init_header(EmbHeader* hdr, uint32_t*
   if (i == 0) {
     hdr->num_unique = 0;
     hdr->n_valid = 0;
+    hdr->n_long = 0;
+    hdr->carry_done = 0;
     if (seg_off) seg_off[0] = 0;
   }
   if (i < zero_count) zero[i] = 0u;
@@ -648,6 +651,24 @@ struct GroupView {
   }
 };
 
+// A row that crosses window borders is finished after the reduction (see bwd_carry): by a lane group
+// when at most kCarryShort windows follow the one that owns it, by a whole block otherwise.
+constexpr uint32_t kCarryShort = 8;
+
+__device__ __forceinline__ void carry_extent(const uint64_t* __restrict__ skv,
+                                             const uint32_t* __restrict__ starts_before,
+                                             const uint32_t* __restrict__ seg_off, uint32_t win, uint32_t W,
+                                             uint32_t bag_bits, uint32_t* row, uint32_t* bag, uint32_t* last) {
+  // a tail exists only when the window is full and its last row continues into the next window
+  const uint32_t p = win * W + W - 1;
+  const uint64_t w64 = skv[p];
+  const uint32_t r = (uint32_t)(w64 >> 32);
+  const uint32_t u = starts_before[win] + ((p == 0 || (uint32_t)(skv[p - 1] >> 32) != r) ? 1u : 0u) - 1u;
+  *row = r;
+  *bag = BagWord::bag((uint32_t)w64, bag_bits);   // any occurrence of the row names its table
+  *last = (seg_off[u + 1] - 1u) / W;   // last window holding a piece of the row
+}
+
 // ------------------------------------------------------------------------------------------------
 // Backward steps 4+5.  The sorted occurrence list is cut into windows of W positions; a group of
 // LPR lanes (4 dY columns per lane) walks one window.  A row whose occurrences all lie inside the
@@ -663,7 +684,8 @@ template <typename T, int LPR, typename View, bool ONCE>
 __global__ __launch_bounds__(256) void bwd_reduce_windows(
     const View view, const uint64_t* __restrict__ skv, const EmbHeader* __restrict__ hdr,
     const int64_t* __restrict__ offsets, float lr, float* __restrict__ head, float* __restrict__ tail,
-    uint8_t* __restrict__ tail_flag, uint32_t W, EmbHeader* hdr_rw, uint32_t bag_bits) {
+    uint8_t* __restrict__ tail_flag, uint32_t W, EmbHeader* hdr_rw, uint32_t bag_bits,
+    uint32_t* __restrict__ long_list) {
   __shared__ GroupLookup lds_lk[View::kLds];
   const GroupLookup* lk = view.stage(lds_lk);
   const int sub = threadIdx.x % LPR;
@@ -671,12 +693,15 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
   const int col = blockIdx.y * (LPR * 4) + sub * 4;
   const int DM = view.dmax();
   const uint32_t n_valid = hdr->n_valid;
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) hdr_rw->n_long = 0;   // for the carry kernels
   const uint64_t start64 = (uint64_t)win * W;
   if (start64 >= n_valid) return;
   const uint32_t start = (uint32_t)start64;
   const uint32_t end = (n_valid - start < W) ? n_valid : start + W;
 
+  // Asked for now, used at the very end: the row at the start of window win + kCarryShort + 1.  If
+  // it is the row that leaves this window, that row goes on for more than kCarryShort windows.
+  const uint64_t far = (uint64_t)(win + kCarryShort + 1u) * W;
+  const uint32_t far_row = (uint32_t)(skv[far < n_valid ? far : n_valid - 1u] >> 32);
   // `before`: the row being summed began in an earlier window (only the window's first row can).
   bool before = start > 0 && (uint32_t)(skv[start - 1] >> 32) == (uint32_t)(skv[start] >> 32);
   bool wrote_tail = false;
@@ -756,53 +781,42 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
     if (col < DM) store4((before ? head : tail) + (int64_t)win * DM + col, acc);
     wrote_tail = !before;
   }
-  if (sub == 0 && blockIdx.y == 0) tail_flag[win] = wrote_tail ? 1 : 0;
+  if (sub == 0 && blockIdx.y == 0) {
+    tail_flag[win] = wrote_tail ? 1 : 0;
+    // this window owns a row that goes on: list it if it goes on for long (the rows are sorted, so
+    // it does exactly when it still is the row kCarryShort + 1 windows further on)
+    if (wrote_tail && far < n_valid && far_row == (uint32_t)(skv[end - 1] >> 32))
+      long_list[atomicAdd(&hdr_rw->n_long, 1u)] = win;
+  }
 }
 
 // Rows that cross window borders.  The window holding a row's first piece owns the row; its last
-// window follows from seg_off.  bwd_carry_short gives every window a lane group: an owner with at
-// most kCarryShort following windows adds their partials itself (all loads in flight at once) and
-// updates the row; longer rows are queued.  bwd_carry_long then gives each queued row a whole block
-// of 1024 threads: the lane groups each add a contiguous share of the partials, the shares are
-// staged in LDS and added in group order.  Which row lands where in the queue does not matter:
-// every row's additions happen in an order fixed by its length alone.
-constexpr uint32_t kCarryShort = 8;
-
-__device__ __forceinline__ void carry_extent(const uint64_t* __restrict__ skv,
-                                             const uint32_t* __restrict__ starts_before,
-                                             const uint32_t* __restrict__ seg_off, uint32_t win, uint32_t W,
-                                             uint32_t bag_bits, uint32_t* row, uint32_t* bag, uint32_t* last) {
-  // a tail exists only when the window is full and its last row continues into the next window
-  const uint32_t p = win * W + W - 1;
-  const uint64_t w64 = skv[p];
-  const uint32_t r = (uint32_t)(w64 >> 32);
-  const uint32_t u = starts_before[win] + ((p == 0 || (uint32_t)(skv[p - 1] >> 32) != r) ? 1u : 0u) - 1u;
-  *row = r;
-  *bag = BagWord::bag((uint32_t)w64, bag_bits);   // any occurrence of the row names its table
-  *last = (seg_off[u + 1] - 1u) / W;   // last window holding a piece of the row
-}
-
-template <typename T, int LPR, typename View>
-__global__ __launch_bounds__(256) void bwd_carry_short(
-    const View view, const uint64_t* __restrict__ skv, const uint32_t* __restrict__ starts_before,
-    const uint32_t* __restrict__ seg_off, EmbHeader* hdr, float lr, const float* __restrict__ head,
-    const float* __restrict__ tail, const uint8_t* __restrict__ tail_flag, uint32_t W,
-    uint32_t* __restrict__ long_list, uint32_t bag_bits) {
-  __shared__ GroupLookup lds_lk[View::kLds];
-  const GroupLookup* lk = view.stage(lds_lk);
+// window follows from seg_off.  One kernel, two kinds of blocks that do not depend on each other.
+// Rows with more than kCarryShort following windows were listed by the reduction kernel; the first
+// long_blocks blocks (first, so that they start at once: they run longest) give each of them a
+// whole block: the lane groups each add a contiguous share of the partials, the shares are staged
+// in LDS and added in group order.  The other blocks give every window a lane group: an owner with
+// at most kCarryShort following windows adds their partials itself (all loads in flight at once)
+// and updates the row.  Which row lands where in the list does not
+// matter: every row's additions happen in an order fixed by its length alone.
+template <typename View, int LPR>
+__device__ __forceinline__ void carry_short_rows(const View& view, const GroupLookup* lk,
+                                                 const uint64_t* __restrict__ skv,
+                                                 const uint32_t* __restrict__ starts_before,
+                                                 const uint32_t* __restrict__ seg_off, uint32_t n_valid, float lr,
+                                                 const float* __restrict__ head, const float* __restrict__ tail,
+                                                 const uint8_t* __restrict__ tail_flag, uint32_t W,
+                                                 uint32_t bag_bits, uint32_t block) {
   const int sub = threadIdx.x % LPR;
-  const uint32_t win = (blockIdx.x * 256u + threadIdx.x) / LPR;
+  const uint32_t win = (block * 1024u + threadIdx.x) / LPR;
   const int col = blockIdx.y * (LPR * 4) + sub * 4;
   const int DM = view.dmax();
-  if ((uint64_t)win * W >= hdr->n_valid) return;
+  if ((uint64_t)win * W >= n_valid) return;
   if (!tail_flag[win]) return;
   uint32_t r, bag, last;
   carry_extent(skv, starts_before, seg_off, win, W, bag_bits, &r, &bag, &last);
   const uint32_t cnt = last - win;   // following windows, each with a head partial
-  if (cnt > kCarryShort) {
-    if (sub == 0 && blockIdx.y == 0) long_list[atomicAdd(&hdr->n_long, 1u)] = win;
-    return;
-  }
+  if (cnt > kCarryShort) return;     // on the list of long rows
   const bool active = col < view.row_width(bag, lk);
   f32x4 h[kCarryShort];
 #pragma unroll
@@ -818,21 +832,20 @@ __global__ __launch_bounds__(256) void bwd_carry_short(
   }
 }
 
-template <typename T, int LPR, typename View>
-__global__ __launch_bounds__(1024) void bwd_carry_long(
-    const View view, const uint64_t* __restrict__ skv, const uint32_t* __restrict__ starts_before,
-    const uint32_t* __restrict__ seg_off, const EmbHeader* __restrict__ hdr, float lr,
-    const float* __restrict__ head, const float* __restrict__ tail, uint32_t W,
-    const uint32_t* __restrict__ long_list, uint32_t bag_bits) {
+template <typename View, int LPR>
+__device__ __forceinline__ void carry_long_rows(const View& view, const GroupLookup* lk,
+                                                const uint64_t* __restrict__ skv,
+                                                const uint32_t* __restrict__ starts_before,
+                                                const uint32_t* __restrict__ seg_off, uint32_t n_long, float lr,
+                                                const float* __restrict__ head, const float* __restrict__ tail,
+                                                uint32_t W, const uint32_t* __restrict__ long_list,
+                                                uint32_t bag_bits, uint32_t n_blocks,
+                                                f32x4* part /*[1024], LDS*/) {
   constexpr int NG = 1024 / LPR;
-  __shared__ f32x4 part[1024];
-  __shared__ GroupLookup lds_lk[View::kLds];
-  const GroupLookup* lk = view.stage(lds_lk);
   const int sub = threadIdx.x % LPR, g = threadIdx.x / LPR;
   const int col = blockIdx.y * (LPR * 4) + sub * 4;
   const int DM = view.dmax();
-  const uint32_t n_long = hdr->n_long;
-  for (uint32_t i = blockIdx.x; i < n_long; i += gridDim.x) {   // block-uniform loop
+  for (uint32_t i = blockIdx.x; i < n_long; i += n_blocks) {   // block-uniform loop
     const uint32_t win = long_list[i];
     uint32_t r, bag, last;
     carry_extent(skv, starts_before, seg_off, win, W, bag_bits, &r, &bag, &last);
@@ -864,6 +877,30 @@ __global__ __launch_bounds__(1024) void bwd_carry_long(
       view.store_weights(r, bag, lk, col, x);
     }
     __syncthreads();   // part is reused by the next row
+  }
+}
+
+template <typename T, int LPR, typename View>
+__global__ __launch_bounds__(1024) void bwd_carry(
+    const View view, const uint64_t* __restrict__ skv, const uint32_t* __restrict__ starts_before,
+    const uint32_t* __restrict__ seg_off, EmbHeader* hdr, float lr, const float* __restrict__ head,
+    const float* __restrict__ tail, const uint8_t* __restrict__ tail_flag, uint32_t W,
+    const uint32_t* __restrict__ long_list, uint32_t bag_bits, uint32_t long_blocks) {
+  __shared__ f32x4 part[1024];
+  __shared__ GroupLookup lds_lk[View::kLds];
+  const GroupLookup* lk = view.stage(lds_lk);
+  if (blockIdx.x >= long_blocks) {
+    carry_short_rows<View, LPR>(view, lk, skv, starts_before, seg_off, hdr->n_valid, lr, head, tail, tail_flag, W,
+                                bag_bits, blockIdx.x - long_blocks);
+    return;
+  }
+  carry_long_rows<View, LPR>(view, lk, skv, starts_before, seg_off, hdr->n_long, lr, head, tail, W, long_list,
+                             bag_bits, long_blocks, part);
+  // Only these blocks read the list's length, each before it gets here (its loop hangs on the
+  // value): the one that arrives last empties the list for the next call.
+  if (threadIdx.x == 0 && atomicAdd(&hdr->carry_done, 1u) == long_blocks * gridDim.y - 1u) {
+    hdr->n_long = 0;
+    hdr->carry_done = 0;
   }
 }
 
@@ -1211,22 +1248,20 @@ static void launch_reduce(const View& view, int dmax, bool once, uint32_t bag_bi
   float* head = reinterpret_cast<float*>(ws + L.head);
   float* tail = reinterpret_cast<float*>(ws + L.tail);
   uint8_t* tflag = reinterpret_cast<uint8_t*>(ws + L.tail_flag);
-  if (once)
-    hipLaunchKernelGGL((bwd_reduce_windows<T, LPR, View, true>), grid, dim3(256), 0, stream, view, skv,
-                       (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr, bag_bits);
-  else
-    hipLaunchKernelGGL((bwd_reduce_windows<T, LPR, View, false>), grid, dim3(256), 0, stream, view, skv,
-                       (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr, bag_bits);
   uint32_t* long_list = reinterpret_cast<uint32_t*>(ws + L.long_list);
   const uint32_t* starts_before = reinterpret_cast<const uint32_t*>(ws + L.flags);
   const uint32_t* seg_off = reinterpret_cast<const uint32_t*>(ws + L.seg_off);
-  hipLaunchKernelGGL((bwd_carry_short<T, LPR, View>), grid, dim3(256), 0, stream, view, skv, starts_before,
-                     seg_off, hdr, lr, (const float*)head, (const float*)tail, (const uint8_t*)tflag, L.window,
-                     long_list, bag_bits);
-  dim3 lgrid(L.n_windows < 256u ? L.n_windows : 256u, ychunks);
-  hipLaunchKernelGGL((bwd_carry_long<T, LPR, View>), lgrid, dim3(1024), 0, stream, view, skv, starts_before,
-                     seg_off, (const EmbHeader*)hdr, lr, (const float*)head, (const float*)tail, L.window,
-                     (const uint32_t*)long_list, bag_bits);
+  if (once)
+    hipLaunchKernelGGL((bwd_reduce_windows<T, LPR, View, true>), grid, dim3(256), 0, stream, view, skv,
+                       (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr, bag_bits, long_list);
+  else
+    hipLaunchKernelGGL((bwd_reduce_windows<T, LPR, View, false>), grid, dim3(256), 0, stream, view, skv,
+                       (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr, bag_bits, long_list);
+  const uint32_t short_blocks = (uint32_t)ceil_div(L.n_windows, 1024 / LPR);
+  const uint32_t long_blocks = L.n_windows < 256u ? L.n_windows : 256u;
+  hipLaunchKernelGGL((bwd_carry<T, LPR, View>), dim3(long_blocks + short_blocks, ychunks), dim3(1024), 0, stream,
+                     view, skv, starts_before, seg_off, hdr, lr, (const float*)head, (const float*)tail,
+                     (const uint8_t*)tflag, L.window, (const uint32_t*)long_list, bag_bits, long_blocks);
 }
 
 template <typename T, typename View>

@@ -268,6 +268,33 @@ def test_split_backward_beside_forward_on_two_streams():
     assert torch.equal(ra, rb) and torch.equal(ca, cb)
 
 
+def test_one_dedup_serves_several_applies():
+    """hctr_emb_backward_dedup once, hctr_emb_backward_apply twice with different gradients on the
+    same workspace: the same bits as two single-call backwards.  Every row here is frequent enough to
+    go on the list of long rows, which each apply has to leave empty for the next."""
+    h = H()
+    rows, dim, batch = [3] * 8, 16, 4000
+    S = len(rows)
+    ro = datagen.row_offsets(rows)
+    table = datagen.table_rows_at(SEED, torch.arange(int(ro[-1])), dim, torch.float32)
+    keys = to_dev(datagen.onehot_keys(SEED, 5, rows, batch, 0.0))
+    g1 = to_dev(datagen.normal_grads(SEED, 6, batch * S * dim).view(batch * S, dim))
+    g2 = to_dev(datagen.normal_grads(SEED, 7, batch * S * dim).view(batch * S, dim))
+    t1, t2 = to_dev(table), to_dev(table)
+    a = h.EmbeddingLayer(t1, S, 0, ro[:-1], rows)
+    b = h.EmbeddingLayer(t2, S, 0, ro[:-1], rows)
+    a.backward_sgd(batch, keys, g1, 0.01)
+    a.backward_sgd(batch, keys, g2, 0.02)
+    ws = b.workspace(batch, keys.numel())
+    b.backward_dedup(batch, keys, ws=ws)
+    b.backward_apply(batch, keys.numel(), g1, 0.01, ws=ws)
+    b.backward_apply(batch, keys.numel(), g2, 0.02, ws=ws)
+    torch.cuda.synchronize()
+    _, counts = b.dedup_result(batch, keys.numel(), ws=ws)
+    assert int(counts.min()) > 9 * 64
+    assert torch.equal(t1, t2)
+
+
 def test_check_offsets_accepts_valid_and_names_broken_input():
     h = H()
     good = torch.tensor([0, 2, 2, 5, 9], dtype=torch.int64, device="cuda")
