@@ -896,8 +896,9 @@ __global__ __launch_bounds__(1024) void bwd_carry(
   }
   carry_long_rows<View, LPR>(view, lk, skv, starts_before, seg_off, hdr->n_long, lr, head, tail, W, long_list,
                              bag_bits, long_blocks, part);
-  // Only these blocks read the list's length, each before it gets here (its loop hangs on the
-  // value): the one that arrives last empties the list for the next call.
+  // Only these blocks read the list's length, and past this barrier every thread of the block has:
+  // the block that is counted last empties the list for the next call.
+  __syncthreads();
   if (threadIdx.x == 0 && atomicAdd(&hdr->carry_done, 1u) == long_blocks * gridDim.y - 1u) {
     hdr->n_long = 0;
     hdr->carry_done = 0;
