@@ -364,13 +364,19 @@ __global__ __launch_bounds__(NT) void sort_scatter(
     const uint32_t idx = wbase + r * 64 + lane;
     const bool valid = idx < n;
     const uint32_t d = (uint32_t)(word[r] >> (32 + shift)) & mask;
-    uint64_t peers = __ballot(valid);
+    // peers = the valid lanes whose digit equals this lane's.  Per bit: m = the lane's bit spread over
+    // a word (0 or ~0), vote ^ m = the lanes whose bit differs; those are collected over all bits
+    // and struck out at the end (four vector instructions per bit, where a select between vote and
+    // ~vote took nine - the ranking is bound by them).
+    uint32_t differs_lo = 0, differs_hi = 0;
 #pragma unroll
     for (int b = 0; b < DBITS; ++b) {
-      const bool bit = (d >> b) & 1u;
-      const uint64_t vote = __ballot(bit);
-      peers &= bit ? vote : ~vote;
+      const uint32_t m = (uint32_t)((int32_t)(d << (31 - b)) >> 31);
+      const uint64_t vote = __ballot(m != 0u);
+      differs_lo |= (uint32_t)vote ^ m;
+      differs_hi |= (uint32_t)(vote >> 32) ^ m;
     }
+    const uint64_t peers = __ballot(valid) & ~(((uint64_t)differs_hi << 32) | differs_lo);
     const uint64_t lower = peers & below;
     uint32_t old = 0;
     if (valid && lower == 0) old = atomicAdd(&cnt[wave][d], (uint32_t)__popcll(peers));
@@ -379,22 +385,78 @@ __global__ __launch_bounds__(NT) void sort_scatter(
     rank[r] = old + (uint32_t)__popcll(lower);
   }
   __syncthreads();
-  for (uint32_t d = threadIdx.x; d < bins; d += NT) {
-    uint32_t run = gbase[d];
+  if constexpr (SCANNED) {
+    // Many tiles: the stores are what counts.  Written straight from the registers, neighbouring
+    // lanes hold words of different digits and a wave's store goes to 64 places, 8 bytes each.
+    // The tile is sorted within LDS first (a word's place in the tile = words of smaller digits +
+    // words of its digit in earlier waves + its rank), then written out in that order: neighbouring
+    // lanes hold neighbouring words of a digit's run, and a store touches as few lines as the runs allow.
+    __shared__ uint64_t stage[kSortTile];
+    const uint32_t d0 = threadIdx.x * 4;   // thread t owns digits 4t .. 4t+3, as above
+    uint32_t c[4][NT / 64], tile_cnt[4] = {0, 0, 0, 0};
+    if (d0 < bins) {
 #pragma unroll
-    for (int w = 0; w < NT / 64; ++w) {
-      const uint32_t c = cnt[w][d];
-      cnt[w][d] = run;
-      run += c;
+      for (int k = 0; k < 4; ++k) {
+#pragma unroll
+        for (int w = 0; w < NT / 64; ++w) {
+          c[k][w] = cnt[w][d0 + k];
+          tile_cnt[k] += c[k][w];
+        }
+      }
     }
-  }
-  __syncthreads();
+    uint32_t total;
+    uint32_t local = block_exclusive_scan<NT>(tile_cnt[0] + tile_cnt[1] + tile_cnt[2] + tile_cnt[3], scan_lds, &total);
+    if (d0 < bins) {
 #pragma unroll
-  for (int r = 0; r < ROUNDS; ++r) {
-    const uint32_t idx = wbase + r * 64 + lane;
-    if (idx < n) {
-      const uint32_t d = (uint32_t)(word[r] >> (32 + shift)) & mask;
-      out[cnt[wave][d] + rank[r]] = word[r];
+      for (int k = 0; k < 4; ++k) {
+        gbase[d0 + k] -= local;   // place in the output = place in the tile + this difference
+        uint32_t run = local;
+#pragma unroll
+        for (int w = 0; w < NT / 64; ++w) {
+          cnt[w][d0 + k] = run;
+          run += c[k][w];
+        }
+        local += tile_cnt[k];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      const uint32_t idx = wbase + r * 64 + lane;
+      if (idx < n) {
+        const uint32_t d = (uint32_t)(word[r] >> (32 + shift)) & mask;
+        stage[cnt[wave][d] + rank[r]] = word[r];
+      }
+    }
+    __syncthreads();
+    const uint32_t held = n - base < kSortTile ? n - base : kSortTile;
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      const uint32_t j = r * NT + threadIdx.x;
+      if (j < held) {
+        const uint64_t w = stage[j];
+        const uint32_t d = (uint32_t)(w >> (32 + shift)) & mask;
+        out[gbase[d] + j] = w;
+      }
+    }
+  } else {
+    for (uint32_t d = threadIdx.x; d < bins; d += NT) {
+      uint32_t run = gbase[d];
+#pragma unroll
+      for (int w = 0; w < NT / 64; ++w) {
+        const uint32_t c = cnt[w][d];
+        cnt[w][d] = run;
+        run += c;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      const uint32_t idx = wbase + r * 64 + lane;
+      if (idx < n) {
+        const uint32_t d = (uint32_t)(word[r] >> (32 + shift)) & mask;
+        out[cnt[wave][d] + rank[r]] = word[r];
+      }
     }
   }
 }
