@@ -1065,7 +1065,7 @@ struct EmbLayout {
   SortPlan sort;
 };
 
-static uint32_t pick_window(int64_t nnz) { return nnz <= (8ll << 20) ? 64u : 128u; }   // powers of two (seg_write)
+static uint32_t pick_window(int64_t nnz) { return nnz <= (8ll << 20) ? 64u : 256u; }   // powers of two (seg_write)
 
 // Workspace of a layer or a group: total_rows rows in all, widest row dmax, hashed = with the
 // key -> row scratch of the hashed mode, extra = bytes appended for the caller (group: CSR offsets).
