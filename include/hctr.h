@@ -148,7 +148,9 @@ hctr_status hctr_emb_backward_sgd(const hctr_emb_desc* desc, int64_t batch, cons
  * time as hctr_emb_forward of the same batch, even on the same workspace (in hashed mode it looks
  * keys up in the hash and must be ordered after the forward that inserts them).
  * hctr_emb_backward_apply then reduces dY over the sorted occurrences and updates the table; it
- * must be ordered after the dedup call on the same `ws`, with the same batch, offsets and nnz.
+ * must be ordered after the dedup call on the same `ws`, with the same batch, offsets, nnz and
+ * combiner.  One dedup call serves any number of apply calls (different dY or lr), one after the
+ * other on the stream; two apply calls on one `ws` must not overlap.
  */
 hctr_status hctr_emb_backward_dedup(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
                                     const int64_t* offsets, int64_t nnz, void* ws, size_t ws_bytes,
