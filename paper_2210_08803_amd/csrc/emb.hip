@@ -180,6 +180,10 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
   float acc[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+  // 1.0f that the compiler cannot see through: acc + x written as fma(x, one, acc) is the same sum
+  // bit for bit, and with fp16 rows the conversion rides along in the one instruction
+  // (v_fma_mix_f32) instead of taking one of its own - the kernel is bound by such instructions.
+  const float one = D > 0 ? 1.0f : 0.0f;
   uint32_t nbad = 0;
   // 64 keys at a time: one coalesced key load and one row computation per lane, then the groups
   // pick their rows from the lanes by shuffle, U row loads each in flight.
@@ -216,7 +220,7 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
         RowVec<T>::widen(raw[u], v);
         if (row[u] != kNoRow && active) {
 #pragma unroll
-          for (int i = 0; i < VEC; ++i) acc[i] += v[i];
+          for (int i = 0; i < VEC; ++i) acc[i] = __builtin_fmaf(v[i], one, acc[i]);
         }
       }
     }
