@@ -122,20 +122,33 @@ __global__ __launch_bounds__(HASHED ? 256 : 512) void fwd_onehot(const T* __rest
 #pragma unroll
     for (int u = 0; u < U; ++u)
       raw[u] = RowVec<T>::load_raw(table + ((row[u] >= 0 && active) ? row[u] * D + col : (int64_t)0));
-    float v[U][VEC];
+    if constexpr (sizeof(T) == 2 && sizeof(OutT) == 2) {
+      // fp16 rows into an fp16 output: the pieces go out as they came in (widening and rounding
+      // back gives the same bits at sixteen conversions per piece)
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      RowVec<T>::widen(raw[u], v[u]);
-      if (!(row[u] >= 0 && active)) {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) v[u][i] = 0.f;
+      for (int u = 0; u < U; ++u) {
+        typename RowVec<T>::Raw x = raw[u];
+        if (!(row[u] >= 0 && active)) x = typename RowVec<T>::Raw{0u, 0u, 0u, 0u};
+        const uint32_t bag = bags[u];
+        if (bag < n_bags && active)
+          __builtin_nontemporal_store(x, reinterpret_cast<typename RowVec<T>::Raw*>(out + (int64_t)bag * D + col));
       }
-    }
+    } else {
+      float v[U][VEC];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t bag = bags[u];
-      if (bag < n_bags && active) {
-        store_stream<VEC>(out + (int64_t)bag * D + col, v[u]);
+      for (int u = 0; u < U; ++u) {
+        RowVec<T>::widen(raw[u], v[u]);
+        if (!(row[u] >= 0 && active)) {
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) v[u][i] = 0.f;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t bag = bags[u];
+        if (bag < n_bags && active) {
+          store_stream<VEC>(out + (int64_t)bag * D + col, v[u]);
+        }
       }
     }
   }
