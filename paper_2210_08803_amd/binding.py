@@ -234,24 +234,35 @@ class EmbeddingLayer:
         d.reuse_forward_rows = int(reuse_forward_rows)
         self.desc = d
         self._wsbuf = None
+        self._invalid_carry = 0   # keys without a row counted on earlier, smaller workspaces of the layer
 
     def workspace_bytes(self, batch: int, nnz: int) -> int:
         return lib().hctr_emb_workspace_bytes(C.byref(self.desc), batch, nnz)
 
-    def workspace(self, batch: int, nnz: int) -> torch.Tensor:
+    def workspace(self, batch: int, nnz: int, stream=None) -> torch.Tensor:
+        """The layer's own workspace, grown when a call needs more.  Growing replaces the buffer: the
+        count of keys without a row seen so far is carried over (invalid_keys() keeps adding up), but
+        the rows a forward left for a reuse_forward_rows backward would be lost, so that case raises."""
         need = self.workspace_bytes(batch, nnz)
         if self._wsbuf is None or self._wsbuf.numel() < need:
-            self._wsbuf = self.new_workspace(need)
+            if self._wsbuf is not None:
+                if self.desc.reuse_forward_rows:
+                    raise HctrError(-3, "the layer's workspace would have to grow between a forward and the "
+                                        "backward that reuses its rows; size it for the largest call first")
+                self._invalid_carry += self.invalid_keys(self._wsbuf)   # explicit buffer: its own count only
+            self._wsbuf = self.new_workspace(need, stream)
         return self._wsbuf
 
-    def new_workspace(self, nbytes: int) -> torch.Tensor:
+    def new_workspace(self, nbytes: int, stream=None) -> torch.Tensor:
+        """A fresh workspace, initialised on `stream` (the stream its first call will use)."""
         ws = _ws(nbytes, self.table.device)
-        _check(lib().hctr_emb_workspace_init(_ptr(ws), ws.numel(), _stream(None)))
+        _check(lib().hctr_emb_workspace_init(_ptr(ws), ws.numel(), _stream(stream)))
         return ws
 
-    def reset_invalid_keys(self, ws: Optional[torch.Tensor] = None) -> None:
-        ws = ws if ws is not None else self._wsbuf
-        _check(lib().hctr_emb_workspace_init(_ptr(ws), ws.numel(), _stream(None)))
+    def reset_invalid_keys(self, ws: Optional[torch.Tensor] = None, stream=None) -> None:
+        if ws is None:
+            ws, self._invalid_carry = self._wsbuf, 0
+        _check(lib().hctr_emb_workspace_init(_ptr(ws), ws.numel(), _stream(stream)))
 
     def forward(self, batch: int, keys: torch.Tensor, offsets: Optional[torch.Tensor] = None,
                 out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
@@ -261,7 +272,7 @@ class EmbeddingLayer:
                               device=self.table.device)
         assert out.dtype == self.io_dtype
         if ws is None:
-            ws = self.workspace(batch, nnz)
+            ws = self.workspace(batch, nnz, stream)
         _check(lib().hctr_emb_forward(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(out),
                                       _ptr(ws), ws.numel(), _stream(stream)))
         return out
@@ -271,7 +282,7 @@ class EmbeddingLayer:
         nnz = keys.numel()
         assert dY.dtype == self.io_dtype and dY.is_contiguous()
         if ws is None:
-            ws = self.workspace(batch, nnz)
+            ws = self.workspace(batch, nnz, stream)
         _check(lib().hctr_emb_backward_sgd(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(dY),
                                            float(lr), _ptr(ws), ws.numel(), _stream(stream)))
 
@@ -279,7 +290,7 @@ class EmbeddingLayer:
                        ws: Optional[torch.Tensor] = None, stream=None) -> None:
         nnz = keys.numel()
         if ws is None:
-            ws = self.workspace(batch, nnz)
+            ws = self.workspace(batch, nnz, stream)
         _check(lib().hctr_emb_backward_dedup(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz,
                                              _ptr(ws), ws.numel(), _stream(stream)))
 
@@ -288,7 +299,7 @@ class EmbeddingLayer:
                        stream=None) -> None:
         assert dY.dtype == self.io_dtype and dY.is_contiguous()
         if ws is None:
-            ws = self.workspace(batch, nnz)
+            ws = self.workspace(batch, nnz, stream)
         _check(lib().hctr_emb_backward_apply(C.byref(self.desc), batch, _ptr(offsets), nnz, _ptr(dY),
                                              float(lr), _ptr(ws), ws.numel(), _stream(stream)))
 
@@ -306,10 +317,13 @@ class EmbeddingLayer:
         return rows, seg[1:] - seg[:-1]
 
     def invalid_keys(self, ws: Optional[torch.Tensor] = None) -> int:
+        """Keys without a row counted on `ws`; for the layer's own workspace (ws None) the total over
+        all the buffers it has had."""
+        carry = self._invalid_carry if ws is None else 0
         ws = ws if ws is not None else self._wsbuf
         v = C.c_int64()
         _check(lib().hctr_emb_invalid_keys(_ptr(ws), ws.numel(), _stream(None), C.byref(v)))
-        return v.value
+        return v.value + carry
 
 
 class EmbeddingGroup:

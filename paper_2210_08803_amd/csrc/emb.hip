@@ -2,6 +2,8 @@
 // for gfx950.  Bandwidth-bound work: every lane moves 16 bytes per load, a table row is covered
 // by a group of LPR adjacent lanes (LPR * 16 bytes >= row bytes), and several independent row
 // loads are in flight per lane before the first use.
+#include <algorithm>
+
 #include "common.h"
 #include "rowvec.h"
 #include "blockscan.h"
@@ -699,9 +701,9 @@ __device__ __forceinline__ void carry_extent(const uint64_t* __restrict__ skv,
 // multi-hot backward ran 45 % slower with streaming loads), so they are read the ordinary way.
 template <typename T, int LPR, typename View, bool ONCE>
 __global__ __launch_bounds__(256) void bwd_reduce_windows(
-    const View view, const uint64_t* __restrict__ skv, const EmbHeader* __restrict__ hdr,
+    const View view, const uint64_t* __restrict__ skv, EmbHeader* hdr,
     const int64_t* __restrict__ offsets, float lr, float* __restrict__ head, float* __restrict__ tail,
-    uint8_t* __restrict__ tail_flag, uint32_t W, EmbHeader* hdr_rw, uint32_t bag_bits,
+    uint8_t* __restrict__ tail_flag, uint32_t W, uint32_t bag_bits,
     uint32_t* __restrict__ long_list) {
   __shared__ GroupLookup lds_lk[View::kLds];
   const GroupLookup* lk = view.stage(lds_lk);
@@ -803,7 +805,7 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
     // this window owns a row that goes on: list it if it goes on for long (the rows are sorted, so
     // it does exactly when it still is the row kCarryShort + 1 windows further on)
     if (wrote_tail && far < n_valid && far_row == (uint32_t)(skv[end - 1] >> 32))
-      long_list[atomicAdd(&hdr_rw->n_long, 1u)] = win;
+      long_list[atomicAdd(&hdr->n_long, 1u)] = win;
   }
 }
 
@@ -1082,7 +1084,8 @@ struct EmbLayout {
   SortPlan sort;
 };
 
-static uint32_t pick_window(int64_t nnz) { return nnz <= (8ll << 20) ? 64u : 256u; }   // powers of two (seg_write)
+constexpr int64_t kWindowSwitch = 8ll << 20;
+static uint32_t pick_window(int64_t nnz) { return nnz <= kWindowSwitch ? 64u : 256u; }   // powers of two (seg_write)
 
 // Workspace of a layer or a group: total_rows rows in all, widest row dmax, hashed = with the
 // key -> row scratch of the hashed mode, extra = bytes appended for the caller (group: CSR offsets).
@@ -1120,6 +1123,15 @@ static EmbLayout emb_layout_raw(int64_t total_rows, int dmax, int64_t nnz_max, b
 
 static EmbLayout emb_layout(const hctr_emb_desc* d, int64_t nnz_max) {
   return emb_layout_raw(d->total_rows, d->dim, nnz_max, d->hash != nullptr, 0);
+}
+
+// Bytes that serve every call of up to nnz_max keys.  A call lays the workspace out from its own
+// key count, and the layout grows with it except where the reduction window widens: a call just
+// below that switch has four times the windows (and partial-sum rows) of a call just above it.
+static size_t emb_bytes_upto(int64_t total_rows, int dmax, int64_t nnz_max, bool hashed, size_t extra) {
+  size_t need = emb_layout_raw(total_rows, dmax, nnz_max, hashed, extra).total;
+  if (nnz_max > kWindowSwitch) need = std::max(need, emb_layout_raw(total_rows, dmax, kWindowSwitch, hashed, extra).total);
+  return need;
 }
 
 static hctr_status validate_desc(const hctr_emb_desc* d) {
@@ -1271,10 +1283,10 @@ static void launch_reduce(const View& view, int dmax, bool once, uint32_t bag_bi
   const uint32_t* seg_off = reinterpret_cast<const uint32_t*>(ws + L.seg_off);
   if (once)
     hipLaunchKernelGGL((bwd_reduce_windows<T, LPR, View, true>), grid, dim3(256), 0, stream, view, skv,
-                       (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr, bag_bits, long_list);
+                       hdr, offsets, lr, head, tail, tflag, L.window, bag_bits, long_list);
   else
     hipLaunchKernelGGL((bwd_reduce_windows<T, LPR, View, false>), grid, dim3(256), 0, stream, view, skv,
-                       (const EmbHeader*)hdr, offsets, lr, head, tail, tflag, L.window, hdr, bag_bits, long_list);
+                       hdr, offsets, lr, head, tail, tflag, L.window, bag_bits, long_list);
   const uint32_t short_blocks = (uint32_t)ceil_div(L.n_windows, 1024 / LPR);
   const uint32_t long_blocks = L.n_windows < 256u ? L.n_windows : 256u;
   hipLaunchKernelGGL((bwd_carry<T, LPR, View>), dim3(long_blocks + short_blocks, ychunks), dim3(1024), 0, stream,
@@ -1318,7 +1330,7 @@ using namespace hctr;
 HCTR_API size_t hctr_emb_workspace_bytes(const hctr_emb_desc* desc, int64_t batch, int64_t nnz_max) {
   (void)batch;
   if (!desc || desc->dim <= 0 || desc->total_rows < 1 || nnz_max < 0 || nnz_max >= (1ll << 31)) return 0;
-  return emb_layout(desc, nnz_max).total;
+  return emb_bytes_upto(desc->total_rows, desc->dim, nnz_max, desc->hash != nullptr, 0);
 }
 
 HCTR_API hctr_status hctr_emb_forward(const hctr_emb_desc* desc, int64_t batch, const int64_t* keys,
@@ -1657,7 +1669,7 @@ HCTR_API size_t hctr_group_workspace_bytes(const hctr_group_desc* desc, int64_t 
   GroupPlan P;
   if (batch < 0 || nnz_max < 0 || nnz_max >= (1ll << 31) || group_plan(desc, &P) != HCTR_OK) return 0;
   if (batch * P.L >= (1ll << 31)) return 0;
-  return group_layout(P, batch, nnz_max).total;
+  return emb_bytes_upto(P.total_rows, P.dmax, nnz_max, false, (size_t)(batch * P.L + 1) * 8);
 }
 
 HCTR_API hctr_status hctr_group_forward(const hctr_group_desc* desc, int64_t batch, const int64_t* keys,

@@ -151,3 +151,32 @@ def test_etc_argument_errors():
     assert L.hctr_etc_dump(None, 1, None) == -2
     assert L.hctr_etc_stats(None, None, None) == -2
     assert L.hctr_hash_clear(None, None) == -2
+
+
+def test_workspace_bytes_serve_every_smaller_call():
+    """A workspace sized for nnz_max keys must be accepted for every call with fewer keys, also
+    where the layout changes with the key count (reduction window at 8 Mi keys, the sort's block
+    shapes at 3 Mi and 4 Mi keys): sizes never shrink as nnz_max grows, and the size check that
+    every call makes (shown here through hctr_emb_dedup_view, which does pointer arithmetic only)
+    accepts the workspace of any larger nnz_max."""
+    L = H.lib()
+    base = (C.c_int64 * 1)(0)
+    num = (C.c_int64 * 1)(1 << 28)
+    d = _EmbDesc(num_slots=1, dim=128, table_dtype=H.F32, combiner=H.SUM, table=4096, total_rows=1 << 28,
+                 slot_row_base=base, slot_num_rows=num, hash=None, insert_on_miss=0)
+    switches = [48 * 16 * 4096, 1024 * 4096, 8 << 20]
+    points = sorted({s + k for s in switches for k in (-4097, -1, 0, 1, 4097)} | {1, 1000, 10_000_000, 12_400_000, 90_000_000})
+    sizes = [L.hctr_emb_workspace_bytes(C.byref(d), 1, n) for n in points]
+    assert all(s > 0 for s in sizes)
+    assert all(a <= b for a, b in zip(sizes, sizes[1:])), list(zip(points, sizes))
+    for n_max in (10_000_000, 12_400_000, (8 << 20) + 1):
+        have = L.hctr_emb_workspace_bytes(C.byref(d), 1, n_max)
+        for n in (8 << 20, (8 << 20) - 5, 8_300_000, n_max):
+            if n <= n_max:
+                a, b, c = C.c_void_p(), C.c_void_p(), C.c_void_p()
+                st = L.hctr_emb_dedup_view(C.byref(d), n, n, 4096, have, C.byref(a), C.byref(b), C.byref(c))
+                assert st == 0, (n_max, n, L.hctr_last_error())
+                assert L.hctr_emb_dedup_view(C.byref(d), n, n, 4096, 4096, C.byref(a), C.byref(b), C.byref(c)) == -3
+    g = _group()
+    gsizes = [L.hctr_group_workspace_bytes(C.byref(g), 2, n) for n in points]
+    assert all(a <= b for a, b in zip(gsizes, gsizes[1:]))
