@@ -374,6 +374,27 @@ hctr_status hctr_cache_update(hctr_cache* cache, const int64_t* keys, const floa
                               size_t ws_bytes, void* stream);
 hctr_status hctr_cache_refresh(hctr_cache* cache, void* stream);
 
+/*
+ * hctr_cache_query for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments, same results and same effect
+ * on the cache as hctr_cache_query, without `ws` / `ws_bytes`.  The work arrays of the call live in
+ * a device array of HCTR_STATIC_SCRATCH_BYTES bytes inside the library, of which every GPU the
+ * library runs on holds one copy until the process ends.  The call allocates and frees nothing.
+ *   Limit   nnz <= HCTR_STATIC_MAX_KEYS; beyond it, or when the call's work arrays would not fit
+ *           (only possible for rows wider than 256 values, or with the small-call limit lowered and
+ *           rows wider than 128 values), HCTR_E_UNSUPPORTED and nothing is launched.
+ *   Sharing all calls on one GPU use that GPU's array: two calls of this function that overlap in
+ *           time on one GPU (different streams, different caches) race and give wrong results; calls
+ *           that follow each other on one stream are safe, the array needs no clearing in between.
+ *   Set-up  the first call on a device looks up the array's address (once per device, with that
+ *           device current); make that call outside graph capture.
+ */
+#define HCTR_STATIC_MAX_KEYS 8192
+#define HCTR_STATIC_SCRATCH_BYTES (8u << 20)
+hctr_status hctr_cache_query_static(hctr_cache* cache, int64_t batch, int32_t num_slots, const int64_t* keys,
+                                    const int64_t* offsets, int64_t nnz, int32_t insert_missing, float* out,
+                                    uint8_t* hit_mask, void* stream);
+
 /* stats[6] (host) = cumulative {keys queried, hits, misses, inserts, evictions, skipped inserts};
  * waits for the stream. */
 hctr_status hctr_cache_stats(hctr_cache* cache, void* stream, int64_t stats[6]);

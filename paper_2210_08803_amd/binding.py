@@ -99,6 +99,7 @@ def lib() -> C.CDLL:
         "hctr_cache_set_epoch_limit": (i32, [p, i64]),
         "hctr_cache_query": (i32, [p, i64, i32, p, p, i64, i32, p, p, p, sz, p]),
         "hctr_cache_query_async": (i32, [p, i64, i32, p, p, i64, i32, p, p, p, sz, p, p]),
+        "hctr_cache_query_static": (i32, [p, i64, i32, p, p, i64, i32, p, p, p]),
         "hctr_cache_insert": (i32, [p, p, i64, p, sz, p]),
         "hctr_cache_update": (i32, [p, p, p, i64, p, sz, p]),
         "hctr_cache_refresh": (i32, [p, p]),
@@ -123,7 +124,7 @@ EXPORTS = [
     "hctr_etc_workspace_bytes", "hctr_etc_create", "hctr_etc_load", "hctr_etc_dump", "hctr_etc_stats",
     "hctr_etc_destroy", "hctr_cache_storage_bytes",
     "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_set_small_call_limit", "hctr_cache_set_epoch_limit", "hctr_cache_query",
-    "hctr_cache_query_async", "hctr_cache_insert", "hctr_cache_update", "hctr_cache_refresh", "hctr_cache_stats",
+    "hctr_cache_query_async", "hctr_cache_query_static", "hctr_cache_insert", "hctr_cache_update", "hctr_cache_refresh", "hctr_cache_stats",
     "hctr_cache_state_view", "hctr_cache_destroy", "hctr_last_error",
 ]
 
@@ -490,6 +491,14 @@ class EmbeddingCache:
         _check(lib().hctr_cache_query(self.handle, batch, num_slots, _ptr(keys), _ptr(offsets), nnz,
                                       int(insert_missing), _ptr(out), _ptr(hit_mask), _ptr(ws), ws.numel(),
                                       _stream(stream)))
+        return out
+
+    def query_static(self, batch: int, num_slots: int, keys: torch.Tensor, out: torch.Tensor,
+                     offsets: Optional[torch.Tensor] = None, insert_missing: bool = True,
+                     hit_mask: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+        """hctr_cache_query_static: the query without a workspace argument; the caller brings `out`."""
+        _check(lib().hctr_cache_query_static(self.handle, batch, num_slots, _ptr(keys), _ptr(offsets), keys.numel(),
+                                             int(insert_missing), _ptr(out), _ptr(hit_mask), _stream(stream)))
         return out
 
     def query_async(self, batch: int, num_slots: int, keys: torch.Tensor, ready: torch.cuda.Event,

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhctr.so")
-SOURCES = ["runtime.cpp", "primitives.hip", "emb.hip", "hash.hip", "cache.hip", "etc.hip"]
+SOURCES = ["runtime.cpp", "primitives.hip", "emb.hip", "hash.hip", "cache.hip", "etc.hip", "noalloc.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -21,7 +21,7 @@ FLAGS = [
 
 
 def sources():
-    return [os.path.join(CSRC, s) for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
+    return [os.path.join(CSRC, s) for s in SOURCES]
 
 
 def needs_build() -> bool:

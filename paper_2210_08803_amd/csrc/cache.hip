@@ -786,6 +786,8 @@ static CacheWsLayout cache_ws_layout(const hctr_cache* c, int64_t nnz_max) {
   return L;
 }
 
+size_t cache_call_ws_bytes(const hctr_cache* c, int64_t nnz) { return cache_ws_layout(c, nnz).total; }
+
 #define HCTR_BY_WAYS(W, CALL)                    \
   switch (W) {                                   \
     case 1: CALL(1); break;                      \

@@ -109,4 +109,8 @@ hctr_status radix_sort_u64(const SortPlan& plan, const uint32_t* n_dev, uint64_t
                            uint32_t* hist, uint32_t* aux, bool aux_is_zero, hipStream_t stream,
                            bool first_hist_done = false);
 
+// Bytes of work arrays that one hctr_cache_query call with nnz keys uses, on the path that call
+// takes (cache.hip).
+size_t cache_call_ws_bytes(const hctr_cache* c, int64_t nnz);
+
 }  // namespace hctr
