@@ -24,7 +24,7 @@ EMPTY_TAG = np.uint64(0xFFFFFFFFFFFFFFFF)
 def build(force: bool = True) -> str:
     """Compile oracle.cpp with g++ (no GPU toolchain involved)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-Wall", "-Wextra",
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-pthread", "-Wall", "-Wextra",
                                _SRC, "-o", _LIB])
     return _LIB
 
@@ -44,6 +44,14 @@ def lib() -> C.CDLL:
         L.oracle_emb_forward.argtypes = [i32, i32, i32, p, i64, p, p, i64, p]
         L.oracle_emb_backward_sgd.restype = i64
         L.oracle_emb_backward_sgd.argtypes = [i32, i32, i32, p, i64, p, p, i64, p, f32, p, p]
+        L.oracle_hardware_threads.restype = i32
+        L.oracle_hardware_threads.argtypes = []
+        L.oracle_rows_direct_mt.restype = i64
+        L.oracle_rows_direct_mt.argtypes = [i32, i32, p, p, i64, p, p, p]
+        L.oracle_emb_forward_mt.restype = None
+        L.oracle_emb_forward_mt.argtypes = [i32, i32, i32, i32, p, i64, p, p, i64, p]
+        L.oracle_emb_backward_sgd_mt.restype = i64
+        L.oracle_emb_backward_sgd_mt.argtypes = [i32, i32, i32, i32, p, i64, p, p, i64, p, f32, p, p]
         L.oracle_emb_forward_mixed.restype = None
         L.oracle_emb_forward_mixed.argtypes = [i32, i32, i32, p, i64, p, p, i64, i32, p]
         L.oracle_emb_backward_sgd_mixed.restype = i64
@@ -110,9 +118,21 @@ def _dtype_code(table: np.ndarray) -> int:
     raise TypeError("table must be float32 or float16")
 
 
-def rows_direct(slot_base, slot_rows, keys, offsets=None, n_bags: Optional[int] = None) -> Tuple[np.ndarray, int]:
+def hardware_threads() -> int:
+    """Threads the all-cores variants may use: the cores this process is allowed to run on."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = int(lib().oracle_hardware_threads())
+    env = os.environ.get("OMP_NUM_THREADS", "")
+    return max(1, min(n, int(env)) if env.isdigit() and int(env) > 0 else n)
+
+
+def rows_direct(slot_base, slot_rows, keys, offsets=None, n_bags: Optional[int] = None,
+                threads: int = 1) -> Tuple[np.ndarray, int]:
     """Global row per key (direct-index mode) and the number of keys without a row.
-    Slot s owns rows [slot_base[s], slot_base[s] + slot_rows[s]) of the fused table."""
+    Slot s owns rows [slot_base[s], slot_base[s] + slot_rows[s]) of the fused table.
+    threads > 1: the all-cores variant (same result)."""
     slot_base, slot_rows, keys = _i64(slot_base), _i64(slot_rows), _i64(keys)
     S = len(slot_base)
     assert len(slot_rows) == S
@@ -122,14 +142,19 @@ def rows_direct(slot_base, slot_rows, keys, offsets=None, n_bags: Optional[int] 
     elif n_bags is None:
         n_bags = len(keys)
     rows = np.empty(len(keys), dtype=np.int64)
-    bad = lib().oracle_rows_direct(S, _ptr(slot_base), _ptr(slot_rows), n_bags, _ptr(keys),
-                                   _ptr(offsets), _ptr(rows))
+    if threads > 1:
+        assert n_bags % S == 0
+        bad = lib().oracle_rows_direct_mt(threads, S, _ptr(slot_base), _ptr(slot_rows), n_bags, _ptr(keys),
+                                          _ptr(offsets), _ptr(rows))
+    else:
+        bad = lib().oracle_rows_direct(S, _ptr(slot_base), _ptr(slot_rows), n_bags, _ptr(keys),
+                                       _ptr(offsets), _ptr(rows))
     return rows, int(bad)
 
 
 def emb_forward(table: np.ndarray, rows, offsets=None, combiner: int = SUM,
-                n_bags: Optional[int] = None) -> np.ndarray:
-    """Pooled output [n_bags, D] float32."""
+                n_bags: Optional[int] = None, threads: int = 1) -> np.ndarray:
+    """Pooled output [n_bags, D] float32.  threads > 1: the all-cores variant (same bits)."""
     assert table.ndim == 2 and table.flags.c_contiguous
     rows = _i64(rows)
     if offsets is not None:
@@ -138,14 +163,19 @@ def emb_forward(table: np.ndarray, rows, offsets=None, combiner: int = SUM,
     elif n_bags is None:
         n_bags = len(rows)
     out = np.empty((n_bags, table.shape[1]), dtype=np.float32)
-    lib().oracle_emb_forward(table.shape[1], _dtype_code(table), combiner, _ptr(table), table.shape[0],
-                             _ptr(rows), _ptr(offsets), n_bags, _ptr(out))
+    if threads > 1:
+        lib().oracle_emb_forward_mt(threads, table.shape[1], _dtype_code(table), combiner, _ptr(table),
+                                    table.shape[0], _ptr(rows), _ptr(offsets), n_bags, _ptr(out))
+    else:
+        lib().oracle_emb_forward(table.shape[1], _dtype_code(table), combiner, _ptr(table), table.shape[0],
+                                 _ptr(rows), _ptr(offsets), n_bags, _ptr(out))
     return out
 
 
 def emb_backward_sgd(table: np.ndarray, rows, dY: np.ndarray, lr: float, offsets=None,
-                     combiner: int = SUM, n_bags: Optional[int] = None):
-    """Updates `table` in place; returns (unique rows ascending, occurrence counts)."""
+                     combiner: int = SUM, n_bags: Optional[int] = None, threads: int = 1):
+    """Updates `table` in place; returns (unique rows ascending, occurrence counts).
+    threads > 1: the all-cores variant (same bits)."""
     assert table.ndim == 2 and table.flags.c_contiguous and table.flags.writeable
     rows = _i64(rows)
     if offsets is not None:
@@ -156,9 +186,14 @@ def emb_backward_sgd(table: np.ndarray, rows, dY: np.ndarray, lr: float, offsets
     dY = np.ascontiguousarray(dY, dtype=np.float32).reshape(n_bags, table.shape[1])
     uniq = np.empty(max(1, len(rows)), dtype=np.int64)
     cnt = np.empty(max(1, len(rows)), dtype=np.int64)
-    u = lib().oracle_emb_backward_sgd(table.shape[1], _dtype_code(table), combiner, _ptr(table),
-                                      table.shape[0], _ptr(rows), _ptr(offsets), n_bags, _ptr(dY),
-                                      float(np.float32(lr)), _ptr(uniq), _ptr(cnt))
+    if threads > 1:
+        u = lib().oracle_emb_backward_sgd_mt(threads, table.shape[1], _dtype_code(table), combiner, _ptr(table),
+                                             table.shape[0], _ptr(rows), _ptr(offsets), n_bags, _ptr(dY),
+                                             float(np.float32(lr)), _ptr(uniq), _ptr(cnt))
+    else:
+        u = lib().oracle_emb_backward_sgd(table.shape[1], _dtype_code(table), combiner, _ptr(table),
+                                          table.shape[0], _ptr(rows), _ptr(offsets), n_bags, _ptr(dY),
+                                          float(np.float32(lr)), _ptr(uniq), _ptr(cnt))
     return uniq[:u].copy(), cnt[:u].copy()
 
 

@@ -3,7 +3,9 @@
 // This file is the slow, plain definition of what the embedding layer computes, used by the tests,
 // by the smoke check and by the benchmark's CPU-baseline leg to judge the GPU library.  The
 // product path never calls it and shares no code with it.  Everything is a single-threaded loop
-// over std::unordered_map / std::vector, floating point accumulates in double and is rounded once.
+// over std::unordered_map / std::vector, floating point accumulates in double and is rounded once
+// (the *_mt functions run the same loops on several threads for the benchmark's CPU baseline and
+// are checked bit-equal to the single-threaded ones).
 //
 // What each function follows in the paper (Merlin HugeCTR, RecSys'22 talk abstract):
 //   * key -> row lookup in an "embedding hash", one table per slot, and the intra-slot reduction
@@ -23,7 +25,9 @@
 #include <cstdint>
 #include <cstring>
 #include <cmath>
+#include <thread>
 #include <unordered_map>
+#include <utility>
 #include <vector>
 #include <algorithm>
 
@@ -77,6 +81,42 @@ inline void store_elem(void* table, int dtype, int64_t idx, double v) {
 inline int64_t bag_begin(const int64_t* offsets, int64_t bag) { return offsets ? offsets[bag] : bag; }
 inline int64_t bag_end(const int64_t* offsets, int64_t bag) { return offsets ? offsets[bag + 1] : bag + 1; }
 
+// The backward + SGD loop over the rows r with r mod n_parts == part (all rows for n_parts = 1):
+// walks the occurrences in batch order, sums each owned row's gradient in double, applies the update
+// and lists the owned rows in ascending order with their occurrence counts.
+void backward_rows_of_part(int64_t part, int64_t n_parts, int32_t dim, int32_t dtype, int32_t combiner,
+                           void* table, int64_t total_rows, const int64_t* rows, const int64_t* offsets,
+                           int64_t n_bags, const float* dY, float lr,
+                           std::vector<std::pair<int64_t, int64_t>>* found) {
+  std::unordered_map<int64_t, std::vector<double>> grad;
+  std::unordered_map<int64_t, int64_t> occ;
+  for (int64_t bag = 0; bag < n_bags; ++bag) {
+    int64_t b0 = bag_begin(offsets, bag), b1 = bag_end(offsets, bag);
+    double w = (combiner == COMB_MEAN && b1 > b0) ? 1.0 / (double)(b1 - b0) : 1.0;
+    for (int64_t i = b0; i < b1; ++i) {
+      int64_t r = rows[i];
+      if (r < 0 || r >= total_rows) continue;
+      if (r % n_parts != part) continue;
+      std::vector<double>& g = grad[r];
+      if (g.empty()) g.assign(dim, 0.0);
+      for (int d = 0; d < dim; ++d) g[d] += w * (double)dY[bag * dim + d];
+      occ[r] += 1;
+    }
+  }
+  std::vector<int64_t> order;
+  order.reserve(grad.size());
+  for (auto& kv : grad) order.push_back(kv.first);
+  std::sort(order.begin(), order.end());
+  for (int64_t r : order) {
+    const std::vector<double>& g = grad[r];
+    for (int d = 0; d < dim; ++d) {
+      double t = load_elem(table, dtype, r * dim + d);
+      store_elem(table, dtype, r * dim + d, t - (double)lr * g[d]);
+    }
+    found->push_back({r, occ[r]});
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -129,33 +169,96 @@ int64_t oracle_emb_backward_sgd(int32_t dim, int32_t dtype, int32_t combiner, vo
                                 int64_t total_rows, const int64_t* rows, const int64_t* offsets,
                                 int64_t n_bags, const float* dY, float lr,
                                 int64_t* uniq_rows, int64_t* counts) {
-  std::unordered_map<int64_t, std::vector<double>> grad;
-  std::unordered_map<int64_t, int64_t> occ;
-  for (int64_t bag = 0; bag < n_bags; ++bag) {
-    int64_t b0 = bag_begin(offsets, bag), b1 = bag_end(offsets, bag);
-    double w = (combiner == COMB_MEAN && b1 > b0) ? 1.0 / (double)(b1 - b0) : 1.0;
-    for (int64_t i = b0; i < b1; ++i) {
-      int64_t r = rows[i];
-      if (r < 0 || r >= total_rows) continue;
-      std::vector<double>& g = grad[r];
-      if (g.empty()) g.assign(dim, 0.0);
-      for (int d = 0; d < dim; ++d) g[d] += w * (double)dY[bag * dim + d];
-      occ[r] += 1;
-    }
-  }
-  std::vector<int64_t> order;
-  order.reserve(grad.size());
-  for (auto& kv : grad) order.push_back(kv.first);
-  std::sort(order.begin(), order.end());
+  std::vector<std::pair<int64_t, int64_t>> found;
+  backward_rows_of_part(0, 1, dim, dtype, combiner, table, total_rows, rows, offsets, n_bags, dY, lr, &found);
   int64_t u = 0;
-  for (int64_t r : order) {
-    const std::vector<double>& g = grad[r];
-    for (int d = 0; d < dim; ++d) {
-      double t = load_elem(table, dtype, r * dim + d);
-      store_elem(table, dtype, r * dim + d, t - (double)lr * g[d]);
-    }
-    if (uniq_rows) uniq_rows[u] = r;
-    if (counts) counts[u] = occ[r];
+  for (auto& rc : found) {
+    if (uniq_rows) uniq_rows[u] = rc.first;
+    if (counts) counts[u] = rc.second;
+    ++u;
+  }
+  return u;
+}
+
+// ---------------------------------------------------------------------------------------------
+// All-cores variants of the three functions above, for the benchmark's CPU baseline: the same loops
+// on `threads` std::thread workers.  Forward and key -> row: bags are independent, a worker takes a
+// contiguous run of whole samples and calls the single-threaded function on it.  Backward: rows are
+// independent, worker t owns the rows with r mod threads == t, walks all occurrences in batch order
+// and handles only its own, so every row sees the additions of the single-threaded loop in the same
+// order: results are bit-identical (tests/test_oracle_mt.py).
+// ---------------------------------------------------------------------------------------------
+int32_t oracle_hardware_threads(void) {
+  unsigned n = std::thread::hardware_concurrency();
+  return n ? (int32_t)n : 1;
+}
+
+// [first, last) samples of worker t when `batch` samples are split over `threads` workers
+static void samples_of(int64_t batch, int threads, int t, int64_t* first, int64_t* last) {
+  int64_t per = (batch + threads - 1) / threads;
+  *first = std::min(batch, per * t);
+  *last = std::min(batch, per * (t + 1));
+}
+
+int64_t oracle_rows_direct_mt(int32_t threads, int32_t num_slots, const int64_t* slot_base,
+                              const int64_t* slot_rows, int64_t n_bags, const int64_t* keys,
+                              const int64_t* offsets, int64_t* rows) {
+  if (threads < 1) threads = 1;
+  const int64_t batch = n_bags / num_slots;   // whole samples, so that a worker's bags start at slot 0
+  std::vector<int64_t> bad(threads, 0);
+  std::vector<std::thread> pool;
+  for (int t = 0; t < threads; ++t) {
+    pool.emplace_back([&, t]() {
+      int64_t s0, s1;
+      samples_of(batch, threads, t, &s0, &s1);
+      const int64_t g0 = s0 * num_slots, g1 = s1 * num_slots;
+      if (offsets) bad[t] = oracle_rows_direct(num_slots, slot_base, slot_rows, g1 - g0, keys, offsets + g0, rows);
+      else bad[t] = oracle_rows_direct(num_slots, slot_base, slot_rows, g1 - g0, keys + g0, nullptr, rows + g0);
+    });
+  }
+  for (auto& th : pool) th.join();
+  int64_t total = 0;
+  for (int64_t b : bad) total += b;
+  return total;
+}
+
+void oracle_emb_forward_mt(int32_t threads, int32_t dim, int32_t dtype, int32_t combiner, const void* table,
+                           int64_t total_rows, const int64_t* rows, const int64_t* offsets,
+                           int64_t n_bags, float* out) {
+  if (threads < 1) threads = 1;
+  std::vector<std::thread> pool;
+  for (int t = 0; t < threads; ++t) {
+    pool.emplace_back([&, t]() {
+      int64_t g0, g1;
+      samples_of(n_bags, threads, t, &g0, &g1);
+      if (offsets) oracle_emb_forward(dim, dtype, combiner, table, total_rows, rows, offsets + g0, g1 - g0, out + g0 * dim);
+      else oracle_emb_forward(dim, dtype, combiner, table, total_rows, rows + g0, nullptr, g1 - g0, out + g0 * dim);
+    });
+  }
+  for (auto& th : pool) th.join();
+}
+
+int64_t oracle_emb_backward_sgd_mt(int32_t threads, int32_t dim, int32_t dtype, int32_t combiner, void* table,
+                                   int64_t total_rows, const int64_t* rows, const int64_t* offsets,
+                                   int64_t n_bags, const float* dY, float lr,
+                                   int64_t* uniq_rows, int64_t* counts) {
+  if (threads < 1) threads = 1;
+  std::vector<std::vector<std::pair<int64_t, int64_t>>> found(threads);
+  std::vector<std::thread> pool;
+  for (int t = 0; t < threads; ++t) {
+    pool.emplace_back([&, t]() {
+      backward_rows_of_part(t, threads, dim, dtype, combiner, table, total_rows, rows, offsets, n_bags, dY, lr,
+                            &found[t]);
+    });
+  }
+  for (auto& th : pool) th.join();
+  std::vector<std::pair<int64_t, int64_t>> all;
+  for (auto& f : found) all.insert(all.end(), f.begin(), f.end());
+  std::sort(all.begin(), all.end());
+  int64_t u = 0;
+  for (auto& rc : all) {
+    if (uniq_rows) uniq_rows[u] = rc.first;
+    if (counts) counts[u] = rc.second;
     ++u;
   }
   return u;
