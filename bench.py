@@ -38,33 +38,106 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(table_rows, base, keys_batches, seed, budget_s=20.0):
-    """The oracle, as it stands, on the host: forward + backward over whole batches of the same
-    workload.  The 85 GB table is not copied to the host: the rows a batch touches are generated
-    into a compact table (same values, same key -> row structure), which keeps the arithmetic and
-    the access pattern per key but makes the host working set smaller than the real one."""
+def host_copy_of(table, log_every_s=5.0):
+    """The device table copied into ordinary host memory, a slab at a time."""
+    total, D = table.shape
+    host = np.empty((total, D), dtype=np.float32)
+    slab = 1 << 22                                             # 2 GiB of fp32 rows of 128
+    t_last = time.time()
+    for r0 in range(0, total, slab):
+        r1 = min(total, r0 + slab)
+        torch.from_numpy(host[r0:r1]).copy_(table[r0:r1])
+        if time.time() - t_last > log_every_s:
+            log(f"  host copy of the table: {r1 / total:.0%}")
+            t_last = time.time()
+    return host
+
+
+def cpu_baseline(table, table_rows, base, keys_batches, seed, alpha, budget_s=25.0):
+    """The oracle's all-cores variant (bit-equal to the single-threaded one, tests/test_oracle_mt.py)
+    on the host: key -> row, forward and backward + SGD over whole batches of the same workload.
+    The host table is dense, the device table copied to ordinary host memory, when it fits in half
+    of the host's RAM; otherwise every table is scaled by one factor (stated in `sample`) and the
+    keys are drawn again for the scaled tables.  Median over at least 5 timed batches."""
     import oracle
+    import psutil
     S = len(table_rows)
-    done_keys, spent, batches = 0, 0.0, 0
-    for keys in keys_batches:
-        k = keys.numpy()
-        rows_global = (k.reshape(-1, S) + base[None, :]).reshape(-1)
-        uniq, inv = np.unique(rows_global, return_inverse=True)
-        compact = datagen.table_rows_at(seed, torch.from_numpy(uniq), DIM, torch.float32).numpy()
-        dY = datagen.normal_grads(seed, 1000 + batches, len(k) * DIM).numpy().reshape(len(k), DIM)
-        comp_keys = inv.astype(np.int64)
+    threads = oracle.hardware_threads()
+    ram = psutil.virtual_memory().total
+    need = int(table.shape[0]) * DIM * 4
+    t0 = time.time()
+    if need <= 0.5 * ram:
+        host = host_copy_of(table)
+        rows_h, base_h, batches, note = list(table_rows), base, [k.numpy() for k in keys_batches], "dense host copy of the full table"
+    else:
+        f = 0.5 * ram / need
+        f = float(f"{f:.1g}") if float(f"{f:.1g}") <= f else float(f"{f:.1g}") / 2
+        rows_h = datagen.scaled_table_rows(f)
+        ro = datagen.row_offsets(rows_h)
+        base_h, total_h = ro[:-1].copy(), int(ro[-1])
+        host = np.empty((total_h, DIM), dtype=np.float32)
+        for r0 in range(0, total_h, 1 << 21):
+            r1 = min(total_h, r0 + (1 << 21))
+            host[r0:r1] = datagen.table_rows_at(seed, torch.arange(r0, r1), DIM, torch.float32).numpy()
+        smp = datagen.make_samplers(rows_h, alpha) if alpha > 0 else None
+        batches = [datagen.onehot_keys(seed, b, rows_h, BATCH, alpha, samplers=smp).numpy() for b in range(len(keys_batches))]
+        note = f"every table scaled x{f:g} to fit half of the host's {ram / 2**30:.0f} GiB"
+    log(f"cpu baseline: host table {host.shape[0]} x {DIM} ready in {time.time() - t0:.1f}s, {threads} threads")
+    times = []
+    spent = 0.0
+    for b, k in enumerate(batches):
+        dY = datagen.normal_grads(seed, 1000 + b, len(k) * DIM).numpy().reshape(len(k), DIM)
         t0 = time.perf_counter()
-        rows, _ = oracle.rows_direct([0] * S, [len(uniq)] * S, comp_keys)
-        oracle.emb_forward(compact, rows)
-        oracle.emb_backward_sgd(compact, rows, dY, LR)
-        spent += time.perf_counter() - t0
-        done_keys += len(k)
-        batches += 1
-        if spent > budget_s:
+        rows, _ = oracle.rows_direct(base_h, rows_h, k, threads=threads)
+        oracle.emb_forward(host, rows, threads=threads)
+        oracle.emb_backward_sgd(host, rows, dY, LR, threads=threads)
+        times.append(time.perf_counter() - t0)
+        spent += times[-1]
+        if spent > budget_s and len(times) >= 5:
             break
-    return {"value": done_keys / spent, "unit": "keys/s", "cores": 1, "kind": "oracle",
-            "sample": f"{batches} full batch(es) of {len(keys_batches[0])} keys, forward+backward, "
-                      f"table compacted to the rows each batch touches"}
+    nk = len(batches[0])
+    return {"value": nk / float(np.median(times)), "unit": "keys/s", "cores": threads, "kind": "oracle",
+            "sample": f"{len(times)} full batches of {nk} keys, key -> row + forward + backward/SGD each, median; "
+                      f"{note}; all-cores variant of the oracle",
+            "batch_s_median": float(np.median(times)), "batch_s_min": float(min(times))}
+
+
+def parity_on_timed_batch(layer, table, base, S, keys_cpu, keys_dev, dY, out, ws):
+    """One more step on a batch, gradient buffer, output buffer and workspace of the timed region,
+    checked against the oracle: pooled rows and dedup result exactly, updated rows within
+    1e-5 * max(|ref|, sum|terms| / 8).  The oracle works on the rows the batch touches, read from the
+    device table as it stands before the step.  Raises on any difference."""
+    import oracle
+    threads = oracle.hardware_threads()
+    k = keys_cpu.numpy()
+    nnz = len(k)
+    g_rows = (k.reshape(-1, S) + base[None, :]).reshape(-1)
+    uniq, inv = np.unique(g_rows, return_inverse=True)
+    u_dev = torch.from_numpy(uniq).to(table.device)
+    before = table[u_dev].cpu().numpy()
+    dY_h = dY.cpu().numpy().reshape(nnz, DIM)
+    ref_out = oracle.emb_forward(before, inv, threads=threads)
+    ref_tab = before.copy()
+    o_uniq, o_cnt = oracle.emb_backward_sgd(ref_tab, inv, dY_h, LR, threads=threads)
+    g_abs = np.zeros(before.shape, dtype=np.float32)
+    oracle.emb_backward_sgd(g_abs, inv, np.abs(dY_h), 1.0, threads=threads)
+    mag = np.abs(before.astype(np.float64)) + float(np.float32(LR)) * np.abs(g_abs.astype(np.float64))   # sum of |terms|
+
+    layer.forward(BATCH, keys_dev, out=out, ws=ws)
+    layer.backward_sgd(BATCH, keys_dev, dY, LR, ws=ws)
+    torch.cuda.synchronize()
+    got_out = out.cpu().numpy().reshape(nnz, DIM)
+    assert np.array_equal(got_out.view(np.uint32), ref_out.view(np.uint32)), "parity: pooled output differs from the oracle"
+    d_rows, d_cnt = layer.dedup_result(BATCH, nnz, ws=ws)
+    assert np.array_equal(d_rows.cpu().numpy(), uniq), "parity: distinct rows differ from the oracle"
+    assert np.array_equal(d_cnt.cpu().numpy(), o_cnt) and np.array_equal(o_uniq, np.arange(len(uniq))), \
+        "parity: occurrence counts differ from the oracle"
+    got = table[u_dev].cpu().numpy().astype(np.float64)
+    ref64 = ref_tab.astype(np.float64)
+    err = np.abs(got - ref64)
+    tol = 1e-5 * np.maximum(np.abs(ref64), mag / 8.0)
+    assert (err <= tol).all(), f"parity: updated rows differ from the oracle, max err {err.max():.3e}"
+    return {"keys": int(nnz), "distinct_rows": int(len(uniq)), "max_abs_err_updated_rows": float(err.max())}
 
 
 def main():
@@ -240,6 +313,19 @@ def main():
                           "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
                           "step_ms_median": float(np.median(step_ms)), "data": "synthetic"}), flush=True)
         return
+    # parity re-asserted on timed inputs: the batch, gradient and buffers the next step would have used
+    j = (args.warmup + args.steps) % N_KEY_BATCHES
+    parity = parity_on_timed_batch(layer, table, base, S, keys_cpu[j], keys[j], dYs[j % 2], out, ws)
+    log(f"parity on a timed batch: {parity}")
+    # what the same chip copies at: a device copy of the pooled-output size (read + write), for scale
+    cp = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for it in range(6):
+        if it == 1:
+            cp[0].record(stream)
+        out.copy_(dYs[0])
+    cp[1].record(stream)
+    torch.cuda.synchronize()
+    copy_gbs = 2 * out.numel() * 4 * 5 / (cp[0].elapsed_time(cp[1]) * 1e-3) / 1e9
     fwd_ms = np.array([e[0].elapsed_time(e[1]) for e in evs])
     bwd_ms = np.array([e[1].elapsed_time(e[2]) for e in evs])
     dedup_ms = None if args.schedule == "serial" else np.array([e[3].elapsed_time(e[4]) for e in evs])
@@ -254,13 +340,21 @@ def main():
     fwd_bytes = nnz * (8 + DIM * 4 + DIM * 4)
     fwd_s = float(fwd_ms.mean()) * 1e-3
     achieved = fwd_bytes / fwd_s / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "fwd_onehot_dlrm_traffic.json")
-    if os.path.exists(tpath) and args.scale == 1.0:
+    # HBM bytes per launch by the profiler's counters: a stored figure from profiles/ (the two
+    # rocprofv3 --pmc runs cannot happen inside this process), stamped with the commit it was taken on.
+    traffic, prof = None, {}
+    tpath = os.path.join(ROOT, "profiles", "dlrm_onehot_hbm_traffic.json")
+    if os.path.exists(tpath) and args.scale == 1.0 and args.alpha == ALPHA:
         try:
-            traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+            prof = json.load(open(tpath))
+            traffic = prof["kernels"]["fwd_onehot"]["traffic_bytes_per_launch"]
         except Exception:
-            traffic = None
+            traffic, prof = None, {}
+    step_traffic = prof.get("step_traffic_bytes")
+    # the stored figure belongs to the kernels as they were when it was taken
+    import hashlib
+    src = os.path.join(ROOT, "paper_2210_08803_amd", "csrc", "emb.hip")
+    traffic_current = bool(prof) and hashlib.sha256(open(src, "rb").read()).hexdigest()[:16] == prof.get("emb_hip_sha16")
     U = float(np.mean(uniq_per_batch))
     bwd_bytes = nnz * 8 + nnz * DIM * 4 + U * 2 * DIM * 4   # keys, dY gather, row read-modify-write (sort excluded)
 
@@ -273,8 +367,22 @@ def main():
                                "Zipf %g, sum, fwd + dedup/segmented-reduce bwd + SGD%s"
                                % (total, args.alpha, "" if args.scale == 1.0 else f" (tables scaled x{args.scale})"),
                    "batch": BATCH, "slots": S, "dim": DIM, "keys_per_step": nnz, "distinct_rows_per_step": int(U)},
+        "parity_checked": True, "parity": parity,
         "roofline": {"bound": "hbm", "kernel": "fwd_onehot<float,float,32,4>", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     # achieved / frac count ALGORITHMIC bytes (every key's row, also when L2 serves it);
+                     # measured_* count the bytes the profiler saw cross the HBM interface
+                     "measured_GBs": None if traffic is None else traffic / fwd_s / 1e9,
+                     "measured_frac": None if traffic is None else traffic / fwd_s / 1e9 / HBM_PEAK_GBS,
+                     "traffic_source": None if traffic is None else
+                     {"file": "profiles/dlrm_onehot_hbm_traffic.json", "kind": "stored rocprofv3 --pmc figure",
+                      "measured_on_commit": prof.get("commit"),
+                      "kernel_source_unchanged_since": traffic_current},
+                     "device_copy_GBs": copy_gbs,
+                     "step_traffic": step_traffic,
+                     "step_measured_GBs": None if step_traffic is None else step_traffic / (elapsed / args.steps) / 1e9,
+                     "step_measured_frac": None if step_traffic is None else
+                     step_traffic / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": fwd_bytes,
                      # the same with every distinct row read once only (what no cache could go below)
                      "compulsory_bytes_per_launch": nnz * (8 + DIM * 4) + int(U) * DIM * 4,
@@ -292,9 +400,9 @@ def main():
                    "fwd_bwd_logical_GBs": (fwd_bytes + bwd_bytes) / (elapsed / args.steps) / 1e9},
     }
     if not args.no_cpu_baseline:
-        del table
-        torch.cuda.empty_cache()
-        res["cpu_baseline"] = cpu_baseline(table_rows, base, keys_cpu, args.seed)
+        del layer
+        res["cpu_baseline"] = cpu_baseline(table, table_rows, base, keys_cpu, args.seed, args.alpha)
+        res["gpu_over_cpu"] = value / res["cpu_baseline"]["value"]
     print(json.dumps(res), flush=True)
 
 
