@@ -96,6 +96,10 @@ def lib() -> C.CDLL:
         L.oracle_etc_dump.argtypes = [p, i32]
         L.oracle_etc_stats.restype = None
         L.oracle_etc_stats.argtypes = [p, p]
+        L.oracle_cache_query_hits.restype = i64
+        L.oracle_cache_query_hits.argtypes = [p, i64, p, p, i64, i64, p, p, p]
+        L.oracle_cache_query_complete.restype = None
+        L.oracle_cache_query_complete.argtypes = [p, i64, p, p, i64, i64, p, i32, p]
         L.oracle_cache_query.restype = None
         L.oracle_cache_query.argtypes = [p, i64, p, p, i64, i64, i32, p, p]
         _lib = L
@@ -337,6 +341,39 @@ class Cache:
         lib().oracle_cache_query(self._c, n_bags, _ptr(keys), _ptr(offsets), hot, nnz,
                                  int(bool(insert_missing)), _ptr(out), _ptr(hit))
         return out, hit
+
+    def _shape(self, keys, n_bags, offsets):
+        keys = _i64(keys)
+        nnz, hot = len(keys), 0
+        if offsets is not None:
+            offsets = _i64(offsets)
+            assert len(offsets) == n_bags + 1 and offsets[-1] == nnz
+        else:
+            assert n_bags > 0 and nnz % n_bags == 0
+            hot = nnz // n_bags
+        return keys, offsets, nnz, hot
+
+    def query_hits(self, keys, n_bags: int, offsets=None):
+        """Phase 1 of a two-phase query: (out [n_bags, D] pooled over the hits only, hit_mask [nnz],
+        positions of the missing keys inside the host table, ascending)."""
+        keys, offsets, nnz, hot = self._shape(keys, n_bags, offsets)
+        out = np.empty((n_bags, self.dim), dtype=np.float32)
+        hit = np.zeros(nnz, dtype=np.uint8)
+        miss = np.empty(max(1, nnz), dtype=np.int64)
+        n = lib().oracle_cache_query_hits(self._c, n_bags, _ptr(keys), _ptr(offsets), hot, nnz, _ptr(out), _ptr(hit),
+                                          _ptr(miss))
+        return out, hit, miss[:n].copy()
+
+    def query_complete(self, keys, n_bags: int, hit_mask: np.ndarray, out: np.ndarray, offsets=None,
+                       insert_missing: bool = True) -> np.ndarray:
+        """Phase 2: adds the missing keys' host rows into `out` (in place) and inserts them."""
+        keys, offsets, nnz, hot = self._shape(keys, n_bags, offsets)
+        assert out.dtype == np.float32 and out.shape == (n_bags, self.dim) and out.flags.c_contiguous
+        hit_mask = np.ascontiguousarray(hit_mask, dtype=np.uint8)
+        assert len(hit_mask) == nnz
+        lib().oracle_cache_query_complete(self._c, n_bags, _ptr(keys), _ptr(offsets), hot, nnz, _ptr(hit_mask),
+                                          int(bool(insert_missing)), _ptr(out))
+        return out
 
     def insert(self, keys) -> None:
         keys = _i64(keys)

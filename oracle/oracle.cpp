@@ -489,6 +489,40 @@ void oracle_cache_state(const oracle_cache* c, uint64_t* tags, uint32_t* stamps,
   if (data) std::memcpy(data, c->data.data(), c->data.size() * sizeof(float));
 }
 
+// Step 4 of a query: the distinct missing keys (where[i] < 0, key inside the host table), in
+// first-appearance order, each into the lowest-index empty way of its set, else over the way with
+// the smallest stamp among those not touched in this call (ties: lowest way), else skipped.
+static void cache_insert_missing(oracle_cache* c, const int64_t* keys, int64_t nnz,
+                                 const std::vector<int64_t>& where) {
+  const int W = c->ways, D = c->dim;
+  std::unordered_map<uint64_t, char> placed;      // missing keys already handled in this call
+  for (int64_t i = 0; i < nnz; ++i) {
+    if (where[i] >= 0 || keys[i] < 0 || keys[i] >= c->host_rows) continue;
+    uint64_t k = (uint64_t)keys[i];
+    if (!placed.emplace(k, 1).second) continue;
+    int64_t set = cache_set_of(k, c->num_sets);
+    int victim = -1;
+    for (int w = 0; w < W && victim < 0; ++w)
+      if (c->tag[set * W + w] == kEmptyTag) victim = w;
+    bool evict = false;
+    if (victim < 0) {
+      uint32_t best = 0;
+      for (int w = 0; w < W; ++w) {
+        uint32_t st = c->stamp[set * W + w];
+        if (st < c->epoch && (victim < 0 || st < best)) { victim = w; best = st; }
+      }
+      evict = victim >= 0;
+    }
+    if (victim < 0) { c->stats[5] += 1; continue; }
+    int64_t line = set * W + victim;
+    c->tag[line] = k;
+    c->stamp[line] = c->epoch;
+    std::memcpy(&c->data[line * D], &c->host_table[(int64_t)k * D], sizeof(float) * D);
+    c->stats[3] += 1;
+    if (evict) c->stats[4] += 1;
+  }
+}
+
 // One query call.  Every key is classified against the cache as it was when the call began (all
 // occurrences of a key get the same answer).  A hit reads the cached copy and refreshes its stamp;
 // a miss reads the host table (key = host row; out-of-range keys read as a zero row and are never
@@ -533,33 +567,85 @@ void oracle_cache_query(oracle_cache* c, int64_t n_bags, const int64_t* keys,
     }
     for (int d = 0; d < D; ++d) out[bag * D + d] = (float)acc[d];
   }
-  if (!insert_missing) return;
-  std::unordered_map<uint64_t, char> placed;      // missing keys already handled in this call
-  for (int64_t i = 0; i < nnz; ++i) {
-    if (where[i] >= 0 || keys[i] < 0 || keys[i] >= c->host_rows) continue;
-    uint64_t k = (uint64_t)keys[i];
-    if (!placed.emplace(k, 1).second) continue;
-    int64_t set = cache_set_of(k, c->num_sets);
-    int victim = -1;
-    for (int w = 0; w < W && victim < 0; ++w)
-      if (c->tag[set * W + w] == kEmptyTag) victim = w;
-    bool evict = false;
-    if (victim < 0) {
-      uint32_t best = 0;
-      for (int w = 0; w < W; ++w) {
-        uint32_t st = c->stamp[set * W + w];
-        if (st < c->epoch && (victim < 0 || st < best)) { victim = w; best = st; }
-      }
-      evict = victim >= 0;
-    }
-    if (victim < 0) { c->stats[5] += 1; continue; }
-    int64_t line = set * W + victim;
-    c->tag[line] = k;
-    c->stamp[line] = c->epoch;
-    std::memcpy(&c->data[line * D], &c->host_table[(int64_t)k * D], sizeof(float) * D);
-    c->stats[3] += 1;
-    if (evict) c->stats[4] += 1;
+  if (insert_missing) cache_insert_missing(c, keys, nnz, where);
+}
+
+// Query in two phases, for a consumer that starts on the hits while the missing rows are still on
+// their way across the host link (section 3: parameter migration overlapped with the dense network;
+// "embedding inference cache": dynamic insertion, asynchronous mechanisms).
+//
+// Phase 1, "hits": one call (epoch) that classifies every key against the cache as it stands, stamps
+// and counts the hits exactly as oracle_cache_query does, and pools ONLY the hits: a missing key adds
+// nothing yet.  miss_pos receives the positions whose key is missing and lies inside the host table,
+// in ascending order; the return value is their number.
+int64_t oracle_cache_query_hits(oracle_cache* c, int64_t n_bags, const int64_t* keys,
+                                const int64_t* offsets, int64_t hotness, int64_t nnz, float* out,
+                                uint8_t* hit_mask, int64_t* miss_pos) {
+  (void)nnz;
+  if (c->epoch >= c->epoch_limit) {
+    const uint32_t by = c->epoch_limit / 2;
+    for (uint32_t& st : c->stamp) st = st > by ? st - by : 0u;
+    c->epoch -= by;
   }
+  c->epoch += 1;
+  const int W = c->ways, D = c->dim;
+  int64_t n_missing = 0;
+  std::vector<double> acc(D);
+  for (int64_t bag = 0; bag < n_bags; ++bag) {
+    std::fill(acc.begin(), acc.end(), 0.0);
+    int64_t b0 = offsets ? offsets[bag] : bag * hotness;
+    int64_t b1 = offsets ? offsets[bag + 1] : (bag + 1) * hotness;
+    for (int64_t i = b0; i < b1; ++i) {
+      int64_t line = -1;
+      if (keys[i] >= 0) {
+        int64_t set = cache_set_of((uint64_t)keys[i], c->num_sets);
+        for (int w = 0; w < W && line < 0; ++w)
+          if (c->tag[set * W + w] == (uint64_t)keys[i]) line = set * W + w;
+      }
+      c->stats[0] += 1;
+      if (line >= 0) {
+        c->stats[1] += 1;
+        c->stamp[line] = c->epoch;                // tags do not change in this phase: order is free
+        hit_mask[i] = 1;
+        for (int d = 0; d < D; ++d) acc[d] += (double)c->data[line * D + d];
+      } else {
+        c->stats[2] += 1;
+        hit_mask[i] = 0;
+        if (keys[i] >= 0 && keys[i] < c->host_rows) miss_pos[n_missing++] = i;
+      }
+    }
+    for (int d = 0; d < D; ++d) out[bag * D + d] = (float)acc[d];
+  }
+  return n_missing;
+}
+
+// Phase 2, "complete": follows the hits call on the same keys with nothing in between.  Every bag
+// that holds missing keys gets their host rows, summed in double, added to what phase 1 left in
+// out[bag, :] (one rounding to fp32); bags without missing keys keep their bits.  With
+// insert_missing the distinct missing keys are then inserted under the epoch of phase 1, exactly
+// as by oracle_cache_query.  hit_mask is phase 1's.
+void oracle_cache_query_complete(oracle_cache* c, int64_t n_bags, const int64_t* keys,
+                                 const int64_t* offsets, int64_t hotness, int64_t nnz,
+                                 const uint8_t* hit_mask, int32_t insert_missing, float* out) {
+  const int D = c->dim;
+  std::vector<double> acc(D);
+  for (int64_t bag = 0; bag < n_bags; ++bag) {
+    std::fill(acc.begin(), acc.end(), 0.0);
+    int64_t b0 = offsets ? offsets[bag] : bag * hotness;
+    int64_t b1 = offsets ? offsets[bag + 1] : (bag + 1) * hotness;
+    bool any = false;
+    for (int64_t i = b0; i < b1; ++i) {
+      if (hit_mask[i] || keys[i] < 0 || keys[i] >= c->host_rows) continue;
+      any = true;
+      for (int d = 0; d < D; ++d) acc[d] += (double)c->host_table[keys[i] * D + d];
+    }
+    if (any)
+      for (int d = 0; d < D; ++d) out[bag * D + d] = (float)((double)out[bag * D + d] + acc[d]);
+  }
+  if (!insert_missing) return;
+  std::vector<int64_t> where(nnz);
+  for (int64_t i = 0; i < nnz; ++i) where[i] = hit_mask[i] ? 0 : -1;   // only the sign is read
+  cache_insert_missing(c, keys, nnz, where);
 }
 
 // Manipulation operators of the cache (section 3, "embedding inference cache": query and

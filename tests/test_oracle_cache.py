@@ -230,3 +230,87 @@ def test_epoch_limit_leaves_classical_lru_intact():
         assert c.epoch <= 64 and stamps.max() <= c.epoch
         top = max(top, c.epoch)
     assert top == 64
+
+
+# ---- two-phase query: hits first, missing rows added afterwards (oracle_cache_query_hits / _complete)
+
+def _traffic(host_rows, n_calls, n_bags, hot, seed):
+    rng = np.random.default_rng(seed)
+    for it in range(n_calls):
+        keys = np.minimum(rng.zipf(1.3, n_bags * hot) - 1, host_rows + 2).astype(np.int64)   # some outside the table
+        keys = (keys * 7919) % (host_rows + 3)
+        if it % 3 == 1:
+            keys[::11] = -4
+        yield it, keys
+
+
+def test_two_phase_query_leaves_the_state_of_the_single_call():
+    """Hits then complete = the one-call query, which the trace and the textbook cases above pin:
+    same hit mask, tags, stamps, cached rows, statistics and call count after every call, with and
+    without insertion, fixed hotness and CSR bags, also across the lowering of the call count."""
+    host_rows, dim = 400, 8
+    ht = host_table(host_rows, dim)
+    for limit in (None, 7):
+        one, two = oracle.Cache(6, 4, ht), oracle.Cache(6, 4, ht)
+        if limit:
+            one.set_epoch_limit(limit)
+            two.set_epoch_limit(limit)
+        for it, keys in _traffic(host_rows, 30, 12, 5, 3):
+            insert = it % 4 != 2
+            offsets = None
+            if it % 5 == 4:   # ragged bags, an empty one among them
+                cuts = np.sort(np.random.default_rng(it).integers(0, len(keys) + 1, 11))
+                offsets = np.concatenate([[0], cuts, [len(keys)]]).astype(np.int64)
+            ref_out, ref_hit = one.query(keys, 12, offsets=offsets, insert_missing=insert)
+            out, hit, miss = two.query_hits(keys, 12, offsets=offsets)
+            assert np.array_equal(hit, ref_hit)
+            assert np.array_equal(miss, np.flatnonzero((hit == 0) & (keys >= 0) & (keys < host_rows)))
+            assert one.stats[:3].tolist() == two.stats[:3].tolist() and one.epoch == two.epoch
+            two.query_complete(keys, 12, hit, out, offsets=offsets, insert_missing=insert)
+            for a, b in zip(one.state(with_data=True), two.state(with_data=True)):
+                assert np.array_equal(a, b), f"call {it}"
+            assert one.stats.tolist() == two.stats.tolist()
+            # rows of this table are multiples of 1/128 below 2^9: every sum is exact in fp32, so the
+            # two-phase result must equal the one-call result bit for bit
+            assert np.array_equal(out, ref_out), f"call {it}"
+
+
+def test_two_phase_outputs_are_the_sums_over_hits_and_over_misses():
+    host_rows, dim, n_bags, hot = 300, 4, 9, 6
+    rng = np.random.default_rng(5)
+    ht = rng.standard_normal((host_rows, dim)).astype(np.float32)
+    c = oracle.Cache(5, 2, ht)
+    for it, keys in _traffic(host_rows, 12, n_bags, hot, 9):
+        out, hit, miss = c.query_hits(keys, n_bags)
+        valid = (keys >= 0) & (keys < host_rows)
+        rows = np.where(valid[:, None], ht[np.clip(keys, 0, host_rows - 1)].astype(np.float64), 0.0)
+        hits_sum = (rows * (hit == 1)[:, None]).reshape(n_bags, hot, dim).sum(1)
+        assert np.array_equal(out, hits_sum.astype(np.float32))           # cached rows are copies of host rows
+        miss_sum = (rows * (hit == 0)[:, None]).reshape(n_bags, hot, dim).sum(1)
+        phase1 = out.copy()
+        c.query_complete(keys, n_bags, hit, out, insert_missing=(it % 2 == 0))
+        want = (phase1.astype(np.float64) + miss_sum).astype(np.float32)
+        has_miss = ((hit == 0) & valid).reshape(n_bags, hot).any(1)
+        assert np.array_equal(out[has_miss], want[has_miss])
+        assert np.array_equal(out[~has_miss].view(np.uint32), phase1[~has_miss].view(np.uint32))   # untouched bits
+        full = (hits_sum + miss_sum)
+        assert np.all(np.abs(out - full) <= 2.0 ** -23 * np.abs(rows).reshape(n_bags, hot, dim).sum(1) + 1e-30)
+
+
+def test_two_phase_extremes():
+    ht = host_table(50, 4)
+    c = oracle.Cache(8, 4, ht)
+    keys = np.arange(20, dtype=np.int64)
+    out, hit, miss = c.query_hits(keys, 5)                    # cold cache: nothing hits
+    assert not out.any() and not hit.any() and np.array_equal(miss, np.arange(20))
+    c.query_complete(keys, 5, hit, out, insert_missing=True)
+    assert np.array_equal(out, ht[keys].reshape(5, 4, 4).sum(1))
+    assert c.stats.tolist() == [20, 0, 20, 20, 0, 0]
+    out, hit, miss = c.query_hits(keys, 5)                    # warm: everything hits, nothing to complete
+    assert hit.all() and len(miss) == 0 and np.array_equal(out, ht[keys].reshape(5, 4, 4).sum(1))
+    before = out.copy()
+    state = [a.copy() for a in c.state(with_data=True)]
+    c.query_complete(keys, 5, hit, out, insert_missing=True)
+    assert np.array_equal(out.view(np.uint32), before.view(np.uint32))
+    assert all(np.array_equal(a, b) for a, b in zip(state, c.state(with_data=True)))
+    assert c.stats.tolist() == [40, 20, 20, 20, 0, 0]
