@@ -324,7 +324,11 @@ size_t hctr_cache_workspace_bytes(const hctr_cache* cache, int64_t nnz_max);
  * fused kernels instead of the general pipeline, because at that size launches cost more than
  * bytes.  Both paths give identical results; 0 switches the fused path off. */
 hctr_status hctr_cache_set_small_call_limit(hctr_cache* cache, int64_t max_keys);
-/* The recency stamps are 32-bit counts of the query / insert calls made so far.  A call that finds
+/* The recency stamps are 32-bit counts of the query / insert calls made so far; the count lives in
+ * device memory and is read and advanced by the kernels, so a call captured in a HIP graph may be
+ * replayed (each replay is one more call).  The host keeps a copy to see the limit coming, which
+ * replays do not advance: hctr_cache_stats brings it up to date, so a server that replays captured
+ * calls should read the statistics at least once every 2^31 replays.  A call that finds
  * the count at or above `limit` (2 .. 2^32 - 256, the default) first lowers every stamp and the
  * count by limit / 2, stamps at or below that becoming 0 = never used (among those the lowest way
  * is replaced first).  The order of the ways used within the last limit / 2 calls is unchanged, so
@@ -368,6 +372,43 @@ hctr_status hctr_cache_query_async(hctr_cache* cache, int64_t batch, int32_t num
                                    const int64_t* offsets, int64_t nnz, int32_t insert_missing, float* out,
                                    uint8_t* hit_mask, void* ws, size_t ws_bytes, void* stream,
                                    void* results_ready_event);
+/*
+ * The query in two phases, for a consumer that starts on the hits while the missing rows are still
+ * crossing the host link (section 3: parameter migration overlapped with the dense network;
+ * "embedding inference cache": dynamic insertion, asynchronous mechanisms).
+ *
+ * hctr_cache_query_hits  one call (it advances the call count like hctr_cache_query): classifies
+ *     every key, marks the hits used, writes hit_mask, and pools ONLY the hits: out[bag, :] = sum of
+ *     the cached vectors of the bag's resident keys, a missing key adding nothing yet.  Nothing is
+ *     read across the host link.  With miss_positions != NULL it also lists the positions of the keys
+ *     that are missing and lie inside the host table, in ascending order (device uint32 [nnz]; their
+ *     number goes to *n_missing, device uint32; both NULL or both given; costs up to four small
+ *     launches).  hits_ready_event (a hipEvent_t of the caller's, or NULL) is recorded on `stream`
+ *     behind this work.
+ * hctr_cache_query_complete  the rest of the same query, on any stream ordered after the hits call
+ *     (typically a side stream that waits for the event): every bag that holds missing keys gets
+ *     their host rows added to what the first phase left in out (bags without keys keep their bits),
+ *     each distinct missing row crossing the host link once; with insert_missing != 0 the missing
+ *     keys are then inserted exactly as by hctr_cache_query.  It must be given the keys, offsets,
+ *     nnz, out and ws of the hits call, with ws untouched in between, and no other call on this cache
+ *     may run between the two.  The consumer may read the hit-only `out` after the event, but must be
+ *     done with it before the stream reaches this call; the final `out` is ready when the stream has
+ *     passed it.
+ * After the pair, the cache (tags, stamps, rows, statistics) is what hctr_cache_query with the same
+ * insert_missing would have left; `out` equals its output up to the order of the fp32 additions
+ * (hits first, then the missing rows).
+ *
+ * Ordering: calls on one cache (query, the two phases, insert, update, refresh) must not overlap in
+ * time; order them on one stream or with events.  A refresh or update that ran beside a query could
+ * hand it a row that is half old and half new.
+ */
+hctr_status hctr_cache_query_hits(hctr_cache* cache, int64_t batch, int32_t num_slots, const int64_t* keys,
+                                  const int64_t* offsets, int64_t nnz, float* out, uint8_t* hit_mask,
+                                  uint32_t* miss_positions, uint32_t* n_missing, void* ws, size_t ws_bytes,
+                                  void* stream, void* hits_ready_event);
+hctr_status hctr_cache_query_complete(hctr_cache* cache, int64_t batch, int32_t num_slots, const int64_t* keys,
+                                      const int64_t* offsets, int64_t nnz, int32_t insert_missing, float* out,
+                                      void* ws, size_t ws_bytes, void* stream);
 hctr_status hctr_cache_insert(hctr_cache* cache, const int64_t* keys, int64_t n, void* ws, size_t ws_bytes,
                               void* stream);
 hctr_status hctr_cache_update(hctr_cache* cache, const int64_t* keys, const float* rows, int64_t n, void* ws,

@@ -100,6 +100,8 @@ def lib() -> C.CDLL:
         "hctr_cache_query": (i32, [p, i64, i32, p, p, i64, i32, p, p, p, sz, p]),
         "hctr_cache_query_async": (i32, [p, i64, i32, p, p, i64, i32, p, p, p, sz, p, p]),
         "hctr_cache_query_static": (i32, [p, i64, i32, p, p, i64, i32, p, p, p]),
+        "hctr_cache_query_hits": (i32, [p, i64, i32, p, p, i64, p, p, p, p, p, sz, p, p]),
+        "hctr_cache_query_complete": (i32, [p, i64, i32, p, p, i64, i32, p, p, sz, p]),
         "hctr_cache_insert": (i32, [p, p, i64, p, sz, p]),
         "hctr_cache_update": (i32, [p, p, p, i64, p, sz, p]),
         "hctr_cache_refresh": (i32, [p, p]),
@@ -124,7 +126,8 @@ EXPORTS = [
     "hctr_etc_workspace_bytes", "hctr_etc_create", "hctr_etc_load", "hctr_etc_dump", "hctr_etc_stats",
     "hctr_etc_destroy", "hctr_cache_storage_bytes",
     "hctr_cache_create", "hctr_cache_workspace_bytes", "hctr_cache_set_small_call_limit", "hctr_cache_set_epoch_limit", "hctr_cache_query",
-    "hctr_cache_query_async", "hctr_cache_query_static", "hctr_cache_insert", "hctr_cache_update", "hctr_cache_refresh", "hctr_cache_stats",
+    "hctr_cache_query_async", "hctr_cache_query_static", "hctr_cache_query_hits",
+    "hctr_cache_query_complete", "hctr_cache_insert", "hctr_cache_update", "hctr_cache_refresh", "hctr_cache_stats",
     "hctr_cache_state_view", "hctr_cache_destroy", "hctr_last_error",
 ]
 
@@ -501,6 +504,31 @@ class EmbeddingCache:
                                              int(insert_missing), _ptr(out), _ptr(hit_mask), _stream(stream)))
         return out
 
+    def query_hits(self, batch: int, num_slots: int, keys: torch.Tensor, out: torch.Tensor,
+                   offsets: Optional[torch.Tensor] = None, hit_mask: Optional[torch.Tensor] = None,
+                   miss_positions: Optional[torch.Tensor] = None, n_missing: Optional[torch.Tensor] = None,
+                   ws: Optional[torch.Tensor] = None, stream=None, ready: Optional[torch.cuda.Event] = None):
+        """hctr_cache_query_hits: first phase, pools the hits only.  `ready` must be an event that has been
+        recorded once already (torch creates the underlying event on the first record)."""
+        nnz = keys.numel()
+        if ws is None:
+            ws = self.workspace(nnz)
+        _check(lib().hctr_cache_query_hits(self.handle, batch, num_slots, _ptr(keys), _ptr(offsets), nnz, _ptr(out),
+                                           _ptr(hit_mask), _ptr(miss_positions), _ptr(n_missing), _ptr(ws), ws.numel(),
+                                           _stream(stream), None if ready is None else ready.cuda_event))
+        return out
+
+    def query_complete(self, batch: int, num_slots: int, keys: torch.Tensor, out: torch.Tensor,
+                       offsets: Optional[torch.Tensor] = None, insert_missing: bool = True,
+                       ws: Optional[torch.Tensor] = None, stream=None):
+        """hctr_cache_query_complete: second phase, adds the missing rows into `out` and inserts them."""
+        nnz = keys.numel()
+        if ws is None:
+            ws = self.workspace(nnz)
+        _check(lib().hctr_cache_query_complete(self.handle, batch, num_slots, _ptr(keys), _ptr(offsets), nnz,
+                                               int(insert_missing), _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+        return out
+
     def query_async(self, batch: int, num_slots: int, keys: torch.Tensor, ready: torch.cuda.Event,
                     offsets: Optional[torch.Tensor] = None, insert_missing: bool = True,
                     out: Optional[torch.Tensor] = None, hit_mask: Optional[torch.Tensor] = None,
@@ -511,7 +539,8 @@ class EmbeddingCache:
             out = torch.empty((batch, num_slots, self.dim), dtype=torch.float32, device=self.device)
         if ws is None:
             ws = self.workspace(nnz)
-        ready.record(torch.cuda.current_stream() if stream is None else stream)   # makes torch create the event
+        if not ready.cuda_event:   # torch creates the underlying event on its first record
+            ready.record(torch.cuda.current_stream() if stream is None else stream)
         _check(lib().hctr_cache_query_async(self.handle, batch, num_slots, _ptr(keys), _ptr(offsets), nnz,
                                             int(insert_missing), _ptr(out), _ptr(hit_mask), _ptr(ws),
                                             ws.numel(), _stream(stream), ready.cuda_event))

@@ -30,7 +30,8 @@ struct hctr_cache {
   const float* host_table;
   int64_t host_rows;
   size_t off_tags, off_stamps, off_data;
-  uint32_t epoch;          // number of query calls so far (host copy; kernels get it as an argument)
+  uint32_t epoch;          // host's copy of the call count, kept to see when the count nears its limit
+                           // (the kernels read the device's own count, which replays of a captured call advance)
   uint32_t epoch_limit;    // a call that finds epoch >= this first lowers stamps and epoch by half of it
   int64_t small_max_keys;  // calls with at most this many keys take the fused small-call kernels
 };
@@ -44,9 +45,28 @@ constexpr int kSmallMaxKeys = 8192;   // 104 KB of LDS in cache_insert_small
 
 struct CacheHeader {  // first 256 bytes of the cache storage
   u64 stats[6];       // queries, hits, (misses = queries - hits, filled in on the host), inserts, evictions, skipped
-  uint32_t epoch;
-  uint32_t pad[51];
+  uint32_t epoch;     // number of query / insert calls so far: the stamp of the last finished call
+  uint32_t pad0;
+  u64 call_acc;       // classifying kernel in flight: blocks finished << 40 | hits so far (0 between kernels)
+  uint32_t pad[48];
 };
+constexpr int kAccShift = 40;
+
+// The call count lives on the device so that a captured call can be replayed: every block of the
+// classifying kernel reads it on entry and works under stamp = count + 1; the kernels that follow in
+// the same call read the count as it is then.  Each block reports once, with one atomic that carries
+// its hits and counts it as finished; the block that finds all others finished has the call's total
+// hits in hand and publishes statistics and the new count (no block waits for another).
+__device__ __forceinline__ void cache_block_report(CacheHeader* hdr, uint32_t block_hits, uint32_t epoch,
+                                                   uint32_t nnz) {
+  const u64 old = atomicAdd(&hdr->call_acc, (1ull << kAccShift) | (u64)block_hits);
+  if ((old >> kAccShift) == (u64)gridDim.x - 1ull) {
+    hdr->stats[0] += (u64)nnz;
+    hdr->stats[1] += (old & ((1ull << kAccShift) - 1ull)) + (u64)block_hits;
+    hdr->epoch = epoch;
+    hdr->call_acc = 0;
+  }
+}
 static_assert(sizeof(CacheHeader) == 256, "header is one 256-byte block");
 
 // The divisor of the set index, with the reciprocal that turns the 64-bit remainder (a few hundred
@@ -73,14 +93,15 @@ __global__ __launch_bounds__(256) void cache_clear(u64* tags, uint32_t* stamps, 
   const uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
   if (i < n_lines) { tags[i] = kEmptyKey; stamps[i] = 0u; }
   if (i < 6) hdr->stats[i] = 0;
-  if (i == 0) hdr->epoch = 0;
+  if (i == 0) { hdr->epoch = 0; hdr->call_acc = 0; }
 }
 
 // Stamps are 32-bit call counts; before the count runs out every stamp is lowered by `by` (and the
 // host's count with them).  Stamps at or below `by` become 0, "never used".
 __global__ __launch_bounds__(256) void cache_lower_stamps(uint32_t* __restrict__ stamps, uint64_t n_lines,
-                                                          uint32_t by) {
+                                                          uint32_t by, CacheHeader* hdr) {
   const uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+  if (i == 0) hdr->epoch = hdr->epoch > by ? hdr->epoch - by : 0u;   // nothing else reads it in this kernel
   if (i < n_lines) {
     const uint32_t s = stamps[i];
     stamps[i] = s > by ? s - by : 0u;
@@ -159,13 +180,14 @@ __device__ __forceinline__ void victim_order_lds(uint32_t* codes, u64 tag, uint3
 template <int WAYS>
 __global__ __launch_bounds__(256) void cache_probe(const u64* __restrict__ tags,
                                                    uint32_t* __restrict__ stamps, SetDiv num_sets,
-                                                   int64_t host_rows, CacheHeader* hdr, uint32_t epoch,
+                                                   int64_t host_rows, CacheHeader* hdr,
                                                    const int64_t* __restrict__ keys, uint32_t nnz,
                                                    uint32_t* __restrict__ line_of,
                                                    uint8_t* __restrict__ hit_mask,
                                                    uint32_t* __restrict__ miss_flag) {
   constexpr int KP = WAYS >= 8 ? 8 : WAYS;
   __shared__ uint32_t block_hits;
+  const uint32_t epoch = hdr->epoch + 1u;   // this call's stamp (see cache_block_report)
   if (threadIdx.x == 0) block_hits = 0;
   __syncthreads();
   const int way = threadIdx.x % WAYS;
@@ -210,27 +232,32 @@ __global__ __launch_bounds__(256) void cache_probe(const u64* __restrict__ tags,
   }
   if (hits) atomicAdd(&block_hits, hits);
   __syncthreads();
-  if (threadIdx.x == 0) {
-    if (block_hits) atomicAdd(&hdr->stats[1], (u64)block_hits);
-    if (blockIdx.x == 0) {
-      hdr->epoch = epoch;
-      atomicAdd(&hdr->stats[0], (u64)nnz);
-    }
-  }
+  if (threadIdx.x == 0) cache_block_report(hdr, block_hits, epoch, nnz);
 }
 
+// What a pooling pass takes in.  kPoolAll: every key (a one-call query).  kPoolHits: cached rows only,
+// a missing key adds nothing (first phase of a two-phase query).  kAddMisses: only the rows of the
+// missing keys, added to what the first phase left in the output (second phase).
+enum PoolMode { kPoolAll = 0, kPoolHits = 1, kAddMisses = 2 };
+
 // Where a key's vector lives: cache line, staging row, host row, or nowhere (zeros).
+template <int MODE>
 __device__ __forceinline__ const float* row_source(uint32_t line, int64_t key, const float* data,
                                                    const float* staging, const float* host_table,
                                                    int64_t host_rows, int D) {
-  if (line == kNoLine) return (key >= 0 && key < host_rows) ? host_table + key * D : nullptr;
-  if (line & kStaged) return staging + (int64_t)(line & ~kStaged) * D;
-  return data + (int64_t)line * D;
+  if (line == kNoLine) {
+    if (MODE == kPoolHits) return nullptr;
+    return (key >= 0 && key < host_rows) ? host_table + key * D : nullptr;
+  }
+  if (line & kStaged) return MODE == kPoolHits ? nullptr : staging + (int64_t)(line & ~kStaged) * D;
+  return MODE == kAddMisses ? nullptr : data + (int64_t)line * D;
 }
 
 // Pooled gather of one bag by one wave: 64/LPR lane groups take the bag's keys round robin, U row
-// loads each in flight; group partial sums are staged in LDS and added in group order.
-template <int LPR, int U>
+// loads each in flight; group partial sums are staged in LDS and added in group order.  With
+// kAddMisses the sum of the missing rows is added to the bag's output, and a bag without a missing
+// key is left alone.
+template <int LPR, int U, int MODE>
 __device__ __forceinline__ void gather_bag(const float* __restrict__ data, const float* __restrict__ staging,
                                            const float* __restrict__ host_table, int64_t host_rows, int D,
                                            const int64_t* __restrict__ keys,
@@ -242,12 +269,14 @@ __device__ __forceinline__ void gather_bag(const float* __restrict__ data, const
   const int col = blockIdx.y * (LPR * 4) + sub * 4;
   const bool active = col < D;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  bool took = false;
   for (int64_t j = b0 + g; j < b1; j += G * U) {
     const float* src[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t jj = j + u * G;
-      src[u] = jj < b1 ? row_source(line_of[jj], keys[jj], data, staging, host_table, host_rows, D) : nullptr;
+      src[u] = jj < b1 ? row_source<MODE>(line_of[jj], keys[jj], data, staging, host_table, host_rows, D) : nullptr;
+      took = took || src[u] != nullptr;
     }
     f32x4 v[U];
 #pragma unroll
@@ -270,13 +299,21 @@ __device__ __forceinline__ void gather_bag(const float* __restrict__ data, const
       }
     }
   }
-  if (live && g == 0 && active) {
+  if (MODE == kAddMisses) {
+    const bool any = __ballot(took) != 0;   // some lane of the wave met a missing row of this bag
+    if (live && g == 0 && active && any) {
+      float* to = out + (int64_t)bag * D + col;
+      f32x4 o = load4(to);
+      o.x += acc.x; o.y += acc.y; o.z += acc.z; o.w += acc.w;
+      store4(to, o);
+    }
+  } else if (live && g == 0 && active) {
     const float v[4] = {acc.x, acc.y, acc.z, acc.w};
     store_stream<4>(out + (int64_t)bag * D + col, v);
   }
 }
 
-template <int LPR, int U>
+template <int LPR, int U, int MODE>
 __global__ __launch_bounds__(256) void cache_gather(const float* __restrict__ data,
                                                     const float* __restrict__ staging,
                                                     const float* __restrict__ host_table,
@@ -295,7 +332,17 @@ __global__ __launch_bounds__(256) void cache_gather(const float* __restrict__ da
     b0 = offsets ? offsets[bag] : (int64_t)bag * hotness;
     b1 = offsets ? offsets[bag + 1] : (int64_t)(bag + 1) * hotness;
   }
-  gather_bag<LPR, U>(data, staging, host_table, host_rows, D, keys, line_of, b0, b1, live, bag, out, part[wave]);
+  gather_bag<LPR, U, MODE>(data, staging, host_table, host_rows, D, keys, line_of, b0, b1, live, bag, out,
+                           part[wave]);
+}
+
+// Positions of the missing keys, ascending: position i goes to list[idx[i]] when its flag is set
+// (idx = exclusive scan of the flags).
+__global__ __launch_bounds__(256) void cache_list_missing(const uint32_t* __restrict__ flag,
+                                                          const uint32_t* __restrict__ idx, uint32_t n,
+                                                          uint32_t* __restrict__ list) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i < n && flag[i]) list[idx[i]] = i;
 }
 
 // First appearances of the missing keys, q = 0..n_new-1 in first-appearance order: remember the
@@ -346,11 +393,12 @@ __global__ __launch_bounds__(256) void cache_fetch(const float* __restrict__ hos
 // whole run.  dst[q] = cache line that key q goes to, or kNoLine when its insert is skipped.
 template <int WAYS>
 __global__ __launch_bounds__(256) void cache_place(u64* __restrict__ tags, uint32_t* __restrict__ stamps,
-                                                   CacheHeader* hdr, uint32_t epoch,
+                                                   CacheHeader* hdr,
                                                    const HashWsHeader* ws_hdr, const u64* __restrict__ skv,
                                                    const u64* __restrict__ new_key,
                                                    uint32_t* __restrict__ dst) {
   __shared__ uint32_t blk_stats[3];
+  const uint32_t epoch = hdr->epoch;   // the classifying kernel of this call has published it
   if (threadIdx.x < 3) blk_stats[threadIdx.x] = 0;
   __syncthreads();
   const int way = threadIdx.x % WAYS;
@@ -413,13 +461,13 @@ __global__ __launch_bounds__(256) void cache_fill(float* __restrict__ data, cons
 // Probe + gather in one launch, a block per four bags: the block first classifies the keys of its
 // bags (a group of WAYS lanes per key), then each wave pools one bag.  Misses are read straight
 // from the host table.  Rows must fit one column chunk (dim <= LPR * 4, i.e. dim <= 256).
-template <int WAYS, int LPR>
+template <int WAYS, int LPR, int MODE>
 __global__ __launch_bounds__(256) void cache_query_small(const u64* __restrict__ tags,
                                                          uint32_t* __restrict__ stamps, SetDiv num_sets,
                                                          const float* __restrict__ data,
                                                          const float* __restrict__ host_table,
                                                          int64_t host_rows, int D, CacheHeader* hdr,
-                                                         uint32_t epoch, const int64_t* __restrict__ keys,
+                                                         const int64_t* __restrict__ keys,
                                                          uint32_t nnz, const int64_t* __restrict__ offsets,
                                                          int64_t hotness, uint32_t n_bags,
                                                          uint32_t* line_of, uint8_t* __restrict__ hit_mask,
@@ -428,6 +476,7 @@ __global__ __launch_bounds__(256) void cache_query_small(const u64* __restrict__
   constexpr int G = 64 / LPR;
   __shared__ float part[4][(G > 1 ? (G - 1) : 1) * LPR * 4];
   __shared__ uint32_t block_hits;
+  const uint32_t epoch = hdr->epoch + 1u;   // this call's stamp (see cache_block_report)
   if (threadIdx.x == 0) block_hits = 0;
   __syncthreads();
   const uint32_t bag_lo = blockIdx.x * 4u;
@@ -467,13 +516,7 @@ __global__ __launch_bounds__(256) void cache_query_small(const u64* __restrict__
   }
   __threadfence_block();
   __syncthreads();   // line_of of this block's keys is complete and visible to the whole block
-  if (threadIdx.x == 0) {
-    if (block_hits) atomicAdd(&hdr->stats[1], (u64)block_hits);
-    if (blockIdx.x == 0) {
-      hdr->epoch = epoch;
-      atomicAdd(&hdr->stats[0], (u64)nnz);
-    }
-  }
+  if (threadIdx.x == 0) cache_block_report(hdr, block_hits, epoch, nnz);
   const int wave = threadIdx.x >> 6;
   const uint32_t bag = bag_lo + wave;
   const bool live = bag < n_bags;
@@ -484,7 +527,8 @@ __global__ __launch_bounds__(256) void cache_query_small(const u64* __restrict__
   }
   // no line of a small call is staged; `data` only fills the staging argument
   if (out != nullptr)   // uniform: an insert-only call pools nothing
-    gather_bag<LPR, 4>(data, data, host_table, host_rows, D, keys, line_of, b0, b1, live, bag, out, part[wave]);
+    gather_bag<LPR, 4, MODE>(data, data, host_table, host_rows, D, keys, line_of, b0, b1, live, bag, out,
+                             part[wave]);
 }
 
 // The whole insertion of a small call in one block of 1024 threads (n <= kSmallMaxKeys keys).
@@ -496,10 +540,11 @@ template <int WAYS>
 __global__ __launch_bounds__(1024) void cache_insert_small(u64* __restrict__ tags, uint32_t* __restrict__ stamps,
                                                            float* __restrict__ data, CacheHeader* hdr,
                                                            const float* __restrict__ host_table, int D,
-                                                           SetDiv num_sets, uint32_t epoch,
+                                                           SetDiv num_sets,
                                                            const int64_t* __restrict__ keys,
                                                            const uint32_t* __restrict__ miss_flag, uint32_t n) {
   constexpr int T = 1024;
+  const uint32_t epoch = hdr->epoch;   // the classifying kernel of this call has published it
   constexpr int PER = kSmallMaxKeys / T;            // positions per thread in the two scans
   __shared__ uint32_t pos_or_dst[kSmallMaxKeys];    // missing positions (steps 1-3), then q -> line (4-6)
   __shared__ u64 wide[kSmallMaxKeys];               // keys of the missing positions (1-2), then two u32 arrays
@@ -767,13 +812,14 @@ static CacheWsLayout cache_ws_layout(const hctr_cache* c, int64_t nnz_max) {
   L.sort = sort_plan((uint32_t)n, L.sort_bits);
   L.header = at(sizeof(HashWsHeader));
   L.line_of = at(n * 4); L.flag = at(n * 4);
+  L.idx = at(n * 4);
+  L.scan_tmp = at(scan_tmp_count((uint32_t)n) * 4);
   if ((int64_t)n <= c->small_max_keys && c->dim <= 256) {   // the small-call kernels need nothing else
     L.total = cv.off;
     return L;
   }
-  L.idx = at(n * 4); L.miss_pos = at(n * 4);
+  L.miss_pos = at(n * 4);
   L.scr_slot = at(n * 4); L.first = at(n * 4); L.rank = at(n * 4);
-  L.scan_tmp = at(scan_tmp_count((uint32_t)n) * 4);
   L.scratch_cap_max = dedup_scratch_capacity((uint32_t)n);
   L.scratch = at((size_t)L.scratch_cap_max * 4);
   L.new_key = at(n * 8);
@@ -812,7 +858,7 @@ struct QueryArgs {
   const int64_t* keys;
   const int64_t* offsets;
   int64_t hotness;
-  uint32_t n, n_bags, epoch;
+  uint32_t n, n_bags;
   float* out;
   uint8_t* hit_mask;
   uint32_t* line_of;
@@ -829,30 +875,40 @@ static void launch_probe(const QueryArgs& a) {
   constexpr int KP = WAYS >= 8 ? 8 : WAYS;
   const uint32_t blocks = (uint32_t)std::min<int64_t>(ceil_div(ceil_div((int64_t)a.n, KP) * WAYS, 256), 2048);
   hipLaunchKernelGGL((cache_probe<WAYS>), dim3(blocks), dim3(256), 0, a.stream, (const u64*)a.tags(), a.stamps(),
-                     make_set_div(a.c->num_sets), a.c->host_rows, a.hdr(), a.epoch, a.keys, a.n, a.line_of, a.hit_mask,
+                     make_set_div(a.c->num_sets), a.c->host_rows, a.hdr(), a.keys, a.n, a.line_of, a.hit_mask,
                      a.flag);
 }
 
-template <int LPR>
+template <int LPR, int MODE>
 static void launch_gather(const QueryArgs& a, const float* staging) {
   dim3 grid((uint32_t)ceil_div(a.n_bags, 4), (uint32_t)ceil_div(a.c->dim, LPR * 4));
-  hipLaunchKernelGGL((cache_gather<LPR, 4>), grid, dim3(256), 0, a.stream, (const float*)a.data(), staging,
+  hipLaunchKernelGGL((cache_gather<LPR, 4, MODE>), grid, dim3(256), 0, a.stream, (const float*)a.data(), staging,
                      a.c->host_table, a.c->host_rows, (int)a.c->dim, a.keys, (const uint32_t*)a.line_of,
                      a.offsets, a.hotness, a.n_bags, a.out);
 }
+template <int MODE>
+static void dispatch_gather(int lpr, const QueryArgs& a, const float* staging) {
+  switch (lpr) {
+    case 4: launch_gather<4, MODE>(a, staging); break;
+    case 8: launch_gather<8, MODE>(a, staging); break;
+    case 16: launch_gather<16, MODE>(a, staging); break;
+    case 32: launch_gather<32, MODE>(a, staging); break;
+    default: launch_gather<64, MODE>(a, staging); break;
+  }
+}
 
-template <int WAYS, int LPR>
+template <int WAYS, int LPR, int MODE>
 static void launch_query_small(const QueryArgs& a) {
   dim3 grid((uint32_t)ceil_div(a.n_bags, 4), 1);
-  hipLaunchKernelGGL((cache_query_small<WAYS, LPR>), grid, dim3(256), 0, a.stream, (const u64*)a.tags(),
+  hipLaunchKernelGGL((cache_query_small<WAYS, LPR, MODE>), grid, dim3(256), 0, a.stream, (const u64*)a.tags(),
                      a.stamps(), make_set_div(a.c->num_sets), (const float*)a.data(), a.c->host_table, a.c->host_rows,
-                     (int)a.c->dim, a.hdr(), a.epoch, a.keys, a.n, a.offsets, a.hotness, a.n_bags, a.line_of,
+                     (int)a.c->dim, a.hdr(), a.keys, a.n, a.offsets, a.hotness, a.n_bags, a.line_of,
                      a.hit_mask, a.flag, a.out);
 }
 
-template <int WAYS>
+template <int WAYS, int MODE>
 static void dispatch_query_small(int lpr, const QueryArgs& a) {
-#define CALL(LL) launch_query_small<WAYS, LL>(a)
+#define CALL(LL) launch_query_small<WAYS, LL, MODE>(a)
   HCTR_BY_LPR(lpr, CALL)
 #undef CALL
 }
@@ -860,7 +916,7 @@ static void dispatch_query_small(int lpr, const QueryArgs& a) {
 template <int WAYS>
 static void launch_insert_small(const QueryArgs& a) {
   hipLaunchKernelGGL((cache_insert_small<WAYS>), dim3(1), dim3(1024), 0, a.stream, a.tags(), a.stamps(), a.data(),
-                     a.hdr(), a.c->host_table, (int)a.c->dim, make_set_div(a.c->num_sets), a.epoch, a.keys,
+                     a.hdr(), a.c->host_table, (int)a.c->dim, make_set_div(a.c->num_sets), a.keys,
                      (const uint32_t*)a.flag, a.n);
 }
 
@@ -870,7 +926,7 @@ static void launch_place(const QueryArgs& a, const HashWsHeader* ws_hdr, const u
   // few blocks: each ends with three atomics on the same statistics words
   const uint32_t blocks = (uint32_t)std::min<int64_t>(ceil_div((int64_t)a.n * WAYS, 256), 512);
   hipLaunchKernelGGL((cache_place<WAYS>), dim3(blocks), dim3(256), 0,
-                     a.stream, a.tags(), a.stamps(), a.hdr(), a.epoch, ws_hdr, skv, new_key, dst);
+                     a.stream, a.tags(), a.stamps(), a.hdr(), ws_hdr, skv, new_key, dst);
 }
 
 template <int LPR>
@@ -975,12 +1031,19 @@ HCTR_API size_t hctr_cache_workspace_bytes(const hctr_cache* cache, int64_t nnz_
   return cache_ws_layout(&general, nnz_max).total;
 }
 
+// Which part of a query a call runs.  kWhole: classify, pool everything, insert.  kHitsPhase: classify
+// and pool the hits only.  kMissPhase: what is left after kHitsPhase on the same keys and workspace
+// (add the missing rows to the output, insert); it classifies nothing and starts no new call.
+enum QueryPart { kWhole = 0, kHitsPhase = 1, kMissPhase = 2 };
+
 // One query call.  out == nullptr pools nothing (insert-only); ready != nullptr is recorded on the
-// stream as soon as out and hit_mask are complete, before the insertion work is enqueued.
-static hctr_status cache_query_impl(hctr_cache* c, int64_t batch, int32_t num_slots, const int64_t* keys,
-                                    const int64_t* offsets, int64_t nnz, int32_t insert_missing, float* out,
-                                    bool need_out, uint8_t* hit_mask, void* ws, size_t ws_bytes, void* stream_,
-                                    hipEvent_t ready) {
+// stream as soon as out and hit_mask (and the miss list, if asked for) are complete, before any
+// insertion work is enqueued.
+static hctr_status cache_query_impl(hctr_cache* c, QueryPart part, int64_t batch, int32_t num_slots,
+                                    const int64_t* keys, const int64_t* offsets, int64_t nnz,
+                                    int32_t insert_missing, float* out, bool need_out, uint8_t* hit_mask,
+                                    uint32_t* miss_list, uint32_t* n_missing, void* ws, size_t ws_bytes,
+                                    void* stream_, hipEvent_t ready) {
   if (!c) return fail(HCTR_E_NULL_PTR, "cache is NULL");
   if (batch < 0 || num_slots < 1 || nnz < 0) return fail(HCTR_E_INVALID_ARG, "batch / num_slots / nnz invalid");
   const int64_t n_bags = batch * num_slots;
@@ -992,6 +1055,8 @@ static hctr_status cache_query_impl(hctr_cache* c, int64_t batch, int32_t num_sl
                   (long long)nnz, (long long)n_bags);
     hotness = n_bags ? nnz / n_bags : 0;
   }
+  if ((miss_list == nullptr) != (n_missing == nullptr))
+    return fail(HCTR_E_NULL_PTR, "miss_positions and n_missing go together");
   if (n_bags == 0) {
     if (nnz != 0) return fail(HCTR_E_INVALID_ARG, "nnz must be 0 when there are no bags");
     return HCTR_OK;
@@ -1005,29 +1070,67 @@ static hctr_status cache_query_impl(hctr_cache* c, int64_t batch, int32_t num_sl
   if (ws_bytes < L.total) return fail(HCTR_E_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, L.total);
 
   char* w = static_cast<char*>(ws);
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
   HashWsHeader* ws_hdr = reinterpret_cast<HashWsHeader*>(w + L.header);
-  if (c->epoch >= c->epoch_limit) {   // the count is about to run out: lower it and every stamp
-    const uint32_t by = c->epoch_limit / 2;
-    const uint64_t lines = (uint64_t)c->num_sets * c->ways;
-    hipLaunchKernelGGL(cache_lower_stamps, dim3((uint32_t)ceil_div((int64_t)lines, 256)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream_), reinterpret_cast<uint32_t*>(c->storage + c->off_stamps),
-                       lines, by);
-    HCTR_TRY(launch_status("cache_lower_stamps"));
-    c->epoch -= by;
+  if (part != kMissPhase) {   // a new call
+    if (c->epoch >= c->epoch_limit) {   // the count is about to run out: lower it and every stamp
+      const uint32_t by = c->epoch_limit / 2;
+      const uint64_t lines = (uint64_t)c->num_sets * c->ways;
+      hipLaunchKernelGGL(cache_lower_stamps, dim3((uint32_t)ceil_div((int64_t)lines, 256)), dim3(256), 0, stream,
+                         reinterpret_cast<uint32_t*>(c->storage + c->off_stamps), lines, by,
+                         reinterpret_cast<CacheHeader*>(c->storage));
+      HCTR_TRY(launch_status("cache_lower_stamps"));
+      c->epoch -= by;
+    }
+    c->epoch += 1;
   }
-  c->epoch += 1;
-  QueryArgs a{c, keys, offsets, hotness, (uint32_t)nnz, (uint32_t)n_bags, c->epoch, out, hit_mask,
+  // the miss flags serve the insertion, the second phase and the miss list
+  const bool want_flags = insert_missing || part != kWhole || miss_list != nullptr;
+  QueryArgs a{c, keys, offsets, hotness, (uint32_t)nnz, (uint32_t)n_bags, out, hit_mask,
               reinterpret_cast<uint32_t*>(w + L.line_of),
-              insert_missing ? reinterpret_cast<uint32_t*>(w + L.flag) : nullptr,
-              static_cast<hipStream_t>(stream_)};
+              want_flags ? reinterpret_cast<uint32_t*>(w + L.flag) : nullptr, stream};
   int lpr = pow2_ceil((int)ceil_div(c->dim, 4));
   lpr = lpr < 4 ? 4 : (lpr > 64 ? 64 : lpr);
+  const bool small = nnz <= c->small_max_keys && c->dim <= 256;
 
-  if (nnz <= c->small_max_keys && c->dim <= 256) {
-#define CALL(W) dispatch_query_small<W>(lpr, a)
-    HCTR_BY_WAYS(c->ways, CALL)
+  // ---- classify and pool
+  if (part != kMissPhase) {
+    if (small) {
+      if (part == kHitsPhase) {
+#define CALL(W) dispatch_query_small<W, kPoolHits>(lpr, a)
+        HCTR_BY_WAYS(c->ways, CALL)
 #undef CALL
-    if (ready) HCTR_TRY_HIP(hipEventRecord(ready, a.stream));
+      } else {
+#define CALL(W) dispatch_query_small<W, kPoolAll>(lpr, a)
+        HCTR_BY_WAYS(c->ways, CALL)
+#undef CALL
+      }
+    } else {
+#define CALL(W) launch_probe<W>(a)
+      HCTR_BY_WAYS(c->ways, CALL)
+#undef CALL
+      if (part == kHitsPhase) {
+        if (out) dispatch_gather<kPoolHits>(lpr, a, nullptr);
+      } else if (!insert_missing) {
+        if (out) dispatch_gather<kPoolAll>(lpr, a, nullptr);   // missing rows straight from the host table
+      }
+    }
+    if (miss_list != nullptr && nnz > 0) {   // ascending positions of the missing keys inside the host table
+      uint32_t* idx = reinterpret_cast<uint32_t*>(w + L.idx);
+      HCTR_TRY(exclusive_scan_u32(a.flag, idx, a.n, reinterpret_cast<uint32_t*>(w + L.scan_tmp), n_missing, stream));
+      hipLaunchKernelGGL(cache_list_missing, dim3((uint32_t)ceil_div(a.n, 256)), dim3(256), 0, stream,
+                         (const uint32_t*)a.flag, (const uint32_t*)idx, a.n, miss_list);
+    }
+    // out and hit_mask are complete here on every path but the general one-call path with insertion,
+    // which pools after the missing rows have been staged (below)
+    const bool pooled_later = part == kWhole && !small && insert_missing;
+    if (ready && !pooled_later) HCTR_TRY_HIP(hipEventRecord(ready, stream));
+    if (part == kHitsPhase) return launch_status("hctr_cache_query_hits");
+  }
+
+  // ---- missing rows into the output (second phase) and insertion
+  if (small) {
+    if (part == kMissPhase && out) dispatch_gather<kAddMisses>(lpr, a, nullptr);   // straight from the host table
     if (insert_missing && nnz > 0) {
 #define CALL(W) launch_insert_small<W>(a)
       HCTR_BY_WAYS(c->ways, CALL)
@@ -1035,17 +1138,8 @@ static hctr_status cache_query_impl(hctr_cache* c, int64_t batch, int32_t num_sl
     }
     return launch_status("hctr_cache_query");
   }
-
-#define CALL(W) launch_probe<W>(a)
-  HCTR_BY_WAYS(c->ways, CALL)
-#undef CALL
   if (!insert_missing) {
-    if (out) {
-#define CALL(LL) launch_gather<LL>(a, nullptr)
-      HCTR_BY_LPR(lpr, CALL)
-#undef CALL
-    }
-    if (ready) HCTR_TRY_HIP(hipEventRecord(ready, a.stream));
+    if (part == kMissPhase && out) dispatch_gather<kAddMisses>(lpr, a, nullptr);
     return launch_status("hctr_cache_query");
   }
   DedupBuffers B{a.flag,
@@ -1075,11 +1169,10 @@ static hctr_status cache_query_impl(hctr_cache* c, int64_t batch, int32_t num_sl
   HCTR_BY_LPR(lpr, CALL)
 #undef CALL
   if (out) {
-#define CALL(LL) launch_gather<LL>(a, staging)
-    HCTR_BY_LPR(lpr, CALL)
-#undef CALL
+    if (part == kMissPhase) dispatch_gather<kAddMisses>(lpr, a, staging);
+    else dispatch_gather<kPoolAll>(lpr, a, staging);
   }
-  if (ready) HCTR_TRY_HIP(hipEventRecord(ready, a.stream));
+  if (ready && part == kWhole) HCTR_TRY_HIP(hipEventRecord(ready, a.stream));
   HCTR_TRY(radix_sort_u64(L.sort, &ws_hdr->n_new, reinterpret_cast<uint64_t*>(kv[0]),
                           reinterpret_cast<uint64_t*>(kv[1]), reinterpret_cast<uint32_t*>(w + L.hist),
                           reinterpret_cast<uint32_t*>(w + L.aux), false, a.stream));
@@ -1097,8 +1190,8 @@ HCTR_API hctr_status hctr_cache_query(hctr_cache* c, int64_t batch, int32_t num_
                                       const int64_t* offsets, int64_t nnz, int32_t insert_missing,
                                       float* out, uint8_t* hit_mask, void* ws, size_t ws_bytes,
                                       void* stream) {
-  return cache_query_impl(c, batch, num_slots, keys, offsets, nnz, insert_missing, out, true, hit_mask, ws,
-                          ws_bytes, stream, nullptr);
+  return cache_query_impl(c, kWhole, batch, num_slots, keys, offsets, nnz, insert_missing, out, true, hit_mask,
+                          nullptr, nullptr, ws, ws_bytes, stream, nullptr);
 }
 
 HCTR_API hctr_status hctr_cache_query_async(hctr_cache* c, int64_t batch, int32_t num_slots,
@@ -1106,14 +1199,32 @@ HCTR_API hctr_status hctr_cache_query_async(hctr_cache* c, int64_t batch, int32_
                                             int32_t insert_missing, float* out, uint8_t* hit_mask, void* ws,
                                             size_t ws_bytes, void* stream, void* results_ready_event) {
   if (!results_ready_event) return fail(HCTR_E_NULL_PTR, "results_ready_event is NULL");
-  return cache_query_impl(c, batch, num_slots, keys, offsets, nnz, insert_missing, out, true, hit_mask, ws,
-                          ws_bytes, stream, static_cast<hipEvent_t>(results_ready_event));
+  return cache_query_impl(c, kWhole, batch, num_slots, keys, offsets, nnz, insert_missing, out, true, hit_mask,
+                          nullptr, nullptr, ws, ws_bytes, stream, static_cast<hipEvent_t>(results_ready_event));
+}
+
+HCTR_API hctr_status hctr_cache_query_hits(hctr_cache* c, int64_t batch, int32_t num_slots, const int64_t* keys,
+                                           const int64_t* offsets, int64_t nnz, float* out, uint8_t* hit_mask,
+                                           uint32_t* miss_positions, uint32_t* n_missing, void* ws,
+                                           size_t ws_bytes, void* stream, void* hits_ready_event) {
+  return cache_query_impl(c, kHitsPhase, batch, num_slots, keys, offsets, nnz, 0, out, true, hit_mask,
+                          miss_positions, n_missing, ws, ws_bytes, stream,
+                          static_cast<hipEvent_t>(hits_ready_event));
+}
+
+HCTR_API hctr_status hctr_cache_query_complete(hctr_cache* c, int64_t batch, int32_t num_slots,
+                                               const int64_t* keys, const int64_t* offsets, int64_t nnz,
+                                               int32_t insert_missing, float* out, void* ws, size_t ws_bytes,
+                                               void* stream) {
+  return cache_query_impl(c, kMissPhase, batch, num_slots, keys, offsets, nnz, insert_missing, out, true, nullptr,
+                          nullptr, nullptr, ws, ws_bytes, stream, nullptr);
 }
 
 HCTR_API hctr_status hctr_cache_insert(hctr_cache* c, const int64_t* keys, int64_t n, void* ws, size_t ws_bytes,
                                        void* stream) {
   if (n == 0) return c ? HCTR_OK : fail(HCTR_E_NULL_PTR, "cache is NULL");
-  return cache_query_impl(c, n, 1, keys, nullptr, n, 1, nullptr, false, nullptr, ws, ws_bytes, stream, nullptr);
+  return cache_query_impl(c, kWhole, n, 1, keys, nullptr, n, 1, nullptr, false, nullptr, nullptr, nullptr, ws,
+                          ws_bytes, stream, nullptr);
 }
 
 HCTR_API hctr_status hctr_cache_update(hctr_cache* c, const int64_t* keys, const float* rows, int64_t n, void* ws,
@@ -1185,10 +1296,13 @@ HCTR_API hctr_status hctr_cache_refresh(hctr_cache* c, void* stream) {
 
 HCTR_API hctr_status hctr_cache_stats(hctr_cache* c, void* stream, int64_t stats[6]) {
   if (!c || !stats) return fail(HCTR_E_NULL_PTR, "NULL argument");
-  HCTR_TRY_HIP(hipMemcpyAsync(stats, c->storage, 6 * sizeof(int64_t), hipMemcpyDeviceToHost,
+  int64_t head[7];   // the six statistics and the word that holds the call count
+  HCTR_TRY_HIP(hipMemcpyAsync(head, c->storage, sizeof(head), hipMemcpyDeviceToHost,
                               static_cast<hipStream_t>(stream)));
   HCTR_TRY_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  for (int i = 0; i < 6; ++i) stats[i] = head[i];
   stats[2] = stats[0] - stats[1];   // every queried key is a hit or a miss
+  c->epoch = (uint32_t)(uint64_t)head[6];   // replays of captured calls advance the device's count only
   return HCTR_OK;
 }
 

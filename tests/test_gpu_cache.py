@@ -245,3 +245,119 @@ def test_async_query_signals_results_before_insertion(small_limit):
     assert_close(copy.cpu().numpy().reshape(260, dim), ref_out, mag, "results seen by the waiting stream")
     torch.cuda.synchronize()
     _state_equal(p, "after async query")
+
+
+# ---- two-phase query and graph replay -------------------------------------------------------------
+
+def _mag(host, keys, n_bags, offsets=None):
+    valid = (keys >= 0) & (keys < host.shape[0])
+    bag = (np.repeat(np.arange(n_bags), np.diff(offsets)) if offsets is not None
+           else np.arange(len(keys)) // max(1, len(keys) // n_bags))
+    mag = np.zeros((n_bags, host.shape[1]))
+    np.add.at(mag, bag[valid], np.abs(host.numpy()[keys[valid]]).astype(np.float64))
+    return mag
+
+
+@pytest.mark.parametrize("small_limit", [0, 8192], ids=["general", "fused-small"])
+def test_two_phase_query_matches_the_simulation(small_limit):
+    """hctr_cache_query_hits + hctr_cache_query_complete against the oracle's pair: after the first
+    phase the hit-only pooled rows, the hit mask, the ascending list of missing positions and the
+    statistics; after the second (on a side stream that waits for the event) the completed rows and
+    the whole cache state; with and without insertion, fixed hotness and CSR bags, keys without a row."""
+    host_rows, dim, n_bags, hot = 20000, 64, 26 * 7, 4
+    p = Pair(96, 8, pinned_table(host_rows, dim), small_limit)
+    smp = datagen.ZipfSampler(host_rows, 1.2)
+    side = torch.cuda.Stream()
+    ready = torch.cuda.Event()
+    ready.record()
+    rng = np.random.default_rng(4)
+    for it in range(10):
+        keys = datagen.cache_keys(SEED, 1200 + it, host_rows, n_bags * hot, 1.2, sampler=smp).numpy()
+        if it == 2:
+            keys[::15] = -1
+            keys[3::40] = host_rows + 11
+        offsets = None
+        if it % 4 == 3:
+            cuts = np.sort(rng.integers(0, len(keys) + 1, n_bags - 1))
+            offsets = np.concatenate([[0], cuts, [len(keys)]]).astype(np.int64)
+        insert = it % 3 != 2
+        d_keys = to_dev(keys)
+        d_off = None if offsets is None else to_dev(offsets)
+        ref_out, ref_hit, ref_miss = p.ref.query_hits(keys, n_bags, offsets=offsets)
+        out = torch.full((n_bags, dim), float("nan"), dtype=torch.float32, device="cuda")
+        d_hit = torch.full((len(keys),), 9, dtype=torch.uint8, device="cuda")
+        d_miss = torch.full((len(keys),), -1, dtype=torch.int32, device="cuda")
+        d_nmiss = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        ws = p.gpu.workspace(len(keys))
+        p.gpu.query_hits(n_bags, 1, d_keys, out, d_off, d_hit, d_miss, d_nmiss, ws=ws, ready=ready)
+        with torch.cuda.stream(side):
+            side.wait_event(ready)
+            seen = out.clone()                       # what a consumer sees once the event has fired
+        side.synchronize()
+        assert np.array_equal(d_hit.cpu().numpy(), ref_hit), f"call {it}: hit mask"
+        assert int(d_nmiss.item()) == len(ref_miss), f"call {it}: number of missing positions"
+        assert np.array_equal(d_miss.cpu().numpy()[:len(ref_miss)], ref_miss), f"call {it}: missing positions"
+        mag = _mag(p.host, keys, n_bags, offsets)
+        assert_close(seen.cpu().numpy(), ref_out, mag, f"call {it}: hit-only rows")
+        assert p.gpu.stats[:3] == p.ref.stats.tolist()[:3]
+        p.ref.query_complete(keys, n_bags, ref_hit, ref_out, offsets=offsets, insert_missing=insert)
+        with torch.cuda.stream(side):                # second phase on the side stream, after the event
+            p.gpu.query_complete(n_bags, 1, d_keys, out, d_off, insert, ws=ws, stream=side)
+        side.synchronize()
+        assert_close(out.cpu().numpy(), ref_out, mag, f"call {it}: completed rows")
+        no_miss = ~np.isin(np.arange(n_bags), (np.searchsorted(offsets, ref_miss, side="right") - 1) if offsets is not None
+                           else ref_miss // hot)
+        assert torch.equal(out[torch.from_numpy(no_miss).cuda()], seen[torch.from_numpy(no_miss).cuda()]), \
+            f"call {it}: bags without a missing key changed"
+        _state_equal(p, f"two-phase call {it}")
+    assert p.ref.stats[1] > 0 and p.ref.stats[3] > 0
+
+
+@pytest.mark.parametrize("small_limit", [0, 8192], ids=["general", "fused-small"])
+def test_captured_query_replays_like_eager_calls(small_limit):
+    """The call count lives on the device, so a query captured in a HIP graph can be replayed: every
+    replay is one more call.  The same graph is replayed on fresh keys (copied into the captured
+    buffers between replays, with eager calls and synchronisations in between) and every replay is
+    checked against the oracle: hit mask, pooled rows, tags, stamps, cached rows, statistics."""
+    host_rows, dim, n_bags, hot = 8000, 32, 26 * 3, 4
+    p = Pair(40, 4, pinned_table(host_rows, dim), small_limit)
+    smp = datagen.ZipfSampler(host_rows, 1.2)
+    n = n_bags * hot
+    d_keys = torch.zeros(n, dtype=torch.int64, device="cuda")
+    d_hit = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    out = torch.zeros((n_bags, dim), dtype=torch.float32, device="cuda")
+    ws = p.gpu.workspace(n)
+
+    def fresh(it):
+        return datagen.cache_keys(SEED, 1300 + it, host_rows, n, 1.2, sampler=smp).numpy()
+
+    def check(it, keys, what):
+        ref_out, ref_hit = p.ref.query(keys, n_bags, insert_missing=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_hit.cpu().numpy(), ref_hit), f"{what} {it}: hit mask"
+        assert_close(out.cpu().numpy(), ref_out, _mag(p.host, keys, n_bags), f"{what} {it}: pooled rows")
+        _state_equal(p, f"{what} {it}")
+
+    for it in range(2):                              # eagerly first: nothing is set up during capture
+        keys = fresh(it)
+        d_keys.copy_(torch.from_numpy(keys))
+        p.gpu.query(n_bags, 1, d_keys, None, True, out=out, hit_mask=d_hit, ws=ws)
+        check(it, keys, "eager")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            p.gpu.query(n_bags, 1, d_keys, None, True, out=out, hit_mask=d_hit, ws=ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for it in range(2, 9):
+        keys = fresh(it)
+        d_keys.copy_(torch.from_numpy(keys))
+        if it % 3 == 0:                              # an eager call between replays advances the same count
+            p.gpu.query(n_bags, 1, d_keys, None, True, out=out, hit_mask=d_hit, ws=ws)
+            check(it, keys, "eager between replays")
+            continue
+        g.replay()
+        check(it, keys, "replay")
+    assert p.ref.stats[1] > 0 and p.ref.stats[4] > 0          # hits and evictions happened under replay
