@@ -11,8 +11,10 @@
 
 Each prints one JSON line.  Inputs are synthetic and seeded (datagen/), resident in HBM (the cache's
 backing table in pinned host memory) before anything is timed.  The inference-cache configuration
-asks for a 5e8-row host table (256 GB); --host-rows scales it (default 2e7 rows = 10 GB), the cache
-always holds 10 % of the rows in 32-way sets.
+asks for a 5e8-row host table (256 GB); the cache benchmark takes the largest table the machine pins
+(1e8 rows = 51 GB on the GPU machine; --host-rows overrides), the cache always holds 10 % of the rows in
+32-way sets.  multihot, hashed and cache also carry a roofline object for their dominant kernel, the
+oracle timed on the host cores (cpu_baseline) and an oracle check on their timed inputs.
 """
 from __future__ import annotations
 
@@ -47,6 +49,37 @@ def timeit(fn, iters=10, warm=2):
     return e0.elapsed_time(e1) / iters
 
 
+HBM_PEAK_GBS = 8000.0
+
+
+def roofline(kernel, algorithmic_bytes, ms, note, bound="hbm", traffic=None):
+    """The dominant kernel against the HBM peak: algorithmic bytes of one launch over its duration;
+    `traffic` is the profiler's HBM byte count for the launch where profiles/ holds one."""
+    gbs = algorithmic_bytes / (ms * 1e-3) / 1e9
+    return {"bound": bound, "kernel": kernel, "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
+            "measured_frac": None if traffic is None else traffic / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "algorithmic_bytes_per_launch": int(algorithmic_bytes), "avg_launch_ms": ms, "note": note}
+
+
+def stored_traffic(name):
+    """HBM bytes per launch of a kernel from the rocprofv3 --pmc summaries under profiles/ (None if absent)."""
+    path = os.path.join(ROOT, "profiles", "other_workloads_hbm_traffic.json")
+    try:
+        return json.load(open(path))["kernels"][name]["traffic_bytes_per_launch"]
+    except Exception:
+        return None
+
+
+def host_copy(table):
+    host = np.empty(tuple(table.shape), dtype={torch.float32: np.float32, torch.float16: np.float16}[table.dtype])
+    slab = 1 << 22
+    for r0 in range(0, table.shape[0], slab):
+        r1 = min(table.shape[0], r0 + slab)
+        torch.from_numpy(host[r0:r1]).copy_(table[r0:r1])
+    return host
+
+
 def multihot(h, args):
     rows_t = datagen.DLRM_TABLE_ROWS
     S, D, B = 26, 128, 65536
@@ -64,15 +97,56 @@ def multihot(h, args):
     ws = layer.new_workspace(layer.workspace_bytes(B, nnz))
     out = torch.empty((B, S, D), device=DEV)
     f = timeit(lambda: layer.forward(B, keys, offsets, out=out, ws=ws), 5, 1)
+    # CPU side first, while the table still holds what the forward read: the oracle's all-cores variant on
+    # a dense host copy of the table, over the first quarter of the samples (whole bags), forward +
+    # backward; its pooled rows are compared with the timed forward's (parity on timed inputs)
+    import oracle
+    threads = oracle.hardware_threads()
+    host = host_copy(table)
+    Bs = B // 4
+    nb = Bs * S
+    off_h = offsets[:nb + 1].cpu().numpy()
+    keys_h = keys[:int(off_h[-1])].cpu().numpy()
+    dY_h = dY.view(B * S, D)[:nb].cpu().numpy()
+    t0 = time.perf_counter()
+    rows_h, bad = oracle.rows_direct(base, rows_t, keys_h, off_h, threads=threads)
+    ref = oracle.emb_forward(host, rows_h, off_h, oracle.MEAN, threads=threads)
+    t1 = time.perf_counter()
+    got = out.view(B * S, D)[:nb].cpu().numpy()
+    mag = oracle.emb_forward(np.abs(host), rows_h, off_h, oracle.MEAN, threads=threads)
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    tol = 1e-5 * np.maximum(np.abs(ref.astype(np.float64)), mag.astype(np.float64) / 8)
+    assert bad == 0 and (err <= tol).all(), f"multi-hot forward differs from the oracle: max err {err.max():.3e}"
+    t2 = time.perf_counter()
+    oracle.emb_backward_sgd(host, rows_h, dY_h, 0.01, off_h, oracle.MEAN, threads=threads)
+    t3 = time.perf_counter()
+    cpu_s = (t1 - t0) + (t3 - t2)
+    del host, mag, ref
     d = timeit(lambda: layer.backward_dedup(B, keys, offsets, ws=ws), 5, 1)
     a = timeit(lambda: layer.backward_apply(B, nnz, dY, 0.01, offsets, ws=ws), 5, 1)
-    uniq, _ = layer.dedup_result(B, nnz, ws=ws)
+    uniq, cnt = layer.dedup_result(B, nnz, ws=ws)
+    assert int(cnt.sum()) == nnz and layer.invalid_keys(ws) == 0
+    U = int(uniq.numel())
     fwd_bytes = nnz * (8 + D * 2) + B * S * (D * 4 + 8)
-    apply_bytes = nnz * (8 + D * 4) + int(uniq.numel()) * 2 * D * 2
+    apply_bytes = nnz * (8 + D * 4) + U * 2 * D * 2
+    compulsory = nnz * 8 + B * S * D * 4 + U * 2 * D * 2      # sorted pairs once, dY once, rows read + written
+    tr = stored_traffic("bwd_reduce_windows_multihot")
     return dict(workload="multi-hot: 26 fp16 tables, dim 128, batch 65536, hotness 1..100, Zipf 1.1, mean", keys=nnz,
-                distinct_rows=int(uniq.numel()), forward_ms=f, forward_algorithmic_GBs=fwd_bytes / f / 1e6,
+                distinct_rows=U, forward_ms=f, forward_algorithmic_GBs=fwd_bytes / f / 1e6,
                 backward_dedup_ms=d, backward_apply_ms=a, backward_apply_logical_GBs=apply_bytes / a / 1e6,
-                fwd_bwd_keys_per_s=nnz / ((f + d + a) * 1e-3))
+                fwd_bwd_keys_per_s=nnz / ((f + d + a) * 1e-3),
+                metric="embedding keys/s fwd+bwd", value=nnz / ((f + d + a) * 1e-3), unit="keys/s",
+                logical_GBs=(fwd_bytes + apply_bytes) / ((f + d + a) * 1e-3) / 1e9,
+                compulsory_GBs=(nnz * 8 + U * D * 2 + B * S * (D * 4 + 8) + compulsory) / ((f + d + a) * 1e-3) / 1e9,
+                parity_checked=True, parity=dict(forward_bags_checked=nb, max_abs_err=float(err.max()),
+                                                 dedup="occurrence counts add up to the key count"),
+                roofline=roofline("bwd_reduce_windows<__half,16,UniformView<__half,float>,false> (+ bwd_carry)",
+                                  apply_bytes, a, "algorithmic = a 512-B gradient row and a 16-B sorted pair per "
+                                  "occurrence + 512 B per distinct row; compulsory (dY once) is %.2f GB" % (compulsory / 1e9),
+                                  traffic=tr),
+                cpu_baseline=dict(value=len(keys_h) / cpu_s, unit="keys/s", cores=threads, kind="oracle",
+                                  sample=f"the first {Bs} samples of the batch ({len(keys_h)} keys), key -> row + forward + "
+                                         "backward/SGD once, dense host copy of the fp16 table, all-cores variant"))
 
 
 def hashed(h, args):
@@ -113,32 +187,100 @@ def hashed(h, args):
                               keys_per_s=nnz / ((f + b) * 1e-3)))
     rows = torch.empty(nnz, dtype=torch.int64, device=DEV)
     find_ms = timeit(lambda: ht.insert_or_find(keys, False, rows=rows), 10, 2)
+    # parity on timed inputs: the rows of the last timed batch in the saturated table, against what the
+    # forward of that batch pooled (one key per bag: the pooled row is the table row; a refused key pools
+    # zeros), and the table's size
+    torch.cuda.synchronize()
+    layer.forward(B, keys, out=out, ws=ws)
+    torch.cuda.synchronize()
+    want = table[rows.clamp(min=0)] * (rows >= 0)[:, None]
+    assert torch.equal(out.view(nnz, D), want) and ht.size <= max_rows
+    # CPU side: the oracle on the first batches of the same key stream, from an empty table: key -> row by
+    # its sequential hash (one thread: first-appearance order is a sequential definition), then forward
+    # and backward on all cores over a dense host table of the rows handed out so far
+    import oracle
+    threads = oracle.hardware_threads()
+    ref = oracle.Hash(max_rows)
+    n_cpu = 3
+    host = np.zeros((n_cpu * nnz, D), dtype=np.float32)
+    host[:] = 0.03125
+    cpu_s = 0.0
+    for it in range(n_cpu):
+        k = datagen.open_space_keys(SEED, it, S, B, 1.05, device=DEV, sampler=smp).cpu().numpy()
+        g = dY.view(nnz, D).cpu().numpy()
+        t0 = time.perf_counter()
+        r = ref.insert_or_find(k, True)
+        oracle.emb_forward(host, r, threads=threads)
+        oracle.emb_backward_sgd(host, r, g, 0.01, threads=threads)
+        cpu_s += time.perf_counter() - t0
+    mid = [t for t in trace if t["load_factor"] == "0.4-0.6"] or trace
     return dict(workload="hashed open key space: capacity 1e8, max 8e7 rows, dim 64 fp32, 26 one-hot slots, "
                          "batch 131072, Zipf 1.05 over 2^63 ids, insert on miss", keys=nnz, find_only_ms=find_ms,
-                find_only_keys_per_s=nnz / find_ms * 1e3, trace=trace)
+                find_only_keys_per_s=nnz / find_ms * 1e3, trace=trace,
+                metric="embedding keys/s fwd+bwd at load factor 0.4-0.6", value=mid[0]["keys_per_s"], unit="keys/s",
+                parity_checked=True, parity=dict(rows_and_pooled_rows_of_last_batch="exact", size=ht.size),
+                roofline=roofline("hash_find (find-only call on the saturated table)", nnz * (8 + 128 + 8), find_ms,
+                                  "algorithmic = key 8 B + one 128-B bucket + row 8 B per key; random 128-B lines, "
+                                  "latency-bound", traffic=stored_traffic("hash_find")),
+                cpu_baseline=dict(value=n_cpu * nnz / cpu_s, unit="keys/s", cores=threads, kind="oracle",
+                                  sample=f"the first {n_cpu} batches of the key stream from an empty table: insert-or-find by "
+                                         "the oracle's sequential hash (one thread), forward + backward/SGD on all cores"))
+
+
+def pinned_host_table(candidates, D):
+    """The largest candidate row count this machine pins in one allocation, filled with the closed form."""
+    for host_rows in candidates:
+        try:
+            host = torch.empty((host_rows, D), dtype=torch.float32, pin_memory=True)
+        except RuntimeError:
+            continue
+        for r0 in range(0, host_rows, 1 << 21):
+            r1 = min(host_rows, r0 + (1 << 21))
+            host[r0:r1].copy_(datagen.table_rows_at(SEED, torch.arange(r0, r1, device=DEV), D, torch.float32))
+        torch.cuda.synchronize()
+        return host
+    raise RuntimeError("no candidate size of the host table could be pinned")
 
 
 def cache(h, args):
-    host_rows, D, S, hot, ways = args.host_rows, 128, 26, 4, 32
+    import oracle
+    import psutil
+    D, S, hot, ways = 128, 26, 4, 32
+    # the configuration names 5e8 rows (256 GB); the largest table this machine pins is used
+    sizes = [args.host_rows] if args.host_rows else [100_000_000, 50_000_000, 20_000_000]
+    host = pinned_host_table(sizes, D)
+    host_rows = host.shape[0]
     num_sets = host_rows // 10 // ways
-    host = torch.empty((host_rows, D), dtype=torch.float32, pin_memory=True)
-    for r0 in range(0, host_rows, 1 << 20):
-        r1 = min(host_rows, r0 + (1 << 20))
-        host[r0:r1].copy_(datagen.table_rows_at(SEED, torch.arange(r0, r1, device=DEV), D, torch.float32))
     c = h.EmbeddingCache(num_sets, ways, host)
     smp = datagen.ZipfSampler(host_rows, 1.2, DEV)
+    big = 16384 * S * hot
+    # the first calls go to the oracle's simulation too: parity on the inputs, and its time is the CPU baseline
+    ref = oracle.Cache(num_sets, ways, host.numpy())
+    n_ref, cpu_s, cpu_keys = 4, 0.0, 0
     call = 0
     for _ in range(30):   # warm up until the hit rate is stationary
-        keys = datagen.cache_keys(SEED, call, host_rows, 16384 * S * hot, 1.2, device=DEV, sampler=smp)
+        keys = datagen.cache_keys(SEED, call, host_rows, big, 1.2, device=DEV, sampler=smp)
+        hm = torch.zeros(big, dtype=torch.uint8, device=DEV)
+        o = c.query(16384, S, keys, hit_mask=hm)
+        if call < n_ref:
+            k = keys.cpu().numpy()
+            t0 = time.perf_counter()
+            ref_out, ref_hit = ref.query(k, 16384 * S, insert_missing=True)
+            cpu_s += time.perf_counter() - t0
+            cpu_keys += big
+            torch.cuda.synchronize()
+            assert np.array_equal(hm.cpu().numpy(), ref_hit) and c.stats == ref.stats.tolist(), "cache differs from the oracle"
+            err = np.abs(o.cpu().numpy().reshape(-1, D).astype(np.float64) - ref_out)
+            assert err.max() <= 1e-5 * 4 / 16 / 8 + 1e-12, f"pooled rows differ from the oracle: {err.max():.3e}"   # 4 terms of at most 1/16
         call += 1
-        c.query(16384, S, keys)
     torch.cuda.synchronize()
     sweep = []
+    side = torch.cuda.Stream()
     for batch in (1, 64, 1024, 16384):
         n = batch * S * hot
-        reps = 1000
+        reps = 1000 if batch < 16384 else 300
         ks_by_mode = {m: [datagen.cache_keys(SEED, 1000 + 2000 * j + call + i, host_rows, n, 1.2, device=DEV, sampler=smp)
-                          for i in range(reps)] for j, m in enumerate(("insert", "lookup_only"))}
+                          for i in range(reps)] for j, m in enumerate(("insert", "lookup_only", "two_phase", "replay_insert", "replay_lookup_only"))}
         o = torch.empty((batch, S, D), device=DEV)
         ws = c.workspace(n)
         hm = torch.zeros(n, dtype=torch.uint8, device=DEV)
@@ -160,10 +302,70 @@ def cache(h, args):
             res[mode] = dict(hit_rate=(s1[1] - s0[1]) / (s1[0] - s0[0]), p50_us=float(np.median(lat)),
                              p99_us=float(np.percentile(lat, 99)), gpu_p50_us=float(np.median(gpu)),
                              keys_per_s=n / np.median(lat) * 1e6)
+        # two phases: when the hit-only rows are ready (event), and when the whole query is (side stream)
+        ready = torch.cuda.Event()
+        ready.record()
+        t_hits, t_all = [], []
+        for k in ks_by_mode["two_phase"]:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            c.query_hits(batch, S, k, o, hit_mask=hm, ws=ws, ready=ready)
+            side.wait_event(ready)
+            c.query_complete(batch, S, k, o, insert_missing=True, ws=ws, stream=side)
+            ready.synchronize()
+            t_hits.append((time.perf_counter() - t0) * 1e6)
+            side.synchronize()
+            t_all.append((time.perf_counter() - t0) * 1e6)
+        res["two_phase"] = dict(hits_ready_p50_us=float(np.median(t_hits)), complete_p50_us=float(np.median(t_all)))
+        # the same query captured once in a HIP graph and replayed (small batches: launches dominate)
+        if batch <= 1024:
+            kbuf = torch.zeros(n, dtype=torch.int64, device=DEV)
+            for mode, insert in (("replay_insert", True), ("replay_lookup_only", False)):
+                g = torch.cuda.CUDAGraph()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    with torch.cuda.graph(g, stream=side):
+                        c.query(batch, S, kbuf, None, insert, out=o, hit_mask=hm, ws=ws, stream=side)
+                torch.cuda.current_stream().wait_stream(side)
+                lat = []
+                for k in ks_by_mode[mode]:
+                    kbuf.copy_(k)
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    g.replay()
+                    torch.cuda.synchronize()
+                    lat.append((time.perf_counter() - t0) * 1e6)
+                res[mode] = dict(p50_us=float(np.median(lat)), p99_us=float(np.percentile(lat, 99)))
+                del g
         sweep.append(dict(batch=batch, keys=n, queries=reps,
                           **{f"{m}_{k}": v for m, r in res.items() for k, v in r.items()}))
-    return dict(workload=f"inference cache: {host_rows} x 128 fp32 host table (pinned), cache 10% in 32-way sets, "
-                         "26 slots x hotness 4, Zipf 1.2; latency = host call + stream sync, gpu = event pair around the call", sweep=sweep)
+    # CPU baseline on small batches too (the oracle's own, partly warm cache)
+    small_cpu = {}
+    for batch in (1, 64, 1024):
+        n = batch * S * hot
+        ks = [datagen.cache_keys(SEED, 9000 + i, host_rows, n, 1.2, sampler=smp, device=DEV).cpu().numpy() for i in range(20)]
+        t0 = time.perf_counter()
+        for k in ks:
+            ref.query(k, batch * S, insert_missing=True)
+        small_cpu[str(batch)] = n * len(ks) / (time.perf_counter() - t0)
+    last = sweep[-1]
+    look_ms = last["lookup_only_gpu_p50_us"] * 1e-3
+    n = last["keys"]
+    alg = n * (8 + ways * 8 + 4 + 9 + D * 4 + 4) + 16384 * S * D * 4
+    return dict(workload=f"inference cache: {host_rows} x 128 fp32 host table ({host_rows * D * 4 / 1e9:.1f} GB pinned; the "
+                         f"configuration names 5e8 rows = 256 GB, this machine has {psutil.virtual_memory().total / 2**30:.0f} GiB of "
+                         "RAM and pins at most 64 GiB in one allocation), cache 10% in 32-way sets, 26 slots x hotness 4, "
+                         "Zipf 1.2; latency = host call + stream sync, gpu = event pair around the call", sweep=sweep,
+                host_rows=host_rows, cache_lines=num_sets * ways,
+                metric="cache query keys/s at batch 16384, lookup only", value=last["lookup_only_keys_per_s"], unit="keys/s",
+                parity_checked=True, parity=dict(calls_compared_with_the_oracle=n_ref, what="hit mask, statistics, pooled rows"),
+                roofline=roofline("cache_probe<32> + cache_gather<32,4> (lookup-only call of 16,384 samples)", alg, look_ms,
+                                  "algorithmic = per key 8 (key) + 256 (tags of the set) + 4 + 9 (line, mask, flag) + 4 + 512 (row); "
+                                  "per bag 512 written; missing rows cross the host link", traffic=stored_traffic("cache_lookup_16384")),
+                cpu_baseline=dict(value=cpu_keys / cpu_s, unit="keys/s", cores=1, kind="oracle",
+                                  sample=f"the first {n_ref} calls of 16,384 samples ({big} keys each) from a cold cache, query + insertion; "
+                                         "the simulation is sequential by definition (one thread)",
+                                  small_batches_keys_per_s=small_cpu))
 
 
 def mixed(h, args):
@@ -204,7 +406,7 @@ def mixed(h, args):
 
 
 def etc(h, args):
-    host_rows, D, S, B, per_pass = args.host_rows, 128, 26, 55296, 8
+    host_rows, D, S, B, per_pass = args.host_rows or 20_000_000, 128, 26, 55296, 8
     host = torch.empty((host_rows, D), dtype=torch.float32, pin_memory=True)
     for r0 in range(0, host_rows, 1 << 20):
         r1 = min(host_rows, r0 + (1 << 20))
@@ -317,7 +519,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group", "mixed", "etc", "fwd_probe"])
     ap.add_argument("--etc-passes", type=int, default=4)
-    ap.add_argument("--host-rows", type=int, default=20_000_000)
+    ap.add_argument("--host-rows", type=int, default=0,
+                    help="rows of the pinned host table (cache: default = the largest of 1e8 / 5e7 / 2e7 that can be "
+                         "pinned; training cache: default 2e7)")
     ap.add_argument("--hash-batches", type=int, default=100)
     args = ap.parse_args()
     if not torch.cuda.is_available():
