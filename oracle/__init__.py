@@ -22,11 +22,35 @@ EMPTY_TAG = np.uint64(0xFFFFFFFFFFFFFFFF)
 
 
 def build(force: bool = True) -> str:
-    """Compile oracle.cpp with g++ (no GPU toolchain involved)."""
+    """Compile oracle.cpp with g++ (no GPU toolchain involved).  With HCTR_SANITIZE=1 in the
+    environment the library is built with UndefinedBehaviorSanitizer (any finding aborts), so the
+    whole test suite can run on an instrumented oracle; AddressSanitizer cannot be loaded into a
+    running Python, see sanitize_check() for that."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-pthread", "-Wall", "-Wextra",
-                               _SRC, "-o", _LIB])
+        extra = []
+        if os.environ.get("HCTR_SANITIZE") == "1":
+            extra = ["-g", "-fsanitize=undefined", "-fno-sanitize-recover=undefined"]
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-pthread", "-Wall", "-Wextra"] + extra +
+                              [_SRC, "-o", _LIB])
     return _LIB
+
+
+def sanitize_check() -> str:
+    """Builds oracle.cpp with sanitize_driver.cpp as one program under AddressSanitizer and
+    UndefinedBehaviorSanitizer and runs it: the driver calls every function of the oracle on small
+    seeded inputs.  Returns the program's output; raises if it reports anything."""
+    out_dir = os.path.join(_HERE, "_build")
+    os.makedirs(out_dir, exist_ok=True)
+    exe = os.path.join(out_dir, "sanitize_driver")
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-pthread", "-Wall", "-Wextra",
+                           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+                           "-static-libasan", "-static-libubsan",
+                           _SRC, os.path.join(_HERE, "sanitize_driver.cpp"), "-o", exe])
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    done = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=600)
+    if done.returncode != 0:
+        raise RuntimeError(f"sanitizer run failed ({done.returncode}):\n{done.stdout}\n{done.stderr}")
+    return done.stdout
 
 
 _lib = None

@@ -63,6 +63,42 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_sanitized(driver_src: str) -> str:
+    """The library with its HOST code under AddressSanitizer and UndefinedBehaviorSanitizer (device code
+    as usual), as _build/libhctr_san.so, and `driver_src` linked against it as _build/abi_sanitize_driver.
+    Returns the driver's path.  For the CPU-side checks of the argument validation: the driver makes only
+    calls that the host answers before any launch, so it runs without a GPU."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ, exist_ok=True)
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+           "-fno-sanitize-recover=all", "-g"]
+    lib_san = os.path.join(OBJ, "libhctr_san.so")
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(OBJ, os.path.basename(src) + ".san.o")
+        subprocess.run([hipcc] + [f for f in FLAGS if f != "-O3"] + ["-O1"] + san + ["-x", "hip", "-c"] + inc +
+                       [src, "-o", obj], check=True, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:
+        objs = list(pool.map(compile_one, sources()))
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined",
+                           "-shared-libsan"] + objs + ["-o", lib_san])
+    exe = os.path.join(OBJ, "abi_sanitize_driver")
+    # the sanitizer runtime as a shared library, found through the run path (it lies in the compiler's tree)
+    rt = subprocess.run([hipcc, "-print-file-name=libclang_rt.asan-x86_64.so"], check=True, capture_output=True,
+                        text=True).stdout.strip()
+    if not os.path.isabs(rt):
+        import glob
+        found = glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so")
+        rt = found[0] if found else rt
+    subprocess.check_call([hipcc, "-x", "c++", "-std=c++17", "-g", "-fsanitize=address", "-fsanitize=undefined",
+                           "-fno-sanitize-recover=all", "-shared-libsan"] + inc + [driver_src, "-x", "none", lib_san,
+                           "-Wl,-rpath," + OBJ, "-Wl,-rpath," + os.path.dirname(rt), "-o", exe])
+    return exe
+
+
 if __name__ == "__main__":
     build(verbose=True)
     print(LIB)
