@@ -465,7 +465,9 @@ def fwd_probe(h, args):
 
     run("all keys name one row", torch.zeros(nnz, dtype=torch.int64, device=DEV))
     for hot in (1 << 10, 1 << 14, 1 << 18, 1 << 22):
-        run(f"uniform over {hot} rows spread over the table", torch.randint(0, hot, (nnz,), device=DEV) * (total // hot))
+        idx = torch.randint(0, hot, (nnz,), device=DEV)
+        run(f"uniform over {hot} rows spread over the table", idx * (total // hot))
+        run(f"uniform over {hot} rows in one stretch of the table", idx)   # same reuse, addresses close together
     run("distinct random rows", torch.randperm(total, device=DEV)[:nnz])
     run("consecutive rows", torch.arange(nnz, device=DEV))
     flat, src = out.view(-1), torch.empty(nnz * D, device=DEV)
