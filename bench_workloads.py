@@ -7,6 +7,7 @@
     python bench_workloads.py mixed      # headline shape in mixed precision: fp16 table + fp32 master rows, fp16 out / dY
     python bench_workloads.py etc        # training cache staged in host memory: load / train / dump passes of 8 batches
     python bench_workloads.py fwd_probe  # the forward kernel on key patterns of known locality (what bounds it)
+    python bench_workloads.py placement  # how much the physical placement of the buffers moves the timings
     python bench_workloads.py group      # fused group: the 26 DLRM-sized tables with widths 128/64/32/16, dense one-hot input
 
 Each prints one JSON line.  Inputs are synthetic and seeded (datagen/), resident in HBM (the cache's
@@ -127,6 +128,14 @@ def multihot(h, args):
     uniq, cnt = layer.dedup_result(B, nnz, ws=ws)
     assert int(cnt.sum()) == nnz and layer.invalid_keys(ws) == 0
     U = int(uniq.numel())
+    # the same batch with fp16 pooled output and fp16 upstream gradient (sums still formed in fp32)
+    half = h.EmbeddingLayer(table, S, h.MEAN, base, rows_t, io_dtype=torch.float16)
+    out16 = torch.empty((B, S, D), dtype=torch.float16, device=DEV)
+    dY16 = dY.to(torch.float16)
+    f16 = timeit(lambda: half.forward(B, keys, offsets, out=out16, ws=ws), 5, 1)
+    half.backward_dedup(B, keys, offsets, ws=ws)
+    a16 = timeit(lambda: half.backward_apply(B, nnz, dY16, 0.01, offsets, ws=ws), 5, 1)
+    del out16, dY16
     fwd_bytes = nnz * (8 + D * 2) + B * S * (D * 4 + 8)
     apply_bytes = nnz * (8 + D * 4) + U * 2 * D * 2
     compulsory = nnz * 8 + B * S * D * 4 + U * 2 * D * 2      # sorted pairs once, dY once, rows read + written
@@ -138,6 +147,7 @@ def multihot(h, args):
                 metric="embedding keys/s fwd+bwd", value=nnz / ((f + d + a) * 1e-3), unit="keys/s",
                 logical_GBs=(fwd_bytes + apply_bytes) / ((f + d + a) * 1e-3) / 1e9,
                 compulsory_GBs=(nnz * 8 + U * D * 2 + B * S * (D * 4 + 8) + compulsory) / ((f + d + a) * 1e-3) / 1e9,
+                fp16_io=dict(forward_ms=f16, backward_apply_ms=a16, fwd_bwd_keys_per_s=nnz / ((f16 + d + a16) * 1e-3)),
                 parity_checked=True, parity=dict(forward_bags_checked=nb, max_abs_err=float(err.max()),
                                                  dedup="occurrence counts add up to the key count"),
                 roofline=roofline("bwd_reduce_windows<__half,16,UniformView<__half,float>,false> (+ bwd_carry)",
@@ -278,7 +288,7 @@ def cache(h, args):
     side = torch.cuda.Stream()
     for batch in (1, 64, 1024, 16384):
         n = batch * S * hot
-        reps = 1000 if batch < 16384 else 300
+        reps = min(args.cache_reps, 1000 if batch < 16384 else 300)
         ks_by_mode = {m: [datagen.cache_keys(SEED, 1000 + 2000 * j + call + i, host_rows, n, 1.2, device=DEV, sampler=smp)
                           for i in range(reps)] for j, m in enumerate(("insert", "lookup_only", "two_phase", "replay_insert", "replay_lookup_only"))}
         o = torch.empty((batch, S, D), device=DEV)
@@ -479,6 +489,78 @@ def fwd_probe(h, args):
                          "of known locality", patterns=res)
 
 
+def placement(h, args):
+    """How much the physical placement of the buffers matters on this machine: (1) a plain device copy of
+    the headline's output size at many distances between source and destination inside one allocation;
+    (2) the headline step with the 85 GB table freed and allocated again; (3) the forward with its output
+    at many offsets inside one allocation."""
+    MB = 1 << 20
+    nb = 55296 * 26 * 128 * 4
+
+    def copy_rate(src, dst, n=10):
+        ms = timeit(lambda: dst.copy_(src), n, 2)
+        return 2 * nb / ms / 1e9                                  # TB/s
+
+    pool = torch.empty(14 * 1024 * MB, dtype=torch.uint8, device=DEV)
+    src = pool[0:nb].view(torch.float32)
+    by_offset = [(d, copy_rate(src, pool[d * MB:d * MB + nb].view(torch.float32))) for d in range(768, 12 * 1024, 32)]
+    del pool, src
+    torch.cuda.empty_cache()
+    slow = [d for d, r in by_offset if r < 4.8]
+    res = dict(copy_TBs_max=max(r for _, r in by_offset), copy_TBs_min=min(r for _, r in by_offset),
+               copy_offsets_probed=len(by_offset), copy_slow_offsets_MB=slow[:16],
+               copy_slow_offsets_mod_128MB=sorted({d % 128 for d in slow}))
+    rows_t = datagen.DLRM_TABLE_ROWS
+    S, D, B = 26, 128, 55296
+    ro = datagen.row_offsets(rows_t)
+    base, total = ro[:-1].copy(), int(ro[-1])
+    nnz = B * S
+    smp = datagen.make_samplers(rows_t, 1.05)
+    keys = [datagen.onehot_keys(SEED, b, rows_t, B, 1.05, samplers=smp).to(DEV) for b in range(8)]
+    del smp
+
+    def step_times(table, out, dYs, n=40):
+        layer = h.EmbeddingLayer(table, S, h.SUM, base, rows_t)
+        ws = layer.new_workspace(layer.workspace_bytes(B, nnz))
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n)]
+        for i in range(n):
+            ev[i][0].record()
+            layer.forward(B, keys[i % 8], out=out, ws=ws)
+            ev[i][1].record()
+            layer.backward_sgd(B, keys[i % 8], dYs[i % 2], 1e-6, ws=ws)
+            ev[i][2].record()
+        torch.cuda.synchronize()
+        return (float(np.median([e[0].elapsed_time(e[1]) for e in ev[5:]])) * 1e3,
+                float(np.median([e[1].elapsed_time(e[2]) for e in ev[5:]])) * 1e3)
+
+    trials = []
+    for trial in range(4):
+        table = torch.empty((total, D), dtype=torch.float32, device=DEV)
+        table.fill_(0.25)
+        dYs = [torch.randn((B, S, D), device=DEV) for _ in range(2)]
+        out = torch.empty((B, S, D), device=DEV)
+        f, b = step_times(table, out, dYs)
+        trials.append(dict(trial=trial, table_at=hex(table.data_ptr()), forward_us=f, backward_us=b))
+        if trial == 3:   # the forward alone, output at 64 offsets inside one allocation
+            pool = torch.empty(nb + 520 * MB, dtype=torch.uint8, device=DEV)
+            layer = h.EmbeddingLayer(table, S, h.SUM, base, rows_t)
+            ws = layer.new_workspace(layer.workspace_bytes(B, nnz))
+            it = [0]
+
+            def fwd(o):
+                layer.forward(B, keys[it[0] % 8], out=o, ws=ws)
+                it[0] += 1
+            outs = [timeit(lambda: fwd(pool[d * MB:d * MB + nb].view(torch.float32).view(B, S, D)), 16, 4) * 1e3
+                    for d in range(0, 512, 8)]
+            res["forward_us_over_64_output_offsets"] = [min(outs), max(outs)]
+            del pool
+        del table, dYs, out
+        torch.cuda.empty_cache()
+    res["step_after_reallocating_the_table"] = trials
+    return dict(workload="placement probes: device copy by source-destination distance; headline step with the table "
+                         "allocated again; forward by output offset", **res)
+
+
 def group(h, args):
     rows_t = datagen.DLRM_TABLE_ROWS
     B, L = 55296, len(rows_t)
@@ -519,18 +601,20 @@ def group(h, args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group", "mixed", "etc", "fwd_probe"])
+    ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group", "mixed", "etc", "fwd_probe", "placement"])
     ap.add_argument("--etc-passes", type=int, default=4)
     ap.add_argument("--host-rows", type=int, default=0,
                     help="rows of the pinned host table (cache: default = the largest of 1e8 / 5e7 / 2e7 that can be "
                          "pinned; training cache: default 2e7)")
     ap.add_argument("--hash-batches", type=int, default=100)
+    ap.add_argument("--cache-reps", type=int, default=1000, help="queries per batch size and mode (fewer under a profiler)")
     args = ap.parse_args()
     if not torch.cuda.is_available():
         print("bench_workloads.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(2)
     import paper_2210_08803_amd as h
-    res = {"multihot": multihot, "hashed": hashed, "cache": cache, "group": group, "mixed": mixed, "etc": etc, "fwd_probe": fwd_probe}[args.workload](h, args)
+    res = {"multihot": multihot, "hashed": hashed, "cache": cache, "group": group, "mixed": mixed, "etc": etc, "fwd_probe": fwd_probe,
+           "placement": placement}[args.workload](h, args)
     res["n_gpus"] = 1
     res["data"] = "synthetic"
     print(json.dumps(res), flush=True)
