@@ -45,7 +45,7 @@ typedef enum {
   HCTR_OK = 0,
   HCTR_E_INVALID_ARG = -1,
   HCTR_E_NULL_PTR = -2,
-  HCTR_E_WORKSPACE = -3,   /* workspace missing, misaligned (256 B) or too small */
+  HCTR_E_WORKSPACE = -3,   /* workspace missing, misaligned (256 B), too small or never initialised */
   HCTR_E_UNSUPPORTED = -4,
   HCTR_E_DEVICE = -5
 } hctr_status;
@@ -102,8 +102,10 @@ typedef struct {
 size_t hctr_emb_workspace_bytes(const hctr_emb_desc* desc, int64_t batch, int64_t nnz_max);
 
 /* Must run once on a fresh workspace before its first use (it zeroes the counter of keys without
- * a row, which forward and backward only ever add to); calling it again resets that counter and
- * forgets the last dedup result. */
+ * a row, which forward and backward only ever add to, and marks the workspace as counted); calling
+ * it again resets that counter and forgets the last dedup result.  Forward and backward themselves
+ * compute the same results on a workspace that skipped this call (they never read the counter), but
+ * hctr_emb_invalid_keys then returns HCTR_E_WORKSPACE instead of a number. */
 hctr_status hctr_emb_workspace_init(void* ws, size_t ws_bytes, void* stream);
 
 /*
@@ -179,7 +181,9 @@ hctr_status hctr_check_offsets(const int64_t* offsets, int64_t n_bags, int64_t n
                                void* stream);
 
 /* Number of keys without a row seen by all forward and backward calls on `ws` since
- * hctr_emb_workspace_init (host int64; waits for the stream). */
+ * hctr_emb_workspace_init (host int64; waits for the stream).  HCTR_E_WORKSPACE if `ws` does not
+ * carry the mark that hctr_emb_workspace_init leaves (the memory was never initialised, or was
+ * overwritten since). */
 hctr_status hctr_emb_invalid_keys(const void* ws, size_t ws_bytes, void* stream, int64_t* count);
 
 /*

@@ -25,7 +25,7 @@ constexpr uint32_t kInvalidParts = 1024;
 
 // First 256 bytes of an embedding workspace; kInvalidParts 8-byte counters follow.
 struct EmbHeader {
-  unsigned long long reserved;
+  unsigned long long mark;     // kEmbMark once hctr_emb_workspace_init has run on this memory
   long long num_unique;        // U of the last backward
   uint32_t n_valid;            // sorted positions holding a real row
   uint32_t n_long;             // rows whose carry is left to whole blocks (0 between backward calls)
@@ -34,6 +34,7 @@ struct EmbHeader {
 };
 static_assert(sizeof(EmbHeader) == 256, "header is one 256-byte block");
 constexpr size_t kEmbHeadBytes = sizeof(EmbHeader) + kInvalidParts * 8;
+constexpr unsigned long long kEmbMark = 0x57424d4552544348ull;   // "HCTREMBW"
 
 // Adds a wave's count of keys without a row (call with the wave's total in every lane).
 __device__ __forceinline__ void add_invalid(EmbHeader* hdr, uint32_t wave_total) {
@@ -48,6 +49,7 @@ __global__ __launch_bounds__(256) void emb_init_header(EmbHeader* hdr, uint32_t*
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
   if (reset_invalid && i < kInvalidParts) reinterpret_cast<unsigned long long*>(hdr + 1)[i] = 0;
   if (i == 0) {
+    if (reset_invalid) hdr->mark = kEmbMark;
     hdr->num_unique = 0;
     hdr->n_valid = 0;
     hdr->n_long = 0;
@@ -165,6 +167,15 @@ __global__ __launch_bounds__(HASHED ? 256 : 512) void fwd_onehot(const T* __rest
 // Forward, CSR bags: one wave per bag.  The wave's 64/LPR lane groups take the bag's keys round
 // robin, U keys each per step; the groups' partial sums are staged in LDS and added in group order
 // by group 0, which scales (mean) and writes the pooled row.
+//
+// With every row served by the caches the kernel takes 85 % of the time it takes on real keys: what
+// bounds it is the number of vector instructions it issues, not memory.  So everything that is the
+// same for the whole wave (bag, slot, offsets, loop bounds) is derived from scalar registers - the
+// slot comes from blockIdx.z when the bags are walked slot by slot, which also spares two integer
+// divisions per wave - and the steps in which every lane has a row to fetch, nearly all of them,
+// take a path without per-row tests: the row id by one ds_bpermute at a precomputed index, the
+// address by one 32 x 32 -> 64 bit multiply-add, then the adds.  Nothing crosses waves, so a wave
+// past the end leaves at once and no wave waits for the longest bag of its block.
 // ------------------------------------------------------------------------------------------------
 template <typename T, typename OutT, int LPR, int U, bool HASHED>
 __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int D, int64_t total_rows,
@@ -175,30 +186,40 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
                                                OutT* __restrict__ out, EmbHeader* hdr) {
   constexpr int VEC = RowVec<T>::VEC;
   constexpr int G = 64 / LPR;
+  constexpr int STEP = G * U;   // keys of one step of the wave (a power of two)
   __shared__ float part[4][(G > 1 ? (G - 1) : 1) * LPR * VEC];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int g = lane / LPR, sub = lane % LPR;
   const int col = blockIdx.y * (LPR * VEC) + sub * VEC;
   const bool active = col < D;
-  const uint32_t bag = walk_to_bag(blockIdx.x * 4u + wave, n_bags, S, n_samples);
-  const bool live = bag < n_bags;
-  int64_t b0 = 0, b1 = 0, base = 0, num = 0;
-  if (live) {
-    b0 = offsets[bag];
-    b1 = offsets[bag + 1];
-    if (!HASHED) {
-      const uint32_t s = bag % S;
-      base = slots.base[s];
-      num = slots.num[s];
-    }
+  const bool all_active = (int)((blockIdx.y + 1u) * (uint32_t)(LPR * VEC)) <= D;   // the whole wave holds columns
+  uint32_t bag, s;
+  if (n_samples != 0) {   // slot by slot: grid z is the slot, x the sample
+    const uint32_t sample = blockIdx.x * 4u + wave;
+    if (sample >= n_samples) return;
+    s = blockIdx.z;
+    bag = sample * S + s;
+  } else {
+    bag = blockIdx.x * 4u + wave;
+    if (bag >= n_bags) return;
+    s = bag % S;
+  }
+  const int64_t b0 = offsets[bag], b1 = offsets[bag + 1];
+  int64_t base = 0, num = 0;
+  if (!HASHED) {
+    base = slots.base[s];
+    num = slots.num[s];
   }
   float acc[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
   // 1.0f that the compiler cannot see through: acc + x written as fma(x, one, acc) is the same sum
   // bit for bit, and with fp16 rows the conversion rides along in the one instruction
-  // (v_fma_mix_f32) instead of taking one of its own - the kernel is bound by such instructions.
+  // (v_fma_mix_f32) instead of taking one of its own.
   const float one = D > 0 ? 1.0f : 0.0f;
+  const char* lane_base = reinterpret_cast<const char*>(table) + (int64_t)col * (int64_t)sizeof(T);
+  const uint32_t row_bytes = (uint32_t)D * (uint32_t)sizeof(T);
   uint32_t nbad = 0;
   // 64 keys at a time: one coalesced key load and one row computation per lane, then the groups
   // pick their rows from the lanes by shuffle, U row loads each in flight.
@@ -215,7 +236,49 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
       }
       nbad += myrow == kNoRow ? 1u : 0u;
     }
-    for (int j0 = 0; j0 < cnt; j0 += G * U) {   // same trip count for every lane: the shuffles need all lanes
+    int j0 = 0;
+    if (all_active && __ballot(lane < cnt && myrow == kNoRow) == 0) {
+      // whole steps: lane group g takes keys j0 + g, j0 + g + G, ... of the chunk, all of them there
+      const int full = cnt & ~(STEP - 1);
+      for (; j0 < full; j0 += STEP) {
+        typename RowVec<T>::Raw raw[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const uint32_t r = (uint32_t)__builtin_amdgcn_ds_bpermute((j0 + g + u * G) << 2, (int)myrow);
+          raw[u] = RowVec<T>::load_raw(reinterpret_cast<const T*>(lane_base + (uint64_t)r * row_bytes));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          float v[VEC];
+          RowVec<T>::widen(raw[u], v);
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) acc[i] = __builtin_fmaf(v[i], one, acc[i]);
+        }
+      }
+      if (j0 < cnt) {
+        // the chunk's last, partial step: the lanes past the chunk's end hold kNoRow, so a group
+        // whose turn lies past the end picks that up, fetches the start of row 0 and leaves it out
+        typename RowVec<T>::Raw raw[U];
+        bool there[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const uint32_t r = (uint32_t)__builtin_amdgcn_ds_bpermute((j0 + g + u * G) << 2, (int)myrow);
+          there[u] = r != kNoRow;
+          raw[u] = RowVec<T>::load_raw(reinterpret_cast<const T*>(lane_base + (uint64_t)(there[u] ? r : 0u) * row_bytes));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          float v[VEC];
+          RowVec<T>::widen(raw[u], v);
+          if (there[u]) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = __builtin_fmaf(v[i], one, acc[i]);
+          }
+        }
+        j0 = cnt;
+      }
+    }
+    for (; j0 < cnt; j0 += STEP) {   // same trip count for every lane: the shuffles need all lanes
       uint32_t row[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -241,11 +304,15 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
     }
   }
   if (G > 1) {
+    // The groups' sums meet in LDS, within the wave: a wave's LDS accesses are carried out in the
+    // order it issues them, and the fences keep the compiler from moving the reads above the writes.
     if (g > 0) {
 #pragma unroll
       for (int i = 0; i < VEC; ++i) part[wave][((g - 1) * LPR + sub) * VEC + i] = acc[i];
     }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     if (g == 0) {
 #pragma unroll
       for (int gg = 1; gg < G; ++gg)
@@ -253,7 +320,7 @@ __global__ __launch_bounds__(256) void fwd_csr(const T* __restrict__ table, int 
         for (int i = 0; i < VEC; ++i) acc[i] += part[wave][((gg - 1) * LPR + sub) * VEC + i];
     }
   }
-  if (live && g == 0 && active) {
+  if (g == 0 && active) {
     if (mean && b1 > b0) {
       const float w = 1.0f / (float)(b1 - b0);
 #pragma unroll
@@ -1234,7 +1301,9 @@ static void launch_forward(const hctr_emb_desc* d, const int64_t* keys, const in
                          d->total_rows, keys, rows64, n_bags, S, n_samples, st, out, hdr);
   } else {
     constexpr int U = 4;
-    dim3 grid((uint32_t)ceil_div(n_bags, 4), ychunks);
+    // four bags (waves) per block; slot by slot: x counts the samples, z the slots
+    const dim3 grid = n_samples ? dim3((uint32_t)ceil_div(n_samples, 4), ychunks, S)
+                                : dim3((uint32_t)ceil_div(n_bags, 4), ychunks, 1);
     const int mean = d->combiner == HCTR_MEAN;
     if (rows64)
       hipLaunchKernelGGL((fwd_csr<T, OutT, LPR, U, true>), grid, dim3(256), 0, stream, table, d->dim,
@@ -1502,10 +1571,16 @@ HCTR_API hctr_status hctr_emb_workspace_init(void* ws, size_t ws_bytes, void* st
 HCTR_API hctr_status hctr_emb_invalid_keys(const void* ws, size_t ws_bytes, void* stream, int64_t* count) {
   if (!ws || !count) return fail(HCTR_E_NULL_PTR, "NULL argument");
   if (ws_bytes < kEmbHeadBytes) return fail(HCTR_E_WORKSPACE, "workspace too small");
-  unsigned long long parts[kInvalidParts];
-  HCTR_TRY_HIP(hipMemcpyAsync(parts, static_cast<const char*>(ws) + sizeof(EmbHeader), sizeof(parts),
-                              hipMemcpyDeviceToHost, static_cast<hipStream_t>(stream)));
+  // header and counters in one copy: the mark tells a workspace that never went through
+  // hctr_emb_workspace_init (whose counters hold whatever the memory held) from a counted one
+  static_assert(sizeof(EmbHeader) % 8 == 0, "counters follow the header as 8-byte words");
+  constexpr uint32_t kHeadWords = sizeof(EmbHeader) / 8;
+  unsigned long long words[kHeadWords + kInvalidParts];
+  HCTR_TRY_HIP(hipMemcpyAsync(words, ws, sizeof(words), hipMemcpyDeviceToHost, static_cast<hipStream_t>(stream)));
   HCTR_TRY_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  if (words[0] != kEmbMark)
+    return fail(HCTR_E_WORKSPACE, "workspace was never initialised (hctr_emb_workspace_init): its counters mean nothing");
+  const unsigned long long* parts = words + kHeadWords;
   unsigned long long v = 0;
   for (uint32_t i = 0; i < kInvalidParts; ++i) v += parts[i];
   *count = (int64_t)v;

@@ -132,6 +132,31 @@ def test_keys_without_a_row():
     assert info["nnz"] == 1500
 
 
+def test_a_workspace_that_was_never_initialised_is_named():
+    """Forward and backward work on raw memory (they never read the counter of keys without a row);
+    asking for that counter is what fails, and initialising afterwards makes it count."""
+    h = H()
+    rows, dim, batch = [50, 70], 8, 40
+    ro = datagen.row_offsets(rows)
+    table = to_dev(datagen.table_rows_at(SEED, torch.arange(int(ro[-1])), dim, torch.float32))
+    layer = h.EmbeddingLayer(table, 2, 0, ro[:-1].copy(), np.asarray(rows, dtype=np.int64))
+    keys = datagen.onehot_keys(SEED, 0, rows, batch, 1.05)
+    keys[3] = -5
+    d_keys = to_dev(keys)
+    raw = torch.full((layer.workspace_bytes(batch, keys.numel()),), 0xA5, dtype=torch.uint8, device="cuda")
+    out_raw = layer.forward(batch, d_keys, ws=raw)
+    with pytest.raises(h.HctrError) as e:
+        layer.invalid_keys(raw)
+    assert e.value.status == -3 and "initialised" in str(e.value)
+    good = layer.new_workspace(raw.numel())
+    out_good = layer.forward(batch, d_keys, ws=good)
+    assert torch.equal(out_raw, out_good)
+    assert layer.invalid_keys(good) == 1
+    layer.reset_invalid_keys(raw)
+    layer.forward(batch, d_keys, ws=raw)
+    assert layer.invalid_keys(raw) == 1
+
+
 def test_every_key_equal_one_long_segment():
     """All 9,000 keys hit one row: a segment spanning hundreds of windows and several sort tiles."""
     info = run_case([1], 128, 9000)
