@@ -3,6 +3,7 @@
 // by a group of LPR adjacent lanes (LPR * 16 bytes >= row bytes), and several independent row
 // loads are in flight per lane before the first use.
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 #include "rowvec.h"
@@ -663,6 +664,7 @@ static_assert(sizeof(GroupLookup) == 24, "kernel-argument layout");
 template <typename T, typename DyT>
 struct UniformView {
   static constexpr int kLds = 1;
+  static constexpr bool kUniform = true;   // one table, one row width, one combiner for all bags
   T* table;
   float* master;   // fp32 copy of an fp16 table that takes the update (the table row is its rounding), or NULL
   const DyT* dY;
@@ -700,6 +702,7 @@ struct UniformView {
 template <typename T>
 struct GroupView {
   static constexpr int kLds = HCTR_MAX_GROUP_LOOKUPS;
+  static constexpr bool kUniform = false;
   const float* dY;
   uint32_t L;
   uint32_t width_total;
@@ -793,6 +796,13 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
   bool wrote_tail = false;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   constexpr int UB = 4;   // occurrences per step: UB dY loads (+ the table rows that finish) in flight
+  // for the steps that only add (uniform views): this lane's piece of gradient row 0, the bytes of a
+  // gradient row, the first lane of the group, and whether every lane of the wave holds columns
+  typedef typename std::remove_const<typename std::remove_pointer<decltype(view.dY)>::type>::type DyPiece;
+  const char* dy_lane = reinterpret_cast<const char*>(view.dY) + (int64_t)col * (int64_t)sizeof(DyPiece);
+  const uint32_t dy_row_bytes = (uint32_t)DM * (uint32_t)sizeof(DyPiece);
+  const uint32_t grp_lane0 = (threadIdx.x & 63u) & ~(uint32_t)(LPR - 1);
+  const bool all_cols = (int)((blockIdx.y + 1u) * (uint32_t)(LPR * 4)) <= DM;
 
   for (uint32_t p0 = start; p0 < end; p0 += LPR) {
     const int cnt = (end - p0 < (uint32_t)LPR) ? (int)(end - p0) : LPR;
@@ -810,7 +820,38 @@ __global__ __launch_bounds__(256) void bwd_reduce_windows(
         myw = 1.0f / (stored ? (float)stored : (float)(offsets[mybag + 1] - offsets[mybag]));
       }
     }
+    // Positions at which a step cannot simply add: a run of equal rows ends there, or the chunk does.
+    const uint64_t stops = __ballot(sub >= cnt || mynext != myrow);
     for (int q0 = 0; q0 < cnt; q0 += UB) {
+      if constexpr (View::kUniform && !ONCE) {
+        // Most occurrences of a batch with several keys per bag lie inside long runs of one row,
+        // and there the kernel is bound by the vector instructions it issues.  A step in which no
+        // group of the wave meets a stop only adds: bag (and weight) by one ds_bpermute each at a
+        // precomputed index, the address by one multiply-add, the load, four adds.
+        const uint32_t q0u = __builtin_amdgcn_readfirstlane(q0);
+        constexpr uint64_t kGroupBit0 = LPR == 64 ? 1ull : 0xFFFFFFFFFFFFFFFFull / ((1ull << (LPR & 63)) - 1ull);
+        const uint64_t step = (kGroupBit0 * ((1ull << UB) - 1ull)) << q0u;
+        if ((stops & step) == 0 && all_cols) {
+          Raw4 vr[UB];
+          float w[UB];
+#pragma unroll
+          for (int u = 0; u < UB; ++u) {
+            const int at = (int)((grp_lane0 + q0u + (uint32_t)u) << 2);
+            const uint32_t bg = (uint32_t)__builtin_amdgcn_ds_bpermute(at, (int)mybag);
+            w[u] = view.mean ? __int_as_float(__builtin_amdgcn_ds_bpermute(at, __float_as_int(myw))) : 1.f;
+            const DyPiece* g = reinterpret_cast<const DyPiece*>(dy_lane + (uint64_t)bg * dy_row_bytes);
+            if constexpr (ONCE) vr[u] = load_stream_raw4(g);
+            else vr[u] = load_raw4(g);
+          }
+#pragma unroll
+          for (int u = 0; u < UB; ++u) {
+            const f32x4 v = widen4(vr[u], static_cast<const DyPiece*>(nullptr));
+            acc.x += w[u] * v.x; acc.y += w[u] * v.y;
+            acc.z += w[u] * v.z; acc.w += w[u] * v.w;
+          }
+          continue;
+        }
+      }
       // All loads of the step raw and first - the UB gradient pieces without a branch (a lane past
       // the row's width reads the row's first piece and leaves it out), the table rows that end
       // here under their branch but with nothing else in it - and widened only afterwards.
