@@ -1052,7 +1052,11 @@ struct GroupFwdArgs {
 // A thread works on NQ quads at a time (the same columns of NQ samples a grid stride apart) and
 // keeps one key and one row load per quad in flight; with dense input the bag bounds are computed,
 // not loaded, so a one-hot lookup costs two dependent loads (key, row), NQ-fold overlapped.
-template <typename T, int NQ>
+// FIXED: the grid's thread count is a multiple of the quads of a sample, so a thread keeps its
+// columns from one step to the next: which lookup owns them (a binary search), that lookup's table,
+// width, row count and combiner are found once per thread instead of once per quad, and a step is
+// left with the loads, the adds and three multiply-adds for its addresses.
+template <typename T, int NQ, bool FIXED>
 __global__ __launch_bounds__(256) void fwd_group(const GroupFwdArgs a, const int64_t* __restrict__ keys,
                                                  const int64_t* __restrict__ offsets, uint64_t n_quads,
                                                  float* __restrict__ out, EmbHeader* hdr) {
@@ -1069,6 +1073,80 @@ __global__ __launch_bounds__(256) void fwd_group(const GroupFwdArgs a, const int
   const uint64_t n_threads = (uint64_t)gridDim.x * 256u;
   const bool dense = a.per_sample != 0;
   uint32_t nbad = 0;   // counted by the lane that owns a lookup's first quad
+  // the lookup that owns column c: the last one starting at or before it
+  auto owner = [&](uint32_t c) {
+    int lo = 0, hi = (int)a.L - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (lk[mid].col <= c) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+  };
+  if constexpr (FIXED) {
+    const uint64_t t = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    const uint32_t c = (uint32_t)(t % W4) * 4u;
+    const uint32_t batch = (uint32_t)(n_quads / W4);
+    const uint32_t bstride = (uint32_t)(n_threads / W4);
+    const int lo = owner(c);
+    const GroupLookup k = lk[lo];
+    const T* tbl = static_cast<const T*>(k.table);
+    const uint32_t cl = c - k.col, dim = k.dim;
+    const int64_t nr = nrows[lo];
+    const uint32_t bef = before[lo], hot_l = hot[lo];
+    for (uint32_t b0 = (uint32_t)(t / W4); b0 < batch; b0 += bstride * NQ) {
+      int64_t k0[NQ], k1[NQ];
+      bool live[NQ];
+      int64_t longest = 0;
+#pragma unroll
+      for (int u = 0; u < NQ; ++u) {
+        const uint32_t b = b0 + (uint32_t)u * bstride;
+        live[u] = b < batch;
+        const uint32_t bb = live[u] ? b : b0;
+        if (dense) {
+          k0[u] = (int64_t)bb * a.per_sample + bef;
+          k1[u] = k0[u] + hot_l;
+        } else {
+          const uint64_t bag = (uint64_t)bb * a.L + (uint32_t)lo;
+          k0[u] = offsets[bag];
+          k1[u] = offsets[bag + 1];
+        }
+        if (!live[u]) k1[u] = k0[u];   // nothing to read, nothing to write
+        if (k1[u] - k0[u] > longest) longest = k1[u] - k0[u];
+      }
+      f32x4 acc[NQ];
+#pragma unroll
+      for (int u = 0; u < NQ; ++u) acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int64_t j = 0; j < longest; ++j) {
+        int64_t key[NQ];
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) key[u] = k0[u] + j < k1[u] ? keys[k0[u] + j] : (int64_t)-1;
+        Raw4 raw[NQ];
+        bool ok[NQ];
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) {
+          ok[u] = key[u] >= 0 && key[u] < nr;
+          raw[u] = load_raw4(tbl + (ok[u] ? key[u] : 0) * dim + cl);
+        }
+#pragma unroll
+        for (int u = 0; u < NQ; ++u) {
+          const f32x4 v = widen4(raw[u], tbl);
+          nbad += (cl == 0 && k0[u] + j < k1[u] && !ok[u]) ? 1u : 0u;
+          if (ok[u]) { acc[u].x += v.x; acc[u].y += v.y; acc[u].z += v.z; acc[u].w += v.w; }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < NQ; ++u) {
+        if (live[u]) {
+          if (k.mean && k1[u] > k0[u]) {
+            const float w = 1.0f / (float)(k1[u] - k0[u]);
+            acc[u].x *= w; acc[u].y *= w; acc[u].z *= w; acc[u].w *= w;
+          }
+          const uint32_t b = b0 + (uint32_t)u * bstride;
+          __builtin_nontemporal_store(acc[u], reinterpret_cast<f32x4*>(out + (uint64_t)b * a.width_total + c));
+        }
+      }
+    }
+  } else {
   for (uint64_t q0 = (uint64_t)blockIdx.x * 256u + threadIdx.x; q0 < n_quads; q0 += n_threads * NQ) {
     const T* tbl[NQ];
     uint32_t cl[NQ], dim[NQ], mean[NQ];
@@ -1082,11 +1160,7 @@ __global__ __launch_bounds__(256) void fwd_group(const GroupFwdArgs a, const int
       const uint64_t qq = live ? q : q0;
       const uint32_t b = (uint32_t)(qq / W4);
       const uint32_t c = (uint32_t)(qq % W4) * 4u;
-      int lo = 0, hi = (int)a.L - 1;   // the lookup that owns column c: the last one starting at or before it
-      while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (lk[mid].col <= c) lo = mid; else hi = mid - 1;
-      }
+      const int lo = owner(c);
       const GroupLookup k = lk[lo];
       tbl[u] = static_cast<const T*>(k.table);
       cl[u] = c - k.col;
@@ -1139,7 +1213,8 @@ __global__ __launch_bounds__(256) void fwd_group(const GroupFwdArgs a, const int
       }
     }
   }
-  if (__ballot(nbad != 0) != 0) {   // every lane of the wave is here: the loop above has no early exit
+  }
+  if (__ballot(nbad != 0) != 0) {   // every lane of the wave is here: the loops above have no early exit
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) nbad += __shfl_xor(nbad, d);
     add_invalid(hdr, nbad);
@@ -1757,10 +1832,26 @@ static void group_launch_forward(const GroupPlan& P, bool dense, int64_t batch, 
   }
   constexpr int NQ = 2;   // quads per thread: 1, 3, 4 and 6 measured 49, 16, 22 and 31 % slower on 26 tables of mixed widths
   const uint64_t n_quads = (uint64_t)batch * (P.width_total / 4);
+  // A grid whose thread count is a multiple of the quads of a sample (W4) lets every thread keep its
+  // columns: `unit` blocks are the smallest such grid, and about 4,000 blocks (16 per compute unit)
+  // are launched in multiples of it.  A sample too wide for that falls back to one pass over all quads.
+  const uint64_t W4 = P.width_total / 4;
+  uint64_t g = W4, h = 256;
+  while (h) { const uint64_t r = g % h; g = h; h = r; }   // g = gcd(W4, 256)
+  const uint64_t unit = W4 / g;
+  if (unit <= 4096 && n_quads >= unit * 256) {
+    const uint64_t want = 4096;
+    uint64_t blocks = unit * (want / unit > 0 ? want / unit : 1);
+    const uint64_t enough = ceil_div((int64_t)ceil_div((int64_t)n_quads, 256 * NQ), (int64_t)unit) * unit;
+    if (blocks > enough) blocks = enough;   // a small batch: one step per thread
+    hipLaunchKernelGGL((fwd_group<T, NQ, true>), dim3((uint32_t)blocks), dim3(256), 0, stream, a, keys, csr, n_quads,
+                       out, hdr);
+    return;
+  }
   uint64_t blocks = ceil_div((int64_t)n_quads, 256 * NQ);
   if (blocks > (1u << 20)) blocks = 1u << 20;   // grid-stride beyond a million blocks
-  hipLaunchKernelGGL((fwd_group<T, NQ>), dim3((uint32_t)blocks), dim3(256), 0, stream, a, keys, csr, n_quads, out,
-                     hdr);
+  hipLaunchKernelGGL((fwd_group<T, NQ, false>), dim3((uint32_t)blocks), dim3(256), 0, stream, a, keys, csr, n_quads,
+                     out, hdr);
 }
 
 template <typename T>
