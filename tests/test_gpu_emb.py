@@ -157,6 +157,19 @@ def test_a_workspace_that_was_never_initialised_is_named():
     assert layer.invalid_keys(raw) == 1
 
 
+@pytest.mark.parametrize("dim,dtype", [(8, torch.float32), (64, torch.float32), (128, torch.float32), (128, torch.float16),
+                                       (256, torch.float16), (100, torch.float32)],
+                         ids=["f32x8", "f32x64", "f32x128", "f16x128", "f16x256", "f32x100"])
+@pytest.mark.parametrize("combiner", [0, 1], ids=["sum", "mean"])
+def test_large_bags_and_long_runs_take_the_steps_that_only_add(dim, dtype, combiner):
+    """Bags of up to 150 keys (whole steps of every lane-group width, a second chunk of 64 keys, a
+    partial last step) on few, heavily reused rows (runs of one row that span many reduction steps and
+    windows); a width that is no multiple of a wave's columns and keys without a row keep the general
+    steps in the picture."""
+    run_case([7, 300, 5000], dim, 257, dtype=dtype, combiner=combiner, alpha=1.3, hot=(0, 150))
+    run_case([7, 300], dim, 64, dtype=dtype, combiner=combiner, alpha=1.3, hot=(60, 70), poison=25)
+
+
 def test_every_key_equal_one_long_segment():
     """All 9,000 keys hit one row: a segment spanning hundreds of windows and several sort tiles."""
     info = run_case([1], 128, 9000)
