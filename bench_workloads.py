@@ -86,7 +86,7 @@ def multihot(h, args):
     S, D, B = 26, 128, 65536
     ro = datagen.row_offsets(rows_t)
     base, total = ro[:-1].copy(), int(ro[-1])
-    table = torch.empty((total, D), dtype=torch.float16, device=DEV)
+    table = h.allocate_table(total, D, torch.float16, DEV)
     datagen.fill_table(SEED, table, 1 << 21)
     smp = datagen.make_samplers(rows_t, 1.1, device=DEV)
     offsets = datagen.multihot_offsets(SEED, 7, B * S, 1, 100, device=DEV)
