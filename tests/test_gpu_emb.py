@@ -170,6 +170,14 @@ def test_large_bags_and_long_runs_take_the_steps_that_only_add(dim, dtype, combi
     run_case([7, 300], dim, 64, dtype=dtype, combiner=combiner, alpha=1.3, hot=(60, 70), poison=25)
 
 
+def test_allocate_table_with_and_without_room_for_the_spacer():
+    h = H()
+    for spacer in (0.0, 0.25, 1e6):   # none, one that fits, one that cannot fit (skipped, not an error)
+        t = h.allocate_table(1000, 16, torch.float16, "cuda", spacer_gib=spacer)
+        assert t.shape == (1000, 16) and t.dtype == torch.float16 and t.is_cuda and t.is_contiguous()
+        assert t.data_ptr() % 256 == 0
+
+
 def test_every_key_equal_one_long_segment():
     """All 9,000 keys hit one row: a segment spanning hundreds of windows and several sort tiles."""
     info = run_case([1], 128, 9000)
