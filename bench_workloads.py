@@ -35,6 +35,7 @@ import datagen  # noqa: E402
 
 SEED = datagen.DEFAULT_SEED
 DEV = "cuda"
+SPACER_GIB = 64.0   # tables are allocated behind this much device memory (see behind_spacer); --spacer-gib 0: the plain way
 
 
 def timeit(fn, iters=10, warm=2):
@@ -86,7 +87,7 @@ def multihot(h, args):
     S, D, B = 26, 128, 65536
     ro = datagen.row_offsets(rows_t)
     base, total = ro[:-1].copy(), int(ro[-1])
-    table = h.allocate_table(total, D, torch.float16, DEV)
+    table = h.allocate_table(total, D, torch.float16, DEV, spacer_gib=SPACER_GIB)
     datagen.fill_table(SEED, table, 1 << 21)
     smp = datagen.make_samplers(rows_t, 1.1, device=DEV)
     offsets = datagen.multihot_offsets(SEED, 7, B * S, 1, 100, device=DEV)
@@ -162,8 +163,9 @@ def multihot(h, args):
 def hashed(h, args):
     S, D, B = 26, 64, 131072
     cap, max_rows = 100_000_000, 80_000_000
-    ht = h.HashTable(cap, max_rows)
-    table = torch.empty((max_rows, D), dtype=torch.float32, device=DEV)
+    with h.behind_spacer(SPACER_GIB, cap * 16 + max_rows * D * 4):
+        ht = h.HashTable(cap, max_rows)
+        table = torch.empty((max_rows, D), dtype=torch.float32, device=DEV)
     datagen.fill_table(SEED, table, 1 << 22)
     layer = h.EmbeddingLayer(table, S, h.SUM, hash_table=ht, insert_on_miss=True, reuse_forward_rows=True)
     nnz = B * S
@@ -383,9 +385,10 @@ def mixed(h, args):
     S, D, B = 26, 128, 55296
     ro = datagen.row_offsets(rows_t)
     base, total = ro[:-1].copy(), int(ro[-1])
-    master = torch.empty((total, D), dtype=torch.float32, device=DEV)
+    with h.behind_spacer(SPACER_GIB, total * D * 6):
+        master = torch.empty((total, D), dtype=torch.float32, device=DEV)
+        table = torch.empty((total, D), dtype=torch.float16, device=DEV)
     datagen.fill_table(SEED, master, 1 << 21)
-    table = torch.empty((total, D), dtype=torch.float16, device=DEV)
     for r0 in range(0, total, 1 << 22):
         table[r0:r0 + (1 << 22)].copy_(master[r0:r0 + (1 << 22)])
     smp = datagen.make_samplers(rows_t, 1.05, device=DEV)
@@ -566,10 +569,11 @@ def group(h, args):
     B, L = 55296, len(rows_t)
     dims = [(128, 64, 32, 16)[t % 4] for t in range(L)]
     tables = []
+    with h.behind_spacer(SPACER_GIB, sum(int(rows_t[t]) * dims[t] * 4 for t in range(L))):
+        for t in range(L):
+            tables.append(torch.empty((int(rows_t[t]), dims[t]), dtype=torch.float32, device=DEV))
     for t in range(L):
-        tab = torch.empty((int(rows_t[t]), dims[t]), dtype=torch.float32, device=DEV)
-        datagen.fill_table(SEED + t, tab, 1 << 21)
-        tables.append(tab)
+        datagen.fill_table(SEED + t, tables[t], 1 << 21)
     smp = datagen.make_samplers(rows_t, 1.05, device=DEV)
     keys = [datagen.onehot_keys(SEED, b, rows_t, B, 1.05, device=DEV, samplers=smp) for b in range(4)]
     del smp
@@ -603,6 +607,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group", "mixed", "etc", "fwd_probe", "placement"])
     ap.add_argument("--etc-passes", type=int, default=4)
+    ap.add_argument("--spacer-gib", type=float, default=SPACER_GIB)
     ap.add_argument("--host-rows", type=int, default=0,
                     help="rows of the pinned host table (cache: default = the largest of 1e8 / 5e7 / 2e7 that can be "
                          "pinned; training cache: default 2e7)")
@@ -613,10 +618,12 @@ def main():
         print("bench_workloads.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(2)
     import paper_2210_08803_amd as h
+    globals()["SPACER_GIB"] = args.spacer_gib
     res = {"multihot": multihot, "hashed": hashed, "cache": cache, "group": group, "mixed": mixed, "etc": etc, "fwd_probe": fwd_probe,
            "placement": placement}[args.workload](h, args)
     res["n_gpus"] = 1
     res["data"] = "synthetic"
+    res["tables_behind_spacer_gib"] = args.spacer_gib
     print(json.dumps(res), flush=True)
 
 

@@ -156,31 +156,45 @@ def check_offsets(offsets: torch.Tensor, nnz: int, stream=None) -> None:
     _check(lib().hctr_check_offsets(_ptr(offsets), offsets.numel() - 1, int(nnz), _ptr(ws), 8, _stream(stream)))
 
 
-def allocate_table(num_rows: int, dim: int, dtype: torch.dtype = torch.float32, device="cuda",
-                   spacer_gib: float = 64.0) -> torch.Tensor:
-    """An uninitialised [num_rows, dim] device tensor for a large table, placed behind `spacer_gib` GiB
-    of device memory that are given back at once (later, smaller buffers may land there).
+class behind_spacer:
+    """Context manager: what is allocated inside lands behind `gib` GiB of device memory, which are
+    given back on exit (later, smaller buffers may land there).
 
     Why: on MI355X the first tens of gigabytes of device memory that a process is handed serve the
     random row reads of the forward and the read-modify-writes of the backward about 7 % slower than
     the memory behind them.  Measured with the 85 GB table of the DLRM-shaped workload: forward /
     backward 218 / 290 us with the table as the first allocation, 200 / 274 us behind 32 to 160 GiB,
-    whatever the other buffers of the step are and wherever they lie.  A process that allocates its
-    table first therefore puts it in the slow place.  This is a property of the machine's memory
-    map, not of the kernels; it only pays as one of the first allocations of a process, and the
-    spacer is skipped when spacer and table do not both fit."""
+    whatever the other buffers of the step are and wherever they lie (the 22 GB of the hashed
+    workload and the tables of the fused group, allocated first, showed no difference).  A process
+    that allocates a large table first therefore puts it in the slow place.  This is a property of the machine's memory
+    map, not of the kernels; it only pays for the first allocations of a process, and the spacer is
+    skipped when less than `gib` + `room_for` bytes + 1 GiB are free."""
+
+    def __init__(self, gib: float = 64.0, room_for: int = 0, device="cuda"):
+        self.gib, self.room_for, self.device, self._spacer = gib, int(room_for), device, None
+
+    def __enter__(self):
+        if self.gib > 0:
+            free, _ = torch.cuda.mem_get_info(self.device)
+            want = int(self.gib * (1 << 30))
+            if free > self.room_for + want + (1 << 30):
+                self._spacer = torch.empty(want, dtype=torch.uint8, device=self.device)
+        return self
+
+    def __exit__(self, *exc):
+        if self._spacer is not None:
+            self._spacer = None
+            torch.cuda.empty_cache()
+        return False
+
+
+def allocate_table(num_rows: int, dim: int, dtype: torch.dtype = torch.float32, device="cuda",
+                   spacer_gib: float = 64.0) -> torch.Tensor:
+    """An uninitialised [num_rows, dim] device tensor for a large table, placed behind a spacer (see
+    behind_spacer; spacer_gib 0: allocated the plain way)."""
     nbytes = int(num_rows) * int(dim) * torch.empty((), dtype=dtype).element_size()
-    spacer = None
-    if spacer_gib > 0:
-        free, _ = torch.cuda.mem_get_info(device)
-        want = int(spacer_gib * (1 << 30))
-        if free > nbytes + want + (1 << 30):
-            spacer = torch.empty(want, dtype=torch.uint8, device=device)
-    table = torch.empty((int(num_rows), int(dim)), dtype=dtype, device=device)
-    if spacer is not None:
-        del spacer
-        torch.cuda.empty_cache()
-    return table
+    with behind_spacer(spacer_gib, nbytes, device):
+        return torch.empty((int(num_rows), int(dim)), dtype=dtype, device=device)
 
 
 class HashTable:
