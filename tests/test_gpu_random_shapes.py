@@ -1,0 +1,39 @@
+"""GPU parity on seeded random combinations of the layer's parameters: slot count, table sizes, row
+width, storage type, combiner, bag sizes, key skew, keys without a row.  Each case is the full
+comparison of tests/test_gpu_emb.py (forward, dedup, backward + SGD, determinism) against the oracle;
+the combinations reach paths that the hand-picked cases meet only one at a time (a width that is no
+multiple of a wave's columns with bags of several chunks, a mean over bags with keys that have no
+row, long runs in narrow rows, ...)."""
+import numpy as np
+import pytest
+import torch
+
+from test_gpu_emb import run_case
+
+pytestmark = pytest.mark.gpu
+
+
+def _cases(n, seed):
+    g = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        dtype = torch.float16 if g.random() < 0.5 else torch.float32
+        mult = 8 if dtype == torch.float16 else 4
+        dim = int(mult * g.choice([1, 2, 3, 4, 8, 13, 16, 25, 32, 48, 64, 96]))
+        S = int(g.choice([1, 2, 3, 5, 26, 40]))
+        rows = [int(x) for x in np.exp(g.uniform(np.log(2), np.log(20000), S)).astype(np.int64)]
+        batch = int(g.choice([1, 7, 64, 130, 517, 1500]))
+        kind = g.integers(0, 4)
+        hot = None if kind == 0 else [(0, 4), (1, 40), (0, 150)][kind - 1]
+        combiner = int(g.integers(0, 2))
+        alpha = float(g.choice([0.0, 1.05, 1.4]))
+        poison = int(g.choice([0, 0, 3, 40])) if batch * S >= 64 else 0
+        out.append(pytest.param(rows, dim, batch, dtype, combiner, alpha, hot, poison, 1000 + i,
+                                id=f"{i}-S{S}-D{dim}-{'f16' if dtype == torch.float16 else 'f32'}-B{batch}-"
+                                   f"{'onehot' if hot is None else 'hot%d_%d' % hot}-{'mean' if combiner else 'sum'}"))
+    return out
+
+
+@pytest.mark.parametrize("rows,dim,batch,dtype,combiner,alpha,hot,poison,seed", _cases(36, 20221008))
+def test_random_layer_configuration(rows, dim, batch, dtype, combiner, alpha, hot, poison, seed):
+    run_case(rows, dim, batch, dtype=dtype, combiner=combiner, alpha=alpha, hot=hot, poison=poison, seed=seed)
