@@ -69,6 +69,10 @@ __device__ __forceinline__ void cache_block_report(CacheHeader* hdr, uint32_t bl
 }
 static_assert(sizeof(CacheHeader) == 256, "header is one 256-byte block");
 
+__global__ void cache_store_u32(uint32_t* where, uint32_t value) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *where = value;
+}
+
 // The divisor of the set index, with the reciprocal that turns the 64-bit remainder (a few hundred
 // instructions when left to the compiler) into a multiply-high and at most two subtractions.
 struct SetDiv {
@@ -873,7 +877,9 @@ struct QueryArgs {
 template <int WAYS>
 static void launch_probe(const QueryArgs& a) {
   constexpr int KP = WAYS >= 8 ? 8 : WAYS;
-  const uint32_t blocks = (uint32_t)std::min<int64_t>(ceil_div(ceil_div((int64_t)a.n, KP) * WAYS, 256), 2048);
+  // at least one block: a call whose bags are all empty still counts as a call (the last block to
+  // finish publishes the call count)
+  const uint32_t blocks = (uint32_t)std::max<int64_t>(1, std::min<int64_t>(ceil_div(ceil_div((int64_t)a.n, KP) * WAYS, 256), 2048));
   hipLaunchKernelGGL((cache_probe<WAYS>), dim3(blocks), dim3(256), 0, a.stream, (const u64*)a.tags(), a.stamps(),
                      make_set_div(a.c->num_sets), a.c->host_rows, a.hdr(), a.keys, a.n, a.line_of, a.hit_mask,
                      a.flag);
@@ -1063,6 +1069,7 @@ static hctr_status cache_query_impl(hctr_cache* c, QueryPart part, int64_t batch
   }
   if (!out && need_out) return fail(HCTR_E_NULL_PTR, "out is NULL");
   if (nnz > 0 && !keys) return fail(HCTR_E_NULL_PTR, "keys is NULL");
+  if (nnz == 0) insert_missing = 0;   // bags without keys: zeros in the output, one more call counted, nothing to insert
   if (out && (uintptr_t)out % 16 != 0) return fail(HCTR_E_INVALID_ARG, "out must be 16-byte aligned");
   const CacheWsLayout L = cache_ws_layout(c, nnz);
   if (!ws) return fail(HCTR_E_WORKSPACE, "workspace is NULL");
@@ -1114,6 +1121,9 @@ static hctr_status cache_query_impl(hctr_cache* c, QueryPart part, int64_t batch
       } else if (!insert_missing) {
         if (out) dispatch_gather<kPoolAll>(lpr, a, nullptr);   // missing rows straight from the host table
       }
+    }
+    if (miss_list != nullptr && nnz == 0) {   // no keys, none missing (a fill kernel: a memset node may not be captured)
+      hipLaunchKernelGGL(cache_store_u32, dim3(1), dim3(64), 0, stream, n_missing, 0u);
     }
     if (miss_list != nullptr && nnz > 0) {   // ascending positions of the missing keys inside the host table
       uint32_t* idx = reinterpret_cast<uint32_t*>(w + L.idx);

@@ -136,6 +136,19 @@ def test_csr_bags_and_batch_of_one_key(small_limit):
 
 
 @pytest.mark.parametrize("small_limit", [0, 8192], ids=["general", "fused-small"])
+@pytest.mark.parametrize("dim", [16, 260], ids=["d16", "d260-never-fused"])
+def test_bags_without_keys_still_count_as_a_call(small_limit, dim):
+    """A call whose bags are all empty writes zeros, inserts nothing and advances the call count, so the
+    stamps of the calls around it come out as in the simulation."""
+    p = Pair(8, 4, pinned_table(500, dim), small_limit)
+    g = np.random.default_rng(5)
+    p.query(g.integers(0, 500, 60), 20, what="before")
+    for insert in (True, False):
+        p.query(np.zeros(0, dtype=np.int64), 3, offsets=np.zeros(4, dtype=np.int64), insert=insert, what="empty bags")
+    p.query(g.integers(0, 500, 60), 20, what="after")
+
+
+@pytest.mark.parametrize("small_limit", [0, 8192], ids=["general", "fused-small"])
 def test_set_overflow_in_one_call_skips_the_surplus(small_limit):
     host_rows, dim = 4096, 8
     p = Pair(2, 4, pinned_table(host_rows, dim), small_limit)

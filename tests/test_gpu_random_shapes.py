@@ -4,6 +4,8 @@ comparison of tests/test_gpu_emb.py (forward, dedup, backward + SGD, determinism
 the combinations reach paths that the hand-picked cases meet only one at a time (a width that is no
 multiple of a wave's columns with bags of several chunks, a mean over bags with keys that have no
 row, long runs in narrow rows, ...)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -34,6 +36,6 @@ def _cases(n, seed):
     return out
 
 
-@pytest.mark.parametrize("rows,dim,batch,dtype,combiner,alpha,hot,poison,seed", _cases(36, 20221008))
+@pytest.mark.parametrize("rows,dim,batch,dtype,combiner,alpha,hot,poison,seed", _cases(int(os.environ.get("HCTR_TEST_CASES", "36")), 20221008))
 def test_random_layer_configuration(rows, dim, batch, dtype, combiner, alpha, hot, poison, seed):
     run_case(rows, dim, batch, dtype=dtype, combiner=combiner, alpha=alpha, hot=hot, poison=poison, seed=seed)
