@@ -349,8 +349,9 @@ hctr_status hctr_cache_set_epoch_limit(hctr_cache* cache, int64_t limit);
  * used way among those not used in this call (ties: lowest way), else the insert is skipped.
  *   n_bags   batch * num_slots bags;  keys device [nnz]
  *   offsets  device [n_bags + 1] or NULL = fixed hotness nnz / n_bags (nnz must divide evenly);
- *            bags may be empty, also all of them (nnz = 0: zeros in out, nothing inserted, and the
- *            call counts as a call for the replacement order; a call without bags does nothing)
+ *            bags may be empty, also all of them (nnz = 0: zeros in out, nothing inserted); every
+ *            call counts as one call for the replacement order, also one without keys or without
+ *            bags (batch = 0, which reads and writes nothing else and needs no workspace)
  *   out      device [n_bags, dim] fp32;  hit_mask device [nnz] uint8 (1 = hit) or NULL
  *   ws       device, >= hctr_cache_workspace_bytes(cache, nnz), 256-byte aligned
  */

@@ -1063,9 +1063,36 @@ static hctr_status cache_query_impl(hctr_cache* c, QueryPart part, int64_t batch
   }
   if ((miss_list == nullptr) != (n_missing == nullptr))
     return fail(HCTR_E_NULL_PTR, "miss_positions and n_missing go together");
-  if (n_bags == 0) {
-    if (nnz != 0) return fail(HCTR_E_INVALID_ARG, "nnz must be 0 when there are no bags");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  // A new call: the count goes up by one (on the device, when the call's first kernel ends), after
+  // the stamps have been lowered if it is about to run out.
+  auto begin_call = [&]() -> hctr_status {
+    if (c->epoch >= c->epoch_limit) {   // the count is about to run out: lower it and every stamp
+      const uint32_t by = c->epoch_limit / 2;
+      const uint64_t lines = (uint64_t)c->num_sets * c->ways;
+      hipLaunchKernelGGL(cache_lower_stamps, dim3((uint32_t)ceil_div((int64_t)lines, 256)), dim3(256), 0, stream,
+                         reinterpret_cast<uint32_t*>(c->storage + c->off_stamps), lines, by,
+                         reinterpret_cast<CacheHeader*>(c->storage));
+      HCTR_TRY(launch_status("cache_lower_stamps"));
+      c->epoch -= by;
+    }
+    c->epoch += 1;
     return HCTR_OK;
+  };
+  if (n_bags == 0) {
+    // No bags: nothing to read or write, no workspace needed, but it is a call like any other for the
+    // replacement order (the simulation counts every call): one block of the probe publishes the count.
+    if (nnz != 0) return fail(HCTR_E_INVALID_ARG, "nnz must be 0 when there are no bags");
+    if (part != kMissPhase) {
+      HCTR_TRY(begin_call());
+      QueryArgs e{c, nullptr, nullptr, 0, 0u, 0u, nullptr, nullptr, nullptr, nullptr, stream};
+#define CALL(W) launch_probe<W>(e)
+      HCTR_BY_WAYS(c->ways, CALL)
+#undef CALL
+      if (n_missing) hipLaunchKernelGGL(cache_store_u32, dim3(1), dim3(64), 0, stream, n_missing, 0u);
+      if (ready) HCTR_TRY_HIP(hipEventRecord(ready, stream));
+    }
+    return launch_status("hctr_cache_query");
   }
   if (!out && need_out) return fail(HCTR_E_NULL_PTR, "out is NULL");
   if (nnz > 0 && !keys) return fail(HCTR_E_NULL_PTR, "keys is NULL");
@@ -1077,20 +1104,8 @@ static hctr_status cache_query_impl(hctr_cache* c, QueryPart part, int64_t batch
   if (ws_bytes < L.total) return fail(HCTR_E_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, L.total);
 
   char* w = static_cast<char*>(ws);
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
   HashWsHeader* ws_hdr = reinterpret_cast<HashWsHeader*>(w + L.header);
-  if (part != kMissPhase) {   // a new call
-    if (c->epoch >= c->epoch_limit) {   // the count is about to run out: lower it and every stamp
-      const uint32_t by = c->epoch_limit / 2;
-      const uint64_t lines = (uint64_t)c->num_sets * c->ways;
-      hipLaunchKernelGGL(cache_lower_stamps, dim3((uint32_t)ceil_div((int64_t)lines, 256)), dim3(256), 0, stream,
-                         reinterpret_cast<uint32_t*>(c->storage + c->off_stamps), lines, by,
-                         reinterpret_cast<CacheHeader*>(c->storage));
-      HCTR_TRY(launch_status("cache_lower_stamps"));
-      c->epoch -= by;
-    }
-    c->epoch += 1;
-  }
+  if (part != kMissPhase) HCTR_TRY(begin_call());
   // the miss flags serve the insertion, the second phase and the miss list
   const bool want_flags = insert_missing || part != kWhole || miss_list != nullptr;
   QueryArgs a{c, keys, offsets, hotness, (uint32_t)nnz, (uint32_t)n_bags, out, hit_mask,
@@ -1232,7 +1247,6 @@ HCTR_API hctr_status hctr_cache_query_complete(hctr_cache* c, int64_t batch, int
 
 HCTR_API hctr_status hctr_cache_insert(hctr_cache* c, const int64_t* keys, int64_t n, void* ws, size_t ws_bytes,
                                        void* stream) {
-  if (n == 0) return c ? HCTR_OK : fail(HCTR_E_NULL_PTR, "cache is NULL");
   return cache_query_impl(c, kWhole, n, 1, keys, nullptr, n, 1, nullptr, false, nullptr, nullptr, nullptr, ws,
                           ws_bytes, stream, nullptr);
 }

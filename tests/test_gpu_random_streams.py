@@ -56,3 +56,86 @@ def test_random_cache_stream(seed):
         if nnz and g.random() < 0.3:
             keys[g.integers(0, nnz, max(1, nnz // 40))] = g.choice([-2, host_rows, host_rows + 9])
         p.query(keys, n_bags, offsets=offsets, insert=bool(g.random() < 0.7), what=f"seed {seed} call {call}")
+
+
+def _close(got, ref, what):
+    # rows may have been replaced by update(): bound the error by the result's own size plus a floor
+    err = np.abs(got.astype(np.float64) - ref)
+    assert (err <= 1e-5 * (4 * np.abs(ref) + 8.0)).all(), f"{what}: max err {err.max():.3g}"
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_random_cache_operator_stream(seed):
+    """One-call queries, two-phase queries, insert-only calls, in-place updates of cached rows and
+    refreshes after the host table changed, in random order and sizes (also without any key), on one
+    cache; after every operator the tags, stamps, cached rows and statistics equal the simulation's."""
+    from test_gpu_cache import _state_equal
+    g = np.random.default_rng(11000 + seed)
+    ways = int(g.choice([1, 4, 8, 32]))
+    num_sets = int(g.choice([2, 31, 200]))
+    dim = int(4 * g.choice([2, 16, 32, 65]))
+    host_rows = int(g.choice([50, 2000]))
+    p = Pair(num_sets, ways, pinned_table(host_rows, dim), int(g.choice([0, 8192])))
+    if g.random() < 0.3:
+        p.gpu.set_epoch_limit(6)          # stamps are lowered every few calls
+        p.ref.set_epoch_limit(6)
+
+    def draw(n):
+        k = np.minimum((g.pareto(1.1, n) * host_rows / 40).astype(np.int64), host_rows - 1)
+        if n and g.random() < 0.3:
+            k[g.integers(0, n, max(1, n // 30))] = g.choice([-4, host_rows, host_rows + 3])
+        return k
+
+    for opn in range(int(g.integers(6, 14))):
+        op = g.choice(["query", "two_phase", "insert", "update", "refresh"], p=[0.35, 0.25, 0.15, 0.15, 0.10])
+        what = f"seed {seed} op {opn} {op}"
+        if op in ("query", "two_phase"):
+            n_bags = int(g.choice([1, 4, 52, 300]))
+            if g.random() < 0.5:
+                offsets, nnz = None, n_bags * int(g.integers(1, 5))
+            else:
+                offsets = np.concatenate([[0], np.cumsum(g.integers(0, 5, n_bags))]).astype(np.int64)
+                nnz = int(offsets[-1])
+            keys = draw(nnz)
+            insert = bool(g.random() < 0.7)
+            d_keys = to_dev(keys)
+            d_off = None if offsets is None else to_dev(offsets)
+            d_hit = torch.full((nnz,), 9, dtype=torch.uint8, device="cuda")
+            if op == "query":
+                ref_out, ref_hit = p.ref.query(keys, n_bags, offsets=offsets, insert_missing=insert)
+                out = p.gpu.query(n_bags, 1, d_keys, d_off, insert, hit_mask=d_hit)
+                torch.cuda.synchronize()
+                assert np.array_equal(d_hit.cpu().numpy(), ref_hit), f"{what}: hit mask"
+                _close(out.cpu().numpy().reshape(n_bags, dim), ref_out, what)
+            else:
+                ref_out, ref_hit, ref_miss = p.ref.query_hits(keys, n_bags, offsets=offsets)
+                out = torch.full((n_bags, dim), float("nan"), dtype=torch.float32, device="cuda")
+                d_miss = torch.full((max(1, nnz),), -1, dtype=torch.int32, device="cuda")
+                d_nmiss = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+                ws = p.gpu.workspace(nnz)
+                p.gpu.query_hits(n_bags, 1, d_keys, out, d_off, d_hit, d_miss, d_nmiss, ws=ws)
+                torch.cuda.synchronize()
+                assert np.array_equal(d_hit.cpu().numpy(), ref_hit), f"{what}: hit mask"
+                assert int(d_nmiss.item()) == len(ref_miss), f"{what}: number of missing positions"
+                assert np.array_equal(d_miss.cpu().numpy()[:len(ref_miss)], ref_miss), f"{what}: missing positions"
+                _close(out.cpu().numpy(), ref_out, what + " (hits)")
+                p.ref.query_complete(keys, n_bags, ref_hit, ref_out, offsets=offsets, insert_missing=insert)
+                p.gpu.query_complete(n_bags, 1, d_keys, out, d_off, insert, ws=ws)
+                torch.cuda.synchronize()
+                _close(out.cpu().numpy(), ref_out, what + " (completed)")
+        elif op == "insert":
+            keys = draw(int(g.choice([0, 1, 40, 900, 9000])))
+            p.ref.insert(keys)
+            p.gpu.insert(to_dev(keys))
+        elif op == "update":
+            n = int(g.choice([0, 1, 60, 3000]))
+            keys = draw(n)
+            rows = g.standard_normal((n, dim)).astype(np.float32)
+            p.ref.update(keys, rows)
+            p.gpu.update(to_dev(keys), to_dev(rows))
+        else:
+            p.host += 0.125               # the host table changes underneath (one memory for both sides)
+            p.ref.refresh()
+            p.gpu.refresh()
+        torch.cuda.synchronize()
+        _state_equal(p, what)
