@@ -39,3 +39,33 @@ def _cases(n, seed):
 @pytest.mark.parametrize("rows,dim,batch,dtype,combiner,alpha,hot,poison,seed", _cases(int(os.environ.get("HCTR_TEST_CASES", "36")), 20221008))
 def test_random_layer_configuration(rows, dim, batch, dtype, combiner, alpha, hot, poison, seed):
     run_case(rows, dim, batch, dtype=dtype, combiner=combiner, alpha=alpha, hot=hot, poison=poison, seed=seed)
+
+
+def _group_cases(n, seed):
+    g = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        f16 = bool(g.random() < 0.4)
+        mult = 8 if f16 else 4
+        n_tables = int(g.integers(1, 7))
+        shapes = [(int(np.exp(g.uniform(0, np.log(6000)))) + 1, int(mult * g.choice([1, 2, 3, 4, 8, 16, 33, 64, 130])))
+                  for _ in range(n_tables)]
+        n_lookups = int(g.integers(1, 13))
+        lookups = [(int(g.integers(0, n_tables)), int(g.integers(0, 2))) for _ in range(n_lookups)]
+        batch = int(g.choice([1, 5, 64, 333, 2100]))
+        dense = bool(g.random() < 0.5)
+        hot = [int(g.integers(1, 6)) for _ in range(n_lookups)] if dense else None
+        hmax = None if dense else int(g.choice([0, 1, 4, 12]))
+        bad = int(g.choice([0, 0, 2, 10])) if batch * n_lookups >= 40 and (dense or hmax) else 0
+        out.append(pytest.param(shapes, lookups, batch, np.float16 if f16 else np.float32, hmax, hot, bool(g.random() < 0.4),
+                                bad, 3000 + i,
+                                id=f"{i}-T{n_tables}-L{n_lookups}-B{batch}-{'f16' if f16 else 'f32'}-{'dense' if dense else 'sparse'}"))
+    return out
+
+
+@pytest.mark.parametrize("shapes,lookups,batch,dtype,hmax,hot,zipf,bad,seed",
+                         _group_cases(int(os.environ.get("HCTR_TEST_CASES", "24")), 20221009))
+def test_random_group_configuration(shapes, lookups, batch, dtype, hmax, hot, zipf, bad, seed):
+    from test_gpu_group import run_case as run_group_case
+    run_group_case(np.random.default_rng(seed), shapes, lookups, batch=batch, dtype=dtype, hmax=hmax, hot=hot,
+                   zipf=zipf, bad=bad)
