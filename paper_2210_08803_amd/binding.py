@@ -150,6 +150,23 @@ def _ws(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(256, nbytes), dtype=torch.uint8, device=device)
 
 
+def _sizes(what: str, n_bags: int, keys: Optional[torch.Tensor] = None, offsets: Optional[torch.Tensor] = None,
+           **arrays) -> None:
+    """The C calls take bare pointers and believe the counts they are given: a tensor shorter than the
+    call says is read or written past its end on the device.  The tensors know their sizes, so the
+    binding compares them before it hands the pointers over.  arrays: name=(tensor or None, least
+    number of elements)."""
+    if offsets is not None and offsets.numel() != n_bags + 1:
+        raise ValueError(f"{what}: offsets has {offsets.numel()} entries, {n_bags} bags need {n_bags + 1}")
+    if offsets is not None and offsets.dtype != torch.int64:
+        raise ValueError(f"{what}: offsets must be int64")
+    if keys is not None and keys.dtype != torch.int64:
+        raise ValueError(f"{what}: keys must be int64")
+    for name, (t, least) in arrays.items():
+        if t is not None and t.numel() < least:
+            raise ValueError(f"{what}: {name} has {t.numel()} elements, the call needs {least}")
+
+
 def check_offsets(offsets: torch.Tensor, nnz: int, stream=None) -> None:
     """hctr_check_offsets: raises HctrError unless offsets is a valid CSR offset array for nnz keys."""
     ws = torch.empty(1, dtype=torch.int64, device=offsets.device)
@@ -316,6 +333,8 @@ class EmbeddingLayer:
             out = torch.empty((batch, self.num_slots, self.table.shape[1]), dtype=self.io_dtype,
                               device=self.table.device)
         assert out.dtype == self.io_dtype
+        n_bags = batch * self.num_slots
+        _sizes("forward", n_bags, keys, offsets, out=(out, n_bags * self.table.shape[1]))
         if ws is None:
             ws = self.workspace(batch, nnz, stream)
         _check(lib().hctr_emb_forward(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(out),
@@ -326,6 +345,8 @@ class EmbeddingLayer:
                      offsets: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> None:
         nnz = keys.numel()
         assert dY.dtype == self.io_dtype and dY.is_contiguous()
+        n_bags = batch * self.num_slots
+        _sizes("backward_sgd", n_bags, keys, offsets, dY=(dY, n_bags * self.table.shape[1]))
         if ws is None:
             ws = self.workspace(batch, nnz, stream)
         _check(lib().hctr_emb_backward_sgd(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(dY),
@@ -334,6 +355,7 @@ class EmbeddingLayer:
     def backward_dedup(self, batch: int, keys: torch.Tensor, offsets: Optional[torch.Tensor] = None,
                        ws: Optional[torch.Tensor] = None, stream=None) -> None:
         nnz = keys.numel()
+        _sizes("backward_dedup", batch * self.num_slots, keys, offsets)
         if ws is None:
             ws = self.workspace(batch, nnz, stream)
         _check(lib().hctr_emb_backward_dedup(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz,
@@ -343,6 +365,8 @@ class EmbeddingLayer:
                        offsets: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
                        stream=None) -> None:
         assert dY.dtype == self.io_dtype and dY.is_contiguous()
+        n_bags = batch * self.num_slots
+        _sizes("backward_apply", n_bags, None, offsets, dY=(dY, n_bags * self.table.shape[1]))
         if ws is None:
             ws = self.workspace(batch, nnz, stream)
         _check(lib().hctr_emb_backward_apply(C.byref(self.desc), batch, _ptr(offsets), nnz, _ptr(dY),
@@ -414,6 +438,7 @@ class EmbeddingGroup:
         nnz = keys.numel()
         if out is None:
             out = torch.empty((batch, self.width), dtype=torch.float32, device=self.device)
+        _sizes("group forward", batch * len(self.lookups), keys, offsets, out=(out, batch * self.width))
         if ws is None:
             ws = self.workspace(batch, nnz)
         _check(lib().hctr_group_forward(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(out),
@@ -423,6 +448,7 @@ class EmbeddingGroup:
     def backward_sgd(self, batch: int, keys: torch.Tensor, dY: torch.Tensor, lr: float,
                      offsets: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> None:
         nnz = keys.numel()
+        _sizes("group backward_sgd", batch * len(self.lookups), keys, offsets, dY=(dY, batch * self.width))
         if ws is None:
             ws = self.workspace(batch, nnz)
         _check(lib().hctr_group_backward_sgd(C.byref(self.desc), batch, _ptr(keys), _ptr(offsets), nnz, _ptr(dY),
@@ -530,6 +556,8 @@ class EmbeddingCache:
         nnz = keys.numel()
         if out is None:
             out = torch.empty((batch, num_slots, self.dim), dtype=torch.float32, device=self.device)
+        _sizes("cache query", batch * num_slots, keys, offsets, out=(out, batch * num_slots * self.dim),
+               hit_mask=(hit_mask, nnz))
         if ws is None:
             ws = self.workspace(nnz)
         _check(lib().hctr_cache_query(self.handle, batch, num_slots, _ptr(keys), _ptr(offsets), nnz,
@@ -541,6 +569,8 @@ class EmbeddingCache:
                      offsets: Optional[torch.Tensor] = None, insert_missing: bool = True,
                      hit_mask: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
         """hctr_cache_query_static: the query without a workspace argument; the caller brings `out`."""
+        _sizes("cache query_static", batch * num_slots, keys, offsets, out=(out, batch * num_slots * self.dim),
+               hit_mask=(hit_mask, keys.numel()))
         _check(lib().hctr_cache_query_static(self.handle, batch, num_slots, _ptr(keys), _ptr(offsets), keys.numel(),
                                              int(insert_missing), _ptr(out), _ptr(hit_mask), _stream(stream)))
         return out
@@ -552,6 +582,8 @@ class EmbeddingCache:
         """hctr_cache_query_hits: first phase, pools the hits only.  `ready` must be an event that has been
         recorded once already (torch creates the underlying event on the first record)."""
         nnz = keys.numel()
+        _sizes("cache query_hits", batch * num_slots, keys, offsets, out=(out, batch * num_slots * self.dim),
+               hit_mask=(hit_mask, nnz), miss_positions=(miss_positions, nnz), n_missing=(n_missing, 1))
         if ws is None:
             ws = self.workspace(nnz)
         _check(lib().hctr_cache_query_hits(self.handle, batch, num_slots, _ptr(keys), _ptr(offsets), nnz, _ptr(out),
@@ -564,6 +596,7 @@ class EmbeddingCache:
                        ws: Optional[torch.Tensor] = None, stream=None):
         """hctr_cache_query_complete: second phase, adds the missing rows into `out` and inserts them."""
         nnz = keys.numel()
+        _sizes("cache query_complete", batch * num_slots, keys, offsets, out=(out, batch * num_slots * self.dim))
         if ws is None:
             ws = self.workspace(nnz)
         _check(lib().hctr_cache_query_complete(self.handle, batch, num_slots, _ptr(keys), _ptr(offsets), nnz,
@@ -578,6 +611,8 @@ class EmbeddingCache:
         nnz = keys.numel()
         if out is None:
             out = torch.empty((batch, num_slots, self.dim), dtype=torch.float32, device=self.device)
+        _sizes("cache query_async", batch * num_slots, keys, offsets, out=(out, batch * num_slots * self.dim),
+               hit_mask=(hit_mask, nnz))
         if ws is None:
             ws = self.workspace(nnz)
         if not ready.cuda_event:   # torch creates the underlying event on its first record

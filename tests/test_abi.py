@@ -180,3 +180,23 @@ def test_workspace_bytes_serve_every_smaller_call():
     g = _group()
     gsizes = [L.hctr_group_workspace_bytes(C.byref(g), 2, n) for n in points]
     assert all(a <= b for a, b in zip(gsizes, gsizes[1:]))
+
+
+def test_binding_compares_tensor_sizes_with_the_counts_of_the_call():
+    """The C calls believe their counts; the binding, which sees the tensors, refuses a call whose
+    offsets, output or gradient is shorter than the counts say (it would be read or written past its
+    end on the device)."""
+    import torch
+    from paper_2210_08803_amd.binding import _sizes
+    keys = torch.zeros(10, dtype=torch.int64)
+    _sizes("ok", 5, keys, torch.zeros(6, dtype=torch.int64), out=(torch.zeros(40), 40), hit_mask=(None, 10))
+    with pytest.raises(ValueError, match="offsets has 5 entries"):
+        _sizes("short offsets", 5, keys, torch.zeros(5, dtype=torch.int64))
+    with pytest.raises(ValueError, match="offsets has 7 entries"):
+        _sizes("long offsets", 5, keys, torch.zeros(7, dtype=torch.int64))
+    with pytest.raises(ValueError, match="int64"):
+        _sizes("int32 keys", 5, keys.to(torch.int32), None)
+    with pytest.raises(ValueError, match="int64"):
+        _sizes("int32 offsets", 5, keys, torch.zeros(6, dtype=torch.int32))
+    with pytest.raises(ValueError, match="out has 39 elements"):
+        _sizes("short out", 5, keys, None, out=(torch.zeros(39), 40))

@@ -43,15 +43,19 @@ def make(table_rows, dim, batch, tdtype, hot, seed=SEED):
 @pytest.mark.parametrize("tdtype", [torch.float32, torch.float16])
 @pytest.mark.parametrize("hot,combiner", [(None, H.SUM), ((0, 9), H.SUM), ((1, 40), H.MEAN)])
 def test_fp16_output(tdtype, hot, combiner):
-    S, base, num, table, keys, offsets, off_np, rows, n_bags = make([3000, 17, 800, 12000], 64, 1500, tdtype, hot)
+    check_fp16_output([3000, 17, 800, 12000], 64, 1500, tdtype, hot, combiner)
+
+
+def check_fp16_output(table_rows, D, batch, tdtype, hot, combiner, seed=SEED):
+    S, base, num, table, keys, offsets, off_np, rows, n_bags = make(table_rows, D, batch, tdtype, hot, seed)
     tab = table.numpy()
     ref16 = oracle.emb_forward_mixed(tab, rows, off_np, combiner, n_bags=n_bags)
     ref32 = oracle.emb_forward(tab, rows, off_np, combiner, n_bags=n_bags)
     mag = oracle.emb_forward(np.abs(tab), rows, off_np, combiner, n_bags=n_bags)
     layer = H.EmbeddingLayer(to_dev(table), S, combiner, base, num, io_dtype=torch.float16)
-    out = layer.forward(1500, to_dev(keys), None if offsets is None else to_dev(offsets))
+    out = layer.forward(batch, to_dev(keys), None if offsets is None else to_dev(offsets))
     assert out.dtype == torch.float16
-    got = out.cpu().numpy().reshape(n_bags, 64)
+    got = out.cpu().numpy().reshape(n_bags, D)
     if hot is None:   # a copy: fp16 rows pass unchanged, fp32 rows are rounded once
         assert np.array_equal(got.view(np.uint16), ref16.view(np.uint16))
     half_close(got, ref16, ref32, mag, "fp16 forward")
@@ -60,8 +64,12 @@ def test_fp16_output(tdtype, hot, combiner):
 @pytest.mark.parametrize("tdtype", [torch.float32, torch.float16])
 @pytest.mark.parametrize("hot,combiner", [(None, H.SUM), ((1, 30), H.MEAN)])
 def test_fp16_gradient(tdtype, hot, combiner):
-    S, base, num, table, keys, offsets, off_np, rows, n_bags = make([5000, 9, 600], 32, 4000, tdtype, hot)
-    dY16 = datagen.normal_grads(SEED, 2, n_bags * 32).view(n_bags, 32).to(torch.float16)
+    check_fp16_gradient([5000, 9, 600], 32, 4000, tdtype, hot, combiner)
+
+
+def check_fp16_gradient(table_rows, D, batch, tdtype, hot, combiner, seed=SEED):
+    S, base, num, table, keys, offsets, off_np, rows, n_bags = make(table_rows, D, batch, tdtype, hot, seed)
+    dY16 = datagen.normal_grads(seed, 2, n_bags * D).view(n_bags, D).to(torch.float16)
     lr = 0.02
     tab = table.numpy()
     ref = tab.copy()
@@ -71,7 +79,7 @@ def test_fp16_gradient(tdtype, hot, combiner):
     mag = np.abs(tab.astype(np.float64)) + lr * g_abs
     d_table = to_dev(table)
     layer = H.EmbeddingLayer(d_table, S, combiner, base, num, io_dtype=torch.float16)
-    layer.backward_sgd(4000, to_dev(keys), to_dev(dY16), lr, None if offsets is None else to_dev(offsets))
+    layer.backward_sgd(batch, to_dev(keys), to_dev(dY16), lr, None if offsets is None else to_dev(offsets))
     got = d_table.cpu().numpy()
     touched = np.unique(rows[rows >= 0])
     rest = np.setdiff1d(np.arange(tab.shape[0]), touched)
@@ -84,24 +92,28 @@ def test_fp16_gradient(tdtype, hot, combiner):
 
 @pytest.mark.parametrize("io", [torch.float32, torch.float16])
 def test_master_rows(io):
-    S, base, num, table32, keys, offsets, off_np, rows, n_bags = make([4000, 33, 900], 64, 3000, torch.float32, (1, 12))
+    check_master_rows([4000, 33, 900], 64, 3000, io, (1, 12), H.MEAN)
+
+
+def check_master_rows(table_rows, D, batch, io, hot, combiner, seed=SEED):
+    S, base, num, table32, keys, offsets, off_np, rows, n_bags = make(table_rows, D, batch, torch.float32, hot, seed)
     master0 = table32.numpy().copy()
     table16_0 = master0.astype(np.float16)
     d_master, d_table = to_dev(master0), to_dev(table16_0)
-    layer = H.EmbeddingLayer(d_table, S, H.MEAN, base, num, io_dtype=io, master=d_master)
+    layer = H.EmbeddingLayer(d_table, S, combiner, base, num, io_dtype=io, master=d_master)
     ref_master, ref_table = master0.copy(), table16_0.copy()
     lr = 0.05
     touched = np.unique(rows[rows >= 0])
     rest = np.setdiff1d(np.arange(master0.shape[0]), touched)
-    d_keys, d_off = to_dev(keys), to_dev(offsets)
+    d_keys, d_off = to_dev(keys), (None if offsets is None else to_dev(offsets))
     for step in range(3):    # errors must not build up: the master is compared after every step
-        dY = datagen.normal_grads(SEED, 10 + step, n_bags * 64).view(n_bags, 64).to(io)
+        dY = datagen.normal_grads(seed, 10 + step, n_bags * D).view(n_bags, D).to(io)
         before = ref_master.copy()
-        oracle.emb_backward_sgd_mixed(ref_table, rows, dY.numpy(), lr, off_np, H.MEAN, n_bags=n_bags, master=ref_master)
+        oracle.emb_backward_sgd_mixed(ref_table, rows, dY.numpy(), lr, off_np, combiner, n_bags=n_bags, master=ref_master)
         g_abs = np.zeros(master0.shape, dtype=np.float32)
-        oracle.emb_backward_sgd(g_abs, rows, np.abs(dY.numpy().astype(np.float32)), -1.0, off_np, H.MEAN, n_bags=n_bags)
+        oracle.emb_backward_sgd(g_abs, rows, np.abs(dY.numpy().astype(np.float32)), -1.0, off_np, combiner, n_bags=n_bags)
         mag = np.abs(before.astype(np.float64)) + lr * g_abs
-        layer.backward_sgd(3000, d_keys, to_dev(dY), lr, d_off)
+        layer.backward_sgd(batch, d_keys, to_dev(dY), lr, d_off)
         got_m, got_t = d_master.cpu().numpy(), d_table.cpu().numpy()
         assert_close(got_m[touched], ref_master[touched], mag[touched], f"master rows, step {step}")
         # the table row is the rounding of the kernel's own master row, bit for bit
@@ -113,12 +125,12 @@ def test_master_rows(io):
         ref_master[:] = got_m
         ref_table[:] = got_t
     # forward reads the fp16 table
-    out = layer.forward(3000, d_keys, d_off)
-    ref = oracle.emb_forward_mixed(d_table.cpu().numpy(), rows, off_np, H.MEAN, n_bags=n_bags,
+    out = layer.forward(batch, d_keys, d_off)
+    ref = oracle.emb_forward_mixed(d_table.cpu().numpy(), rows, off_np, combiner, n_bags=n_bags,
                                    out_dtype=np.float16 if io == torch.float16 else np.float32)
-    ref32 = oracle.emb_forward(d_table.cpu().numpy(), rows, off_np, H.MEAN, n_bags=n_bags)
-    mag = oracle.emb_forward(np.abs(d_table.cpu().numpy()), rows, off_np, H.MEAN, n_bags=n_bags)
-    got = out.cpu().numpy().reshape(n_bags, 64)
+    ref32 = oracle.emb_forward(d_table.cpu().numpy(), rows, off_np, combiner, n_bags=n_bags)
+    mag = oracle.emb_forward(np.abs(d_table.cpu().numpy()), rows, off_np, combiner, n_bags=n_bags)
+    got = out.cpu().numpy().reshape(n_bags, D)
     if io == torch.float16:
         half_close(got, ref, ref32, mag, "forward after master updates")
     else:

@@ -69,3 +69,29 @@ def test_random_group_configuration(shapes, lookups, batch, dtype, hmax, hot, zi
     from test_gpu_group import run_case as run_group_case
     run_group_case(np.random.default_rng(seed), shapes, lookups, batch=batch, dtype=dtype, hmax=hmax, hot=hot,
                    zipf=zipf, bad=bad)
+
+
+def _mixed_cases(n, seed):
+    g = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        S = int(g.choice([1, 2, 4, 26]))
+        rows = [int(x) + 1 for x in np.exp(g.uniform(0, np.log(8000), S)).astype(np.int64)]
+        dim = int(8 * g.choice([1, 2, 4, 5, 8, 16, 32, 33]))
+        batch = int(g.choice([1, 9, 200, 1100]))
+        hot = [None, (0, 5), (1, 30), (0, 120)][int(g.integers(0, 4))]
+        out.append(pytest.param(int(g.integers(0, 3)), rows, dim, batch, bool(g.random() < 0.5), hot, int(g.integers(0, 2)), 5000 + i,
+                                id=f"{i}-S{S}-D{dim}-B{batch}"))
+    return out
+
+
+@pytest.mark.parametrize("kind,rows,dim,batch,half,hot,combiner,seed",
+                         _mixed_cases(int(os.environ.get("HCTR_TEST_CASES", "24")), 20221010))
+def test_random_mixed_precision_configuration(kind, rows, dim, batch, half, hot, combiner, seed):
+    import test_gpu_mixed as m
+    if kind == 0:
+        m.check_fp16_output(rows, dim, batch, torch.float16 if half else torch.float32, hot, combiner, seed)
+    elif kind == 1:
+        m.check_fp16_gradient(rows, dim, batch, torch.float16 if half else torch.float32, hot, combiner, seed)
+    else:
+        m.check_master_rows(rows, dim, batch, torch.float16 if half else torch.float32, hot, combiner, seed)
