@@ -93,19 +93,24 @@ def test_split_calls_give_the_same_mapping():
 @pytest.mark.parametrize("reuse", [False, True], ids=["lookup-twice", "reuse-forward-rows"])
 def test_hashed_embedding_forward_backward(reuse):
     """26 one-hot slots over an open key space, dim 64 fp32, insert on miss in forward."""
+    check_hashed_layer(26, 64, 513, 16384, 12000, reuse, 3, SEED)
+
+
+def check_hashed_layer(S, dim, batch, capacity, max_rows, reuse, steps, seed, dtype=torch.float32, alpha=1.05):
+    """One-hot slots over an open key space, insert on miss in forward, `steps` forward + backward
+    steps (the table may fill up on the way: keys that are refused have no row)."""
     h = H()
-    S, dim, batch, max_rows = 26, 64, 513, 12000
-    ht, ref_hash = both(16384, max_rows)
-    table = datagen.table_rows_at(SEED, torch.arange(max_rows), dim, torch.float32)
+    ht, ref_hash = both(capacity, max_rows)
+    table = datagen.table_rows_at(seed, torch.arange(max_rows), dim, dtype)
     d_table = to_dev(table)
     layer = h.EmbeddingLayer(d_table, S, h.SUM, hash_table=ht, insert_on_miss=True, reuse_forward_rows=reuse)
     tab_np = table.numpy().copy()
-    smp = datagen.ZipfSampler(1 << 63, 1.05)
-    for it in range(3):
-        keys = datagen.open_space_keys(SEED, it, S, batch, 1.05, sampler=smp)
+    smp = datagen.ZipfSampler(1 << 63, alpha)
+    for it in range(steps):
+        keys = datagen.open_space_keys(seed, it, S, batch, alpha, sampler=smp)
         if it == 2:
             keys[::50] = -5                                              # keys that can never get a row
-        dY = datagen.normal_grads(SEED, it, batch * S * dim).view(batch * S, dim)
+        dY = datagen.normal_grads(seed, it, batch * S * dim).view(batch * S, dim)
         rows = ref_hash.insert_or_find(keys.numpy(), True)
         ref_out, mag = oracle_forward(tab_np, rows, None, 0, batch * S)
         out = layer.forward(batch, to_dev(keys))
@@ -114,7 +119,7 @@ def test_hashed_embedding_forward_backward(reuse):
         assert layer.invalid_keys() == int((rows < 0).sum())
         layer.reset_invalid_keys()
         out_np = out.cpu().numpy().reshape(batch * S, dim)
-        assert np.array_equal(out_np.view(np.uint32), ref_out.view(np.uint32))
+        assert np.array_equal(out_np.view(np.uint32), ref_out.view(np.uint32))      # out is fp32: a copy, or an exact widening
         ref_tab, mag_tab, uniq, cnt = oracle_backward(tab_np, rows, None, 0, batch * S, dY.numpy(), 0.01)
         layer.backward_sgd(batch, to_dev(keys), to_dev(dY), 0.01)
         g_rows, g_cnt = layer.dedup_result(batch, keys.numel())

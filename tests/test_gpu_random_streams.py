@@ -139,3 +139,26 @@ def test_random_cache_operator_stream(seed):
             p.gpu.refresh()
         torch.cuda.synchronize()
         _state_equal(p, what)
+
+
+def _hashed_cases(n, seed):
+    g = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        S = int(g.choice([1, 3, 26]))
+        dim = int(4 * g.choice([1, 4, 16, 25, 64]))
+        batch = int(g.choice([1, 40, 513, 1500]))
+        max_rows = int(g.choice([5, 300, 4000, 30000]))
+        capacity = int(max(64, max_rows / g.uniform(0.35, 0.8) + 1))
+        out.append(pytest.param(S, dim, batch, capacity, max_rows, bool(g.random() < 0.5), int(g.integers(1, 5)), 13000 + i,
+                                float(g.choice([1.05, 1.5])), id=f"{i}-S{S}-D{dim}-B{batch}-rows{max_rows}"))
+    return out
+
+
+@pytest.mark.parametrize("S,dim,batch,capacity,max_rows,reuse,steps,seed,alpha",
+                         _hashed_cases(int(os.environ.get("HCTR_TEST_SEEDS", "8")) * 2, 20221011))
+def test_random_hashed_layer(S, dim, batch, capacity, max_rows, reuse, steps, seed, alpha):
+    """The layer in hashed mode (insert on miss in the forward, the forward's rows reused by the backward
+    or looked up again) on random shapes, with tables that fill up during the steps."""
+    from test_gpu_hash import check_hashed_layer
+    check_hashed_layer(S, dim, batch, capacity, max_rows, reuse, steps, seed, alpha=alpha)
