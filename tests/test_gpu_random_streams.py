@@ -162,3 +162,46 @@ def test_random_hashed_layer(S, dim, batch, capacity, max_rows, reuse, steps, se
     or looked up again) on random shapes, with tables that fill up during the steps."""
     from test_gpu_hash import check_hashed_layer
     check_hashed_layer(S, dim, batch, capacity, max_rows, reuse, steps, seed, alpha=alpha)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_random_training_cache_stream(seed):
+    """The staged training cache: load calls of random sizes (also empty, with keys outside the host
+    table), working rows changed on the device in between, dumps with and without eviction; rows,
+    statistics, working table and host table equal the simulation's after every call."""
+    import oracle
+    import paper_2210_08803_amd as H
+    from test_gpu_etc import pinned
+    g = np.random.default_rng(15000 + seed)
+    host_rows = int(g.choice([9, 400, 7000]))
+    dim = int(4 * g.choice([1, 8, 33]))
+    max_rows = int(g.choice([1, 50, 3000]))
+    host_np = g.standard_normal((host_rows, dim)).astype(np.float32)
+    host = pinned(host_np)
+    etc = H.EmbeddingTrainingCache(host, max_rows=max_rows)
+    ref = oracle.Etc(host_np.copy(), max_rows)
+    for call in range(int(g.integers(4, 12))):
+        op = g.choice(["load", "load", "load", "touch", "dump", "dump_evict"])
+        what = f"seed {seed} call {call} {op}"
+        if op == "load":
+            n = int(g.choice([0, 1, 30, 700, 5000]))
+            keys = (g.random(n) ** 2 * host_rows * 1.05).astype(np.int64)          # a few past the end
+            if n and g.random() < 0.4:
+                keys[g.integers(0, n, max(1, n // 25))] = g.choice([-1, -2 ** 62, 2 ** 40])
+            rows = torch.full((max(1, n),), -7, dtype=torch.int64, device="cuda")
+            etc.load(to_dev(keys), rows[:n] if n else None)
+            want = ref.load(keys)
+            assert np.array_equal(rows.cpu().numpy()[:n], want), what
+        elif op == "touch":               # training changes working rows: the same change on both sides
+            n = ref.stats[0]
+            if n:
+                etc.table[:n] += 0.5
+                ref.work[:n] += np.float32(0.5)
+        else:
+            etc.dump(evict=(op == "dump_evict"))
+            ref.dump(evict=(op == "dump_evict"))
+        torch.cuda.synchronize()
+        assert etc.stats == ref.stats, what
+        n = ref.stats[0]
+        assert np.array_equal(etc.table[:n].cpu().numpy(), ref.work[:n]), what
+        assert np.array_equal(host.numpy(), ref.host), what
