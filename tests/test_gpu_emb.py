@@ -247,6 +247,15 @@ def test_dedup_around_the_switches_of_the_sort(tiles):
     del table, ws
 
 
+@pytest.mark.parametrize("batch", [(8 << 20), (8 << 20) + 1], ids=["8Mi-keys-windows-of-64", "8Mi+1-keys-windows-of-256"])
+def test_both_sides_of_the_window_switch(batch):
+    """The reduction cuts the sorted list into windows of 64 positions up to 8 Mi keys and of 256 above:
+    one batch on either side of the switch, on few rows (runs of thousands of windows) and on many."""
+    info = run_case([1000, 3_000_000], 4, batch // 2 + batch % 2, alpha=1.05) if batch % 2 == 0 else \
+        run_case([3_000_000], 4, batch, alpha=0.0)
+    assert info["nnz"] == batch
+
+
 def test_all_keys_distinct():
     h = H()
     n = 5000
