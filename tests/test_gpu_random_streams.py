@@ -90,8 +90,8 @@ def test_random_cache_operator_stream(seed):
         op = g.choice(["query", "two_phase", "insert", "update", "refresh"], p=[0.35, 0.25, 0.15, 0.15, 0.10])
         what = f"seed {seed} op {opn} {op}"
         if op in ("query", "two_phase"):
-            n_bags = int(g.choice([1, 4, 52, 300]))
-            if g.random() < 0.5:
+            n_bags = int(g.choice([0, 1, 4, 52, 300]))
+            if n_bags and g.random() < 0.5:     # (a call without bags has no hotness: it comes with offsets [0])
                 offsets, nnz = None, n_bags * int(g.integers(1, 5))
             else:
                 offsets = np.concatenate([[0], np.cumsum(g.integers(0, 5, n_bags))]).astype(np.int64)
