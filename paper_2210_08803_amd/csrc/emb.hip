@@ -60,13 +60,16 @@ __global__ __launch_bounds__(256) void emb_init_header(EmbHeader* hdr, uint32_t*
   if (i < zero_count) zero[i] = 0u;
 }
 
-constexpr size_t kSlotMajorMinRowBytes = 512;
 // Order in which the forward kernels walk the bags.  n_samples == 0: in memory order (bag = sample *
 // S + slot).  n_samples == batch: slot by slot (all samples of slot 0, then slot 1, ...): the chip
 // then works on one table at a time and that table's hot rows stay in the 4 MB L2 of every XCD
 // instead of sharing it with the other slots' (headline forward 226 -> 205 us, multi-hot forward
 // 3.30 -> 2.85 ms).  The price is that consecutive work items write output rows S rows apart, so the
-// host asks for it only when an output row is at least 512 bytes.
+// host asks for it only from a certain size of the output row on: 256 bytes with one key per bag
+// (fp16 rows of 128 columns: forward 0.113 -> 0.106-0.110 ms), 128 bytes with several keys per bag,
+// where many rows are read per row written (the same rows pooled into an fp16 output: 1.47 -> 1.25 ms).
+constexpr size_t kSlotMajorMinRowBytes = 256;
+constexpr size_t kSlotMajorMinRowBytesCsr = 128;
 __device__ __forceinline__ uint32_t walk_to_bag(uint32_t v, uint32_t n_bags, uint32_t S, uint32_t n_samples) {
   if (n_samples == 0 || v >= n_bags) return v;
   return (v % n_samples) * S + v / n_samples;
@@ -1403,7 +1406,9 @@ static void launch_forward(const hctr_emb_desc* d, const int64_t* keys, const in
   const T* table = static_cast<const T*>(d->table);
   // slot by slot when every slot has a table of its own and an output row fills four cache lines
   const uint32_t S = (uint32_t)d->num_slots;
-  const uint32_t n_samples = (!rows64 && S > 1 && (size_t)d->dim * sizeof(OutT) >= kSlotMajorMinRowBytes) ? n_bags / S : 0u;
+  // (bags of several keys read many rows per row they write, so there the walk pays from one cache line on)
+  const size_t min_row_bytes = offsets ? kSlotMajorMinRowBytesCsr : kSlotMajorMinRowBytes;
+  const uint32_t n_samples = (!rows64 && S > 1 && (size_t)d->dim * sizeof(OutT) >= min_row_bytes) ? n_bags / S : 0u;
   if (!offsets) {
     constexpr int U = 4;
     const uint32_t threads = rows64 ? 256u : 512u;   // as in the kernel
