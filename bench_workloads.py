@@ -98,7 +98,7 @@ def multihot(h, args):
     layer = h.EmbeddingLayer(table, S, h.MEAN, base, rows_t)
     ws = layer.new_workspace(layer.workspace_bytes(B, nnz))
     out = torch.empty((B, S, D), device=DEV)
-    f = timeit(lambda: layer.forward(B, keys, offsets, out=out, ws=ws), 5, 1)
+    f = timeit(lambda: layer.forward(B, keys, offsets, out=out, ws=ws), 10, 3)
     # CPU side first, while the table still holds what the forward read: the oracle's all-cores variant on
     # a dense host copy of the table, over the first quarter of the samples (whole bags), forward +
     # backward; its pooled rows are compared with the timed forward's (parity on timed inputs)
@@ -124,8 +124,8 @@ def multihot(h, args):
     t3 = time.perf_counter()
     cpu_s = (t1 - t0) + (t3 - t2)
     del host, mag, ref
-    d = timeit(lambda: layer.backward_dedup(B, keys, offsets, ws=ws), 5, 1)
-    a = timeit(lambda: layer.backward_apply(B, nnz, dY, 0.01, offsets, ws=ws), 5, 1)
+    d = timeit(lambda: layer.backward_dedup(B, keys, offsets, ws=ws), 10, 3)
+    a = timeit(lambda: layer.backward_apply(B, nnz, dY, 0.01, offsets, ws=ws), 10, 3)
     uniq, cnt = layer.dedup_result(B, nnz, ws=ws)
     assert int(cnt.sum()) == nnz and layer.invalid_keys(ws) == 0
     U = int(uniq.numel())
@@ -133,9 +133,9 @@ def multihot(h, args):
     half = h.EmbeddingLayer(table, S, h.MEAN, base, rows_t, io_dtype=torch.float16)
     out16 = torch.empty((B, S, D), dtype=torch.float16, device=DEV)
     dY16 = dY.to(torch.float16)
-    f16 = timeit(lambda: half.forward(B, keys, offsets, out=out16, ws=ws), 5, 1)
+    f16 = timeit(lambda: half.forward(B, keys, offsets, out=out16, ws=ws), 10, 3)
     half.backward_dedup(B, keys, offsets, ws=ws)
-    a16 = timeit(lambda: half.backward_apply(B, nnz, dY16, 0.01, offsets, ws=ws), 5, 1)
+    a16 = timeit(lambda: half.backward_apply(B, nnz, dY16, 0.01, offsets, ws=ws), 10, 3)
     del out16, dY16
     fwd_bytes = nnz * (8 + D * 2) + B * S * (D * 4 + 8)
     apply_bytes = nnz * (8 + D * 4) + U * 2 * D * 2
