@@ -436,3 +436,78 @@ def test_forward_and_backward_can_be_captured_in_a_graph():
         assert scratch == scratch
         assert torch.equal(out_g, eager[i][0]), f"replay {i}: forward differs from the eager step"
         assert torch.equal(t_g, eager[i][1]), f"replay {i}: table differs from the eager step"
+
+
+def _replays_like_eager(make, step, n=3):
+    """Runs `step` n times eagerly on one state and replays a graph of one captured step n times on
+    another (with eager work and synchronisations between the replays); what the states watch must be
+    equal after every step."""
+    st_e = make()
+    eager = []
+    for i in range(n):
+        step(st_e)
+        eager.append([t.clone() for t in st_e["watch"]])
+    st_g = make()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step(st_g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for i in range(n):
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.randn(1 << 20, device="cuda").sum().item() is not None   # eager work between the replays
+        for k, (a, b) in enumerate(zip(st_g["watch"], eager[i])):
+            assert torch.equal(a, b), f"replay {i}: watched tensor {k} differs from the eager step"
+
+
+def test_multi_hot_step_can_be_captured_in_a_graph():
+    h = H()
+    rows, dim, batch = [5000, 60, 900], 64, 700
+    S = len(rows)
+    ro = datagen.row_offsets(rows)
+    table0 = datagen.table_rows_at(SEED, torch.arange(int(ro[-1])), dim, torch.float16)
+    offsets = datagen.multihot_offsets(SEED, 0, batch * S, 0, 40)
+    keys = to_dev(datagen.multihot_keys(SEED, 0, rows, batch, 1.05, offsets))
+    d_off = to_dev(offsets)
+    dY = to_dev(datagen.normal_grads(SEED, 0, batch * S * dim).view(batch, S, dim))
+
+    def make():
+        t = to_dev(table0)
+        layer = h.EmbeddingLayer(t, S, h.MEAN, ro[:-1].copy(), rows)
+        ws = layer.new_workspace(layer.workspace_bytes(batch, keys.numel()))
+        out = torch.empty((batch, S, dim), device="cuda")
+        return dict(layer=layer, ws=ws, out=out, watch=[out, t])
+
+    def step(s):
+        s["layer"].forward(batch, keys, d_off, out=s["out"], ws=s["ws"])
+        s["layer"].backward_sgd(batch, keys, dY, 0.05, d_off, ws=s["ws"])
+
+    _replays_like_eager(make, step)
+
+
+def test_hashed_step_with_insertion_can_be_captured_in_a_graph():
+    """Insert-or-find takes its counts from device memory, so the captured step inserts on its first
+    replay and finds on the later ones, as the eager steps do."""
+    h = H()
+    S, dim, batch, max_rows = 26, 32, 400, 20000
+    table0 = datagen.table_rows_at(SEED, torch.arange(max_rows), dim, torch.float32)
+    keys = to_dev(datagen.open_space_keys(SEED, 0, S, batch, 1.05))
+    dY = to_dev(datagen.normal_grads(SEED, 1, batch * S * dim).view(batch, S, dim))
+
+    def make():
+        t = to_dev(table0)
+        ht = h.HashTable(32768, max_rows)
+        layer = h.EmbeddingLayer(t, S, h.SUM, hash_table=ht, insert_on_miss=True, reuse_forward_rows=True)
+        ws = layer.new_workspace(layer.workspace_bytes(batch, batch * S))
+        out = torch.empty((batch, S, dim), device="cuda")
+        return dict(layer=layer, ws=ws, out=out, ht=ht, watch=[out, t])
+
+    def step(s):
+        s["layer"].forward(batch, keys, out=s["out"], ws=s["ws"])
+        s["layer"].backward_sgd(batch, keys, dY, 0.05, ws=s["ws"])
+
+    _replays_like_eager(make, step)
