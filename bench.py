@@ -149,7 +149,7 @@ def main():
     ap.add_argument("--seed", type=int, default=datagen.DEFAULT_SEED)
     ap.add_argument("--alpha", type=float, default=ALPHA,
                     help="Zipf exponent of the keys (0 = uniform); anything but the default is an experiment")
-    ap.add_argument("--table-spacer-gib", type=float, default=64.0,
+    ap.add_argument("--table-spacer-gib", type=float, default=96.0,
                     help="device memory allocated before the table and freed right after (0: none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--schedule", choices=["serial", "overlap", "pipeline"], default="serial",

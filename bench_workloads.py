@@ -8,6 +8,8 @@
     python bench_workloads.py etc        # training cache staged in host memory: load / train / dump passes of 8 batches
     python bench_workloads.py fwd_probe  # the forward kernel on key patterns of known locality (what bounds it)
     python bench_workloads.py placement  # how much the physical placement of the buffers moves the timings
+    python bench_workloads.py speedmap   # fill / copy / random-row gather by the position at which a process is handed its memory
+    python bench_workloads.py which_buffer  # the headline step with one buffer replaced at a time (the table's place decides)
     python bench_workloads.py group      # fused group: the 26 DLRM-sized tables with widths 128/64/32/16, dense one-hot input
 
 Each prints one JSON line.  Inputs are synthetic and seeded (datagen/), resident in HBM (the cache's
@@ -35,7 +37,7 @@ import datagen  # noqa: E402
 
 SEED = datagen.DEFAULT_SEED
 DEV = "cuda"
-SPACER_GIB = 64.0   # tables are allocated behind this much device memory (see behind_spacer); --spacer-gib 0: the plain way
+SPACER_GIB = 96.0   # tables are allocated behind this much device memory (see behind_spacer); --spacer-gib 0: the plain way
 
 
 def timeit(fn, iters=10, warm=2):
@@ -564,6 +566,86 @@ def placement(h, args):
                          "allocated again; forward by output offset", **res)
 
 
+def speedmap(h, args):
+    """Speed of plain fills, copies and gathers of random 512-byte rows by the position at which a new
+    process is handed its memory: pieces of 8 GiB allocated one after the other, each timed on its own."""
+    GiB = 1 << 30
+    free, _ = torch.cuda.mem_get_info(DEV)
+    n_pieces = int((free - 6 * GiB) // (8 * GiB))
+    pieces = [torch.empty(8 * GiB, dtype=torch.uint8, device=DEV) for _ in range(n_pieces)]
+    for c in pieces:
+        c.fill_(1)
+    idx = torch.randint(0, 8 * GiB // 512, (1 << 21,), device=DEV)
+    dst = torch.empty((1 << 21, 128), dtype=torch.float32, device=DEV)
+    res = []
+    for i, c in enumerate(pieces):
+        f32 = c.view(torch.float32)
+        half = f32.numel() // 2
+        rows = f32.view(-1, 128)
+        t_fill = timeit(lambda: f32.fill_(2.0), 5, 1) * 1e-3
+        t_copy = timeit(lambda: f32[half:].copy_(f32[:half]), 5, 1) * 1e-3
+        t_gath = timeit(lambda: torch.index_select(rows, 0, idx, out=dst), 5, 1) * 1e-3
+        res.append(dict(piece=i, handed_out_GiB=[8 * i, 8 * i + 8], fill_TBs=8 * GiB / t_fill / 1e12,
+                        copy_TBs=8 * GiB / t_copy / 1e12, gather_512B_rows_TBs=2 * (1 << 21) * 512 / t_gath / 1e12))
+    return dict(workload="fill, copy (read + write) and torch.index_select of 2 M random 512-byte rows inside pieces of 8 GiB "
+                         "allocated one after the other by a new process", pieces=res)
+
+
+def which_buffer(h, args):
+    """Which buffer's placement decides the speed of the headline step: bench.py's allocations in
+    bench.py's order with the table allocated the plain way, then one buffer replaced at a time."""
+    rows_t = datagen.DLRM_TABLE_ROWS
+    S, D, B = 26, 128, 55296
+    ro = datagen.row_offsets(rows_t)
+    base, total = ro[:-1].copy(), int(ro[-1])
+    nnz = B * S
+    table = torch.empty((total, D), dtype=torch.float32, device=DEV)
+    datagen.fill_table(SEED, table, 1 << 21)
+    smp = datagen.make_samplers(rows_t, 1.05)
+    keys = [datagen.onehot_keys(SEED, b, rows_t, B, 1.05, samplers=smp).to(DEV) for b in range(8)]
+    del smp
+    dYs = [datagen.normal_grads(SEED, b, nnz * D, device=DEV).view(B, S, D) for b in range(2)]
+    out = torch.empty((B, S, D), dtype=torch.float32, device=DEV)
+    layer = h.EmbeddingLayer(table, S, h.SUM, base, rows_t)
+    ws = layer.workspace(B, nnz)
+
+    def times(layer, out, dYs, ws, n=40):
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n)]
+        for i in range(n):
+            ev[i][0].record()
+            layer.forward(B, keys[i % 8], out=out, ws=ws)
+            ev[i][1].record()
+            layer.backward_sgd(B, keys[i % 8], dYs[i % 2], 1e-6, ws=ws)
+            ev[i][2].record()
+        torch.cuda.synchronize()
+        return dict(forward_us=float(np.median([e[0].elapsed_time(e[1]) for e in ev[5:]])) * 1e3,
+                    backward_us=float(np.median([e[1].elapsed_time(e[2]) for e in ev[5:]])) * 1e3)
+
+    res = [dict(what="as bench.py allocates, table first", **times(layer, out, dYs, ws))]
+    out2 = torch.empty((B, S, D), dtype=torch.float32, device=DEV)
+    res.append(dict(what="new output", **times(layer, out2, dYs, ws)))
+    dY2 = [d.clone() for d in dYs]
+    res.append(dict(what="new gradients", **times(layer, out, dY2, ws)))
+    ws2 = layer.new_workspace(layer.workspace_bytes(B, nnz))
+    res.append(dict(what="new workspace", **times(layer, out, dYs, ws2)))
+    res.append(dict(what="new output, gradients and workspace", **times(layer, out2, dY2, ws2)))
+    MB = 1 << 20
+    nb = nnz * D * 4
+    pool = torch.empty(nb + 300 * MB, dtype=torch.uint8, device=DEV)
+    for d in (0, 4, 16, 36, 64, 100, 128, 200, 256):
+        o = pool[d * MB:d * MB + nb].view(torch.float32).view(B, S, D)
+        res.append(dict(what=f"output inside a new pool at +{d} MB", **times(layer, o, dYs, ws, n=25)))
+    del pool, out2, dY2, ws2
+    for trial in range(3):
+        del layer, table
+        torch.cuda.empty_cache()
+        table = torch.empty((total, D), dtype=torch.float32, device=DEV)
+        datagen.fill_table(SEED, table, 1 << 21)
+        layer = h.EmbeddingLayer(table, S, h.SUM, base, rows_t)
+        res.append(dict(what=f"table freed and allocated again ({trial + 1}), other buffers kept", **times(layer, out, dYs, ws)))
+    return dict(workload="headline step (forward / backward, medians of 35 steps) with one buffer replaced at a time", probes=res)
+
+
 def group(h, args):
     rows_t = datagen.DLRM_TABLE_ROWS
     B, L = 55296, len(rows_t)
@@ -605,7 +687,7 @@ def group(h, args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group", "mixed", "etc", "fwd_probe", "placement"])
+    ap.add_argument("workload", choices=["multihot", "hashed", "cache", "group", "mixed", "etc", "fwd_probe", "placement", "speedmap", "which_buffer"])
     ap.add_argument("--etc-passes", type=int, default=4)
     ap.add_argument("--spacer-gib", type=float, default=SPACER_GIB)
     ap.add_argument("--host-rows", type=int, default=0,
@@ -620,7 +702,7 @@ def main():
     import paper_2210_08803_amd as h
     globals()["SPACER_GIB"] = args.spacer_gib
     res = {"multihot": multihot, "hashed": hashed, "cache": cache, "group": group, "mixed": mixed, "etc": etc, "fwd_probe": fwd_probe,
-           "placement": placement}[args.workload](h, args)
+           "placement": placement, "speedmap": speedmap, "which_buffer": which_buffer}[args.workload](h, args)
     res["n_gpus"] = 1
     res["data"] = "synthetic"
     res["tables_behind_spacer_gib"] = args.spacer_gib

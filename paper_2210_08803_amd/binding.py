@@ -177,17 +177,18 @@ class behind_spacer:
     """Context manager: what is allocated inside lands behind `gib` GiB of device memory, which are
     given back on exit (later, smaller buffers may land there).
 
-    Why: on MI355X the first tens of gigabytes of device memory that a process is handed serve the
-    random row reads of the forward and the read-modify-writes of the backward about 7 % slower than
-    the memory behind them.  Measured with the 85 GB table of the DLRM-shaped workload: forward /
-    backward 218 / 290 us with the table as the first allocation, 200 / 274 us behind 32 to 160 GiB,
-    whatever the other buffers of the step are and wherever they lie (the 22 GB of the hashed
-    workload and the tables of the fused group, allocated first, showed no difference).  A process
-    that allocates a large table first therefore puts it in the slow place.  This is a property of the machine's memory
-    map, not of the kernels; it only pays for the first allocations of a process, and the spacer is
-    skipped when less than `gib` + `room_for` bytes + 1 GiB are free."""
+    Why: on MI355X the first 88 GiB of device memory that a process is handed serve random row
+    reads about 8 % slower than the memory behind them, while fills and copies run at the same rate
+    everywhere (a gather of random 512-byte rows out of 8 GiB pieces allocated one after the other:
+    3.70 TB/s in pieces 0 to 10, 4.00 TB/s in all later ones).  With the 85 GB table of the
+    DLRM-shaped workload: forward / backward 218 / 290 us with the table as the first allocation,
+    200 / 274 us behind the spacer, whatever the other buffers of the step are and wherever they lie
+    (the 22 GB of the hashed workload and the tables of the fused group, allocated first, showed no
+    difference).  A process that allocates a large table first therefore puts it in the slow place.
+    This is a property of the machine, not of the kernels; it only pays for the first allocations of
+    a process, and the spacer is skipped when less than `gib` + `room_for` bytes + 1 GiB are free."""
 
-    def __init__(self, gib: float = 64.0, room_for: int = 0, device="cuda"):
+    def __init__(self, gib: float = 96.0, room_for: int = 0, device="cuda"):
         self.gib, self.room_for, self.device, self._spacer = gib, int(room_for), device, None
 
     def __enter__(self):
@@ -206,7 +207,7 @@ class behind_spacer:
 
 
 def allocate_table(num_rows: int, dim: int, dtype: torch.dtype = torch.float32, device="cuda",
-                   spacer_gib: float = 64.0) -> torch.Tensor:
+                   spacer_gib: float = 96.0) -> torch.Tensor:
     """An uninitialised [num_rows, dim] device tensor for a large table, placed behind a spacer (see
     behind_spacer; spacer_gib 0: allocated the plain way)."""
     nbytes = int(num_rows) * int(dim) * torch.empty((), dtype=dtype).element_size()
