@@ -77,16 +77,23 @@ __device__ __forceinline__ uint32_t walk_to_bag(uint32_t v, uint32_t n_bags, uin
 
 // ------------------------------------------------------------------------------------------------
 // Forward, one key per bag: a group of LPR lanes copies U rows (U independent 16-byte loads per
-// lane in flight), so a wave covers 64/LPR * U bags.
+// lane in flight), so a wave covers 64/LPR * U bags.  Measured on the 26-table workload of 512-byte
+// rows, same buffers: 1 / 2 / 4 / 8 / 16 / 24 / 32 rows per group in blocks of 256 threads 253 /
+// 205 / 191 / 188 / 184 / 194 / 214 us; 4 / 8 / 12 / 16 rows in blocks of 512 threads 188 / 185 /
+// 184 / 197 us; 16 rows in blocks of 64 / 128 threads 194 / 192 us.  (A plain copy of the same size
+// behaves the other way round: the fewer loads a thread has under way, the faster.  What the gather
+// needs to hide is the chain key -> row address -> row.)
 // ------------------------------------------------------------------------------------------------
+constexpr int kOneHotRows = 16;          // U of the launch below
+constexpr uint32_t kOneHotThreads = 256;
 template <typename T, typename OutT, int LPR, int U, bool HASHED>
-__global__ __launch_bounds__(HASHED ? 256 : 512) void fwd_onehot(const T* __restrict__ table, int D,
+__global__ __launch_bounds__(kOneHotThreads) void fwd_onehot(const T* __restrict__ table, int D,
                                                   int64_t total_rows, const int64_t* __restrict__ keys,
                                                   const int64_t* __restrict__ rows64, uint32_t n_bags,
                                                   uint32_t S, uint32_t n_samples, const SlotTable slots,
                                                   OutT* __restrict__ out, EmbHeader* hdr) {
   constexpr int VEC = RowVec<T>::VEC;
-  constexpr uint32_t kThreads = HASHED ? 256u : 512u;   // direct mode measured 1.5 % faster with 512 (same buffers)
+  constexpr uint32_t kThreads = kOneHotThreads;
   const int sub = threadIdx.x % LPR;
   const uint32_t group0 = (blockIdx.x * kThreads + threadIdx.x) / LPR;
   const uint32_t n_groups = gridDim.x * (kThreads / LPR);
@@ -1410,15 +1417,14 @@ static void launch_forward(const hctr_emb_desc* d, const int64_t* keys, const in
   const size_t min_row_bytes = offsets ? kSlotMajorMinRowBytesCsr : kSlotMajorMinRowBytes;
   const uint32_t n_samples = (!rows64 && S > 1 && (size_t)d->dim * sizeof(OutT) >= min_row_bytes) ? n_bags / S : 0u;
   if (!offsets) {
-    constexpr int U = 4;
-    const uint32_t threads = rows64 ? 256u : 512u;   // as in the kernel
-    const uint32_t bags_per_block = (threads / LPR) * U;
+    constexpr int U = kOneHotRows;
+    const uint32_t bags_per_block = (kOneHotThreads / LPR) * U;
     dim3 grid((uint32_t)ceil_div(n_bags, bags_per_block), ychunks);
     if (rows64)
-      hipLaunchKernelGGL((fwd_onehot<T, OutT, LPR, U, true>), grid, dim3(256), 0, stream, table, d->dim,
+      hipLaunchKernelGGL((fwd_onehot<T, OutT, LPR, U, true>), grid, dim3(kOneHotThreads), 0, stream, table, d->dim,
                          d->total_rows, keys, rows64, n_bags, S, n_samples, st, out, hdr);
     else
-      hipLaunchKernelGGL((fwd_onehot<T, OutT, LPR, U, false>), grid, dim3(512), 0, stream, table, d->dim,
+      hipLaunchKernelGGL((fwd_onehot<T, OutT, LPR, U, false>), grid, dim3(kOneHotThreads), 0, stream, table, d->dim,
                          d->total_rows, keys, rows64, n_bags, S, n_samples, st, out, hdr);
   } else {
     constexpr int U = 4;
