@@ -177,16 +177,22 @@ class behind_spacer:
     """Context manager: what is allocated inside lands behind `gib` GiB of device memory, which are
     given back on exit (later, smaller buffers may land there).
 
-    Why: on MI355X the first 88 GiB of device memory that a process is handed serve random row
-    reads about 8 % slower than the memory behind them, while fills and copies run at the same rate
-    everywhere (a gather of random 512-byte rows out of 8 GiB pieces allocated one after the other:
-    3.70 TB/s in pieces 0 to 10, 4.00 TB/s in all later ones).  With the 85 GB table of the
-    DLRM-shaped workload: forward / backward 218 / 290 us with the table as the first allocation,
-    200 / 274 us behind the spacer, whatever the other buffers of the step are and wherever they lie
-    (the 22 GB of the hashed workload and the tables of the fused group, allocated first, showed no
-    difference).  A process that allocates a large table first therefore puts it in the slow place.
-    This is a property of the machine, not of the kernels; it only pays for the first allocations of
-    a process, and the spacer is skipped when less than `gib` + `room_for` bytes + 1 GiB are free."""
+    Why: on MI355X the first 88 GiB of device memory that a process is handed in pieces of 8 GiB
+    serve random row reads about 8 % slower than the memory handed out after them, while fills and
+    copies run at the same rate everywhere (a gather of random 512-byte rows out of 8 GiB pieces
+    allocated one after the other: 3.70 TB/s in pieces 0 to 10, 4.00 TB/s in all later ones, on
+    every box looked at).  With the 85 GB table of the DLRM-shaped workload: forward / backward
+    218 / 290 us with the table as the first allocation, 200 / 274 us behind the spacer, whatever
+    the other buffers of the step are and wherever they lie (the 22 GB of the hashed workload and
+    the tables of the fused group, allocated first, showed no difference).  A process that
+    allocates a large table first therefore puts it in the slow place.  The spacer is allocated
+    in pieces of 8 GiB because that is the request size for which the order in which the driver
+    hands out its memory was seen to repeat: behind one 96 GiB allocation the table came to lie
+    in the fast place on one day's boxes and in the slow place on another's.  This is a property
+    of the machine, not of the kernels; it only pays for the first allocations of a process, and
+    the spacer is skipped when less than `gib` + `room_for` bytes + 1 GiB are free."""
+
+    PIECE = 8 << 30
 
     def __init__(self, gib: float = 96.0, room_for: int = 0, device="cuda"):
         self.gib, self.room_for, self.device, self._spacer = gib, int(room_for), device, None
@@ -196,7 +202,8 @@ class behind_spacer:
             free, _ = torch.cuda.mem_get_info(self.device)
             want = int(self.gib * (1 << 30))
             if free > self.room_for + want + (1 << 30):
-                self._spacer = torch.empty(want, dtype=torch.uint8, device=self.device)
+                self._spacer = [torch.empty(min(self.PIECE, want - at), dtype=torch.uint8, device=self.device)
+                                for at in range(0, want, self.PIECE)]
         return self
 
     def __exit__(self, *exc):
