@@ -184,20 +184,6 @@ def main():
     table = hctr.allocate_table(total, DIM, torch.float32, dev, spacer_gib=args.table_spacer_gib)
     datagen.fill_table(args.seed, table, chunk_rows=1 << 21)
     torch.cuda.synchronize()
-    # where the table came to lie, told by a plain gather of random rows (a diagnostic beside the
-    # figures, outside the timed region): about 3.7 TB/s in the slow place, 4.0 TB/s elsewhere
-    probe_idx = torch.randint(0, total, (1 << 21,), device=dev)
-    probe_dst = torch.empty((1 << 21, DIM), dtype=torch.float32, device=dev)
-    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    torch.index_select(table, 0, probe_idx, out=probe_dst)
-    pe[0].record()
-    for _ in range(5):
-        torch.index_select(table, 0, probe_idx, out=probe_dst)
-    pe[1].record()
-    torch.cuda.synchronize()
-    table_gather_tbs = 2 * (1 << 21) * DIM * 4 / (pe[0].elapsed_time(pe[1]) / 5 * 1e-3) / 1e12
-    del probe_idx, probe_dst
-    torch.cuda.empty_cache()
     log(f"table {total} x {DIM} fp32 = {total * DIM * 4 / 1e9:.1f} GB filled in {time.time() - t0:.1f}s")
 
     t0 = time.time()
@@ -387,8 +373,7 @@ def main():
                    "batch": BATCH, "slots": S, "dim": DIM, "keys_per_step": nnz, "distinct_rows_per_step": int(U),
                    "table_allocation": ("first allocation of the process" if args.table_spacer_gib <= 0 else
                                         "behind %g GiB of device memory (pieces of 8 GiB) that are freed again "
-                                        "before the other buffers are made" % args.table_spacer_gib),
-                   "table_gather_probe_TBs": round(table_gather_tbs, 3)},
+                                        "before the other buffers are made" % args.table_spacer_gib)},
         "parity_checked": True, "parity": parity,
         "roofline": {"bound": "hbm", "kernel": "fwd_onehot<float,float,32,16>", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
