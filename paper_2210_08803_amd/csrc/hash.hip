@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void hash_clear(u64x2* slots, uint64_t n_slots
 // An 8-lane group reads one bucket (8 slots of 16 bytes = one 128-byte line) per probe and works on
 // kFindKeys keys at once, so that many independent bucket loads are in flight per wave: the search
 // is bound by the latency of random lines, not by bandwidth.
-constexpr int kFindKeys = 4;   // find-only call on 3.4 M keys, load 0.8: 0.277 / 0.236 / 0.227 ms with 1 / 2 / 4
+constexpr int kFindKeys = 4;   // find-only call on 3.4 M keys, load 0.8: 0.277 / 0.236 / 0.227 ms with 1 / 2 / 4 (8 and 16: 30 % and 2.5 x slower)
 __global__ __launch_bounds__(256) void hash_find(const u64x2* __restrict__ slots, uint32_t n_buckets,
                                                  const int64_t* __restrict__ keys, uint32_t n,
                                                  int64_t* __restrict__ rows,
